@@ -1,0 +1,169 @@
+"""CPU oracle for block-circulant layers (CirCNN, arXiv 1708.08917).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+HIP kernels are checked against.  Only tests, the smoke check and the
+`cpu_baseline` leg of the benchmark may import it; the product path never does,
+and this file imports nothing from the product package.
+
+What it computes is the *definition*, in float64, with no FFT anywhere:
+every k x k circulant block is written out as a dense matrix from its defining
+vector and the layer is an ordinary dense matrix product (Sec. 3.1, Eq. 3;
+Sec. 3.2, Eq. 6).  Because Eq. 3 and the circulant convolution theorem are
+identities, the FFT route of Algorithms 1 and 2 must reproduce these numbers up
+to rounding.  `numpy.matmul` is used as the matrix-product step.
+
+Readings of the paper taken here (each also pinned by a CPU test):
+
+* Orientation.  Sec. 3.1 calls w_ij the "first row" of W_ij and, in the same
+  sentence, states W_ij x_j = IFFT(FFT(w_ij) o FFT(x_j)).  With rows that rotate
+  to the right these two cannot both hold; the printed formula is kept:
+  W_ij[a][b] = w_ij[(a - b) mod k], i.e. w_ij is the first *column* and
+  W_ij x_j is the circular convolution of w_ij and x_j.
+* Algorithm 2 has no batch index; gradients of the block vectors are summed
+  over the batch, without a 1/B factor.
+* CONV (Eq. 6, Eq. 7): for each spatial offset (dh, dw) the C_out x C_in
+  channel-mixing matrix is block-circulant with k x k blocks; cross-correlation
+  (no kernel flip), zero padding, stride 1.
+
+Parity pins: all functions below are pinned (see tests/test_oracle_pins.py):
+circulant definition, shift direction, DFT diagonalisation, brute-force
+circular convolution, exact integers, k = 1 dense layer, p = q = 1 library
+circular convolution, finite differences and bilinear identities for the
+gradients, library convolution and single-pixel response for CONV.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def circulant(w_vec: np.ndarray) -> np.ndarray:
+    """Dense k x k circulant block from its defining vector (Sec. 3.1).
+
+    C[a][b] = w[(a - b) mod k]: column 0 is w, each column is the previous one
+    rotated down by one.
+    """
+    w_vec = np.asarray(w_vec, dtype=np.float64)
+    k = w_vec.shape[0]
+    a = np.arange(k).reshape(k, 1)
+    b = np.arange(k).reshape(1, k)
+    return w_vec[(a - b) % k]
+
+
+def expand_block_circulant(w: np.ndarray) -> np.ndarray:
+    """Dense (p*k) x (q*k) matrix W = [W_ij] from w[p][q][k] (Sec. 3.1, Eq. 3)."""
+    w = np.asarray(w, dtype=np.float64)
+    p, q, k = w.shape
+    W = np.empty((p * k, q * k), dtype=np.float64)
+    for i in range(p):
+        for j in range(q):
+            W[i * k:(i + 1) * k, j * k:(j + 1) * k] = circulant(w[i, j])
+    return W
+
+
+def fc_forward(w, x, bias=None, relu=False, block_rows=None) -> np.ndarray:
+    """y = psi(W x + theta) for a batch (Eq. 1 with W from Eq. 3).
+
+    w[p][q][k], x[B][q*k] -> y[B][p*k].  `block_rows` (a list of block-row
+    indices i) restricts the result to the columns y[:, i*k:(i+1)*k] of those
+    block rows, concatenated in the given order; the arithmetic per output is
+    unchanged.
+    """
+    w = np.asarray(w, dtype=np.float64)
+    x = np.asarray(x, dtype=np.float64)
+    p, q, k = w.shape
+    rows = list(range(p)) if block_rows is None else list(block_rows)
+    out = np.empty((x.shape[0], len(rows) * k), dtype=np.float64)
+    for s, i in enumerate(rows):
+        Wi = expand_block_circulant(w[i:i + 1])          # k x n : block row i of W
+        a = np.matmul(x, Wi.T)
+        if bias is not None:
+            a = a + np.asarray(bias, dtype=np.float64)[i * k:(i + 1) * k]
+        out[:, s * k:(s + 1) * k] = a
+    if relu:
+        out = np.maximum(out, 0.0)
+    return out
+
+
+def fc_backward_dx(w, dy, block_cols=None) -> np.ndarray:
+    """dL/dx = W^T dL/da (Eq. 5).  dy[B][p*k] -> dx[B][q*k] (or the listed block columns)."""
+    w = np.asarray(w, dtype=np.float64)
+    dy = np.asarray(dy, dtype=np.float64)
+    p, q, k = w.shape
+    cols = list(range(q)) if block_cols is None else list(block_cols)
+    out = np.empty((dy.shape[0], len(cols) * k), dtype=np.float64)
+    for s, j in enumerate(cols):
+        Wj = expand_block_circulant(w[:, j:j + 1])       # m x k : block column j of W
+        out[:, s * k:(s + 1) * k] = np.matmul(dy, Wj)
+    return out
+
+
+def fc_backward_dw(x, dy, k, pairs=None) -> np.ndarray:
+    """dL/dw_ij (Eq. 4), summed over the batch.
+
+    The gradient of the dense matrix is G = dy^T x.  Since
+    W_ij[a][b] = w_ij[(a - b) mod k], the chain rule collects every entry of
+    block (i, j) that holds w_ij[t]:  dw_ij[t] = sum_a G_ij[a][(a - t) mod k].
+
+    Returns dw[p][q][k], or dw[len(pairs)][k] for a list of (i, j) pairs.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    dy = np.asarray(dy, dtype=np.float64)
+    q = x.shape[1] // k
+    p = dy.shape[1] // k
+    a = np.arange(k).reshape(k, 1)
+    t = np.arange(k).reshape(1, k)
+    col = (a - t) % k                                    # col[a][t] = (a - t) mod k
+
+    def one(i, j):
+        G = np.matmul(dy[:, i * k:(i + 1) * k].T, x[:, j * k:(j + 1) * k])   # k x k
+        return G[a, col].sum(axis=0)
+
+    if pairs is not None:
+        return np.stack([one(i, j) for (i, j) in pairs])
+    dw = np.empty((p, q, k), dtype=np.float64)
+    for i in range(p):
+        for j in range(q):
+            dw[i, j] = one(i, j)
+    return dw
+
+
+def conv_forward(w, x, bias=None, relu=False, pad=0) -> np.ndarray:
+    """Block-circulant CONV layer, stride 1 (Eq. 6 with the structure of Eq. 7).
+
+    w[r][r][p][q][k] (offset-major), x[N][C_in][H][W] ->
+    y[N][C_out][H + 2 pad - r + 1][W + 2 pad - r + 1], with
+    y[n, co, h, w] = sum_{dh, dw, ci} Wd[dh, dw][co, ci] * xpad[n, ci, h + dh, w + dw]
+    where Wd[dh, dw] is the dense expansion of the p x q grid of that offset.
+    """
+    w = np.asarray(w, dtype=np.float64)
+    x = np.asarray(x, dtype=np.float64)
+    r = w.shape[0]
+    N, C_in, H, Wd_ = x.shape
+    p, q, k = w.shape[2:]
+    assert C_in == q * k
+    C_out = p * k
+    Ho, Wo = H + 2 * pad - r + 1, Wd_ + 2 * pad - r + 1
+    xp = np.zeros((N, C_in, H + 2 * pad, Wd_ + 2 * pad), dtype=np.float64)
+    xp[:, :, pad:pad + H, pad:pad + Wd_] = x
+    y = np.zeros((N, C_out, Ho, Wo), dtype=np.float64)
+    for dh in range(r):
+        for dw in range(r):
+            M = expand_block_circulant(w[dh, dw])        # C_out x C_in
+            win = xp[:, :, dh:dh + Ho, dw:dw + Wo]       # N x C_in x Ho x Wo
+            # channel mixing at every pixel: y[n, :, h, w] += M @ win[n, :, h, w]
+            y += np.matmul(M, win.reshape(N, C_in, Ho * Wo)).reshape(N, C_out, Ho, Wo)
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64).reshape(1, C_out, 1, 1)
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y
+
+
+def max_norm_rel_err(got, ref) -> float:
+    """max_e |got_e - ref_e| / max_e |ref_e| — the parity gate for one tensor."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    denom = float(np.max(np.abs(ref)))
+    if denom == 0.0:
+        return float(np.max(np.abs(got)))
+    return float(np.max(np.abs(got - ref)) / denom)

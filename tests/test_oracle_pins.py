@@ -1,0 +1,254 @@
+"""CPU-only pins of the oracle against what the paper and the mathematics fix.
+
+None of these tests compares the oracle with itself: each one re-derives the
+expected numbers by a different route (hand arithmetic, a two-line brute-force
+loop, a naive DFT matrix, a library FFT / GEMM / convolution, finite
+differences, exact integer arithmetic).
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import circ_oracle as O
+from paper_1708_08917_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+RNG = np.random.default_rng(20170808)
+
+
+# ---- circulant definition (Sec. 1: every row/column is a rotation of the others) ----------
+@pytest.mark.parametrize("k", [1, 2, 3, 5, 8, 16])
+def test_circulant_definition(k):
+    w = RNG.standard_normal(k)
+    C = O.circulant(w)
+    assert C.shape == (k, k)
+    np.testing.assert_array_equal(C[:, 0], w)                       # first column is w
+    for a in range(k):
+        for b in range(k):
+            assert C[(a + 1) % k, (b + 1) % k] == C[a, b]           # constant along diagonals
+    for a in range(k):                                              # each row rotates row 0
+        np.testing.assert_array_equal(C[a], np.roll(C[0], a))
+
+
+# ---- direction of the rotation (the reading that the printed FFT formula fixes) ------------
+def test_shift_direction():
+    k = 8
+    x = np.arange(1.0, k + 1.0)
+    e0 = np.zeros(k); e0[0] = 1
+    e1 = np.zeros(k); e1[1] = 1
+    np.testing.assert_array_equal(O.circulant(e0), np.eye(k))
+    y = O.circulant(e1) @ x
+    np.testing.assert_array_equal(y, np.roll(x, 1))                 # (Wx)[a] = x[(a-1) mod k]
+    y = O.fc_forward(e1.reshape(1, 1, k), x.reshape(1, k))[0]
+    np.testing.assert_array_equal(y, np.roll(x, 1))
+
+
+# ---- hand-worked example, p = 2, q = 1, k = 3 (Fig. 1 bookkeeping) ------------------------
+def test_golden_k3():
+    rows = [l for l in open(os.path.join(GOLDEN, "circulant_k3_worked.txt")) if not l.startswith("#")]
+    p, q, k = (int(v) for v in rows[0].split())
+    w = np.array(rows[1].split(), dtype=np.float64).reshape(p, q, k)
+    x = np.array(rows[2].split(), dtype=np.float64).reshape(1, q * k)
+    y = np.array(rows[3].split(), dtype=np.float64)
+    assert w.size == 6 and O.expand_block_circulant(w).size == 18   # 6 stored parameters for 18 entries
+    np.testing.assert_array_equal(O.fc_forward(w, x)[0], y)
+
+
+# ---- DFT diagonalisation: circulant = F^-1 diag(F w) F, naive O(k^2) DFT matrix ------------
+@pytest.mark.parametrize("k", [2, 3, 4, 8, 16])
+def test_dft_diagonalisation(k):
+    w = RNG.standard_normal(k)
+    n = np.arange(k)
+    F = np.exp(-2j * np.pi * np.outer(n, n) / k)
+    Finv = np.conj(F) / k
+    C = Finv @ np.diag(F @ w) @ F
+    np.testing.assert_allclose(C.imag, 0, atol=1e-12)
+    np.testing.assert_allclose(C.real, O.circulant(w), atol=1e-12)
+
+
+# ---- brute-force circular convolution, k <= 8 ----------------------------------------------
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 7, 8])
+def test_bruteforce_circular_convolution(k):
+    w = RNG.standard_normal(k)
+    x = RNG.standard_normal(k)
+    y = np.zeros(k)
+    for a in range(k):
+        for b in range(k):
+            y[a] += w[(a - b) % k] * x[b]
+    np.testing.assert_allclose(O.circulant(w) @ x, y, atol=1e-14)
+    np.testing.assert_allclose(O.fc_forward(w.reshape(1, 1, k), x.reshape(1, k))[0], y, atol=1e-14)
+
+
+# ---- exact integers: polynomial multiplication mod z^k - 1 ---------------------------------
+def test_exact_integers():
+    p, q, k, B = 3, 2, 8, 4
+    w = synth.small_integers(11, 0, (p, q, k))
+    x = synth.small_integers(11, 1, (B, q * k))
+    y = O.fc_forward(w, x)
+    assert np.all(y == np.round(y))
+    ref = np.zeros((B, p * k), dtype=np.int64)
+    wi, xi = w.astype(np.int64), x.astype(np.int64)
+    for b in range(B):
+        for i in range(p):
+            for j in range(q):
+                for s in range(k):                    # coefficient of z^s in w(z) times z^t term
+                    for t in range(k):
+                        ref[b, i * k + (s + t) % k] += wi[i, j, s] * xi[b, j * k + t]
+    np.testing.assert_array_equal(y.astype(np.int64), ref)
+
+
+# ---- k = 1: no compression, an ordinary dense layer (Sec. 2.3) -----------------------------
+def test_k1_is_dense_layer():
+    m, n, B = 7, 5, 3
+    Wd = RNG.standard_normal((m, n))
+    x = RNG.standard_normal((B, n))
+    bias = RNG.standard_normal(m)
+    y = O.fc_forward(Wd.reshape(m, n, 1), x, bias=bias, relu=True)
+    ref = torch.relu(torch.from_numpy(x) @ torch.from_numpy(Wd).T + torch.from_numpy(bias)).numpy()
+    np.testing.assert_allclose(y, ref, atol=1e-13)
+    dy = RNG.standard_normal((B, m))
+    np.testing.assert_allclose(O.fc_backward_dx(Wd.reshape(m, n, 1), dy), dy @ Wd, atol=1e-13)
+    np.testing.assert_allclose(O.fc_backward_dw(x, dy, 1)[:, :, 0], dy.T @ x, atol=1e-13)
+
+
+# ---- p = q = 1: one circulant matrix = library circular convolution ------------------------
+@pytest.mark.parametrize("k", [3, 8, 16, 64])
+def test_single_circulant_vs_library_fft(k):
+    w = RNG.standard_normal(k)
+    x = RNG.standard_normal((5, k))
+    ref = np.fft.irfft(np.fft.rfft(w)[None, :] * np.fft.rfft(x, axis=1), n=k, axis=1)
+    np.testing.assert_allclose(O.fc_forward(w.reshape(1, 1, k), x), ref, atol=1e-12)
+
+
+# ---- Algorithm 1 written out with a library FFT, general p, q ------------------------------
+@pytest.mark.parametrize("p,q,k,B", [(2, 3, 4, 2), (3, 2, 8, 3), (4, 4, 16, 5), (2, 5, 6, 2)])
+def test_algorithm1_with_library_fft(p, q, k, B):
+    w = RNG.standard_normal((p, q, k))
+    x = RNG.standard_normal((B, q * k))
+    a = np.zeros((B, p * k))
+    for i in range(p):
+        for j in range(q):
+            a[:, i * k:(i + 1) * k] += np.fft.ifft(
+                np.fft.fft(w[i, j])[None, :] * np.fft.fft(x[:, j * k:(j + 1) * k], axis=1), axis=1).real
+    np.testing.assert_allclose(O.fc_forward(w, x), a, atol=1e-12)
+
+
+# ---- block additivity (Eq. 3): q block columns = sum of q single-column layers -------------
+def test_block_additivity():
+    p, q, k, B = 3, 4, 8, 2
+    w = RNG.standard_normal((p, q, k))
+    x = RNG.standard_normal((B, q * k))
+    total = sum(O.fc_forward(w[:, j:j + 1], x[:, j * k:(j + 1) * k]) for j in range(q))
+    np.testing.assert_allclose(O.fc_forward(w, x), total, atol=1e-13)
+
+
+def test_block_row_subset_matches_full():
+    p, q, k, B = 5, 3, 4, 3
+    w = RNG.standard_normal((p, q, k)); x = RNG.standard_normal((B, q * k)); b = RNG.standard_normal(p * k)
+    full = O.fc_forward(w, x, bias=b, relu=True)
+    sub = O.fc_forward(w, x, bias=b, relu=True, block_rows=[4, 1])
+    np.testing.assert_array_equal(sub, np.concatenate([full[:, 16:20], full[:, 4:8]], axis=1))
+    dy = RNG.standard_normal((B, p * k))
+    np.testing.assert_array_equal(O.fc_backward_dx(w, dy, block_cols=[2])[:, :], O.fc_backward_dx(w, dy)[:, 8:12])
+    np.testing.assert_array_equal(O.fc_backward_dw(x, dy, k, pairs=[(3, 1)])[0], O.fc_backward_dw(x, dy, k)[3, 1])
+
+
+# ---- gradients: central finite differences and the bilinear identities ---------------------
+@pytest.mark.parametrize("p,q,k,B", [(2, 3, 4, 2), (3, 2, 8, 3), (1, 1, 5, 1)])
+def test_gradients_finite_differences(p, q, k, B):
+    w = RNG.standard_normal((p, q, k))
+    x = RNG.standard_normal((B, q * k))
+    dy = RNG.standard_normal((B, p * k))
+    loss = lambda w_, x_: float(np.sum(dy * O.fc_forward(w_, x_)))
+    dx = O.fc_backward_dx(w, dy)
+    dw = O.fc_backward_dw(x, dy, k)
+    h = 1e-6
+    for idx in np.ndindex(*x.shape):
+        xp, xm = x.copy(), x.copy(); xp[idx] += h; xm[idx] -= h
+        assert abs((loss(w, xp) - loss(w, xm)) / (2 * h) - dx[idx]) < 1e-7
+    for idx in np.ndindex(*w.shape):
+        wp, wm = w.copy(), w.copy(); wp[idx] += h; wm[idx] -= h
+        assert abs((loss(wp, x) - loss(wm, x)) / (2 * h) - dw[idx]) < 1e-7
+    y = O.fc_forward(w, x)
+    s = np.sum(dy * y)
+    assert abs(s - np.sum(dx * x)) < 1e-10 * max(1, abs(s))
+    assert abs(s - np.sum(dw * w)) < 1e-10 * max(1, abs(s))
+
+
+def test_backward_formulas_with_library_fft():
+    """dx_j = sum_i IFFT(conj(FFT w_ij) o FFT dy_i); dw_ij = sum_b IFFT(conj(FFT x_j) o FFT dy_i)."""
+    p, q, k, B = 3, 2, 8, 4
+    w = RNG.standard_normal((p, q, k)); x = RNG.standard_normal((B, q * k)); dy = RNG.standard_normal((B, p * k))
+    dx = np.zeros((B, q * k)); dw = np.zeros((p, q, k))
+    for i in range(p):
+        G = np.fft.fft(dy[:, i * k:(i + 1) * k], axis=1)
+        for j in range(q):
+            dx[:, j * k:(j + 1) * k] += np.fft.ifft(np.conj(np.fft.fft(w[i, j]))[None, :] * G, axis=1).real
+            dw[i, j] = np.fft.ifft(np.conj(np.fft.fft(x[:, j * k:(j + 1) * k], axis=1)) * G, axis=1).real.sum(axis=0)
+    np.testing.assert_allclose(O.fc_backward_dx(w, dy), dx, atol=1e-12)
+    np.testing.assert_allclose(O.fc_backward_dw(x, dy, k), dw, atol=1e-12)
+
+
+# ---- CONV ----------------------------------------------------------------------------------
+def test_conv_r1_equals_fc_per_pixel():
+    p, q, k, N, H, W = 2, 3, 4, 2, 3, 5
+    w = RNG.standard_normal((1, 1, p, q, k))
+    x = RNG.standard_normal((N, q * k, H, W))
+    y = O.conv_forward(w, x, pad=0)
+    pix = x.transpose(0, 2, 3, 1).reshape(N * H * W, q * k)
+    ref = O.fc_forward(w[0, 0], pix).reshape(N, H, W, p * k).transpose(0, 3, 1, 2)
+    np.testing.assert_allclose(y, ref, atol=1e-13)
+
+
+@pytest.mark.parametrize("k,pad", [(1, 1), (4, 1), (4, 0), (2, 2)])
+def test_conv_vs_library_convolution(k, pad):
+    p, q, r, N, H, W = 2, 3, 3, 2, 6, 5
+    w = RNG.standard_normal((r, r, p, q, k))
+    x = RNG.standard_normal((N, q * k, H, W))
+    bias = RNG.standard_normal(p * k)
+    # dense filter bank built entry by entry from the block vectors (own loop, not the oracle's expansion)
+    Wd = np.zeros((p * k, q * k, r, r))
+    for dh in range(r):
+        for dw in range(r):
+            for i in range(p):
+                for j in range(q):
+                    for a in range(k):
+                        for b in range(k):
+                            Wd[i * k + a, j * k + b, dh, dw] = w[dh, dw, i, j, (a - b) % k]
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x), torch.from_numpy(Wd), torch.from_numpy(bias),
+                                     stride=1, padding=pad).numpy()
+    np.testing.assert_allclose(O.conv_forward(w, x, bias=bias, pad=pad), ref, atol=1e-12)
+    np.testing.assert_allclose(O.conv_forward(w, x, bias=bias, relu=True, pad=pad), np.maximum(ref, 0), atol=1e-12)
+
+
+def test_conv_single_pixel_response():
+    """One non-zero input pixel: the output shows the filter taps spatially reflected."""
+    p, q, k, r, H, W = 1, 1, 4, 3, 5, 5
+    w = RNG.standard_normal((r, r, p, q, k))
+    x = np.zeros((1, k, H, W)); x[0, 0, 2, 2] = 1.0          # channel 0, centre pixel
+    y = O.conv_forward(w, x, pad=1)
+    for dh in range(r):
+        for dw in range(r):
+            # y[h, w] takes x[h + dh - 1, w + dw - 1]: the tap (dh, dw) lands at (2 - dh + 1, 2 - dw + 1)
+            np.testing.assert_allclose(y[0, :, 3 - dh, 3 - dw], w[dh, dw, 0, 0, :], atol=1e-15)
+    assert np.count_nonzero(y) <= r * r * k
+
+
+def test_error_measure():
+    ref = np.array([1.0, -4.0, 0.0]); got = np.array([1.0, -4.0, 0.002])
+    assert abs(O.max_norm_rel_err(got, ref) - 0.0005) < 1e-15
+
+
+# ---- the generator itself: deterministic, right moments ------------------------------------
+def test_synth_streams():
+    a = synth.normal(5, 0, (4096,), 0.25); b = synth.normal(5, 0, (4096,), 0.25)
+    np.testing.assert_array_equal(a, b)
+    assert a.dtype == np.float32 and abs(a.std() - 0.5) < 0.03 and abs(a.mean()) < 0.03
+    u = synth.uniform(5, 1, (4096,), -1, 1)
+    assert u.min() >= -1 and u.max() <= 1 and abs(u.mean()) < 0.05 and abs(u.var() - 1 / 3) < 0.03
+    assert not np.array_equal(synth.uniform(6, 1, (16,), -1, 1), u[:16])
+    w, x, bias = synth.fc_inputs(synth.CFG2, batch=2)
+    assert w.shape == (64, 64, 64) and x.shape == (2, 4096) and bias.shape == (4096,)
+    assert abs(w.std() - 1 / 64) < 1e-3 and abs(bias.std() - 0.1) < 0.01
