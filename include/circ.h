@@ -1,0 +1,126 @@
+/*
+ * circ.h — C ABI of the block-circulant layer library for MI355X (gfx950).
+ *
+ * The library evaluates the product of a block-circulant weight matrix with a
+ * batch of activations (CirCNN, arXiv 1708.08917, Sec. 3): a p x q grid of
+ * k x k circulant blocks, each stored as one length-k vector w_ij, applied as
+ *
+ *     a_i = sum_j IFFT( FFT(w_ij) o FFT(x_j) )                (Algorithm 1)
+ *
+ * for fully-connected layers (forward and backward, Algorithms 1 and 2) and for
+ * CONV layers whose channel-mixing matrices are block-circulant (Sec. 3.2,
+ * Eq. 6 and Eq. 7).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Orientation: W_ij[a][b] = w_ij[(a - b) mod k]; w_ij is the first column of
+ *    its block and W_ij x_j is the circular convolution of w_ij with x_j.  This
+ *    is the reading under which the FFT formula of Sec. 3.1 holds as printed.
+ *  - All tensors are fp32, dense, row-major, in DEVICE memory of the current HIP
+ *    device.  Every pointer must be 16-byte aligned.  The caller owns every
+ *    buffer; the library allocates no device memory and keeps no global state.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work on it and return; nothing synchronises.
+ *  - Block size k must be a power of two with 2 <= k <= 512, and must divide the
+ *    layer widths exactly (p = m / k, q = n / k; the paper assumes the same).
+ *  - Errors are returned as circ_status; nothing aborts or throws across the
+ *    ABI.  Argument errors are detected on the host before any launch, so a
+ *    failing call has enqueued nothing.
+ *  - Output buffers must not alias input buffers.
+ */
+#ifndef CIRC_H_
+#define CIRC_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CIRC_OK = 0,
+  CIRC_EINVAL = -1,     /* null/misaligned pointer, non-positive size, bad k, aliasing */
+  CIRC_ENOTSUP = -2,    /* valid request this build does not implement (stride != 1, even r) */
+  CIRC_EWORKSPACE = -3, /* workspace NULL or smaller than the matching *_workspace_bytes */
+  CIRC_EHIP = -4        /* a HIP launch failed; hipGetLastError holds the detail */
+} circ_status;
+
+/* epilogue bit flags for the forward entry points (Eq. 1: y = psi(Wx + theta)) */
+enum { CIRC_EPI_NONE = 0, CIRC_EPI_BIAS = 1, CIRC_EPI_RELU = 2 };
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* circ_status_string(circ_status s);
+
+/*
+ * Size in bytes of the cached weight spectra for `n_grids` grids of p x q
+ * blocks of size k (n_grids = 1 for an FC layer, r*r for a CONV layer).
+ * Returns 0 for invalid arguments.  (Sec. 3.1: only w_ij or FFT(w_ij) needs to
+ * be stored; Sec. 4.2: the FFT results of the weights are what is kept in RAM.)
+ */
+size_t circ_spectra_bytes(int n_grids, int p, int q, int k);
+
+/*
+ * Weight-spectrum precompute: FFT(w_ij) for every block, half spectrum only
+ * (real input, Sec. 4.1), in the library's private layout.
+ *   w      device, [n_grids][p][q][k] fp32 (for CONV: grids in (dh, dw) order)
+ *   w_hat  device, circ_spectra_bytes(n_grids,p,q,k) bytes, opaque; must be
+ *          recomputed after every update of w.
+ */
+circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, int k,
+                                    void* w_hat, void* stream);
+
+/* Workspace size of circ_fc_forward (backward = 0) or circ_fc_backward (backward = 1). */
+size_t circ_fc_workspace_bytes(int p, int q, int k, int batch, int backward);
+
+/*
+ * FC forward (Algorithm 1 plus the bias/ReLU of Eq. 1):
+ *   y[b][i*k + t] = psi( sum_j (W_ij x_j[b])[t] + bias[i*k + t] ).
+ *   w_hat     device, from circ_precompute_spectra with n_grids = 1
+ *   x         device, [batch][q*k]
+ *   bias      device, [p*k]; required iff epilogue has CIRC_EPI_BIAS, else may be NULL
+ *   y         device, [batch][p*k], overwritten
+ *   workspace device scratch of at least circ_fc_workspace_bytes(p,q,k,batch,0) bytes
+ */
+circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias, float* y,
+                            int p, int q, int k, int batch, int epilogue,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * FC backward (Algorithm 2; Eq. 4 and Eq. 5).  `dy` is the gradient with respect
+ * to the pre-activation a = Wx + theta (the caller applies the ReLU mask).
+ *   dx[b][j*k + :] = sum_i IFFT( conj(FFT w_ij) o FFT(dy_i[b]) )        (may be NULL)
+ *   dw[i][j][:]    = sum_b IFFT( conj(FFT x_j[b]) o FFT(dy_i[b]) )      (may be NULL)
+ * Both are overwritten, not accumulated; the batch sum carries no 1/batch.
+ * The result is deterministic (no floating-point atomics).
+ *   workspace  at least circ_fc_workspace_bytes(p,q,k,batch,1) bytes
+ */
+circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
+                             float* dx, float* dw,
+                             int p, int q, int k, int batch,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace size of circ_conv_forward for the same arguments. */
+size_t circ_conv_workspace_bytes(int N, int C_in, int C_out, int H, int W,
+                                 int r, int stride, int pad, int k);
+
+/*
+ * Block-circulant CONV forward (Sec. 3.2, Eq. 6 with the weight structure of Eq. 7),
+ * cross-correlation with zero padding:
+ *   y[n][co][h][w] = psi( sum_{dh,dw,ci} Wd[dh][dw][co][ci] * x[n][ci][h+dh-pad][w+dw-pad] + bias[co] )
+ * where each Wd[dh][dw] is a (C_out/k) x (C_in/k) grid of k x k circulant blocks
+ * and the FFT runs over the channel dimension of every pixel.
+ *   w_hat  from circ_precompute_spectra with n_grids = r*r, p = C_out/k, q = C_in/k
+ *   x      device, NCHW [N][C_in][H][W]
+ *   bias   device, [C_out] (per output channel) or NULL
+ *   y      device, NCHW [N][C_out][H+2*pad-r+1][W+2*pad-r+1]
+ * stride must be 1 and r odd (CIRC_ENOTSUP otherwise); 0 <= pad < r.
+ */
+circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bias, float* y,
+                              int N, int C_in, int C_out, int H, int W,
+                              int r, int stride, int pad, int k, int epilogue,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CIRC_H_ */

@@ -1,0 +1,140 @@
+"""Thin ctypes binding of libcirc.so: argument marshalling only.
+
+Every step of the layers runs inside the HIP library; PyTorch is used here for
+device buffers and the current stream.  There is no CPU fallback: if the shared
+library is missing the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcirc.so")
+
+CIRC_OK, CIRC_EINVAL, CIRC_ENOTSUP, CIRC_EWORKSPACE, CIRC_EHIP = 0, -1, -2, -3, -4
+EPI_NONE, EPI_BIAS, EPI_RELU = 0, 1, 2
+
+_lib = None
+
+_c_int, _c_size, _c_ptr = ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
+
+SIGNATURES = {
+    "circ_status_string": (ctypes.c_char_p, [_c_int]),
+    "circ_spectra_bytes": (_c_size, [_c_int] * 4),
+    "circ_precompute_spectra": (_c_int, [_c_ptr, _c_int, _c_int, _c_int, _c_int, _c_ptr, _c_ptr]),
+    "circ_fc_workspace_bytes": (_c_size, [_c_int] * 5),
+    "circ_fc_forward": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_int, _c_int, _c_int, _c_int, _c_int,
+                                 _c_ptr, _c_size, _c_ptr]),
+    "circ_fc_backward": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_int, _c_int, _c_int, _c_int,
+                                  _c_ptr, _c_size, _c_ptr]),
+    "circ_conv_workspace_bytes": (_c_size, [_c_int] * 9),
+    "circ_conv_forward": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr] + [_c_int] * 10 + [_c_ptr, _c_size, _c_ptr]),
+}
+
+
+class CircError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+def lib() -> ctypes.CDLL:
+    """Load libcirc.so (built by paper_1708_08917_amd.build); fail loudly if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().circ_status_string(status).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != CIRC_OK:
+        raise CircError(status, where)
+
+
+def circ_spectra_bytes(n_grids: int, p: int, q: int, k: int) -> int:
+    return lib().circ_spectra_bytes(n_grids, p, q, k)
+
+
+def circ_fc_workspace_bytes(p: int, q: int, k: int, batch: int, backward: bool = False) -> int:
+    return lib().circ_fc_workspace_bytes(p, q, k, batch, int(backward))
+
+
+def circ_conv_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k) -> int:
+    return lib().circ_conv_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
+
+
+def circ_precompute_spectra(w: torch.Tensor, w_hat: torch.Tensor | None = None) -> torch.Tensor:
+    """w: device fp32 [p][q][k] or [r][r][p][q][k] -> opaque spectra blob (uint8 tensor)."""
+    assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous()
+    p, q, k = w.shape[-3:]
+    n_grids = int(w.numel() // (p * q * k))
+    nbytes = circ_spectra_bytes(n_grids, p, q, k)
+    if nbytes == 0:
+        raise CircError(CIRC_EINVAL, "circ_spectra_bytes")
+    if w_hat is None:
+        w_hat = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    _check(lib().circ_precompute_spectra(_ptr(w), n_grids, p, q, k, _ptr(w_hat), _stream()), "circ_precompute_spectra")
+    return w_hat
+
+
+def circ_fc_forward(w_hat, x, bias, y, p, q, k, epilogue=EPI_NONE, workspace=None):
+    """x: [batch][q*k] -> y: [batch][p*k] (y allocated if None).  Returns y."""
+    batch = x.shape[0]
+    if y is None:
+        y = torch.empty(batch, p * k, dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(1, circ_fc_workspace_bytes(p, q, k, batch)), dtype=torch.uint8, device=x.device)
+    _check(lib().circ_fc_forward(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), p, q, k, batch, epilogue,
+                                 _ptr(workspace), workspace.numel(), _stream()), "circ_fc_forward")
+    return y
+
+
+def circ_fc_backward(w_hat, x, dy, p, q, k, need_dx=True, need_dw=True, dx=None, dw=None, workspace=None):
+    """Returns (dx [batch][q*k] or None, dw [p][q][k] or None)."""
+    batch = dy.shape[0]
+    if need_dx and dx is None:
+        dx = torch.empty(batch, q * k, dtype=torch.float32, device=dy.device)
+    if need_dw and dw is None:
+        dw = torch.empty(p, q, k, dtype=torch.float32, device=dy.device)
+    if workspace is None:
+        workspace = torch.empty(max(1, circ_fc_workspace_bytes(p, q, k, batch, True)), dtype=torch.uint8,
+                                device=dy.device)
+    _check(lib().circ_fc_backward(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx if need_dx else None),
+                                  _ptr(dw if need_dw else None), p, q, k, batch, _ptr(workspace),
+                                  workspace.numel(), _stream()), "circ_fc_backward")
+    return (dx if need_dx else None), (dw if need_dw else None)
+
+
+def circ_conv_forward(w_hat, x, bias, y, C_out, r, stride, pad, k, epilogue=EPI_NONE, workspace=None):
+    """x: NCHW -> y: NCHW (allocated if None).  Returns y."""
+    N, C_in, H, W = x.shape
+    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    if y is None:
+        y = torch.empty(N, C_out, Ho, Wo, dtype=torch.float32, device=x.device)
+    if workspace is None:
+        nb = circ_conv_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
+        workspace = torch.empty(max(1, nb), dtype=torch.uint8, device=x.device)
+    _check(lib().circ_conv_forward(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), N, C_in, C_out, H, W, r, stride, pad,
+                                   k, epilogue, _ptr(workspace), workspace.numel(), _stream()), "circ_conv_forward")
+    return y

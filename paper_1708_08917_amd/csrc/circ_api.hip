@@ -1,0 +1,337 @@
+// C ABI of the block-circulant layer library: argument checks, workspace carving,
+// launch planning.  Every operation of the layers runs in the kernels of circ_kernels.h.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "../../include/circ.h"
+#include "circ_kernels.h"
+
+namespace {
+
+using namespace circ;
+
+constexpr int kMinK = 2, kMaxK = 512;
+
+inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+inline bool valid_k(int k) { return is_pow2(k) && k >= kMinK && k <= kMaxK; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
+
+inline size_t spectrum_elems(int k, long long rows) { return size_t(k / 2 + 1) * size_t(rows); }
+
+// Spectra blob: section 0 = forward operand [g][f][j][i] (i fastest), section 1 =
+// backward operand [g][f][i][j] (j fastest, conjugated).  Both carry the 1/k of the IFFT.
+inline size_t spectra_section_elems(int n_grids, int p, int q, int k) {
+  return size_t(n_grids) * spectrum_elems(k, (long long)p * q);
+}
+
+struct FftPlan { int P, NT; size_t lds; };
+
+// P column pairs per block, NT threads.  Small problems get small tiles so that the
+// launch still covers the chip; the tile must fit comfortably in LDS.
+FftPlan plan_fft(int K, long long nrows) {
+  int R2 = radix2_of(K);
+  int P = 64;
+  while (P > 8 && fft_tile_lds_bytes(K, P) > 40 * 1024) P >>= 1;
+  long long pairs = cdiv(nrows, 2);
+  while (P > 8 && cdiv(pairs, P) < 512) P >>= 1;
+  int TT = R2;
+  if (P * TT > 256) TT = 256 / P;
+  if (TT < 1) TT = 1;
+  int NT = P * TT;
+  if (NT < 64) NT = 64;
+  return FftPlan{P, NT, fft_tile_lds_bytes(K, P)};
+}
+
+template <int K>
+hipError_t launch_rfft_k(bool rows_fast, const float* in, float2* out, const RowMap& map, long long nrows,
+                         long long out_fstride, int n_grids, long long in_gstride, long long out_gstride,
+                         float scale, int conj, hipStream_t s) {
+  FftPlan pl = plan_fft(K, nrows);
+  dim3 grid((unsigned)cdiv(nrows, 2 * pl.P), (unsigned)n_grids);
+  if (rows_fast)
+    hipLaunchKernelGGL((rfft_kernel<K, true>), grid, dim3(pl.NT), pl.lds, s, in, out, map, nrows, out_fstride,
+                       in_gstride, out_gstride, pl.P, scale, conj);
+  else
+    hipLaunchKernelGGL((rfft_kernel<K, false>), grid, dim3(pl.NT), pl.lds, s, in, out, map, nrows, out_fstride,
+                       in_gstride, out_gstride, pl.P, scale, conj);
+  return hipGetLastError();
+}
+
+template <int K>
+hipError_t launch_irfft_k(bool rows_fast, const float2* in, float* out, const RowMap& map, long long nrows,
+                          long long in_fstride, float scale, const float* bias, long long bias_div, int relu,
+                          hipStream_t s) {
+  FftPlan pl = plan_fft(K, nrows);
+  dim3 grid((unsigned)cdiv(nrows, 2 * pl.P));
+  if (rows_fast)
+    hipLaunchKernelGGL((irfft_kernel<K, true>), grid, dim3(pl.NT), pl.lds, s, in, out, map, nrows, in_fstride,
+                       pl.P, scale, bias, bias_div, relu);
+  else
+    hipLaunchKernelGGL((irfft_kernel<K, false>), grid, dim3(pl.NT), pl.lds, s, in, out, map, nrows, in_fstride,
+                       pl.P, scale, bias, bias_div, relu);
+  return hipGetLastError();
+}
+
+#define CIRC_DISPATCH_K(k, CALL)                    \
+  switch (k) {                                      \
+    case 2: return CALL(2);                         \
+    case 4: return CALL(4);                         \
+    case 8: return CALL(8);                         \
+    case 16: return CALL(16);                       \
+    case 32: return CALL(32);                       \
+    case 64: return CALL(64);                       \
+    case 128: return CALL(128);                     \
+    case 256: return CALL(256);                     \
+    case 512: return CALL(512);                     \
+    default: return hipErrorInvalidValue;           \
+  }
+
+hipError_t launch_rfft(int k, bool rows_fast, const float* in, float2* out, const RowMap& map, long long nrows,
+                       long long out_fstride, int n_grids, long long in_gstride, long long out_gstride,
+                       float scale, int conj, hipStream_t s) {
+#define CALL(KK) launch_rfft_k<KK>(rows_fast, in, out, map, nrows, out_fstride, n_grids, in_gstride, out_gstride, scale, conj, s)
+  CIRC_DISPATCH_K(k, CALL)
+#undef CALL
+}
+
+hipError_t launch_irfft(int k, bool rows_fast, const float2* in, float* out, const RowMap& map, long long nrows,
+                        long long in_fstride, float scale, const float* bias, long long bias_div, int relu,
+                        hipStream_t s) {
+#define CALL(KK) launch_irfft_k<KK>(rows_fast, in, out, map, nrows, in_fstride, scale, bias, bias_div, relu, s)
+  CIRC_DISPATCH_K(k, CALL)
+#undef CALL
+}
+
+// C[f][m][n] = sum_kd A[f][kd][m] * (conj?)B[f][kd][n] for f in [0, NF)
+hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, bool conj_b,
+                        hipStream_t s) {
+  long long sA = (long long)Kd * M, sB = (long long)Kd * N, sC = (long long)M * N;
+  bool big = (long long)NF * cdiv(M, 32) * cdiv(N, 32) >= 1024;
+  int tile = big ? 32 : 16;
+  dim3 grid((unsigned)cdiv(N, tile), (unsigned)cdiv(M, tile), (unsigned)NF);
+  if (big) {
+    if (conj_b) hipLaunchKernelGGL((cgemm_kernel<32, true>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC);
+    else hipLaunchKernelGGL((cgemm_kernel<32, false>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC);
+  } else {
+    if (conj_b) hipLaunchKernelGGL((cgemm_kernel<16, true>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC);
+    else hipLaunchKernelGGL((cgemm_kernel<16, false>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC);
+  }
+  return hipGetLastError();
+}
+
+inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+  uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+  return x < y + nb && y < x + na;
+}
+
+// dims whose products must stay inside what the kernels index with 32-bit grid sizes
+inline bool fc_dims_ok(int p, int q, int k, int batch) {
+  if (p <= 0 || q <= 0 || batch <= 0 || !valid_k(k)) return false;
+  if ((long long)p * k > (1ll << 30) || (long long)q * k > (1ll << 30)) return false;
+  if ((long long)p * batch > (1ll << 31) - 1 || (long long)q * batch > (1ll << 31) - 1) return false;
+  if ((long long)p * q > (1ll << 31) - 1) return false;
+  if (batch > 65535 * 16 || p > 65535 * 16 || q > 65535 * 16) return false;   // gridDim.x/y limits of the GEMM
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* circ_status_string(circ_status s) {
+  switch (s) {
+    case CIRC_OK: return "CIRC_OK";
+    case CIRC_EINVAL: return "CIRC_EINVAL: invalid argument";
+    case CIRC_ENOTSUP: return "CIRC_ENOTSUP: not supported";
+    case CIRC_EWORKSPACE: return "CIRC_EWORKSPACE: workspace missing or too small";
+    case CIRC_EHIP: return "CIRC_EHIP: HIP launch failed";
+  }
+  return "unknown circ_status";
+}
+
+size_t circ_spectra_bytes(int n_grids, int p, int q, int k) {
+  if (n_grids <= 0 || p <= 0 || q <= 0 || !valid_k(k)) return 0;
+  if ((long long)p * q > (1ll << 31) - 1) return 0;
+  return 2 * align_up(spectra_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
+}
+
+circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, int k, void* w_hat, void* stream) {
+  if (!w || !w_hat || n_grids <= 0 || n_grids > 65535 || p <= 0 || q <= 0 || !valid_k(k)) return CIRC_EINVAL;
+  if ((long long)p * q > (1ll << 31) - 1) return CIRC_EINVAL;
+  if (!aligned16(w) || !aligned16(w_hat)) return CIRC_EINVAL;
+  size_t wbytes = size_t(n_grids) * p * q * k * sizeof(float);
+  if (overlaps(w, wbytes, w_hat, circ_spectra_bytes(n_grids, p, q, k))) return CIRC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t sec = align_up(spectra_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
+  float2* fwd = static_cast<float2*>(w_hat);
+  float2* bwd = reinterpret_cast<float2*>(static_cast<char*>(w_hat) + sec);
+  const long long rows = (long long)p * q;
+  const long long in_g = rows * k, out_g = (long long)spectrum_elems(k, rows);
+  const float inv_k = 1.0f / float(k);
+  // forward operand: row id = j*p + i  ->  w[i][j][:]
+  RowMap mf{p, q, (long long)q * k, (long long)k, 0, 1};
+  if (launch_rfft(k, false, w, fwd, mf, rows, rows, n_grids, in_g, out_g, inv_k, 0, s) != hipSuccess) return CIRC_EHIP;
+  // backward operand: row id = i*q + j, conjugated
+  RowMap mb{q, p, (long long)k, (long long)q * k, 0, 1};
+  if (launch_rfft(k, false, w, bwd, mb, rows, rows, n_grids, in_g, out_g, inv_k, 1, s) != hipSuccess) return CIRC_EHIP;
+  return CIRC_OK;
+}
+
+size_t circ_fc_workspace_bytes(int p, int q, int k, int batch, int backward) {
+  if (!fc_dims_ok(p, q, k, batch)) return 0;
+  size_t xa = align_up(spectrum_elems(k, (long long)q * batch) * sizeof(float2), 256);
+  size_t ya = align_up(spectrum_elems(k, (long long)p * batch) * sizeof(float2), 256);
+  if (!backward) return xa + ya;
+  size_t wa = align_up(spectrum_elems(k, (long long)p * q) * sizeof(float2), 256);
+  return xa + ya + wa;
+}
+
+circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias, float* y, int p, int q, int k,
+                            int batch, int epilogue, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!fc_dims_ok(p, q, k, batch)) return CIRC_EINVAL;
+  if (!w_hat || !x || !y) return CIRC_EINVAL;
+  if (epilogue & ~(CIRC_EPI_BIAS | CIRC_EPI_RELU)) return CIRC_EINVAL;
+  const bool use_bias = epilogue & CIRC_EPI_BIAS;
+  if (use_bias && !bias) return CIRC_EINVAL;
+  if (!aligned16(w_hat) || !aligned16(x) || !aligned16(y) || (use_bias && !aligned16(bias))) return CIRC_EINVAL;
+  const size_t xbytes = size_t(batch) * q * k * sizeof(float), ybytes = size_t(batch) * p * k * sizeof(float);
+  if (overlaps(x, xbytes, y, ybytes)) return CIRC_EINVAL;
+  const size_t need = circ_fc_workspace_bytes(p, q, k, batch, 0);
+  if (!workspace || workspace_bytes < need) return CIRC_EWORKSPACE;
+  if (!aligned16(workspace)) return CIRC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  const int NF = k / 2 + 1;
+  float2* xh = static_cast<float2*>(workspace);
+  float2* yh = reinterpret_cast<float2*>(static_cast<char*>(workspace) +
+                                         align_up(spectrum_elems(k, (long long)q * batch) * sizeof(float2), 256));
+  const float2* wf = static_cast<const float2*>(w_hat);
+  const long long xrows = (long long)q * batch, yrows = (long long)p * batch;
+  // X^[f][j][b]: row id = j*batch + b -> x[b][j*k : (j+1)*k]
+  RowMap mx{batch, q, (long long)q * k, (long long)k, 0, 1};
+  if (launch_rfft(k, false, x, xh, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+  // Y^[f][i][b] = sum_j W^[f][j][i] X^[f][j][b]
+  if (launch_cgemm(wf, xh, yh, NF, p, batch, q, false, s) != hipSuccess) return CIRC_EHIP;
+  RowMap my{batch, p, (long long)p * k, (long long)k, 0, 1};
+  if (launch_irfft(k, false, yh, y, my, yrows, yrows, 1.0f, use_bias ? bias : nullptr, batch,
+                   (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
+    return CIRC_EHIP;
+  return CIRC_OK;
+}
+
+circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy, float* dx, float* dw, int p, int q,
+                             int k, int batch, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!fc_dims_ok(p, q, k, batch)) return CIRC_EINVAL;
+  if (!w_hat || !dy) return CIRC_EINVAL;
+  if (!dx && !dw) return CIRC_EINVAL;
+  if (dw && !x) return CIRC_EINVAL;
+  if (!aligned16(w_hat) || !aligned16(dy) || !aligned16(x) || !aligned16(dx) || !aligned16(dw)) return CIRC_EINVAL;
+  const size_t xbytes = size_t(batch) * q * k * sizeof(float), ybytes = size_t(batch) * p * k * sizeof(float);
+  const size_t wbytes = size_t(p) * q * k * sizeof(float);
+  if (dx && (overlaps(dx, xbytes, dy, ybytes) || (x && overlaps(dx, xbytes, x, xbytes)))) return CIRC_EINVAL;
+  if (dw && (overlaps(dw, wbytes, dy, ybytes) || overlaps(dw, wbytes, x, xbytes))) return CIRC_EINVAL;
+  if (dx && dw && overlaps(dx, xbytes, dw, wbytes)) return CIRC_EINVAL;
+  const size_t need = circ_fc_workspace_bytes(p, q, k, batch, 1);
+  if (!workspace || workspace_bytes < need) return CIRC_EWORKSPACE;
+  if (!aligned16(workspace)) return CIRC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  const int NF = k / 2 + 1;
+  const size_t xa = align_up(spectrum_elems(k, (long long)q * batch) * sizeof(float2), 256);
+  const size_t ya = align_up(spectrum_elems(k, (long long)p * batch) * sizeof(float2), 256);
+  float2* bufx = static_cast<float2*>(workspace);
+  float2* bufy = reinterpret_cast<float2*>(static_cast<char*>(workspace) + xa);
+  float2* bufw = reinterpret_cast<float2*>(static_cast<char*>(workspace) + xa + ya);
+  const size_t sec = align_up(spectra_section_elems(1, p, q, k) * sizeof(float2), 256);
+  const float2* wb = reinterpret_cast<const float2*>(static_cast<const char*>(w_hat) + sec);
+  const long long xrows = (long long)q * batch, yrows = (long long)p * batch;
+
+  if (dx) {
+    // dY^[f][i][b];  dX^[f][j][b] = sum_i conj(W^)[f][i][j] dY^[f][i][b]
+    RowMap mdy{batch, p, (long long)p * k, (long long)k, 0, 1};
+    if (launch_rfft(k, false, dy, bufy, mdy, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    if (launch_cgemm(wb, bufy, bufx, NF, q, batch, p, false, s) != hipSuccess) return CIRC_EHIP;
+    RowMap mdx{batch, q, (long long)q * k, (long long)k, 0, 1};
+    if (launch_irfft(k, false, bufx, dx, mdx, xrows, xrows, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
+  }
+  if (dw) {
+    // batch-major spectra: dY^[f][b][i], X^[f][b][j];  dW^[f][i][j] = sum_b dY^[f][b][i] conj(X^[f][b][j])
+    RowMap mdy{p, batch, (long long)k, (long long)p * k, 0, 1};
+    if (launch_rfft(k, false, dy, bufy, mdy, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    RowMap mx{q, batch, (long long)k, (long long)q * k, 0, 1};
+    if (launch_rfft(k, false, x, bufx, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    if (launch_cgemm(bufy, bufx, bufw, NF, p, q, batch, true, s) != hipSuccess) return CIRC_EHIP;
+    const long long wrows = (long long)p * q;
+    RowMap mw{q, p, (long long)k, (long long)q * k, 0, 1};
+    if (launch_irfft(k, false, bufw, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s) != hipSuccess)
+      return CIRC_EHIP;
+  }
+  return CIRC_OK;
+}
+
+static bool conv_dims_ok(int N, int C_in, int C_out, int H, int W, int r, int pad, int k) {
+  if (N <= 0 || C_in <= 0 || C_out <= 0 || H <= 0 || W <= 0 || r <= 0 || !valid_k(k)) return false;
+  if (C_in % k || C_out % k) return false;
+  if (pad < 0 || pad >= r) return false;
+  if (H + 2 * pad < r || W + 2 * pad < r) return false;
+  long long pix = (long long)N * H * W;
+  if (pix * (C_in / k) > (1ll << 31) - 1 || pix * (C_out / k) > (1ll << 31) - 1) return false;
+  if (r * r > 65535 || (C_out / k) > 65535 * 4 || k / 2 + 1 > 65535) return false;
+  return true;
+}
+
+size_t circ_conv_workspace_bytes(int N, int C_in, int C_out, int H, int W, int r, int stride, int pad, int k) {
+  if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k) || stride != 1 || (r % 2) == 0) return 0;
+  const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
+  size_t xa = align_up(spectrum_elems(k, (long long)(C_in / k) * N * H * W) * sizeof(float2), 256);
+  size_t ya = align_up(spectrum_elems(k, (long long)(C_out / k) * N * Ho * Wo) * sizeof(float2), 256);
+  return xa + ya;
+}
+
+circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bias, float* y, int N, int C_in,
+                              int C_out, int H, int W, int r, int stride, int pad, int k, int epilogue,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k)) return CIRC_EINVAL;
+  if (stride <= 0) return CIRC_EINVAL;
+  if (stride != 1 || (r % 2) == 0) return CIRC_ENOTSUP;
+  if (!w_hat || !x || !y) return CIRC_EINVAL;
+  if (epilogue & ~(CIRC_EPI_BIAS | CIRC_EPI_RELU)) return CIRC_EINVAL;
+  const bool use_bias = epilogue & CIRC_EPI_BIAS;
+  if (use_bias && !bias) return CIRC_EINVAL;
+  if (!aligned16(w_hat) || !aligned16(x) || !aligned16(y) || (use_bias && !aligned16(bias))) return CIRC_EINVAL;
+  const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
+  const size_t xbytes = size_t(N) * C_in * H * W * sizeof(float), ybytes = size_t(N) * C_out * Ho * Wo * sizeof(float);
+  if (overlaps(x, xbytes, y, ybytes)) return CIRC_EINVAL;
+  const size_t need = circ_conv_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k);
+  if (!workspace || workspace_bytes < need) return CIRC_EWORKSPACE;
+  if (!aligned16(workspace)) return CIRC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  const int p = C_out / k, q = C_in / k, NF = k / 2 + 1;
+  const long long HW = (long long)H * W, HWo = (long long)Ho * Wo;
+  const long long xrows = (long long)q * N * HW, yrows = (long long)p * N * HWo;
+  float2* xh = static_cast<float2*>(workspace);
+  float2* yh = reinterpret_cast<float2*>(static_cast<char*>(workspace) +
+                                         align_up(spectrum_elems(k, xrows) * sizeof(float2), 256));
+  // X^[f][j][n][pixel]: the FFT runs down the channel axis (element stride H*W)
+  RowMap mx{(int)HW, N, 1, (long long)C_in * HW, (long long)k * HW, HW};
+  if (launch_rfft(k, true, x, xh, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+  {
+    constexpr int IT = 4;
+    const long long npix = (long long)N * HWo;
+    dim3 grid((unsigned)cdiv(npix, 256), (unsigned)NF, (unsigned)cdiv(p, IT));
+    hipLaunchKernelGGL((conv_contract_kernel<IT>), grid, dim3(256), 0, s, static_cast<const float2*>(w_hat), xh, yh,
+                       p, q, NF, N, H, W, Ho, Wo, r, pad);
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  }
+  RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo};
+  if (launch_irfft(k, true, yh, y, my, yrows, yrows, 1.0f, use_bias ? bias : nullptr, (long long)N * HWo,
+                   (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
+    return CIRC_EHIP;
+  return CIRC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,158 @@
+// Length-K complex FFT of a tile of column pairs held in LDS.
+//
+// The paper's FFT kernel is recursive radix-2: a size-n transform is two size-n/2
+// transforms plus one butterfly level (Sec. 4.1).  On a wave64 machine the recursion
+// is cut in two at K = R1 * R2: each lane runs whole radix-2 sub-transforms of R1 (then
+// R2) points in registers with compile-time twiddles, and the two passes exchange
+// data through LDS.  Real inputs are exploited (Sec. 4.1: the symmetric half of the
+// spectrum is never computed or stored) by packing two real rows into one complex
+// sequence z = row_a + i*row_b; the half spectra of both rows are separated from
+// Z[f] and conj(Z[K-f]) when the tile is written out.
+//
+// LDS layout of a tile: two float planes (re, im), element (n, pair) at n*PP + pair,
+// with `pair` the fastest index so that lanes of a wave that work on the same n hit
+// consecutive banks.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "circ_twiddle.h"
+
+namespace circ {
+
+__device__ const TwiddleTable kTw = TwiddleTable();
+
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
+// K = R1 * R2 with R2 <= R1 <= 2 * R2
+constexpr int radix2_of(int K) { return 1 << (ilog2(K) / 2); }
+constexpr int radix1_of(int K) { return K / radix2_of(K); }
+
+// ---- in-register radix-2 FFT of R points, natural order in and out ------------------
+template <int R, bool INV>
+struct FftReg {
+  template <int M>
+  static __device__ __forceinline__ void combine(float (&re)[R], float (&im)[R],
+                                                 const float (&er)[R / 2], const float (&ei)[R / 2],
+                                                 const float (&pr)[R / 2], const float (&pi)[R / 2]) {
+    if constexpr (M < R / 2) {
+      float tr, ti;
+      if constexpr (M == 0) {
+        tr = pr[M];
+        ti = pi[M];
+      } else if constexpr (4 * M == R) {           // twiddle = -i (forward) or +i (inverse)
+        tr = INV ? -pi[M] : pi[M];
+        ti = INV ? pr[M] : -pr[M];
+      } else {
+        constexpr float c = tw_cos(M, R);
+        constexpr float s = INV ? tw_sin(M, R) : -tw_sin(M, R);   // twiddle = c + i*s
+        tr = c * pr[M] - s * pi[M];
+        ti = c * pi[M] + s * pr[M];
+      }
+      re[M] = er[M] + tr;
+      im[M] = ei[M] + ti;
+      re[M + R / 2] = er[M] - tr;
+      im[M + R / 2] = ei[M] - ti;
+      combine<M + 1>(re, im, er, ei, pr, pi);
+    }
+  }
+
+  static __device__ __forceinline__ void run(float (&re)[R], float (&im)[R]) {
+    float er[R / 2], ei[R / 2], pr[R / 2], pi[R / 2];
+#pragma unroll
+    for (int i = 0; i < R / 2; ++i) {
+      er[i] = re[2 * i];
+      ei[i] = im[2 * i];
+      pr[i] = re[2 * i + 1];
+      pi[i] = im[2 * i + 1];
+    }
+    FftReg<R / 2, INV>::run(er, ei);
+    FftReg<R / 2, INV>::run(pr, pi);
+    combine<0>(re, im, er, ei, pr, pi);
+  }
+};
+
+template <bool INV>
+struct FftReg<1, INV> {
+  static __device__ __forceinline__ void run(float (&)[1], float (&)[1]) {}
+};
+
+// ---- the two LDS passes ------------------------------------------------------------
+// Index split: n = R2*n1 + n2 on the way in, f = f1 + R1*f2 on the way out:
+//   pass 1: A[f1][n2] = sum_n1 z[R2*n1+n2] W_R1^(f1*n1), then times W_K^(f1*n2)
+//   pass 2: Z[f1+R1*f2] = sum_n2 A[f1][n2] W_R2^(f2*n2)
+// Both passes work in place; after pass 2 the value of index f sits at
+// position fft_pos<K>(f) = R2*(f % R1) + f / R1.
+template <int K>
+__device__ __forceinline__ int fft_pos(int f) {
+  constexpr int R2 = radix2_of(K), R1 = radix1_of(K);
+  return R2 * (f % R1) + f / R1;
+}
+
+// pair: column of this thread; t, TT: index and count of threads sharing a column.
+template <int K, bool INV>
+__device__ __forceinline__ void fft_lds_pass1(float* zre, float* zim, int PP, int pair, int t, int TT) {
+  constexpr int R2 = radix2_of(K), R1 = radix1_of(K);
+  for (int n2 = t; n2 < R2; n2 += TT) {
+    float re[R1], im[R1];
+#pragma unroll
+    for (int n1 = 0; n1 < R1; ++n1) {
+      re[n1] = zre[(R2 * n1 + n2) * PP + pair];
+      im[n1] = zim[(R2 * n1 + n2) * PP + pair];
+    }
+    FftReg<R1, INV>::run(re, im);
+#pragma unroll
+    for (int f1 = 0; f1 < R1; ++f1) {
+      float vr = re[f1], vi = im[f1];
+      if (f1 > 0 && R2 > 1) {
+        int ti = f1 * n2 * (kTwN / K);
+        float c = kTw.c[ti];
+        float s = INV ? kTw.s[ti] : -kTw.s[ti];
+        float xr = c * vr - s * vi;
+        vi = c * vi + s * vr;
+        vr = xr;
+      }
+      zre[(R2 * f1 + n2) * PP + pair] = vr;
+      zim[(R2 * f1 + n2) * PP + pair] = vi;
+    }
+  }
+}
+
+template <int K, bool INV>
+__device__ __forceinline__ void fft_lds_pass2(float* zre, float* zim, int PP, int pair, int t, int TT) {
+  constexpr int R2 = radix2_of(K), R1 = radix1_of(K);
+  if constexpr (R2 > 1) {
+    for (int f1 = t; f1 < R1; f1 += TT) {
+      float re[R2], im[R2];
+#pragma unroll
+      for (int n2 = 0; n2 < R2; ++n2) {
+        re[n2] = zre[(R2 * f1 + n2) * PP + pair];
+        im[n2] = zim[(R2 * f1 + n2) * PP + pair];
+      }
+      FftReg<R2, INV>::run(re, im);
+#pragma unroll
+      for (int f2 = 0; f2 < R2; ++f2) {
+        zre[(R2 * f1 + f2) * PP + pair] = re[f2];
+        zim[(R2 * f1 + f2) * PP + pair] = im[f2];
+      }
+    }
+  }
+}
+
+// ---- addressing of "rows" (the length-K vectors that are transformed) ----------------
+// Row ids enumerate the rows in the order of the spectrum buffer:
+// spectrum[f][rid].  A row id decomposes as rid = (a*n1 + b)*n0 + c and the first
+// element of the row sits at c*s0 + b*s1 + a*s2; consecutive elements are `es` apart.
+struct RowMap {
+  int n0, n1;
+  long long s0, s1, s2, es;
+};
+
+__device__ __forceinline__ long long row_base(const RowMap& m, long long rid) {
+  long long c = rid % m.n0;
+  long long ab = rid / m.n0;
+  long long b = ab % m.n1;
+  long long a = ab / m.n1;
+  return c * m.s0 + b * m.s1 + a * m.s2;
+}
+
+}  // namespace circ

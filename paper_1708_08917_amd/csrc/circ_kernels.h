@@ -1,0 +1,271 @@
+// HIP kernels (gfx950) of the block-circulant layer pipeline:
+//   rfft_kernel      real rows -> half spectra            (FFT of Algorithm 1 / 2)
+//   cgemm_kernel     per-frequency complex contraction on the fp32 matrix cores
+//                    (the "o" of Algorithm 1 with the sum over j moved inside the IFFT,
+//                    which Eq. 3 allows because the transform is linear)
+//   conv_contract_kernel  the same contraction for CONV: sum over the r*r offsets and
+//                    the input channel blocks (Eq. 6 / Eq. 7)
+//   irfft_kernel     half spectra -> real rows, fused bias + ReLU (Eq. 1)
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "circ_fft.h"
+
+namespace circ {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// LDS bytes of one FFT tile of P column pairs.
+inline size_t fft_tile_lds_bytes(int K, int P) {
+  return size_t(2 * K * (P + 1) + 16) * sizeof(float) + size_t(2 * P) * (sizeof(long long) + sizeof(int));
+}
+
+struct TileLds {
+  float* zre;
+  float* zim;
+  long long* rbase;
+  int* rblk;
+};
+
+template <int K>
+__device__ __forceinline__ TileLds carve_tile(float* smem, int P) {
+  const int PP = P + 1;
+  TileLds t;
+  t.zre = smem;
+  t.zim = smem + K * PP + 16;   // +16 floats: the two planes start half a bank row apart
+  t.rbase = reinterpret_cast<long long*>(t.zim + K * PP);
+  t.rblk = reinterpret_cast<int*>(t.rbase + 2 * P);
+  return t;
+}
+
+// -------------------------------------------------------------------------------------
+// Forward real FFT of rows.  Block b handles rows [2*P*b, 2*P*(b+1)); out[f*fstride + rid]
+// holds bin f (0..K/2) of row rid, scaled by `scale`, conjugated if `conj`.
+// blockIdx.y selects one of several independent grids (weight precompute for CONV).
+// ROWS_FAST: consecutive rows are adjacent in memory (CONV, NCHW: the FFT axis is the
+// channel axis and pixels are contiguous) — lanes then run along rows when loading.
+template <int K, bool ROWS_FAST>
+__global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ out, RowMap map,
+                            long long nrows, long long out_fstride, long long in_gstride,
+                            long long out_gstride, int P, float scale, int conj) {
+  extern __shared__ float smem[];
+  const int PP = P + 1;
+  const int lgP = __ffs(P) - 1;
+  TileLds L = carve_tile<K>(smem, P);
+  in += (long long)blockIdx.y * in_gstride;
+  out += (long long)blockIdx.y * out_gstride;
+  const long long t0 = (long long)blockIdx.x * 2 * P;
+  const int tid = threadIdx.x, NT = blockDim.x;
+
+  for (int r = tid; r < 2 * P; r += NT) {
+    long long rid = t0 + r;
+    L.rbase[r] = rid < nrows ? row_base(map, rid) : -1;
+  }
+  __syncthreads();
+
+  // load: row 2u -> real part of column u, row 2u+1 -> imaginary part
+  if (ROWS_FAST) {
+    for (int idx = tid; idx < 2 * P * K; idx += NT) {
+      int row = idx & (2 * P - 1), n = idx >> (lgP + 1);
+      long long b = L.rbase[row];
+      float v = b >= 0 ? in[b + n * map.es] : 0.f;
+      ((row & 1) ? L.zim : L.zre)[n * PP + (row >> 1)] = v;
+    }
+  } else {
+    for (int idx = tid; idx < 2 * P * K; idx += NT) {
+      int row = idx / K, n = idx % K;
+      long long b = L.rbase[row];
+      float v = b >= 0 ? in[b + n * map.es] : 0.f;
+      ((row & 1) ? L.zim : L.zre)[n * PP + (row >> 1)] = v;
+    }
+  }
+  __syncthreads();
+
+  const int pair = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
+  fft_lds_pass1<K, false>(L.zre, L.zim, PP, pair, t, TT);
+  __syncthreads();
+  fft_lds_pass2<K, false>(L.zre, L.zim, PP, pair, t, TT);
+  __syncthreads();
+
+  // separate the two real rows of each column and store bins 0..K/2
+  constexpr int NF = K / 2 + 1;
+  for (int idx = tid; idx < NF * P; idx += NT) {
+    int pr = idx & (P - 1), f = idx >> lgP;
+    int p1 = fft_pos<K>(f) * PP + pr, p2 = fft_pos<K>((K - f) % K) * PP + pr;
+    float a = L.zre[p1], b = L.zim[p1], c = L.zre[p2], d = L.zim[p2];
+    float h = 0.5f * scale;
+    float2 xa = make_float2(h * (a + c), h * (b - d));
+    float2 xb = make_float2(h * (b + d), h * (c - a));
+    if (conj) { xa.y = -xa.y; xb.y = -xb.y; }
+    long long rid = t0 + 2 * pr;
+    float2* o = out + f * out_fstride + rid;
+    if (rid < nrows) o[0] = xa;
+    if (rid + 1 < nrows) o[1] = xb;
+  }
+}
+
+// -------------------------------------------------------------------------------------
+// Inverse real FFT of rows with epilogue:  out_row[n] = psi(scale * z[n] + bias[blk*K + n]),
+// blk = rid / bias_div (the output block row / channel block of the row).
+template <int K, bool ROWS_FAST>
+__global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ out, RowMap map,
+                             long long nrows, long long in_fstride, int P, float scale,
+                             const float* __restrict__ bias, long long bias_div, int relu) {
+  extern __shared__ float smem[];
+  const int PP = P + 1;
+  const int lgP = __ffs(P) - 1;
+  TileLds L = carve_tile<K>(smem, P);
+  const long long t0 = (long long)blockIdx.x * 2 * P;
+  const int tid = threadIdx.x, NT = blockDim.x;
+
+  for (int r = tid; r < 2 * P; r += NT) {
+    long long rid = t0 + r;
+    bool ok = rid < nrows;
+    L.rbase[r] = ok ? row_base(map, rid) : -1;
+    L.rblk[r] = ok ? int(rid / bias_div) : 0;
+  }
+
+  // build Z = Ya + i*Yb on all K bins from the two half spectra (Hermitian symmetry)
+  constexpr int NF = K / 2 + 1;
+  for (int idx = tid; idx < NF * P; idx += NT) {
+    int pr = idx & (P - 1), f = idx >> lgP;
+    long long rid = t0 + 2 * pr;
+    const float2* s = in + f * in_fstride + rid;
+    float2 ya = rid < nrows ? s[0] : make_float2(0.f, 0.f);
+    float2 yb = rid + 1 < nrows ? s[1] : make_float2(0.f, 0.f);
+    if (f == 0 || 2 * f == K) {            // DC and Nyquist bins of a real signal are real
+      L.zre[f * PP + pr] = ya.x;
+      L.zim[f * PP + pr] = yb.x;
+    } else {
+      L.zre[f * PP + pr] = ya.x - yb.y;
+      L.zim[f * PP + pr] = ya.y + yb.x;
+      L.zre[(K - f) * PP + pr] = ya.x + yb.y;
+      L.zim[(K - f) * PP + pr] = yb.x - ya.y;
+    }
+  }
+  __syncthreads();
+
+  const int pair = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
+  fft_lds_pass1<K, true>(L.zre, L.zim, PP, pair, t, TT);
+  __syncthreads();
+  fft_lds_pass2<K, true>(L.zre, L.zim, PP, pair, t, TT);
+  __syncthreads();
+
+  for (int idx = tid; idx < 2 * P * K; idx += NT) {
+    int row, n;
+    if (ROWS_FAST) { row = idx & (2 * P - 1); n = idx >> (lgP + 1); }
+    else { row = idx / K; n = idx % K; }
+    long long b = L.rbase[row];
+    if (b < 0) continue;
+    float v = ((row & 1) ? L.zim : L.zre)[fft_pos<K>(n) * PP + (row >> 1)] * scale;
+    if (bias) v += bias[(long long)L.rblk[row] * K + n];
+    if (relu) v = fmaxf(v, 0.f);
+    out[b + n * map.es] = v;
+  }
+}
+
+// -------------------------------------------------------------------------------------
+// Per-frequency complex GEMM on the fp32 MFMA units, one wave per output tile:
+//   C[f][m][n] = sum_k A[f][k][m] * B[f][k][n]        (B conjugated if CONJ_B)
+// A is stored with m fastest, B and C with n fastest, so every operand load is one
+// contiguous run per k.  A complex product is four real MFMA accumulations.
+// TILE = 32 uses v_mfma_f32_32x32x2_f32, TILE = 16 uses v_mfma_f32_16x16x4_f32.
+template <int TILE, bool CONJ_B>
+__global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
+                                                   const float2* __restrict__ B,
+                                                   float2* __restrict__ C, int M, int N, int Kd,
+                                                   long long sA, long long sB, long long sC) {
+  constexpr int KS = 64 / TILE;           // k values per MFMA: 2 or 4
+  constexpr int NACC = TILE * TILE / 64;  // accumulator registers per lane: 16 or 4
+  typedef float accv __attribute__((ext_vector_type(NACC)));
+  const int lane = threadIdx.x;
+  const int f = blockIdx.z, m0 = blockIdx.y * TILE, n0 = blockIdx.x * TILE;
+  A += f * sA;
+  B += f * sB;
+  C += f * sC;
+  const int kk = lane / TILE, mm = lane % TILE;
+  const int am = min(m0 + mm, M - 1);
+  const int bn = min(n0 + mm, N - 1);
+  accv accR, accI;
+#pragma unroll
+  for (int r = 0; r < NACC; ++r) { accR[r] = 0.f; accI[r] = 0.f; }
+
+#pragma unroll 4
+  for (int k0 = 0; k0 < Kd; k0 += KS) {
+    int kidx = k0 + kk;
+    int kc = min(kidx, Kd - 1);
+    float2 a = A[(long long)kc * M + am];
+    float2 b = B[(long long)kc * N + bn];
+    if (kidx >= Kd) { a = make_float2(0.f, 0.f); b = make_float2(0.f, 0.f); }
+    // (ar + i ai)(br + i bi) = (ar br - ai bi) + i (ar bi + ai br); conj(b): bi -> -bi
+    float a_for_rr = a.x, a_for_ii = CONJ_B ? a.y : -a.y;
+    float a_for_ri = CONJ_B ? -a.x : a.x, a_for_ir = a.y;
+    if constexpr (TILE == 32) {
+      accR = __builtin_amdgcn_mfma_f32_32x32x2f32(a_for_rr, b.x, accR, 0, 0, 0);
+      accR = __builtin_amdgcn_mfma_f32_32x32x2f32(a_for_ii, b.y, accR, 0, 0, 0);
+      accI = __builtin_amdgcn_mfma_f32_32x32x2f32(a_for_ri, b.y, accI, 0, 0, 0);
+      accI = __builtin_amdgcn_mfma_f32_32x32x2f32(a_for_ir, b.x, accI, 0, 0, 0);
+    } else {
+      accR = __builtin_amdgcn_mfma_f32_16x16x4f32(a_for_rr, b.x, accR, 0, 0, 0);
+      accR = __builtin_amdgcn_mfma_f32_16x16x4f32(a_for_ii, b.y, accR, 0, 0, 0);
+      accI = __builtin_amdgcn_mfma_f32_16x16x4f32(a_for_ri, b.y, accI, 0, 0, 0);
+      accI = __builtin_amdgcn_mfma_f32_16x16x4f32(a_for_ir, b.x, accI, 0, 0, 0);
+    }
+  }
+
+  // accumulator layout: column = lane % TILE; rows in groups of 4
+  const int j = n0 + lane % TILE;
+#pragma unroll
+  for (int r = 0; r < NACC; ++r) {
+    int i;
+    if constexpr (TILE == 32) i = 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+    else i = 4 * (lane / 16) + r;
+    i += m0;
+    if (i < M && j < N) C[(long long)i * N + j] = make_float2(accR[r], accI[r]);
+  }
+}
+
+// -------------------------------------------------------------------------------------
+// CONV contraction, one thread per (frequency, image, output pixel), IT output channel
+// blocks at a time:
+//   Yh[f][i][n][ho][wo] = sum_{dh,dw,j} What[dh*r+dw][f][j][i] * Xh[f][j][n][ho+dh-pad][wo+dw-pad]
+// with zero spectra outside the image (the channel FFT of a zero pixel is zero, so the
+// spatial shift is taken after the transform and every input pixel is transformed once).
+template <int IT>
+__global__ void conv_contract_kernel(const float2* __restrict__ What, const float2* __restrict__ Xh,
+                                     float2* __restrict__ Yh, int p, int q, int NF, int Nimg, int H,
+                                     int W, int Ho, int Wo, int r, int pad) {
+  const long long npix = (long long)Nimg * Ho * Wo;
+  const long long opix = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (opix >= npix) return;
+  const int f = blockIdx.y, i0 = blockIdx.z * IT;
+  const int n = int(opix / (Ho * Wo)), rem = int(opix % (Ho * Wo));
+  const int ho = rem / Wo, wo = rem % Wo;
+  float2 acc[IT];
+#pragma unroll
+  for (int ii = 0; ii < IT; ++ii) acc[ii] = make_float2(0.f, 0.f);
+  for (int dh = 0; dh < r; ++dh) {
+    for (int dw = 0; dw < r; ++dw) {
+      const int hi = ho + dh - pad, wi = wo + dw - pad;
+      const bool inb = hi >= 0 && hi < H && wi >= 0 && wi < W;
+      const float2* wg = What + ((long long)(dh * r + dw) * NF + f) * q * p;
+      for (int j = 0; j < q; ++j) {
+        float2 xv = make_float2(0.f, 0.f);
+        if (inb) xv = Xh[(((long long)f * q + j) * Nimg + n) * H * W + hi * W + wi];
+#pragma unroll
+        for (int ii = 0; ii < IT; ++ii) {
+          float2 wv = wg[j * p + min(i0 + ii, p - 1)];
+          acc[ii].x += wv.x * xv.x - wv.y * xv.y;
+          acc[ii].y += wv.x * xv.y + wv.y * xv.x;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int ii = 0; ii < IT; ++ii)
+    if (i0 + ii < p) Yh[(((long long)f * p + i0 + ii) * Nimg + n) * Ho * Wo + rem] = acc[ii];
+}
+
+}  // namespace circ

@@ -1,0 +1,39 @@
+"""Glue for the GPU parity tests: numpy in -> C ABI on cuda:0 -> numpy out."""
+import numpy as np
+import torch
+
+from paper_1708_08917_amd import binding as B
+
+DEV = "cuda:0"
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def epi_flags(bias, relu):
+    return (B.EPI_BIAS if bias is not None else 0) | (B.EPI_RELU if relu else 0)
+
+
+def gpu_fc_forward(w, x, bias=None, relu=False):
+    p, q, k = w.shape
+    wh = B.circ_precompute_spectra(dev(w))
+    y = B.circ_fc_forward(wh, dev(x), dev(bias), None, p, q, k, epi_flags(bias, relu))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def gpu_fc_backward(w, x, dy, need_dx=True, need_dw=True):
+    p, q, k = w.shape
+    wh = B.circ_precompute_spectra(dev(w))
+    dx, dw = B.circ_fc_backward(wh, dev(x), dev(dy), p, q, k, need_dx, need_dw)
+    torch.cuda.synchronize()
+    return (None if dx is None else dx.cpu().numpy()), (None if dw is None else dw.cpu().numpy())
+
+
+def gpu_conv_forward(w, x, bias=None, relu=False, pad=0):
+    r, _, p, q, k = w.shape
+    wh = B.circ_precompute_spectra(dev(w))
+    y = B.circ_conv_forward(wh, dev(x), dev(bias), None, p * k, r, 1, pad, k, epi_flags(bias, relu))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()

@@ -1,0 +1,122 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, sizes are as documented, and argument errors come back as status codes
+before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1708_08917_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "circ.h")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="libcirc.so not built (run __graft_entry__.build())")
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(circ_[a-z_]+)\s*\(", src)))
+
+
+def test_exports_every_declared_symbol():
+    L = ctypes.CDLL(B.LIB_PATH)
+    names = declared_functions()
+    assert {"circ_precompute_spectra", "circ_fc_forward", "circ_conv_forward", "circ_fc_backward"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(B.SIGNATURES), "binding and header list different entry points"
+
+
+def test_status_strings():
+    for s in (0, -1, -2, -3, -4):
+        assert B.status_string(s).startswith("CIRC_")
+    assert "unknown" in B.status_string(-99)
+
+
+def test_spectra_bytes():
+    # forward-operand and backward-operand sections, each (k/2+1) complex bins per block, 256 B aligned
+    assert B.circ_spectra_bytes(1, 64, 64, 64) == 2 * 64 * 64 * 33 * 8
+    assert B.circ_spectra_bytes(9, 4, 4, 64) == 2 * ((9 * 16 * 33 * 8 + 255) // 256 * 256)
+    for bad in [(0, 1, 1, 8), (1, 0, 1, 8), (1, 1, 0, 8), (1, 1, 1, 3), (1, 1, 1, 1), (1, 1, 1, 1024), (1, 1, 1, 0)]:
+        assert B.circ_spectra_bytes(*bad) == 0
+
+
+def test_workspace_bytes():
+    F = 33
+    assert B.circ_fc_workspace_bytes(64, 64, 64, 64) == 2 * F * 64 * 64 * 8
+    assert B.circ_fc_workspace_bytes(64, 64, 64, 64, True) == 3 * F * 64 * 64 * 8
+    assert B.circ_fc_workspace_bytes(64, 64, 48, 64) == 0
+    assert B.circ_conv_workspace_bytes(32, 256, 256, 28, 28, 3, 1, 1, 64) == 2 * F * 4 * 32 * 784 * 8
+    assert B.circ_conv_workspace_bytes(32, 256, 256, 28, 28, 3, 2, 1, 64) == 0
+    assert B.circ_conv_workspace_bytes(32, 250, 256, 28, 28, 3, 1, 1, 64) == 0
+
+
+A = 0x1000  # fake, aligned, never dereferenced: the calls below must fail before any launch
+
+
+def test_fc_forward_argument_errors():
+    f = B.lib().circ_fc_forward
+    ws = 1 << 30
+    ok_args = dict(w_hat=A, x=A, bias=None, y=A + (1 << 28), p=2, q=2, k=8, batch=2, epi=0, wsp=A + (2 << 28), wsb=ws)
+
+    def call(**kw):
+        a = dict(ok_args); a.update(kw)
+        return f(a["w_hat"], a["x"], a["bias"], a["y"], a["p"], a["q"], a["k"], a["batch"], a["epi"], a["wsp"], a["wsb"], None)
+
+    assert call(k=3) == B.CIRC_EINVAL
+    assert call(k=1024) == B.CIRC_EINVAL
+    assert call(p=0) == B.CIRC_EINVAL
+    assert call(batch=-1) == B.CIRC_EINVAL
+    assert call(x=None) == B.CIRC_EINVAL
+    assert call(y=None) == B.CIRC_EINVAL
+    assert call(w_hat=None) == B.CIRC_EINVAL
+    assert call(x=A + 4) == B.CIRC_EINVAL                     # misaligned
+    assert call(epi=B.EPI_BIAS) == B.CIRC_EINVAL              # bias flag without bias pointer
+    assert call(epi=8) == B.CIRC_EINVAL
+    assert call(y=A) == B.CIRC_EINVAL                         # in place
+    assert call(wsb=16) == B.CIRC_EWORKSPACE
+    assert call(wsp=None) == B.CIRC_EWORKSPACE
+
+
+def test_fc_backward_argument_errors():
+    f = B.lib().circ_fc_backward
+    big = 1 << 28
+
+    def call(w_hat=A, x=A + big, dy=A + 2 * big, dx=A + 3 * big, dw=A + 4 * big, p=2, q=2, k=8, batch=2,
+             wsp=A + 5 * big, wsb=1 << 30):
+        return f(w_hat, x, dy, dx, dw, p, q, k, batch, wsp, wsb, None)
+
+    assert call(k=12) == B.CIRC_EINVAL
+    assert call(dy=None) == B.CIRC_EINVAL
+    assert call(dx=None, dw=None) == B.CIRC_EINVAL
+    assert call(x=None) == B.CIRC_EINVAL                      # dw needs x
+    assert call(dx=A + 2 * big) == B.CIRC_EINVAL              # dx aliases dy
+    assert call(wsb=0) == B.CIRC_EWORKSPACE
+
+
+def test_conv_argument_errors():
+    f = B.lib().circ_conv_forward
+    big = 1 << 28
+
+    def call(w_hat=A, x=A + big, bias=None, y=A + 2 * big, N=1, C_in=8, C_out=8, H=4, W=4, r=3, stride=1, pad=1, k=4,
+             epi=0, wsp=A + 3 * big, wsb=1 << 30):
+        return f(w_hat, x, bias, y, N, C_in, C_out, H, W, r, stride, pad, k, epi, wsp, wsb, None)
+
+    assert call(C_in=6) == B.CIRC_EINVAL                      # k does not divide C_in
+    assert call(k=3, C_in=6, C_out=6) == B.CIRC_EINVAL
+    assert call(stride=2) == B.CIRC_ENOTSUP
+    assert call(r=2) == B.CIRC_ENOTSUP
+    assert call(pad=3) == B.CIRC_EINVAL
+    assert call(x=None) == B.CIRC_EINVAL
+    assert call(wsb=8) == B.CIRC_EWORKSPACE
+
+
+def test_precompute_argument_errors():
+    f = B.lib().circ_precompute_spectra
+    assert f(None, 1, 2, 2, 8, A, None) == B.CIRC_EINVAL
+    assert f(A, 1, 2, 2, 6, A + (1 << 20), None) == B.CIRC_EINVAL
+    assert f(A, 0, 2, 2, 8, A + (1 << 20), None) == B.CIRC_EINVAL
+    assert f(A, 1, 2, 2, 8, A, None) == B.CIRC_EINVAL         # output aliases input
