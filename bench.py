@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-circulant FC hot path on one MI355X.
+
+Workload (`config.workload`): the 4096x4096 block-circulant FC layer with block size 64
+(p = q = 64), batch 64, fp32, bias + ReLU epilogue.  A "step" is one call of
+circ_fc_forward (FFT of the activations, per-frequency contraction with the cached weight
+spectra, inverse FFT with the epilogue) over one batch of 64 synthetic input vectors.  The
+weight spectra are computed once before the timed region, as the method caches FFT(w_ij).
+
+Timed region: K steps recorded into one HIP graph and replayed once, bracketed by events on
+the launch stream and by torch.cuda.synchronize().  Each step reads a different activation
+buffer and writes a different output buffer out of a pool larger than twice the 256 MB
+Infinity Cache, so activations really come from HBM while the 1 MB of weight spectra
+legitimately stays cached.  Extra fields report the same loop with eager launches and with
+one warm buffer pair.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
+
+# HBM bytes per step measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
+# None until measured for the current kernels.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def algorithmic_work(p, q, k, B, bias):
+    F = k // 2 + 1
+    byts = 8 * p * q * F + 4 * B * q * k + 4 * B * p * k + (4 * p * k if bias else 0)
+    lg = k.bit_length() - 1
+    flops = 8 * p * q * (k // 2) * B + (p + q) * B * (5 * k * lg) // 2
+    return byts, flops
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pool-mb", type=int, default=640, help="size of the rotating activation/output pool")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
+              "(the multi-GPU sharding is described in DESIGN.md, not built)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1708_08917_amd import binding as B
+    from paper_1708_08917_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = synth.CFG2
+    p, q, k, batch = cfg.p, cfg.q, cfg.k, cfg.batch
+    K, Wm = args.steps, args.warmup
+
+    w, x0, bias = synth.fc_inputs(cfg)
+    w_d, bias_d = torch.from_numpy(w).to(dev), torch.from_numpy(bias).to(dev)
+    w_hat = B.circ_precompute_spectra(w_d)
+    ws = torch.empty(B.circ_fc_workspace_bytes(p, q, k, batch), dtype=torch.uint8, device=dev)
+    epi = B.EPI_BIAS | B.EPI_RELU
+
+    # rotating pool of (x, y) pairs: pair 0 is the seeded parity input, the rest are seeded
+    # Uniform[-1,1] draws made on the device
+    pair_bytes = 4 * batch * (cfg.n_in + cfg.n_out)
+    npairs = max(2, (args.pool_mb << 20) // pair_bytes)
+    gen = torch.Generator(device=dev); gen.manual_seed(synth.BASE_SEED)
+    xs = torch.empty(npairs, batch, cfg.n_in, dtype=torch.float32, device=dev)
+    xs.uniform_(-1.0, 1.0, generator=gen)
+    xs[0].copy_(torch.from_numpy(x0))
+    ys = torch.zeros(npairs, batch, cfg.n_out, dtype=torch.float32, device=dev)
+
+    import ctypes
+    fn = B.lib().circ_fc_forward
+    stream = torch.cuda.Stream(device=dev)      # default priority
+    sptr = ctypes.c_void_p(stream.cuda_stream)
+    wsp, wsn = ctypes.c_void_p(ws.data_ptr()), ws.numel()
+    whp, bp = ctypes.c_void_p(w_hat.data_ptr()), ctypes.c_void_p(bias_d.data_ptr())
+    xp = [ctypes.c_void_p(xs[i].data_ptr()) for i in range(npairs)]
+    yp = [ctypes.c_void_p(ys[i].data_ptr()) for i in range(npairs)]
+
+    def step(i):
+        st = fn(whp, xp[i], bp, yp[i], p, q, k, batch, epi, wsp, wsn, sptr)
+        if st != 0:
+            raise RuntimeError(B.status_string(st))
+
+    def timed(run):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(stream):
+            e0.record(stream)
+            run()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return e0.elapsed_time(e1) * 1e-3, wall      # seconds by events, by host clock
+
+    with torch.cuda.stream(stream):
+        for i in range(Wm):
+            step(i % npairs)
+    torch.cuda.synchronize()
+
+    # --- eager launches, rotating buffers
+    ev_eager, wall_eager = timed(lambda: [step(i % npairs) for i in range(K)])
+    # --- eager launches, one warm pair
+    ev_warm, _ = timed(lambda: [step(0) for _ in range(K)])
+
+    # --- K steps in one HIP graph (rotating buffers), replayed: the figure reported
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        for i in range(K):
+            step((Wm + i) % npairs)
+    graph.replay()                                   # untimed: uploads the executable graph
+    torch.cuda.synchronize()
+    ev_graph, wall_graph = timed(graph.replay)
+
+    t_step = ev_graph / K
+    alg_bytes, alg_flops = algorithmic_work(p, q, k, batch, True)
+    out = {
+        "metric": "vectors/s for block-circulant FC (4096^2, k=64, B=64); % of HBM/MFMA roofline",
+        "value": batch * K / wall_graph,
+        "unit": "vectors/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": wall_graph / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "cfg2: block-circulant FC forward, n_in=n_out=4096, k=64 (p=q=64), batch 64, "
+                               "fp32, bias+ReLU; cached weight spectra; activations rotate through a "
+                               f"{npairs * pair_bytes >> 20} MB pool (HBM-resident, not cache-resident)",
+                   "p": p, "q": q, "k": k, "batch": batch, "launch": "hip graph of K steps"},
+        "dense_equivalent_gflops": 2.0 * cfg.n_in * cfg.n_out * batch / t_step * 1e-9,
+        "roofline": {
+            "bound": "mfma", "kernel": "circ_fc_forward step (all kernels of one step)",
+            "achieved": alg_flops / t_step * 1e-12, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": alg_flops / t_step * 1e-12 / MFMA_FP32_PEAK_TFLOPS,
+            "traffic": MEASURED_TRAFFIC_BYTES,
+            "algorithmic_flops_per_step": alg_flops, "algorithmic_bytes_per_step": alg_bytes,
+            "avg_step_us_by_events": t_step * 1e6,
+            "hbm_view": {"achieved": alg_bytes / t_step * 1e-9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": alg_bytes / t_step * 1e-9 / HBM_PEAK_GBS},
+        },
+        "timing_detail_us_per_step": {
+            "graph_events": ev_graph / K * 1e6, "graph_wall": wall_graph / K * 1e6,
+            "eager_rotating_events": ev_eager / K * 1e6, "eager_rotating_wall": wall_eager / K * 1e6,
+            "eager_warm_pair_events": ev_warm / K * 1e6,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import circ_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        ref = O.fc_forward(w, x0, bias, True)        # also the parity check of pair 0
+        with torch.cuda.stream(stream):
+            step(0)
+        torch.cuda.synchronize()
+        out["max_norm_rel_err_vs_oracle"] = O.max_norm_rel_err(ys[0].cpu().numpy(), ref)
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            O.fc_forward(w, x0, bias, True)
+            reps += 1
+            el = time.perf_counter() - t0
+            if el > 10.0 or reps >= 50:
+                break
+        out["cpu_baseline"] = {
+            "value": batch * reps / el, "unit": "vectors/s", "cores": cores, "kind": "oracle",
+            "sample": f"{reps} repetitions of the full cfg2 batch (64 vectors each, float64, dense expansion of "
+                      f"the blocks included), {el:.1f} s",
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

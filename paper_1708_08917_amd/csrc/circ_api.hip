@@ -6,6 +6,7 @@
 
 #include "../../include/circ.h"
 #include "circ_kernels.h"
+#include "circ_fused.h"
 
 namespace {
 
@@ -25,6 +26,12 @@ inline size_t spectrum_elems(int k, long long rows) { return size_t(k / 2 + 1) *
 // backward operand [g][f][i][j] (j fastest, conjugated).  Both carry the 1/k of the IFFT.
 inline size_t spectra_section_elems(int n_grids, int p, int q, int k) {
   return size_t(n_grids) * spectrum_elems(k, (long long)p * q);
+}
+
+// Section 2 (FC only, k >= 32): the operand order of the fused forward kernel.
+inline size_t fused_section_elems(int n_grids, int p, int q, int k) {
+  if (n_grids != 1 || k < 32) return 0;
+  return size_t((p + 3) / 4) * q * (k / 32) * 64;
 }
 
 struct FftPlan { int P, NT; size_t lds; };
@@ -122,6 +129,39 @@ hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int NF, int
   return hipGetLastError();
 }
 
+template <int K, int IT, int NP>
+hipError_t launch_fused_t(const float2* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
+                          int relu, hipStream_t s) {
+  using Sh = FusedShape<K, IT, NP>;
+  const int n_it = (int)cdiv(p, IT), n_bt = (int)cdiv(batch, 2 * NP);
+  hipLaunchKernelGGL((fc_fused_kernel<K, IT, NP>), dim3((unsigned)n_it * n_bt), dim3(256), Sh::LDS_BYTES, s, wf, x, bias,
+                     y, p, q, batch, n_it, relu);
+  return hipGetLastError();
+}
+
+// Output block rows per workgroup of the fused kernel for block size k (0: not fused).
+inline int fused_it(int k) { return k < 32 ? 0 : (k == 32 ? 16 : 8); }
+
+// The fused kernel recomputes the FFT of x once per tile of output block rows; it is
+// chosen while that redundancy stays small.
+inline bool use_fused_forward(int p, int q, int k, int batch) {
+  (void)q; (void)batch;
+  const int it = fused_it(k);
+  return it > 0 && cdiv(p, it) <= 8;
+}
+
+hipError_t launch_fused(int k, const float2* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
+                        int relu, hipStream_t s) {
+  switch (k) {
+    case 32: return launch_fused_t<32, 16, 1>(wf, x, bias, y, p, q, batch, relu, s);
+    case 64: return launch_fused_t<64, 8, 1>(wf, x, bias, y, p, q, batch, relu, s);
+    case 128: return launch_fused_t<128, 8, 1>(wf, x, bias, y, p, q, batch, relu, s);
+    case 256: return launch_fused_t<256, 8, 1>(wf, x, bias, y, p, q, batch, relu, s);
+    case 512: return launch_fused_t<512, 8, 1>(wf, x, bias, y, p, q, batch, relu, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
   return x < y + nb && y < x + na;
@@ -155,7 +195,8 @@ const char* circ_status_string(circ_status s) {
 size_t circ_spectra_bytes(int n_grids, int p, int q, int k) {
   if (n_grids <= 0 || p <= 0 || q <= 0 || !valid_k(k)) return 0;
   if ((long long)p * q > (1ll << 31) - 1) return 0;
-  return 2 * align_up(spectra_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
+  return 2 * align_up(spectra_section_elems(n_grids, p, q, k) * sizeof(float2), 256) +
+         align_up(fused_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
 }
 
 circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, int k, void* w_hat, void* stream) {
@@ -177,6 +218,12 @@ circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, i
   // backward operand: row id = i*q + j, conjugated
   RowMap mb{q, p, (long long)k, (long long)q * k, 0, 1};
   if (launch_rfft(k, false, w, bwd, mb, rows, rows, n_grids, in_g, out_g, inv_k, 1, s) != hipSuccess) return CIRC_EHIP;
+  const size_t nfused = fused_section_elems(n_grids, p, q, k);
+  if (nfused) {
+    float2* wfu = reinterpret_cast<float2*>(static_cast<char*>(w_hat) + 2 * sec);
+    hipLaunchKernelGGL(pack_fused_kernel, dim3((unsigned)cdiv((long long)nfused, 256)), dim3(256), 0, s, fwd, wfu, p, q, k);
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  }
   return CIRC_OK;
 }
 
@@ -203,6 +250,15 @@ circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias
   if (!workspace || workspace_bytes < need) return CIRC_EWORKSPACE;
   if (!aligned16(workspace)) return CIRC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
+
+  if (use_fused_forward(p, q, k, batch)) {
+    const size_t sec = align_up(spectra_section_elems(1, p, q, k) * sizeof(float2), 256);
+    const float2* wfu = reinterpret_cast<const float2*>(static_cast<const char*>(w_hat) + 2 * sec);
+    if (launch_fused(k, wfu, x, use_bias ? bias : nullptr, y, p, q, batch, (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) !=
+        hipSuccess)
+      return CIRC_EHIP;
+    return CIRC_OK;
+  }
 
   const int NF = k / 2 + 1;
   float2* xh = static_cast<float2*>(workspace);

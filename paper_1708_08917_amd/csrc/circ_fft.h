@@ -9,8 +9,8 @@
 // sequence z = row_a + i*row_b; the half spectra of both rows are separated from
 // Z[f] and conj(Z[K-f]) when the tile is written out.
 //
-// LDS layout of a tile: two float planes (re, im), element (n, pair) at n*PP + pair,
-// with `pair` the fastest index so that lanes of a wave that work on the same n hit
+// LDS layout of a tile: complex (float2) values, element (n, column) at n*PP + column,
+// with the column the fastest index so that lanes of a wave that work on the same n hit
 // consecutive banks.
 #pragma once
 
@@ -88,16 +88,18 @@ __device__ __forceinline__ int fft_pos(int f) {
   return R2 * (f % R1) + f / R1;
 }
 
-// pair: column of this thread; t, TT: index and count of threads sharing a column.
+// z: tile of complex values, element (n, col) at z[n*PP + col].
+// col: column of this thread; t, TT: index and count of threads sharing a column.
 template <int K, bool INV>
-__device__ __forceinline__ void fft_lds_pass1(float* zre, float* zim, int PP, int pair, int t, int TT) {
+__device__ __forceinline__ void fft_lds_pass1(float2* z, int PP, int col, int t, int TT) {
   constexpr int R2 = radix2_of(K), R1 = radix1_of(K);
   for (int n2 = t; n2 < R2; n2 += TT) {
     float re[R1], im[R1];
 #pragma unroll
     for (int n1 = 0; n1 < R1; ++n1) {
-      re[n1] = zre[(R2 * n1 + n2) * PP + pair];
-      im[n1] = zim[(R2 * n1 + n2) * PP + pair];
+      float2 v = z[(R2 * n1 + n2) * PP + col];
+      re[n1] = v.x;
+      im[n1] = v.y;
     }
     FftReg<R1, INV>::run(re, im);
 #pragma unroll
@@ -111,31 +113,34 @@ __device__ __forceinline__ void fft_lds_pass1(float* zre, float* zim, int PP, in
         vi = c * vi + s * vr;
         vr = xr;
       }
-      zre[(R2 * f1 + n2) * PP + pair] = vr;
-      zim[(R2 * f1 + n2) * PP + pair] = vi;
+      z[(R2 * f1 + n2) * PP + col] = make_float2(vr, vi);
     }
   }
 }
 
-template <int K, bool INV>
-__device__ __forceinline__ void fft_lds_pass2(float* zre, float* zim, int PP, int pair, int t, int TT) {
+// Pass 2 hands every finished value to `sink(f, value)` with f = f1 + R1*f2 instead of
+// storing it, so that callers choose where spectra (or time samples) go.
+template <int K, bool INV, class Sink>
+__device__ __forceinline__ void fft_lds_pass2(const float2* z, int PP, int col, int t, int TT, Sink&& sink) {
   constexpr int R2 = radix2_of(K), R1 = radix1_of(K);
-  if constexpr (R2 > 1) {
-    for (int f1 = t; f1 < R1; f1 += TT) {
-      float re[R2], im[R2];
+  for (int f1 = t; f1 < R1; f1 += TT) {
+    float re[R2], im[R2];
 #pragma unroll
-      for (int n2 = 0; n2 < R2; ++n2) {
-        re[n2] = zre[(R2 * f1 + n2) * PP + pair];
-        im[n2] = zim[(R2 * f1 + n2) * PP + pair];
-      }
-      FftReg<R2, INV>::run(re, im);
-#pragma unroll
-      for (int f2 = 0; f2 < R2; ++f2) {
-        zre[(R2 * f1 + f2) * PP + pair] = re[f2];
-        zim[(R2 * f1 + f2) * PP + pair] = im[f2];
-      }
+    for (int n2 = 0; n2 < R2; ++n2) {
+      float2 v = z[(R2 * f1 + n2) * PP + col];
+      re[n2] = v.x;
+      im[n2] = v.y;
     }
+    FftReg<R2, INV>::run(re, im);
+#pragma unroll
+    for (int f2 = 0; f2 < R2; ++f2) sink(f1 + R1 * f2, make_float2(re[f2], im[f2]));
   }
+}
+
+// In-place variant: the value of index f is left at position fft_pos<K>(f).
+template <int K, bool INV>
+__device__ __forceinline__ void fft_lds_pass2_inplace(float2* z, int PP, int col, int t, int TT) {
+  fft_lds_pass2<K, INV>(z, PP, col, t, TT, [&](int f, float2 v) { z[fft_pos<K>(f) * PP + col] = v; });
 }
 
 // ---- addressing of "rows" (the length-K vectors that are transformed) ----------------

@@ -19,25 +19,29 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // LDS bytes of one FFT tile of P column pairs.
 inline size_t fft_tile_lds_bytes(int K, int P) {
-  return size_t(2 * K * (P + 1) + 16) * sizeof(float) + size_t(2 * P) * (sizeof(long long) + sizeof(int));
+  return size_t(K) * (P + 1) * sizeof(float2) + size_t(2 * P) * (sizeof(long long) + sizeof(int));
 }
 
 struct TileLds {
-  float* zre;
-  float* zim;
+  float2* z;
   long long* rbase;
   int* rblk;
 };
 
 template <int K>
 __device__ __forceinline__ TileLds carve_tile(float* smem, int P) {
-  const int PP = P + 1;
   TileLds t;
-  t.zre = smem;
-  t.zim = smem + K * PP + 16;   // +16 floats: the two planes start half a bank row apart
-  t.rbase = reinterpret_cast<long long*>(t.zim + K * PP);
+  t.z = reinterpret_cast<float2*>(smem);
+  t.rbase = reinterpret_cast<long long*>(t.z + K * (P + 1));
   t.rblk = reinterpret_cast<int*>(t.rbase + 2 * P);
   return t;
+}
+
+__device__ __forceinline__ void lds_put(float2* z, int idx, int half, float v) {
+  reinterpret_cast<float*>(z)[2 * idx + half] = v;
+}
+__device__ __forceinline__ float lds_get(const float2* z, int idx, int half) {
+  return reinterpret_cast<const float*>(z)[2 * idx + half];
 }
 
 // -------------------------------------------------------------------------------------
@@ -66,38 +70,53 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
   __syncthreads();
 
   // load: row 2u -> real part of column u, row 2u+1 -> imaginary part
-  if (ROWS_FAST) {
+  if constexpr (ROWS_FAST) {
+#pragma unroll 4
     for (int idx = tid; idx < 2 * P * K; idx += NT) {
       int row = idx & (2 * P - 1), n = idx >> (lgP + 1);
       long long b = L.rbase[row];
       float v = b >= 0 ? in[b + n * map.es] : 0.f;
-      ((row & 1) ? L.zim : L.zre)[n * PP + (row >> 1)] = v;
+      lds_put(L.z, n * PP + (row >> 1), row & 1, v);
+    }
+  } else if constexpr (K >= 4) {
+    // rows are contiguous (element stride 1) and 16-byte aligned: vector loads along the row
+#pragma unroll 4
+    for (int idx = tid; idx < 2 * P * (K / 4); idx += NT) {
+      int row = idx / (K / 4), n = 4 * (idx % (K / 4));
+      long long b = L.rbase[row];
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n);
+      int c = row >> 1, h = row & 1;
+      lds_put(L.z, (n + 0) * PP + c, h, v.x);
+      lds_put(L.z, (n + 1) * PP + c, h, v.y);
+      lds_put(L.z, (n + 2) * PP + c, h, v.z);
+      lds_put(L.z, (n + 3) * PP + c, h, v.w);
     }
   } else {
     for (int idx = tid; idx < 2 * P * K; idx += NT) {
       int row = idx / K, n = idx % K;
       long long b = L.rbase[row];
-      float v = b >= 0 ? in[b + n * map.es] : 0.f;
-      ((row & 1) ? L.zim : L.zre)[n * PP + (row >> 1)] = v;
+      float v = b >= 0 ? in[b + n] : 0.f;
+      lds_put(L.z, n * PP + (row >> 1), row & 1, v);
     }
   }
   __syncthreads();
 
-  const int pair = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
-  fft_lds_pass1<K, false>(L.zre, L.zim, PP, pair, t, TT);
+  const int col = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
+  fft_lds_pass1<K, false>(L.z, PP, col, t, TT);
   __syncthreads();
-  fft_lds_pass2<K, false>(L.zre, L.zim, PP, pair, t, TT);
+  fft_lds_pass2_inplace<K, false>(L.z, PP, col, t, TT);
   __syncthreads();
 
   // separate the two real rows of each column and store bins 0..K/2
   constexpr int NF = K / 2 + 1;
+  const float h = 0.5f * scale;
+#pragma unroll 2
   for (int idx = tid; idx < NF * P; idx += NT) {
     int pr = idx & (P - 1), f = idx >> lgP;
-    int p1 = fft_pos<K>(f) * PP + pr, p2 = fft_pos<K>((K - f) % K) * PP + pr;
-    float a = L.zre[p1], b = L.zim[p1], c = L.zre[p2], d = L.zim[p2];
-    float h = 0.5f * scale;
-    float2 xa = make_float2(h * (a + c), h * (b - d));
-    float2 xb = make_float2(h * (b + d), h * (c - a));
+    float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>((K - f) % K) * PP + pr];
+    float2 xa = make_float2(h * (u.x + w.x), h * (u.y - w.y));
+    float2 xb = make_float2(h * (u.y + w.y), h * (w.x - u.x));
     if (conj) { xa.y = -xa.y; xb.y = -xb.y; }
     long long rid = t0 + 2 * pr;
     float2* o = out + f * out_fstride + rid;
@@ -120,15 +139,9 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
   const long long t0 = (long long)blockIdx.x * 2 * P;
   const int tid = threadIdx.x, NT = blockDim.x;
 
-  for (int r = tid; r < 2 * P; r += NT) {
-    long long rid = t0 + r;
-    bool ok = rid < nrows;
-    L.rbase[r] = ok ? row_base(map, rid) : -1;
-    L.rblk[r] = ok ? int(rid / bias_div) : 0;
-  }
-
   // build Z = Ya + i*Yb on all K bins from the two half spectra (Hermitian symmetry)
   constexpr int NF = K / 2 + 1;
+#pragma unroll 4
   for (int idx = tid; idx < NF * P; idx += NT) {
     int pr = idx & (P - 1), f = idx >> lgP;
     long long rid = t0 + 2 * pr;
@@ -136,30 +149,34 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
     float2 ya = rid < nrows ? s[0] : make_float2(0.f, 0.f);
     float2 yb = rid + 1 < nrows ? s[1] : make_float2(0.f, 0.f);
     if (f == 0 || 2 * f == K) {            // DC and Nyquist bins of a real signal are real
-      L.zre[f * PP + pr] = ya.x;
-      L.zim[f * PP + pr] = yb.x;
+      L.z[f * PP + pr] = make_float2(ya.x, yb.x);
     } else {
-      L.zre[f * PP + pr] = ya.x - yb.y;
-      L.zim[f * PP + pr] = ya.y + yb.x;
-      L.zre[(K - f) * PP + pr] = ya.x + yb.y;
-      L.zim[(K - f) * PP + pr] = yb.x - ya.y;
+      L.z[f * PP + pr] = make_float2(ya.x - yb.y, ya.y + yb.x);
+      L.z[(K - f) * PP + pr] = make_float2(ya.x + yb.y, yb.x - ya.y);
     }
+  }
+  for (int r = tid; r < 2 * P; r += NT) {
+    long long rid = t0 + r;
+    bool ok = rid < nrows;
+    L.rbase[r] = ok ? row_base(map, rid) : -1;
+    L.rblk[r] = ok ? int(rid / bias_div) : 0;
   }
   __syncthreads();
 
-  const int pair = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
-  fft_lds_pass1<K, true>(L.zre, L.zim, PP, pair, t, TT);
+  const int col = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
+  fft_lds_pass1<K, true>(L.z, PP, col, t, TT);
   __syncthreads();
-  fft_lds_pass2<K, true>(L.zre, L.zim, PP, pair, t, TT);
+  fft_lds_pass2_inplace<K, true>(L.z, PP, col, t, TT);
   __syncthreads();
 
+#pragma unroll 4
   for (int idx = tid; idx < 2 * P * K; idx += NT) {
     int row, n;
     if (ROWS_FAST) { row = idx & (2 * P - 1); n = idx >> (lgP + 1); }
     else { row = idx / K; n = idx % K; }
     long long b = L.rbase[row];
     if (b < 0) continue;
-    float v = ((row & 1) ? L.zim : L.zre)[fft_pos<K>(n) * PP + (row >> 1)] * scale;
+    float v = lds_get(L.z, fft_pos<K>(n) * PP + (row >> 1), row & 1) * scale;
     if (bias) v += bias[(long long)L.rblk[row] * K + n];
     if (relu) v = fmaxf(v, 0.f);
     out[b + n * map.es] = v;
@@ -172,6 +189,7 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
 // A is stored with m fastest, B and C with n fastest, so every operand load is one
 // contiguous run per k.  A complex product is four real MFMA accumulations.
 // TILE = 32 uses v_mfma_f32_32x32x2_f32, TILE = 16 uses v_mfma_f32_16x16x4_f32.
+// Operand loads run one group of U k-steps ahead of the matrix instructions.
 template <int TILE, bool CONJ_B>
 __global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
                                                    const float2* __restrict__ B,
@@ -179,6 +197,7 @@ __global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
                                                    long long sA, long long sB, long long sC) {
   constexpr int KS = 64 / TILE;           // k values per MFMA: 2 or 4
   constexpr int NACC = TILE * TILE / 64;  // accumulator registers per lane: 16 or 4
+  constexpr int U = 8;                    // k-steps per group
   typedef float accv __attribute__((ext_vector_type(NACC)));
   const int lane = threadIdx.x;
   const int f = blockIdx.z, m0 = blockIdx.y * TILE, n0 = blockIdx.x * TILE;
@@ -192,27 +211,41 @@ __global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
 #pragma unroll
   for (int r = 0; r < NACC; ++r) { accR[r] = 0.f; accI[r] = 0.f; }
 
-#pragma unroll 4
-  for (int k0 = 0; k0 < Kd; k0 += KS) {
-    int kidx = k0 + kk;
-    int kc = min(kidx, Kd - 1);
-    float2 a = A[(long long)kc * M + am];
-    float2 b = B[(long long)kc * N + bn];
-    if (kidx >= Kd) { a = make_float2(0.f, 0.f); b = make_float2(0.f, 0.f); }
-    // (ar + i ai)(br + i bi) = (ar br - ai bi) + i (ar bi + ai br); conj(b): bi -> -bi
-    float a_for_rr = a.x, a_for_ii = CONJ_B ? a.y : -a.y;
-    float a_for_ri = CONJ_B ? -a.x : a.x, a_for_ir = a.y;
-    if constexpr (TILE == 32) {
-      accR = __builtin_amdgcn_mfma_f32_32x32x2f32(a_for_rr, b.x, accR, 0, 0, 0);
-      accR = __builtin_amdgcn_mfma_f32_32x32x2f32(a_for_ii, b.y, accR, 0, 0, 0);
-      accI = __builtin_amdgcn_mfma_f32_32x32x2f32(a_for_ri, b.y, accI, 0, 0, 0);
-      accI = __builtin_amdgcn_mfma_f32_32x32x2f32(a_for_ir, b.x, accI, 0, 0, 0);
-    } else {
-      accR = __builtin_amdgcn_mfma_f32_16x16x4f32(a_for_rr, b.x, accR, 0, 0, 0);
-      accR = __builtin_amdgcn_mfma_f32_16x16x4f32(a_for_ii, b.y, accR, 0, 0, 0);
-      accI = __builtin_amdgcn_mfma_f32_16x16x4f32(a_for_ri, b.y, accI, 0, 0, 0);
-      accI = __builtin_amdgcn_mfma_f32_16x16x4f32(a_for_ir, b.x, accI, 0, 0, 0);
+  float2 a[U], b[U], an[U], bn2[U];
+  auto load_group = [&](int k0, float2 (&ga)[U], float2 (&gb)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int kidx = k0 + u * KS + kk;
+      int kc = min(kidx, Kd - 1);
+      float2 va = A[(long long)kc * M + am];
+      float2 vb = B[(long long)kc * N + bn];
+      if (kidx >= Kd) { va = make_float2(0.f, 0.f); vb = make_float2(0.f, 0.f); }
+      ga[u] = va;
+      gb[u] = vb;
     }
+  };
+  load_group(0, a, b);
+  for (int k0 = 0; k0 < Kd; k0 += U * KS) {
+    if (k0 + U * KS < Kd) load_group(k0 + U * KS, an, bn2);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      // (ar + i ai)(br + i bi) = (ar br - ai bi) + i (ar bi + ai br); conj(b): bi -> -bi
+      float a_rr = a[u].x, a_ii = CONJ_B ? a[u].y : -a[u].y;
+      float a_ri = CONJ_B ? -a[u].x : a[u].x, a_ir = a[u].y;
+      if constexpr (TILE == 32) {
+        accR = __builtin_amdgcn_mfma_f32_32x32x2f32(a_rr, b[u].x, accR, 0, 0, 0);
+        accI = __builtin_amdgcn_mfma_f32_32x32x2f32(a_ri, b[u].y, accI, 0, 0, 0);
+        accR = __builtin_amdgcn_mfma_f32_32x32x2f32(a_ii, b[u].y, accR, 0, 0, 0);
+        accI = __builtin_amdgcn_mfma_f32_32x32x2f32(a_ir, b[u].x, accI, 0, 0, 0);
+      } else {
+        accR = __builtin_amdgcn_mfma_f32_16x16x4f32(a_rr, b[u].x, accR, 0, 0, 0);
+        accI = __builtin_amdgcn_mfma_f32_16x16x4f32(a_ri, b[u].y, accI, 0, 0, 0);
+        accR = __builtin_amdgcn_mfma_f32_16x16x4f32(a_ii, b[u].y, accR, 0, 0, 0);
+        accI = __builtin_amdgcn_mfma_f32_16x16x4f32(a_ir, b[u].x, accI, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) { a[u] = an[u]; b[u] = bn2[u]; }
   }
 
   // accumulator layout: column = lane % TILE; rows in groups of 4

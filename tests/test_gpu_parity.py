@@ -48,6 +48,10 @@ def test_fc_forward_all_block_sizes(k):
 @pytest.mark.parametrize("p,q,k,batch", [
     (1, 1, 8, 1), (1, 1, 64, 1), (2, 1, 16, 2), (1, 3, 16, 33), (37, 41, 16, 35), (33, 2, 64, 70),
     (5, 67, 32, 3), (64, 64, 16, 1), (40, 24, 64, 100), (3, 3, 128, 129), (2, 2, 256, 65),
+    # more than 8 tiles of output block rows: the unfused FFT -> contraction -> IFFT route
+    (72, 3, 64, 5), (70, 2, 128, 34), (130, 2, 32, 3), (66, 1, 256, 2), (65, 1, 512, 3),
+    # fused route with ragged tiles: p not a multiple of 8, odd batch, q not a multiple of the chunk
+    (9, 33, 64, 3), (7, 17, 128, 5), (5, 9, 256, 1), (3, 5, 512, 2), (17, 65, 32, 1), (64, 64, 64, 2),
 ])
 def test_fc_forward_shapes(p, q, k, batch):
     w, x, b = rand_fc(p, q, k, batch)
