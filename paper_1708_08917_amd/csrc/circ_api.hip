@@ -28,10 +28,15 @@ inline size_t spectra_section_elems(int n_grids, int p, int q, int k) {
   return size_t(n_grids) * spectrum_elems(k, (long long)p * q);
 }
 
-// Section 2 (FC only, k >= 32): the operand order of the fused forward kernel.
-inline size_t fused_section_elems(int n_grids, int p, int q, int k) {
-  if (n_grids != 1 || k < 32) return 0;
-  return size_t((p + 3) / 4) * q * (k / 32) * 64;
+// Output block rows per workgroup of the fused kernel for block size k (0: not fused).
+inline int fused_it(int k) { return (k < 32 || k > 256) ? 0 : (k == 32 ? 16 : 8); }
+// Section 2 (FC only, 32 <= k <= 256): the operand order of the fused forward kernel,
+// zero-padded to whole tiles: igp groups of 4 block rows, q2p pairs of block columns.
+inline int fused_igp(int p, int k) { return int(cdiv(p, fused_it(k))) * fused_it(k) / 4; }
+inline int fused_q2p(int q, int k) { const int jc = 4096 / k; return int(cdiv(q, jc)) * (jc / 2); }
+inline size_t fused_section_elems(int n_grids, int p, int q, int k) {   // in float4 units
+  if (n_grids != 1 || fused_it(k) == 0) return 0;
+  return size_t(fused_igp(p, k)) * fused_q2p(q, k) * (k / 32) * 64;
 }
 
 struct FftPlan { int P, NT; size_t lds; };
@@ -129,18 +134,26 @@ hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int NF, int
   return hipGetLastError();
 }
 
-template <int K, int IT, int NP>
-hipError_t launch_fused_t(const float2* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
+template <int K, int IT, int NP, int NT>
+hipError_t launch_fused_t(const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
                           int relu, hipStream_t s) {
-  using Sh = FusedShape<K, IT, NP>;
+  using Sh = FusedShape<K, IT, NP, NT>;
+  static_assert((4096 / K) % Sh::JC == 0, "packed weights are padded to chunks of 4096/K input blocks");
+  if (Sh::LDS_BYTES > 64 * 1024) {   // more than the default limit: opt in (gfx950 has 160 KB per workgroup)
+    static bool opted_in = false;
+    if (!opted_in) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&fc_fused_kernel<K, IT, NP, NT>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)Sh::LDS_BYTES) != hipSuccess)
+        return hipErrorInvalidValue;
+      opted_in = true;
+    }
+  }
   const int n_it = (int)cdiv(p, IT), n_bt = (int)cdiv(batch, 2 * NP);
-  hipLaunchKernelGGL((fc_fused_kernel<K, IT, NP>), dim3((unsigned)n_it * n_bt), dim3(256), Sh::LDS_BYTES, s, wf, x, bias,
-                     y, p, q, batch, n_it, relu);
+  const long long grid = cdiv((long long)n_it * n_bt, 8) * 8;   // whole rounds over the 8 XCDs
+  hipLaunchKernelGGL((fc_fused_kernel<K, IT, NP, NT>), dim3((unsigned)grid), dim3(NT), Sh::LDS_BYTES, s, wf, x, bias,
+                     y, p, q, batch, n_it, fused_q2p(q, K), relu);
   return hipGetLastError();
 }
-
-// Output block rows per workgroup of the fused kernel for block size k (0: not fused).
-inline int fused_it(int k) { return k < 32 ? 0 : (k == 32 ? 16 : 8); }
 
 // The fused kernel recomputes the FFT of x once per tile of output block rows; it is
 // chosen while that redundancy stays small.
@@ -150,14 +163,13 @@ inline bool use_fused_forward(int p, int q, int k, int batch) {
   return it > 0 && cdiv(p, it) <= 8;
 }
 
-hipError_t launch_fused(int k, const float2* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
+hipError_t launch_fused(int k, const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
                         int relu, hipStream_t s) {
   switch (k) {
-    case 32: return launch_fused_t<32, 16, 1>(wf, x, bias, y, p, q, batch, relu, s);
-    case 64: return launch_fused_t<64, 8, 1>(wf, x, bias, y, p, q, batch, relu, s);
-    case 128: return launch_fused_t<128, 8, 1>(wf, x, bias, y, p, q, batch, relu, s);
-    case 256: return launch_fused_t<256, 8, 1>(wf, x, bias, y, p, q, batch, relu, s);
-    case 512: return launch_fused_t<512, 8, 1>(wf, x, bias, y, p, q, batch, relu, s);
+    case 32: return launch_fused_t<32, 16, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
+    case 64: return launch_fused_t<64, 8, 1, 512>(wf, x, bias, y, p, q, batch, relu, s);
+    case 128: return launch_fused_t<128, 8, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
+    case 256: return launch_fused_t<256, 8, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -196,7 +208,7 @@ size_t circ_spectra_bytes(int n_grids, int p, int q, int k) {
   if (n_grids <= 0 || p <= 0 || q <= 0 || !valid_k(k)) return 0;
   if ((long long)p * q > (1ll << 31) - 1) return 0;
   return 2 * align_up(spectra_section_elems(n_grids, p, q, k) * sizeof(float2), 256) +
-         align_up(fused_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
+         align_up(fused_section_elems(n_grids, p, q, k) * sizeof(float4), 256);
 }
 
 circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, int k, void* w_hat, void* stream) {
@@ -220,8 +232,9 @@ circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, i
   if (launch_rfft(k, false, w, bwd, mb, rows, rows, n_grids, in_g, out_g, inv_k, 1, s) != hipSuccess) return CIRC_EHIP;
   const size_t nfused = fused_section_elems(n_grids, p, q, k);
   if (nfused) {
-    float2* wfu = reinterpret_cast<float2*>(static_cast<char*>(w_hat) + 2 * sec);
-    hipLaunchKernelGGL(pack_fused_kernel, dim3((unsigned)cdiv((long long)nfused, 256)), dim3(256), 0, s, fwd, wfu, p, q, k);
+    float4* wfu = reinterpret_cast<float4*>(static_cast<char*>(w_hat) + 2 * sec);
+    hipLaunchKernelGGL(pack_fused_kernel, dim3((unsigned)cdiv((long long)nfused, 256)), dim3(256), 0, s, fwd, wfu, p, q, k,
+                       fused_igp(p, k), fused_q2p(q, k));
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
   }
   return CIRC_OK;
@@ -253,7 +266,7 @@ circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias
 
   if (use_fused_forward(p, q, k, batch)) {
     const size_t sec = align_up(spectra_section_elems(1, p, q, k) * sizeof(float2), 256);
-    const float2* wfu = reinterpret_cast<const float2*>(static_cast<const char*>(w_hat) + 2 * sec);
+    const float4* wfu = reinterpret_cast<const float4*>(static_cast<const char*>(w_hat) + 2 * sec);
     if (launch_fused(k, wfu, x, use_bias ? bias : nullptr, y, p, q, batch, (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) !=
         hipSuccess)
       return CIRC_EHIP;

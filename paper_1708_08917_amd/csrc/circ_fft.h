@@ -88,10 +88,18 @@ __device__ __forceinline__ int fft_pos(int f) {
   return R2 * (f % R1) + f / R1;
 }
 
+// Copy the K inter-pass twiddles (cos, sin)(2*pi*m/K), m < K, from the table in the code
+// object into LDS; call at kernel start so that the global latency overlaps the data loads.
+template <int K>
+__device__ __forceinline__ void stage_twiddles(float2* twl, int tid, int nthreads) {
+  for (int m = tid; m < K; m += nthreads) twl[m] = make_float2(kTw.c[m * (kTwN / K)], kTw.s[m * (kTwN / K)]);
+}
+
 // z: tile of complex values, element (n, col) at z[n*PP + col].
 // col: column of this thread; t, TT: index and count of threads sharing a column.
+// twl: LDS copy of the twiddles made by stage_twiddles<K>.
 template <int K, bool INV>
-__device__ __forceinline__ void fft_lds_pass1(float2* z, int PP, int col, int t, int TT) {
+__device__ __forceinline__ void fft_lds_pass1(float2* z, int PP, int col, int t, int TT, const float2* twl) {
   constexpr int R2 = radix2_of(K), R1 = radix1_of(K);
   for (int n2 = t; n2 < R2; n2 += TT) {
     float re[R1], im[R1];
@@ -106,9 +114,9 @@ __device__ __forceinline__ void fft_lds_pass1(float2* z, int PP, int col, int t,
     for (int f1 = 0; f1 < R1; ++f1) {
       float vr = re[f1], vi = im[f1];
       if (f1 > 0 && R2 > 1) {
-        int ti = f1 * n2 * (kTwN / K);
-        float c = kTw.c[ti];
-        float s = INV ? kTw.s[ti] : -kTw.s[ti];
+        float2 w = twl[f1 * n2];
+        float c = w.x;
+        float s = INV ? w.y : -w.y;
         float xr = c * vr - s * vi;
         vi = c * vi + s * vr;
         vr = xr;

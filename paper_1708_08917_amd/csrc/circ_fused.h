@@ -27,132 +27,213 @@
 #include "circ_fft.h"
 #include "circ_kernels.h"
 
+// Optional phase-timing hook for profiling builds; expands to nothing in the library.
+#ifndef CIRC_PROBE
+#define CIRC_PROBE(id)
+#endif
+
 namespace circ {
 
-template <int K, int IT, int NP>
+// K block size, IT output block rows per workgroup, NP packed batch pairs per workgroup,
+// NT threads per workgroup (256 or 512).
+template <int K, int IT, int NP, int NT>
 struct FusedShape {
-  static constexpr int NT = 256;
-  static constexpr int PT = 2048 / K;          // packed column pairs per chunk
+  static constexpr int NW = NT / 64;           // waves
+  static constexpr int PT = 8 * NT / K;        // packed column pairs (complex FFTs) per chunk
   static constexpr int JC = PT / NP;           // input blocks j per chunk
   static constexpr int S = K / 2;              // complex slots per block
   static constexpr int FG = S / 16;            // slot groups (16 slots = one MFMA)
   static constexpr int IG = IT / 4;            // groups of 4 output block rows
-  static constexpr int NCOMBO = FG * IG;
-  static constexpr int CPW = NCOMBO / 4;       // (slot group, i group) combos per wave
+  static constexpr int NCOMBO = FG * IG;       // (slot group, row group) pairs to accumulate
+  static constexpr int JS = NCOMBO >= NW ? 1 : NW / NCOMBO;   // waves sharing a combo split the j range
+  static constexpr int CPW = NCOMBO >= NW ? NCOMBO / NW : 1;  // combos per wave
+  static constexpr int JW = JC / JS;           // input blocks per wave and chunk
   static constexpr int PP = PT + 1;
   static constexpr int OPROW = 2 * K + 2;      // floats per operand row (4 per slot, +2 pad)
   static constexpr int PTI = IT * NP;          // columns of the inverse transform
   static constexpr int PPI = PTI + 1;
   static constexpr int TILE_ELEMS = K * (PP > PPI ? PP : PPI);
-  static constexpr size_t LDS_BYTES = size_t(TILE_ELEMS) * sizeof(float2) + size_t(PT) * OPROW * sizeof(float);
+  static constexpr int RED_FLOATS = (JS - 1) * NCOMBO * NP * 8 * 64;
+  static constexpr size_t LDS_BYTES = size_t(TILE_ELEMS) * sizeof(float2) + size_t(PT) * OPROW * sizeof(float) +
+                                      size_t(K) * sizeof(float2) + size_t(RED_FLOATS) * sizeof(float);
   static_assert(K >= 32 && PT >= 1 && JC >= 1 && JC * NP == PT, "bad chunk shape");
-  static_assert(IT % 4 == 0 && NCOMBO % 4 == 0 && CPW >= 1, "combos must split over 4 waves");
+  static_assert(IT % 4 == 0 && (NCOMBO % NW == 0 || NW % NCOMBO == 0), "combos must split over the waves");
+  static_assert(JW >= 2 && JW % 2 == 0 && JW * JS == JC, "each wave needs an even number of input blocks");
   static_assert((PTI & (PTI - 1)) == 0 && PTI <= NT, "inverse columns must be a power of two");
   static_assert(2 * PT * (K / 4) == 4 * NT, "x staging assumes 4 float4 per thread");
 };
 
-// Weight spectra in the operand order of the fused kernel:
-//   Wf[((ig*q + j)*FG + fg)*64 + 4*blk + m] = W^[i = 4*ig + m][j][slot = 16*fg + blk]
-// slot 0 = (W^[0].re, W^[K/2].re); rows i >= p are zero.  `spec` is the [f][j][i] section.
-__global__ void pack_fused_kernel(const float2* __restrict__ spec, float2* __restrict__ Wf, int p, int q, int K) {
+// Weight spectra in the operand order of the fused kernel, two input blocks per element:
+//   Wf[((ig*q2p + j2)*FG + fg)*64 + 4*blk + m] = (W^[i][2*j2][slot], W^[i][2*j2+1][slot]),
+//   i = 4*ig + m, slot = 16*fg + blk
+// slot 0 = (W^[0].re, W^[K/2].re).  The section is padded with zeros to whole tiles:
+// igp groups of 4 block rows (p rounded up to the kernel's IT), q2p pairs of block columns
+// (q rounded up to the kernel's chunk).  `spec` is the [f][j][i] section.
+__global__ void pack_fused_kernel(const float2* __restrict__ spec, float4* __restrict__ Wf, int p, int q, int K,
+                                  int igp, int q2p) {
   const int FG = K / 32;
-  const long long total = (long long)((p + 3) / 4) * q * FG * 64;
+  const long long total = (long long)igp * q2p * FG * 64;
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
   const int l = int(idx & 63);
   long long r = idx >> 6;
   const int fg = int(r % FG); r /= FG;
-  const int j = int(r % q);
-  const int ig = int(r / q);
+  const int j2 = int(r % q2p);
+  const int ig = int(r / q2p);
   const int i = 4 * ig + (l & 3), slot = 16 * fg + (l >> 2);
-  float2 v = make_float2(0.f, 0.f);
-  if (i < p) {
-    const long long fs = (long long)p * q;
-    if (slot == 0) v = make_float2(spec[(long long)j * p + i].x, spec[(K / 2) * fs + (long long)j * p + i].x);
-    else v = spec[slot * fs + (long long)j * p + i];
+  const long long fs = (long long)p * q;
+  float2 v[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int j = 2 * j2 + h;
+    v[h] = make_float2(0.f, 0.f);
+    if (i < p && j < q) {
+      if (slot == 0) v[h] = make_float2(spec[(long long)j * p + i].x, spec[(K / 2) * fs + (long long)j * p + i].x);
+      else v[h] = spec[slot * fs + (long long)j * p + i];
+    }
   }
-  Wf[idx] = v;
+  Wf[idx] = make_float4(v[0].x, v[0].y, v[1].x, v[1].y);
 }
 
-template <int K, int IT, int NP>
-__global__ __launch_bounds__(256) void fc_fused_kernel(const float2* __restrict__ Wf, const float* __restrict__ x,
-                                                       const float* __restrict__ bias, float* __restrict__ y,
-                                                       int p, int q, int B, int n_it, int relu) {
-  using Sh = FusedShape<K, IT, NP>;
-  constexpr int PT = Sh::PT, JC = Sh::JC, S = Sh::S, FG = Sh::FG, IG = Sh::IG, CPW = Sh::CPW;
+// Exchange each lane's value with its neighbour inside a quad: lanes (0,1) and (2,3) swap.
+__device__ __forceinline__ float quad_swap_pairs(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false));
+}
+
+template <int K, int IT, int NP, int NT>
+__global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
+                                                      const float* __restrict__ bias, float* __restrict__ y,
+                                                      int p, int q, int B, int n_it, int q2p, int relu) {
+  using Sh = FusedShape<K, IT, NP, NT>;
+  constexpr int PT = Sh::PT, JC = Sh::JC, S = Sh::S, FG = Sh::FG, IG = Sh::IG, CPW = Sh::CPW, JS = Sh::JS;
+  constexpr int JW = Sh::JW, NW = Sh::NW, NCOMBO = Sh::NCOMBO;
   constexpr int PP = Sh::PP, OPROW = Sh::OPROW, PTI = Sh::PTI, PPI = Sh::PPI;
+  constexpr int NFW = CPW > IG ? CPW / IG : 1;       // distinct slot groups per wave
+  constexpr int JB = JW < 8 ? JW : 8;                // operand rows fetched from LDS per batch
+  constexpr int NOUT4 = 2 * PTI * K / 4;             // float4 outputs of the tile
+  constexpr int NV = (NOUT4 + NT - 1) / NT;          // ... per thread
+  static_assert(JW % JB == 0, "batching of operand rows");
   extern __shared__ float smem[];
   float2* z = reinterpret_cast<float2*>(smem);
   float* op = smem + 2 * Sh::TILE_ELEMS;
+  float2* twl = reinterpret_cast<float2*>(op + PT * OPROW);
+  float* red = reinterpret_cast<float*>(twl + K);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int it = blockIdx.x % n_it, bt = blockIdx.x / n_it;
+  // Workgroups go round-robin to the 8 XCDs, each with its own L2.  Give every XCD a
+  // contiguous range of tiles in batch-major order: it then reads its own slice of x once
+  // from HBM, and the (small, reused) weight spectra stay resident in each L2.
+  const int n_bt = (B + 2 * NP - 1) / (2 * NP), total = n_it * n_bt;
+  const int tile = (blockIdx.x & 7) * ((total + 7) >> 3) + (blockIdx.x >> 3);
+  if (tile >= total) return;
+  const int it = tile % n_it, bt = tile / n_it;
   const int i0 = it * IT, b0 = bt * 2 * NP;
   const long long ldx = (long long)q * K, ldy = (long long)p * K;
   const int nchunks = (q + JC - 1) / JC;
-  const int ig_max = (p + 3) / 4 - 1;
+  // this wave's share of the contraction: CPW combos starting at combo0, input blocks
+  // [js*JW, (js+1)*JW) of every chunk
+  const int combo0 = (wave % (NW / JS)) * CPW, js = wave / (NW / JS);
 
-  floatx4 P[CPW][NP], Q[CPW][NP];
+  floatx4 P[2][CPW][NP], Q[2][CPW][NP];
 #pragma unroll
-  for (int cc = 0; cc < CPW; ++cc)
+  for (int h = 0; h < 2; ++h)
 #pragma unroll
-    for (int u = 0; u < NP; ++u) {
-      P[cc][u] = floatx4{0.f, 0.f, 0.f, 0.f};
-      Q[cc][u] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
+    for (int cc = 0; cc < CPW; ++cc)
+#pragma unroll
+      for (int u = 0; u < NP; ++u) {
+        P[h][cc][u] = floatx4{0.f, 0.f, 0.f, 0.f};
+        Q[h][cc][u] = floatx4{0.f, 0.f, 0.f, 0.f};
+      }
 
-  // --- global loads: 4 float4 of x per thread and JC weight operands per combo, per chunk
+  // --- global loads: 4 float4 of x per thread and JW/2 weight operands per combo, per chunk.
+  // Addresses are a wave-uniform base plus a 32-bit per-lane offset fixed for the whole
+  // kernel, so that issuing a load costs no vector arithmetic.
   float4 xr[4];
+  unsigned xoff[4];
+  bool xrow_ok[4];
+  int xjj[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int flat = e * NT + tid;
+    const int row = flat / (K / 4), n4 = flat % (K / 4);
+    const int cl = row >> 1, half = row & 1;
+    const int jj = cl / NP, brow = 2 * (cl % NP) + half;
+    xjj[e] = jj;
+    xrow_ok[e] = b0 + brow < B;
+    xoff[e] = unsigned(brow) * unsigned(ldx) + unsigned(jj * K + 4 * n4);
+  }
+  const float* xtile = x + (long long)b0 * ldx;
   auto load_x = [&](int c) {
+    const float* xc = xtile + (long long)c * JC * K;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int flat = e * 256 + tid;
-      const int row = flat / (K / 4), n4 = flat % (K / 4);
-      const int col = row >> 1, half = row & 1;
-      const int j = c * JC + col / NP, b = b0 + 2 * (col % NP) + half;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (j < q && b < B) v = *reinterpret_cast<const float4*>(x + (long long)b * ldx + (long long)j * K + 4 * n4);
+      if (xrow_ok[e] && c * JC + xjj[e] < q) v = *reinterpret_cast<const float4*>(xc + xoff[e]);
       xr[e] = v;
     }
   };
   auto store_x = [&]() {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int flat = e * 256 + tid;
+      const int flat = e * NT + tid;
       const int row = flat / (K / 4), n = 4 * (flat % (K / 4));
-      const int col = row >> 1, half = row & 1;
-      lds_put(z, (n + 0) * PP + col, half, xr[e].x);
-      lds_put(z, (n + 1) * PP + col, half, xr[e].y);
-      lds_put(z, (n + 2) * PP + col, half, xr[e].z);
-      lds_put(z, (n + 3) * PP + col, half, xr[e].w);
+      const int cl = row >> 1, half = row & 1;
+      lds_put(z, (n + 0) * PP + cl, half, xr[e].x);
+      lds_put(z, (n + 1) * PP + cl, half, xr[e].y);
+      lds_put(z, (n + 2) * PP + cl, half, xr[e].z);
+      lds_put(z, (n + 3) * PP + cl, half, xr[e].w);
     }
   };
-  float2 a_cur[CPW][JC], a_nxt[CPW][JC];
-  auto load_a = [&](int c, float2 (&a)[CPW][JC]) {
+  // weight operands: the packed section is zero-padded to whole tiles (q2p pairs of block
+  // columns per row group), so no clamping is needed
+  const float4* wtile = Wf + ((long long)it * IG * q2p + js * (JW / 2)) * FG * 64;
+  unsigned aoff[CPW];
 #pragma unroll
-    for (int cc = 0; cc < CPW; ++cc) {
-      const int combo = wave * CPW + cc;
-      const int fg = combo / IG, ig = min(it * IG + combo % IG, ig_max);
+  for (int cc = 0; cc < CPW; ++cc) {
+    const int combo = combo0 + cc;
+    aoff[cc] = unsigned(((combo % IG) * q2p) * FG + combo / IG) * 64u + unsigned(lane);
+  }
+  float4 a_even[CPW][JW / 2], a_odd[CPW][JW / 2];
+  auto load_a = [&](int c, float4 (&a)[CPW][JW / 2]) {
+    const float4* wc = wtile + (long long)c * (JC / 2) * FG * 64;
 #pragma unroll
-      for (int jj = 0; jj < JC; ++jj) {
-        const int j = min(c * JC + jj, q - 1);
-        a[cc][jj] = Wf[(((long long)ig * q + j) * FG + fg) * 64 + lane];
-      }
-    }
+    for (int jh = 0; jh < JW / 2; ++jh)
+#pragma unroll
+      for (int cc = 0; cc < CPW; ++cc) a[cc][jh] = wc[(long long)jh * FG * 64 + aoff[cc]];
   };
 
+  CIRC_PROBE(0);
   load_x(0);
-  load_a(0, a_cur);
+  load_a(0, a_even);
+  stage_twiddles<K>(twl, tid, NT);
+
+  // bias of the outputs this thread will store (fetched now, used at the very end)
+  float4 bv4[NV];
+#pragma unroll
+  for (int s = 0; s < NV; ++s) {
+    const int idx = s * NT + tid;
+    const int row = idx / (K / 4), n = 4 * (idx % (K / 4));
+    const int i = i0 + (row >> 1) / NP;
+    bv4[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (bias && idx < NOUT4 && i < p) bv4[s] = *reinterpret_cast<const float4*>(bias + (long long)i * K + n);
+  }
 
   const int col = tid % PT, t = tid / PT;
-  constexpr int TT = 256 / PT;
+  constexpr int TT = NT / PT;
 
-  for (int c = 0; c < nchunks; ++c) {
+  // one chunk of JC input blocks: FFT of its 2*PT rows, then the contraction with `a_use`;
+  // meanwhile the loads of the next chunk (x into xr, weights into `a_pref`) are in flight.
+  auto chunk = [&](int c, float4 (&a_use)[CPW][JW / 2], float4 (&a_pref)[CPW][JW / 2]) {
     store_x();
     __syncthreads();
-    if (c + 1 < nchunks) load_x(c + 1);
-    fft_lds_pass1<K, false>(z, PP, col, t, TT);
+    CIRC_PROBE(1 + 4 * c);
+    if (c + 1 < nchunks) {
+      load_x(c + 1);
+      load_a(c + 1, a_pref);
+    }
+    fft_lds_pass1<K, false>(z, PP, col, t, TT, twl);
     __syncthreads();
+    CIRC_PROBE(2 + 4 * c);
     // pass 2 writes the spectrum of column `col` straight into MFMA operand order
     fft_lds_pass2<K, false>(z, PP, col, t, TT, [&](int f, float2 v) {
       int slot, h;
@@ -163,34 +244,93 @@ __global__ __launch_bounds__(256) void fc_fused_kernel(const float2* __restrict_
       *reinterpret_cast<float2*>(op + col * OPROW + 4 * slot + 2 * h) = v;
     });
     __syncthreads();
-    if (c + 1 < nchunks) load_a(c + 1, a_nxt);
+    CIRC_PROBE(3 + 4 * c);
+    // operand rows come from LDS one batch ahead of the matrix instructions that use them
+    const float* opw = op + (js * JW * NP) * OPROW + lane;
+    float bvv[2][JB][NP][NFW];
+    auto fetch_b = [&](int jb, float (&dst)[JB][NP][NFW]) {
 #pragma unroll
-    for (int jj = 0; jj < JC; ++jj) {
+      for (int jj = 0; jj < JB; ++jj)
 #pragma unroll
-      for (int u = 0; u < NP; ++u) {
+        for (int u = 0; u < NP; ++u)
 #pragma unroll
-        for (int cc = 0; cc < CPW; ++cc) {
-          const int fg = (wave * CPW + cc) / IG;
-          const float bv = op[(jj * NP + u) * OPROW + fg * 64 + lane];
-          P[cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(a_cur[cc][jj].x, bv, P[cc][u], 0, 0, 0);
-          Q[cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(a_cur[cc][jj].y, bv, Q[cc][u], 0, 0, 0);
-        }
-      }
+          for (int fw = 0; fw < NFW; ++fw) {
+            const int fg = (combo0 + fw * IG) / IG;
+            dst[jj][u][fw] = opw[((jb + jj) * NP + u) * OPROW + fg * 64];
+          }
+    };
+    fetch_b(0, bvv[0]);
+#pragma unroll
+    for (int jb = 0; jb < JW; jb += JB) {
+      const int cur = (jb / JB) & 1;
+      if (jb + JB < JW) fetch_b(jb + JB, bvv[cur ^ 1]);
+#pragma unroll
+      for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+        for (int u = 0; u < NP; ++u)
+#pragma unroll
+          for (int cc = 0; cc < CPW; ++cc) {
+            const float bval = bvv[cur][jj][u][NFW > 1 ? cc / IG : 0];
+            const float4 av = a_use[cc][(jb + jj) / 2];
+            const float ar = ((jb + jj) & 1) ? av.z : av.x, ai = ((jb + jj) & 1) ? av.w : av.y;
+            P[jj & 1][cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(ar, bval, P[jj & 1][cc][u], 0, 0, 0);
+            Q[jj & 1][cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(ai, bval, Q[jj & 1][cc][u], 0, 0, 0);
+          }
     }
-    if (c + 1 < nchunks) {
+    CIRC_PROBE(4 + 4 * c);
+  };
+  for (int c = 0; c < nchunks; c += 2) {
+    chunk(c, a_even, a_odd);
+    if (c + 1 < nchunks) chunk(c + 1, a_odd, a_even);
+  }
+
+  // --- sum the partial accumulators; waves that split the j range meet in LDS, and the
+  // additions happen in a fixed order, so the result is deterministic
+#pragma unroll
+  for (int cc = 0; cc < CPW; ++cc)
+#pragma unroll
+    for (int u = 0; u < NP; ++u) {
+      P[0][cc][u] += P[1][cc][u];
+      Q[0][cc][u] += Q[1][cc][u];
+    }
+  if constexpr (JS > 1) {
+    if (js > 0) {
 #pragma unroll
       for (int cc = 0; cc < CPW; ++cc)
 #pragma unroll
-        for (int jj = 0; jj < JC; ++jj) a_cur[cc][jj] = a_nxt[cc][jj];
+        for (int u = 0; u < NP; ++u) {
+          float* r = red + ((((js - 1) * NCOMBO + combo0 + cc) * NP + u) * 8) * 64 + lane;
+#pragma unroll
+          for (int m = 0; m < 4; ++m) {
+            r[m * 64] = P[0][cc][u][m];
+            r[(4 + m) * 64] = Q[0][cc][u][m];
+          }
+        }
+    }
+    __syncthreads();
+    if (js == 0) {
+#pragma unroll
+      for (int s2 = 1; s2 < JS; ++s2)
+#pragma unroll
+        for (int cc = 0; cc < CPW; ++cc)
+#pragma unroll
+          for (int u = 0; u < NP; ++u) {
+            const float* r = red + ((((s2 - 1) * NCOMBO + combo0 + cc) * NP + u) * 8) * 64 + lane;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+              P[0][cc][u][m] += r[m * 64];
+              Q[0][cc][u][m] += r[(4 + m) * 64];
+            }
+          }
     }
   }
 
   // --- assemble Zy of every (output block row, batch pair) into the inverse tile
-  {
+  if (js == 0) {
     const int n = lane & 3, blk = lane >> 2;
 #pragma unroll
     for (int cc = 0; cc < CPW; ++cc) {
-      const int combo = wave * CPW + cc;
+      const int combo = combo0 + cc;
       const int fg = combo / IG, ig = combo % IG;
       const int slot = 16 * fg + blk;
       const int fidx = (n < 2) ? slot : (slot == 0 ? S : K - slot);
@@ -198,8 +338,8 @@ __global__ __launch_bounds__(256) void fc_fused_kernel(const float2* __restrict_
       for (int u = 0; u < NP; ++u) {
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
-          const float pv = P[cc][u][m], qv = Q[cc][u][m];
-          const float qs = __shfl_xor(qv, 1, 64);
+          const float pv = P[0][cc][u][m], qv = Q[0][cc][u][m];
+          const float qs = quad_swap_pairs(qv);
           float val;
           if (slot == 0) val = (n < 2) ? pv : qv;
           else val = (n == 0 || n == 3) ? pv - qs : pv + qs;
@@ -209,26 +349,33 @@ __global__ __launch_bounds__(256) void fc_fused_kernel(const float2* __restrict_
     }
   }
   __syncthreads();
+  CIRC_PROBE(12);
   {
     const int coli = tid % PTI, ti = tid / PTI;
-    constexpr int TTI = 256 / PTI;
-    fft_lds_pass1<K, true>(z, PPI, coli, ti, TTI);
+    constexpr int TTI = NT / PTI;
+    fft_lds_pass1<K, true>(z, PPI, coli, ti, TTI, twl);
     __syncthreads();
     fft_lds_pass2_inplace<K, true>(z, PPI, coli, ti, TTI);
     __syncthreads();
   }
-#pragma unroll 4
-  for (int idx = tid; idx < 2 * PTI * K; idx += 256) {
-    const int row = idx / K, n = idx % K;
+  CIRC_PROBE(13);
+#pragma unroll
+  for (int s = 0; s < NV; ++s) {
+    const int idx = s * NT + tid;
+    const int row = idx / (K / 4), n = 4 * (idx % (K / 4));
     const int coli = row >> 1, half = row & 1;
     const int i = i0 + coli / NP, b = b0 + 2 * (coli % NP) + half;
-    if (i < p && b < B) {
-      float v = lds_get(z, fft_pos<K>(n) * PPI + coli, half);
-      if (bias) v += bias[(long long)i * K + n];
-      if (relu) v = fmaxf(v, 0.f);
-      y[(long long)b * ldy + (long long)i * K + n] = v;
+    if (idx < NOUT4 && i < p && b < B) {
+      float4 v;
+      v.x = lds_get(z, fft_pos<K>(n + 0) * PPI + coli, half) + bv4[s].x;
+      v.y = lds_get(z, fft_pos<K>(n + 1) * PPI + coli, half) + bv4[s].y;
+      v.z = lds_get(z, fft_pos<K>(n + 2) * PPI + coli, half) + bv4[s].z;
+      v.w = lds_get(z, fft_pos<K>(n + 3) * PPI + coli, half) + bv4[s].w;
+      if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+      *reinterpret_cast<float4*>(y + (long long)b * ldy + (long long)i * K + n) = v;
     }
   }
+  CIRC_PROBE(14);
 }
 
 }  // namespace circ

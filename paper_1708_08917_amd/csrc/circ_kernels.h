@@ -19,11 +19,13 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // LDS bytes of one FFT tile of P column pairs.
 inline size_t fft_tile_lds_bytes(int K, int P) {
-  return size_t(K) * (P + 1) * sizeof(float2) + size_t(2 * P) * (sizeof(long long) + sizeof(int));
+  return size_t(K) * (P + 1) * sizeof(float2) + size_t(K) * sizeof(float2) +
+         size_t(2 * P) * (sizeof(long long) + sizeof(int));
 }
 
 struct TileLds {
   float2* z;
+  float2* tw;
   long long* rbase;
   int* rblk;
 };
@@ -32,7 +34,8 @@ template <int K>
 __device__ __forceinline__ TileLds carve_tile(float* smem, int P) {
   TileLds t;
   t.z = reinterpret_cast<float2*>(smem);
-  t.rbase = reinterpret_cast<long long*>(t.z + K * (P + 1));
+  t.tw = t.z + K * (P + 1);
+  t.rbase = reinterpret_cast<long long*>(t.tw + K);
   t.rblk = reinterpret_cast<int*>(t.rbase + 2 * P);
   return t;
 }
@@ -63,6 +66,7 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
   const long long t0 = (long long)blockIdx.x * 2 * P;
   const int tid = threadIdx.x, NT = blockDim.x;
 
+  stage_twiddles<K>(L.tw, tid, NT);
   for (int r = tid; r < 2 * P; r += NT) {
     long long rid = t0 + r;
     L.rbase[r] = rid < nrows ? row_base(map, rid) : -1;
@@ -103,7 +107,7 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
   __syncthreads();
 
   const int col = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
-  fft_lds_pass1<K, false>(L.z, PP, col, t, TT);
+  fft_lds_pass1<K, false>(L.z, PP, col, t, TT, L.tw);
   __syncthreads();
   fft_lds_pass2_inplace<K, false>(L.z, PP, col, t, TT);
   __syncthreads();
@@ -139,6 +143,7 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
   const long long t0 = (long long)blockIdx.x * 2 * P;
   const int tid = threadIdx.x, NT = blockDim.x;
 
+  stage_twiddles<K>(L.tw, tid, NT);
   // build Z = Ya + i*Yb on all K bins from the two half spectra (Hermitian symmetry)
   constexpr int NF = K / 2 + 1;
 #pragma unroll 4
@@ -164,7 +169,7 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
   __syncthreads();
 
   const int col = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
-  fft_lds_pass1<K, true>(L.z, PP, col, t, TT);
+  fft_lds_pass1<K, true>(L.z, PP, col, t, TT, L.tw);
   __syncthreads();
   fft_lds_pass2_inplace<K, true>(L.z, PP, col, t, TT);
   __syncthreads();
