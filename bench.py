@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pool-mb", type=int, default=640, help="size of the rotating activation/output pool")
+    ap.add_argument("--pmc", action="store_true",
+                    help="counter-collection mode for rocprofv3 --pmc: eager launches only (no graph), plus "
+                         "8 plain device copies of 256 MiB as the known-size reference for FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
@@ -115,6 +118,18 @@ def main():
         for i in range(Wm):
             step(i % npairs)
     torch.cuda.synchronize()
+
+    if args.pmc:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            dst.copy_(src)
+        with torch.cuda.stream(stream):
+            for i in range(K):
+                step((Wm + i) % npairs)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_mode": True, "steps": K, "warmup": Wm, "copy_bytes": 256 << 20, "copies": 8}))
+        return
 
     # --- eager launches, rotating buffers
     ev_eager, wall_eager = timed(lambda: [step(i % npairs) for i in range(K)])

@@ -149,9 +149,18 @@ hipError_t launch_fused_t(const float4* wf, const float* x, const float* bias, f
     }
   }
   const int n_it = (int)cdiv(p, IT), n_bt = (int)cdiv(batch, 2 * NP);
-  const long long grid = cdiv((long long)n_it * n_bt, 8) * 8;   // whole rounds over the 8 XCDs
+  // Split the tile grid over the 8 XCDs as xa x (8/xa) rectangles; pick the split that
+  // minimises the bytes every XCD pulls into its own L2 (weight tiles + x rows).
+  int xa = 1;
+  double best = 1e300;
+  for (int cand = 1; cand <= 8; cand *= 2) {
+    const double wbytes = double(cdiv(n_it, cand)) * IT * q * K * 4.0;
+    const double xbytes = double(cdiv(n_bt, 8 / cand)) * 2 * NP * q * K * 4.0;
+    if (wbytes + xbytes < best) { best = wbytes + xbytes; xa = cand; }
+  }
+  const long long grid = 8 * cdiv(n_it, xa) * cdiv(n_bt, 8 / xa);
   hipLaunchKernelGGL((fc_fused_kernel<K, IT, NP, NT>), dim3((unsigned)grid), dim3(NT), Sh::LDS_BYTES, s, wf, x, bias,
-                     y, p, q, batch, n_it, fused_q2p(q, K), relu);
+                     y, p, q, batch, n_it, fused_q2p(q, K), xa, relu);
   return hipGetLastError();
 }
 

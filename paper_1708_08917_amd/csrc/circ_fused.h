@@ -103,7 +103,7 @@ __device__ __forceinline__ float quad_swap_pairs(float v) {
 template <int K, int IT, int NP, int NT>
 __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
                                                       const float* __restrict__ bias, float* __restrict__ y,
-                                                      int p, int q, int B, int n_it, int q2p, int relu) {
+                                                      int p, int q, int B, int n_it, int q2p, int xa, int relu) {
   using Sh = FusedShape<K, IT, NP, NT>;
   constexpr int PT = Sh::PT, JC = Sh::JC, S = Sh::S, FG = Sh::FG, IG = Sh::IG, CPW = Sh::CPW, JS = Sh::JS;
   constexpr int JW = Sh::JW, NW = Sh::NW, NCOMBO = Sh::NCOMBO;
@@ -120,13 +120,14 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
   float* red = reinterpret_cast<float*>(twl + K);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // Workgroups go round-robin to the 8 XCDs, each with its own L2.  Give every XCD a
-  // contiguous range of tiles in batch-major order: it then reads its own slice of x once
-  // from HBM, and the (small, reused) weight spectra stay resident in each L2.
-  const int n_bt = (B + 2 * NP - 1) / (2 * NP), total = n_it * n_bt;
-  const int tile = (blockIdx.x & 7) * ((total + 7) >> 3) + (blockIdx.x >> 3);
-  if (tile >= total) return;
-  const int it = tile % n_it, bt = tile / n_it;
+  // Workgroups go round-robin to the 8 XCDs, each with its own L2 (not kept across
+  // launches).  The tile grid (n_it x n_bt) is cut into xa x (8/xa) rectangles, one per XCD,
+  // so that the weight tiles and x rows an XCD has to pull into its L2 are as few as possible.
+  const int n_bt = (B + 2 * NP - 1) / (2 * NP);
+  const int xb = 8 / xa, xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int ni = (n_it + xa - 1) / xa, nb = (n_bt + xb - 1) / xb;
+  const int it = (xcd % xa) * ni + local % ni, bt = (xcd / xa) * nb + local / ni;
+  if (local >= ni * nb || it >= n_it || bt >= n_bt) return;
   const int i0 = it * IT, b0 = bt * 2 * NP;
   const long long ldx = (long long)q * K, ldy = (long long)p * K;
   const int nchunks = (q + JC - 1) / JC;
@@ -203,9 +204,19 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
   };
 
   CIRC_PROBE(0);
+  // memory returns loads in issue order: the twiddles go first because they are needed first,
+  // so that waiting for them does not also wait for the weight operands
+  float2 tw_stage[(K + NT - 1) / NT];
+#pragma unroll
+  for (int s = 0; s < (K + NT - 1) / NT; ++s) {
+    const int m = min(s * NT + tid, K - 1);
+    tw_stage[s] = make_float2(kTw.c[m * (kTwN / K)], kTw.s[m * (kTwN / K)]);
+  }
   load_x(0);
   load_a(0, a_even);
-  stage_twiddles<K>(twl, tid, NT);
+#pragma unroll
+  for (int s = 0; s < (K + NT - 1) / NT; ++s)
+    if (s * NT + tid < K) twl[s * NT + tid] = tw_stage[s];
 
   // bias of the outputs this thread will store (fetched now, used at the very end)
   float4 bv4[NV];
