@@ -31,9 +31,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
 
-# HBM bytes per step measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
-# None until measured for the current kernels.
-MEASURED_TRAFFIC_BYTES = None
+# Bytes per launch between L2 and the memory side, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# each scaled by what the counter reads for a plain 256 MiB copy
+# (profiles/fc_fused_kernel_cfg2_pmc_traffic.md): 6.55 MB fetched + 1.05 MB written.
+MEASURED_TRAFFIC_BYTES = 7594433
 
 
 def algorithmic_work(p, q, k, B, bias):

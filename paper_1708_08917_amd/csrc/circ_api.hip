@@ -164,12 +164,25 @@ hipError_t launch_fused_t(const float4* wf, const float* x, const float* bias, f
   return hipGetLastError();
 }
 
-// The fused kernel recomputes the FFT of x once per tile of output block rows; it is
-// chosen while that redundancy stays small.
+// Upper bound, in MiB, of the operand bytes all workgroups of the fused kernel pull through
+// L2 (see use_fused_forward).
+#ifndef CIRC_FUSED_MAX_L2_MIB
+#define CIRC_FUSED_MAX_L2_MIB 256
+#endif
+
+// Fused or unfused forward?  The fused kernel re-reads the weight tile once per tile of batch
+// rows and the x tile once per tile of output block rows, all through L2 (about 45 GB/s per
+// CU for data first touched in a launch), and recomputes the FFT of x once per tile of output
+// block rows.  That wins while the problem is small (one launch, no spectra round trip through
+// HBM); for large batches the unfused route, whose GEMM reuses operands from registers over
+// 32x32 tiles, is faster.
 inline bool use_fused_forward(int p, int q, int k, int batch) {
-  (void)q; (void)batch;
   const int it = fused_it(k);
-  return it > 0 && cdiv(p, it) <= 8;
+  if (it == 0) return false;
+  const double n_it = double(cdiv(p, it)), n_bt = double(cdiv(batch, 2));
+  const double w_bytes = double(p) * q * k * 4.0, x_bytes = double(batch) * q * k * 4.0;
+  const double l2_bytes = n_bt * w_bytes + n_it * x_bytes;
+  return n_it <= 8 && l2_bytes <= double(CIRC_FUSED_MAX_L2_MIB) * 1048576.0;
 }
 
 hipError_t launch_fused(int k, const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,

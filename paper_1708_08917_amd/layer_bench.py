@@ -1,0 +1,105 @@
+"""Time one layer configuration through the C ABI (HIP events around back-to-back calls).
+
+    python -m paper_1708_08917_amd.layer_bench --config cfg3 [--reps 100] [--backward]
+
+Configurations: cfg1 (FC 1024x1024, k=16, batch 1), cfg2 (FC 4096x4096, k=64, batch 64),
+cfg3 (9216->4096->4096 head, k=128, batch 256, both layers), cfg4 (3x3 CONV 256->256, 28x28,
+batch 32, k=64), cfg5 (FC 16384x16384, k=256, batch 1024; --backward adds dx and dw).
+Prints one line per layer with the time per call and the algorithmic bytes/flops rates.
+This is the companion of bench.py for the workloads that bench.py does not time; it is also
+the program that the rocprofv3 summaries under profiles/ were collected with.
+"""
+from __future__ import annotations
+
+import argparse
+
+import torch
+
+from . import binding as B
+from . import synth
+
+DEV = "cuda:0"
+
+
+def _time(fn, reps, warm):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps          # microseconds per call
+
+
+def fc_work(cfg):
+    F = cfg.k // 2 + 1
+    lg = cfg.k.bit_length() - 1
+    byts = 8 * cfg.p * cfg.q * F + 4 * cfg.batch * (cfg.n_in + cfg.n_out) + (4 * cfg.n_out if cfg.bias else 0)
+    flops = 8 * cfg.p * cfg.q * (cfg.k // 2) * cfg.batch + (cfg.p + cfg.q) * cfg.batch * 5 * cfg.k * lg // 2
+    return byts, flops
+
+
+def bench_fc(cfg, reps, backward=False):
+    w, x, b = synth.fc_inputs(cfg)
+    wd, xd = torch.from_numpy(w).to(DEV), torch.from_numpy(x).to(DEV)
+    bd = None if b is None else torch.from_numpy(b).to(DEV)
+    wh = B.circ_precompute_spectra(wd)
+    y = torch.empty(cfg.batch, cfg.n_out, device=DEV)
+    ws = torch.empty(max(1, B.circ_fc_workspace_bytes(cfg.p, cfg.q, cfg.k, cfg.batch, True)), dtype=torch.uint8, device=DEV)
+    epi = (B.EPI_BIAS if b is not None else 0) | (B.EPI_RELU if cfg.relu else 0)
+    t = _time(lambda: B.circ_fc_forward(wh, xd, bd, y, cfg.p, cfg.q, cfg.k, epi, ws), reps, max(3, reps // 10))
+    byts, flops = fc_work(cfg)
+    print(f"{cfg.name}: forward {t:9.2f} us/call  {cfg.batch / t * 1e6:12.0f} vectors/s  alg {byts / t * 1e-3:7.1f} GB/s "
+          f"{flops / t * 1e-6:6.2f} TFLOP/s  dense-equivalent {2.0 * cfg.n_in * cfg.n_out * cfg.batch / t * 1e-6:7.1f} TFLOP/s", flush=True)
+    tp = _time(lambda: B.circ_precompute_spectra(wd, wh), 20, 3)
+    print(f"{cfg.name}: precompute_spectra {tp:9.2f} us/call", flush=True)
+    if backward:
+        dy = torch.from_numpy(synth.fc_upstream_grad(cfg)).to(DEV)
+        dx, dw = torch.empty_like(xd), torch.empty_like(wd)
+        r = max(5, reps // 4)
+        tb = _time(lambda: B.circ_fc_backward(wh, xd, dy, cfg.p, cfg.q, cfg.k, True, True, dx, dw, ws), r, 3)
+        tdx = _time(lambda: B.circ_fc_backward(wh, xd, dy, cfg.p, cfg.q, cfg.k, True, False, dx, None, ws), r, 3)
+        tdw = _time(lambda: B.circ_fc_backward(wh, xd, dy, cfg.p, cfg.q, cfg.k, False, True, None, dw, ws), r, 3)
+        print(f"{cfg.name}: backward {tb:9.2f} us/call (dx only {tdx:.2f}, dw only {tdw:.2f})  dense-equivalent "
+              f"{4.0 * cfg.n_in * cfg.n_out * cfg.batch / tb * 1e-6:7.1f} TFLOP/s", flush=True)
+
+
+def bench_conv(cfg, reps):
+    w, x = synth.conv_inputs(cfg)
+    wd, xd = torch.from_numpy(w).to(DEV), torch.from_numpy(x).to(DEV)
+    wh = B.circ_precompute_spectra(wd)
+    y = torch.empty(cfg.N, cfg.C_out, cfg.H, cfg.W, device=DEV)
+    nws = B.circ_conv_workspace_bytes(cfg.N, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.r, 1, cfg.pad, cfg.k)
+    ws = torch.empty(nws, dtype=torch.uint8, device=DEV)
+    t = _time(lambda: B.circ_conv_forward(wh, xd, None, y, cfg.C_out, cfg.r, 1, cfg.pad, cfg.k, 0, ws), reps, max(3, reps // 10))
+    byts = 2 * x.nbytes + w.nbytes
+    dense = 2.0 * cfg.N * cfg.H * cfg.W * cfg.r * cfg.r * cfg.C_in * cfg.C_out
+    print(f"{cfg.name}: forward {t:9.2f} us/call  {cfg.N / t * 1e6:10.0f} images/s  alg {byts / t * 1e-3:7.1f} GB/s  "
+          f"dense-equivalent {dense / t * 1e-6:7.1f} TFLOP/s", flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", default="all", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "all"])
+    ap.add_argument("--reps", type=int, default=100)
+    ap.add_argument("--backward", action="store_true")
+    a = ap.parse_args()
+    sel = lambda n: a.config in (n, "all")
+    if sel("cfg1"):
+        bench_fc(synth.CFG1, a.reps)
+    if sel("cfg2"):
+        bench_fc(synth.CFG2, a.reps)
+    if sel("cfg3"):
+        bench_fc(synth.CFG3_L1, a.reps)
+        bench_fc(synth.CFG3_L2, a.reps)
+    if sel("cfg4"):
+        bench_conv(synth.CFG4, a.reps)
+    if sel("cfg5"):
+        bench_fc(synth.CFG5, max(10, a.reps // 4), backward=a.backward or a.config == "all")
+
+
+if __name__ == "__main__":
+    main()
