@@ -7,6 +7,7 @@
 #include "../../include/circ.h"
 #include "circ_kernels.h"
 #include "circ_fused.h"
+#include "circ_gemv.h"
 
 namespace {
 
@@ -37,6 +38,12 @@ inline int fused_q2p(int q, int k) { const int jc = 4096 / k; return int(cdiv(q,
 inline size_t fused_section_elems(int n_grids, int p, int q, int k) {   // in float4 units
   if (n_grids != 1 || fused_it(k) == 0) return 0;
   return size_t(fused_igp(p, k)) * fused_q2p(q, k) * (k / 32) * 64;
+}
+
+// Section 3 (FC only, k >= 4): [i][j][slot] order of the batch <= 2 kernel.
+inline size_t gemv_section_elems(int n_grids, int p, int q, int k) {      // in float2 units
+  if (n_grids != 1 || k < 4) return 0;
+  return size_t(p) * q * (k / 2);
 }
 
 struct FftPlan { int P, NT; size_t lds; };
@@ -134,20 +141,24 @@ hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int NF, int
   return hipGetLastError();
 }
 
+// Kernels whose LDS tile exceeds the 64 KB default opt in once (gfx950: 160 KB per workgroup).
+template <class Kern>
+hipError_t ensure_lds(Kern kern, size_t bytes, bool& done) {
+  if (bytes > 64 * 1024 && !done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+    done = true;
+  }
+  return hipSuccess;
+}
+
 template <int K, int IT, int NP, int NT>
 hipError_t launch_fused_t(const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
                           int relu, hipStream_t s) {
   using Sh = FusedShape<K, IT, NP, NT>;
   static_assert((4096 / K) % Sh::JC == 0, "packed weights are padded to chunks of 4096/K input blocks");
-  if (Sh::LDS_BYTES > 64 * 1024) {   // more than the default limit: opt in (gfx950 has 160 KB per workgroup)
-    static bool opted_in = false;
-    if (!opted_in) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&fc_fused_kernel<K, IT, NP, NT>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)Sh::LDS_BYTES) != hipSuccess)
-        return hipErrorInvalidValue;
-      opted_in = true;
-    }
-  }
+  static bool opted_in = false;
+  if (ensure_lds(&fc_fused_kernel<K, IT, NP, NT>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
   const int n_it = (int)cdiv(p, IT), n_bt = (int)cdiv(batch, 2 * NP);
   // Split the tile grid over the 8 XCDs as xa x (8/xa) rectangles; pick the split that
   // minimises the bytes every XCD pulls into its own L2 (weight tiles + x rows).
@@ -196,6 +207,31 @@ hipError_t launch_fused(int k, const float4* wf, const float* x, const float* bi
   }
 }
 
+template <int K>
+hipError_t launch_gemv_k(const float2* wg, const float* x, const float* bias, float* y, int p, int q, int batch, int relu,
+                         hipStream_t s) {
+  using Sh = GemvShape<K>;
+  static bool opted_in = false;
+  if (ensure_lds(&fc_gemv_kernel<K>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((fc_gemv_kernel<K>), dim3((unsigned)p), dim3(256), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch, relu);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemv(int k, const float2* wg, const float* x, const float* bias, float* y, int p, int q, int batch,
+                       int relu, hipStream_t s) {
+  switch (k) {
+    case 4: return launch_gemv_k<4>(wg, x, bias, y, p, q, batch, relu, s);
+    case 8: return launch_gemv_k<8>(wg, x, bias, y, p, q, batch, relu, s);
+    case 16: return launch_gemv_k<16>(wg, x, bias, y, p, q, batch, relu, s);
+    case 32: return launch_gemv_k<32>(wg, x, bias, y, p, q, batch, relu, s);
+    case 64: return launch_gemv_k<64>(wg, x, bias, y, p, q, batch, relu, s);
+    case 128: return launch_gemv_k<128>(wg, x, bias, y, p, q, batch, relu, s);
+    case 256: return launch_gemv_k<256>(wg, x, bias, y, p, q, batch, relu, s);
+    case 512: return launch_gemv_k<512>(wg, x, bias, y, p, q, batch, relu, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
   return x < y + nb && y < x + na;
@@ -230,7 +266,8 @@ size_t circ_spectra_bytes(int n_grids, int p, int q, int k) {
   if (n_grids <= 0 || p <= 0 || q <= 0 || !valid_k(k)) return 0;
   if ((long long)p * q > (1ll << 31) - 1) return 0;
   return 2 * align_up(spectra_section_elems(n_grids, p, q, k) * sizeof(float2), 256) +
-         align_up(fused_section_elems(n_grids, p, q, k) * sizeof(float4), 256);
+         align_up(fused_section_elems(n_grids, p, q, k) * sizeof(float4), 256) +
+         align_up(gemv_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
 }
 
 circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, int k, void* w_hat, void* stream) {
@@ -257,6 +294,12 @@ circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, i
     float4* wfu = reinterpret_cast<float4*>(static_cast<char*>(w_hat) + 2 * sec);
     hipLaunchKernelGGL(pack_fused_kernel, dim3((unsigned)cdiv((long long)nfused, 256)), dim3(256), 0, s, fwd, wfu, p, q, k,
                        fused_igp(p, k), fused_q2p(q, k));
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  }
+  const size_t ngemv = gemv_section_elems(n_grids, p, q, k);
+  if (ngemv) {
+    float2* wg = reinterpret_cast<float2*>(static_cast<char*>(w_hat) + 2 * sec + align_up(nfused * sizeof(float4), 256));
+    hipLaunchKernelGGL(pack_gemv_kernel, dim3((unsigned)cdiv((long long)ngemv, 256)), dim3(256), 0, s, fwd, wg, p, q, k);
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
   }
   return CIRC_OK;
@@ -286,6 +329,14 @@ circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias
   if (!aligned16(workspace)) return CIRC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
+  if (batch <= 2 && k >= 4) {   // one or two vectors: streaming matrix-vector kernel
+    const size_t sec = align_up(spectra_section_elems(1, p, q, k) * sizeof(float2), 256);
+    const size_t fsec = align_up(fused_section_elems(1, p, q, k) * sizeof(float4), 256);
+    const float2* wg = reinterpret_cast<const float2*>(static_cast<const char*>(w_hat) + 2 * sec + fsec);
+    if (launch_gemv(k, wg, x, use_bias ? bias : nullptr, y, p, q, batch, (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
+      return CIRC_EHIP;
+    return CIRC_OK;
+  }
   if (use_fused_forward(p, q, k, batch)) {
     const size_t sec = align_up(spectra_section_elems(1, p, q, k) * sizeof(float2), 256);
     const float4* wfu = reinterpret_cast<const float4*>(static_cast<const char*>(w_hat) + 2 * sec);

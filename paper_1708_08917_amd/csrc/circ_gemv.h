@@ -1,0 +1,167 @@
+// FC forward for batch <= 2 in one launch: a bandwidth-bound streaming reduction.
+//
+// With one or two input vectors the contraction  Y^[i,f] = sum_j W^[i,j,f] X^[j,f]  is a
+// matrix-vector product per frequency: every weight is used once, so the kernel is bound by
+// streaming the cached weight spectra and runs on the vector ALUs (no matrix cores).
+// One workgroup per output block row i:
+//   1. FFT of the packed pair z = x_b0 + i*x_b1 for all q input blocks (recomputed by every
+//      workgroup: x is tiny compared with the weights), written as the four real columns
+//      (Re U, Im U, Re V, Im V), U = Z[f], V = conj(Z[K-f]) (column 3 stores +Im Z[K-f]);
+//   2. thread (j-group, slot) streams W^[i][j][slot] (fully coalesced) and accumulates
+//      P += Re(W^) * cols, Q += Im(W^) * cols;
+//   3. the j-groups are summed through LDS in a fixed order, Zy[f] = (P0-Q1, P1+Q0),
+//      Zy[K-f] = (P2+Q3, P3-Q2), slot 0 holds the real DC and Nyquist bins;
+//   4. one inverse FFT gives (y_b0, y_b1); bias and ReLU are applied on the way out.
+// This is Algorithm 1 with the weights cached in the frequency domain (Sec. 3.1, Sec. 4.2)
+// and the real-input symmetry of Sec. 4.1.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "circ_fft.h"
+#include "circ_kernels.h"
+
+namespace circ {
+
+template <int K>
+struct GemvShape {
+  static constexpr int NT = 256;
+  static constexpr int S = K / 2;                       // complex slots per block
+  static constexpr int PT = 4096 / K < 128 ? 4096 / K : 128;   // input blocks (FFT columns) per chunk
+  static constexpr int PP = PT + 1;
+  static constexpr int OPROW = 2 * K + 2;
+  static constexpr int JG = NT / S >= 1 ? NT / S : 1;   // threads sharing a slot split the j range
+  static constexpr int ZELEMS = K * PP;
+  static constexpr size_t LDS_BYTES = size_t(ZELEMS) * sizeof(float2) + size_t(PT) * OPROW * sizeof(float) +
+                                      size_t(K) * sizeof(float2) + size_t(NT) * 8 * sizeof(float);
+  static_assert(K >= 4 && K <= 512 && S <= NT, "block size out of range for this kernel");
+};
+
+// Weight spectra for the batch <= 2 kernel: Wg[(i*q + j)*S + slot], slot 0 = (W^[0].re,
+// W^[K/2].re), slot f = W^[f] otherwise.  `spec` is the [f][j][i] section.
+__global__ void pack_gemv_kernel(const float2* __restrict__ spec, float2* __restrict__ Wg, int p, int q, int K) {
+  const int S = K / 2;
+  const long long total = (long long)p * q * S;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int slot = int(idx % S);
+  const long long ij = idx / S;
+  const int j = int(ij % q), i = int(ij / q);
+  const long long fs = (long long)p * q, e = (long long)j * p + i;
+  Wg[idx] = slot == 0 ? make_float2(spec[e].x, spec[(long long)S * fs + e].x) : spec[(long long)slot * fs + e];
+}
+
+template <int K>
+__global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__ Wg, const float* __restrict__ x,
+                                                      const float* __restrict__ bias, float* __restrict__ y,
+                                                      int p, int q, int B, int relu) {
+  using Sh = GemvShape<K>;
+  constexpr int NT = Sh::NT, S = Sh::S, PT = Sh::PT, PP = Sh::PP, OPROW = Sh::OPROW, JG = Sh::JG;
+  extern __shared__ float smem[];
+  float2* z = reinterpret_cast<float2*>(smem);
+  float* op = smem + 2 * Sh::ZELEMS;
+  float2* twl = reinterpret_cast<float2*>(op + PT * OPROW);
+  float* red = reinterpret_cast<float*>(twl + K);
+
+  const int tid = threadIdx.x;
+  const int i = blockIdx.x;
+  const long long ldx = (long long)q * K, ldy = (long long)p * K;
+  const int nchunks = (q + PT - 1) / PT;
+  stage_twiddles<K>(twl, tid, NT);
+
+  const int slot = tid % S, jg = tid / S;          // contraction role (threads beyond S*JG idle)
+  const bool active = jg < JG;
+  float P[4] = {0.f, 0.f, 0.f, 0.f}, Q[4] = {0.f, 0.f, 0.f, 0.f};
+  const float2* wrow = Wg + (long long)i * q * S + slot;
+
+  for (int c = 0; c < nchunks; ++c) {
+    const int j0 = c * PT;
+    // rows b0 (real part) and b1 (imaginary part) of the chunk -> z[n][column j]
+    for (int idx = tid; idx < 2 * PT * (K / 4); idx += NT) {
+      const int half = idx / (PT * (K / 4)), rem = idx % (PT * (K / 4));
+      const int col = rem / (K / 4), n = 4 * (rem % (K / 4));
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (half < B && j0 + col < q) v = *reinterpret_cast<const float4*>(x + (long long)half * ldx + (long long)(j0 + col) * K + n);
+      lds_put(z, (n + 0) * PP + col, half, v.x);
+      lds_put(z, (n + 1) * PP + col, half, v.y);
+      lds_put(z, (n + 2) * PP + col, half, v.z);
+      lds_put(z, (n + 3) * PP + col, half, v.w);
+    }
+    __syncthreads();
+    auto sink = [&](int col) {
+      return [=](int f, float2 v) {
+        int sl, h;
+        if (f == 0) { sl = 0; h = 0; }
+        else if (f == S) { sl = 0; h = 1; }
+        else if (f < S) { sl = f; h = 0; }
+        else { sl = K - f; h = 1; }
+        *reinterpret_cast<float2*>(op + col * OPROW + 4 * sl + 2 * h) = v;
+      };
+    };
+    {
+      const int col = tid % PT, t = tid / PT;
+      fft_lds_pass1<K, false>(z, PP, col, t, NT / PT, twl);
+      __syncthreads();
+      fft_lds_pass2<K, false>(z, PP, col, t, NT / PT, sink(col));
+    }
+    __syncthreads();
+    if (active) {
+      const int jend = min(PT, q - j0);
+#pragma unroll 4
+      for (int jj = jg; jj < jend; jj += JG) {
+        const float2 w = wrow[(long long)(j0 + jj) * S];
+        const float4 cv = *reinterpret_cast<const float4*>(op + jj * OPROW + 4 * slot);
+        P[0] += w.x * cv.x; P[1] += w.x * cv.y; P[2] += w.x * cv.z; P[3] += w.x * cv.w;
+        Q[0] += w.y * cv.x; Q[1] += w.y * cv.y; Q[2] += w.y * cv.z; Q[3] += w.y * cv.w;
+      }
+    }
+    __syncthreads();   // z and op are rewritten by the next chunk
+  }
+
+  // sum over the j-groups in a fixed order, then assemble the spectrum of the output pair
+  if (active) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      red[(m * JG + jg) * S + slot] = P[m];
+      red[((4 + m) * JG + jg) * S + slot] = Q[m];
+    }
+  }
+  __syncthreads();
+  if (tid < S) {
+    float Ps[4], Qs[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      float a = 0.f, b = 0.f;
+      for (int g = 0; g < JG; ++g) {
+        a += red[(m * JG + g) * S + tid];
+        b += red[((4 + m) * JG + g) * S + tid];
+      }
+      Ps[m] = a;
+      Qs[m] = b;
+    }
+    if (tid == 0) {
+      z[0] = make_float2(Ps[0], Ps[1]);              // DC of (y_b0, y_b1)
+      z[S * 2] = make_float2(Qs[2], Qs[3]);          // Nyquist
+    } else {
+      z[tid * 2] = make_float2(Ps[0] - Qs[1], Ps[1] + Qs[0]);
+      z[(K - tid) * 2] = make_float2(Ps[2] + Qs[3], Ps[3] - Qs[2]);
+    }
+  }
+  __syncthreads();
+  // inverse transform of the single column (row stride 2)
+  fft_lds_pass1<K, true>(z, 2, 0, tid, NT, twl);
+  __syncthreads();
+  fft_lds_pass2_inplace<K, true>(z, 2, 0, tid, NT);
+  __syncthreads();
+  for (int idx = tid; idx < 2 * K; idx += NT) {
+    const int half = idx / K, n = idx % K;
+    if (half < B) {
+      float v = lds_get(z, fft_pos<K>(n) * 2, half);
+      if (bias) v += bias[(long long)i * K + n];
+      if (relu) v = fmaxf(v, 0.f);
+      y[(long long)half * ldy + (long long)i * K + n] = v;
+    }
+  }
+}
+
+}  // namespace circ

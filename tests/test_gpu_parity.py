@@ -58,6 +58,17 @@ def test_fc_forward_shapes(p, q, k, batch):
     check(G.gpu_fc_forward(w, x, b, relu=False), O.fc_forward(w, x, b), f"fc fwd {p}x{q} k={k} B={batch}")
 
 
+# ---- one or two input vectors: the streaming matrix-vector kernel, every block size, more
+# input blocks than one chunk holds (chunk = min(4096/k, 128) blocks)
+@pytest.mark.parametrize("k,q", [(4, 3), (4, 130), (8, 129), (16, 64), (16, 131), (32, 129), (64, 65), (128, 33), (256, 17), (512, 9)])
+@pytest.mark.parametrize("batch", [1, 2])
+def test_fc_forward_one_or_two_vectors(k, q, batch):
+    p = 5
+    w, x, b = rand_fc(p, q, k, batch)
+    check(G.gpu_fc_forward(w, x, b, relu=True), O.fc_forward(w, x, b, relu=True), f"gemv k={k} q={q} B={batch}")
+    check(G.gpu_fc_forward(w, x), O.fc_forward(w, x), f"gemv k={k} q={q} B={batch} no epilogue")
+
+
 def test_fc_forward_bias_only_and_relu_only():
     w, x, b = rand_fc(4, 4, 16, 9)
     check(G.gpu_fc_forward(w, x, None, relu=True), O.fc_forward(w, x, None, relu=True), "relu only")
