@@ -175,6 +175,28 @@ hipError_t launch_fused_t(const float4* wf, const float* x, const float* bias, f
   return hipGetLastError();
 }
 
+// Packed batch pairs per workgroup: two when that still leaves at least 256 tiles (one per
+// CU); the weight tile is then streamed half as often.
+inline int fused_np(int p, int k, int batch) {
+  const long long tiles2 = cdiv(p, fused_it(k)) * cdiv(batch, 4);
+  return (k >= 64 && tiles2 >= 256) ? 2 : 1;
+}
+
+hipError_t launch_fused(int k, const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
+                        int relu, hipStream_t s) {
+  const int np = fused_np(p, k, batch);
+  switch (k) {
+    case 32: return launch_fused_t<32, 16, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
+    case 64: return np == 2 ? launch_fused_t<64, 8, 2, 512>(wf, x, bias, y, p, q, batch, relu, s)
+                            : launch_fused_t<64, 8, 1, 512>(wf, x, bias, y, p, q, batch, relu, s);
+    case 128: return np == 2 ? launch_fused_t<128, 8, 2, 256>(wf, x, bias, y, p, q, batch, relu, s)
+                             : launch_fused_t<128, 8, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
+    case 256: return np == 2 ? launch_fused_t<256, 8, 2, 256>(wf, x, bias, y, p, q, batch, relu, s)
+                             : launch_fused_t<256, 8, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 // Upper bound, in MiB, of the operand bytes all workgroups of the fused kernel pull through
 // L2 (see use_fused_forward).
 #ifndef CIRC_FUSED_MAX_L2_MIB
@@ -190,21 +212,10 @@ hipError_t launch_fused_t(const float4* wf, const float* x, const float* bias, f
 inline bool use_fused_forward(int p, int q, int k, int batch) {
   const int it = fused_it(k);
   if (it == 0) return false;
-  const double n_it = double(cdiv(p, it)), n_bt = double(cdiv(batch, 2));
+  const double n_it = double(cdiv(p, it)), n_bt = double(cdiv(batch, 2 * fused_np(p, k, batch)));
   const double w_bytes = double(p) * q * k * 4.0, x_bytes = double(batch) * q * k * 4.0;
   const double l2_bytes = n_bt * w_bytes + n_it * x_bytes;
   return n_it <= 8 && l2_bytes <= double(CIRC_FUSED_MAX_L2_MIB) * 1048576.0;
-}
-
-hipError_t launch_fused(int k, const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
-                        int relu, hipStream_t s) {
-  switch (k) {
-    case 32: return launch_fused_t<32, 16, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
-    case 64: return launch_fused_t<64, 8, 1, 512>(wf, x, bias, y, p, q, batch, relu, s);
-    case 128: return launch_fused_t<128, 8, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
-    case 256: return launch_fused_t<256, 8, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
-    default: return hipErrorInvalidValue;
-  }
 }
 
 template <int K>

@@ -52,6 +52,8 @@ def test_fc_forward_all_block_sizes(k):
     (72, 3, 64, 5), (70, 2, 128, 34), (130, 2, 32, 3), (66, 1, 256, 2), (65, 1, 512, 3),
     # fused route with ragged tiles: p not a multiple of 8, odd batch, q not a multiple of the chunk
     (9, 33, 64, 3), (7, 17, 128, 5), (5, 9, 256, 1), (3, 5, 512, 2), (17, 65, 32, 1), (64, 64, 64, 2),
+    # fused route, two packed batch pairs per workgroup (taken when >= 256 such tiles exist)
+    (64, 3, 64, 130), (33, 5, 128, 207), (17, 2, 256, 341), (60, 70, 64, 133),
 ])
 def test_fc_forward_shapes(p, q, k, batch):
     w, x, b = rand_fc(p, q, k, batch)
