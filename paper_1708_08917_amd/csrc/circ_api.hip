@@ -8,6 +8,7 @@
 #include "circ_kernels.h"
 #include "circ_fused.h"
 #include "circ_gemv.h"
+#include "circ_conv_fused.h"
 
 namespace {
 
@@ -44,6 +45,24 @@ inline size_t fused_section_elems(int n_grids, int p, int q, int k) {   // in fl
 inline size_t gemv_section_elems(int n_grids, int p, int q, int k) {      // in float2 units
   if (n_grids != 1 || k < 4) return 0;
   return size_t(p) * q * (k / 2);
+}
+
+// Fused CONV kernel: built for k = 64, 3x3 filters, q in {1, 2, 4} input channel blocks and
+// up to 16 output channel blocks.  ncombo = (slot groups) x (groups of 4 output blocks, rounded
+// up to a power of two) must divide the 8 waves of a workgroup.
+inline int conv_fused_ncombo(int p, int q, int k, int r) {
+  if (k != 64 || r != 3 || !(q == 1 || q == 2 || q == 4)) return 0;
+  int ig = 1;
+  while (ig * 4 < p) ig *= 2;
+  const int ncombo = (k / 32) * ig;
+  return ncombo <= 8 ? ncombo : 0;
+}
+// Section 2 of a CONV blob (n_grids = r*r > 1): operand order of the fused CONV kernel.
+inline size_t conv_section_elems(int n_grids, int p, int q, int k) {      // in float2 units
+  int r = 1;
+  while (r * r < n_grids) ++r;
+  if (n_grids == 1 || r * r != n_grids) return 0;
+  return size_t(n_grids) * q * conv_fused_ncombo(p, q, k, r) * 64;
 }
 
 struct FftPlan { int P, NT; size_t lds; };
@@ -278,7 +297,8 @@ size_t circ_spectra_bytes(int n_grids, int p, int q, int k) {
   if ((long long)p * q > (1ll << 31) - 1) return 0;
   return 2 * align_up(spectra_section_elems(n_grids, p, q, k) * sizeof(float2), 256) +
          align_up(fused_section_elems(n_grids, p, q, k) * sizeof(float4), 256) +
-         align_up(gemv_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
+         align_up(gemv_section_elems(n_grids, p, q, k) * sizeof(float2), 256) +
+         align_up(conv_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
 }
 
 circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, int k, void* w_hat, void* stream) {
@@ -305,6 +325,13 @@ circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, i
     float4* wfu = reinterpret_cast<float4*>(static_cast<char*>(w_hat) + 2 * sec);
     hipLaunchKernelGGL(pack_fused_kernel, dim3((unsigned)cdiv((long long)nfused, 256)), dim3(256), 0, s, fwd, wfu, p, q, k,
                        fused_igp(p, k), fused_q2p(q, k));
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  }
+  const size_t nconv = conv_section_elems(n_grids, p, q, k);
+  if (nconv) {   // FC sections are empty for n_grids > 1, so this one follows section 1 directly
+    float2* wc = reinterpret_cast<float2*>(static_cast<char*>(w_hat) + 2 * sec);
+    hipLaunchKernelGGL(pack_conv_kernel, dim3((unsigned)cdiv((long long)nconv, 256)), dim3(256), 0, s, fwd, wc, n_grids, p,
+                       q, k, int(nconv / (size_t(n_grids) * q * 64)));
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
   }
   const size_t ngemv = gemv_section_elems(n_grids, p, q, k);
@@ -425,6 +452,61 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
   return CIRC_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+struct ConvTilePlan { int TH, TW, tiles_h, tiles_w; size_t lds; };
+
+// Output tile of the fused CONV kernel: the one with the fewest transformed input positions
+// in total (tile + halo, summed over the tiles) that fits LDS and the per-wave task limit.
+template <int K, int NT>
+bool plan_conv_tile(int p, int qh, int r, int Ho, int Wo, int ncombo, ConvTilePlan& best) {
+  using Sh = ConvFusedShape<K, NT>;
+  const int max_pos = Sh::MAXT * (Sh::NW / ncombo);
+  long long best_cost = -1;
+  for (int th = 1; th <= Ho && th + r - 1 <= 16; ++th)
+    for (int tw = 1; tw <= Wo && tw + r - 1 <= 16; ++tw) {   // the kernel lays input positions out with a row pitch of 16
+      if (th * tw > max_pos) continue;
+      const int ipos = (th + r - 1) * 16;
+      const size_t lds = conv_fused_lds_bytes<K, NT>(qh * ipos, p * th * tw);
+      if (lds > 160 * 1024) continue;
+      const long long nt = cdiv(Ho, th) * cdiv(Wo, tw);
+      // FFT chunks (PT columns each, per channel block) over all tiles, then fewer tiles, then wider tiles
+      const long long cost = nt * cdiv(ipos, Sh::PT) * 1024 + nt * 8 - tw;
+      if (best_cost < 0 || cost < best_cost) {
+        best_cost = cost;
+        best = ConvTilePlan{th, tw, (int)cdiv(Ho, th), (int)cdiv(Wo, tw), lds};
+      }
+    }
+  return best_cost >= 0;
+}
+
+template <int Q>
+hipError_t launch_conv_fused_q(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
+                               int W, int Ho, int Wo, int pad, int ncombo, int relu, hipStream_t s) {
+  constexpr int K = 64, NT = 512, R = 3, QH = Q < 2 ? Q : 2;
+  ConvTilePlan pl;
+  if (!plan_conv_tile<K, NT>(C_out / K, QH, R, Ho, Wo, ncombo, pl)) return hipErrorInvalidValue;
+  if (pl.lds > 64 * 1024) {   // opt in to more than the default LDS limit, once per size increase
+    static size_t opted = 0;
+    if (pl.lds > opted) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_fused_kernel<K, NT, R, Q, QH>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
+        return hipErrorInvalidValue;
+      opted = pl.lds;
+    }
+  }
+  const long long grid = (long long)cdiv(N, 2) * pl.tiles_h * pl.tiles_w;
+  hipLaunchKernelGGL((conv_fused_kernel<K, NT, R, Q, QH>), dim3((unsigned)grid), dim3(NT), pl.lds, s, wc, x, bias, y, N, C_out,
+                     H, W, Ho, Wo, pad, pl.TH, pl.TW, pl.tiles_h, pl.tiles_w, ncombo, relu);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" {
+
 static bool conv_dims_ok(int N, int C_in, int C_out, int H, int W, int r, int pad, int k) {
   if (N <= 0 || C_in <= 0 || C_out <= 0 || H <= 0 || W <= 0 || r <= 0 || !valid_k(k)) return false;
   if (C_in % k || C_out % k) return false;
@@ -465,6 +547,17 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
 
   const int p = C_out / k, q = C_in / k, NF = k / 2 + 1;
   const long long HW = (long long)H * W, HWo = (long long)Ho * Wo;
+  const int ncombo = conv_fused_ncombo(p, q, k, r);
+  if (ncombo > 0 && (long long)cdiv(N, 2) * Ho * Wo < (1ll << 31)) {
+    const size_t sec = align_up(spectra_section_elems(r * r, p, q, k) * sizeof(float2), 256);
+    const float2* wc = reinterpret_cast<const float2*>(static_cast<const char*>(w_hat) + 2 * sec);
+    const float* bp = use_bias ? bias : nullptr;
+    const int relu = (epilogue & CIRC_EPI_RELU) ? 1 : 0;
+    hipError_t e = q == 1 ? launch_conv_fused_q<1>(wc, x, bp, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
+                 : q == 2 ? launch_conv_fused_q<2>(wc, x, bp, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
+                          : launch_conv_fused_q<4>(wc, x, bp, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+    return e == hipSuccess ? CIRC_OK : CIRC_EHIP;
+  }
   const long long xrows = (long long)q * N * HW, yrows = (long long)p * N * HWo;
   float2* xh = static_cast<float2*>(workspace);
   float2* yh = reinterpret_cast<float2*>(static_cast<char*>(workspace) +

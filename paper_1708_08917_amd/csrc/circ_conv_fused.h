@@ -1,0 +1,295 @@
+// Fused block-circulant CONV forward (Sec. 3.2, Eq. 6 with the weight structure of Eq. 7):
+// channel FFT -> contraction over the r*r offsets and the input channel blocks -> channel
+// IFFT -> bias/ReLU in ONE kernel; x, the cached weight spectra and y are the only HBM traffic.
+//
+// The FFT runs over the channel axis of every pixel, and a spatial shift commutes with it, so
+// each input pixel of a tile (output tile + halo) is transformed once and the r*r taps only
+// pick different rows of the transformed tile; pixels outside the image have a zero spectrum.
+//
+// As in the fused FC kernel two real vectors share one complex transform, here the same pixel
+// of two consecutive images (z = x[n] + i*x[n+1]): offsets and borders act identically on
+// both, so the pair never has to be separated.  The contraction uses
+// v_mfma_f32_4x4x1_16B_f32: block = frequency slot, rows = 4 output channel blocks,
+// columns = (Re U, Im U, Re V, Im V) of one pixel pair, k = one (offset, input block).
+// The r*r*q weight operands of a wave stay in registers for the whole tile.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "circ_fft.h"
+#include "circ_fused.h"
+#include "circ_kernels.h"
+
+namespace circ {
+
+template <int K, int NT>
+struct ConvFusedShape {
+  static constexpr int NW = NT / 64;
+  static constexpr int PT = 8 * NT / K;        // FFT columns per chunk
+  static constexpr int PP = PT + 1;
+  static constexpr int S = K / 2;
+  static constexpr int FG = S / 16;
+  static constexpr int OPROW = 2 * K + 2;
+  static constexpr int MAXT = 8;               // output positions per wave
+  static_assert(K >= 32 && NT % PT == 0 && (2 * K * PT) % NT == 0, "bad chunk shape");
+};
+
+// LDS bytes of a tile with `nrows` operand rows held at a time (input positions * channel
+// blocks per round) and `ncoli` inverse columns (p * output positions).
+template <int K, int NT>
+inline size_t conv_fused_lds_bytes(int nrows, int ncoli) {
+  using Sh = ConvFusedShape<K, NT>;
+  size_t op = size_t(nrows) * Sh::OPROW * sizeof(float);
+  size_t inv = size_t(K) * (ncoli + 1) * sizeof(float2);
+  return size_t(K) * Sh::PP * sizeof(float2) + size_t(K) * sizeof(float2) + (256 + 64) * sizeof(int) + (op > inv ? op : inv);
+}
+
+// Weight spectra in the operand order of the fused CONV kernel:
+//   Wc[((g*q + j)*ncombo + combo)*64 + 4*blk + m] = W^[g][i = 4*ig + m][j][slot = 16*fg + blk]
+// with combo = ig*FG + fg, slot 0 = (W^[0].re, W^[K/2].re), rows i >= p zero.
+// `spec` is the [g][f][j][i] section.
+__global__ void pack_conv_kernel(const float2* __restrict__ spec, float2* __restrict__ Wc, int n_grids, int p, int q,
+                                 int K, int ncombo) {
+  const int FG = K / 32;
+  const long long total = (long long)n_grids * q * ncombo * 64;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int l = int(idx & 63);
+  long long rr = idx >> 6;
+  const int combo = int(rr % ncombo); rr /= ncombo;
+  const int j = int(rr % q);
+  const int g = int(rr / q);
+  const int fg = combo % FG, ig = combo / FG;
+  const int i = 4 * ig + (l & 3), slot = 16 * fg + (l >> 2);
+  float2 v = make_float2(0.f, 0.f);
+  if (i < p) {
+    const long long fs = (long long)p * q;
+    const float2* sg = spec + (long long)g * (K / 2 + 1) * fs;
+    const long long e = (long long)j * p + i;
+    v = slot == 0 ? make_float2(sg[e].x, sg[(long long)(K / 2) * fs + e].x) : sg[(long long)slot * fs + e];
+  }
+  Wc[idx] = v;
+}
+
+// R: filter size r, Q: input channel blocks q, QH: input channel blocks whose spectra are held
+// in LDS at a time (the contraction runs in Q/QH rounds over the same accumulators).  All are
+// compile-time so that the weight operands live in registers.
+// One workgroup = one tile of TH x TW output positions of one image pair.
+template <int K, int NT, int R, int Q, int QH>
+__global__ __launch_bounds__(NT) void conv_fused_kernel(const float2* __restrict__ Wc, const float* __restrict__ x,
+                                                        const float* __restrict__ bias, float* __restrict__ y,
+                                                        int N, int C_out, int H, int W, int Ho, int Wo, int pad,
+                                                        int TH, int TW, int tiles_h, int tiles_w, int ncombo, int relu) {
+  using Sh = ConvFusedShape<K, NT>;
+  constexpr int PT = Sh::PT, PP = Sh::PP, S = Sh::S, FG = Sh::FG, OPROW = Sh::OPROW, NW = Sh::NW, MAXT = Sh::MAXT;
+  constexpr int C_in = Q * K;
+  constexpr int R2 = radix2_of(K), R1 = radix1_of(K);
+  constexpr int NLD = 2 * K * PT / NT;              // x elements per thread and chunk (16)
+  static_assert(Q % QH == 0, "rounds must cover the input channel blocks evenly");
+  extern __shared__ float smem[];
+  float2* z = reinterpret_cast<float2*>(smem);
+  float2* twl = z + K * PP;
+  int* postab = reinterpret_cast<int*>(twl + K);    // input position -> offset in an image plane, or -1
+  float* op = reinterpret_cast<float*>(postab + 256 + 64);
+  float2* zi = reinterpret_cast<float2*>(op);       // inverse tile, reuses the operand buffer
+
+  // the wave index is made explicitly wave-uniform: combo, positions and row addresses derived
+  // from it then live in scalar registers
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int p = C_out / K;
+  int bid = blockIdx.x;
+  const int tw_i = bid % tiles_w; bid /= tiles_w;
+  const int th_i = bid % tiles_h; bid /= tiles_h;
+  const int n0 = 2 * bid;                           // first image of the pair
+  const int h0 = th_i * TH, w0 = tw_i * TW;         // output tile origin
+  // input positions of the tile use a fixed row pitch of 16 (IW <= 16), so that the offset of a
+  // tap (dh, dw) inside the operand buffer is a compile-time constant
+  constexpr int IWP = 16;
+  const int IH = TH + R - 1, IW = TW + R - 1, IPOS = IH * IWP, NPOS = TH * TW;
+  const int cpj = (IPOS + PT - 1) / PT;             // chunks per input channel block
+  const int HW = H * W, HWo = Ho * Wo;
+
+  CIRC_PROBE(0);
+  stage_twiddles<K>(twl, tid, NT);
+  for (int pos = tid; pos < 256; pos += NT) {
+    const int iw = pos % IWP, gh = h0 - pad + pos / IWP, gw = w0 - pad + iw;
+    postab[pos] = (pos < IPOS && iw < IW && gh >= 0 && gh < H && gw >= 0 && gw < W) ? gh * W + gw : -1;
+  }
+
+  // weight operands of this wave's (slot group, row group), one round (R*R*QH values) at a time
+  const int combo = wave % ncombo, fg = combo % FG, ig = combo / FG;
+  float2 a[R * R * QH];
+  auto load_a = [&](int round) {
+#pragma unroll
+    for (int g = 0; g < R * R; ++g)
+#pragma unroll
+      for (int jl = 0; jl < QH; ++jl)
+        a[g * QH + jl] = Wc[((g * Q + round * QH + jl) * ncombo + combo) * 64 + lane];
+  };
+
+  // output positions of this wave and their first input position
+  floatx4 P[MAXT], Qa[MAXT];
+  const int pos_first = wave / ncombo, pos_step = NW / ncombo;
+#pragma unroll
+  for (int tk = 0; tk < MAXT; ++tk) {
+    P[tk] = floatx4{0.f, 0.f, 0.f, 0.f};
+    Qa[tk] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+  // output position -> its first input position (top-left tap), or -1 past the tile
+  int* outtab = postab + 256;
+  for (int pos = tid; pos < 64; pos += NT) outtab[pos] = pos < NPOS ? (pos / TW) * IWP + pos % TW : -1;
+  __syncthreads();   // the tables are ready
+
+  // x of one chunk: column = input position, 2*K (image, channel) values per column
+  const int colc = tid % PT, ht0 = tid / PT;
+  const float* ximg = x + (long long)n0 * C_in * HW;
+  const bool second = n0 + 1 < N;
+  auto load_chunk = [&](int ch, float (&xr)[NLD]) {   // ch = global chunk index over (j, position chunk)
+    const int j = ch / cpj, pos = (ch % cpj) * PT + colc;
+    const int off = pos < 256 ? postab[pos] : -1;
+    const int toff = off + ht0 * HW;                       // per-thread part of the address
+    const float* pj = ximg + (long long)j * K * HW;        // wave-uniform part
+#pragma unroll
+    for (int it = 0; it < NLD; ++it) {
+      constexpr int HT_STEP = NT / PT;                     // ht = it*HT_STEP + ht0, no carry from ht0 into t's multiple
+      const int half = (it * HT_STEP) / K, tc = (it * HT_STEP) % K;
+      const float* pu = pj + (long long)(half * C_in + tc) * HW;
+      xr[it] = (off >= 0 && (half == 0 || second)) ? pu[toff] : 0.f;
+    }
+  };
+  const int nch_total = Q * cpj, nch_round = QH * cpj;
+  float xa[NLD];
+  load_chunk(0, xa);
+
+  // one chunk: registers -> z tile -> two FFT passes -> operand rows
+  auto fft_chunk = [&](int ch, float (&xr)[NLD], float (&xnext)[NLD]) {
+    float* zb = reinterpret_cast<float*>(z) + 2 * (ht0 * PP + colc);
+#pragma unroll
+    for (int it = 0; it < NLD; ++it) {
+      constexpr int HT_STEP = NT / PT;
+      const int half = (it * HT_STEP) / K, tc = (it * HT_STEP) % K;
+      zb[2 * tc * PP + half] = xr[it];
+    }
+    __syncthreads();
+    if (ch + 1 < nch_total) load_chunk(ch + 1, xnext);
+    const int t = tid / PT;
+    fft_lds_pass1<K, false>(z, PP, colc, t, NT / PT, twl);
+    __syncthreads();
+    const int jl = (ch % nch_round) / cpj, pos = (ch % cpj) * PT + colc;
+    float* orow = op + (jl * IPOS + pos) * OPROW;
+    const bool keep = pos < IPOS;
+    fft_lds_pass2<K, false>(z, PP, colc, t, NT / PT, [&](int f, float2 v) {
+      int sl, h;
+      if (f == 0) { sl = 0; h = 0; }
+      else if (f == S) { sl = 0; h = 1; }
+      else if (f < S) { sl = f; h = 0; }
+      else { sl = K - f; h = 1; }
+      if (keep) *reinterpret_cast<float2*>(orow + 4 * sl + 2 * h) = v;
+    });
+    __syncthreads();
+  };
+
+  for (int round = 0; round < Q / QH; ++round) {
+    load_a(round);
+    for (int cl = 0; cl < nch_round; ++cl) fft_chunk(round * nch_round + cl, xa, xa);
+    CIRC_PROBE(1 + 3 * round);
+    // ---- contraction of this round: every wave takes up to MAXT output positions for its combo
+    // Rows of positions outside the image hold the spectrum of zeros, so the taps need no
+    // border test.  Row indices are wave-uniform; only the lane offset is per thread.
+    const float* opw = op + fg * 64 + lane;
+#pragma unroll
+    for (int tk = 0; tk < MAXT; ++tk) {
+      const int ipos0 = __builtin_amdgcn_readfirstlane(outtab[pos_first + tk * pos_step]);
+      if (ipos0 >= 0) {
+        const float* r0 = opw + ipos0 * OPROW;
+#pragma unroll
+        for (int dh = 0; dh < R; ++dh) {
+#pragma unroll
+          for (int dw = 0; dw < R; ++dw) {
+            float bv[QH];
+#pragma unroll
+            for (int jl = 0; jl < QH; ++jl) bv[jl] = (r0 + jl * IPOS * OPROW)[(dh * IWP + dw) * OPROW];
+#pragma unroll
+            for (int jl = 0; jl < QH; ++jl) {
+              const float2 av = a[(dh * R + dw) * QH + jl];
+              P[tk] = __builtin_amdgcn_mfma_f32_4x4x1f32(av.x, bv[jl], P[tk], 0, 0, 0);
+              Qa[tk] = __builtin_amdgcn_mfma_f32_4x4x1f32(av.y, bv[jl], Qa[tk], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+    CIRC_PROBE(2 + 3 * round);
+    __syncthreads();   // every wave is done with the operand rows of this round
+    CIRC_PROBE(3 + 3 * round);
+  }
+  // ---- spectra of the output pairs -> inverse tile (reuses the operand buffer),
+  // column = i*NPOS + position, padded to CP (a power of two) columns for the thread mapping
+  const int NCOLI = p * NPOS, PPI = NCOLI + 1;
+  {
+    const int n = lane & 3, blk = lane >> 2;
+    const int slot = 16 * fg + blk;
+    const int fidx = (n < 2) ? slot : (slot == 0 ? S : K - slot);
+    float* zl = reinterpret_cast<float*>(zi) + 2 * fidx * PPI + (n & 1);   // per-lane part of the address
+    // value = ca*P + cb*Q + cs*swap(Q) with per-lane constants (no divergent branches)
+    const float ca = (slot == 0 && n >= 2) ? 0.f : 1.f;
+    const float cb = (slot == 0 && n >= 2) ? 1.f : 0.f;
+    const float cs = slot == 0 ? 0.f : ((n == 0 || n == 3) ? -1.f : 1.f);
+#pragma unroll
+    for (int tk = 0; tk < MAXT; ++tk) {
+      const int pos = pos_first + tk * pos_step;
+      if (pos < NPOS) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          const float pv = P[tk][m], qv = Qa[tk][m];
+          const float qs = quad_swap_pairs(qv);
+          const int i = 4 * ig + m;
+          if (i < p) zl[2 * (i * NPOS + pos)] = fmaf(cs, qs, fmaf(cb, qv, ca * pv));
+        }
+      }
+    }
+  }
+  __syncthreads();
+  CIRC_PROBE(10);
+  int lgcp = 6;
+  while ((1 << lgcp) < NCOLI) ++lgcp;
+  const int CP = 1 << lgcp;
+  for (int wk = tid; wk < CP * R2; wk += NT) {
+    const int col = wk & (CP - 1);
+    if (col < NCOLI) fft_lds_pass1<K, true>(zi, PPI, col, wk >> lgcp, R2, twl);
+  }
+  __syncthreads();
+  CIRC_PROBE(11);
+  for (int wk = tid; wk < CP * R1; wk += NT) {
+    const int col = wk & (CP - 1);
+    if (col < NCOLI) fft_lds_pass2_inplace<K, true>(zi, PPI, col, wk >> lgcp, R1);
+  }
+  __syncthreads();
+  CIRC_PROBE(12);
+
+  // ---- store: lanes run along the output positions of one channel; (image, channel) is
+  // wave-uniform in every iteration
+  for (int colb = 0; colb < NCOLI; colb += 64) {
+    const int col = colb + lane;
+    const int i = col / NPOS, pos = col % NPOS;
+    const int oh = h0 + pos / TW, ow = w0 + pos % TW;
+    const bool ok = col < NCOLI && oh < Ho && ow < Wo;
+    const int toff = i * K * HWo + oh * Wo + ow;                        // per-thread part (fits 32 bits per image pair)
+    const float* zc = reinterpret_cast<const float*>(zi) + 2 * col;
+    const float* brow = bias ? bias + i * K : nullptr;
+    float* yimg = y + (long long)n0 * C_out * HWo;
+#pragma unroll 4
+    for (int ht = wave; ht < 2 * K; ht += NW) {
+      const int half = ht / K, t = ht % K;
+      if (ok && (half == 0 || second)) {
+        float v = zc[2 * fft_pos<K>(t) * PPI + half];
+        if (brow) v += brow[t];
+        if (relu) v = fmaxf(v, 0.f);
+        (yimg + (long long)(half * C_out + t) * HWo)[toff] = v;
+      }
+    }
+  }
+  CIRC_PROBE(14);
+}
+
+}  // namespace circ

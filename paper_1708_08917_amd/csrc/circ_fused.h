@@ -119,7 +119,9 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
   float2* twl = reinterpret_cast<float2*>(op + PT * OPROW);
   float* red = reinterpret_cast<float*>(twl + K);
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the wave index is made explicitly wave-uniform, so that everything derived from it
+  // (combo, slot group, operand addresses) lives in scalar registers and branches on it are scalar
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // Workgroups go round-robin to the 8 XCDs, each with its own L2 (not kept across
   // launches).  The tile grid (n_it x n_bt) is cut into xa x (8/xa) rectangles, one per XCD,
   // so that the weight tiles and x rows an XCD has to pull into its L2 are as few as possible.
@@ -345,16 +347,19 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
       const int fg = combo / IG, ig = combo % IG;
       const int slot = 16 * fg + blk;
       const int fidx = (n < 2) ? slot : (slot == 0 ? S : K - slot);
+      // value = ca*P + cb*Q + cc*swap(Q) with per-lane constants (no divergent branches):
+      // slot 0: (P, P, Q, Q) by column; other slots: (P - Qs, P + Qs, P + Qs, P - Qs)
+      const float ca = (slot == 0 && n >= 2) ? 0.f : 1.f;
+      const float cb = (slot == 0 && n >= 2) ? 1.f : 0.f;
+      const float cs = slot == 0 ? 0.f : ((n == 0 || n == 3) ? -1.f : 1.f);
+      float* zl = reinterpret_cast<float*>(z) + 2 * (fidx * PPI + 4 * ig * NP) + (n & 1);
 #pragma unroll
       for (int u = 0; u < NP; ++u) {
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
           const float pv = P[0][cc][u][m], qv = Q[0][cc][u][m];
           const float qs = quad_swap_pairs(qv);
-          float val;
-          if (slot == 0) val = (n < 2) ? pv : qv;
-          else val = (n == 0 || n == 3) ? pv - qs : pv + qs;
-          lds_put(z, fidx * PPI + (4 * ig + m) * NP + u, n & 1, val);
+          zl[2 * (m * NP + u)] = fmaf(cs, qs, fmaf(cb, qv, ca * pv));
         }
       }
     }

@@ -123,6 +123,18 @@ def test_fc_backward_shapes(p, q, k, batch):
 @pytest.mark.parametrize("N,p,q,k,H,W,r,pad", [(1, 1, 1, 4, 5, 5, 3, 1), (2, 2, 3, 8, 6, 7, 3, 1), (3, 5, 2, 16, 9, 4, 3, 0),
                                                (2, 1, 2, 64, 7, 7, 1, 0), (1, 2, 2, 32, 8, 8, 5, 2), (2, 4, 4, 64, 14, 14, 3, 1)])
 def test_conv_forward_shapes(N, p, q, k, H, W, r, pad):
+    _conv_case(N, p, q, k, H, W, r, pad)
+
+
+# ---- fused CONV kernel (k = 64, 3x3, q in {1,2,4}, p <= 16): odd image counts, ragged tiles,
+# every padding, every row-group count
+@pytest.mark.parametrize("N,p,q,H,W,pad", [(1, 1, 1, 5, 5, 1), (3, 4, 4, 9, 11, 1), (2, 5, 2, 13, 6, 0), (5, 9, 1, 7, 30, 2),
+                                           (2, 16, 4, 8, 8, 1), (4, 3, 2, 28, 28, 1), (1, 2, 4, 3, 3, 0), (2, 4, 4, 33, 5, 2)])
+def test_conv_forward_fused_shapes(N, p, q, H, W, pad):
+    _conv_case(N, p, q, 64, H, W, 3, pad)
+
+
+def _conv_case(N, p, q, k, H, W, r, pad):
     w = (RNG.standard_normal((r, r, p, q, k)) * np.sqrt(2.0 / (r * r * q * k))).astype(np.float32)
     x = RNG.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32)
     b = (0.1 * RNG.standard_normal(p * k)).astype(np.float32)
