@@ -65,14 +65,43 @@ inline size_t conv_section_elems(int n_grids, int p, int q, int k) {      // in 
   return size_t(n_grids) * q * conv_fused_ncombo(p, q, k, r) * 64;
 }
 
+// Byte offsets of the sections of a spectra blob.  FC (n_grids == 1): unfused forward and
+// backward operands, then the fused / batch<=2 operand orders for the forward pass (p x q grid)
+// and for backward-data, which is the same computation on the transposed, conjugated grid
+// (q x p).  CONV: unfused operands, then the fused CONV order.
+struct BlobLayout {
+  size_t fwd, bwd, fused_fwd, gemv_fwd, fused_bwd, gemv_bwd, conv, total;
+};
+inline BlobLayout blob_layout(int n_grids, int p, int q, int k) {
+  BlobLayout b;
+  const size_t sec = align_up(spectra_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
+  size_t off = 0;
+  b.fwd = off; off += sec;
+  b.bwd = off; off += sec;
+  b.fused_fwd = off; off += align_up(fused_section_elems(n_grids, p, q, k) * sizeof(float4), 256);
+  b.gemv_fwd = off; off += align_up(gemv_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
+  b.fused_bwd = off; off += align_up(fused_section_elems(n_grids, q, p, k) * sizeof(float4), 256);
+  b.gemv_bwd = off; off += align_up(gemv_section_elems(n_grids, q, p, k) * sizeof(float2), 256);
+  b.conv = off; off += align_up(conv_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
+  b.total = off;
+  return b;
+}
+template <class T>
+inline T* blob_at(void* blob, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(blob) + off); }
+template <class T>
+inline const T* blob_at(const void* blob, size_t off) { return reinterpret_cast<const T*>(static_cast<const char*>(blob) + off); }
+
 struct FftPlan { int P, NT; size_t lds; };
 
 // P column pairs per block, NT threads.  Small problems get small tiles so that the
 // launch still covers the chip; the tile must fit comfortably in LDS.
+#ifndef CIRC_FFT_MAXLDS_KB
+#define CIRC_FFT_MAXLDS_KB 40
+#endif
 FftPlan plan_fft(int K, long long nrows) {
   int R2 = radix2_of(K);
   int P = 64;
-  while (P > 8 && fft_tile_lds_bytes(K, P) > 40 * 1024) P >>= 1;
+  while (P > 8 && fft_tile_lds_bytes(K, P) > CIRC_FFT_MAXLDS_KB * 1024) P >>= 1;
   long long pairs = cdiv(nrows, 2);
   while (P > 8 && cdiv(pairs, P) < 512) P >>= 1;
   int TT = R2;
@@ -80,6 +109,7 @@ FftPlan plan_fft(int K, long long nrows) {
   if (TT < 1) TT = 1;
   int NT = P * TT;
   if (NT < 64) NT = 64;
+  if (NT < K / 4) NT = K / 4;   // the row loaders keep one float4 column per thread
   return FftPlan{P, NT, fft_tile_lds_bytes(K, P)};
 }
 
@@ -295,10 +325,7 @@ const char* circ_status_string(circ_status s) {
 size_t circ_spectra_bytes(int n_grids, int p, int q, int k) {
   if (n_grids <= 0 || p <= 0 || q <= 0 || !valid_k(k)) return 0;
   if ((long long)p * q > (1ll << 31) - 1) return 0;
-  return 2 * align_up(spectra_section_elems(n_grids, p, q, k) * sizeof(float2), 256) +
-         align_up(fused_section_elems(n_grids, p, q, k) * sizeof(float4), 256) +
-         align_up(gemv_section_elems(n_grids, p, q, k) * sizeof(float2), 256) +
-         align_up(conv_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
+  return blob_layout(n_grids, p, q, k).total;
 }
 
 circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, int k, void* w_hat, void* stream) {
@@ -308,9 +335,9 @@ circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, i
   size_t wbytes = size_t(n_grids) * p * q * k * sizeof(float);
   if (overlaps(w, wbytes, w_hat, circ_spectra_bytes(n_grids, p, q, k))) return CIRC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const size_t sec = align_up(spectra_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
-  float2* fwd = static_cast<float2*>(w_hat);
-  float2* bwd = reinterpret_cast<float2*>(static_cast<char*>(w_hat) + sec);
+  const BlobLayout bl = blob_layout(n_grids, p, q, k);
+  float2* fwd = blob_at<float2>(w_hat, bl.fwd);
+  float2* bwd = blob_at<float2>(w_hat, bl.bwd);
   const long long rows = (long long)p * q;
   const long long in_g = rows * k, out_g = (long long)spectrum_elems(k, rows);
   const float inv_k = 1.0f / float(k);
@@ -320,24 +347,29 @@ circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, i
   // backward operand: row id = i*q + j, conjugated
   RowMap mb{q, p, (long long)k, (long long)q * k, 0, 1};
   if (launch_rfft(k, false, w, bwd, mb, rows, rows, n_grids, in_g, out_g, inv_k, 1, s) != hipSuccess) return CIRC_EHIP;
-  const size_t nfused = fused_section_elems(n_grids, p, q, k);
-  if (nfused) {
-    float4* wfu = reinterpret_cast<float4*>(static_cast<char*>(w_hat) + 2 * sec);
-    hipLaunchKernelGGL(pack_fused_kernel, dim3((unsigned)cdiv((long long)nfused, 256)), dim3(256), 0, s, fwd, wfu, p, q, k,
-                       fused_igp(p, k), fused_q2p(q, k));
-    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  // The backward section [f][i][j] (conjugated) is exactly the "[f][j'][i']" forward section of the
+  // transposed grid (p' = q output block rows, q' = p input blocks), so the same pack kernels
+  // produce the operands that make backward-data a forward pass.
+  struct { const float2* spec; int pp, qq; size_t fused_off, gemv_off; } dir[2] = {
+      {fwd, p, q, bl.fused_fwd, bl.gemv_fwd}, {bwd, q, p, bl.fused_bwd, bl.gemv_bwd}};
+  for (const auto& d : dir) {
+    const size_t nfused = fused_section_elems(n_grids, d.pp, d.qq, k);
+    if (nfused) {
+      hipLaunchKernelGGL(pack_fused_kernel, dim3((unsigned)cdiv((long long)nfused, 256)), dim3(256), 0, s, d.spec,
+                         blob_at<float4>(w_hat, d.fused_off), d.pp, d.qq, k, fused_igp(d.pp, k), fused_q2p(d.qq, k));
+      if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+    }
+    const size_t ngemv = gemv_section_elems(n_grids, d.pp, d.qq, k);
+    if (ngemv) {
+      hipLaunchKernelGGL(pack_gemv_kernel, dim3((unsigned)cdiv((long long)ngemv, 256)), dim3(256), 0, s, d.spec,
+                         blob_at<float2>(w_hat, d.gemv_off), d.pp, d.qq, k);
+      if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+    }
   }
   const size_t nconv = conv_section_elems(n_grids, p, q, k);
-  if (nconv) {   // FC sections are empty for n_grids > 1, so this one follows section 1 directly
-    float2* wc = reinterpret_cast<float2*>(static_cast<char*>(w_hat) + 2 * sec);
-    hipLaunchKernelGGL(pack_conv_kernel, dim3((unsigned)cdiv((long long)nconv, 256)), dim3(256), 0, s, fwd, wc, n_grids, p,
-                       q, k, int(nconv / (size_t(n_grids) * q * 64)));
-    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
-  }
-  const size_t ngemv = gemv_section_elems(n_grids, p, q, k);
-  if (ngemv) {
-    float2* wg = reinterpret_cast<float2*>(static_cast<char*>(w_hat) + 2 * sec + align_up(nfused * sizeof(float4), 256));
-    hipLaunchKernelGGL(pack_gemv_kernel, dim3((unsigned)cdiv((long long)ngemv, 256)), dim3(256), 0, s, fwd, wg, p, q, k);
+  if (nconv) {
+    hipLaunchKernelGGL(pack_conv_kernel, dim3((unsigned)cdiv((long long)nconv, 256)), dim3(256), 0, s, fwd,
+                       blob_at<float2>(w_hat, bl.conv), n_grids, p, q, k, int(nconv / (size_t(n_grids) * q * 64)));
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
   }
   return CIRC_OK;
@@ -367,17 +399,15 @@ circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias
   if (!aligned16(workspace)) return CIRC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
+  const BlobLayout bl = blob_layout(1, p, q, k);
   if (batch <= 2 && k >= 4) {   // one or two vectors: streaming matrix-vector kernel
-    const size_t sec = align_up(spectra_section_elems(1, p, q, k) * sizeof(float2), 256);
-    const size_t fsec = align_up(fused_section_elems(1, p, q, k) * sizeof(float4), 256);
-    const float2* wg = reinterpret_cast<const float2*>(static_cast<const char*>(w_hat) + 2 * sec + fsec);
+    const float2* wg = blob_at<float2>(w_hat, bl.gemv_fwd);
     if (launch_gemv(k, wg, x, use_bias ? bias : nullptr, y, p, q, batch, (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
       return CIRC_EHIP;
     return CIRC_OK;
   }
   if (use_fused_forward(p, q, k, batch)) {
-    const size_t sec = align_up(spectra_section_elems(1, p, q, k) * sizeof(float2), 256);
-    const float4* wfu = reinterpret_cast<const float4*>(static_cast<const char*>(w_hat) + 2 * sec);
+    const float4* wfu = blob_at<float4>(w_hat, bl.fused_fwd);
     if (launch_fused(k, wfu, x, use_bias ? bias : nullptr, y, p, q, batch, (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) !=
         hipSuccess)
       return CIRC_EHIP;
@@ -425,11 +455,18 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
   float2* bufx = static_cast<float2*>(workspace);
   float2* bufy = reinterpret_cast<float2*>(static_cast<char*>(workspace) + xa);
   float2* bufw = reinterpret_cast<float2*>(static_cast<char*>(workspace) + xa + ya);
-  const size_t sec = align_up(spectra_section_elems(1, p, q, k) * sizeof(float2), 256);
-  const float2* wb = reinterpret_cast<const float2*>(static_cast<const char*>(w_hat) + sec);
+  const BlobLayout bl = blob_layout(1, p, q, k);
+  const float2* wb = blob_at<float2>(w_hat, bl.bwd);
   const long long xrows = (long long)q * batch, yrows = (long long)p * batch;
 
-  if (dx) {
+  // Backward-data is a forward pass on the transposed, conjugated grid (q output block rows,
+  // p input blocks, no epilogue): the small-problem kernels serve it from their own sections.
+  if (dx && batch <= 2 && k >= 4) {
+    if (launch_gemv(k, blob_at<float2>(w_hat, bl.gemv_bwd), dy, nullptr, dx, q, p, batch, 0, s) != hipSuccess) return CIRC_EHIP;
+  } else if (dx && use_fused_forward(q, p, k, batch)) {
+    if (launch_fused(k, blob_at<float4>(w_hat, bl.fused_bwd), dy, nullptr, dx, q, p, batch, 0, s) != hipSuccess)
+      return CIRC_EHIP;
+  } else if (dx) {
     // dY^[f][i][b];  dX^[f][j][b] = sum_i conj(W^)[f][i][j] dY^[f][i][b]
     RowMap mdy{batch, p, (long long)p * k, (long long)k, 0, 1};
     if (launch_rfft(k, false, dy, bufy, mdy, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
@@ -549,8 +586,7 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
   const long long HW = (long long)H * W, HWo = (long long)Ho * Wo;
   const int ncombo = conv_fused_ncombo(p, q, k, r);
   if (ncombo > 0 && (long long)cdiv(N, 2) * Ho * Wo < (1ll << 31)) {
-    const size_t sec = align_up(spectra_section_elems(r * r, p, q, k) * sizeof(float2), 256);
-    const float2* wc = reinterpret_cast<const float2*>(static_cast<const char*>(w_hat) + 2 * sec);
+    const float2* wc = blob_at<float2>(w_hat, blob_layout(r * r, p, q, k).conv);
     const float* bp = use_bias ? bias : nullptr;
     const int relu = (epilogue & CIRC_EPI_RELU) ? 1 : 0;
     hipError_t e = q == 1 ? launch_conv_fused_q<1>(wc, x, bp, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)

@@ -160,12 +160,12 @@ struct RowMap {
   long long s0, s1, s2, es;
 };
 
+// Row ids fit 32 bits (checked on the host), so the decomposition uses 32-bit divisions.
 __device__ __forceinline__ long long row_base(const RowMap& m, long long rid) {
-  long long c = rid % m.n0;
-  long long ab = rid / m.n0;
-  long long b = ab % m.n1;
-  long long a = ab / m.n1;
-  return c * m.s0 + b * m.s1 + a * m.s2;
+  const unsigned r = (unsigned)rid, n0 = (unsigned)m.n0, n1 = (unsigned)m.n1;
+  const unsigned ab = r / n0, c = r - ab * n0;
+  const unsigned a = ab / n1, b = ab - a * n1;
+  return (long long)c * m.s0 + (long long)b * m.s1 + (long long)a * m.s2;
 }
 
 }  // namespace circ

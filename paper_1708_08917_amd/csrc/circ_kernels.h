@@ -83,18 +83,21 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
       lds_put(L.z, n * PP + (row >> 1), row & 1, v);
     }
   } else if constexpr (K >= 4) {
-    // rows are contiguous (element stride 1) and 16-byte aligned: vector loads along the row
+    // rows are contiguous (element stride 1) and 16-byte aligned: vector loads along the row.
+    // NT is a multiple of K/4 (both powers of two, NT >= K/4): a thread keeps its position n in
+    // the row and only its row index advances, by NT/(K/4) per step.
+    const int n = 4 * (tid % (K / 4)), rstep = NT / (K / 4);
+    float* zcol = reinterpret_cast<float*>(L.z) + 2 * n * PP;
 #pragma unroll 4
-    for (int idx = tid; idx < 2 * P * (K / 4); idx += NT) {
-      int row = idx / (K / 4), n = 4 * (idx % (K / 4));
+    for (int row = tid / (K / 4); row < 2 * P; row += rstep) {
       long long b = L.rbase[row];
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n);
-      int c = row >> 1, h = row & 1;
-      lds_put(L.z, (n + 0) * PP + c, h, v.x);
-      lds_put(L.z, (n + 1) * PP + c, h, v.y);
-      lds_put(L.z, (n + 2) * PP + c, h, v.z);
-      lds_put(L.z, (n + 3) * PP + c, h, v.w);
+      float* zd = zcol + 2 * (row >> 1) + (row & 1);
+      zd[0] = v.x;
+      zd[2 * PP] = v.y;
+      zd[4 * PP] = v.z;
+      zd[6 * PP] = v.w;
     }
   } else {
     for (int idx = tid; idx < 2 * P * K; idx += NT) {
@@ -114,18 +117,20 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
 
   // separate the two real rows of each column and store bins 0..K/2
   constexpr int NF = K / 2 + 1;
-  const float h = 0.5f * scale;
+  const float h = 0.5f * scale, hc = conj ? -h : h;
+  {
+    // a thread keeps its column pair; its bin advances by NT/P per step
+    const int pr = tid & (P - 1), fstep = NT >> lgP;
+    const long long rid = t0 + 2 * pr;
+    const bool ok0 = rid < nrows, ok1 = rid + 1 < nrows;
+    float2* o = out + (long long)(tid >> lgP) * out_fstride + rid;
+    const long long ostep = (long long)fstep * out_fstride;
 #pragma unroll 2
-  for (int idx = tid; idx < NF * P; idx += NT) {
-    int pr = idx & (P - 1), f = idx >> lgP;
-    float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>((K - f) % K) * PP + pr];
-    float2 xa = make_float2(h * (u.x + w.x), h * (u.y - w.y));
-    float2 xb = make_float2(h * (u.y + w.y), h * (w.x - u.x));
-    if (conj) { xa.y = -xa.y; xb.y = -xb.y; }
-    long long rid = t0 + 2 * pr;
-    float2* o = out + f * out_fstride + rid;
-    if (rid < nrows) o[0] = xa;
-    if (rid + 1 < nrows) o[1] = xb;
+    for (int f = tid >> lgP; f < NF; f += fstep, o += ostep) {
+      float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>((K - f) & (K - 1)) * PP + pr];
+      if (ok0) o[0] = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
+      if (ok1) o[1] = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
+    }
   }
 }
 
@@ -146,25 +151,30 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
   stage_twiddles<K>(L.tw, tid, NT);
   // build Z = Ya + i*Yb on all K bins from the two half spectra (Hermitian symmetry)
   constexpr int NF = K / 2 + 1;
+  {
+    // a thread keeps its column pair; its bin advances by NT/P per step
+    const int pr = tid & (P - 1), fstep = NT >> lgP;
+    const long long rid = t0 + 2 * pr;
+    const bool ok0 = rid < nrows, ok1 = rid + 1 < nrows;
+    const float2* s = in + (long long)(tid >> lgP) * in_fstride + rid;
+    const long long sstep = (long long)fstep * in_fstride;
 #pragma unroll 4
-  for (int idx = tid; idx < NF * P; idx += NT) {
-    int pr = idx & (P - 1), f = idx >> lgP;
-    long long rid = t0 + 2 * pr;
-    const float2* s = in + f * in_fstride + rid;
-    float2 ya = rid < nrows ? s[0] : make_float2(0.f, 0.f);
-    float2 yb = rid + 1 < nrows ? s[1] : make_float2(0.f, 0.f);
-    if (f == 0 || 2 * f == K) {            // DC and Nyquist bins of a real signal are real
-      L.z[f * PP + pr] = make_float2(ya.x, yb.x);
-    } else {
-      L.z[f * PP + pr] = make_float2(ya.x - yb.y, ya.y + yb.x);
-      L.z[(K - f) * PP + pr] = make_float2(ya.x + yb.y, yb.x - ya.y);
+    for (int f = tid >> lgP; f < NF; f += fstep, s += sstep) {
+      float2 ya = ok0 ? s[0] : make_float2(0.f, 0.f);
+      float2 yb = ok1 ? s[1] : make_float2(0.f, 0.f);
+      if (f == 0 || 2 * f == K) {            // DC and Nyquist bins of a real signal are real
+        L.z[f * PP + pr] = make_float2(ya.x, yb.x);
+      } else {
+        L.z[f * PP + pr] = make_float2(ya.x - yb.y, ya.y + yb.x);
+        L.z[(K - f) * PP + pr] = make_float2(ya.x + yb.y, yb.x - ya.y);
+      }
     }
   }
   for (int r = tid; r < 2 * P; r += NT) {
     long long rid = t0 + r;
     bool ok = rid < nrows;
     L.rbase[r] = ok ? row_base(map, rid) : -1;
-    L.rblk[r] = ok ? int(rid / bias_div) : 0;
+    L.rblk[r] = ok ? int((unsigned)rid / (unsigned)bias_div) : 0;   // both fit 32 bits (host check)
   }
   __syncthreads();
 
@@ -174,17 +184,40 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
   fft_lds_pass2_inplace<K, true>(L.z, PP, col, t, TT);
   __syncthreads();
 
+  if constexpr (!ROWS_FAST && K >= 4) {
+    // contiguous rows: float4 stores; a thread keeps its position n in the row, its row index
+    // advances by NT/(K/4) per step (NT is a multiple of K/4)
+    const int n = 4 * (tid % (K / 4)), rstep = NT / (K / 4);
+    const float* z0 = reinterpret_cast<const float*>(L.z) + 2 * fft_pos<K>(n + 0) * PP;
+    const float* z1 = reinterpret_cast<const float*>(L.z) + 2 * fft_pos<K>(n + 1) * PP;
+    const float* z2 = reinterpret_cast<const float*>(L.z) + 2 * fft_pos<K>(n + 2) * PP;
+    const float* z3 = reinterpret_cast<const float*>(L.z) + 2 * fft_pos<K>(n + 3) * PP;
 #pragma unroll 4
-  for (int idx = tid; idx < 2 * P * K; idx += NT) {
-    int row, n;
-    if (ROWS_FAST) { row = idx & (2 * P - 1); n = idx >> (lgP + 1); }
-    else { row = idx / K; n = idx % K; }
-    long long b = L.rbase[row];
-    if (b < 0) continue;
-    float v = lds_get(L.z, fft_pos<K>(n) * PP + (row >> 1), row & 1) * scale;
-    if (bias) v += bias[(long long)L.rblk[row] * K + n];
-    if (relu) v = fmaxf(v, 0.f);
-    out[b + n * map.es] = v;
+    for (int row = tid / (K / 4); row < 2 * P; row += rstep) {
+      long long b = L.rbase[row];
+      if (b < 0) continue;
+      const int c = 2 * (row >> 1) + (row & 1);
+      float4 v = make_float4(z0[c] * scale, z1[c] * scale, z2[c] * scale, z3[c] * scale);
+      if (bias) {
+        const float4 bb = *reinterpret_cast<const float4*>(bias + (long long)L.rblk[row] * K + n);
+        v.x += bb.x; v.y += bb.y; v.z += bb.z; v.w += bb.w;
+      }
+      if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+      *reinterpret_cast<float4*>(out + b + n) = v;
+    }
+  } else {
+#pragma unroll 4
+    for (int idx = tid; idx < 2 * P * K; idx += NT) {
+      int row, n;
+      if (ROWS_FAST) { row = idx & (2 * P - 1); n = idx >> (lgP + 1); }
+      else { row = idx / K; n = idx % K; }
+      long long b = L.rbase[row];
+      if (b < 0) continue;
+      float v = lds_get(L.z, fft_pos<K>(n) * PP + (row >> 1), row & 1) * scale;
+      if (bias) v += bias[(long long)L.rblk[row] * K + n];
+      if (relu) v = fmaxf(v, 0.f);
+      out[b + n * map.es] = v;
+    }
   }
 }
 

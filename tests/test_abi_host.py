@@ -37,11 +37,13 @@ def test_status_strings():
 
 
 def test_spectra_bytes():
-    # forward-operand and backward-operand sections, each (k/2+1) complex bins per block, 256 B aligned
-    # third section (FC, k >= 32): the same spectra packed to k/2 slots in the fused kernel's operand order
-    # fourth section (FC, k >= 4): the same k/2 slots in [i][j][slot] order for the batch <= 2 kernel
-    assert B.circ_spectra_bytes(1, 64, 64, 64) == 2 * 64 * 64 * 33 * 8 + 2 * 64 * 64 * 32 * 8
-    assert B.circ_spectra_bytes(9, 4, 4, 64) == 2 * ((9 * 16 * 33 * 8 + 255) // 256 * 256)
+    # FC blob: unfused forward + backward operands ((k/2+1) bins per block), then for each of the two
+    # directions (forward grid p x q, backward-data grid q x p) the k/2-slot operands of the fused
+    # kernel (k >= 32) and of the batch <= 2 kernel (k >= 4); every section 256 B aligned
+    assert B.circ_spectra_bytes(1, 64, 64, 64) == 2 * 64 * 64 * 33 * 8 + 4 * 64 * 64 * 32 * 8
+    assert B.circ_spectra_bytes(1, 3, 5, 2) == 2 * 256          # k = 2: only the two unfused sections
+    # CONV blob (9 grids of 4 x 4 blocks, k = 64): unfused sections + fused CONV operands (9*4*2*64 float2)
+    assert B.circ_spectra_bytes(9, 4, 4, 64) == 2 * ((9 * 16 * 33 * 8 + 255) // 256 * 256) + 9 * 4 * 2 * 64 * 8
     for bad in [(0, 1, 1, 8), (1, 0, 1, 8), (1, 1, 0, 8), (1, 1, 1, 3), (1, 1, 1, 1), (1, 1, 1, 1024), (1, 1, 1, 0)]:
         assert B.circ_spectra_bytes(*bad) == 0
 

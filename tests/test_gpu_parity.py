@@ -104,8 +104,11 @@ def test_deterministic():
 
 
 # ---- backward ------------------------------------------------------------------------------
+# backward-data runs as a forward pass on the transposed grid: batch <= 2 -> streaming kernel,
+# 32 <= k <= 256 and small -> fused kernel (one or two packed pairs per workgroup), else unfused
 @pytest.mark.parametrize("p,q,k,batch", [(1, 1, 8, 1), (3, 5, 16, 7), (5, 3, 64, 33), (2, 2, 256, 10), (33, 34, 4, 70),
-                                         (4, 6, 128, 67), (2, 3, 512, 5)])
+                                         (4, 6, 128, 67), (2, 3, 512, 5), (7, 9, 32, 2), (17, 64, 64, 130), (3, 70, 64, 5),
+                                         (64, 64, 64, 64)])
 def test_fc_backward_shapes(p, q, k, batch):
     w, x, _ = rand_fc(p, q, k, batch, bias=False)
     dy = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
