@@ -131,15 +131,15 @@ hipError_t launch_rfft_k(bool rows_fast, const float* in, float2* out, const Row
 template <int K>
 hipError_t launch_irfft_k(bool rows_fast, const float2* in, float* out, const RowMap& map, long long nrows,
                           long long in_fstride, float scale, const float* bias, long long bias_div, int relu,
-                          hipStream_t s) {
+                          int nparts, long long part_stride, hipStream_t s) {
   FftPlan pl = plan_fft(K, nrows);
   dim3 grid((unsigned)cdiv(nrows, 2 * pl.P));
   if (rows_fast)
     hipLaunchKernelGGL((irfft_kernel<K, true>), grid, dim3(pl.NT), pl.lds, s, in, out, map, nrows, in_fstride,
-                       pl.P, scale, bias, bias_div, relu);
+                       pl.P, scale, bias, bias_div, relu, nparts, part_stride);
   else
     hipLaunchKernelGGL((irfft_kernel<K, false>), grid, dim3(pl.NT), pl.lds, s, in, out, map, nrows, in_fstride,
-                       pl.P, scale, bias, bias_div, relu);
+                       pl.P, scale, bias, bias_div, relu, nparts, part_stride);
   return hipGetLastError();
 }
 
@@ -167,25 +167,37 @@ hipError_t launch_rfft(int k, bool rows_fast, const float* in, float2* out, cons
 
 hipError_t launch_irfft(int k, bool rows_fast, const float2* in, float* out, const RowMap& map, long long nrows,
                         long long in_fstride, float scale, const float* bias, long long bias_div, int relu,
-                        hipStream_t s) {
-#define CALL(KK) launch_irfft_k<KK>(rows_fast, in, out, map, nrows, in_fstride, scale, bias, bias_div, relu, s)
+                        hipStream_t s, int nparts = 1, long long part_stride = 0) {
+#define CALL(KK) launch_irfft_k<KK>(rows_fast, in, out, map, nrows, in_fstride, scale, bias, bias_div, relu, nparts, part_stride, s)
   CIRC_DISPATCH_K(k, CALL)
 #undef CALL
 }
 
-// C[f][m][n] = sum_kd A[f][kd][m] * (conj?)B[f][kd][n] for f in [0, NF)
+// Number of k slices for a GEMM with few output tiles and a long reduction (backward-weights):
+// enough slices to put about two waves of 32x32 tiles on every SIMD, each at least 64 deep.
+inline int cgemm_ksplit(int NF, int M, int N, int Kd) {
+  const long long tiles = (long long)NF * cdiv(M, 32) * cdiv(N, 32);
+  int ks = 1;
+  while (ks < 16 && tiles * ks < 2048 && Kd / (ks * 2) >= 64) ks *= 2;
+  return ks;
+}
+
+// C[f][m][n] = sum_kd A[f][kd][m] * (conj?)B[f][kd][n] for f in [0, NF); with ksplit > 1 slice s
+// writes its partial sums to C + s*part_stride.
 hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, bool conj_b,
-                        hipStream_t s) {
+                        hipStream_t s, int ksplit = 1, long long part_stride = 0) {
   long long sA = (long long)Kd * M, sB = (long long)Kd * N, sC = (long long)M * N;
-  bool big = (long long)NF * cdiv(M, 32) * cdiv(N, 32) >= 1024;
+  bool big = (long long)NF * cdiv(M, 32) * cdiv(N, 32) * ksplit >= 1024;
   int tile = big ? 32 : 16;
-  dim3 grid((unsigned)cdiv(N, tile), (unsigned)cdiv(M, tile), (unsigned)NF);
+  const int ntn = (int)cdiv(N, tile);
+  const int kchunk = (int)(cdiv(cdiv(Kd, ksplit), 32) * 32);   // whole operand groups per slice
+  dim3 grid((unsigned)(ntn * ksplit), (unsigned)cdiv(M, tile), (unsigned)NF);
   if (big) {
-    if (conj_b) hipLaunchKernelGGL((cgemm_kernel<32, true>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC);
-    else hipLaunchKernelGGL((cgemm_kernel<32, false>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC);
+    if (conj_b) hipLaunchKernelGGL((cgemm_kernel<32, true>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC, ntn, kchunk, part_stride);
+    else hipLaunchKernelGGL((cgemm_kernel<32, false>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC, ntn, kchunk, part_stride);
   } else {
-    if (conj_b) hipLaunchKernelGGL((cgemm_kernel<16, true>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC);
-    else hipLaunchKernelGGL((cgemm_kernel<16, false>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC);
+    if (conj_b) hipLaunchKernelGGL((cgemm_kernel<16, true>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC, ntn, kchunk, part_stride);
+    else hipLaunchKernelGGL((cgemm_kernel<16, false>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC, ntn, kchunk, part_stride);
   }
   return hipGetLastError();
 }
@@ -381,7 +393,7 @@ size_t circ_fc_workspace_bytes(int p, int q, int k, int batch, int backward) {
   size_t ya = align_up(spectrum_elems(k, (long long)p * batch) * sizeof(float2), 256);
   if (!backward) return xa + ya;
   size_t wa = align_up(spectrum_elems(k, (long long)p * q) * sizeof(float2), 256);
-  return xa + ya + wa;
+  return xa + ya + wa * cgemm_ksplit(k / 2 + 1, p, q, batch);   // one dW^ buffer per k slice
 }
 
 circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias, float* y, int p, int q, int k,
@@ -480,10 +492,13 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
     if (launch_rfft(k, false, dy, bufy, mdy, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
     RowMap mx{q, batch, (long long)k, (long long)q * k, 0, 1};
     if (launch_rfft(k, false, x, bufx, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
-    if (launch_cgemm(bufy, bufx, bufw, NF, p, q, batch, true, s) != hipSuccess) return CIRC_EHIP;
+    // the reduction over the batch is cut into slices; the IFFT adds the partial spectra in order
+    const int ksplit = cgemm_ksplit(NF, p, q, batch);
+    const long long wpart = (long long)(align_up(spectrum_elems(k, (long long)p * q) * sizeof(float2), 256) / sizeof(float2));
+    if (launch_cgemm(bufy, bufx, bufw, NF, p, q, batch, true, s, ksplit, wpart) != hipSuccess) return CIRC_EHIP;
     const long long wrows = (long long)p * q;
     RowMap mw{q, p, (long long)k, (long long)q * k, 0, 1};
-    if (launch_irfft(k, false, bufw, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s) != hipSuccess)
+    if (launch_irfft(k, false, bufw, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, ksplit, wpart) != hipSuccess)
       return CIRC_EHIP;
   }
   return CIRC_OK;

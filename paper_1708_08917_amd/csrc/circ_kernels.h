@@ -137,10 +137,13 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
 // -------------------------------------------------------------------------------------
 // Inverse real FFT of rows with epilogue:  out_row[n] = psi(scale * z[n] + bias[blk*K + n]),
 // blk = rid / bias_div (the output block row / channel block of the row).
+// The spectrum may come as `nparts` partial sums (split-K GEMM), `part_stride` elements apart;
+// they are added in index order, so the result does not depend on scheduling.
 template <int K, bool ROWS_FAST>
 __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ out, RowMap map,
                              long long nrows, long long in_fstride, int P, float scale,
-                             const float* __restrict__ bias, long long bias_div, int relu) {
+                             const float* __restrict__ bias, long long bias_div, int relu,
+                             int nparts, long long part_stride) {
   extern __shared__ float smem[];
   const int PP = P + 1;
   const int lgP = __ffs(P) - 1;
@@ -162,6 +165,11 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
     for (int f = tid >> lgP; f < NF; f += fstep, s += sstep) {
       float2 ya = ok0 ? s[0] : make_float2(0.f, 0.f);
       float2 yb = ok1 ? s[1] : make_float2(0.f, 0.f);
+      for (int part = 1; part < nparts; ++part) {
+        const float2* sp = s + part * part_stride;
+        if (ok0) { ya.x += sp[0].x; ya.y += sp[0].y; }
+        if (ok1) { yb.x += sp[1].x; yb.y += sp[1].y; }
+      }
       if (f == 0 || 2 * f == K) {            // DC and Nyquist bins of a real signal are real
         L.z[f * PP + pr] = make_float2(ya.x, yb.x);
       } else {
@@ -228,20 +236,25 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
 // contiguous run per k.  A complex product is four real MFMA accumulations.
 // TILE = 32 uses v_mfma_f32_32x32x2_f32, TILE = 16 uses v_mfma_f32_16x16x4_f32.
 // Operand loads run one group of U k-steps ahead of the matrix instructions.
+// Split-K: blockIdx.x = ks*ntn + (tile along n); slice ks reduces k in [ks*kchunk, (ks+1)*kchunk)
+// and writes its partial sums to C + ks*part_stride (summed later in a fixed order).
 template <int TILE, bool CONJ_B>
 __global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
                                                    const float2* __restrict__ B,
                                                    float2* __restrict__ C, int M, int N, int Kd,
-                                                   long long sA, long long sB, long long sC) {
+                                                   long long sA, long long sB, long long sC,
+                                                   int ntn, int kchunk, long long part_stride) {
   constexpr int KS = 64 / TILE;           // k values per MFMA: 2 or 4
   constexpr int NACC = TILE * TILE / 64;  // accumulator registers per lane: 16 or 4
   constexpr int U = 8;                    // k-steps per group
   typedef float accv __attribute__((ext_vector_type(NACC)));
   const int lane = threadIdx.x;
-  const int f = blockIdx.z, m0 = blockIdx.y * TILE, n0 = blockIdx.x * TILE;
+  const int ks = blockIdx.x / ntn;
+  const int f = blockIdx.z, m0 = blockIdx.y * TILE, n0 = (blockIdx.x - ks * ntn) * TILE;
+  const int kbeg = ks * kchunk, kend = min(Kd, kbeg + kchunk);
   A += f * sA;
   B += f * sB;
-  C += f * sC;
+  C += f * sC + ks * part_stride;
   const int kk = lane / TILE, mm = lane % TILE;
   const int am = min(m0 + mm, M - 1);
   const int bn = min(n0 + mm, N - 1);
@@ -254,17 +267,17 @@ __global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       int kidx = k0 + u * KS + kk;
-      int kc = min(kidx, Kd - 1);
+      int kc = min(kidx, kend - 1);
       float2 va = A[(long long)kc * M + am];
       float2 vb = B[(long long)kc * N + bn];
-      if (kidx >= Kd) { va = make_float2(0.f, 0.f); vb = make_float2(0.f, 0.f); }
+      if (kidx >= kend) { va = make_float2(0.f, 0.f); vb = make_float2(0.f, 0.f); }
       ga[u] = va;
       gb[u] = vb;
     }
   };
-  load_group(0, a, b);
-  for (int k0 = 0; k0 < Kd; k0 += U * KS) {
-    if (k0 + U * KS < Kd) load_group(k0 + U * KS, an, bn2);
+  load_group(kbeg, a, b);
+  for (int k0 = kbeg; k0 < kend; k0 += U * KS) {
+    if (k0 + U * KS < kend) load_group(k0 + U * KS, an, bn2);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       // (ar + i ai)(br + i bi) = (ar br - ai bi) + i (ar bi + ai br); conj(b): bi -> -bi
