@@ -243,6 +243,9 @@ inline int fused_np(int p, int k, int batch) {
   return (k >= 64 && tiles2 >= 256) ? 2 : 1;
 }
 
+#ifndef CIRC_NT128
+#define CIRC_NT128 512
+#endif
 hipError_t launch_fused(int k, const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
                         int relu, hipStream_t s) {
   const int np = fused_np(p, k, batch);
@@ -250,8 +253,8 @@ hipError_t launch_fused(int k, const float4* wf, const float* x, const float* bi
     case 32: return launch_fused_t<32, 16, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
     case 64: return np == 2 ? launch_fused_t<64, 8, 2, 512>(wf, x, bias, y, p, q, batch, relu, s)
                             : launch_fused_t<64, 8, 1, 512>(wf, x, bias, y, p, q, batch, relu, s);
-    case 128: return np == 2 ? launch_fused_t<128, 8, 2, 256>(wf, x, bias, y, p, q, batch, relu, s)
-                             : launch_fused_t<128, 8, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
+    case 128: return np == 2 ? launch_fused_t<128, 8, 2, CIRC_NT128>(wf, x, bias, y, p, q, batch, relu, s)
+                             : launch_fused_t<128, 8, 1, CIRC_NT128>(wf, x, bias, y, p, q, batch, relu, s);
     case 256: return np == 2 ? launch_fused_t<256, 8, 2, 256>(wf, x, bias, y, p, q, batch, relu, s)
                              : launch_fused_t<256, 8, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
     default: return hipErrorInvalidValue;

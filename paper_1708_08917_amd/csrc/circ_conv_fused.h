@@ -250,7 +250,7 @@ __global__ __launch_bounds__(NT) void conv_fused_kernel(const float2* __restrict
     }
   }
   __syncthreads();
-  CIRC_PROBE(10);
+  CIRC_PROBE(58);
   int lgcp = 6;
   while ((1 << lgcp) < NCOLI) ++lgcp;
   const int CP = 1 << lgcp;
@@ -259,13 +259,13 @@ __global__ __launch_bounds__(NT) void conv_fused_kernel(const float2* __restrict
     if (col < NCOLI) fft_lds_pass1<K, true>(zi, PPI, col, wk >> lgcp, R2, twl);
   }
   __syncthreads();
-  CIRC_PROBE(11);
+  CIRC_PROBE(59);
   for (int wk = tid; wk < CP * R1; wk += NT) {
     const int col = wk & (CP - 1);
     if (col < NCOLI) fft_lds_pass2_inplace<K, true>(zi, PPI, col, wk >> lgcp, R1);
   }
   __syncthreads();
-  CIRC_PROBE(12);
+  CIRC_PROBE(60);
 
   // ---- store: lanes run along the output positions of one channel; (image, channel) is
   // wave-uniform in every iteration
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(NT) void conv_fused_kernel(const float2* __restrict
       }
     }
   }
-  CIRC_PROBE(14);
+  CIRC_PROBE(62);
 }
 
 }  // namespace circ

@@ -24,6 +24,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "circ_fft.h"
 #include "circ_kernels.h"
 
@@ -151,28 +153,27 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
   // --- global loads: 4 float4 of x per thread and JW/2 weight operands per combo, per chunk.
   // Addresses are a wave-uniform base plus a 32-bit per-lane offset fixed for the whole
   // kernel, so that issuing a load costs no vector arithmetic.
+  // Rows past the batch and input blocks past q are clamped to the last valid one instead of
+  // being skipped (their products meet zero weights or are never stored), so that the loads
+  // are unconditional and the number of loads in flight is known at compile time.
   float4 xr[4];
   unsigned xoff[4];
-  bool xrow_ok[4];
   int xjj[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int flat = e * NT + tid;
     const int row = flat / (K / 4), n4 = flat % (K / 4);
     const int cl = row >> 1, half = row & 1;
-    const int jj = cl / NP, brow = 2 * (cl % NP) + half;
+    const int jj = cl / NP, brow = min(2 * (cl % NP) + half, B - 1 - b0);
     xjj[e] = jj;
-    xrow_ok[e] = b0 + brow < B;
-    xoff[e] = unsigned(brow) * unsigned(ldx) + unsigned(jj * K + 4 * n4);
+    xoff[e] = unsigned(brow) * unsigned(ldx) + unsigned(4 * n4);
   }
   const float* xtile = x + (long long)b0 * ldx;
   auto load_x = [&](int c) {
-    const float* xc = xtile + (long long)c * JC * K;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (xrow_ok[e] && c * JC + xjj[e] < q) v = *reinterpret_cast<const float4*>(xc + xoff[e]);
-      xr[e] = v;
+      const unsigned j = unsigned(min(c * JC + xjj[e], q - 1));
+      xr[e] = *reinterpret_cast<const float4*>(xtile + (xoff[e] + j * unsigned(K)));
     }
   };
   auto store_x = [&]() {
@@ -197,13 +198,18 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
     aoff[cc] = unsigned(((combo % IG) * q2p) * FG + combo / IG) * 64u + unsigned(lane);
   }
   float4 a_even[CPW][JW / 2], a_odd[CPW][JW / 2];
-  auto load_a = [&](int c, float4 (&a)[CPW][JW / 2]) {
+  // [lo, hi) selects a part of the chunk's operands: a workgroup can only push requests into
+  // the memory pipeline at a bounded rate, so the loads of the next chunk are issued in
+  // pieces between the phases of the current one instead of stalling one phase
+  auto load_a = [&](int c, float4 (&a)[CPW][JW / 2], int lo, int hi) {
     const float4* wc = wtile + (long long)c * (JC / 2) * FG * 64;
 #pragma unroll
     for (int jh = 0; jh < JW / 2; ++jh)
 #pragma unroll
-      for (int cc = 0; cc < CPW; ++cc) a[cc][jh] = wc[(long long)jh * FG * 64 + aoff[cc]];
+      for (int cc = 0; cc < CPW; ++cc)
+        if (jh >= lo && jh < hi) a[cc][jh] = wc[(long long)jh * FG * 64 + aoff[cc]];
   };
+  constexpr int AH = JW / 2, AH1 = (AH + 2) / 3, AH2 = (2 * AH + 2) / 3;
 
   CIRC_PROBE(0);
   // memory returns loads in issue order: the twiddles go first because they are needed first,
@@ -215,7 +221,7 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
     tw_stage[s] = make_float2(kTw.c[m * (kTwN / K)], kTw.s[m * (kTwN / K)]);
   }
   load_x(0);
-  load_a(0, a_even);
+  load_a(0, a_even, 0, AH);
 #pragma unroll
   for (int s = 0; s < (K + NT - 1) / NT; ++s)
     if (s * NT + tid < K) twl[s * NT + tid] = tw_stage[s];
@@ -236,17 +242,20 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
 
   // one chunk of JC input blocks: FFT of its 2*PT rows, then the contraction with `a_use`;
   // meanwhile the loads of the next chunk (x into xr, weights into `a_pref`) are in flight.
-  auto chunk = [&](int c, float4 (&a_use)[CPW][JW / 2], float4 (&a_pref)[CPW][JW / 2]) {
+  // `more` (a compile-time tag): another chunk follows, so its loads are issued here.
+  auto chunk = [&](int c, float4 (&a_use)[CPW][JW / 2], float4 (&a_pref)[CPW][JW / 2], auto more_tag) {
+    constexpr bool more = decltype(more_tag)::value;
     store_x();
     __syncthreads();
     CIRC_PROBE(1 + 4 * c);
-    if (c + 1 < nchunks) {
+    if constexpr (more) {
       load_x(c + 1);
-      load_a(c + 1, a_pref);
+      load_a(c + 1, a_pref, 0, AH1);
     }
     fft_lds_pass1<K, false>(z, PP, col, t, TT, twl);
     __syncthreads();
     CIRC_PROBE(2 + 4 * c);
+    if constexpr (more) load_a(c + 1, a_pref, AH1, AH2);
     // pass 2 writes the spectrum of column `col` straight into MFMA operand order
     fft_lds_pass2<K, false>(z, PP, col, t, TT, [&](int f, float2 v) {
       int slot, h;
@@ -258,6 +267,7 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
     });
     __syncthreads();
     CIRC_PROBE(3 + 4 * c);
+    if constexpr (more) load_a(c + 1, a_pref, AH2, AH);
     // operand rows come from LDS one batch ahead of the matrix instructions that use them
     const float* opw = op + (js * JW * NP) * OPROW + lane;
     float bvv[2][JB][NP][NFW];
@@ -292,9 +302,22 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
     }
     CIRC_PROBE(4 + 4 * c);
   };
-  for (int c = 0; c < nchunks; c += 2) {
-    chunk(c, a_even, a_odd);
-    if (c + 1 < nchunks) chunk(c + 1, a_odd, a_even);
+  // steady state without conditionals around the loads (the compiler then waits for exactly the
+  // operands a phase needs, not for everything in flight); the last one or two chunks are peeled
+  {
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
+    int c = 0;
+    for (; c + 2 < nchunks; c += 2) {
+      chunk(c, a_even, a_odd, yes);
+      chunk(c + 1, a_odd, a_even, yes);
+    }
+    if (c + 2 == nchunks) {
+      chunk(c, a_even, a_odd, yes);
+      chunk(c + 1, a_odd, a_even, no);
+    } else {
+      chunk(c, a_even, a_odd, no);
+    }
   }
 
   // --- sum the partial accumulators; waves that split the j range meet in LDS, and the
@@ -365,7 +388,7 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
     }
   }
   __syncthreads();
-  CIRC_PROBE(12);
+  CIRC_PROBE(60);
   {
     const int coli = tid % PTI, ti = tid / PTI;
     constexpr int TTI = NT / PTI;
@@ -374,7 +397,7 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
     fft_lds_pass2_inplace<K, true>(z, PPI, coli, ti, TTI);
     __syncthreads();
   }
-  CIRC_PROBE(13);
+  CIRC_PROBE(61);
 #pragma unroll
   for (int s = 0; s < NV; ++s) {
     const int idx = s * NT + tid;
@@ -391,7 +414,7 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
       *reinterpret_cast<float4*>(y + (long long)b * ldy + (long long)i * K + n) = v;
     }
   }
-  CIRC_PROBE(14);
+  CIRC_PROBE(62);
 }
 
 }  // namespace circ
