@@ -521,7 +521,7 @@ bool plan_conv_tile(int p, int qh, int r, int Ho, int Wo, int ncombo, ConvTilePl
   const int max_pos = Sh::MAXT * (Sh::NW / ncombo);
   long long best_cost = -1;
   for (int th = 1; th <= Ho && th + r - 1 <= 16; ++th)
-    for (int tw = 1; tw <= Wo && tw + r - 1 <= 16; ++tw) {   // the kernel lays input positions out with a row pitch of 16
+    for (int tw = 2; tw <= Wo && tw + r - 1 <= 16; tw += 2) {   // row pitch of 16 input positions; outputs stored in pairs
       if (th * tw > max_pos) continue;
       const int ipos = (th + r - 1) * 16;
       const size_t lds = conv_fused_lds_bytes<K, NT>(qh * ipos, p * th * tw);
@@ -537,10 +537,11 @@ bool plan_conv_tile(int p, int qh, int r, int Ho, int Wo, int ncombo, ConvTilePl
   return best_cost >= 0;
 }
 
-template <int Q>
-hipError_t launch_conv_fused_q(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
+// NT threads per workgroup, QH input channel blocks whose spectra are held in LDS at a time.
+template <int Q, int NT, int QH>
+hipError_t launch_conv_fused_t(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
                                int W, int Ho, int Wo, int pad, int ncombo, int relu, hipStream_t s) {
-  constexpr int K = 64, NT = 512, R = 3, QH = Q < 2 ? Q : 2;
+  constexpr int K = 64, R = 3;
   ConvTilePlan pl;
   if (!plan_conv_tile<K, NT>(C_out / K, QH, R, Ho, Wo, ncombo, pl)) return hipErrorInvalidValue;
   if (pl.lds > 64 * 1024) {   // opt in to more than the default LDS limit, once per size increase
@@ -556,6 +557,21 @@ hipError_t launch_conv_fused_q(const float2* wc, const float* x, const float* bi
   hipLaunchKernelGGL((conv_fused_kernel<K, NT, R, Q, QH>), dim3((unsigned)grid), dim3(NT), pl.lds, s, wc, x, bias, y, N, C_out,
                      H, W, Ho, Wo, pad, pl.TH, pl.TW, pl.tiles_h, pl.tiles_w, ncombo, relu);
   return hipGetLastError();
+}
+
+// Up to 4 (slot group, row group) combinations (p <= 8) run as workgroups of 256 threads with one
+// channel block of spectra in LDS at a time: two such workgroups share a CU, so the loads and
+// stores of one overlap the transforms and the contraction of the other.  More combinations need
+// the 8 waves of a 512-thread workgroup.
+#ifndef CIRC_CONV_SMALL_WG
+#define CIRC_CONV_SMALL_WG 1
+#endif
+template <int Q>
+hipError_t launch_conv_fused_q(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
+                               int W, int Ho, int Wo, int pad, int ncombo, int relu, hipStream_t s) {
+  if (CIRC_CONV_SMALL_WG && ncombo <= 4)
+    return launch_conv_fused_t<Q, 256, 1>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+  return launch_conv_fused_t<Q, 512, (Q < 2 ? Q : 2)>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
 }
 
 }  // namespace
@@ -603,7 +619,11 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
   const int p = C_out / k, q = C_in / k, NF = k / 2 + 1;
   const long long HW = (long long)H * W, HWo = (long long)Ho * Wo;
   const int ncombo = conv_fused_ncombo(p, q, k, r);
-  if (ncombo > 0 && (long long)cdiv(N, 2) * Ho * Wo < (1ll << 31)) {
+  // the fused kernel loads aligned groups of 4 pixels and stores pairs of outputs, and keeps
+  // offsets inside an image pair in 32 bits
+  const bool fused_ok = ncombo > 0 && W % 4 == 0 && Wo % 2 == 0 && 2 * (long long)C_in * HW < (1ll << 31) &&
+                        2 * (long long)C_out * HWo < (1ll << 31) && (long long)cdiv(N, 2) * Ho * Wo < (1ll << 31);
+  if (fused_ok) {
     const float2* wc = blob_at<float2>(w_hat, blob_layout(r * r, p, q, k).conv);
     const float* bp = use_bias ? bias : nullptr;
     const int relu = (epilogue & CIRC_EPI_RELU) ? 1 : 0;

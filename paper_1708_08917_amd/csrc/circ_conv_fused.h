@@ -30,7 +30,7 @@ struct ConvFusedShape {
   static constexpr int S = K / 2;
   static constexpr int FG = S / 16;
   static constexpr int OPROW = 2 * K + 2;
-  static constexpr int MAXT = 8;               // output positions per wave
+  static constexpr int MAXT = 4096 / NT;       // output positions per wave (8 or 16)
   static_assert(K >= 32 && NT % PT == 0 && (2 * K * PT) % NT == 0, "bad chunk shape");
 };
 
@@ -39,9 +39,9 @@ struct ConvFusedShape {
 template <int K, int NT>
 inline size_t conv_fused_lds_bytes(int nrows, int ncoli) {
   using Sh = ConvFusedShape<K, NT>;
-  size_t op = size_t(nrows) * Sh::OPROW * sizeof(float);
-  size_t inv = size_t(K) * (ncoli + 1) * sizeof(float2);
-  return size_t(K) * Sh::PP * sizeof(float2) + size_t(K) * sizeof(float2) + (256 + 64) * sizeof(int) + (op > inv ? op : inv);
+  size_t fwd = size_t(K) * Sh::PP * sizeof(float2) + size_t(nrows) * Sh::OPROW * sizeof(float);
+  size_t inv = size_t(K) * (ncoli + 1) * sizeof(float2);   // overlays the forward tile and the operand rows
+  return size_t(K) * sizeof(float2) + 64 * sizeof(int) + (fwd > inv ? fwd : inv);
 }
 
 // Weight spectra in the operand order of the fused CONV kernel:
@@ -76,7 +76,7 @@ __global__ void pack_conv_kernel(const float2* __restrict__ spec, float2* __rest
 // compile-time so that the weight operands live in registers.
 // One workgroup = one tile of TH x TW output positions of one image pair.
 template <int K, int NT, int R, int Q, int QH>
-__global__ __launch_bounds__(NT) void conv_fused_kernel(const float2* __restrict__ Wc, const float* __restrict__ x,
+__global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restrict__ Wc, const float* __restrict__ x,
                                                         const float* __restrict__ bias, float* __restrict__ y,
                                                         int N, int C_out, int H, int W, int Ho, int Wo, int pad,
                                                         int TH, int TW, int tiles_h, int tiles_w, int ncombo, int relu) {
@@ -84,14 +84,13 @@ __global__ __launch_bounds__(NT) void conv_fused_kernel(const float2* __restrict
   constexpr int PT = Sh::PT, PP = Sh::PP, S = Sh::S, FG = Sh::FG, OPROW = Sh::OPROW, NW = Sh::NW, MAXT = Sh::MAXT;
   constexpr int C_in = Q * K;
   constexpr int R2 = radix2_of(K), R1 = radix1_of(K);
-  constexpr int NLD = 2 * K * PT / NT;              // x elements per thread and chunk (16)
   static_assert(Q % QH == 0, "rounds must cover the input channel blocks evenly");
   extern __shared__ float smem[];
-  float2* z = reinterpret_cast<float2*>(smem);
-  float2* twl = z + K * PP;
-  int* postab = reinterpret_cast<int*>(twl + K);    // input position -> offset in an image plane, or -1
-  float* op = reinterpret_cast<float*>(postab + 256 + 64);
-  float2* zi = reinterpret_cast<float2*>(op);       // inverse tile, reuses the operand buffer
+  float2* twl = reinterpret_cast<float2*>(smem);
+  int* outtab = reinterpret_cast<int*>(twl + K);    // output position -> its first input position, or -1
+  float2* z = reinterpret_cast<float2*>(outtab + 64);
+  float* op = reinterpret_cast<float*>(z + K * PP);
+  float2* zi = z;                                   // inverse tile, reuses the forward tile and the operand rows
 
   // the wave index is made explicitly wave-uniform: combo, positions and row addresses derived
   // from it then live in scalar registers
@@ -110,11 +109,61 @@ __global__ __launch_bounds__(NT) void conv_fused_kernel(const float2* __restrict
   const int HW = H * W, HWo = Ho * Wo;
 
   CIRC_PROBE(0);
+  // x of one chunk (RPC input rows of the tile, one channel block, both images).  Image rows are
+  // multiples of 4 pixels (checked on the host), so a tile row of 16 input positions lies inside
+  // NG aligned groups of 4 pixels: a task is one such group of one (image, channel, row) and
+  // costs one 16-byte load; the lanes of a wave run along groups, then rows, then channels.
+  // A group is entirely inside or outside the image; outside groups and rows load nothing and
+  // put zeros into the tile (the zero padding of the convolution).
+  constexpr int RPC = PT / IWP;                     // tile rows per chunk
+  constexpr int NG = IWP / 4 + 1;                   // aligned groups that can touch one tile row
+  constexpr int NLD = 2 * K * RPC * NG / NT;        // tasks per thread and chunk
+  static_assert(PT % IWP == 0 && (2 * K * RPC * NG) % NT == 0, "x tasks must split evenly over the threads");
+  const int colc = tid % PT;
+  const float* ximg = x + (long long)n0 * C_in * HW;
+  const bool second = n0 + 1 < N;
+  const int gx0 = w0 - pad, g0 = gx0 >> 2, gsh = gx0 - 4 * g0;   // arithmetic shift = floor division
+  auto load_chunk = [&](int ch, float4 (&xr)[NLD]) {  // ch = global chunk index over (j, row chunk)
+    const int j = ch / cpj, pc = ch % cpj;
+    const float* pj = ximg + (long long)j * K * HW;        // wave-uniform part of the address
+#pragma unroll
+    for (int it = 0; it < NLD; ++it) {
+      const int task = it * NT + tid;
+      const int g = task % NG, r1 = task / NG;
+      const int row = r1 % RPC, r2 = r1 / RPC;
+      const int chn = r2 % K, img = r2 / K;
+      const int rowg = pc * RPC + row, gh = h0 - pad + rowg, px0 = 4 * (g0 + g);
+      const bool ok = rowg < IH && gh >= 0 && gh < H && px0 >= 0 && px0 < W && (img == 0 || second);
+      const int off = ok ? (img * C_in + chn) * HW + gh * W + px0 : 0;   // clamped: the load is unconditional
+      const float4 v = *reinterpret_cast<const float4*>(pj + off);
+      xr[it] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto store_chunk = [&](const float4 (&xr)[NLD]) {
+    float* zf = reinterpret_cast<float*>(z);
+#pragma unroll
+    for (int it = 0; it < NLD; ++it) {
+      const int task = it * NT + tid;
+      const int g = task % NG, r1 = task / NG;
+      const int row = r1 % RPC, r2 = r1 / RPC;
+      const int chn = r2 % K, img = r2 / K;
+      const int iw0 = 4 * g - gsh;                         // tile column of the group's first pixel
+      // pixels that fall left or right of the tile row go to the spare column PT of the tile
+      // (never transformed), so that every write is unconditional
+      float* zrow = zf + 2 * (chn * PP) + img;
+      const float vals[4] = {xr[it].x, xr[it].y, xr[it].z, xr[it].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int iw = iw0 + e;
+        const int col = (iw >= 0 && iw < IWP) ? row * IWP + iw : PT;
+        zrow[2 * col] = vals[e];
+      }
+    }
+  };
+  // the first chunk's loads go out before anything else needs memory
+  float4 xa[NLD];
+  load_chunk(0, xa);
   stage_twiddles<K>(twl, tid, NT);
-  for (int pos = tid; pos < 256; pos += NT) {
-    const int iw = pos % IWP, gh = h0 - pad + pos / IWP, gw = w0 - pad + iw;
-    postab[pos] = (pos < IPOS && iw < IW && gh >= 0 && gh < H && gw >= 0 && gw < W) ? gh * W + gw : -1;
-  }
 
   // weight operands of this wave's (slot group, row group), one round (R*R*QH values) at a time
   const int combo = wave % ncombo, fg = combo % FG, ig = combo / FG;
@@ -136,45 +185,32 @@ __global__ __launch_bounds__(NT) void conv_fused_kernel(const float2* __restrict
     Qa[tk] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
   // output position -> its first input position (top-left tap), or -1 past the tile
-  int* outtab = postab + 256;
   for (int pos = tid; pos < 64; pos += NT) outtab[pos] = pos < NPOS ? (pos / TW) * IWP + pos % TW : -1;
   __syncthreads();   // the tables are ready
-
-  // x of one chunk: column = input position, 2*K (image, channel) values per column
-  const int colc = tid % PT, ht0 = tid / PT;
-  const float* ximg = x + (long long)n0 * C_in * HW;
-  const bool second = n0 + 1 < N;
-  auto load_chunk = [&](int ch, float (&xr)[NLD]) {   // ch = global chunk index over (j, position chunk)
-    const int j = ch / cpj, pos = (ch % cpj) * PT + colc;
-    const int off = pos < 256 ? postab[pos] : -1;
-    const int toff = off + ht0 * HW;                       // per-thread part of the address
-    const float* pj = ximg + (long long)j * K * HW;        // wave-uniform part
+  // first input position of each of this wave's output positions (wave-uniform); positions past
+  // the end of the tile use row 0 (their results are never stored); ntk = positions that count
+  static_assert(MAXT % 2 == 0, "positions are taken in pairs");
+  int ipos[MAXT];
+  int ntk = 0;
 #pragma unroll
-    for (int it = 0; it < NLD; ++it) {
-      constexpr int HT_STEP = NT / PT;                     // ht = it*HT_STEP + ht0, no carry from ht0 into t's multiple
-      const int half = (it * HT_STEP) / K, tc = (it * HT_STEP) % K;
-      const float* pu = pj + (long long)(half * C_in + tc) * HW;
-      xr[it] = (off >= 0 && (half == 0 || second)) ? pu[toff] : 0.f;
-    }
-  };
+  for (int tk = 0; tk < MAXT; ++tk) {
+    const int v = __builtin_amdgcn_readfirstlane(outtab[pos_first + tk * pos_step]);
+    ipos[tk] = v >= 0 ? v : 0;
+    ntk += v >= 0 ? 1 : 0;
+  }
+
   const int nch_total = Q * cpj, nch_round = QH * cpj;
-  float xa[NLD];
-  load_chunk(0, xa);
 
   // one chunk: registers -> z tile -> two FFT passes -> operand rows
-  auto fft_chunk = [&](int ch, float (&xr)[NLD], float (&xnext)[NLD]) {
-    float* zb = reinterpret_cast<float*>(z) + 2 * (ht0 * PP + colc);
-#pragma unroll
-    for (int it = 0; it < NLD; ++it) {
-      constexpr int HT_STEP = NT / PT;
-      const int half = (it * HT_STEP) / K, tc = (it * HT_STEP) % K;
-      zb[2 * tc * PP + half] = xr[it];
-    }
+  auto fft_chunk = [&](int ch, float4 (&xr)[NLD], float4 (&xnext)[NLD]) {
+    store_chunk(xr);
     __syncthreads();
+    CIRC_PROBE(10 + 4 * ch);
     if (ch + 1 < nch_total) load_chunk(ch + 1, xnext);
     const int t = tid / PT;
     fft_lds_pass1<K, false>(z, PP, colc, t, NT / PT, twl);
     __syncthreads();
+    CIRC_PROBE(11 + 4 * ch);
     const int jl = (ch % nch_round) / cpj, pos = (ch % cpj) * PT + colc;
     float* orow = op + (jl * IPOS + pos) * OPROW;
     const bool keep = pos < IPOS;
@@ -187,35 +223,42 @@ __global__ __launch_bounds__(NT) void conv_fused_kernel(const float2* __restrict
       if (keep) *reinterpret_cast<float2*>(orow + 4 * sl + 2 * h) = v;
     });
     __syncthreads();
+    CIRC_PROBE(12 + 4 * ch);
   };
 
+#pragma unroll 1
   for (int round = 0; round < Q / QH; ++round) {
     load_a(round);
     for (int cl = 0; cl < nch_round; ++cl) fft_chunk(round * nch_round + cl, xa, xa);
     CIRC_PROBE(1 + 3 * round);
-    // ---- contraction of this round: every wave takes up to MAXT output positions for its combo
-    // Rows of positions outside the image hold the spectrum of zeros, so the taps need no
-    // border test.  Row indices are wave-uniform; only the lane offset is per thread.
+    // ---- contraction of this round: every wave takes up to MAXT output positions for its combo,
+    // two at a time (independent accumulators back to back).  Rows of positions outside the
+    // image hold the spectrum of zeros, so the taps need no border test.  Row indices are
+    // wave-uniform (scalar registers); only the lane offset is per thread.  All operand rows of
+    // a pair of positions are fetched before its matrix instructions.
     const float* opw = op + fg * 64 + lane;
 #pragma unroll
-    for (int tk = 0; tk < MAXT; ++tk) {
-      const int ipos0 = __builtin_amdgcn_readfirstlane(outtab[pos_first + tk * pos_step]);
-      if (ipos0 >= 0) {
-        const float* r0 = opw + ipos0 * OPROW;
+    for (int tk = 0; tk < MAXT; tk += 2) {
+      if (tk < ntk) {                                       // wave-uniform
+        const float* r0 = opw + ipos[tk] * OPROW;
+        const float* r1 = opw + ipos[tk + 1] * OPROW;       // the row of position 0 if tk + 1 is past the end
+        float b0[R * R * QH], b1[R * R * QH];
 #pragma unroll
-        for (int dh = 0; dh < R; ++dh) {
+        for (int dh = 0; dh < R; ++dh)
 #pragma unroll
-          for (int dw = 0; dw < R; ++dw) {
-            float bv[QH];
-#pragma unroll
-            for (int jl = 0; jl < QH; ++jl) bv[jl] = (r0 + jl * IPOS * OPROW)[(dh * IWP + dw) * OPROW];
+          for (int dw = 0; dw < R; ++dw)
 #pragma unroll
             for (int jl = 0; jl < QH; ++jl) {
-              const float2 av = a[(dh * R + dw) * QH + jl];
-              P[tk] = __builtin_amdgcn_mfma_f32_4x4x1f32(av.x, bv[jl], P[tk], 0, 0, 0);
-              Qa[tk] = __builtin_amdgcn_mfma_f32_4x4x1f32(av.y, bv[jl], Qa[tk], 0, 0, 0);
+              b0[(dh * R + dw) * QH + jl] = (r0 + jl * IPOS * OPROW)[(dh * IWP + dw) * OPROW];
+              b1[(dh * R + dw) * QH + jl] = (r1 + jl * IPOS * OPROW)[(dh * IWP + dw) * OPROW];
             }
-          }
+#pragma unroll
+        for (int g = 0; g < R * R * QH; ++g) {
+          const float2 av = a[g];
+          P[tk] = __builtin_amdgcn_mfma_f32_4x4x1f32(av.x, b0[g], P[tk], 0, 0, 0);
+          Qa[tk] = __builtin_amdgcn_mfma_f32_4x4x1f32(av.y, b0[g], Qa[tk], 0, 0, 0);
+          P[tk + 1] = __builtin_amdgcn_mfma_f32_4x4x1f32(av.x, b1[g], P[tk + 1], 0, 0, 0);
+          Qa[tk + 1] = __builtin_amdgcn_mfma_f32_4x4x1f32(av.y, b1[g], Qa[tk + 1], 0, 0, 0);
         }
       }
     }
@@ -267,25 +310,35 @@ __global__ __launch_bounds__(NT) void conv_fused_kernel(const float2* __restrict
   __syncthreads();
   CIRC_PROBE(60);
 
-  // ---- store: lanes run along the output positions of one channel; (image, channel) is
-  // wave-uniform in every iteration
-  for (int colb = 0; colb < NCOLI; colb += 64) {
-    const int col = colb + lane;
-    const int i = col / NPOS, pos = col % NPOS;
-    const int oh = h0 + pos / TW, ow = w0 + pos % TW;
-    const bool ok = col < NCOLI && oh < Ho && ow < Wo;
-    const int toff = i * K * HWo + oh * Wo + ow;                        // per-thread part (fits 32 bits per image pair)
-    const float* zc = reinterpret_cast<const float*>(zi) + 2 * col;
-    const float* brow = bias ? bias + i * K : nullptr;
-    float* yimg = y + (long long)n0 * C_out * HWo;
+  // ---- store: a task is one pair of neighbouring output positions of one output channel,
+  // for both images (two 8-byte stores); tile origins and row lengths are even (checked on the
+  // host), so a pair is aligned and entirely inside or outside the image.  A wave covers
+  // 64 / (pairs per channel) channels at a time; a lane keeps its pair for the whole loop.
+  {
+    const int NPAIR = TW / 2, per_ch = TH * NPAIR;          // per_ch <= 32
+    const int cpl = 64 / per_ch;                            // channels per wave iteration
+    const int c_sub = lane / per_ch, rem = lane - c_sub * per_ch;
+    const int orow = rem / NPAIR, pr = rem - orow * NPAIR;
+    const int oh = h0 + orow, ow = w0 + 2 * pr;
+    const bool lane_ok = c_sub < cpl && oh < Ho && ow < Wo;
+    const int zoff = orow * TW + 2 * pr;
+    float* yimg = y + (long long)n0 * C_out * HWo + oh * Wo + ow;
 #pragma unroll 4
-    for (int ht = wave; ht < 2 * K; ht += NW) {
-      const int half = ht / K, t = ht % K;
-      if (ok && (half == 0 || second)) {
-        float v = zc[2 * fft_pos<K>(t) * PPI + half];
-        if (brow) v += brow[t];
-        if (relu) v = fmaxf(v, 0.f);
-        (yimg + (long long)(half * C_out + t) * HWo)[toff] = v;
+    for (int cb = wave * cpl; cb < C_out; cb += NW * cpl) {
+      const int c = cb + c_sub;
+      if (lane_ok && c < C_out) {
+        const int i = c / K, t = c % K;
+        const float2* zc = zi + fft_pos<K>(t) * PPI + i * NPOS + zoff;
+        const float2 u0 = zc[0], u1 = zc[1];               // (image 0, image 1) of the two positions
+        const float bv = bias ? bias[c] : 0.f;
+        float2 o0 = make_float2(u0.x + bv, u1.x + bv), o1 = make_float2(u0.y + bv, u1.y + bv);
+        if (relu) {
+          o0.x = fmaxf(o0.x, 0.f); o0.y = fmaxf(o0.y, 0.f);
+          o1.x = fmaxf(o1.x, 0.f); o1.y = fmaxf(o1.y, 0.f);
+        }
+        float* yo = yimg + (long long)c * HWo;
+        *reinterpret_cast<float2*>(yo) = o0;
+        if (second) *reinterpret_cast<float2*>(yo + (long long)C_out * HWo) = o1;
       }
     }
   }

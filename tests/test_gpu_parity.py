@@ -129,10 +129,13 @@ def test_conv_forward_shapes(N, p, q, k, H, W, r, pad):
     _conv_case(N, p, q, k, H, W, r, pad)
 
 
-# ---- fused CONV kernel (k = 64, 3x3, q in {1,2,4}, p <= 16): odd image counts, ragged tiles,
-# every padding, every row-group count
-@pytest.mark.parametrize("N,p,q,H,W,pad", [(1, 1, 1, 5, 5, 1), (3, 4, 4, 9, 11, 1), (2, 5, 2, 13, 6, 0), (5, 9, 1, 7, 30, 2),
-                                           (2, 16, 4, 8, 8, 1), (4, 3, 2, 28, 28, 1), (1, 2, 4, 3, 3, 0), (2, 4, 4, 33, 5, 2)])
+# ---- fused CONV kernel (k = 64, 3x3, q in {1,2,4}, p <= 16, image rows a multiple of 4 pixels):
+# odd image counts, ragged tiles in both directions, every padding, every row-group count; the
+# shapes with other row lengths take the unfused route
+@pytest.mark.parametrize("N,p,q,H,W,pad", [(1, 1, 1, 5, 8, 1), (3, 4, 4, 9, 12, 1), (2, 5, 2, 13, 8, 0), (5, 9, 1, 7, 32, 2),
+                                           (2, 16, 4, 8, 8, 1), (4, 3, 2, 28, 28, 1), (1, 2, 4, 3, 4, 0), (2, 4, 4, 33, 4, 2),
+                                           (3, 2, 2, 10, 20, 1), (2, 4, 4, 16, 16, 0), (1, 1, 1, 5, 5, 1), (3, 4, 4, 9, 11, 1),
+                                           (2, 5, 2, 13, 6, 0)])
 def test_conv_forward_fused_shapes(N, p, q, H, W, pad):
     _conv_case(N, p, q, 64, H, W, 3, pad)
 
