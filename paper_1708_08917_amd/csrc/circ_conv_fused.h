@@ -22,6 +22,10 @@
 
 namespace circ {
 
+// source of the zero padding (one aligned group of 4 pixels)
+// (not const: it then lives in the same address space as x, and the loads stay global loads)
+__device__ float kZeroPixels[4] __attribute__((aligned(16))) = {0.f, 0.f, 0.f, 0.f};
+
 template <int K, int NT>
 struct ConvFusedShape {
   static constexpr int NW = NT / 64;
@@ -133,10 +137,12 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
       const int row = r1 % RPC, r2 = r1 / RPC;
       const int chn = r2 % K, img = r2 / K;
       const int rowg = pc * RPC + row, gh = h0 - pad + rowg, px0 = 4 * (g0 + g);
-      const bool ok = rowg < IH && gh >= 0 && gh < H && px0 >= 0 && px0 < W && (img == 0 || second);
-      const int off = ok ? (img * C_in + chn) * HW + gh * W + px0 : 0;   // clamped: the load is unconditional
-      const float4 v = *reinterpret_cast<const float4*>(pj + off);
-      xr[it] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+      // bitwise on purpose: one mask, no short-circuit branches
+      const bool ok = bool(int(rowg < IH) & int(gh >= 0) & int(gh < H) & int(px0 >= 0) & int(px0 < W) &
+                           (int(img == 0) | int(second)));
+      // padding is read from a block of zeros: the load itself is unconditional
+      const float* src = ok ? pj + ((img * C_in + chn) * HW + gh * W + px0) : kZeroPixels;
+      xr[it] = *reinterpret_cast<const float4*>(src);
     }
   };
   auto store_chunk = [&](const float4 (&xr)[NLD]) {
