@@ -12,8 +12,9 @@ the launch stream and by torch.cuda.synchronize().  Each step reads a different 
 buffer and writes a different output buffer out of a pool larger than twice the 256 MB
 Infinity Cache, so activations really come from HBM while the 1 MB of weight spectra
 legitimately stays cached.  The steps are independent batches, so the graph issues them
-alternately on two streams (both default priority): the ~2 us between the end of one kernel
-and the start of the next on a single stream is then filled by the other stream's kernel.
+round-robin on several streams (--streams, all default priority): two workgroups of the
+kernel fit one CU, so a step starts while the previous ones are still waiting for their
+operands or draining, and the ~2 us between two kernels of one stream is filled as well.
 Extra fields report the single-stream graph, eager launches, and one warm buffer pair; the
 roofline entry always uses the single-stream kernel time.
 
@@ -54,6 +55,7 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=8, help="streams the graph of independent steps is spread over")
     ap.add_argument("--pool-mb", type=int, default=640, help="size of the rotating activation/output pool")
     ap.add_argument("--pmc", action="store_true",
                     help="counter-collection mode for rocprofv3 --pmc: eager launches only (no graph), plus "
@@ -149,23 +151,29 @@ def main():
     torch.cuda.synchronize()
     ev_graph, wall_graph = timed(graph.replay)
 
-    # --- the same K steps, alternating between two streams inside one graph
-    stream2 = torch.cuda.Stream(device=dev)     # default priority
-    sptr2 = ctypes.c_void_p(stream2.cuda_stream)
-    ws2 = torch.empty_like(ws)
-    wsp2 = ctypes.c_void_p(ws2.data_ptr())
+    # --- the same K steps, round-robin over several streams inside one graph
+    S = max(1, args.streams)
+    side = [torch.cuda.Stream(device=dev) for _ in range(S - 1)]     # default priority
+    lanes = [(sptr, wsp)]
+    side_ws = []
+    for st_ in side:
+        side_ws.append(torch.empty_like(ws))
+        lanes.append((ctypes.c_void_p(st_.cuda_stream), ctypes.c_void_p(side_ws[-1].data_ptr())))
 
-    def step2(i):
-        st = fn(whp, xp[i], bp, yp[i], p, q, k, batch, epi, wsp2, wsn, sptr2)
+    def step_on(i, lane):
+        sp_, wp_ = lanes[lane]
+        st = fn(whp, xp[i], bp, yp[i], p, q, k, batch, epi, wp_, wsn, sp_)
         if st != 0:
             raise RuntimeError(B.status_string(st))
 
     graph2 = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph2, stream=stream):
-        stream2.wait_stream(stream)                  # fork
+        for st_ in side:
+            st_.wait_stream(stream)                  # fork
         for i in range(K):
-            (step if i % 2 == 0 else step2)((Wm + i) % npairs)
-        stream.wait_stream(stream2)                  # join
+            step_on((Wm + i) % npairs, i % S)
+        for st_ in side:
+            stream.wait_stream(st_)                  # join
     graph2.replay()
     torch.cuda.synchronize()
     ev_graph2, wall_graph2 = timed(graph2.replay)
@@ -183,7 +191,7 @@ def main():
         "config": {"workload": "cfg2: block-circulant FC forward, n_in=n_out=4096, k=64 (p=q=64), batch 64, "
                                "fp32, bias+ReLU; cached weight spectra; activations rotate through a "
                                f"{npairs * pair_bytes >> 20} MB pool (HBM-resident, not cache-resident)",
-                   "p": p, "q": q, "k": k, "batch": batch, "launch": "one hip graph of K independent steps, alternating between two streams"},
+                   "p": p, "q": q, "k": k, "batch": batch, "launch": f"one hip graph of K independent steps, round-robin over {S} streams"},
         "dense_equivalent_gflops": 2.0 * cfg.n_in * cfg.n_out * batch / t_step * 1e-9,
         "roofline": {
             "bound": "mfma", "kernel": "circ::fc_fused_kernel<64,8,1,512> (the one kernel of a step)",
@@ -196,7 +204,7 @@ def main():
                          "frac": alg_bytes / t_step * 1e-9 / HBM_PEAK_GBS},
         },
         "timing_detail_us_per_step": {
-            "graph_two_streams_events": ev_graph2 / K * 1e6, "graph_two_streams_wall": wall_graph2 / K * 1e6,
+            "graph_multi_stream_events": ev_graph2 / K * 1e6, "graph_multi_stream_wall": wall_graph2 / K * 1e6, "streams": S,
             "graph_one_stream_events": ev_graph / K * 1e6, "graph_one_stream_wall": wall_graph / K * 1e6,
             "eager_rotating_events": ev_eager / K * 1e6, "eager_rotating_wall": wall_eager / K * 1e6,
             "eager_warm_pair_events": ev_warm / K * 1e6,

@@ -213,13 +213,14 @@ hipError_t ensure_lds(Kern kern, size_t bytes, bool& done) {
   return hipSuccess;
 }
 
-template <int K, int IT, int NP, int NT>
-hipError_t launch_fused_t(const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
+// ONE: all q input blocks fit one chunk of the kernel (no double buffering of the operands).
+template <int K, int IT, int NP, int NT, bool ONE>
+hipError_t launch_fused_v(const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
                           int relu, hipStream_t s) {
   using Sh = FusedShape<K, IT, NP, NT>;
   static_assert((4096 / K) % Sh::JC == 0, "packed weights are padded to chunks of 4096/K input blocks");
   static bool opted_in = false;
-  if (ensure_lds(&fc_fused_kernel<K, IT, NP, NT>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
+  if (ensure_lds(&fc_fused_kernel<K, IT, NP, NT, ONE>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
   const int n_it = (int)cdiv(p, IT), n_bt = (int)cdiv(batch, 2 * NP);
   // Split the tile grid over the 8 XCDs as xa x (8/xa) rectangles; pick the split that
   // minimises the bytes every XCD pulls into its own L2 (weight tiles + x rows).
@@ -231,9 +232,16 @@ hipError_t launch_fused_t(const float4* wf, const float* x, const float* bias, f
     if (wbytes + xbytes < best) { best = wbytes + xbytes; xa = cand; }
   }
   const long long grid = 8 * cdiv(n_it, xa) * cdiv(n_bt, 8 / xa);
-  hipLaunchKernelGGL((fc_fused_kernel<K, IT, NP, NT>), dim3((unsigned)grid), dim3(NT), Sh::LDS_BYTES, s, wf, x, bias,
+  hipLaunchKernelGGL((fc_fused_kernel<K, IT, NP, NT, ONE>), dim3((unsigned)grid), dim3(NT), Sh::LDS_BYTES, s, wf, x, bias,
                      y, p, q, batch, n_it, fused_q2p(q, K), xa, relu);
   return hipGetLastError();
+}
+
+template <int K, int IT, int NP, int NT>
+hipError_t launch_fused_t(const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
+                          int relu, hipStream_t s) {
+  if (q <= FusedShape<K, IT, NP, NT>::JC) return launch_fused_v<K, IT, NP, NT, true>(wf, x, bias, y, p, q, batch, relu, s);
+  return launch_fused_v<K, IT, NP, NT, false>(wf, x, bias, y, p, q, batch, relu, s);
 }
 
 // Packed batch pairs per workgroup: two when that still leaves at least 256 tiles (one per
@@ -246,6 +254,7 @@ inline int fused_np(int p, int k, int batch) {
 #ifndef CIRC_NT128
 #define CIRC_NT128 512
 #endif
+
 hipError_t launch_fused(int k, const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
                         int relu, hipStream_t s) {
   const int np = fused_np(p, k, batch);

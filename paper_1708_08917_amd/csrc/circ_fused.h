@@ -102,8 +102,14 @@ __device__ __forceinline__ float quad_swap_pairs(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false));
 }
 
-template <int K, int IT, int NP, int NT>
-__global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
+// ONE: all q input blocks fit one chunk, so the second (prefetch) set of weight operands is
+// never needed.  With 512 threads that variant is held to 128 registers per lane: two
+// workgroups then fit one CU (registers and LDS), and a launch on another stream can start on
+// a CU while the previous one is still waiting for its operands or draining.  Kernels of
+// independent batches overlap that way; a single launch is not slowed down.
+template <int K, int IT, int NP, int NT, bool ONE = false>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(ONE && NT == 512 ? 4 : 1, ONE && NT == 512 ? 4 : 8)))
+void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
                                                       const float* __restrict__ bias, float* __restrict__ y,
                                                       int p, int q, int B, int n_it, int q2p, int xa, int relu) {
   using Sh = FusedShape<K, IT, NP, NT>;
@@ -197,7 +203,7 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
     const int combo = combo0 + cc;
     aoff[cc] = unsigned(((combo % IG) * q2p) * FG + combo / IG) * 64u + unsigned(lane);
   }
-  float4 a_even[CPW][JW / 2], a_odd[CPW][JW / 2];
+  float4 a_even[CPW][JW / 2], a_odd[ONE ? 1 : CPW][ONE ? 1 : JW / 2];
   // [lo, hi) selects a part of the chunk's operands: a workgroup can only push requests into
   // the memory pipeline at a bounded rate, so the loads of the next chunk are issued in
   // pieces between the phases of the current one instead of stalling one phase
@@ -308,6 +314,9 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
     constexpr std::true_type yes{};
     constexpr std::false_type no{};
     int c = 0;
+    if constexpr (ONE) {
+      chunk(0, a_even, a_even, no);
+    } else {
     for (; c + 2 < nchunks; c += 2) {
       chunk(c, a_even, a_odd, yes);
       chunk(c + 1, a_odd, a_even, yes);
@@ -317,6 +326,7 @@ __global__ __launch_bounds__(NT) void fc_fused_kernel(const float4* __restrict__
       chunk(c + 1, a_odd, a_even, no);
     } else {
       chunk(c, a_even, a_odd, no);
+    }
     }
   }
 
