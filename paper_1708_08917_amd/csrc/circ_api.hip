@@ -6,6 +6,7 @@
 
 #include "../../include/circ.h"
 #include "circ_kernels.h"
+#include "circ_gemm.h"
 #include "circ_fused.h"
 #include "circ_gemv.h"
 #include "circ_conv_fused.h"
@@ -23,6 +24,10 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
 
 inline size_t spectrum_elems(int k, long long rows) { return size_t(k / 2 + 1) * size_t(rows); }
+
+// Activation spectra in the FC workspace are stored [f][row], densely.
+inline long long ws_fstride(long long rows) { return rows; }
+inline size_t ws_spectrum_elems(int k, long long rows) { return size_t(k / 2 + 1) * size_t(ws_fstride(rows)); }
 
 // Spectra blob: section 0 = forward operand [g][f][j][i] (i fastest), section 1 =
 // backward operand [g][f][i][j] (j fastest, conjugated).  Both carry the 1/k of the IFFT.
@@ -174,23 +179,62 @@ hipError_t launch_irfft(int k, bool rows_fast, const float2* in, float* out, con
 }
 
 // Number of k slices for a GEMM with few output tiles and a long reduction (backward-weights):
-// enough slices to put about two waves of 32x32 tiles on every SIMD, each at least 64 deep.
+// enough slices to put about four workgroups of 64x64 tiles on every CU, each at least 64 deep.
 inline int cgemm_ksplit(int NF, int M, int N, int Kd) {
-  const long long tiles = (long long)NF * cdiv(M, 32) * cdiv(N, 32);
+  const long long tiles = (long long)NF * cdiv(M, 64) * cdiv(N, 64);
   int ks = 1;
-  while (ks < 16 && tiles * ks < 2048 && Kd / (ks * 2) >= 64) ks *= 2;
+  while (ks < 16 && tiles * ks < 1024 && Kd / (ks * 2) >= 64) ks *= 2;
   return ks;
 }
 
+// Workgroups of the persistent tiled GEMM: two per CU.
+#ifndef CIRC_GEMM_WGS
+#define CIRC_GEMM_WGS 512
+#endif
+template <int FM, int WM, int WN>
+hipError_t launch_cgemm_tiled(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, long long sA,
+                              long long sB, long long sC, bool conj_b, hipStream_t s, int ksplit, int kchunk,
+                              long long part_stride) {
+  using Sh = GemmShape<FM, WM, WN>;
+  const int ntm = (int)cdiv(M, Sh::TM), ntn = (int)cdiv(N, Sh::TN);
+  const long long ntiles = (long long)(NF - 1) * ksplit * ntm * ntn;   // bins 0 and NF-1 share a tile
+  if (ntiles > (1ll << 31) - 8) return hipErrorInvalidValue;
+  const long long chunk = cdiv(ntiles, CIRC_GEMM_WGS);
+  dim3 grid((unsigned)(cdiv(cdiv(ntiles, chunk), 8) * 8));
+  if (conj_b)
+    hipLaunchKernelGGL((cgemm_tiled_kernel<FM, WM, WN, true>), grid, dim3(256), 0, s, A, B, C, M, N, Kd, NF, sA, sB, sC, ntm,
+                       ntn, ksplit, kchunk, part_stride, (unsigned)ntiles, (unsigned)chunk);
+  else
+    hipLaunchKernelGGL((cgemm_tiled_kernel<FM, WM, WN, false>), grid, dim3(256), 0, s, A, B, C, M, N, Kd, NF, sA, sB, sC, ntm,
+                       ntn, ksplit, kchunk, part_stride, (unsigned)ntiles, (unsigned)chunk);
+  return hipGetLastError();
+}
+
 // C[f][m][n] = sum_kd A[f][kd][m] * (conj?)B[f][kd][n] for f in [0, NF); with ksplit > 1 slice s
-// writes its partial sums to C + s*part_stride.
-hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, bool conj_b,
-                        hipStream_t s, int ksplit = 1, long long part_stride = 0) {
-  long long sA = (long long)Kd * M, sB = (long long)Kd * N, sC = (long long)M * N;
+// writes its partial sums to C + s*part_stride.  sA, sB, sC: elements between consecutive
+// frequencies of A, B, C.
+// Problems with a narrow output and a long reduction (backward-weights: N = q <= 64, reduction
+// over the batch) run on LDS-staged 64x64 workgroup tiles (measured at the 16384x16384, k=256,
+// batch 1024 layer: 58 us against 64 us); all others run one wave per 32x32 or 16x16 tile
+// straight from global memory, which was measured faster there (56 us against 62 us for
+// 64x128 tiles): its many independent waves drift apart, whereas the workgroups of the tiled
+// kernel stay in step and load, multiply and store at the same moments.
+#ifndef CIRC_GEMM_TILED_MIN
+#define CIRC_GEMM_TILED_MIN 256
+#endif
+hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, long long sA,
+                        long long sB, long long sC, bool conj_b, hipStream_t s, int ksplit = 1,
+                        long long part_stride = 0) {
+  const int kchunk = (int)(cdiv(cdiv(Kd, ksplit), 32) * 32);   // whole operand groups per slice
+  const long long tiles_s = (long long)(NF - 1) * ksplit * cdiv(M, 64) * cdiv(N, 64);
+  // the tiled kernel keeps offsets inside one frequency of an operand in 32 bits
+  const long long lim = (1ll << 31) - 1;
+  const bool fits32 = (long long)Kd * M <= lim && (long long)Kd * N <= lim && (long long)M * N <= lim;
+  if (fits32 && M > 32 && N <= 64 && tiles_s >= CIRC_GEMM_TILED_MIN)
+    return launch_cgemm_tiled<1, 2, 2>(A, B, C, NF, M, N, Kd, sA, sB, sC, conj_b, s, ksplit, kchunk, part_stride);
   bool big = (long long)NF * cdiv(M, 32) * cdiv(N, 32) * ksplit >= 1024;
   int tile = big ? 32 : 16;
   const int ntn = (int)cdiv(N, tile);
-  const int kchunk = (int)(cdiv(cdiv(Kd, ksplit), 32) * 32);   // whole operand groups per slice
   dim3 grid((unsigned)(ntn * ksplit), (unsigned)cdiv(M, tile), (unsigned)NF);
   if (big) {
     if (conj_b) hipLaunchKernelGGL((cgemm_kernel<32, true>), grid, dim3(64), 0, s, A, B, C, M, N, Kd, sA, sB, sC, ntn, kchunk, part_stride);
@@ -401,8 +445,8 @@ circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, i
 
 size_t circ_fc_workspace_bytes(int p, int q, int k, int batch, int backward) {
   if (!fc_dims_ok(p, q, k, batch)) return 0;
-  size_t xa = align_up(spectrum_elems(k, (long long)q * batch) * sizeof(float2), 256);
-  size_t ya = align_up(spectrum_elems(k, (long long)p * batch) * sizeof(float2), 256);
+  size_t xa = align_up(ws_spectrum_elems(k, (long long)q * batch) * sizeof(float2), 256);
+  size_t ya = align_up(ws_spectrum_elems(k, (long long)p * batch) * sizeof(float2), 256);
   if (!backward) return xa + ya;
   size_t wa = align_up(spectrum_elems(k, (long long)p * q) * sizeof(float2), 256);
   return xa + ya + wa * cgemm_ksplit(k / 2 + 1, p, q, batch);   // one dW^ buffer per k slice
@@ -441,16 +485,17 @@ circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias
   const int NF = k / 2 + 1;
   float2* xh = static_cast<float2*>(workspace);
   float2* yh = reinterpret_cast<float2*>(static_cast<char*>(workspace) +
-                                         align_up(spectrum_elems(k, (long long)q * batch) * sizeof(float2), 256));
+                                         align_up(ws_spectrum_elems(k, (long long)q * batch) * sizeof(float2), 256));
   const float2* wf = static_cast<const float2*>(w_hat);
   const long long xrows = (long long)q * batch, yrows = (long long)p * batch;
   // X^[f][j][b]: row id = j*batch + b -> x[b][j*k : (j+1)*k]
   RowMap mx{batch, q, (long long)q * k, (long long)k, 0, 1};
-  if (launch_rfft(k, false, x, xh, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+  const long long xfs = ws_fstride(xrows), yfs = ws_fstride(yrows);
+  if (launch_rfft(k, false, x, xh, mx, xrows, xfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
   // Y^[f][i][b] = sum_j W^[f][j][i] X^[f][j][b]
-  if (launch_cgemm(wf, xh, yh, NF, p, batch, q, false, s) != hipSuccess) return CIRC_EHIP;
+  if (launch_cgemm(wf, xh, yh, NF, p, batch, q, (long long)p * q, xfs, yfs, false, s) != hipSuccess) return CIRC_EHIP;
   RowMap my{batch, p, (long long)p * k, (long long)k, 0, 1};
-  if (launch_irfft(k, false, yh, y, my, yrows, yrows, 1.0f, use_bias ? bias : nullptr, batch,
+  if (launch_irfft(k, false, yh, y, my, yrows, yfs, 1.0f, use_bias ? bias : nullptr, batch,
                    (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
     return CIRC_EHIP;
   return CIRC_OK;
@@ -474,14 +519,15 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   const int NF = k / 2 + 1;
-  const size_t xa = align_up(spectrum_elems(k, (long long)q * batch) * sizeof(float2), 256);
-  const size_t ya = align_up(spectrum_elems(k, (long long)p * batch) * sizeof(float2), 256);
+  const size_t xa = align_up(ws_spectrum_elems(k, (long long)q * batch) * sizeof(float2), 256);
+  const size_t ya = align_up(ws_spectrum_elems(k, (long long)p * batch) * sizeof(float2), 256);
   float2* bufx = static_cast<float2*>(workspace);
   float2* bufy = reinterpret_cast<float2*>(static_cast<char*>(workspace) + xa);
   float2* bufw = reinterpret_cast<float2*>(static_cast<char*>(workspace) + xa + ya);
   const BlobLayout bl = blob_layout(1, p, q, k);
   const float2* wb = blob_at<float2>(w_hat, bl.bwd);
   const long long xrows = (long long)q * batch, yrows = (long long)p * batch;
+  const long long xfs = ws_fstride(xrows), yfs = ws_fstride(yrows), wfs = (long long)p * q;
 
   // Backward-data is a forward pass on the transposed, conjugated grid (q output block rows,
   // p input blocks, no epilogue): the small-problem kernels serve it from their own sections.
@@ -493,21 +539,21 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
   } else if (dx) {
     // dY^[f][i][b];  dX^[f][j][b] = sum_i conj(W^)[f][i][j] dY^[f][i][b]
     RowMap mdy{batch, p, (long long)p * k, (long long)k, 0, 1};
-    if (launch_rfft(k, false, dy, bufy, mdy, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
-    if (launch_cgemm(wb, bufy, bufx, NF, q, batch, p, false, s) != hipSuccess) return CIRC_EHIP;
+    if (launch_rfft(k, false, dy, bufy, mdy, yrows, yfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    if (launch_cgemm(wb, bufy, bufx, NF, q, batch, p, wfs, yfs, xfs, false, s) != hipSuccess) return CIRC_EHIP;
     RowMap mdx{batch, q, (long long)q * k, (long long)k, 0, 1};
-    if (launch_irfft(k, false, bufx, dx, mdx, xrows, xrows, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
+    if (launch_irfft(k, false, bufx, dx, mdx, xrows, xfs, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
   }
   if (dw) {
     // batch-major spectra: dY^[f][b][i], X^[f][b][j];  dW^[f][i][j] = sum_b dY^[f][b][i] conj(X^[f][b][j])
     RowMap mdy{p, batch, (long long)k, (long long)p * k, 0, 1};
-    if (launch_rfft(k, false, dy, bufy, mdy, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    if (launch_rfft(k, false, dy, bufy, mdy, yrows, yfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
     RowMap mx{q, batch, (long long)k, (long long)q * k, 0, 1};
-    if (launch_rfft(k, false, x, bufx, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    if (launch_rfft(k, false, x, bufx, mx, xrows, xfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
     // the reduction over the batch is cut into slices; the IFFT adds the partial spectra in order
     const int ksplit = cgemm_ksplit(NF, p, q, batch);
     const long long wpart = (long long)(align_up(spectrum_elems(k, (long long)p * q) * sizeof(float2), 256) / sizeof(float2));
-    if (launch_cgemm(bufy, bufx, bufw, NF, p, q, batch, true, s, ksplit, wpart) != hipSuccess) return CIRC_EHIP;
+    if (launch_cgemm(bufy, bufx, bufw, NF, p, q, batch, yfs, xfs, wfs, true, s, ksplit, wpart) != hipSuccess) return CIRC_EHIP;
     const long long wrows = (long long)p * q;
     RowMap mw{q, p, (long long)k, (long long)q * k, 0, 1};
     if (launch_irfft(k, false, bufw, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, ksplit, wpart) != hipSuccess)

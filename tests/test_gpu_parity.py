@@ -122,6 +122,35 @@ def test_fc_backward_shapes(p, q, k, batch):
     np.testing.assert_array_equal(dw_only, dw)
 
 
+# ---- unfused route with large batches (k too small or too large for the fused kernel): ragged
+# tails of the 32x32 GEMM tiles in m, n and k; sampled block rows against the oracle
+@pytest.mark.parametrize("p,q,k,batch", [(40, 3, 512, 200), (40, 3, 512, 100), (20, 2, 512, 150), (40, 5, 16, 8000),
+                                         (70, 33, 16, 4100), (3, 2, 8, 9000)])
+def test_fc_forward_unfused_large_batch(p, q, k, batch):
+    w, x, b = rand_fc(p, q, k, batch)
+    y = G.gpu_fc_forward(w, x, b, relu=True)
+    rows = sorted(RNG.choice(p, min(p, 6), replace=False).tolist())
+    y_s = np.concatenate([y[:, i * k:(i + 1) * k] for i in rows], axis=1)
+    check(y_s, O.fc_forward(w, x, b, True, block_rows=rows), f"unfused fwd {p}x{q} k={k} B={batch}")
+
+
+# ---- backward-weights on the LDS-tiled GEMM (taken when q <= 64, p > 32 and enough 64x64 tiles
+# exist): ragged tails in m, n and k, a reduction slice shorter than one k-slab, split-K slices
+# with a tail, the tile shared by the DC and Nyquist bins; the last two shapes take the
+# one-wave-per-tile GEMM with split-K
+@pytest.mark.parametrize("p,q,k,batch", [(40, 40, 512, 300), (40, 3, 512, 130), (70, 33, 16, 5000), (64, 64, 64, 700),
+                                         (40, 70, 16, 5000), (70, 3, 8, 3000)])
+def test_fc_backward_tiled_gemm(p, q, k, batch):
+    w, x, _ = rand_fc(p, q, k, batch, bias=False)
+    dy = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
+    dx, dw = G.gpu_fc_backward(w, x, dy)
+    cols = sorted(RNG.choice(q, min(q, 4), replace=False).tolist())
+    pairs = [(int(i), int(j)) for i, j in zip(RNG.integers(0, p, 24), RNG.integers(0, q, 24))]
+    dx_s = np.concatenate([dx[:, j * k:(j + 1) * k] for j in cols], axis=1)
+    check(dx_s, O.fc_backward_dx(w, dy, block_cols=cols), f"tiled gemm dx {p}x{q} k={k} B={batch}")
+    check(np.stack([dw[i, j] for (i, j) in pairs]), O.fc_backward_dw(x, dy, k, pairs=pairs), f"tiled gemm dw {p}x{q} k={k} B={batch}")
+
+
 # ---- CONV ----------------------------------------------------------------------------------
 @pytest.mark.parametrize("N,p,q,k,H,W,r,pad", [(1, 1, 1, 4, 5, 5, 3, 1), (2, 2, 3, 8, 6, 7, 3, 1), (3, 5, 2, 16, 9, 4, 3, 0),
                                                (2, 1, 2, 64, 7, 7, 1, 0), (1, 2, 2, 32, 8, 8, 5, 2), (2, 4, 4, 64, 14, 14, 3, 1)])
