@@ -37,8 +37,8 @@ MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
 
 # Bytes per launch between L2 and the memory side, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # each scaled by what the counter reads for a plain 256 MiB copy
-# (profiles/fc_fused_kernel_cfg2_pmc_traffic.md): 6.55 MB fetched + 1.05 MB written.
-MEASURED_TRAFFIC_BYTES = 7594433
+# (profiles/fc_fused_kernel_cfg2_pmc_traffic.md): 6.49 MB fetched + 1.05 MB written.
+MEASURED_TRAFFIC_BYTES = 7537095
 
 
 def algorithmic_work(p, q, k, B, bias):
@@ -178,6 +178,44 @@ def main():
     torch.cuda.synchronize()
     ev_graph2, wall_graph2 = timed(graph2.replay)
 
+    # --- floors: kernels without arithmetic, same launch shape (256 workgroups x 512 threads), timed
+    # like the one-stream graph above.  `copy`: every byte of x, of a weight-sized buffer and of y
+    # is touched once (the algorithmic bytes); `same_footprint`: every workgroup loads what a
+    # workgroup of the fused kernel loads (one 128 KB weight tile and two rows of x, shared
+    # between workgroups and XCDs through the same tile map) and stores its 4 KB of y.
+    floors = None
+    floor_path = os.path.join(ROOT, "paper_1708_08917_amd", "libcirc_floor.so")
+    if os.path.exists(floor_path):
+        FL = ctypes.CDLL(floor_path)
+        FL.circ_floor_empty.restype = ctypes.c_int
+        FL.circ_floor_empty.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+        FL.circ_floor_stream.restype = ctypes.c_int
+        FL.circ_floor_stream.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 2 + [ctypes.c_size_t] * 3 + \
+                                        [ctypes.c_int] * 3 + [ctypes.c_void_p]
+        wdummy = torch.zeros(p * q * k, dtype=torch.float32, device=dev)      # size of the weight operand
+        wdp = ctypes.c_void_p(wdummy.data_ptr())
+        nwg, nthr = 256, 512
+        xb, wb, yb = 4 * batch * cfg.n_in, 4 * p * q * k, 4 * batch * cfg.n_out
+
+        def graph_time(launch):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for i in range(K):
+                    if launch((Wm + i) % npairs) != 0:
+                        raise RuntimeError("floor kernel launch failed")
+            g.replay()
+            torch.cuda.synchronize()
+            return timed(g.replay)[0] / K * 1e6
+
+        floors = {
+            "empty_launch_us": graph_time(lambda i: FL.circ_floor_empty(nwg, nthr, sptr)),
+            "copy_algorithmic_bytes_us": graph_time(lambda i: FL.circ_floor_stream(
+                wdp, xp[i], yp[i], nwg, nthr, wb // nwg, xb // nwg, yb // nwg, 0, 0, 0, sptr)),
+            "same_footprint_loads_us": graph_time(lambda i: FL.circ_floor_stream(
+                wdp, xp[i], yp[i], nwg, nthr, wb // 8, xb // 32, yb // nwg, 4, 2, 16, sptr)),
+            "note": "HIP events over a one-stream graph of K launches of 256 workgroups x 512 threads, no arithmetic",
+        }
+
     t_step = ev_graph / K
     alg_bytes, alg_flops = algorithmic_work(p, q, k, batch, True)
     out = {
@@ -211,6 +249,9 @@ def main():
         },
     }
 
+    if floors is not None:
+        out["floors"] = floors
+        out["roofline"]["kernel_us_over_copy_floor_us"] = t_step * 1e6 / floors["copy_algorithmic_bytes_us"]
     if not args.no_cpu_baseline:
         from oracle import circ_oracle as O
         try:

@@ -8,6 +8,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libcirc.so")
 SOURCES = [os.path.join(HERE, "csrc", "circ_api.hip")]
+# measurement helpers of bench.py (launch and memory floors); no layer arithmetic
+FLOOR_LIB_PATH = os.path.join(HERE, "libcirc_floor.so")
+FLOOR_SOURCES = [os.path.join(HERE, "csrc", "circ_floor.hip")]
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 VALU forms are not used on this target
@@ -16,9 +19,9 @@ FLAGS = [
 ]
 
 
-def build_lib(verbose: bool = True) -> str:
+def _compile(out: str, sources, verbose: bool) -> None:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-o", LIB_PATH, *SOURCES]
+    cmd = [hipcc, *FLAGS, "-o", out, *sources]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -27,6 +30,11 @@ def build_lib(verbose: bool = True) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+
+
+def build_lib(verbose: bool = True) -> str:
+    _compile(LIB_PATH, SOURCES, verbose)
+    _compile(FLOOR_LIB_PATH, FLOOR_SOURCES, verbose)
     return LIB_PATH
 
 
