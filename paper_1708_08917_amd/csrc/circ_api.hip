@@ -193,7 +193,7 @@ inline int cgemm_ksplit(int NF, int M, int N, int Kd) {
 #endif
 template <int FM, int WM, int WN>
 hipError_t launch_cgemm_tiled(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, long long sA,
-                              long long sB, long long sC, bool conj_b, hipStream_t s, int ksplit, int kchunk,
+                              long long sB, long long sC, bool conj_b, bool a_t, hipStream_t s, int ksplit, int kchunk,
                               long long part_stride) {
   using Sh = GemmShape<FM, WM, WN>;
   const int ntm = (int)cdiv(M, Sh::TM), ntn = (int)cdiv(N, Sh::TN);
@@ -201,12 +201,14 @@ hipError_t launch_cgemm_tiled(const float2* A, const float2* B, float2* C, int N
   if (ntiles > (1ll << 31) - 8) return hipErrorInvalidValue;
   const long long chunk = cdiv(ntiles, CIRC_GEMM_WGS);
   dim3 grid((unsigned)(cdiv(cdiv(ntiles, chunk), 8) * 8));
-  if (conj_b)
-    hipLaunchKernelGGL((cgemm_tiled_kernel<FM, WM, WN, true>), grid, dim3(256), 0, s, A, B, C, M, N, Kd, NF, sA, sB, sC, ntm,
-                       ntn, ksplit, kchunk, part_stride, (unsigned)ntiles, (unsigned)chunk);
-  else
-    hipLaunchKernelGGL((cgemm_tiled_kernel<FM, WM, WN, false>), grid, dim3(256), 0, s, A, B, C, M, N, Kd, NF, sA, sB, sC, ntm,
-                       ntn, ksplit, kchunk, part_stride, (unsigned)ntiles, (unsigned)chunk);
+#define CIRC_TILED(CJ, AT)                                                                                              \
+  hipLaunchKernelGGL((cgemm_tiled_kernel<FM, WM, WN, CJ, AT>), grid, dim3(256), 0, s, A, B, C, M, N, Kd, NF, sA, sB, sC, ntm, \
+                     ntn, ksplit, kchunk, part_stride, (unsigned)ntiles, (unsigned)chunk)
+  if (conj_b && a_t) CIRC_TILED(true, true);
+  else if (conj_b) CIRC_TILED(true, false);
+  else if (a_t) CIRC_TILED(false, true);
+  else CIRC_TILED(false, false);
+#undef CIRC_TILED
   return hipGetLastError();
 }
 
@@ -222,16 +224,22 @@ hipError_t launch_cgemm_tiled(const float2* A, const float2* B, float2* C, int N
 #ifndef CIRC_GEMM_TILED_MIN
 #define CIRC_GEMM_TILED_MIN 256
 #endif
-hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, long long sA,
-                        long long sB, long long sC, bool conj_b, hipStream_t s, int ksplit = 1,
-                        long long part_stride = 0) {
-  const int kchunk = (int)(cdiv(cdiv(Kd, ksplit), 32) * 32);   // whole operand groups per slice
+inline bool cgemm_takes_tiled(int NF, int M, int N, int Kd, int ksplit) {
   const long long tiles_s = (long long)(NF - 1) * ksplit * cdiv(M, 64) * cdiv(N, 64);
   // the tiled kernel keeps offsets inside one frequency of an operand in 32 bits
   const long long lim = (1ll << 31) - 1;
   const bool fits32 = (long long)Kd * M <= lim && (long long)Kd * N <= lim && (long long)M * N <= lim;
-  if (fits32 && M > 32 && N <= 64 && tiles_s >= CIRC_GEMM_TILED_MIN)
-    return launch_cgemm_tiled<1, 2, 2>(A, B, C, NF, M, N, Kd, sA, sB, sC, conj_b, s, ksplit, kchunk, part_stride);
+  return fits32 && M > 32 && N <= 64 && tiles_s >= CIRC_GEMM_TILED_MIN;
+}
+// a_t: A is stored [f][m][kd] instead of [f][kd][m]; only the tiled kernel reads that layout, so
+// callers pass it only when cgemm_takes_tiled() holds.
+hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, long long sA,
+                        long long sB, long long sC, bool conj_b, hipStream_t s, int ksplit = 1,
+                        long long part_stride = 0, bool a_t = false) {
+  const int kchunk = (int)(cdiv(cdiv(Kd, ksplit), 32) * 32);   // whole operand groups per slice
+  if (cgemm_takes_tiled(NF, M, N, Kd, ksplit))
+    return launch_cgemm_tiled<1, 2, 2>(A, B, C, NF, M, N, Kd, sA, sB, sC, conj_b, a_t, s, ksplit, kchunk, part_stride);
+  if (a_t) return hipErrorInvalidValue;
   bool big = (long long)NF * cdiv(M, 32) * cdiv(N, 32) * ksplit >= 1024;
   int tile = big ? 32 : 16;
   const int ntn = (int)cdiv(N, tile);
@@ -531,6 +539,11 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
 
   // Backward-data is a forward pass on the transposed, conjugated grid (q output block rows,
   // p input blocks, no epilogue): the small-problem kernels serve it from their own sections.
+  const int ksplit = cgemm_ksplit(NF, p, q, batch);
+  // The tiled GEMM reads dY^ in the [f][i][b] order of backward-data, so dy is transformed once
+  // for both results; the one-wave-per-tile GEMM needs the batch-major order [f][b][i].
+  const bool dw_shares_dy = dw && cgemm_takes_tiled(NF, p, q, batch, ksplit);
+  bool have_dyh = false;   // bufy holds dY^[f][i][b]
   if (dx && batch <= 2 && k >= 4) {
     if (launch_gemv(k, blob_at<float2>(w_hat, bl.gemv_bwd), dy, nullptr, dx, q, p, batch, 0, s) != hipSuccess) return CIRC_EHIP;
   } else if (dx && use_fused_forward(q, p, k, batch)) {
@@ -540,20 +553,29 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
     // dY^[f][i][b];  dX^[f][j][b] = sum_i conj(W^)[f][i][j] dY^[f][i][b]
     RowMap mdy{batch, p, (long long)p * k, (long long)k, 0, 1};
     if (launch_rfft(k, false, dy, bufy, mdy, yrows, yfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    have_dyh = true;
     if (launch_cgemm(wb, bufy, bufx, NF, q, batch, p, wfs, yfs, xfs, false, s) != hipSuccess) return CIRC_EHIP;
     RowMap mdx{batch, q, (long long)q * k, (long long)k, 0, 1};
     if (launch_irfft(k, false, bufx, dx, mdx, xrows, xfs, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
   }
   if (dw) {
-    // batch-major spectra: dY^[f][b][i], X^[f][b][j];  dW^[f][i][j] = sum_b dY^[f][b][i] conj(X^[f][b][j])
-    RowMap mdy{p, batch, (long long)k, (long long)p * k, 0, 1};
-    if (launch_rfft(k, false, dy, bufy, mdy, yrows, yfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    // dW^[f][i][j] = sum_b dY^[f][i][b] conj(X^[f][b][j]); X^ is batch-major, dY^ is [f][i][b] for
+    // the tiled GEMM (shared with backward-data above) and batch-major [f][b][i] otherwise
+    if (dw_shares_dy) {
+      if (!have_dyh) {
+        RowMap mdy{batch, p, (long long)p * k, (long long)k, 0, 1};
+        if (launch_rfft(k, false, dy, bufy, mdy, yrows, yfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+      }
+    } else {
+      RowMap mdy{p, batch, (long long)k, (long long)p * k, 0, 1};
+      if (launch_rfft(k, false, dy, bufy, mdy, yrows, yfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    }
     RowMap mx{q, batch, (long long)k, (long long)q * k, 0, 1};
     if (launch_rfft(k, false, x, bufx, mx, xrows, xfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
     // the reduction over the batch is cut into slices; the IFFT adds the partial spectra in order
-    const int ksplit = cgemm_ksplit(NF, p, q, batch);
     const long long wpart = (long long)(align_up(spectrum_elems(k, (long long)p * q) * sizeof(float2), 256) / sizeof(float2));
-    if (launch_cgemm(bufy, bufx, bufw, NF, p, q, batch, yfs, xfs, wfs, true, s, ksplit, wpart) != hipSuccess) return CIRC_EHIP;
+    if (launch_cgemm(bufy, bufx, bufw, NF, p, q, batch, yfs, xfs, wfs, true, s, ksplit, wpart, dw_shares_dy) != hipSuccess)
+      return CIRC_EHIP;
     const long long wrows = (long long)p * q;
     RowMap mw{q, p, (long long)k, (long long)q * k, 0, 1};
     if (launch_irfft(k, false, bufw, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, ksplit, wpart) != hipSuccess)

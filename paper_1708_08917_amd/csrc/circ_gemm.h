@@ -41,7 +41,11 @@ struct GemmShape {
 // the 8 XCDs, each with a private L2).  Split-K: slice ks reduces k in
 // [ks*kchunk, (ks+1)*kchunk) and writes its partial sums to C + ks*part_stride (summed later
 // in a fixed order).
-template <int FM, int WM, int WN, bool CONJ_B>
+// A_T: A is stored [f][m][k] (k fastest, row pitch Kd) instead of [f][k][m]: the slab is then
+// fetched along k and kept in LDS as [m][KT+1]; the odd pitch makes the operand reads (32 lanes
+// along m) hit every bank once.  This lets backward-weights take the spectrum of dy in the
+// layout that backward-data needs, so that dy is transformed once.
+template <int FM, int WM, int WN, bool CONJ_B, bool A_T>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void cgemm_tiled_kernel(const float2* __restrict__ A, const float2* __restrict__ B,
                                                           float2* __restrict__ C, int M, int N, int Kd, int NF,
                                                           long long sA, long long sB, long long sC, int ntm, int ntn,
@@ -49,7 +53,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
                                                           unsigned ntiles, unsigned chunk) {
   using Sh = GemmShape<FM, WM, WN>;
   constexpr int TM = Sh::TM, TN = Sh::TN, KT = Sh::KT, NT = Sh::NT, LA = Sh::LA, LB = Sh::LB;
-  __shared__ float2 sa[KT * TM];
+  constexpr int PA = KT + 1;                       // row pitch of the transposed A slab
+  __shared__ float2 sa[A_T ? TM * PA : KT * TM];
   __shared__ float2 sb[KT * TN];
 
   const unsigned v = (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
@@ -99,20 +104,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
   bool staged_shared = false;
   // Every thread keeps its column of the slab (TM and TN divide the thread count) and walks
   // down the rows; offsets inside one frequency of an operand fit 32 bits (host check).
-  const int col_a = tid % TM, row_a = tid / TM, col_b = tid % TN, row_b = tid / TN;
+  // (A_T: a thread keeps its k and walks down the m rows, NT/KT at a time.)
+  const int col_a = A_T ? tid % KT : tid % TM, row_a = A_T ? tid / KT : tid / TM;
+  const int col_b = tid % TN, row_b = tid / TN;
   auto fetch = [&](const Tile& T, int slab) {
     const int k0 = T.kbeg + slab * KT, klast = max(T.kend - 1, 0);
     keep_a = keep_b = 0;
     staged_shared = T.shared;
-    const int ma = T.m0 + col_a, nb = T.n0 + col_b;
-    const unsigned ca = unsigned(min(ma, M - 1)), cb = unsigned(min(nb, N - 1));
+    const int nb = T.n0 + col_b;
+    const unsigned cb = unsigned(min(nb, N - 1));
     unsigned offa[LA], offb[LB];
+    if constexpr (A_T) {
+      const int k = k0 + col_a;
+      const unsigned ck = unsigned(min(k, klast));
 #pragma unroll
-    for (int e = 0; e < LA; ++e) {
-      const int k = k0 + e * (NT / TM) + row_a;
-      offa[e] = unsigned(min(k, klast)) * unsigned(M) + ca;
-      ra[e] = T.a0[offa[e]];
-      keep_a |= (k < T.kend && ma < M) ? (1u << e) : 0u;
+      for (int e = 0; e < LA; ++e) {
+        const int m = T.m0 + e * (NT / KT) + row_a;
+        offa[e] = unsigned(min(m, M - 1)) * unsigned(Kd) + ck;
+        ra[e] = T.a0[offa[e]];
+        keep_a |= (k < T.kend && m < M) ? (1u << e) : 0u;
+      }
+    } else {
+      const int ma = T.m0 + col_a;
+      const unsigned ca = unsigned(min(ma, M - 1));
+#pragma unroll
+      for (int e = 0; e < LA; ++e) {
+        const int k = k0 + e * (NT / TM) + row_a;
+        offa[e] = unsigned(min(k, klast)) * unsigned(M) + ca;
+        ra[e] = T.a0[offa[e]];
+        keep_a |= (k < T.kend && ma < M) ? (1u << e) : 0u;
+      }
     }
 #pragma unroll
     for (int e = 0; e < LB; ++e) {
@@ -134,7 +155,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
       float2 val = ra[e];
       if (staged_shared) val.y = ra1[e];
       if (!((keep_a >> e) & 1u)) val = make_float2(0.f, 0.f);
-      sa[e * NT + tid] = val;
+      if constexpr (A_T) sa[(e * (NT / KT) + row_a) * PA + col_a] = val;
+      else sa[e * NT + tid] = val;
     }
 #pragma unroll
     for (int e = 0; e < LB; ++e) {
@@ -145,7 +167,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
     }
   };
 
-  const float2* pa = sa + (lane >> 5) * TM + wm * 32 * FM + (lane & 31);
+  // operand element (k = 2*kk + lane/32, m = lane%32 of sub-tile fm) sits at pa[kk*KSA + fm*FSA]
+  const float2* pa = A_T ? sa + (wm * 32 * FM + (lane & 31)) * PA + (lane >> 5)
+                         : sa + (lane >> 5) * TM + wm * 32 * FM + (lane & 31);
+  constexpr int KSA = A_T ? 2 : 2 * TM, FSA = A_T ? 32 * PA : 32;
   const float2* pb = sb + (lane >> 5) * TN + wn * 32 + (lane & 31);
 
   // accumulator layout of a 32x32 tile: column = lane % 32; row = 8*(r/4) + 4*(lane/32) + r%4
@@ -189,7 +214,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
       if (CONJ_B) b.y = -b.y;
 #pragma unroll
       for (int fm = 0; fm < FM; ++fm) {
-        const float2 a = pa[2 * kk * TM + fm * 32];
+        const float2 a = pa[kk * KSA + fm * FSA];
         // (ar + i ai)(br + i bi) = (ar br - ai bi) + i (ar bi + ai br)
         const float a2 = sh ? (CONJ_B ? -a.y : a.y) : a.x, a3 = sh ? 0.f : -a.y, a4 = sh ? 0.f : a.y;
         accR[fm] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, accR[fm], 0, 0, 0);

@@ -149,6 +149,10 @@ def test_fc_backward_tiled_gemm(p, q, k, batch):
     dx_s = np.concatenate([dx[:, j * k:(j + 1) * k] for j in cols], axis=1)
     check(dx_s, O.fc_backward_dx(w, dy, block_cols=cols), f"tiled gemm dx {p}x{q} k={k} B={batch}")
     check(np.stack([dw[i, j] for (i, j) in pairs]), O.fc_backward_dw(x, dy, k, pairs=pairs), f"tiled gemm dw {p}x{q} k={k} B={batch}")
+    # dw alone transforms dy itself (with dx it reuses the spectrum made for backward-data)
+    none, dw_only = G.gpu_fc_backward(w, x, dy, need_dx=False)
+    assert none is None
+    np.testing.assert_array_equal(dw_only, dw)
 
 
 # ---- CONV ----------------------------------------------------------------------------------
