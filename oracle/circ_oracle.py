@@ -29,7 +29,10 @@ Parity pins: all functions below are pinned (see tests/test_oracle_pins.py):
 circulant definition, shift direction, DFT diagonalisation, brute-force
 circular convolution, exact integers, k = 1 dense layer, p = q = 1 library
 circular convolution, finite differences and bilinear identities for the
-gradients, library convolution and single-pixel response for CONV.
+gradients, library convolution and single-pixel response for CONV; the CONV
+gradients and the bias gradient by finite differences, the library's own
+convolution gradients, the bilinear identities and the r = 1 reduction to the
+FC gradients.
 """
 from __future__ import annotations
 
@@ -157,6 +160,72 @@ def conv_forward(w, x, bias=None, relu=False, pad=0) -> np.ndarray:
     if relu:
         y = np.maximum(y, 0.0)
     return y
+
+
+def conv_backward_dx(w, dy, H, W, pad=0) -> np.ndarray:
+    """dL/dx of the block-circulant CONV layer (chain rule through Eq. 6; Sec. 3.2 notes that
+    training of CONV layers follows the FC derivation).
+
+    y[n, co, ho, wo] takes x[n, ci, ho + dh - pad, wo + dw - pad] with weight
+    Wd[dh, dw][co, ci], so every (dh, dw) scatters Wd[dh, dw]^T dy[n, :, ho, wo] back to that
+    input pixel; positions in the zero padding receive nothing.
+    w[r][r][p][q][k], dy[N][C_out][Ho][Wo] -> dx[N][C_in][H][W].
+    """
+    w = np.asarray(w, dtype=np.float64)
+    dy = np.asarray(dy, dtype=np.float64)
+    r = w.shape[0]
+    p, q, k = w.shape[2:]
+    N, C_out, Ho, Wo = dy.shape
+    assert C_out == p * k and Ho == H + 2 * pad - r + 1 and Wo == W + 2 * pad - r + 1
+    C_in = q * k
+    dxp = np.zeros((N, C_in, H + 2 * pad, W + 2 * pad), dtype=np.float64)
+    for dh in range(r):
+        for dw in range(r):
+            M = expand_block_circulant(w[dh, dw])        # C_out x C_in
+            g = np.matmul(M.T, dy.reshape(N, C_out, Ho * Wo)).reshape(N, C_in, Ho, Wo)
+            dxp[:, :, dh:dh + Ho, dw:dw + Wo] += g
+    return dxp[:, :, pad:pad + H, pad:pad + W].copy()
+
+
+def conv_backward_dw(x, dy, k, r, pad=0) -> np.ndarray:
+    """dL/dw of the block-circulant CONV layer, summed over images and pixels.
+
+    For every offset the gradient of the dense channel-mixing matrix is
+    G[dh, dw] = sum_{n, ho, wo} dy[n, :, ho, wo] xpad[n, :, ho + dh, wo + dw]^T, and, as for
+    FC layers (Eq. 4), dw[dh][dw][i][j][t] collects the entries of block (i, j) that hold
+    that weight: sum_a G_ij[a][(a - t) mod k].
+    x[N][C_in][H][W], dy[N][C_out][Ho][Wo] -> dw[r][r][p][q][k].
+    """
+    x = np.asarray(x, dtype=np.float64)
+    dy = np.asarray(dy, dtype=np.float64)
+    N, C_in, H, W = x.shape
+    _, C_out, Ho, Wo = dy.shape
+    assert Ho == H + 2 * pad - r + 1 and Wo == W + 2 * pad - r + 1
+    p, q = C_out // k, C_in // k
+    xp = np.zeros((N, C_in, H + 2 * pad, W + 2 * pad), dtype=np.float64)
+    xp[:, :, pad:pad + H, pad:pad + W] = x
+    a = np.arange(k).reshape(k, 1)
+    t = np.arange(k).reshape(1, k)
+    col = (a - t) % k
+    dyf = dy.transpose(1, 0, 2, 3).reshape(C_out, N * Ho * Wo)
+    dw = np.empty((r, r, p, q, k), dtype=np.float64)
+    for dh in range(r):
+        for dw_ in range(r):
+            win = xp[:, :, dh:dh + Ho, dw_:dw_ + Wo].transpose(1, 0, 2, 3).reshape(C_in, N * Ho * Wo)
+            G = np.matmul(dyf, win.T)                    # C_out x C_in
+            for i in range(p):
+                for j in range(q):
+                    Gb = G[i * k:(i + 1) * k, j * k:(j + 1) * k]
+                    dw[dh, dw_, i, j] = Gb[a, col].sum(axis=0)
+    return dw
+
+
+def bias_grad(dy, channel_axis=1) -> np.ndarray:
+    """dL/dtheta (Eq. 1: a = Wx + theta, so the gradient of theta is dL/da summed over
+    everything but the channel axis): dy[B][m] -> db[m]; dy[N][C][H][W] -> db[C]."""
+    dy = np.asarray(dy, dtype=np.float64)
+    axes = tuple(ax for ax in range(dy.ndim) if ax != channel_axis)
+    return dy.sum(axis=axes)
 
 
 def max_norm_rel_err(got, ref) -> float:

@@ -236,6 +236,95 @@ def test_conv_single_pixel_response():
     assert np.count_nonzero(y) <= r * r * k
 
 
+# ---- CONV gradients and the bias gradient ---------------------------------------------------
+def _dense_filter_bank(w):
+    """Wd[co][ci][dh][dw] built entry by entry (own loop, not the oracle's expansion)."""
+    r, _, p, q, k = w.shape
+    Wd = np.zeros((p * k, q * k, r, r))
+    for dh in range(r):
+        for dw in range(r):
+            for i in range(p):
+                for j in range(q):
+                    for a in range(k):
+                        for b in range(k):
+                            Wd[i * k + a, j * k + b, dh, dw] = w[dh, dw, i, j, (a - b) % k]
+    return Wd
+
+
+@pytest.mark.parametrize("k,r,pad", [(1, 3, 1), (4, 3, 1), (4, 3, 0), (2, 3, 2), (3, 1, 0), (2, 5, 2)])
+def test_conv_gradients_vs_library_autograd(k, r, pad):
+    """The library's own convolution gradients (float64 autograd through conv2d on the dense
+    filter bank), folded onto the block vectors by an explicit loop over the bank entries."""
+    p, q, N, H, W = 2, 3, 2, 6, 5
+    w = RNG.standard_normal((r, r, p, q, k))
+    x = RNG.standard_normal((N, q * k, H, W))
+    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    dy = RNG.standard_normal((N, p * k, Ho, Wo))
+    xt = torch.from_numpy(x).requires_grad_(True)
+    Wt = torch.from_numpy(_dense_filter_bank(w)).requires_grad_(True)
+    bt = torch.zeros(p * k, dtype=torch.float64, requires_grad=True)
+    y = torch.nn.functional.conv2d(xt, Wt, bt, stride=1, padding=pad)
+    (y * torch.from_numpy(dy)).sum().backward()
+    np.testing.assert_allclose(O.conv_backward_dx(w, dy, H, W, pad), xt.grad.numpy(), atol=1e-11)
+    gW = Wt.grad.numpy()
+    ref_dw = np.zeros_like(w)
+    for dh in range(r):
+        for dw in range(r):
+            for i in range(p):
+                for j in range(q):
+                    for a in range(k):
+                        for b in range(k):
+                            ref_dw[dh, dw, i, j, (a - b) % k] += gW[i * k + a, j * k + b, dh, dw]
+    np.testing.assert_allclose(O.conv_backward_dw(x, dy, k, r, pad), ref_dw, atol=1e-11)
+    np.testing.assert_allclose(O.bias_grad(dy), bt.grad.numpy(), atol=1e-12)
+
+
+def test_conv_gradients_finite_differences_and_bilinear_identities():
+    p, q, k, r, pad, N, H, W = 2, 2, 4, 3, 1, 2, 4, 5
+    w = RNG.standard_normal((r, r, p, q, k))
+    x = RNG.standard_normal((N, q * k, H, W))
+    dy = RNG.standard_normal((N, p * k, H, W))
+    loss = lambda w_, x_: float(np.sum(dy * O.conv_forward(w_, x_, pad=pad)))
+    dx, dw = O.conv_backward_dx(w, dy, H, W, pad), O.conv_backward_dw(x, dy, k, r, pad)
+    eps = 1e-6
+    pick = np.random.default_rng(7)
+    for _ in range(12):
+        idx = tuple(int(pick.integers(0, n)) for n in x.shape)
+        xp_, xm_ = x.copy(), x.copy(); xp_[idx] += eps; xm_[idx] -= eps
+        assert abs((loss(w, xp_) - loss(w, xm_)) / (2 * eps) - dx[idx]) < 1e-6
+        idw = tuple(int(pick.integers(0, n)) for n in w.shape)
+        wp_, wm_ = w.copy(), w.copy(); wp_[idw] += eps; wm_[idw] -= eps
+        assert abs((loss(wp_, x) - loss(wm_, x)) / (2 * eps) - dw[idw]) < 1e-6
+    # y is bilinear in (w, x): <dy, y> = <dx, x> = <dw, w>
+    s = loss(w, x)
+    assert abs(np.sum(dx * x) - s) < 1e-10 * max(1.0, abs(s))
+    assert abs(np.sum(dw * w) - s) < 1e-10 * max(1.0, abs(s))
+
+
+def test_conv_gradients_r1_reduce_to_fc_gradients():
+    p, q, k, N, H, W = 2, 3, 4, 2, 3, 5
+    w = RNG.standard_normal((1, 1, p, q, k))
+    x = RNG.standard_normal((N, q * k, H, W))
+    dy = RNG.standard_normal((N, p * k, H, W))
+    pix_x = x.transpose(0, 2, 3, 1).reshape(N * H * W, q * k)
+    pix_dy = dy.transpose(0, 2, 3, 1).reshape(N * H * W, p * k)
+    ref_dx = O.fc_backward_dx(w[0, 0], pix_dy).reshape(N, H, W, q * k).transpose(0, 3, 1, 2)
+    np.testing.assert_allclose(O.conv_backward_dx(w, dy, H, W, 0), ref_dx, atol=1e-12)
+    np.testing.assert_allclose(O.conv_backward_dw(x, dy, k, 1, 0)[0, 0], O.fc_backward_dw(pix_x, pix_dy, k), atol=1e-12)
+
+
+def test_bias_grad_closed_forms():
+    dy = RNG.standard_normal((5, 12))
+    np.testing.assert_allclose(O.bias_grad(dy), np.ones(5) @ dy, atol=1e-13)      # FC: column sums
+    g = np.zeros((3, 4, 2, 2)); g[:, 2] = 1.5                                      # CONV: count of pixels x images
+    np.testing.assert_array_equal(O.bias_grad(g), np.array([0, 0, 1.5 * 3 * 4, 0]))
+    # finite difference of L = sum(dy * (a + theta)) in theta is the same sum
+    a = RNG.standard_normal((5, 12)); theta = RNG.standard_normal(12); eps = 1e-6
+    L = lambda th: float(np.sum(dy * (a + th)))
+    e3 = np.zeros(12); e3[3] = eps
+    assert abs((L(theta + e3) - L(theta - e3)) / (2 * eps) - O.bias_grad(dy)[3]) < 1e-6
+
+
 def test_error_measure():
     ref = np.array([1.0, -4.0, 0.0]); got = np.array([1.0, -4.0, 0.002])
     assert abs(O.max_norm_rel_err(got, ref) - 0.0005) < 1e-15
