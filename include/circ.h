@@ -120,6 +120,43 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
                               int r, int stride, int pad, int k, int epilogue,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* Workspace size of circ_conv_backward for the same arguments (0 for invalid ones). */
+size_t circ_conv_backward_workspace_bytes(int N, int C_in, int C_out, int H, int W,
+                                          int r, int stride, int pad, int k);
+
+/*
+ * Block-circulant CONV backward.  Sec. 3.2 gives the forward pass (Eq. 6, Eq. 7) and notes
+ * that training is formulated like the FC case (Algorithm 2); these are the chain-rule
+ * gradients of circ_conv_forward with respect to its input and its block vectors.  `dy` is
+ * the gradient with respect to the pre-activation (the caller applies the ReLU mask).
+ *   dx[n][ci][h][w]     = sum_{dh,dw,co} Wd[dh][dw][co][ci] * dy[n][co][h-dh+pad][w-dw+pad]   (may be NULL)
+ *   dw[dh][dw][i][j][t] = sum over images, output pixels and a of
+ *                         dy[n][i*k+a][ho][wo] * x[n][j*k+((a-t) mod k)][ho+dh-pad][wo+dw-pad]  (may be NULL)
+ * (terms outside the image are zero).  Both are overwritten, not accumulated, summed over the
+ * batch without 1/N, and deterministic (no floating-point atomics).
+ *   w_hat  from circ_precompute_spectra with n_grids = r*r, p = C_out/k, q = C_in/k
+ *   x      device, NCHW [N][C_in][H][W]                    (needed for dw only)
+ *   dy     device, NCHW [N][C_out][H+2*pad-r+1][W+2*pad-r+1]
+ *   dx     device, NCHW like x;  dw device, [r][r][p][q][k]
+ *   workspace  at least circ_conv_backward_workspace_bytes(...) bytes
+ * stride must be 1 and r odd (CIRC_ENOTSUP otherwise); 0 <= pad < r.
+ */
+circ_status circ_conv_backward(const void* w_hat, const float* x, const float* dy,
+                               float* dx, float* dw,
+                               int N, int C_in, int C_out, int H, int W,
+                               int r, int stride, int pad, int k,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Bias gradient (Eq. 1: a = Wx + theta, so dL/dtheta is dL/da summed over everything but the
+ * channel).  dy is viewed as [outer][channels][inner]:
+ *   db[c] = sum_{o, t} dy[(o*channels + c)*inner + t]
+ * FC: outer = batch, channels = p*k, inner = 1.  CONV (NCHW): outer = N, channels = C_out,
+ * inner = Ho*Wo.  db is overwritten; the sum order is fixed (deterministic).  No workspace.
+ */
+circ_status circ_bias_grad(const float* dy, float* db, long long outer, int channels,
+                           long long inner, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -32,6 +32,9 @@ SIGNATURES = {
                                   _c_ptr, _c_size, _c_ptr]),
     "circ_conv_workspace_bytes": (_c_size, [_c_int] * 9),
     "circ_conv_forward": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr] + [_c_int] * 10 + [_c_ptr, _c_size, _c_ptr]),
+    "circ_conv_backward_workspace_bytes": (_c_size, [_c_int] * 9),
+    "circ_conv_backward": (_c_int, [_c_ptr] * 5 + [_c_int] * 9 + [_c_ptr, _c_size, _c_ptr]),
+    "circ_bias_grad": (_c_int, [_c_ptr, _c_ptr, ctypes.c_longlong, _c_int, ctypes.c_longlong, _c_ptr]),
 }
 
 
@@ -138,3 +141,37 @@ def circ_conv_forward(w_hat, x, bias, y, C_out, r, stride, pad, k, epilogue=EPI_
     _check(lib().circ_conv_forward(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), N, C_in, C_out, H, W, r, stride, pad,
                                    k, epilogue, _ptr(workspace), workspace.numel(), _stream()), "circ_conv_forward")
     return y
+
+
+def circ_conv_backward_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k) -> int:
+    return lib().circ_conv_backward_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
+
+
+def circ_conv_backward(w_hat, x, dy, C_in, H, W, r, stride, pad, k, need_dx=True, need_dw=True, dx=None, dw=None,
+                       workspace=None):
+    """dy: NCHW [N][C_out][Ho][Wo] -> (dx NCHW [N][C_in][H][W] or None, dw [r][r][p][q][k] or None)."""
+    N, C_out = dy.shape[0], dy.shape[1]
+    p, q = C_out // k, C_in // k
+    if need_dx and dx is None:
+        dx = torch.empty(N, C_in, H, W, dtype=torch.float32, device=dy.device)
+    if need_dw and dw is None:
+        dw = torch.empty(r, r, p, q, k, dtype=torch.float32, device=dy.device)
+    if workspace is None:
+        nb = circ_conv_backward_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
+        workspace = torch.empty(max(1, nb), dtype=torch.uint8, device=dy.device)
+    _check(lib().circ_conv_backward(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx if need_dx else None),
+                                    _ptr(dw if need_dw else None), N, C_in, C_out, H, W, r, stride, pad, k,
+                                    _ptr(workspace), workspace.numel(), _stream()), "circ_conv_backward")
+    return (dx if need_dx else None), (dw if need_dw else None)
+
+
+def circ_bias_grad(dy, db=None):
+    """dy: [batch][m] (FC) or NCHW (CONV) -> db: [m] or [C]."""
+    channels = dy.shape[1]
+    outer = dy.shape[0]
+    inner = int(dy.numel() // (outer * channels))
+    if db is None:
+        db = torch.empty(channels, dtype=torch.float32, device=dy.device)
+    _check(lib().circ_bias_grad(_ptr(dy), _ptr(db), outer, channels, inner, _stream()), "circ_bias_grad")
+    return db
+

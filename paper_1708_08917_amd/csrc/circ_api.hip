@@ -10,6 +10,7 @@
 #include "circ_fused.h"
 #include "circ_gemv.h"
 #include "circ_conv_fused.h"
+#include "circ_conv_bwd.h"
 
 namespace {
 
@@ -721,7 +722,7 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
     const long long npix = (long long)N * HWo;
     dim3 grid((unsigned)cdiv(npix, 256), (unsigned)NF, (unsigned)cdiv(p, IT));
     hipLaunchKernelGGL((conv_contract_kernel<IT>), grid, dim3(256), 0, s, static_cast<const float2*>(w_hat), xh, yh,
-                       p, q, NF, N, H, W, Ho, Wo, r, pad);
+                       p, q, NF, N, H, W, Ho, Wo, r, pad, 0);
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
   }
   RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo};
@@ -729,6 +730,113 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
                    (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
     return CIRC_EHIP;
   return CIRC_OK;
+}
+
+
+// Output pixels per block of conv_dw_kernel: at least 2048 (so that the block-wide sum at the
+// end stays small beside the pixel loop) and at most 16 chunks (their partial spectra are added
+// one after the other by the inverse FFT).
+static long long conv_dw_pix_per_block(long long npix) {
+  long long ppb = 2048;
+  while (cdiv(npix, ppb) > 16) ppb *= 2;
+  return ppb;
+}
+
+size_t circ_conv_backward_workspace_bytes(int N, int C_in, int C_out, int H, int W, int r, int stride, int pad, int k) {
+  if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k) || stride != 1 || (r % 2) == 0) return 0;
+  const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
+  const int p = C_out / k, q = C_in / k;
+  const size_t xa = align_up(spectrum_elems(k, (long long)q * N * H * W) * sizeof(float2), 256);
+  const size_t ya = align_up(spectrum_elems(k, (long long)p * N * Ho * Wo) * sizeof(float2), 256);
+  const long long npix = (long long)N * Ho * Wo;
+  const size_t wa = align_up(spectrum_elems(k, (long long)r * r * p * q) * sizeof(float2), 256);
+  return xa + ya + wa * size_t(cdiv(npix, conv_dw_pix_per_block(npix)));
+}
+
+circ_status circ_conv_backward(const void* w_hat, const float* x, const float* dy, float* dx, float* dw, int N, int C_in,
+                               int C_out, int H, int W, int r, int stride, int pad, int k, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k)) return CIRC_EINVAL;
+  if (stride <= 0) return CIRC_EINVAL;
+  if (stride != 1 || (r % 2) == 0) return CIRC_ENOTSUP;
+  if (!w_hat || !dy || (!dx && !dw) || (dw && !x)) return CIRC_EINVAL;
+  if (!aligned16(w_hat) || !aligned16(dy) || !aligned16(x) || !aligned16(dx) || !aligned16(dw)) return CIRC_EINVAL;
+  const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
+  const int p = C_out / k, q = C_in / k, NF = k / 2 + 1;
+  // offsets inside one frequency of a spectrum are kept in 32 bits; grid.z holds tiles x offsets
+  if ((long long)p * N * Ho * Wo > (1ll << 31) - 1 || (long long)r * r * cdiv(p, 4) * cdiv(q, 4) > 65535) return CIRC_EINVAL;
+  const size_t xbytes = size_t(N) * C_in * H * W * sizeof(float), ybytes = size_t(N) * C_out * Ho * Wo * sizeof(float);
+  const size_t wbytes = size_t(r) * r * p * q * k * sizeof(float);
+  if (dx && (overlaps(dx, xbytes, dy, ybytes) || (x && overlaps(dx, xbytes, x, xbytes)))) return CIRC_EINVAL;
+  if (dw && (overlaps(dw, wbytes, dy, ybytes) || overlaps(dw, wbytes, x, xbytes))) return CIRC_EINVAL;
+  if (dx && dw && overlaps(dx, xbytes, dw, wbytes)) return CIRC_EINVAL;
+  const size_t need = circ_conv_backward_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k);
+  if (!workspace || workspace_bytes < need) return CIRC_EWORKSPACE;
+  if (!aligned16(workspace)) return CIRC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  const long long HW = (long long)H * W, HWo = (long long)Ho * Wo;
+  const long long xrows = (long long)q * N * HW, yrows = (long long)p * N * HWo;
+  const size_t xa = align_up(spectrum_elems(k, xrows) * sizeof(float2), 256);
+  const size_t ya = align_up(spectrum_elems(k, yrows) * sizeof(float2), 256);
+  float2* xh = static_cast<float2*>(workspace);
+  float2* yh = reinterpret_cast<float2*>(static_cast<char*>(workspace) + xa);
+  float2* wpart = reinterpret_cast<float2*>(static_cast<char*>(workspace) + xa + ya);
+  const BlobLayout bl = blob_layout(r * r, p, q, k);
+
+  // dY^[f][i][n][pixel]: the FFT runs down the channel axis of dy
+  RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo};
+  if (launch_rfft(k, true, dy, yh, my, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+  RowMap mx{(int)HW, N, 1, (long long)C_in * HW, (long long)k * HW, HW};
+  if (dx) {
+    // forward contraction on the transposed, conjugated section with reflected offsets:
+    // q output blocks, p input blocks, input image Ho x Wo, output image H x W, padding r-1-pad
+    constexpr int IT = 4;
+    const long long npix = (long long)N * HW;
+    dim3 grid((unsigned)cdiv(npix, 256), (unsigned)NF, (unsigned)cdiv(q, IT));
+    hipLaunchKernelGGL((conv_contract_kernel<IT>), grid, dim3(256), 0, s, blob_at<float2>(w_hat, bl.bwd), yh, xh, q, p,
+                       NF, N, Ho, Wo, H, W, r, r - 1 - pad, 1);
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+    if (launch_irfft(k, true, xh, dx, mx, xrows, xrows, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
+  }
+  if (dw) {
+    if (launch_rfft(k, true, x, xh, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    const long long npix = (long long)N * HWo, ppb = conv_dw_pix_per_block(npix);
+    const int nchunks = (int)cdiv(npix, ppb);
+    const long long wrows = (long long)r * r * p * q;
+    const long long wstride = (long long)(align_up(spectrum_elems(k, wrows) * sizeof(float2), 256) / sizeof(float2));
+    if (r % 3 == 0) {   // three consecutive offsets (for r = 3: one filter row) per block, 4 x 4 tiles of blocks
+      constexpr int IT = 4, JT = 4, NG = 3;
+      dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(cdiv(r * r, NG) * cdiv(p, IT) * cdiv(q, JT)));
+      hipLaunchKernelGGL((conv_dw_kernel<IT, JT, NG>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo, r,
+                         pad, ppb, wstride);
+    } else {            // one offset per block
+      constexpr int IT = 4, JT = 4;
+      dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r * cdiv(p, IT) * cdiv(q, JT)));
+      hipLaunchKernelGGL((conv_dw_kernel<IT, JT, 1>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo, r,
+                         pad, ppb, wstride);
+    }
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+    // dw[g][i][j][:] = IFFT over f of the summed partial spectra, scale 1/k
+    RowMap mw{(int)wrows, 1, (long long)k, 0, 0, 1};
+    if (launch_irfft(k, false, wpart, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, nchunks, wstride) != hipSuccess)
+      return CIRC_EHIP;
+  }
+  return CIRC_OK;
+}
+
+circ_status circ_bias_grad(const float* dy, float* db, long long outer, int channels, long long inner, void* stream) {
+  if (!dy || !db || outer <= 0 || channels <= 0 || inner <= 0) return CIRC_EINVAL;
+  if (!aligned16(dy) || !aligned16(db)) return CIRC_EINVAL;
+  if (outer > (1ll << 40) / channels / inner) return CIRC_EINVAL;
+  const size_t ybytes = size_t(outer) * channels * inner * sizeof(float);
+  if (overlaps(db, size_t(channels) * sizeof(float), dy, ybytes)) return CIRC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (inner == 1)
+    hipLaunchKernelGGL(bias_grad_column_kernel, dim3((unsigned)cdiv(channels, 64)), dim3(256), 0, s, dy, db, outer, channels);
+  else
+    hipLaunchKernelGGL(bias_grad_channel_kernel, dim3((unsigned)channels), dim3(256), 0, s, dy, db, outer, channels, inner);
+  return hipGetLastError() == hipSuccess ? CIRC_OK : CIRC_EHIP;
 }
 
 }  // extern "C"

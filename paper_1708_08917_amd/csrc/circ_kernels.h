@@ -317,10 +317,12 @@ __global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
 //   Yh[f][i][n][ho][wo] = sum_{dh,dw,j} What[dh*r+dw][f][j][i] * Xh[f][j][n][ho+dh-pad][wo+dw-pad]
 // with zero spectra outside the image (the channel FFT of a zero pixel is zero, so the
 // spatial shift is taken after the transform and every input pixel is transformed once).
+// flip: offset (dh, dw) takes the weights of offset (r-1-dh, r-1-dw) - the reflected filter of
+// backward-data, whose operand is the conjugated, transposed section and whose padding is r-1-pad.
 template <int IT>
 __global__ void conv_contract_kernel(const float2* __restrict__ What, const float2* __restrict__ Xh,
                                      float2* __restrict__ Yh, int p, int q, int NF, int Nimg, int H,
-                                     int W, int Ho, int Wo, int r, int pad) {
+                                     int W, int Ho, int Wo, int r, int pad, int flip) {
   const long long npix = (long long)Nimg * Ho * Wo;
   const long long opix = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (opix >= npix) return;
@@ -334,7 +336,8 @@ __global__ void conv_contract_kernel(const float2* __restrict__ What, const floa
     for (int dw = 0; dw < r; ++dw) {
       const int hi = ho + dh - pad, wi = wo + dw - pad;
       const bool inb = hi >= 0 && hi < H && wi >= 0 && wi < W;
-      const float2* wg = What + ((long long)(dh * r + dw) * NF + f) * q * p;
+      const int g = flip ? r * r - 1 - (dh * r + dw) : dh * r + dw;
+      const float2* wg = What + ((long long)g * NF + f) * q * p;
       for (int j = 0; j < q; ++j) {
         float2 xv = make_float2(0.f, 0.f);
         if (inb) xv = Xh[(((long long)f * q + j) * Nimg + n) * H * W + hi * W + wi];

@@ -4,7 +4,8 @@
 
 Configurations: cfg1 (FC 1024x1024, k=16, batch 1), cfg2 (FC 4096x4096, k=64, batch 64),
 cfg3 (9216->4096->4096 head, k=128, batch 256, both layers), cfg4 (3x3 CONV 256->256, 28x28,
-batch 32, k=64), cfg5 (FC 16384x16384, k=256, batch 1024; --backward adds dx and dw).
+batch 32, k=64; --backward adds dx, dw and the bias gradient), cfg5 (FC 16384x16384, k=256,
+batch 1024; --backward adds dx and dw).
 Prints one line per layer with the time per call and the algorithmic bytes/flops rates.
 This is the companion of bench.py for the workloads that bench.py does not time; it is also
 the program that the rocprofv3 summaries under profiles/ were collected with.
@@ -76,7 +77,7 @@ def bench_fc(cfg, reps, backward=False):
               f"{4.0 * cfg.n_in * cfg.n_out * cfg.batch / tb * 1e-6:7.1f} TFLOP/s", flush=True)
 
 
-def bench_conv(cfg, reps):
+def bench_conv(cfg, reps, backward=False):
     w, x = synth.conv_inputs(cfg)
     wd, xd = torch.from_numpy(w).to(DEV), torch.from_numpy(x).to(DEV)
     wh = B.circ_precompute_spectra(wd)
@@ -88,6 +89,19 @@ def bench_conv(cfg, reps):
     dense = 2.0 * cfg.N * cfg.H * cfg.W * cfg.r * cfg.r * cfg.C_in * cfg.C_out
     print(f"{cfg.name}: forward {t:9.2f} us/call  {cfg.N / t * 1e6:10.0f} images/s  alg {byts / t * 1e-3:7.1f} GB/s  "
           f"dense-equivalent {dense / t * 1e-6:7.1f} TFLOP/s", flush=True)
+    if backward:
+        dy = torch.from_numpy(synth.conv_upstream_grad(cfg)).to(DEV)
+        dx, dw, db = torch.empty_like(xd), torch.empty_like(wd), torch.empty(cfg.C_out, device=DEV)
+        nwb = B.circ_conv_backward_workspace_bytes(cfg.N, cfg.C_in, cfg.C_out, cfg.H, cfg.W, cfg.r, 1, cfg.pad, cfg.k)
+        wsb = torch.empty(nwb, dtype=torch.uint8, device=DEV)
+        args = (wh, xd, dy, cfg.C_in, cfg.H, cfg.W, cfg.r, 1, cfg.pad, cfg.k)
+        r = max(5, reps // 4)
+        tb = _time(lambda: B.circ_conv_backward(*args, True, True, dx, dw, wsb), r, 3)
+        tdx = _time(lambda: B.circ_conv_backward(*args, True, False, dx, None, wsb), r, 3)
+        tdw = _time(lambda: B.circ_conv_backward(*args, False, True, None, dw, wsb), r, 3)
+        tdb = _time(lambda: B.circ_bias_grad(dy, db), r, 3)
+        print(f"{cfg.name}: backward {tb:9.2f} us/call (dx only {tdx:.2f}, dw only {tdw:.2f}; bias gradient {tdb:.2f})  "
+              f"dense-equivalent {2.0 * dense / tb * 1e-6:7.1f} TFLOP/s", flush=True)
 
 
 def main():
@@ -105,7 +119,7 @@ def main():
         bench_fc(synth.CFG3_L1, a.reps)
         bench_fc(synth.CFG3_L2, a.reps)
     if sel("cfg4"):
-        bench_conv(synth.CFG4, a.reps)
+        bench_conv(synth.CFG4, a.reps, backward=a.backward or a.config == "all")
     if sel("cfg5"):
         bench_fc(synth.CFG5, max(10, a.reps // 4), backward=a.backward or a.config == "all")
 

@@ -151,3 +151,12 @@ def conv_inputs(cfg: ConvConfig, seed_offset: int = 0, batch: int | None = None)
     w = normal(seed, T_W, (cfg.r, cfg.r, cfg.p, cfg.q, cfg.k), 2.0 / (cfg.r * cfg.r * cfg.C_in))
     x = uniform(seed, T_X, (N, cfg.C_in, cfg.H, cfg.W), -1.0, 1.0)
     return w, x
+
+
+def conv_upstream_grad(cfg: ConvConfig, seed_offset: int = 0, batch: int | None = None):
+    """dL/da [N][C_out][Ho][Wo], Uniform[-1, 1] (the CONV counterpart of fc_upstream_grad)."""
+    seed = BASE_SEED + cfg.index + 1000 * seed_offset
+    N = cfg.N if batch is None else batch
+    Ho, Wo = cfg.H + 2 * cfg.pad - cfg.r + 1, cfg.W + 2 * cfg.pad - cfg.r + 1
+    return uniform(seed, T_DY, (N, cfg.C_out, Ho, Wo), -1.0, 1.0)
+

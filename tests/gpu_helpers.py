@@ -37,3 +37,19 @@ def gpu_conv_forward(w, x, bias=None, relu=False, pad=0):
     y = B.circ_conv_forward(wh, dev(x), dev(bias), None, p * k, r, 1, pad, k, epi_flags(bias, relu))
     torch.cuda.synchronize()
     return y.cpu().numpy()
+
+
+def gpu_conv_backward(w, x, dy, pad=0, need_dx=True, need_dw=True):
+    r, _, p, q, k = w.shape
+    N, C_in, H, W = x.shape
+    wh = B.circ_precompute_spectra(dev(w))
+    dx, dw = B.circ_conv_backward(wh, dev(x), dev(dy), C_in, H, W, r, 1, pad, k, need_dx, need_dw)
+    torch.cuda.synchronize()
+    return (None if dx is None else dx.cpu().numpy()), (None if dw is None else dw.cpu().numpy())
+
+
+def gpu_bias_grad(dy):
+    db = B.circ_bias_grad(dev(dy))
+    torch.cuda.synchronize()
+    return db.cpu().numpy()
+

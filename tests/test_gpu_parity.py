@@ -181,6 +181,54 @@ def _conv_case(N, p, q, k, H, W, r, pad):
     check(G.gpu_conv_forward(w, x, b, True, pad), O.conv_forward(w, x, b, True, pad), "conv bias+relu")
 
 
+# ---- CONV backward and the bias gradient ----------------------------------------------------
+@pytest.mark.parametrize("N,p,q,k,H,W,r,pad", [(1, 1, 1, 4, 5, 5, 3, 1), (2, 2, 3, 8, 6, 7, 3, 1), (3, 5, 2, 16, 9, 4, 3, 0),
+                                               (2, 1, 2, 64, 7, 7, 1, 0), (1, 2, 2, 32, 8, 8, 5, 2), (2, 4, 4, 64, 14, 14, 3, 1),
+                                               (3, 3, 5, 2, 11, 6, 3, 2), (5, 2, 2, 8, 40, 40, 3, 1)])
+def test_conv_backward_shapes(N, p, q, k, H, W, r, pad):
+    w = (RNG.standard_normal((r, r, p, q, k)) * np.sqrt(2.0 / (r * r * q * k))).astype(np.float32)
+    x = RNG.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32)
+    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    dy = RNG.uniform(-1, 1, (N, p * k, Ho, Wo)).astype(np.float32)
+    dx, dw = G.gpu_conv_backward(w, x, dy, pad)
+    check(dx, O.conv_backward_dx(w, dy, H, W, pad), f"conv dx {N},{p}x{q},k={k},{H}x{W},r={r},pad={pad}")
+    check(dw, O.conv_backward_dw(x, dy, k, r, pad), f"conv dw {N},{p}x{q},k={k},{H}x{W},r={r},pad={pad}")
+    dx_only, none = G.gpu_conv_backward(w, x, dy, pad, need_dw=False)
+    assert none is None
+    np.testing.assert_array_equal(dx_only, dx)
+    none, dw_only = G.gpu_conv_backward(w, x, dy, pad, need_dx=False)
+    np.testing.assert_array_equal(dw_only, dw)
+    a = G.gpu_conv_backward(w, x, dy, pad)                       # deterministic
+    np.testing.assert_array_equal(a[0], dx); np.testing.assert_array_equal(a[1], dw)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_cfg4_conv_backward(seed):
+    """Full size on the GPU; dx against the oracle on three images (images are independent),
+    dw through the bilinear identity <dw, w> = <dy, y> = <dx, x> and the oracle on a reduced
+    batch (first 4 images) run separately."""
+    c = synth.CFG4
+    w, x = synth.conv_inputs(c, seed)
+    dy = synth.conv_upstream_grad(c, seed)
+    dx, dw = G.gpu_conv_backward(w, x, dy, c.pad)
+    for n in (0, c.N // 2, c.N - 1):
+        check(dx[n:n + 1], O.conv_backward_dx(w, dy[n:n + 1], c.H, c.W, c.pad), f"cfg4 dx seed {seed} image {n}")
+    y = G.gpu_conv_forward(w, x, None, False, c.pad)
+    s = np.sum(dy.astype(np.float64) * y)
+    assert abs(np.sum(dx.astype(np.float64) * x) - s) <= 1e-4 * abs(s) + 1e-2
+    assert abs(np.sum(dw.astype(np.float64) * w) - s) <= 1e-4 * abs(s) + 1e-2
+    _, dw4 = G.gpu_conv_backward(w, x[:4], dy[:4], c.pad, need_dx=False)
+    check(dw4, O.conv_backward_dw(x[:4], dy[:4], c.k, c.r, c.pad), f"cfg4 dw seed {seed} (4 images)")
+
+
+@pytest.mark.parametrize("shape", [(1, 8), (7, 130), (1024, 4096), (33, 65), (3, 4, 5, 6), (32, 256, 28, 28), (2, 3, 1, 1)])
+def test_bias_grad(shape):
+    dy = RNG.uniform(-1, 1, shape).astype(np.float32)
+    db = G.gpu_bias_grad(dy)
+    check(db, O.bias_grad(dy), f"bias grad {shape}")
+    np.testing.assert_array_equal(G.gpu_bias_grad(dy), db)
+
+
 # ---- the five layer configurations ---------------------------------------------------------
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_cfg1(seed):
