@@ -190,8 +190,8 @@ def main():
         FL.circ_floor_empty.restype = ctypes.c_int
         FL.circ_floor_empty.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
         FL.circ_floor_stream.restype = ctypes.c_int
-        FL.circ_floor_stream.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 2 + [ctypes.c_size_t] * 3 + \
-                                        [ctypes.c_int] * 3 + [ctypes.c_void_p]
+        FL.circ_floor_stream.argtypes = [ctypes.c_void_p, ctypes.c_size_t] * 3 + [ctypes.c_int] * 2 + \
+                                        [ctypes.c_size_t] * 3 + [ctypes.c_int] * 3 + [ctypes.c_void_p]
         wdummy = torch.zeros(p * q * k, dtype=torch.float32, device=dev)      # size of the weight operand
         wdp = ctypes.c_void_p(wdummy.data_ptr())
         nwg, nthr = 256, 512
@@ -210,9 +210,9 @@ def main():
         floors = {
             "empty_launch_us": graph_time(lambda i: FL.circ_floor_empty(nwg, nthr, sptr)),
             "copy_algorithmic_bytes_us": graph_time(lambda i: FL.circ_floor_stream(
-                wdp, xp[i], yp[i], nwg, nthr, wb // nwg, xb // nwg, yb // nwg, 0, 0, 0, sptr)),
+                wdp, wb, xp[i], xb, yp[i], yb, nwg, nthr, wb // nwg, xb // nwg, yb // nwg, 0, 0, 0, sptr)),
             "same_footprint_loads_us": graph_time(lambda i: FL.circ_floor_stream(
-                wdp, xp[i], yp[i], nwg, nthr, wb // 8, xb // 32, yb // nwg, 4, 2, 16, sptr)),
+                wdp, wb, xp[i], xb, yp[i], yb, nwg, nthr, wb // 8, xb // 32, yb // nwg, 4, 2, 16, sptr)),
             "note": "HIP events over a one-stream graph of K launches of 256 workgroups x 512 threads, no arithmetic",
         }
 

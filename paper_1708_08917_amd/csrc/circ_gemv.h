@@ -73,6 +73,19 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
   const bool active = jg < JG;
   float P[4] = {0.f, 0.f, 0.f, 0.f}, Q[4] = {0.f, 0.f, 0.f, 0.f};
   const float2* wrow = Wg + (long long)i * q * S + slot;
+  // The weights of a chunk are fetched one chunk ahead (those of the first chunk before x is
+  // even staged), so that their latency overlaps the FFT instead of following it.
+  constexpr int NPF = (PT + JG - 1) / JG;          // weights per thread and chunk
+  float2 wnext[NPF];
+  auto fetch_w = [&](int c) {
+#pragma unroll
+    for (int u = 0; u < NPF; ++u) {
+      const int jj = jg + u * JG, j = c * PT + jj;
+      wnext[u] = make_float2(0.f, 0.f);
+      if (active && jj < PT && j < q) wnext[u] = wrow[(long long)j * S];
+    }
+  };
+  fetch_w(0);
 
   for (int c = 0; c < nchunks; ++c) {
     const int j0 = c * PT;
@@ -105,14 +118,21 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
       fft_lds_pass2<K, false>(z, PP, col, t, NT / PT, sink(col));
     }
     __syncthreads();
+    float2 wcur[NPF];
+#pragma unroll
+    for (int u = 0; u < NPF; ++u) wcur[u] = wnext[u];
+    if (c + 1 < nchunks) fetch_w(c + 1);
     if (active) {
       const int jend = min(PT, q - j0);
-#pragma unroll 4
-      for (int jj = jg; jj < jend; jj += JG) {
-        const float2 w = wrow[(long long)(j0 + jj) * S];
-        const float4 cv = *reinterpret_cast<const float4*>(op + jj * OPROW + 4 * slot);
-        P[0] += w.x * cv.x; P[1] += w.x * cv.y; P[2] += w.x * cv.z; P[3] += w.x * cv.w;
-        Q[0] += w.y * cv.x; Q[1] += w.y * cv.y; Q[2] += w.y * cv.z; Q[3] += w.y * cv.w;
+#pragma unroll
+      for (int u = 0; u < NPF; ++u) {
+        const int jj = jg + u * JG;
+        if (jj < jend) {     // (weights past the end were fetched as zeros; the operand row must exist)
+          const float2 w = wcur[u];
+          const float4 cv = *reinterpret_cast<const float4*>(op + jj * OPROW + 4 * slot);
+          P[0] += w.x * cv.x; P[1] += w.x * cv.y; P[2] += w.x * cv.z; P[3] += w.x * cv.w;
+          Q[0] += w.y * cv.x; Q[1] += w.y * cv.y; Q[2] += w.y * cv.z; Q[3] += w.y * cv.w;
+        }
       }
     }
     __syncthreads();   // z and op are rewritten by the next chunk

@@ -124,3 +124,25 @@ def test_precompute_argument_errors():
     assert f(A, 1, 2, 2, 6, A + (1 << 20), None) == B.CIRC_EINVAL
     assert f(A, 0, 2, 2, 8, A + (1 << 20), None) == B.CIRC_EINVAL
     assert f(A, 1, 2, 2, 8, A, None) == B.CIRC_EINVAL         # output aliases input
+
+
+def test_floor_helper_rejects_out_of_range_pieces():
+    """The measurement helper library checks every piece index against the region sizes on the
+    host and launches nothing when one does not fit."""
+    path = os.path.join(os.path.dirname(B.LIB_PATH), "libcirc_floor.so")
+    if not os.path.exists(path):
+        pytest.skip("libcirc_floor.so not built")
+    FL = ctypes.CDLL(path)
+    FL.circ_floor_stream.restype = ctypes.c_int
+    FL.circ_floor_stream.argtypes = [ctypes.c_void_p, ctypes.c_size_t] * 3 + [ctypes.c_int] * 2 + \
+                                    [ctypes.c_size_t] * 3 + [ctypes.c_int] * 3 + [ctypes.c_void_p]
+    a = 0x1000   # never dereferenced: every call below is rejected before a launch
+    mb = 1 << 20
+    assert FL.circ_floor_stream(a, 64 * mb, a, 64 * mb, a, 64 * mb, 1024, 512, 256 << 10, 16, 16, 0, 0, 0, None) == -1
+    assert FL.circ_floor_stream(a, mb - 16, a, mb, a, mb, 256, 512, 131072, 32768, 4096, 4, 2, 16, None) == -1
+    assert FL.circ_floor_stream(a, mb, a, mb - 16, a, mb, 256, 512, 131072, 32768, 4096, 4, 2, 16, None) == -1
+    assert FL.circ_floor_stream(a, mb, a, mb, a, mb - 16, 256, 512, 131072, 32768, 4096, 4, 2, 16, None) == -1
+    assert FL.circ_floor_stream(a, mb, a, mb, a, mb, 256, 512, 131072, 32768, 4100, 4, 2, 16, None) == -1   # not a multiple of 16
+    assert FL.circ_floor_stream(None, mb, a, mb, a, mb, 256, 512, 16, 16, 16, 0, 0, 0, None) == -1
+    assert FL.circ_floor_empty(0, 512, None) == -1 and FL.circ_floor_empty(256, 2048, None) == -1
+
