@@ -165,10 +165,20 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
   float4 xr[4];
   unsigned xoff[4];
   int xjj[4];
+  // A wave-load covers 8 rows x 8 float4 (128 contiguous bytes of each row): with the lanes of a
+  // wave spread over rows as well as over n, the four LDS stores per float4 spread over all banks
+  // (lanes that only differ in n are 8*PP floats apart, which is 8 banks modulo 32).
+  constexpr int RB = 2 * PT / 8;                 // blocks of 8 rows per chunk
+  auto x_elem = [&](int e, int& row, int& n4) {
+    const int blk = e * NW + wave;               // NT/16 blocks of 8 x 8 float4, four per wave
+    row = 8 * (blk % RB) + (lane >> 3);
+    n4 = 8 * (blk / RB) + (lane & 7);
+  };
+  static_assert((2 * PT) % 8 == 0 && (K / 4) % 8 == 0 && RB * (K / 32) == NT / 16, "x staging blocks");
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    const int flat = e * NT + tid;
-    const int row = flat / (K / 4), n4 = flat % (K / 4);
+    int row, n4;
+    x_elem(e, row, n4);
     const int cl = row >> 1, half = row & 1;
     const int jj = cl / NP, brow = min(2 * (cl % NP) + half, B - 1 - b0);
     xjj[e] = jj;
@@ -185,9 +195,9 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
   auto store_x = [&]() {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int flat = e * NT + tid;
-      const int row = flat / (K / 4), n = 4 * (flat % (K / 4));
-      const int cl = row >> 1, half = row & 1;
+      int row, n4;
+      x_elem(e, row, n4);
+      const int n = 4 * n4, cl = row >> 1, half = row & 1;
       lds_put(z, (n + 0) * PP + cl, half, xr[e].x);
       lds_put(z, (n + 1) * PP + cl, half, xr[e].y);
       lds_put(z, (n + 2) * PP + cl, half, xr[e].z);
