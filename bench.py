@@ -269,7 +269,7 @@ def main():
             O.fc_forward(w, x0, bias, True)
             reps += 1
             el = time.perf_counter() - t0
-            if el > 10.0 or reps >= 50:
+            if el > 12.0 or reps >= 1000:
                 break
         out["cpu_baseline"] = {
             "value": batch * reps / el, "unit": "vectors/s", "cores": cores, "kind": "oracle",

@@ -118,6 +118,54 @@ def test_conv_argument_errors():
     assert call(wsb=8) == B.CIRC_EWORKSPACE
 
 
+def test_conv_backward_argument_errors():
+    f = B.lib().circ_conv_backward
+    big = 1 << 28
+
+    def call(w_hat=A, x=A + big, dy=A + 2 * big, dx=A + 3 * big, dw=A + 4 * big, N=1, C_in=8, C_out=8, H=4, W=4, r=3,
+             stride=1, pad=1, k=4, wsp=A + 5 * big, wsb=1 << 30):
+        return f(w_hat, x, dy, dx, dw, N, C_in, C_out, H, W, r, stride, pad, k, wsp, wsb, None)
+
+    assert call(C_out=6) == B.CIRC_EINVAL                     # k does not divide C_out
+    assert call(stride=2) == B.CIRC_ENOTSUP
+    assert call(r=4) == B.CIRC_ENOTSUP
+    assert call(pad=3) == B.CIRC_EINVAL
+    assert call(N=0) == B.CIRC_EINVAL                         # empty batch
+    assert call(dy=None) == B.CIRC_EINVAL
+    assert call(dx=None, dw=None) == B.CIRC_EINVAL
+    assert call(x=None) == B.CIRC_EINVAL                      # dw needs x
+    assert call(dx=A + 2 * big) == B.CIRC_EINVAL              # dx aliases dy
+    assert call(dw=A + big) == B.CIRC_EINVAL                  # dw aliases x
+    assert call(dy=A + 2 * big + 8) == B.CIRC_EINVAL          # misaligned
+    assert call(wsb=64) == B.CIRC_EWORKSPACE
+    assert call(wsp=None) == B.CIRC_EWORKSPACE
+    wb = B.circ_conv_backward_workspace_bytes
+    assert wb(1, 8, 8, 4, 4, 3, 1, 1, 4) > B.circ_conv_workspace_bytes(1, 8, 8, 4, 4, 3, 1, 1, 4)
+    assert wb(1, 8, 8, 4, 4, 3, 2, 1, 4) == 0 and wb(1, 6, 8, 4, 4, 3, 1, 1, 4) == 0
+
+
+def test_bias_grad_argument_errors():
+    f = B.lib().circ_bias_grad
+    assert f(None, A, 2, 8, 1, None) == B.CIRC_EINVAL
+    assert f(A, None, 2, 8, 1, None) == B.CIRC_EINVAL
+    assert f(A, A + (1 << 20), 0, 8, 1, None) == B.CIRC_EINVAL    # empty batch
+    assert f(A, A + (1 << 20), 2, 0, 1, None) == B.CIRC_EINVAL
+    assert f(A, A + (1 << 20), 2, 8, 0, None) == B.CIRC_EINVAL
+    assert f(A, A + 16, 2, 8, 1, None) == B.CIRC_EINVAL           # db inside dy
+    assert f(A + 4, A + (1 << 20), 2, 8, 1, None) == B.CIRC_EINVAL
+
+
+def test_empty_and_degenerate_sizes_are_rejected():
+    """Empty inputs (batch 0, no blocks) and k = 1 (no compression: an ordinary dense layer, which
+    this library does not serve) come back as CIRC_EINVAL / size 0, never as a launch."""
+    assert B.circ_fc_workspace_bytes(2, 2, 8, 0) == 0
+    assert B.circ_fc_workspace_bytes(0, 2, 8, 4) == 0
+    assert B.circ_spectra_bytes(1, 2, 2, 1) == 0
+    f = B.lib().circ_fc_forward
+    assert f(A, A + (1 << 28), None, A + (2 << 28), 2, 2, 8, 0, 0, A + (3 << 28), 1 << 30, None) == B.CIRC_EINVAL
+    assert f(A, A + (1 << 28), None, A + (2 << 28), 2, 2, 1, 4, 0, A + (3 << 28), 1 << 30, None) == B.CIRC_EINVAL
+
+
 def test_precompute_argument_errors():
     f = B.lib().circ_precompute_spectra
     assert f(None, 1, 2, 2, 8, A, None) == B.CIRC_EINVAL
