@@ -145,9 +145,12 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
   // [js*JW, (js+1)*JW) of every chunk
   const int combo0 = (wave % (NW / JS)) * CPW, js = wave / (NW / JS);
 
-  floatx4 P[2][CPW][NP], Q[2][CPW][NP];
+  // NCH independent accumulation chains per result (consecutive input blocks alternate between
+  // them), so that a matrix instruction never waits for the previous one on the same registers
+  constexpr int NCH = (CPW * NP >= 2) ? 2 : 4;
+  floatx4 P[NCH][CPW][NP], Q[NCH][CPW][NP];
 #pragma unroll
-  for (int h = 0; h < 2; ++h)
+  for (int h = 0; h < NCH; ++h)
 #pragma unroll
     for (int cc = 0; cc < CPW; ++cc)
 #pragma unroll
@@ -312,8 +315,8 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
             const float bval = bvv[cur][jj][u][NFW > 1 ? cc / IG : 0];
             const float4 av = a_use[cc][(jb + jj) / 2];
             const float ar = ((jb + jj) & 1) ? av.z : av.x, ai = ((jb + jj) & 1) ? av.w : av.y;
-            P[jj & 1][cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(ar, bval, P[jj & 1][cc][u], 0, 0, 0);
-            Q[jj & 1][cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(ai, bval, Q[jj & 1][cc][u], 0, 0, 0);
+            P[jj % NCH][cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(ar, bval, P[jj % NCH][cc][u], 0, 0, 0);
+            Q[jj % NCH][cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(ai, bval, Q[jj % NCH][cc][u], 0, 0, 0);
           }
     }
     CIRC_PROBE(4 + 4 * c);
@@ -346,8 +349,13 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
   for (int cc = 0; cc < CPW; ++cc)
 #pragma unroll
     for (int u = 0; u < NP; ++u) {
-      P[0][cc][u] += P[1][cc][u];
-      Q[0][cc][u] += Q[1][cc][u];
+      if constexpr (NCH == 4) {
+        P[0][cc][u] = (P[0][cc][u] + P[1][cc][u]) + (P[2][cc][u] + P[3][cc][u]);
+        Q[0][cc][u] = (Q[0][cc][u] + Q[1][cc][u]) + (Q[2][cc][u] + Q[3][cc][u]);
+      } else {
+        P[0][cc][u] += P[1][cc][u];
+        Q[0][cc][u] += Q[1][cc][u];
+      }
     }
   if constexpr (JS > 1) {
     if (js > 0) {
