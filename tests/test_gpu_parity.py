@@ -242,6 +242,50 @@ def test_cfg2(seed):
     check(G.gpu_fc_forward(w, x, b, True), O.fc_forward(w, x, b, True), f"cfg2 seed {seed}")
 
 
+def test_cfg2_graph_over_streams_matches_eager():
+    """The launch configuration of the benchmark: independent cfg2 steps recorded into one HIP graph,
+    round-robin over several streams, replayed several times with eager work in between.  Every
+    output of every replay must equal the eager result bit for bit (and the oracle on one pair)."""
+    import ctypes
+    c = synth.CFG2
+    w, x0, b = synth.fc_inputs(c)
+    wh = B.circ_precompute_spectra(G.dev(w))
+    bd = G.dev(b)
+    nsteps, nstreams = 24, 4
+    gen = torch.Generator(device=G.DEV); gen.manual_seed(7)
+    xs = torch.empty(nsteps, c.batch, c.n_in, device=G.DEV).uniform_(-1, 1, generator=gen)
+    xs[0].copy_(torch.from_numpy(x0))
+    epi = B.EPI_BIAS | B.EPI_RELU
+    eager = torch.stack([B.circ_fc_forward(wh, xs[i], bd, None, c.p, c.q, c.k, epi) for i in range(nsteps)])
+    torch.cuda.synchronize()
+    check(eager[0].cpu().numpy(), O.fc_forward(w, x0, b, True), "cfg2 eager pair 0")
+    ys = torch.zeros_like(eager)
+    main = torch.cuda.Stream()
+    side = [torch.cuda.Stream() for _ in range(nstreams - 1)]
+    lanes = [main] + side
+    wss = [torch.empty(max(1, B.circ_fc_workspace_bytes(c.p, c.q, c.k, c.batch)), dtype=torch.uint8, device=G.DEV)
+           for _ in lanes]
+    fn = B.lib().circ_fc_forward
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=main):
+        for s_ in side:
+            s_.wait_stream(main)
+        for i in range(nsteps):
+            ln = i % nstreams
+            st = fn(ctypes.c_void_p(wh.data_ptr()), ctypes.c_void_p(xs[i].data_ptr()), ctypes.c_void_p(bd.data_ptr()),
+                    ctypes.c_void_p(ys[i].data_ptr()), c.p, c.q, c.k, c.batch, epi, ctypes.c_void_p(wss[ln].data_ptr()),
+                    wss[ln].numel(), ctypes.c_void_p(lanes[ln].cuda_stream))
+            assert st == 0
+        for s_ in side:
+            main.wait_stream(s_)
+    for rep in range(3):
+        ys.fill_(-1.0)                         # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ys, eager), f"replay {rep} differs from the eager result"
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_cfg3_two_stacked_layers(seed):
     w1, x, b1 = synth.fc_inputs(synth.CFG3_L1, seed)
