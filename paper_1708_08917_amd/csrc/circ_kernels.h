@@ -165,10 +165,14 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
     for (int f = tid >> lgP; f < NF; f += fstep, s += sstep) {
       float2 ya = ok0 ? s[0] : make_float2(0.f, 0.f);
       float2 yb = ok1 ? s[1] : make_float2(0.f, 0.f);
+      // partial sums: loads four parts ahead, additions in index order
+#pragma unroll 4
       for (int part = 1; part < nparts; ++part) {
         const float2* sp = s + part * part_stride;
-        if (ok0) { ya.x += sp[0].x; ya.y += sp[0].y; }
-        if (ok1) { yb.x += sp[1].x; yb.y += sp[1].y; }
+        const float2 pa = ok0 ? sp[0] : make_float2(0.f, 0.f);
+        const float2 pb = ok1 ? sp[1] : make_float2(0.f, 0.f);
+        ya.x += pa.x; ya.y += pa.y;
+        yb.x += pb.x; yb.y += pb.y;
       }
       if (f == 0 || 2 * f == K) {            // DC and Nyquist bins of a real signal are real
         L.z[f * PP + pr] = make_float2(ya.x, yb.x);
