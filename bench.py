@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=8, help="streams the graph of independent steps is spread over")
+    ap.add_argument("--streams", type=int, default=16, help="streams the graph of independent steps is spread over")
     ap.add_argument("--pool-mb", type=int, default=640, help="size of the rotating activation/output pool")
     ap.add_argument("--pmc", action="store_true",
                     help="counter-collection mode for rocprofv3 --pmc: eager launches only (no graph), plus "
