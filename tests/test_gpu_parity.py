@@ -229,6 +229,64 @@ def test_bias_grad(shape):
     np.testing.assert_array_equal(G.gpu_bias_grad(dy), db)
 
 
+# ---- seeded sweep over random valid shapes: every entry point, every dispatch path that small
+# shapes reach (streaming kernel, fused kernels with one or several chunks, unfused route,
+# fused and unfused CONV), ragged everywhere
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_shapes_sweep(seed):
+    rng = np.random.default_rng(seed)
+    for case in range(60):
+        kind = rng.choice(["fc", "fcb", "conv", "convb"], p=[0.4, 0.25, 0.2, 0.15])
+        if kind in ("fc", "fcb"):
+            k = int(rng.choice([2, 4, 8, 16, 32, 64, 128, 256, 512]))
+            p, q = int(rng.integers(1, 80)), int(rng.integers(1, 80))
+            batch = int(rng.choice([1, 2, 3, 5, 8, 17, 33, 64, 100, 130, 257]))
+            while (p * k) * (q * k) * batch > 2e8 and (p > 1 or q > 1):     # keep the dense oracle quick
+                p, q = max(1, p // 2), max(1, q // 2)
+            while (p * k) * (q * k) * batch > 2e8 and batch > 1:
+                batch = max(1, batch // 2)
+            w = (rng.standard_normal((p, q, k)) / np.sqrt(q * k)).astype(np.float32)
+            x = rng.uniform(-1, 1, (batch, q * k)).astype(np.float32)
+            what = f"sweep {seed}/{case} {kind} {p}x{q} k={k} B={batch}"
+            print(what, flush=True)
+            if kind == "fc":
+                b = (0.1 * rng.standard_normal(p * k)).astype(np.float32) if rng.integers(0, 2) else None
+                relu = bool(rng.integers(0, 2))
+                check(G.gpu_fc_forward(w, x, b, relu), O.fc_forward(w, x, b, relu), what)
+            else:
+                dy = rng.uniform(-1, 1, (batch, p * k)).astype(np.float32)
+                dx, dw = G.gpu_fc_backward(w, x, dy)
+                check(dx, O.fc_backward_dx(w, dy), what + " dx")
+                check(dw, O.fc_backward_dw(x, dy, k), what + " dw")
+        else:
+            k = int(rng.choice([2, 4, 8, 16, 32, 64]))
+            p, q = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+            r = int(rng.choice([1, 3, 3, 3, 5]))
+            pad = int(rng.integers(0, r))
+            H, W = int(rng.integers(1, 18)), int(rng.integers(1, 18))
+            if rng.integers(0, 2):
+                W = max(4, (W // 4) * 4)                 # rows that are a multiple of 4 pixels can take the fused kernel
+            while W + 2 * pad < r:
+                W += 4
+            while H + 2 * pad < r:
+                H += 1
+            N = int(rng.integers(1, 6))
+            w = (rng.standard_normal((r, r, p, q, k)) * np.sqrt(2.0 / (r * r * q * k))).astype(np.float32)
+            x = rng.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32)
+            what = f"sweep {seed}/{case} {kind} N={N} {p}x{q} k={k} {H}x{W} r={r} pad={pad}"
+            print(what, flush=True)
+            if kind == "conv":
+                b = (0.1 * rng.standard_normal(p * k)).astype(np.float32)
+                check(G.gpu_conv_forward(w, x, b, True, pad), O.conv_forward(w, x, b, True, pad), what)
+            else:
+                Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+                dy = rng.uniform(-1, 1, (N, p * k, Ho, Wo)).astype(np.float32)
+                dx, dw = G.gpu_conv_backward(w, x, dy, pad)
+                check(dx, O.conv_backward_dx(w, dy, H, W, pad), what + " dx")
+                check(dw, O.conv_backward_dw(x, dy, k, r, pad), what + " dw")
+                check(G.gpu_bias_grad(dy), O.bias_grad(dy), what + " db")
+
+
 # ---- the five layer configurations ---------------------------------------------------------
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_cfg1(seed):
