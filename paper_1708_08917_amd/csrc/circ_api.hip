@@ -76,7 +76,7 @@ inline size_t conv_section_elems(int n_grids, int p, int q, int k) {      // in 
 // and for backward-data, which is the same computation on the transposed, conjugated grid
 // (q x p).  CONV: unfused operands, then the fused CONV order.
 struct BlobLayout {
-  size_t fwd, bwd, fused_fwd, gemv_fwd, fused_bwd, gemv_bwd, conv, total;
+  size_t fwd, bwd, fused_fwd, gemv_fwd, fused_bwd, gemv_bwd, conv, conv_bwd, total;
 };
 inline BlobLayout blob_layout(int n_grids, int p, int q, int k) {
   BlobLayout b;
@@ -89,6 +89,7 @@ inline BlobLayout blob_layout(int n_grids, int p, int q, int k) {
   b.fused_bwd = off; off += align_up(fused_section_elems(n_grids, q, p, k) * sizeof(float4), 256);
   b.gemv_bwd = off; off += align_up(gemv_section_elems(n_grids, q, p, k) * sizeof(float2), 256);
   b.conv = off; off += align_up(conv_section_elems(n_grids, p, q, k) * sizeof(float2), 256);
+  b.conv_bwd = off; off += align_up(conv_section_elems(n_grids, q, p, k) * sizeof(float2), 256);
   b.total = off;
   return b;
 }
@@ -446,7 +447,15 @@ circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, i
   const size_t nconv = conv_section_elems(n_grids, p, q, k);
   if (nconv) {
     hipLaunchKernelGGL(pack_conv_kernel, dim3((unsigned)cdiv((long long)nconv, 256)), dim3(256), 0, s, fwd,
-                       blob_at<float2>(w_hat, bl.conv), n_grids, p, q, k, int(nconv / (size_t(n_grids) * q * 64)));
+                       blob_at<float2>(w_hat, bl.conv), n_grids, p, q, k, int(nconv / (size_t(n_grids) * q * 64)), 0);
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  }
+  // backward-data of a CONV layer is the forward kernel on the transposed grids (q output blocks,
+  // p input blocks) with the conjugated spectra and the reflected filter
+  const size_t nconvb = conv_section_elems(n_grids, q, p, k);
+  if (nconvb) {
+    hipLaunchKernelGGL(pack_conv_kernel, dim3((unsigned)cdiv((long long)nconvb, 256)), dim3(256), 0, s, bwd,
+                       blob_at<float2>(w_hat, bl.conv_bwd), n_grids, q, p, k, int(nconvb / (size_t(n_grids) * p * 64)), 1);
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
   }
   return CIRC_OK;
@@ -654,6 +663,28 @@ hipError_t launch_conv_fused_q(const float2* wc, const float* x, const float* bi
 
 }  // namespace
 
+namespace {
+
+// The fused CONV kernel serves k = 64, 3x3 filters, 1, 2 or 4 input channel blocks and up to 16
+// output channel blocks; it loads aligned groups of 4 pixels and stores pairs of outputs, and
+// keeps offsets inside an image pair in 32 bits.  p, q: output / input channel blocks; H x W the
+// input image, Ho x Wo the output image.
+inline bool conv_fused_applicable(int p, int q, int k, int r, int N, int H, int W, int Ho, int Wo) {
+  const long long HW = (long long)H * W, HWo = (long long)Ho * Wo;
+  return conv_fused_ncombo(p, q, k, r) > 0 && W % 4 == 0 && Wo % 2 == 0 && 2 * (long long)q * k * HW < (1ll << 31) &&
+         2 * (long long)p * k * HWo < (1ll << 31) && (long long)cdiv(N, 2) * HWo < (1ll << 31);
+}
+
+hipError_t launch_conv_fused(const float2* wc, const float* x, const float* bias, float* y, int N, int p, int q, int k,
+                             int r, int H, int W, int Ho, int Wo, int pad, int relu, hipStream_t s) {
+  const int ncombo = conv_fused_ncombo(p, q, k, r), C_out = p * k;
+  return q == 1 ? launch_conv_fused_q<1>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
+       : q == 2 ? launch_conv_fused_q<2>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
+                : launch_conv_fused_q<4>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+}
+
+}  // namespace
+
 extern "C" {
 
 static bool conv_dims_ok(int N, int C_in, int C_out, int H, int W, int r, int pad, int k) {
@@ -696,19 +727,10 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
 
   const int p = C_out / k, q = C_in / k, NF = k / 2 + 1;
   const long long HW = (long long)H * W, HWo = (long long)Ho * Wo;
-  const int ncombo = conv_fused_ncombo(p, q, k, r);
-  // the fused kernel loads aligned groups of 4 pixels and stores pairs of outputs, and keeps
-  // offsets inside an image pair in 32 bits
-  const bool fused_ok = ncombo > 0 && W % 4 == 0 && Wo % 2 == 0 && 2 * (long long)C_in * HW < (1ll << 31) &&
-                        2 * (long long)C_out * HWo < (1ll << 31) && (long long)cdiv(N, 2) * Ho * Wo < (1ll << 31);
-  if (fused_ok) {
+  if (conv_fused_applicable(p, q, k, r, N, H, W, Ho, Wo)) {
     const float2* wc = blob_at<float2>(w_hat, blob_layout(r * r, p, q, k).conv);
-    const float* bp = use_bias ? bias : nullptr;
-    const int relu = (epilogue & CIRC_EPI_RELU) ? 1 : 0;
-    hipError_t e = q == 1 ? launch_conv_fused_q<1>(wc, x, bp, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
-                 : q == 2 ? launch_conv_fused_q<2>(wc, x, bp, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
-                          : launch_conv_fused_q<4>(wc, x, bp, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
-    return e == hipSuccess ? CIRC_OK : CIRC_EHIP;
+    return launch_conv_fused(wc, x, use_bias ? bias : nullptr, y, N, p, q, k, r, H, W, Ho, Wo, pad,
+                             (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) == hipSuccess ? CIRC_OK : CIRC_EHIP;
   }
   const long long xrows = (long long)q * N * HW, yrows = (long long)p * N * HWo;
   float2* xh = static_cast<float2*>(workspace);
@@ -784,11 +806,21 @@ circ_status circ_conv_backward(const void* w_hat, const float* x, const float* d
   float2* wpart = reinterpret_cast<float2*>(static_cast<char*>(workspace) + xa + ya);
   const BlobLayout bl = blob_layout(r * r, p, q, k);
 
+  // backward-data: the fused forward kernel on the transposed grids when the shape allows it
+  // (q output blocks, p input blocks, input image Ho x Wo, output image H x W, padding r-1-pad)
+  const bool dx_fused = dx && conv_fused_applicable(q, p, k, r, N, Ho, Wo, H, W);
+  if (dx_fused) {
+    if (launch_conv_fused(blob_at<float2>(w_hat, bl.conv_bwd), dy, nullptr, dx, N, q, p, k, r, Ho, Wo, H, W, r - 1 - pad, 0,
+                          s) != hipSuccess)
+      return CIRC_EHIP;
+  }
   // dY^[f][i][n][pixel]: the FFT runs down the channel axis of dy
   RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo};
-  if (launch_rfft(k, true, dy, yh, my, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+  if (dw || (dx && !dx_fused)) {
+    if (launch_rfft(k, true, dy, yh, my, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+  }
   RowMap mx{(int)HW, N, 1, (long long)C_in * HW, (long long)k * HW, HW};
-  if (dx) {
+  if (dx && !dx_fused) {
     // forward contraction on the transposed, conjugated section with reflected offsets:
     // q output blocks, p input blocks, input image Ho x Wo, output image H x W, padding r-1-pad
     constexpr int IT = 4;

@@ -51,9 +51,11 @@ inline size_t conv_fused_lds_bytes(int nrows, int ncoli) {
 // Weight spectra in the operand order of the fused CONV kernel:
 //   Wc[((g*q + j)*ncombo + combo)*64 + 4*blk + m] = W^[g][i = 4*ig + m][j][slot = 16*fg + blk]
 // with combo = ig*FG + fg, slot 0 = (W^[0].re, W^[K/2].re), rows i >= p zero.
-// `spec` is the [g][f][j][i] section.
+// `spec` is the [g][f][j][i] section.  flip: grid g takes the spectra of grid n_grids-1-g (the
+// spatially reflected filter of backward-data, where `spec` is the conjugated, transposed
+// section and p, q are the block counts of the transposed grids).
 __global__ void pack_conv_kernel(const float2* __restrict__ spec, float2* __restrict__ Wc, int n_grids, int p, int q,
-                                 int K, int ncombo) {
+                                 int K, int ncombo, int flip) {
   const int FG = K / 32;
   const long long total = (long long)n_grids * q * ncombo * 64;
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -68,7 +70,7 @@ __global__ void pack_conv_kernel(const float2* __restrict__ spec, float2* __rest
   float2 v = make_float2(0.f, 0.f);
   if (i < p) {
     const long long fs = (long long)p * q;
-    const float2* sg = spec + (long long)g * (K / 2 + 1) * fs;
+    const float2* sg = spec + (long long)(flip ? n_grids - 1 - g : g) * (K / 2 + 1) * fs;
     const long long e = (long long)j * p + i;
     v = slot == 0 ? make_float2(sg[e].x, sg[(long long)(K / 2) * fs + e].x) : sg[(long long)slot * fs + e];
   }

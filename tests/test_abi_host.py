@@ -43,7 +43,8 @@ def test_spectra_bytes():
     assert B.circ_spectra_bytes(1, 64, 64, 64) == 2 * 64 * 64 * 33 * 8 + 4 * 64 * 64 * 32 * 8
     assert B.circ_spectra_bytes(1, 3, 5, 2) == 2 * 256          # k = 2: only the two unfused sections
     # CONV blob (9 grids of 4 x 4 blocks, k = 64): unfused sections + fused CONV operands (9*4*2*64 float2)
-    assert B.circ_spectra_bytes(9, 4, 4, 64) == 2 * ((9 * 16 * 33 * 8 + 255) // 256 * 256) + 9 * 4 * 2 * 64 * 8
+    # for the forward pass and the same again for backward-data (transposed grids, reflected filter)
+    assert B.circ_spectra_bytes(9, 4, 4, 64) == 2 * ((9 * 16 * 33 * 8 + 255) // 256 * 256) + 2 * 9 * 4 * 2 * 64 * 8
     for bad in [(0, 1, 1, 8), (1, 0, 1, 8), (1, 1, 0, 8), (1, 1, 1, 3), (1, 1, 1, 1), (1, 1, 1, 1024), (1, 1, 1, 0)]:
         assert B.circ_spectra_bytes(*bad) == 0
 

@@ -202,6 +202,25 @@ def test_conv_backward_shapes(N, p, q, k, H, W, r, pad):
     np.testing.assert_array_equal(a[0], dx); np.testing.assert_array_equal(a[1], dw)
 
 
+# backward-data on the fused forward kernel (k = 64, 3x3; the p x q grid is transposed, so it needs
+# p in {1, 2, 4} and q <= 16, and rows of dy that are a multiple of 4 pixels): odd image
+# counts, ragged tiles, every padding; the shapes that do not qualify take the unfused route
+@pytest.mark.parametrize("N,p,q,H,W,pad", [(1, 1, 1, 5, 8, 1), (3, 4, 4, 9, 12, 1), (2, 2, 5, 13, 8, 0), (5, 1, 9, 7, 32, 2),
+                                           (2, 4, 16, 8, 8, 1), (4, 2, 3, 28, 28, 1), (1, 4, 2, 3, 6, 0), (2, 4, 4, 33, 4, 2),
+                                           (3, 2, 2, 10, 20, 1), (2, 3, 4, 16, 16, 1), (1, 1, 1, 5, 5, 1), (2, 5, 2, 13, 6, 0)])
+def test_conv_backward_fused_shapes(N, p, q, H, W, pad):
+    k, r = 64, 3
+    w = (RNG.standard_normal((r, r, p, q, k)) * np.sqrt(2.0 / (r * r * q * k))).astype(np.float32)
+    x = RNG.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32)
+    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    dy = RNG.uniform(-1, 1, (N, p * k, Ho, Wo)).astype(np.float32)
+    dx, dw = G.gpu_conv_backward(w, x, dy, pad)
+    check(dx, O.conv_backward_dx(w, dy, H, W, pad), f"conv dx fused {N},{p}x{q},{H}x{W},pad={pad}")
+    check(dw, O.conv_backward_dw(x, dy, k, r, pad), f"conv dw {N},{p}x{q},{H}x{W},pad={pad}")
+    dx_only, _ = G.gpu_conv_backward(w, x, dy, pad, need_dw=False)
+    np.testing.assert_array_equal(dx_only, dx)
+
+
 @pytest.mark.parametrize("seed", [0, 1])
 def test_cfg4_conv_backward(seed):
     """Full size on the GPU; dx against the oracle on three images (images are independent),
