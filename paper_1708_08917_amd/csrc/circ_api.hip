@@ -755,7 +755,7 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
 }
 
 
-// Output pixels per block of conv_dw_kernel: at least 2048 (so that the block-wide sum at the
+// Output pixels per block of conv_dw_mfma_kernel: at least 2048 (so that the block-wide sum at the
 // end stays small beside the pixel loop) and at most 16 chunks (their partial spectra are added
 // one after the other by the inverse FFT).
 static long long conv_dw_pix_per_block(long long npix) {
@@ -837,16 +837,25 @@ circ_status circ_conv_backward(const void* w_hat, const float* x, const float* d
     const int nchunks = (int)cdiv(npix, ppb);
     const long long wrows = (long long)r * r * p * q;
     const long long wstride = (long long)(align_up(spectrum_elems(k, wrows) * sizeof(float2), 256) / sizeof(float2));
-    if (r % 3 == 0) {   // three consecutive offsets (for r = 3: one filter row) per block, 4 x 4 tiles of blocks
-      constexpr int IT = 4, JT = 4, NG = 3;
-      dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(cdiv(r * r, NG) * cdiv(p, IT) * cdiv(q, JT)));
-      hipLaunchKernelGGL((conv_dw_kernel<IT, JT, NG>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo, r,
-                         pad, ppb, wstride);
+#ifndef CIRC_DW_NG
+#define CIRC_DW_NG 3
+#endif
+    // exact division of the pixel index by a multiply-high: q = (pix * ceil(2^32/d)) >> 32 equals
+    // pix / d whenever pix * d < 2^32 (the rounding excess of the multiplier, below d, times pix
+    // stays below 2^32)
+    auto fast_mul = [](long long limit, long long d) -> unsigned {
+      if (d <= 1 || limit * d >= (1ll << 32)) return 0u;
+      return (unsigned)(((1ll << 32) + d - 1) / d);
+    };
+    const unsigned mul_hwo = fast_mul(npix, HWo), mul_wo = fast_mul(HWo, Wo);
+    if (r % CIRC_DW_NG == 0) {   // CIRC_DW_NG consecutive offsets per block (for r = 3: one filter row)
+      dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r / CIRC_DW_NG * cdiv(p, 4) * cdiv(q, 4)));
+      hipLaunchKernelGGL((conv_dw_mfma_kernel<CIRC_DW_NG>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo,
+                         r, pad, ppb, wstride, mul_hwo, mul_wo);
     } else {            // one offset per block
-      constexpr int IT = 4, JT = 4;
-      dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r * cdiv(p, IT) * cdiv(q, JT)));
-      hipLaunchKernelGGL((conv_dw_kernel<IT, JT, 1>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo, r,
-                         pad, ppb, wstride);
+      dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r * cdiv(p, 4) * cdiv(q, 4)));
+      hipLaunchKernelGGL((conv_dw_mfma_kernel<1>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo, r, pad,
+                         ppb, wstride, mul_hwo, mul_wo);
     }
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
     // dw[g][i][j][:] = IFFT over f of the summed partial spectra, scale 1/k

@@ -29,105 +29,130 @@ __device__ __forceinline__ float block_sum_256(float v, float* red, int tid) {
   return s;
 }
 
-// Partial weight-gradient spectra.  Block (x = pixel chunk, y = frequency f,
-// z = (offset group, tile of IT output blocks, tile of JT input blocks)) accumulates, over its
-// chunk of output pixels, the IT x JT x NG products dY^ conj(X^) of NG consecutive offsets and
+// Partial weight-gradient spectra on the matrix cores.  Block (x = pixel chunk, y = frequency f,
+// z = (offset group, tile of 4 output blocks, tile of 4 input blocks)) accumulates, over its
+// chunk of output pixels, the 4 x 4 x NG products dY^ conj(X^) of NG consecutive offsets and
 // writes part[chunk][f][(g*p + i)*q + j].  The chunks are added later in index order, so the
 // result does not depend on scheduling.
 //   dyh  [f][i][n][ho][wo]  spectrum of dy over the channel axis (NF frequencies)
 //   xh   [f][j][n][h][w]    spectrum of x
-template <int IT, int JT, int NG>
-__global__ __launch_bounds__(256) void conv_dw_kernel(const float2* __restrict__ dyh, const float2* __restrict__ xh,
-                                                      float2* __restrict__ part, int p, int q, int NF, int Nimg, int H,
-                                                      int W, int Ho, int Wo, int r, int pad, long long pix_per_block,
-                                                      long long part_stride) {
-  const int tid = threadIdx.x, f = blockIdx.y;
-  const int nit = (p + IT - 1) / IT, njt = (q + JT - 1) / JT;
+// v_mfma_f32_4x4x1_16B_f32 runs 16 independent 4x4 outer products: block b of a wave takes output pixel pix0 + b, rows are
+// the 4 output blocks i (operand A: dY^[f][i][pixel]), columns the 4 input blocks j (operand B:
+// X^[f][j][shifted pixel]); a complex product d * conj(x) is four instructions on two
+// accumulators.  Every block thus sums its own subset of the pixels; at the end the 16 blocks of
+// a wave are added by a butterfly over the lanes (fixed order), then the four waves through LDS.
+// mul_hwo, mul_wo: ceil(2^32 / (Ho*Wo)) and ceil(2^32 / Wo) when the pixel index can be divided
+// exactly by a multiply-high with them (host check: pixels * divisor < 2^32), else 0 (plain
+// division): one pixel per lane and step leaves little else to amortise the division over.
+typedef float dw_floatx4 __attribute__((ext_vector_type(4)));
+
+template <int NG>
+__global__ __launch_bounds__(256) void conv_dw_mfma_kernel(const float2* __restrict__ dyh, const float2* __restrict__ xh,
+                                                           float2* __restrict__ part, int p, int q, int NF, int Nimg,
+                                                           int H, int W, int Ho, int Wo, int r, int pad,
+                                                           long long pix_per_block, long long part_stride,
+                                                           unsigned mul_hwo, unsigned mul_wo) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, f = blockIdx.y;
+  const int blk = lane >> 2, sub = lane & 3;
+  const int nit = (p + 3) / 4, njt = (q + 3) / 4;
   int z = blockIdx.z;
   const int jt = z % njt; z /= njt;
   const int it = z % nit;
   const int g0 = (z / nit) * NG;
-  const int i0 = it * IT, j0 = jt * JT;
+  const int i0 = it * 4, j0 = jt * 4;
   const long long npix = (long long)Nimg * Ho * Wo;
   const long long pbeg = (long long)blockIdx.x * pix_per_block, pend = min(npix, pbeg + pix_per_block);
   // offsets inside one frequency of a spectrum fit 32 bits (host check)
   const unsigned HW = unsigned(H) * unsigned(W), HWo = unsigned(Ho) * unsigned(Wo);
   const float2* dyf = dyh + (long long)f * p * npix;
   const float2* xf = xh + (long long)f * q * Nimg * HW;
+  const bool iok = i0 + sub < p, jok = j0 + sub < q;
+  const unsigned irow = unsigned(min(i0 + sub, p - 1)) * unsigned(npix);
+  const unsigned jrow = unsigned(min(j0 + sub, q - 1)) * (unsigned(Nimg) * HW);
 
-  float2 acc[NG][IT][JT];
+  dw_floatx4 accR[NG], accI[NG];
 #pragma unroll
-  for (int g = 0; g < NG; ++g)
-#pragma unroll
-    for (int ii = 0; ii < IT; ++ii)
-#pragma unroll
-      for (int jj = 0; jj < JT; ++jj) acc[g][ii][jj] = make_float2(0.f, 0.f);
-
-  for (long long pix64 = pbeg + tid; pix64 < pend; pix64 += 256) {
-    const unsigned pix = unsigned(pix64);
-    const unsigned n = pix / HWo, rem = pix - n * HWo;
-    const int ho = int(rem / unsigned(Wo)), wo = int(rem - unsigned(ho) * unsigned(Wo));
-    float2 dv[IT];
-#pragma unroll
-    for (int ii = 0; ii < IT; ++ii) {
-      const unsigned i = unsigned(min(i0 + ii, p - 1));
-      dv[ii] = dyf[i * unsigned(npix) + pix];
-      if (i0 + ii >= p) dv[ii] = make_float2(0.f, 0.f);
-    }
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const int gg = g0 + g;
-      const int dh = gg / r, dw = gg % r;
-      const int hi = ho + dh - pad, wi = wo + dw - pad;
-      // positions outside the image (and offsets past r*r) read a clamped address and count as zero
-      const bool inb = gg < r * r && hi >= 0 && hi < H && wi >= 0 && wi < W;
-      const unsigned pos = n * HW + unsigned(min(max(hi, 0), H - 1)) * unsigned(W) + unsigned(min(max(wi, 0), W - 1));
-#pragma unroll
-      for (int jj = 0; jj < JT; ++jj) {
-        const unsigned j = unsigned(min(j0 + jj, q - 1));
-        float2 xv = xf[j * (unsigned(Nimg) * HW) + pos];
-        if (!inb || j0 + jj >= q) xv = make_float2(0.f, 0.f);
-#pragma unroll
-        for (int ii = 0; ii < IT; ++ii) {
-          // d * conj(x)
-          acc[g][ii][jj].x += dv[ii].x * xv.x + dv[ii].y * xv.y;
-          acc[g][ii][jj].y += dv[ii].y * xv.x - dv[ii].x * xv.y;
-        }
-      }
-    }
+  for (int g = 0; g < NG; ++g) {
+    accR[g] = dw_floatx4{0.f, 0.f, 0.f, 0.f};
+    accI[g] = dw_floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // Block sum in a fixed order: butterfly inside each wave, the four wave sums through LDS,
-  // then thread v adds the four partial sums of value v in wave order.
-  constexpr int NV = NG * IT * JT * 2;
-  __shared__ float wsum[4][NV];
-  const int lane = tid & 63, wave = tid >> 6;
+  // A wave takes 16 consecutive pixels per step and UNR steps per iteration: all loads of an
+  // iteration are issued before its first matrix instruction, so that several steps' worth of
+  // memory latency overlap.  The trip count is the same for every lane of a wave.
+  constexpr int UNR = NG >= 9 ? 2 : 4;
+  int goff_h[NG], goff_w[NG];                     // wave-uniform: offset (dh, dw) minus the padding
+  bool gok[NG];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    const int gg = g0 + g;
+    goff_h[g] = gg / r - pad;
+    goff_w[g] = gg % r - pad;
+    gok[g] = gg < r * r;
+  }
+  for (long long base = pbeg + wave * 16; base < pend; base += 64 * UNR) {
+    float2 d[UNR], xv[UNR][NG];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const long long pix64 = base + 64 * u + blk;
+      const bool valid = pix64 < pend;
+      const unsigned pix = unsigned(min(pix64, pend - 1));
+      const unsigned n = mul_hwo ? __umulhi(pix, mul_hwo) : pix / HWo;
+      const unsigned rem = pix - n * HWo;
+      const int ho = int(mul_wo ? __umulhi(rem, mul_wo) : rem / unsigned(Wo));
+      const int wo = int(rem) - ho * Wo;
+      d[u] = dyf[irow + pix];
+      if (!valid || !iok) d[u] = make_float2(0.f, 0.f);
+      const unsigned xbase = jrow + n * HW;
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const int hi = ho + goff_h[g], wi = wo + goff_w[g];
+        // positions outside the image (and offsets past r*r) read a clamped address and count as zero
+        const bool inb = gok[g] && unsigned(hi) < unsigned(H) && unsigned(wi) < unsigned(W);
+        xv[u][g] = xf[xbase + unsigned(min(max(hi, 0), H - 1)) * unsigned(W) + unsigned(min(max(wi, 0), W - 1))];
+        if (!inb || !jok) xv[u][g] = make_float2(0.f, 0.f);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        // d * conj(x) = (dr xr + di xi) + i (di xr - dr xi)
+        accR[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(d[u].x, xv[u][g].x, accR[g], 0, 0, 0);
+        accI[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(d[u].y, xv[u][g].x, accI[g], 0, 0, 0);
+        accR[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(d[u].y, xv[u][g].y, accR[g], 0, 0, 0);
+        accI[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(-d[u].x, xv[u][g].y, accI[g], 0, 0, 0);
+      }
+  }
+
+  // lane (blk, sub) holds, in register m, the sum over its block's pixels for (i = i0 + m, j = j0 + sub)
+  constexpr int NV = NG * 4 * 2;                  // values per column j
+  __shared__ float wsum[4][4][NV];                // [wave][j][value]
 #pragma unroll
   for (int g = 0; g < NG; ++g)
 #pragma unroll
-    for (int ii = 0; ii < IT; ++ii)
+    for (int m = 0; m < 4; ++m) {
+      float vx = accR[g][m], vy = accI[g][m];
 #pragma unroll
-      for (int jj = 0; jj < JT; ++jj) {
-        float vx = acc[g][ii][jj].x, vy = acc[g][ii][jj].y;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-          vx += __shfl_down(vx, off, 64);
-          vy += __shfl_down(vy, off, 64);
-        }
-        if (lane == 0) {
-          wsum[wave][((g * IT + ii) * JT + jj) * 2 + 0] = vx;
-          wsum[wave][((g * IT + ii) * JT + jj) * 2 + 1] = vy;
-        }
+      for (int off = 4; off <= 32; off <<= 1) {
+        vx += __shfl_xor(vx, off, 64);
+        vy += __shfl_xor(vy, off, 64);
       }
+      if (blk == 0) {
+        wsum[wave][sub][(g * 4 + m) * 2 + 0] = vx;
+        wsum[wave][sub][(g * 4 + m) * 2 + 1] = vy;
+      }
+    }
   __syncthreads();
   const long long rows = (long long)r * r * p * q;
   float* out = reinterpret_cast<float*>(part + (long long)blockIdx.x * part_stride + (long long)f * rows);
-  for (int v = tid; v < NV; v += 256) {
-    const int c = v & 1, e = v >> 1;
-    const int jj = e % JT, ii = (e / JT) % IT, g = e / (JT * IT);
-    const int gg = g0 + g, i = i0 + ii, j = j0 + jj;
+  for (int v = tid; v < 4 * NV; v += 256) {
+    const int j4 = v / NV, e = v % NV;
+    const int c = e & 1, m = (e >> 1) & 3, g = e >> 3;
+    const int gg = g0 + g, i = i0 + m, j = j0 + j4;
     if (gg < r * r && i < p && j < q)
-      out[2 * (((long long)gg * p + i) * q + j) + c] = (wsum[0][v] + wsum[1][v]) + (wsum[2][v] + wsum[3][v]);
+      out[2 * (((long long)gg * p + i) * q + j) + c] =
+          (wsum[0][j4][e] + wsum[1][j4][e]) + (wsum[2][j4][e] + wsum[3][j4][e]);
   }
 }
 
