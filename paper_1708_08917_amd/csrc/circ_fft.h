@@ -151,6 +151,22 @@ __device__ __forceinline__ void fft_lds_pass2_inplace(float2* z, int PP, int col
   fft_lds_pass2<K, INV>(z, PP, col, t, TT, [&](int f, float2 v) { z[fft_pos<K>(f) * PP + col] = v; });
 }
 
+// Whole transform of one column by one thread (small K): no exchange between passes, no
+// twiddle table.  Every finished value goes to `sink(f, value)`.
+template <int K, bool INV, class Sink>
+__device__ __forceinline__ void fft_lds_single(const float2* z, int PP, int col, Sink&& sink) {
+  float re[K], im[K];
+#pragma unroll
+  for (int n = 0; n < K; ++n) {
+    float2 v = z[n * PP + col];
+    re[n] = v.x;
+    im[n] = v.y;
+  }
+  FftReg<K, INV>::run(re, im);
+#pragma unroll
+  for (int f = 0; f < K; ++f) sink(f, make_float2(re[f], im[f]));
+}
+
 // ---- addressing of "rows" (the length-K vectors that are transformed) ----------------
 // Row ids enumerate the rows in the order of the spectrum buffer:
 // spectrum[f][rid].  A row id decomposes as rid = (a*n1 + b)*n0 + c and the first

@@ -111,7 +111,10 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
         *reinterpret_cast<float2*>(op + col * OPROW + 4 * sl + 2 * h) = v;
       };
     };
-    {
+    if constexpr (K <= 16) {
+      // short blocks: one thread transforms a whole column in registers (no second pass)
+      for (int col = tid; col < PT; col += NT) fft_lds_single<K, false>(z, PP, col, sink(col));
+    } else {
       const int col = tid % PT, t = tid / PT;
       fft_lds_pass1<K, false>(z, PP, col, t, NT / PT, twl);
       __syncthreads();
@@ -168,15 +171,23 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
     }
   }
   __syncthreads();
-  // inverse transform of the single column (row stride 2)
-  fft_lds_pass1<K, true>(z, 2, 0, tid, NT, twl);
-  __syncthreads();
-  fft_lds_pass2_inplace<K, true>(z, 2, 0, tid, NT);
-  __syncthreads();
+  // inverse transform of the single column (row stride 2); afterwards sample n of the pair sits
+  // at position opos(n)
+  if constexpr (K <= 16) {
+    float2* zo = z + 2 * K;                      // natural order, behind the input column
+    if (tid == 0) fft_lds_single<K, true>(z, 2, 0, [&](int n, float2 v) { zo[2 * n] = v; });
+    __syncthreads();
+  } else {
+    fft_lds_pass1<K, true>(z, 2, 0, tid, NT, twl);
+    __syncthreads();
+    fft_lds_pass2_inplace<K, true>(z, 2, 0, tid, NT);
+    __syncthreads();
+  }
+  auto opos = [](int n) { return K <= 16 ? K + n : fft_pos<K>(n); };
   for (int idx = tid; idx < 2 * K; idx += NT) {
     const int half = idx / K, n = idx % K;
     if (half < B) {
-      float v = lds_get(z, fft_pos<K>(n) * 2, half);
+      float v = lds_get(z, opos(n) * 2, half);
       if (bias) v += bias[(long long)i * K + n];
       if (relu) v = fmaxf(v, 0.f);
       y[(long long)half * ldy + (long long)i * K + n] = v;
