@@ -737,7 +737,7 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
   float2* yh = reinterpret_cast<float2*>(static_cast<char*>(workspace) +
                                          align_up(spectrum_elems(k, xrows) * sizeof(float2), 256));
   // X^[f][j][n][pixel]: the FFT runs down the channel axis (element stride H*W)
-  RowMap mx{(int)HW, N, 1, (long long)C_in * HW, (long long)k * HW, HW};
+  RowMap mx{(int)HW, N, 1, (long long)C_in * HW, (long long)k * HW, HW, HW % 4 == 0};
   if (launch_rfft(k, true, x, xh, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
   {
     constexpr int IT = 4;
@@ -747,7 +747,7 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
                        p, q, NF, N, H, W, Ho, Wo, r, pad, 0);
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
   }
-  RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo};
+  RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo, HWo % 4 == 0};
   if (launch_irfft(k, true, yh, y, my, yrows, yrows, 1.0f, use_bias ? bias : nullptr, (long long)N * HWo,
                    (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
     return CIRC_EHIP;
@@ -815,11 +815,11 @@ circ_status circ_conv_backward(const void* w_hat, const float* x, const float* d
       return CIRC_EHIP;
   }
   // dY^[f][i][n][pixel]: the FFT runs down the channel axis of dy
-  RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo};
+  RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo, HWo % 4 == 0};
   if (dw || (dx && !dx_fused)) {
     if (launch_rfft(k, true, dy, yh, my, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
   }
-  RowMap mx{(int)HW, N, 1, (long long)C_in * HW, (long long)k * HW, HW};
+  RowMap mx{(int)HW, N, 1, (long long)C_in * HW, (long long)k * HW, HW, HW % 4 == 0};
   if (dx && !dx_fused) {
     // forward contraction on the transposed, conjugated section with reflected offsets:
     // q output blocks, p input blocks, input image Ho x Wo, output image H x W, padding r-1-pad

@@ -171,9 +171,13 @@ __device__ __forceinline__ void fft_lds_single(const float2* z, int PP, int col,
 // Row ids enumerate the rows in the order of the spectrum buffer:
 // spectrum[f][rid].  A row id decomposes as rid = (a*n1 + b)*n0 + c and the first
 // element of the row sits at c*s0 + b*s1 + a*s2; consecutive elements are `es` apart.
+// quad: set when every aligned group of 4 consecutive row ids is 4 contiguous, 16-byte aligned
+// floats at every element index (s0 == 1, n0 and the row count multiples of 4, s1, s2 and es
+// multiples of 4): the kernels then move 4 rows per 16-byte access.
 struct RowMap {
   int n0, n1;
   long long s0, s1, s2, es;
+  int quad;
 };
 
 // Row ids fit 32 bits (checked on the host), so the decomposition uses 32-bit divisions.

@@ -75,12 +75,28 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
 
   // load: row 2u -> real part of column u, row 2u+1 -> imaginary part
   if constexpr (ROWS_FAST) {
+    if (map.quad) {
+      // 4 rows per 16-byte load; they are the (re, im) slots of two neighbouring columns, i.e.
+      // 4 consecutive floats of the tile (8-byte aligned: two 8-byte LDS stores)
+      const int nq = P >> 1;                       // groups of 4 rows in the tile
 #pragma unroll 4
-    for (int idx = tid; idx < 2 * P * K; idx += NT) {
-      int row = idx & (2 * P - 1), n = idx >> (lgP + 1);
-      long long b = L.rbase[row];
-      float v = b >= 0 ? in[b + n * map.es] : 0.f;
-      lds_put(L.z, n * PP + (row >> 1), row & 1, v);
+      for (int idx = tid; idx < nq * K; idx += NT) {
+        const int qd = idx & (nq - 1), n = idx >> (lgP - 1);
+        long long b = L.rbase[4 * qd];
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n * map.es);
+        float2* zd = L.z + n * PP + 2 * qd;
+        zd[0] = make_float2(v.x, v.y);
+        zd[1] = make_float2(v.z, v.w);
+      }
+    } else {
+#pragma unroll 4
+      for (int idx = tid; idx < 2 * P * K; idx += NT) {
+        int row = idx & (2 * P - 1), n = idx >> (lgP + 1);
+        long long b = L.rbase[row];
+        float v = b >= 0 ? in[b + n * map.es] : 0.f;
+        lds_put(L.z, n * PP + (row >> 1), row & 1, v);
+      }
     }
   } else if constexpr (K >= 4) {
     // rows are contiguous (element stride 1) and 16-byte aligned: vector loads along the row.
@@ -216,6 +232,25 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
       }
       if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
       *reinterpret_cast<float4*>(out + b + n) = v;
+    }
+  } else if (ROWS_FAST && map.quad) {
+    // 4 rows per 16-byte store (see the loader of rfft_kernel); a group of 4 rows lies inside
+    // one bias block
+    const int nq = P >> 1;
+#pragma unroll 4
+    for (int idx = tid; idx < nq * K; idx += NT) {
+      const int qd = idx & (nq - 1), n = idx >> (lgP - 1);
+      long long b = L.rbase[4 * qd];
+      if (b < 0) continue;
+      const float2* zs = L.z + fft_pos<K>(n) * PP + 2 * qd;
+      const float2 u0 = zs[0], u1 = zs[1];
+      float4 v = make_float4(u0.x * scale, u0.y * scale, u1.x * scale, u1.y * scale);
+      if (bias) {
+        const float bb = bias[(long long)L.rblk[4 * qd] * K + n];
+        v.x += bb; v.y += bb; v.z += bb; v.w += bb;
+      }
+      if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+      *reinterpret_cast<float4*>(out + b + n * map.es) = v;
     }
   } else {
 #pragma unroll 4
