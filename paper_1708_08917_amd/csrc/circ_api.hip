@@ -345,27 +345,60 @@ inline bool use_fused_forward(int p, int q, int k, int batch) {
   return n_it <= 8 && l2_bytes <= double(CIRC_FUSED_MAX_L2_MIB) * 1048576.0;
 }
 
+// Batch <= 2 on few block rows with long rows: split the input blocks over several workgroups per
+// block row (two launches, partial spectra through the workspace).  Returns the number of splits
+// (1 = single launch).  Each split keeps at least 8 input blocks; the split pays for its second
+// launch only when a workgroup would otherwise transform >= 8192 input values.
+inline int gemv_splits(int p, int q, int k) {
+#ifndef CIRC_GEMV_MAXWG
+#define CIRC_GEMV_MAXWG 256
+#endif
+  if ((long long)q * k < 8192 || p * 2 > CIRC_GEMV_MAXWG) return 1;
+  int ns = 1;
+  while (ns < 16 && p * ns * 2 <= CIRC_GEMV_MAXWG && q / (ns * 2) >= 8) ns *= 2;
+  return ns;
+}
+inline size_t gemv_partial_bytes(int p, int q, int k) {
+  const int ns = gemv_splits(p, q, k);
+  return ns > 1 ? size_t(ns) * p * k * sizeof(float2) : 0;
+}
+
 template <int K>
 hipError_t launch_gemv_k(const float2* wg, const float* x, const float* bias, float* y, int p, int q, int batch, int relu,
-                         hipStream_t s) {
+                         void* workspace, hipStream_t s) {
   using Sh = GemvShape<K>;
   static bool opted_in = false;
-  if (ensure_lds(&fc_gemv_kernel<K>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((fc_gemv_kernel<K>), dim3((unsigned)p), dim3(256), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch, relu);
+  const int ns = gemv_splits(p, q, K);
+  if (ns > 1) {
+    static bool opted1 = false, opted2 = false;
+    if (ensure_lds(&fc_gemv_kernel<K, 1>, Sh::LDS_BYTES, opted1) != hipSuccess) return hipErrorInvalidValue;
+    if (ensure_lds(&fc_gemv_kernel<K, 2>, Sh::LDS_BYTES, opted2) != hipSuccess) return hipErrorInvalidValue;
+    float2* part = static_cast<float2*>(workspace);
+    const int jper = (int)cdiv(q, ns);
+    hipLaunchKernelGGL((fc_gemv_kernel<K, 1>), dim3((unsigned)p, (unsigned)ns), dim3(256), Sh::LDS_BYTES, s, wg, x,
+                       (const float*)nullptr, (float*)nullptr, p, q, batch, 0, part, ns, jper);
+    if (hipGetLastError() != hipSuccess) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((fc_gemv_kernel<K, 2>), dim3((unsigned)p), dim3(256), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch,
+                       relu, part, ns, jper);
+    return hipGetLastError();
+  }
+  if (ensure_lds(&fc_gemv_kernel<K, 0>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((fc_gemv_kernel<K, 0>), dim3((unsigned)p), dim3(256), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch,
+                     relu, (float2*)nullptr, 1, q);
   return hipGetLastError();
 }
 
 hipError_t launch_gemv(int k, const float2* wg, const float* x, const float* bias, float* y, int p, int q, int batch,
-                       int relu, hipStream_t s) {
+                       int relu, void* workspace, hipStream_t s) {
   switch (k) {
-    case 4: return launch_gemv_k<4>(wg, x, bias, y, p, q, batch, relu, s);
-    case 8: return launch_gemv_k<8>(wg, x, bias, y, p, q, batch, relu, s);
-    case 16: return launch_gemv_k<16>(wg, x, bias, y, p, q, batch, relu, s);
-    case 32: return launch_gemv_k<32>(wg, x, bias, y, p, q, batch, relu, s);
-    case 64: return launch_gemv_k<64>(wg, x, bias, y, p, q, batch, relu, s);
-    case 128: return launch_gemv_k<128>(wg, x, bias, y, p, q, batch, relu, s);
-    case 256: return launch_gemv_k<256>(wg, x, bias, y, p, q, batch, relu, s);
-    case 512: return launch_gemv_k<512>(wg, x, bias, y, p, q, batch, relu, s);
+    case 4: return launch_gemv_k<4>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 8: return launch_gemv_k<8>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 16: return launch_gemv_k<16>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 32: return launch_gemv_k<32>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 64: return launch_gemv_k<64>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 128: return launch_gemv_k<128>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 256: return launch_gemv_k<256>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 512: return launch_gemv_k<512>(wg, x, bias, y, p, q, batch, relu, workspace, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -465,9 +498,15 @@ size_t circ_fc_workspace_bytes(int p, int q, int k, int batch, int backward) {
   if (!fc_dims_ok(p, q, k, batch)) return 0;
   size_t xa = align_up(ws_spectrum_elems(k, (long long)q * batch) * sizeof(float2), 256);
   size_t ya = align_up(ws_spectrum_elems(k, (long long)p * batch) * sizeof(float2), 256);
-  if (!backward) return xa + ya;
+  // batch <= 2: partial spectra of the split streaming kernel (forward grid, or the transposed
+  // grid for backward-data); they live at the start of the workspace, which nothing else uses
+  // at that time
+  size_t gp = 0;
+  if (batch <= 2 && k >= 4) gp = align_up(backward ? gemv_partial_bytes(q, p, k) : gemv_partial_bytes(p, q, k), 256);
+  if (!backward) return xa + ya > gp ? xa + ya : gp;
   size_t wa = align_up(spectrum_elems(k, (long long)p * q) * sizeof(float2), 256);
-  return xa + ya + wa * cgemm_ksplit(k / 2 + 1, p, q, batch);   // one dW^ buffer per k slice
+  const size_t tot = xa + ya + wa * cgemm_ksplit(k / 2 + 1, p, q, batch);   // one dW^ buffer per k slice
+  return tot > gp ? tot : gp;
 }
 
 circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias, float* y, int p, int q, int k,
@@ -488,7 +527,7 @@ circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias
   const BlobLayout bl = blob_layout(1, p, q, k);
   if (batch <= 2 && k >= 4) {   // one or two vectors: streaming matrix-vector kernel
     const float2* wg = blob_at<float2>(w_hat, bl.gemv_fwd);
-    if (launch_gemv(k, wg, x, use_bias ? bias : nullptr, y, p, q, batch, (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
+    if (launch_gemv(k, wg, x, use_bias ? bias : nullptr, y, p, q, batch, (epilogue & CIRC_EPI_RELU) ? 1 : 0, workspace, s) != hipSuccess)
       return CIRC_EHIP;
     return CIRC_OK;
   }
@@ -555,7 +594,7 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
   const bool dw_shares_dy = dw && cgemm_takes_tiled(NF, p, q, batch, ksplit);
   bool have_dyh = false;   // bufy holds dY^[f][i][b]
   if (dx && batch <= 2 && k >= 4) {
-    if (launch_gemv(k, blob_at<float2>(w_hat, bl.gemv_bwd), dy, nullptr, dx, q, p, batch, 0, s) != hipSuccess) return CIRC_EHIP;
+    if (launch_gemv(k, blob_at<float2>(w_hat, bl.gemv_bwd), dy, nullptr, dx, q, p, batch, 0, workspace, s) != hipSuccess) return CIRC_EHIP;
   } else if (dx && use_fused_forward(q, p, k, batch)) {
     if (launch_fused(k, blob_at<float4>(w_hat, bl.fused_bwd), dy, nullptr, dx, q, p, batch, 0, s) != hipSuccess)
       return CIRC_EHIP;

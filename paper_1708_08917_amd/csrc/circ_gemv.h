@@ -51,10 +51,18 @@ __global__ void pack_gemv_kernel(const float2* __restrict__ spec, float2* __rest
   Wg[idx] = slot == 0 ? make_float2(spec[e].x, spec[(long long)S * fs + e].x) : spec[(long long)slot * fs + e];
 }
 
-template <int K>
+// MODE 0: the whole layer in one launch, one workgroup per output block row (grid p).
+// Layers with few block rows and long rows leave most of the chip idle that way and make every
+// workgroup transform all of x; they run as two launches instead:
+// MODE 1 (grid p x nsplit): workgroup (i, js) transforms and contracts only the input blocks
+//   [js*jper, (js+1)*jper) and writes the spectrum of its partial output pair to
+//   part[(js*p + i)*K + f];
+// MODE 2 (grid p): adds the nsplit partial spectra in index order, inverse transform, epilogue.
+template <int K, int MODE>
 __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__ Wg, const float* __restrict__ x,
                                                       const float* __restrict__ bias, float* __restrict__ y,
-                                                      int p, int q, int B, int relu) {
+                                                      int p, int q, int B, int relu, float2* __restrict__ part,
+                                                      int nsplit, int jper) {
   using Sh = GemvShape<K>;
   constexpr int NT = Sh::NT, S = Sh::S, PT = Sh::PT, PP = Sh::PP, OPROW = Sh::OPROW, JG = Sh::JG;
   extern __shared__ float smem[];
@@ -66,7 +74,10 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
   const int tid = threadIdx.x;
   const int i = blockIdx.x;
   const long long ldx = (long long)q * K, ldy = (long long)p * K;
-  const int nchunks = (q + PT - 1) / PT;
+  // input blocks of this workgroup: [jbeg, jend)
+  const int jbeg = MODE == 1 ? blockIdx.y * jper : 0;
+  const int jend = MODE == 1 ? min(q, jbeg + jper) : q;
+  const int nchunks = MODE == 2 ? 0 : (jend - jbeg + PT - 1) / PT;
   stage_twiddles<K>(twl, tid, NT);
 
   const int slot = tid % S, jg = tid / S;          // contraction role (threads beyond S*JG idle)
@@ -80,21 +91,21 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
   auto fetch_w = [&](int c) {
 #pragma unroll
     for (int u = 0; u < NPF; ++u) {
-      const int jj = jg + u * JG, j = c * PT + jj;
+      const int jj = jg + u * JG, j = jbeg + c * PT + jj;
       wnext[u] = make_float2(0.f, 0.f);
-      if (active && jj < PT && j < q) wnext[u] = wrow[(long long)j * S];
+      if (active && jj < PT && j < jend) wnext[u] = wrow[(long long)j * S];
     }
   };
-  fetch_w(0);
+  if (MODE != 2) fetch_w(0);
 
   for (int c = 0; c < nchunks; ++c) {
-    const int j0 = c * PT;
+    const int j0 = jbeg + c * PT;
     // rows b0 (real part) and b1 (imaginary part) of the chunk -> z[n][column j]
     for (int idx = tid; idx < 2 * PT * (K / 4); idx += NT) {
       const int half = idx / (PT * (K / 4)), rem = idx % (PT * (K / 4));
       const int col = rem / (K / 4), n = 4 * (rem % (K / 4));
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (half < B && j0 + col < q) v = *reinterpret_cast<const float4*>(x + (long long)half * ldx + (long long)(j0 + col) * K + n);
+      if (half < B && j0 + col < jend) v = *reinterpret_cast<const float4*>(x + (long long)half * ldx + (long long)(j0 + col) * K + n);
       lds_put(z, (n + 0) * PP + col, half, v.x);
       lds_put(z, (n + 1) * PP + col, half, v.y);
       lds_put(z, (n + 2) * PP + col, half, v.z);
@@ -126,11 +137,11 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
     for (int u = 0; u < NPF; ++u) wcur[u] = wnext[u];
     if (c + 1 < nchunks) fetch_w(c + 1);
     if (active) {
-      const int jend = min(PT, q - j0);
+      const int jlim = min(PT, jend - j0);
 #pragma unroll
       for (int u = 0; u < NPF; ++u) {
         const int jj = jg + u * JG;
-        if (jj < jend) {     // (weights past the end were fetched as zeros; the operand row must exist)
+        if (jj < jlim) {     // (weights past the end were fetched as zeros; the operand row must exist)
           const float2 w = wcur[u];
           const float4 cv = *reinterpret_cast<const float4*>(op + jj * OPROW + 4 * slot);
           P[0] += w.x * cv.x; P[1] += w.x * cv.y; P[2] += w.x * cv.z; P[3] += w.x * cv.w;
@@ -141,36 +152,57 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
     __syncthreads();   // z and op are rewritten by the next chunk
   }
 
-  // sum over the j-groups in a fixed order, then assemble the spectrum of the output pair
-  if (active) {
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-      red[(m * JG + jg) * S + slot] = P[m];
-      red[((4 + m) * JG + jg) * S + slot] = Q[m];
-    }
-  }
-  __syncthreads();
-  if (tid < S) {
-    float Ps[4], Qs[4];
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-      float a = 0.f, b = 0.f;
-      for (int g = 0; g < JG; ++g) {
-        a += red[(m * JG + g) * S + tid];
-        b += red[((4 + m) * JG + g) * S + tid];
+  if constexpr (MODE == 2) {
+    // spectrum of the output pair = sum of the partial spectra, in index order
+    for (int f = tid; f < K; f += NT) {
+      float2 acc = make_float2(0.f, 0.f);
+      const float2* src = part + (long long)i * K + f;
+#pragma unroll 4
+      for (int js = 0; js < nsplit; ++js) {
+        const float2 v = src[(long long)js * p * K];
+        acc.x += v.x;
+        acc.y += v.y;
       }
-      Ps[m] = a;
-      Qs[m] = b;
+      z[2 * f] = acc;
     }
-    if (tid == 0) {
-      z[0] = make_float2(Ps[0], Ps[1]);              // DC of (y_b0, y_b1)
-      z[S * 2] = make_float2(Qs[2], Qs[3]);          // Nyquist
-    } else {
-      z[tid * 2] = make_float2(Ps[0] - Qs[1], Ps[1] + Qs[0]);
-      z[(K - tid) * 2] = make_float2(Ps[2] + Qs[3], Ps[3] - Qs[2]);
+  } else {
+    // sum over the j-groups in a fixed order, then assemble the spectrum of the output pair
+    if (active) {
+  #pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        red[(m * JG + jg) * S + slot] = P[m];
+        red[((4 + m) * JG + jg) * S + slot] = Q[m];
+      }
+    }
+    __syncthreads();
+    if (tid < S) {
+      float Ps[4], Qs[4];
+  #pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        float a = 0.f, b = 0.f;
+        for (int g = 0; g < JG; ++g) {
+          a += red[(m * JG + g) * S + tid];
+          b += red[((4 + m) * JG + g) * S + tid];
+        }
+        Ps[m] = a;
+        Qs[m] = b;
+      }
+      if (tid == 0) {
+        z[0] = make_float2(Ps[0], Ps[1]);              // DC of (y_b0, y_b1)
+        z[S * 2] = make_float2(Qs[2], Qs[3]);          // Nyquist
+      } else {
+        z[tid * 2] = make_float2(Ps[0] - Qs[1], Ps[1] + Qs[0]);
+        z[(K - tid) * 2] = make_float2(Ps[2] + Qs[3], Ps[3] - Qs[2]);
+      }
     }
   }
   __syncthreads();
+  if constexpr (MODE == 1) {
+    // partial spectrum of the output pair (column 0 of z, row stride 2) -> workspace
+    float2* dst = part + ((long long)blockIdx.y * p + i) * K;
+    for (int f = tid; f < K; f += NT) dst[f] = z[2 * f];
+    return;
+  }
   // inverse transform of the single column (row stride 2); afterwards sample n of the pair sits
   // at position opos(n)
   if constexpr (K <= 16) {

@@ -5,7 +5,7 @@
 Configurations: cfg1 (FC 1024x1024, k=16, batch 1), cfg2 (FC 4096x4096, k=64, batch 64),
 cfg3 (9216->4096->4096 head, k=128, batch 256, both layers), cfg4 (3x3 CONV 256->256, 28x28,
 batch 32, k=64; --backward adds dx, dw and the bias gradient), cfg5 (FC 16384x16384, k=256,
-batch 1024; --backward adds dx and dw).
+batch 1024; --backward adds dx and dw), head_b1 (the two head layers of cfg3 at batch 1).
 Prints one line per layer with the time per call and the algorithmic bytes/flops rates.
 This is the companion of bench.py for the workloads that bench.py does not time; it is also
 the program that the rocprofv3 summaries under profiles/ were collected with.
@@ -106,7 +106,7 @@ def bench_conv(cfg, reps, backward=False):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", default="all", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "all"])
+    ap.add_argument("--config", default="all", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "head_b1", "all"])
     ap.add_argument("--reps", type=int, default=100)
     ap.add_argument("--backward", action="store_true")
     a = ap.parse_args()
@@ -120,6 +120,12 @@ def main():
         bench_fc(synth.CFG3_L2, a.reps)
     if sel("cfg4"):
         bench_conv(synth.CFG4, a.reps, backward=a.backward or a.config == "all")
+    if sel("head_b1"):
+        # the two head layers at batch 1 (single-image inference, the regime of the paper's
+        # layers-per-second figures): time per layer = 1 / (layers per second)
+        import dataclasses
+        bench_fc(dataclasses.replace(synth.CFG3_L1, name="head_fc9216x4096_k128_b1", batch=1), a.reps)
+        bench_fc(dataclasses.replace(synth.CFG3_L2, name="head_fc4096x4096_k128_b1", batch=1), a.reps)
     if sel("cfg5"):
         bench_fc(synth.CFG5, max(10, a.reps // 4), backward=a.backward or a.config == "all")
 

@@ -71,6 +71,23 @@ def test_fc_forward_one_or_two_vectors(k, q, batch):
     check(G.gpu_fc_forward(w, x), O.fc_forward(w, x), f"gemv k={k} q={q} B={batch} no epilogue")
 
 
+# ---- batch <= 2 on few block rows with long rows: two launches, the input blocks split over
+# several workgroups per block row (split counts 2..16, ragged last split, several chunks per split)
+@pytest.mark.parametrize("p,q,k", [(5, 72, 128), (3, 40, 256), (2, 130, 64), (3, 600, 16), (4, 17, 512), (32, 72, 128),
+                                   (1, 300, 32), (7, 1100, 8)])
+@pytest.mark.parametrize("batch", [1, 2])
+def test_fc_one_or_two_vectors_split(p, q, k, batch):
+    w, x, b = rand_fc(p, q, k, batch)
+    check(G.gpu_fc_forward(w, x, b, relu=True), O.fc_forward(w, x, b, relu=True), f"split gemv {p}x{q} k={k} B={batch}")
+    # backward-data of the transposed layer takes the same route
+    wt, _, _ = rand_fc(q, p, k, batch, bias=False)
+    dy = RNG.uniform(-1, 1, (batch, q * k)).astype(np.float32)
+    xt = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
+    dx, dw = G.gpu_fc_backward(wt, xt, dy)
+    check(dx, O.fc_backward_dx(wt, dy), f"split gemv dx {q}x{p} k={k} B={batch}")
+    check(dw, O.fc_backward_dw(xt, dy, k), f"split gemv dw {q}x{p} k={k} B={batch}")
+
+
 def test_fc_forward_bias_only_and_relu_only():
     w, x, b = rand_fc(4, 4, 16, 9)
     check(G.gpu_fc_forward(w, x, None, relu=True), O.fc_forward(w, x, None, relu=True), "relu only")
