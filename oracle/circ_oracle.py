@@ -32,7 +32,9 @@ circular convolution, finite differences and bilinear identities for the
 gradients, library convolution and single-pixel response for CONV; the CONV
 gradients and the bias gradient by finite differences, the library's own
 convolution gradients, the bilinear identities and the r = 1 reduction to the
-FC gradients.
+FC gradients; the gradient-descent steps by the library's own optimiser acting
+on gathered dense weights, a closed form for k = 1 and the decrease of a
+quadratic loss.
 """
 from __future__ import annotations
 
@@ -226,6 +228,25 @@ def bias_grad(dy, channel_axis=1) -> np.ndarray:
     dy = np.asarray(dy, dtype=np.float64)
     axes = tuple(ax for ax in range(dy.ndim) if ax != channel_axis)
     return dy.sum(axis=axes)
+
+
+def fc_sgd_step(w, x, dy, lr) -> np.ndarray:
+    """One plain gradient-descent step on the block vectors of an FC layer.
+
+    The training of Sec. 3.1 (Algorithm 2) ends in dL/dw_ij; the update itself is the
+    ordinary one, w_ij <- w_ij - lr * dL/dw_ij, with the gradient summed over the batch.
+    Because the FFT is linear, the same step applied to cached spectra,
+    FFT(w_ij) <- FFT(w_ij) - lr * FFT(dL/dw_ij), must give FFT of this result.
+    w[p][q][k], x[B][q*k], dy[B][p*k] -> w_new[p][q][k].
+    """
+    w = np.asarray(w, dtype=np.float64)
+    return w - float(lr) * fc_backward_dw(x, dy, w.shape[2])
+
+
+def conv_sgd_step(w, x, dy, lr, pad=0) -> np.ndarray:
+    """The same step for a block-circulant CONV layer (Sec. 3.2): w[r][r][p][q][k]."""
+    w = np.asarray(w, dtype=np.float64)
+    return w - float(lr) * conv_backward_dw(x, dy, w.shape[4], w.shape[0], pad)
 
 
 def max_norm_rel_err(got, ref) -> float:

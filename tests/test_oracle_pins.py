@@ -325,6 +325,71 @@ def test_bias_grad_closed_forms():
     assert abs((L(theta + e3) - L(theta - e3)) / (2 * eps) - O.bias_grad(dy)[3]) < 1e-6
 
 
+# ---- gradient-descent step on the block vectors ---------------------------------------------
+def _gather_index(p, q, k):
+    """idx[a][b] = flat position in w[p][q][k] of the weight at dense entry (a, b)."""
+    idx = np.zeros((p * k, q * k), dtype=np.int64)
+    for i in range(p):
+        for j in range(q):
+            for a in range(k):
+                for b in range(k):
+                    idx[i * k + a, j * k + b] = (i * q + j) * k + (a - b) % k
+    return idx
+
+
+@pytest.mark.parametrize("p,q,k,B", [(2, 3, 4, 5), (1, 1, 8, 3), (3, 2, 1, 4)])
+def test_fc_sgd_step_vs_library_optimiser(p, q, k, B):
+    """The library's SGD optimiser on the block vectors, the dense matrix gathered entry by
+    entry from them: autograd folds the dense gradient, the optimiser applies the step."""
+    w = RNG.standard_normal((p, q, k))
+    x = RNG.standard_normal((B, q * k))
+    dy = RNG.standard_normal((B, p * k))
+    lr = 0.037
+    wt = torch.from_numpy(w.reshape(-1).copy()).requires_grad_(True)
+    opt = torch.optim.SGD([wt], lr=lr)
+    Wd = wt[torch.from_numpy(_gather_index(p, q, k))]
+    ((torch.from_numpy(x) @ Wd.T) * torch.from_numpy(dy)).sum().backward()
+    opt.step()
+    np.testing.assert_allclose(O.fc_sgd_step(w, x, dy, lr), wt.detach().numpy().reshape(p, q, k), atol=1e-12)
+
+
+@pytest.mark.parametrize("k,r,pad", [(4, 3, 1), (2, 3, 0), (1, 1, 0)])
+def test_conv_sgd_step_vs_library_optimiser(k, r, pad):
+    p, q, N, H, W = 2, 2, 2, 5, 4
+    w = RNG.standard_normal((r, r, p, q, k))
+    x = RNG.standard_normal((N, q * k, H, W))
+    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    dy = RNG.standard_normal((N, p * k, Ho, Wo))
+    lr = 0.011
+    wt = torch.from_numpy(w.reshape(-1).copy()).requires_grad_(True)
+    opt = torch.optim.SGD([wt], lr=lr)
+    idx = _gather_index(p, q, k)
+    bank = torch.stack([torch.stack([wt[torch.from_numpy(idx + (dh * r + dw) * p * q * k)] for dw in range(r)], dim=-1)
+                        for dh in range(r)], dim=-2)          # [co][ci][dh][dw]
+    y = torch.nn.functional.conv2d(torch.from_numpy(x), bank, None, stride=1, padding=pad)
+    (y * torch.from_numpy(dy)).sum().backward()
+    opt.step()
+    np.testing.assert_allclose(O.conv_sgd_step(w, x, dy, lr, pad), wt.detach().numpy().reshape(w.shape), atol=1e-12)
+
+
+def test_sgd_step_closed_form_and_descent():
+    # k = 1, p = q = 1: a scalar weight; w' = w - lr * sum_b dy_b x_b
+    x = RNG.standard_normal((6, 1)); dy = RNG.standard_normal((6, 1))
+    got = O.fc_sgd_step(np.array([[[0.5]]]), x, dy, 0.1)
+    assert abs(got[0, 0, 0] - (0.5 - 0.1 * float((x * dy).sum()))) < 1e-14
+    # a small step along the negative gradient of L = 1/2 |y - t|^2 lowers L; lr = 0 changes nothing
+    p, q, k, B = 2, 2, 4, 7
+    w = RNG.standard_normal((p, q, k)); x = RNG.standard_normal((B, q * k)); t = RNG.standard_normal((B, p * k))
+    loss = lambda ww: 0.5 * float(((O.fc_forward(ww, x) - t) ** 2).sum())
+    dy = O.fc_forward(w, x) - t
+    assert loss(O.fc_sgd_step(w, x, dy, 1e-3)) < loss(w)
+    np.testing.assert_array_equal(O.fc_sgd_step(w, x, dy, 0.0), w)
+    # first-order decrease: L(w') - L(w) = -lr |dw|^2 + O(lr^2)
+    g = O.fc_backward_dw(x, dy, k)
+    lr = 1e-6
+    assert abs((loss(O.fc_sgd_step(w, x, dy, lr)) - loss(w)) / (-lr * float((g * g).sum())) - 1.0) < 1e-3
+
+
 def test_error_measure():
     ref = np.array([1.0, -4.0, 0.0]); got = np.array([1.0, -4.0, 0.002])
     assert abs(O.max_norm_rel_err(got, ref) - 0.0005) < 1e-15
