@@ -148,6 +148,37 @@ circ_status circ_conv_backward(const void* w_hat, const float* x, const float* d
                                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * One gradient-descent step taken on the cached spectra (training, Sec. 3.1 / Algorithm 2).
+ * Algorithm 2 yields dL/dw_ij as the inverse FFT of a spectrum G_ij summed over the batch; the
+ * step w_ij <- w_ij - lr * dL/dw_ij and the FFT are both linear, so these calls subtract
+ * (lr/k) * G_ij from the stored FFT(w_ij)/k directly: no inverse transform of the gradient, no
+ * forward transform of the new weights.  Afterwards `w_hat` is what circ_precompute_spectra
+ * would return for w - lr * dw (dw as defined at circ_fc_backward / circ_conv_backward), up to
+ * fp32 rounding, in every operand order the blob holds.
+ *   w_hat  device blob, updated in place; x, dy, dx and the workspace must not overlap it
+ *   dx     optional (NULL to skip): backward-data, computed from the spectra before the step
+ *   lr     step size (any finite float; 0 leaves the weights unchanged); NaN -> CIRC_EINVAL
+ *   other arguments, workspace size and error behaviour as for the backward call of the layer
+ * Deterministic.  Calls that share a blob must be ordered by the caller (same stream).
+ */
+circ_status circ_fc_sgd_step(void* w_hat, const float* x, const float* dy, float* dx, float lr,
+                             int p, int q, int k, int batch,
+                             void* workspace, size_t workspace_bytes, void* stream);
+circ_status circ_conv_sgd_step(void* w_hat, const float* x, const float* dy, float* dx, float lr,
+                               int N, int C_in, int C_out, int H, int W,
+                               int r, int stride, int pad, int k,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Block vectors back from a spectra blob (the inverse of circ_precompute_spectra; Sec. 3.1:
+ * either w_ij or FFT(w_ij) represents a block).  Needed after circ_*_sgd_step, when the blob is
+ * the only up-to-date copy of the weights.
+ *   w_hat  device blob of (n_grids, p, q, k);  w  device, [n_grids][p][q][k] floats, overwritten
+ */
+circ_status circ_export_weights(const void* w_hat, int n_grids, int p, int q, int k,
+                                float* w, void* stream);
+
+/*
  * Bias gradient (Eq. 1: a = Wx + theta, so dL/dtheta is dL/da summed over everything but the
  * channel).  dy is viewed as [outer][channels][inner]:
  *   db[c] = sum_{o, t} dy[(o*channels + c)*inner + t]

@@ -35,6 +35,9 @@ SIGNATURES = {
     "circ_conv_backward_workspace_bytes": (_c_size, [_c_int] * 9),
     "circ_conv_backward": (_c_int, [_c_ptr] * 5 + [_c_int] * 9 + [_c_ptr, _c_size, _c_ptr]),
     "circ_bias_grad": (_c_int, [_c_ptr, _c_ptr, ctypes.c_longlong, _c_int, ctypes.c_longlong, _c_ptr]),
+    "circ_fc_sgd_step": (_c_int, [_c_ptr] * 4 + [ctypes.c_float] + [_c_int] * 4 + [_c_ptr, _c_size, _c_ptr]),
+    "circ_conv_sgd_step": (_c_int, [_c_ptr] * 4 + [ctypes.c_float] + [_c_int] * 9 + [_c_ptr, _c_size, _c_ptr]),
+    "circ_export_weights": (_c_int, [_c_ptr] + [_c_int] * 4 + [_c_ptr, _c_ptr]),
 }
 
 
@@ -163,6 +166,41 @@ def circ_conv_backward(w_hat, x, dy, C_in, H, W, r, stride, pad, k, need_dx=True
                                     _ptr(dw if need_dw else None), N, C_in, C_out, H, W, r, stride, pad, k,
                                     _ptr(workspace), workspace.numel(), _stream()), "circ_conv_backward")
     return (dx if need_dx else None), (dw if need_dw else None)
+
+
+def circ_fc_sgd_step(w_hat, x, dy, lr, p, q, k, need_dx=False, dx=None, workspace=None):
+    """Updates the blob in place by -lr * dL/dw; returns dx [batch][q*k] (from the old weights) or None."""
+    batch = dy.shape[0]
+    if need_dx and dx is None:
+        dx = torch.empty(batch, q * k, dtype=torch.float32, device=dy.device)
+    if workspace is None:
+        workspace = torch.empty(max(1, circ_fc_workspace_bytes(p, q, k, batch, True)), dtype=torch.uint8,
+                                device=dy.device)
+    _check(lib().circ_fc_sgd_step(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx if need_dx else None), float(lr), p, q, k,
+                                  batch, _ptr(workspace), workspace.numel(), _stream()), "circ_fc_sgd_step")
+    return dx if need_dx else None
+
+
+def circ_conv_sgd_step(w_hat, x, dy, lr, C_in, H, W, r, stride, pad, k, need_dx=False, dx=None, workspace=None):
+    """CONV counterpart of circ_fc_sgd_step; dy: NCHW [N][C_out][Ho][Wo]."""
+    N, C_out = dy.shape[0], dy.shape[1]
+    if need_dx and dx is None:
+        dx = torch.empty(N, C_in, H, W, dtype=torch.float32, device=dy.device)
+    if workspace is None:
+        nb = circ_conv_backward_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
+        workspace = torch.empty(max(1, nb), dtype=torch.uint8, device=dy.device)
+    _check(lib().circ_conv_sgd_step(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx if need_dx else None), float(lr), N, C_in,
+                                    C_out, H, W, r, stride, pad, k, _ptr(workspace), workspace.numel(), _stream()),
+           "circ_conv_sgd_step")
+    return dx if need_dx else None
+
+
+def circ_export_weights(w_hat, n_grids, p, q, k, w=None):
+    """Block vectors [n_grids][p][q][k] recovered from a spectra blob."""
+    if w is None:
+        w = torch.empty(n_grids, p, q, k, dtype=torch.float32, device=w_hat.device)
+    _check(lib().circ_export_weights(_ptr(w_hat), n_grids, p, q, k, _ptr(w), _stream()), "circ_export_weights")
+    return w
 
 
 def circ_bias_grad(dy, db=None):

@@ -11,6 +11,7 @@
 #include "circ_gemv.h"
 #include "circ_conv_fused.h"
 #include "circ_conv_bwd.h"
+#include "circ_update.h"
 
 namespace {
 
@@ -418,6 +419,42 @@ inline bool fc_dims_ok(int p, int q, int k, int batch) {
   return true;
 }
 
+// Sections 2.. of the blob (the operand orders of the fused, streaming and CONV kernels) are
+// rearrangements of the two spectrum sections; this rewrites all of them from those two.
+circ_status pack_derived_sections(void* w_hat, int n_grids, int p, int q, int k, hipStream_t s) {
+  const BlobLayout bl = blob_layout(n_grids, p, q, k);
+  const float2* fwd = blob_at<float2>(w_hat, bl.fwd);
+  const float2* bwd = blob_at<float2>(w_hat, bl.bwd);
+  // The backward section [f][i][j] (conjugated) is exactly the "[f][j'][i']" forward section of the
+  // transposed grid (p' = q output block rows, q' = p input blocks), so the same packing
+  // produces the operands that make backward-data a forward pass.  For CONV, backward-data is
+  // the forward kernel on the transposed grids with the conjugated spectra and the reflected filter.
+  PackPlan pl;
+  pl.n = 0;
+  unsigned blocks = 0;
+  auto add = [&](int kind, const float2* spec, size_t off, int pp, int qq, int a, int b, size_t elems) {
+    if (!elems) return;
+    const int i = pl.n++;
+    pl.first[i] = blocks;
+    pl.kind[i] = kind; pl.spec[i] = spec; pl.dst[i] = blob_at<char>(w_hat, off);
+    pl.p[i] = pp; pl.q[i] = qq; pl.a[i] = a; pl.b[i] = b;
+    blocks += (unsigned)cdiv((long long)elems, 256);
+  };
+  const bool fused = fused_section_elems(n_grids, p, q, k) != 0;   // block size served by the fused FC kernel
+  add(0, fwd, bl.fused_fwd, p, q, fused ? fused_igp(p, k) : 0, fused ? fused_q2p(q, k) : 0, fused_section_elems(n_grids, p, q, k));
+  add(1, fwd, bl.gemv_fwd, p, q, 0, 0, gemv_section_elems(n_grids, p, q, k));
+  add(0, bwd, bl.fused_bwd, q, p, fused ? fused_igp(q, k) : 0, fused ? fused_q2p(p, k) : 0, fused_section_elems(n_grids, q, p, k));
+  add(1, bwd, bl.gemv_bwd, q, p, 0, 0, gemv_section_elems(n_grids, q, p, k));
+  const size_t nconv = conv_section_elems(n_grids, p, q, k), nconvb = conv_section_elems(n_grids, q, p, k);
+  add(2, fwd, bl.conv, p, q, nconv ? int(nconv / (size_t(n_grids) * q * 64)) : 0, 0, nconv);
+  add(2, bwd, bl.conv_bwd, q, p, nconvb ? int(nconvb / (size_t(n_grids) * p * 64)) : 0, 1, nconvb);
+  if (pl.n == 0) return CIRC_OK;
+  pl.first[pl.n] = blocks;
+  hipLaunchKernelGGL(pack_sections_kernel, dim3(blocks), dim3(256), 0, s, pl, n_grids, k);
+  if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  return CIRC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -458,40 +495,7 @@ circ_status circ_precompute_spectra(const float* w, int n_grids, int p, int q, i
   // backward operand: row id = i*q + j, conjugated
   RowMap mb{q, p, (long long)k, (long long)q * k, 0, 1};
   if (launch_rfft(k, false, w, bwd, mb, rows, rows, n_grids, in_g, out_g, inv_k, 1, s) != hipSuccess) return CIRC_EHIP;
-  // The backward section [f][i][j] (conjugated) is exactly the "[f][j'][i']" forward section of the
-  // transposed grid (p' = q output block rows, q' = p input blocks), so the same pack kernels
-  // produce the operands that make backward-data a forward pass.
-  struct { const float2* spec; int pp, qq; size_t fused_off, gemv_off; } dir[2] = {
-      {fwd, p, q, bl.fused_fwd, bl.gemv_fwd}, {bwd, q, p, bl.fused_bwd, bl.gemv_bwd}};
-  for (const auto& d : dir) {
-    const size_t nfused = fused_section_elems(n_grids, d.pp, d.qq, k);
-    if (nfused) {
-      hipLaunchKernelGGL(pack_fused_kernel, dim3((unsigned)cdiv((long long)nfused, 256)), dim3(256), 0, s, d.spec,
-                         blob_at<float4>(w_hat, d.fused_off), d.pp, d.qq, k, fused_igp(d.pp, k), fused_q2p(d.qq, k));
-      if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
-    }
-    const size_t ngemv = gemv_section_elems(n_grids, d.pp, d.qq, k);
-    if (ngemv) {
-      hipLaunchKernelGGL(pack_gemv_kernel, dim3((unsigned)cdiv((long long)ngemv, 256)), dim3(256), 0, s, d.spec,
-                         blob_at<float2>(w_hat, d.gemv_off), d.pp, d.qq, k);
-      if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
-    }
-  }
-  const size_t nconv = conv_section_elems(n_grids, p, q, k);
-  if (nconv) {
-    hipLaunchKernelGGL(pack_conv_kernel, dim3((unsigned)cdiv((long long)nconv, 256)), dim3(256), 0, s, fwd,
-                       blob_at<float2>(w_hat, bl.conv), n_grids, p, q, k, int(nconv / (size_t(n_grids) * q * 64)), 0);
-    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
-  }
-  // backward-data of a CONV layer is the forward kernel on the transposed grids (q output blocks,
-  // p input blocks) with the conjugated spectra and the reflected filter
-  const size_t nconvb = conv_section_elems(n_grids, q, p, k);
-  if (nconvb) {
-    hipLaunchKernelGGL(pack_conv_kernel, dim3((unsigned)cdiv((long long)nconvb, 256)), dim3(256), 0, s, bwd,
-                       blob_at<float2>(w_hat, bl.conv_bwd), n_grids, q, p, k, int(nconvb / (size_t(n_grids) * p * 64)), 1);
-    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
-  }
-  return CIRC_OK;
+  return pack_derived_sections(w_hat, n_grids, p, q, k, s);
 }
 
 size_t circ_fc_workspace_bytes(int p, int q, int k, int batch, int backward) {
@@ -558,18 +562,46 @@ circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias
   return CIRC_OK;
 }
 
-circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy, float* dx, float* dw, int p, int q,
-                             int k, int batch, void* workspace, size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Launch one step (kernel above) on the spectrum sections of `w_hat`, then rebuild the operand
+// sections that are rearrangements of them.  `src` holds nparts partial spectra
+// [f][g][i][j] (strides given), not normalised: a = lr / k.
+circ_status apply_spectra_step(void* w_hat, const float2* src, int nparts, long long part_stride, long long src_fstride,
+                               long long src_gstride, int n_grids, int p, int q, int k, float lr, hipStream_t s) {
+  const BlobLayout bl = blob_layout(n_grids, p, q, k);
+  const int NF = k / 2 + 1;
+  dim3 grid((unsigned)(cdiv(p, 32) * cdiv(q, 32)), (unsigned)NF, (unsigned)n_grids);
+  hipLaunchKernelGGL(spectra_step_kernel, grid, dim3(256), 0, s, src, nparts, part_stride, src_fstride, src_gstride,
+                     blob_at<float2>(w_hat, bl.fwd), blob_at<float2>(w_hat, bl.bwd), p, q, NF, lr / float(k));
+  if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  return pack_derived_sections(w_hat, n_grids, p, q, k, s);
+}
+
+// FC backward.  `dw` receives the gradient of the block vectors; `w_upd` (the same blob as
+// w_hat, writable) takes the step -lr * gradient in the frequency domain instead.  Either, both
+// or neither may be given; backward-data always reads the spectra as they are on entry.
+circ_status fc_backward_impl(const void* w_hat, const float* x, const float* dy, float* dx, float* dw, void* w_upd,
+                             float lr, int p, int q, int k, int batch, void* workspace, size_t workspace_bytes,
+                             void* stream) {
   if (!fc_dims_ok(p, q, k, batch)) return CIRC_EINVAL;
   if (!w_hat || !dy) return CIRC_EINVAL;
-  if (!dx && !dw) return CIRC_EINVAL;
-  if (dw && !x) return CIRC_EINVAL;
+  if (!dx && !dw && !w_upd) return CIRC_EINVAL;
+  if ((dw || w_upd) && !x) return CIRC_EINVAL;
   if (!aligned16(w_hat) || !aligned16(dy) || !aligned16(x) || !aligned16(dx) || !aligned16(dw)) return CIRC_EINVAL;
   const size_t xbytes = size_t(batch) * q * k * sizeof(float), ybytes = size_t(batch) * p * k * sizeof(float);
   const size_t wbytes = size_t(p) * q * k * sizeof(float);
   if (dx && (overlaps(dx, xbytes, dy, ybytes) || (x && overlaps(dx, xbytes, x, xbytes)))) return CIRC_EINVAL;
   if (dw && (overlaps(dw, wbytes, dy, ybytes) || overlaps(dw, wbytes, x, xbytes))) return CIRC_EINVAL;
   if (dx && dw && overlaps(dx, xbytes, dw, wbytes)) return CIRC_EINVAL;
+  if (w_upd) {   // the blob is rewritten: none of the operands may lie inside it
+    const size_t bbytes = circ_spectra_bytes(1, p, q, k);
+    if (overlaps(w_upd, bbytes, x, xbytes) || overlaps(w_upd, bbytes, dy, ybytes) || (dx && overlaps(w_upd, bbytes, dx, xbytes)) ||
+        (dw && overlaps(w_upd, bbytes, dw, wbytes)))
+      return CIRC_EINVAL;
+  }
   const size_t need = circ_fc_workspace_bytes(p, q, k, batch, 1);
   if (!workspace || workspace_bytes < need) return CIRC_EWORKSPACE;
   if (!aligned16(workspace)) return CIRC_EINVAL;
@@ -591,7 +623,8 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
   const int ksplit = cgemm_ksplit(NF, p, q, batch);
   // The tiled GEMM reads dY^ in the [f][i][b] order of backward-data, so dy is transformed once
   // for both results; the one-wave-per-tile GEMM needs the batch-major order [f][b][i].
-  const bool dw_shares_dy = dw && cgemm_takes_tiled(NF, p, q, batch, ksplit);
+  const bool want_dw = dw || w_upd;
+  const bool dw_shares_dy = want_dw && cgemm_takes_tiled(NF, p, q, batch, ksplit);
   bool have_dyh = false;   // bufy holds dY^[f][i][b]
   if (dx && batch <= 2 && k >= 4) {
     if (launch_gemv(k, blob_at<float2>(w_hat, bl.gemv_bwd), dy, nullptr, dx, q, p, batch, 0, workspace, s) != hipSuccess) return CIRC_EHIP;
@@ -607,7 +640,7 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
     RowMap mdx{batch, q, (long long)q * k, (long long)k, 0, 1};
     if (launch_irfft(k, false, bufx, dx, mdx, xrows, xfs, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
   }
-  if (dw) {
+  if (want_dw) {
     // dW^[f][i][j] = sum_b dY^[f][i][b] conj(X^[f][b][j]); X^ is batch-major, dY^ is [f][i][b] for
     // the tiled GEMM (shared with backward-data above) and batch-major [f][b][i] otherwise
     if (dw_shares_dy) {
@@ -627,9 +660,45 @@ circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy,
       return CIRC_EHIP;
     const long long wrows = (long long)p * q;
     RowMap mw{q, p, (long long)k, (long long)q * k, 0, 1};
-    if (launch_irfft(k, false, bufw, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, ksplit, wpart) != hipSuccess)
+    if (dw && launch_irfft(k, false, bufw, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, ksplit, wpart) != hipSuccess)
       return CIRC_EHIP;
+    if (w_upd) return apply_spectra_step(w_upd, bufw, ksplit, wpart, wrows, 0, 1, p, q, k, lr, s);
   }
+  return CIRC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+circ_status circ_fc_backward(const void* w_hat, const float* x, const float* dy, float* dx, float* dw, int p, int q,
+                             int k, int batch, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dx && !dw) return CIRC_EINVAL;
+  return fc_backward_impl(w_hat, x, dy, dx, dw, nullptr, 0.f, p, q, k, batch, workspace, workspace_bytes, stream);
+}
+
+circ_status circ_fc_sgd_step(void* w_hat, const float* x, const float* dy, float* dx, float lr, int p, int q, int k,
+                             int batch, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!w_hat || !(lr == lr)) return CIRC_EINVAL;   // NaN step
+  return fc_backward_impl(w_hat, x, dy, dx, nullptr, w_hat, lr, p, q, k, batch, workspace, workspace_bytes, stream);
+}
+
+circ_status circ_export_weights(const void* w_hat, int n_grids, int p, int q, int k, float* w, void* stream) {
+  if (!w || !w_hat || n_grids <= 0 || n_grids > 65535 || p <= 0 || q <= 0 || !valid_k(k)) return CIRC_EINVAL;
+  if ((long long)p * q > (1ll << 31) - 1) return CIRC_EINVAL;
+  if (!aligned16(w) || !aligned16(w_hat)) return CIRC_EINVAL;
+  if (overlaps(w, size_t(n_grids) * p * q * k * sizeof(float), w_hat, circ_spectra_bytes(n_grids, p, q, k)))
+    return CIRC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const BlobLayout bl = blob_layout(n_grids, p, q, k);
+  const float2* fwd = blob_at<float2>(w_hat, bl.fwd);
+  const long long rows = (long long)p * q;
+  // forward section of grid g: [f][j*p + i] = FFT(w[g][i][j])/k, so the plain inverse sum returns w
+  RowMap mf{p, q, (long long)q * k, (long long)k, 0, 1};
+  for (int g = 0; g < n_grids; ++g)
+    if (launch_irfft(k, false, fwd + (long long)g * spectrum_elems(k, rows), w + (long long)g * rows * k, mf, rows, rows,
+                     1.0f, nullptr, 1, 0, s) != hipSuccess)
+      return CIRC_EHIP;
   return CIRC_OK;
 }
 
@@ -814,13 +883,19 @@ size_t circ_conv_backward_workspace_bytes(int N, int C_in, int C_out, int H, int
   return xa + ya + wa * size_t(cdiv(npix, conv_dw_pix_per_block(npix)));
 }
 
-circ_status circ_conv_backward(const void* w_hat, const float* x, const float* dy, float* dx, float* dw, int N, int C_in,
-                               int C_out, int H, int W, int r, int stride, int pad, int k, void* workspace,
-                               size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// CONV backward; dw / w_upd as in fc_backward_impl.
+circ_status conv_backward_impl(const void* w_hat, const float* x, const float* dy, float* dx, float* dw, void* w_upd,
+                               float lr, int N, int C_in, int C_out, int H, int W, int r, int stride, int pad, int k,
+                               void* workspace, size_t workspace_bytes, void* stream) {
   if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k)) return CIRC_EINVAL;
   if (stride <= 0) return CIRC_EINVAL;
   if (stride != 1 || (r % 2) == 0) return CIRC_ENOTSUP;
-  if (!w_hat || !dy || (!dx && !dw) || (dw && !x)) return CIRC_EINVAL;
+  const bool want_dw = dw || w_upd;
+  if (!w_hat || !dy || (!dx && !want_dw) || (want_dw && !x)) return CIRC_EINVAL;
   if (!aligned16(w_hat) || !aligned16(dy) || !aligned16(x) || !aligned16(dx) || !aligned16(dw)) return CIRC_EINVAL;
   const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
   const int p = C_out / k, q = C_in / k, NF = k / 2 + 1;
@@ -831,6 +906,12 @@ circ_status circ_conv_backward(const void* w_hat, const float* x, const float* d
   if (dx && (overlaps(dx, xbytes, dy, ybytes) || (x && overlaps(dx, xbytes, x, xbytes)))) return CIRC_EINVAL;
   if (dw && (overlaps(dw, wbytes, dy, ybytes) || overlaps(dw, wbytes, x, xbytes))) return CIRC_EINVAL;
   if (dx && dw && overlaps(dx, xbytes, dw, wbytes)) return CIRC_EINVAL;
+  if (w_upd) {   // the blob is rewritten: none of the operands may lie inside it
+    const size_t bbytes = circ_spectra_bytes(r * r, p, q, k);
+    if (overlaps(w_upd, bbytes, x, xbytes) || overlaps(w_upd, bbytes, dy, ybytes) || (dx && overlaps(w_upd, bbytes, dx, xbytes)) ||
+        (dw && overlaps(w_upd, bbytes, dw, wbytes)))
+      return CIRC_EINVAL;
+  }
   const size_t need = circ_conv_backward_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k);
   if (!workspace || workspace_bytes < need) return CIRC_EWORKSPACE;
   if (!aligned16(workspace)) return CIRC_EINVAL;
@@ -855,7 +936,7 @@ circ_status circ_conv_backward(const void* w_hat, const float* x, const float* d
   }
   // dY^[f][i][n][pixel]: the FFT runs down the channel axis of dy
   RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo, HWo % 4 == 0};
-  if (dw || (dx && !dx_fused)) {
+  if (want_dw || (dx && !dx_fused)) {
     if (launch_rfft(k, true, dy, yh, my, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
   }
   RowMap mx{(int)HW, N, 1, (long long)C_in * HW, (long long)k * HW, HW, HW % 4 == 0};
@@ -870,7 +951,7 @@ circ_status circ_conv_backward(const void* w_hat, const float* x, const float* d
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
     if (launch_irfft(k, true, xh, dx, mx, xrows, xrows, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
   }
-  if (dw) {
+  if (want_dw) {
     if (launch_rfft(k, true, x, xh, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
     const long long npix = (long long)N * HWo, ppb = conv_dw_pix_per_block(npix);
     const int nchunks = (int)cdiv(npix, ppb);
@@ -899,10 +980,31 @@ circ_status circ_conv_backward(const void* w_hat, const float* x, const float* d
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
     // dw[g][i][j][:] = IFFT over f of the summed partial spectra, scale 1/k
     RowMap mw{(int)wrows, 1, (long long)k, 0, 0, 1};
-    if (launch_irfft(k, false, wpart, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, nchunks, wstride) != hipSuccess)
+    if (dw && launch_irfft(k, false, wpart, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, nchunks, wstride) != hipSuccess)
       return CIRC_EHIP;
+    if (w_upd) return apply_spectra_step(w_upd, wpart, nchunks, wstride, wrows, (long long)p * q, r * r, p, q, k, lr, s);
   }
   return CIRC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+circ_status circ_conv_backward(const void* w_hat, const float* x, const float* dy, float* dx, float* dw, int N, int C_in,
+                               int C_out, int H, int W, int r, int stride, int pad, int k, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  if (!dx && !dw) return CIRC_EINVAL;
+  return conv_backward_impl(w_hat, x, dy, dx, dw, nullptr, 0.f, N, C_in, C_out, H, W, r, stride, pad, k, workspace,
+                            workspace_bytes, stream);
+}
+
+circ_status circ_conv_sgd_step(void* w_hat, const float* x, const float* dy, float* dx, float lr, int N, int C_in,
+                               int C_out, int H, int W, int r, int stride, int pad, int k, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  if (!w_hat || !(lr == lr)) return CIRC_EINVAL;   // NaN step
+  return conv_backward_impl(w_hat, x, dy, dx, nullptr, w_hat, lr, N, C_in, C_out, H, W, r, stride, pad, k, workspace,
+                            workspace_bytes, stream);
 }
 
 circ_status circ_bias_grad(const float* dy, float* db, long long outer, int channels, long long inner, void* stream) {

@@ -54,11 +54,10 @@ inline size_t conv_fused_lds_bytes(int nrows, int ncoli) {
 // `spec` is the [g][f][j][i] section.  flip: grid g takes the spectra of grid n_grids-1-g (the
 // spatially reflected filter of backward-data, where `spec` is the conjugated, transposed
 // section and p, q are the block counts of the transposed grids).
-__global__ void pack_conv_kernel(const float2* __restrict__ spec, float2* __restrict__ Wc, int n_grids, int p, int q,
-                                 int K, int ncombo, int flip) {
+__device__ __forceinline__ void pack_conv_elem(long long idx, const float2* __restrict__ spec, float2* __restrict__ Wc,
+                                               int n_grids, int p, int q, int K, int ncombo, int flip) {
   const int FG = K / 32;
   const long long total = (long long)n_grids * q * ncombo * 64;
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
   const int l = int(idx & 63);
   long long rr = idx >> 6;

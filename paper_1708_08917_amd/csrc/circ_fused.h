@@ -71,11 +71,11 @@ struct FusedShape {
 // slot 0 = (W^[0].re, W^[K/2].re).  The section is padded with zeros to whole tiles:
 // igp groups of 4 block rows (p rounded up to the kernel's IT), q2p pairs of block columns
 // (q rounded up to the kernel's chunk).  `spec` is the [f][j][i] section.
-__global__ void pack_fused_kernel(const float2* __restrict__ spec, float4* __restrict__ Wf, int p, int q, int K,
-                                  int igp, int q2p) {
+// Element idx of the section (one call per element; see pack_sections_kernel).
+__device__ __forceinline__ void pack_fused_elem(long long idx, const float2* __restrict__ spec, float4* __restrict__ Wf,
+                                                int p, int q, int K, int igp, int q2p) {
   const int FG = K / 32;
   const long long total = (long long)igp * q2p * FG * 64;
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
   const int l = int(idx & 63);
   long long r = idx >> 6;

@@ -39,10 +39,10 @@ struct GemvShape {
 
 // Weight spectra for the batch <= 2 kernel: Wg[(i*q + j)*S + slot], slot 0 = (W^[0].re,
 // W^[K/2].re), slot f = W^[f] otherwise.  `spec` is the [f][j][i] section.
-__global__ void pack_gemv_kernel(const float2* __restrict__ spec, float2* __restrict__ Wg, int p, int q, int K) {
+__device__ __forceinline__ void pack_gemv_elem(long long idx, const float2* __restrict__ spec, float2* __restrict__ Wg,
+                                               int p, int q, int K) {
   const int S = K / 2;
   const long long total = (long long)p * q * S;
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
   const int slot = int(idx % S);
   const long long ij = idx / S;

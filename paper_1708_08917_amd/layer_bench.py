@@ -75,6 +75,10 @@ def bench_fc(cfg, reps, backward=False):
         tdw = _time(lambda: B.circ_fc_backward(wh, xd, dy, cfg.p, cfg.q, cfg.k, False, True, None, dw, ws), r, 3)
         print(f"{cfg.name}: backward {tb:9.2f} us/call (dx only {tdx:.2f}, dw only {tdw:.2f})  dense-equivalent "
               f"{4.0 * cfg.n_in * cfg.n_out * cfg.batch / tb * 1e-6:7.1f} TFLOP/s", flush=True)
+        # dx + step on the cached spectra (lr = 0 keeps the weights as they are over the repetitions),
+        # against dx + dw + precompute of the new weights
+        tsg = _time(lambda: B.circ_fc_sgd_step(wh, xd, dy, 0.0, cfg.p, cfg.q, cfg.k, True, dx, ws), r, 3)
+        print(f"{cfg.name}: sgd step {tsg:9.2f} us/call (backward + precompute: {tb + tp:.2f})", flush=True)
 
 
 def bench_conv(cfg, reps, backward=False):
@@ -102,6 +106,10 @@ def bench_conv(cfg, reps, backward=False):
         tdb = _time(lambda: B.circ_bias_grad(dy, db), r, 3)
         print(f"{cfg.name}: backward {tb:9.2f} us/call (dx only {tdx:.2f}, dw only {tdw:.2f}; bias gradient {tdb:.2f})  "
               f"dense-equivalent {2.0 * dense / tb * 1e-6:7.1f} TFLOP/s", flush=True)
+        tp = _time(lambda: B.circ_precompute_spectra(wd, wh), 20, 3)
+        tsg = _time(lambda: B.circ_conv_sgd_step(wh, xd, dy, 0.0, cfg.C_in, cfg.H, cfg.W, cfg.r, 1, cfg.pad, cfg.k, True, dx,
+                                                 wsb), r, 3)
+        print(f"{cfg.name}: sgd step {tsg:9.2f} us/call (backward + precompute: {tb + tp:.2f})", flush=True)
 
 
 def main():

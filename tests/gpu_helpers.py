@@ -53,3 +53,29 @@ def gpu_bias_grad(dy):
     torch.cuda.synchronize()
     return db.cpu().numpy()
 
+
+
+def gpu_fc_sgd_steps(w, batches, lr, need_dx=False):
+    """Precompute once, take one step per (x, dy) pair on the spectra, export the weights.
+    Returns (w_new [p][q][k], blob, list of dx)."""
+    p, q, k = w.shape
+    wh = B.circ_precompute_spectra(dev(w.astype(np.float32)))
+    dxs = []
+    for x, dy in batches:
+        dx = B.circ_fc_sgd_step(wh, dev(x.astype(np.float32)), dev(dy.astype(np.float32)), lr, p, q, k, need_dx=need_dx)
+        dxs.append(None if dx is None else dx.cpu().numpy())
+    w_new = B.circ_export_weights(wh, 1, p, q, k).cpu().numpy().reshape(p, q, k)
+    return w_new, wh, dxs
+
+
+def gpu_conv_sgd_steps(w, batches, lr, pad, need_dx=False):
+    r, _, p, q, k = w.shape
+    wh = B.circ_precompute_spectra(dev(w.astype(np.float32)))
+    dxs = []
+    for x, dy in batches:
+        _, C_in, H, W = x.shape
+        dx = B.circ_conv_sgd_step(wh, dev(x.astype(np.float32)), dev(dy.astype(np.float32)), lr, C_in, H, W, r, 1, pad, k,
+                                  need_dx=need_dx)
+        dxs.append(None if dx is None else dx.cpu().numpy())
+    w_new = B.circ_export_weights(wh, r * r, p, q, k).cpu().numpy().reshape(w.shape)
+    return w_new, wh, dxs

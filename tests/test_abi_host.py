@@ -145,6 +145,43 @@ def test_conv_backward_argument_errors():
     assert wb(1, 8, 8, 4, 4, 3, 2, 1, 4) == 0 and wb(1, 6, 8, 4, 4, 3, 1, 1, 4) == 0
 
 
+def test_sgd_step_and_export_argument_errors():
+    import ctypes
+    big = 1 << 28
+    f = B.lib().circ_fc_sgd_step
+
+    def call(w_hat=A, x=A + big, dy=A + 2 * big, dx=A + 3 * big, lr=0.1, p=2, q=2, k=8, batch=2, wsp=A + 5 * big,
+             wsb=1 << 30):
+        return f(w_hat, x, dy, dx, ctypes.c_float(lr), p, q, k, batch, wsp, wsb, None)
+
+    assert call(w_hat=None) == B.CIRC_EINVAL
+    assert call(lr=float("nan")) == B.CIRC_EINVAL
+    assert call(x=None) == B.CIRC_EINVAL                      # the step needs x
+    assert call(k=12) == B.CIRC_EINVAL
+    assert call(batch=0) == B.CIRC_EINVAL
+    assert call(x=A + 256) == B.CIRC_EINVAL                   # x lies inside the blob that is rewritten
+    assert call(dx=A) == B.CIRC_EINVAL
+    assert call(wsb=0) == B.CIRC_EWORKSPACE
+    g = B.lib().circ_conv_sgd_step
+
+    def callc(w_hat=A, x=A + big, dy=A + 2 * big, dx=None, lr=0.1, N=1, C_in=8, C_out=8, H=4, W=4, r=3, stride=1, pad=1,
+              k=4, wsp=A + 5 * big, wsb=1 << 30):
+        return g(w_hat, x, dy, dx, ctypes.c_float(lr), N, C_in, C_out, H, W, r, stride, pad, k, wsp, wsb, None)
+
+    assert callc(w_hat=None) == B.CIRC_EINVAL
+    assert callc(lr=float("nan")) == B.CIRC_EINVAL
+    assert callc(stride=2) == B.CIRC_ENOTSUP
+    assert callc(x=None) == B.CIRC_EINVAL
+    assert callc(dy=A + 512) == B.CIRC_EINVAL                 # dy lies inside the blob
+    assert callc(wsb=64) == B.CIRC_EWORKSPACE
+    e = B.lib().circ_export_weights
+    assert e(A, 1, 2, 2, 8, None, None) == B.CIRC_EINVAL
+    assert e(None, 1, 2, 2, 8, A + big, None) == B.CIRC_EINVAL
+    assert e(A, 0, 2, 2, 8, A + big, None) == B.CIRC_EINVAL
+    assert e(A, 1, 2, 2, 12, A + big, None) == B.CIRC_EINVAL
+    assert e(A, 1, 2, 2, 8, A + 64, None) == B.CIRC_EINVAL    # w lies inside the blob
+
+
 def test_bias_grad_argument_errors():
     f = B.lib().circ_bias_grad
     assert f(None, A, 2, 8, 1, None) == B.CIRC_EINVAL

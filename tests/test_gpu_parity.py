@@ -268,6 +268,90 @@ def test_bias_grad(shape):
 # ---- seeded sweep over random valid shapes: every entry point, every dispatch path that small
 # shapes reach (streaming kernel, fused kernels with one or several chunks, unfused route,
 # fused and unfused CONV), ragged everywhere
+# ---- gradient step on the cached spectra -------------------------------------------------------
+def _step_size(w, dw):
+    """A step that changes the weights by about half their size, so that both terms of
+    w - lr*dw carry weight in the comparison."""
+    return float(0.5 * np.max(np.abs(w)) / max(np.max(np.abs(dw)), 1e-30))
+
+
+@pytest.mark.parametrize("k", [2, 4, 8, 16, 32, 64, 128, 256, 512])
+def test_export_weights_roundtrip(k):
+    for n_grids, p, q in ((1, 3, 5), (9, 2, 3)):
+        w = RNG.standard_normal((n_grids, p, q, k)).astype(np.float32)
+        wh = B.circ_precompute_spectra(G.dev(w))
+        check(B.circ_export_weights(wh, n_grids, p, q, k).cpu().numpy(), w, f"export k={k} grids={n_grids}")
+
+
+@pytest.mark.parametrize("p,q,k,batch", [(1, 1, 8, 1), (3, 5, 16, 7), (5, 3, 64, 33), (2, 2, 256, 10), (33, 34, 4, 70),
+                                         (4, 6, 128, 2), (2, 3, 512, 5), (7, 9, 2, 3), (17, 64, 64, 130), (64, 64, 64, 64),
+                                         (40, 33, 32, 700), (70, 33, 16, 5000), (3, 70, 64, 1)])
+def test_fc_sgd_step_shapes(p, q, k, batch):
+    """Two steps in a row on the blob against two oracle steps on the block vectors; then every
+    operand order of the updated blob is exercised: backward-data (returned by the second step
+    from the once-updated weights), forward at this batch and forward of a single vector."""
+    w, x1, b = rand_fc(p, q, k, batch)
+    x2 = RNG.uniform(-1, 1, (batch, q * k)).astype(np.float32)
+    dy1 = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
+    dy2 = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
+    lr = _step_size(w, O.fc_backward_dw(x1, dy1, k))
+    w1 = O.fc_sgd_step(w, x1, dy1, lr)
+    w2 = O.fc_sgd_step(w1, x2, dy2, lr)
+    got, wh, dxs = G.gpu_fc_sgd_steps(w, [(x1, dy1), (x2, dy2)], lr, need_dx=True)
+    what = f"{p}x{q} k={k} B={batch}"
+    check(got, w2, "sgd w " + what)
+    check(dxs[0], O.fc_backward_dx(w, dy1), "sgd dx before the step " + what)
+    check(dxs[1], O.fc_backward_dx(w1, dy2), "sgd dx after one step " + what)
+    y = B.circ_fc_forward(wh, G.dev(x1), G.dev(b), None, p, q, k, epilogue=B.EPI_BIAS).cpu().numpy()
+    check(y, O.fc_forward(w2, x1, b), "forward after two steps " + what)
+    y1 = B.circ_fc_forward(wh, G.dev(x1[:1]), None, None, p, q, k).cpu().numpy()
+    check(y1, O.fc_forward(w2, x1[:1]), "single-vector forward after two steps " + what)
+    dx1, _ = B.circ_fc_backward(wh, None, G.dev(dy1[:1]), p, q, k, need_dw=False)
+    check(dx1.cpu().numpy(), O.fc_backward_dx(w2, dy1[:1]), "single-vector dx after two steps " + what)
+
+
+def test_fc_sgd_step_zero_step_and_agreement_with_time_domain():
+    p, q, k, batch = 5, 7, 64, 40
+    w, x, _ = rand_fc(p, q, k, batch, bias=False)
+    dy = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
+    wh = B.circ_precompute_spectra(G.dev(w))
+    before = wh.clone()
+    B.circ_fc_sgd_step(wh, G.dev(x), G.dev(dy), 0.0, p, q, k)
+    # lr = 0: every stored value unchanged (the sign of a zero may flip; bytes between the
+    # sections are never written and may hold anything)
+    a, b = wh.view(torch.float32), before.view(torch.float32)
+    assert bool(((a == b) | (a.isnan() & b.isnan())).all())
+    # the step in the frequency domain against: gradient to the time domain, step there, precompute again
+    lr = 0.01
+    B.circ_fc_sgd_step(wh, G.dev(x), G.dev(dy), lr, p, q, k)
+    _, dw = B.circ_fc_backward(before, G.dev(x), G.dev(dy), p, q, k, need_dx=False)
+    wh_t = B.circ_precompute_spectra((G.dev(w) - lr * dw).contiguous())
+    xt = G.dev(x)
+    ya = B.circ_fc_forward(wh, xt, None, None, p, q, k).cpu().numpy()
+    yb = B.circ_fc_forward(wh_t, xt, None, None, p, q, k).cpu().numpy()
+    check(ya, yb, "frequency-domain step vs time-domain step")
+
+
+@pytest.mark.parametrize("N,p,q,k,H,W,r,pad", [(1, 1, 1, 4, 5, 5, 3, 1), (2, 2, 3, 8, 6, 7, 3, 1), (3, 5, 2, 16, 9, 4, 3, 0),
+                                               (2, 3, 2, 32, 5, 6, 1, 0), (3, 4, 4, 64, 9, 12, 3, 1), (2, 2, 5, 64, 13, 8, 3, 0),
+                                               (2, 1, 2, 128, 6, 6, 5, 2), (40, 2, 2, 64, 14, 14, 3, 1)])
+def test_conv_sgd_step_shapes(N, p, q, k, H, W, r, pad):
+    w = (RNG.standard_normal((r, r, p, q, k)) / np.sqrt(r * r * q * k)).astype(np.float32)
+    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    mk = lambda: (RNG.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32),
+                  RNG.uniform(-1, 1, (N, p * k, Ho, Wo)).astype(np.float32))
+    (x1, dy1), (x2, dy2) = mk(), mk()
+    lr = _step_size(w, O.conv_backward_dw(x1, dy1, k, r, pad))
+    w1 = O.conv_sgd_step(w, x1, dy1, lr, pad)
+    w2 = O.conv_sgd_step(w1, x2, dy2, lr, pad)
+    got, wh, dxs = G.gpu_conv_sgd_steps(w, [(x1, dy1), (x2, dy2)], lr, pad, need_dx=True)
+    what = f"N={N} {p}x{q} k={k} {H}x{W} r={r} pad={pad}"
+    check(got, w2, "conv sgd w " + what)
+    check(dxs[1], O.conv_backward_dx(w1, dy2, H, W, pad), "conv sgd dx after one step " + what)
+    y = B.circ_conv_forward(wh, G.dev(x1), None, None, p * k, r, 1, pad, k).cpu().numpy()
+    check(y, O.conv_forward(w2, x1, None, False, pad), "conv forward after two steps " + what)
+
+
 @pytest.mark.parametrize("seed", [11, 12, 13])
 def test_random_shapes_sweep(seed):
     rng = np.random.default_rng(seed)
