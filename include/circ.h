@@ -21,8 +21,11 @@
  *    buffer; the library allocates no device memory and keeps no global state.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue work on it and return; nothing synchronises.
- *  - Block size k must be a power of two with 2 <= k <= 512, and must divide the
- *    layer widths exactly (p = m / k, q = n / k; the paper assumes the same).
+ *  - Block size k: 1 <= k <= 512, and k must divide the layer widths exactly
+ *    (p = m / k, q = n / k; the paper assumes the same).  Powers of two run on
+ *    the radix-2 FFT kernels (Sec. 4.1) and, where the shape allows, on the fused
+ *    kernels; any other k (Fig. 1 uses k = 3) takes the transforms by their
+ *    definition, O(k^2) per block, around the same per-frequency contraction.
  *  - Errors are returned as circ_status; nothing aborts or throws across the
  *    ABI.  Argument errors are detected on the host before any launch, so a
  *    failing call has enqueued nothing.

@@ -6,6 +6,7 @@
 
 #include "../../include/circ.h"
 #include "circ_kernels.h"
+#include "circ_dft.h"
 #include "circ_gemm.h"
 #include "circ_fused.h"
 #include "circ_gemv.h"
@@ -17,10 +18,14 @@ namespace {
 
 using namespace circ;
 
-constexpr int kMinK = 2, kMaxK = 512;
+constexpr int kMinK = 1, kMaxK = 512;
 
 inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
-inline bool valid_k(int k) { return is_pow2(k) && k >= kMinK && k <= kMaxK; }
+inline bool valid_k(int k) { return k >= kMinK && k <= kMaxK; }
+// Block sizes served by the radix-2 kernels; every other size takes the direct transforms.
+inline bool radix2_k(int k) { return is_pow2(k) && k >= 2; }
+// Block sizes served by the batch <= 2 streaming kernel.
+inline bool gemv_k(int k) { return is_pow2(k) && k >= 4; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
@@ -38,7 +43,7 @@ inline size_t spectra_section_elems(int n_grids, int p, int q, int k) {
 }
 
 // Output block rows per workgroup of the fused kernel for block size k (0: not fused).
-inline int fused_it(int k) { return (k < 32 || k > 256) ? 0 : (k == 32 ? 16 : 8); }
+inline int fused_it(int k) { return (!is_pow2(k) || k < 32 || k > 256) ? 0 : (k == 32 ? 16 : 8); }
 // Section 2 (FC only, 32 <= k <= 256): the operand order of the fused forward kernel,
 // zero-padded to whole tiles: igp groups of 4 block rows, q2p pairs of block columns.
 inline int fused_igp(int p, int k) { return int(cdiv(p, fused_it(k))) * fused_it(k) / 4; }
@@ -50,7 +55,7 @@ inline size_t fused_section_elems(int n_grids, int p, int q, int k) {   // in fl
 
 // Section 3 (FC only, k >= 4): [i][j][slot] order of the batch <= 2 kernel.
 inline size_t gemv_section_elems(int n_grids, int p, int q, int k) {      // in float2 units
-  if (n_grids != 1 || k < 4) return 0;
+  if (n_grids != 1 || !gemv_k(k)) return 0;
   return size_t(p) * q * (k / 2);
 }
 
@@ -168,6 +173,13 @@ hipError_t launch_irfft_k(bool rows_fast, const float2* in, float* out, const Ro
 hipError_t launch_rfft(int k, bool rows_fast, const float* in, float2* out, const RowMap& map, long long nrows,
                        long long out_fstride, int n_grids, long long in_gstride, long long out_gstride,
                        float scale, int conj, hipStream_t s) {
+  if (!radix2_k(k)) {
+    const int R = dft_rows_per_block(k, nrows);
+    hipLaunchKernelGGL(dft_rows_kernel, dim3((unsigned)cdiv(nrows, R), (unsigned)n_grids), dim3(256),
+                       dft_tile_lds_bytes(k, R), s, in, out, map, nrows, out_fstride, in_gstride, out_gstride, k, R, scale,
+                       conj, int(rows_fast));
+    return hipGetLastError();
+  }
 #define CALL(KK) launch_rfft_k<KK>(rows_fast, in, out, map, nrows, out_fstride, n_grids, in_gstride, out_gstride, scale, conj, s)
   CIRC_DISPATCH_K(k, CALL)
 #undef CALL
@@ -176,6 +188,12 @@ hipError_t launch_rfft(int k, bool rows_fast, const float* in, float2* out, cons
 hipError_t launch_irfft(int k, bool rows_fast, const float2* in, float* out, const RowMap& map, long long nrows,
                         long long in_fstride, float scale, const float* bias, long long bias_div, int relu,
                         hipStream_t s, int nparts = 1, long long part_stride = 0) {
+  if (!radix2_k(k)) {
+    const int R = dft_rows_per_block(k, nrows);
+    hipLaunchKernelGGL(idft_rows_kernel, dim3((unsigned)cdiv(nrows, R)), dim3(256), dft_tile_lds_bytes(k, R), s, in, out,
+                       map, nrows, in_fstride, k, R, scale, bias, bias_div, relu, nparts, part_stride, int(rows_fast));
+    return hipGetLastError();
+  }
 #define CALL(KK) launch_irfft_k<KK>(rows_fast, in, out, map, nrows, in_fstride, scale, bias, bias_div, relu, nparts, part_stride, s)
   CIRC_DISPATCH_K(k, CALL)
 #undef CALL
@@ -183,7 +201,8 @@ hipError_t launch_irfft(int k, bool rows_fast, const float2* in, float* out, con
 
 // Number of k slices for a GEMM with few output tiles and a long reduction (backward-weights):
 // enough slices to put about four workgroups of 64x64 tiles on every CU, each at least 64 deep.
-inline int cgemm_ksplit(int NF, int M, int N, int Kd) {
+inline int cgemm_ksplit(int k, int M, int N, int Kd) {
+  const int NF = k / 2 + 1;
   const long long tiles = (long long)NF * cdiv(M, 64) * cdiv(N, 64);
   int ks = 1;
   while (ks < 16 && tiles * ks < 1024 && Kd / (ks * 2) >= 64) ks *= 2;
@@ -227,7 +246,9 @@ hipError_t launch_cgemm_tiled(const float2* A, const float2* B, float2* C, int N
 #ifndef CIRC_GEMM_TILED_MIN
 #define CIRC_GEMM_TILED_MIN 256
 #endif
-inline bool cgemm_takes_tiled(int NF, int M, int N, int Kd, int ksplit) {
+inline bool cgemm_takes_tiled(int k, int M, int N, int Kd, int ksplit) {
+  if (k & 1) return false;   // the tiled kernel pairs bin 0 with a real Nyquist bin, which odd sizes lack
+  const int NF = k / 2 + 1;
   const long long tiles_s = (long long)(NF - 1) * ksplit * cdiv(M, 64) * cdiv(N, 64);
   // the tiled kernel keeps offsets inside one frequency of an operand in 32 bits
   const long long lim = (1ll << 31) - 1;
@@ -236,11 +257,12 @@ inline bool cgemm_takes_tiled(int NF, int M, int N, int Kd, int ksplit) {
 }
 // a_t: A is stored [f][m][kd] instead of [f][kd][m]; only the tiled kernel reads that layout, so
 // callers pass it only when cgemm_takes_tiled() holds.
-hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, long long sA,
+hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int k, int M, int N, int Kd, long long sA,
                         long long sB, long long sC, bool conj_b, hipStream_t s, int ksplit = 1,
                         long long part_stride = 0, bool a_t = false) {
+  const int NF = k / 2 + 1;                                    // one complex product per bin 0..k/2
   const int kchunk = (int)(cdiv(cdiv(Kd, ksplit), 32) * 32);   // whole operand groups per slice
-  if (cgemm_takes_tiled(NF, M, N, Kd, ksplit))
+  if (cgemm_takes_tiled(k, M, N, Kd, ksplit))
     return launch_cgemm_tiled<1, 2, 2>(A, B, C, NF, M, N, Kd, sA, sB, sC, conj_b, a_t, s, ksplit, kchunk, part_stride);
   if (a_t) return hipErrorInvalidValue;
   bool big = (long long)NF * cdiv(M, 32) * cdiv(N, 32) * ksplit >= 1024;
@@ -506,10 +528,10 @@ size_t circ_fc_workspace_bytes(int p, int q, int k, int batch, int backward) {
   // grid for backward-data); they live at the start of the workspace, which nothing else uses
   // at that time
   size_t gp = 0;
-  if (batch <= 2 && k >= 4) gp = align_up(backward ? gemv_partial_bytes(q, p, k) : gemv_partial_bytes(p, q, k), 256);
+  if (batch <= 2 && gemv_k(k)) gp = align_up(backward ? gemv_partial_bytes(q, p, k) : gemv_partial_bytes(p, q, k), 256);
   if (!backward) return xa + ya > gp ? xa + ya : gp;
   size_t wa = align_up(spectrum_elems(k, (long long)p * q) * sizeof(float2), 256);
-  const size_t tot = xa + ya + wa * cgemm_ksplit(k / 2 + 1, p, q, batch);   // one dW^ buffer per k slice
+  const size_t tot = xa + ya + wa * cgemm_ksplit(k, p, q, batch);   // one dW^ buffer per k slice
   return tot > gp ? tot : gp;
 }
 
@@ -529,7 +551,7 @@ circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   const BlobLayout bl = blob_layout(1, p, q, k);
-  if (batch <= 2 && k >= 4) {   // one or two vectors: streaming matrix-vector kernel
+  if (batch <= 2 && gemv_k(k)) {   // one or two vectors: streaming matrix-vector kernel
     const float2* wg = blob_at<float2>(w_hat, bl.gemv_fwd);
     if (launch_gemv(k, wg, x, use_bias ? bias : nullptr, y, p, q, batch, (epilogue & CIRC_EPI_RELU) ? 1 : 0, workspace, s) != hipSuccess)
       return CIRC_EHIP;
@@ -554,7 +576,7 @@ circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias
   const long long xfs = ws_fstride(xrows), yfs = ws_fstride(yrows);
   if (launch_rfft(k, false, x, xh, mx, xrows, xfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
   // Y^[f][i][b] = sum_j W^[f][j][i] X^[f][j][b]
-  if (launch_cgemm(wf, xh, yh, NF, p, batch, q, (long long)p * q, xfs, yfs, false, s) != hipSuccess) return CIRC_EHIP;
+  if (launch_cgemm(wf, xh, yh, k, p, batch, q, (long long)p * q, xfs, yfs, false, s) != hipSuccess) return CIRC_EHIP;
   RowMap my{batch, p, (long long)p * k, (long long)k, 0, 1};
   if (launch_irfft(k, false, yh, y, my, yrows, yfs, 1.0f, use_bias ? bias : nullptr, batch,
                    (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
@@ -575,7 +597,7 @@ circ_status apply_spectra_step(void* w_hat, const float2* src, int nparts, long 
   const int NF = k / 2 + 1;
   dim3 grid((unsigned)(cdiv(p, 32) * cdiv(q, 32)), (unsigned)NF, (unsigned)n_grids);
   hipLaunchKernelGGL(spectra_step_kernel, grid, dim3(256), 0, s, src, nparts, part_stride, src_fstride, src_gstride,
-                     blob_at<float2>(w_hat, bl.fwd), blob_at<float2>(w_hat, bl.bwd), p, q, NF, lr / float(k));
+                     blob_at<float2>(w_hat, bl.fwd), blob_at<float2>(w_hat, bl.bwd), p, q, NF, k, lr / float(k));
   if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
   return pack_derived_sections(w_hat, n_grids, p, q, k, s);
 }
@@ -620,13 +642,13 @@ circ_status fc_backward_impl(const void* w_hat, const float* x, const float* dy,
 
   // Backward-data is a forward pass on the transposed, conjugated grid (q output block rows,
   // p input blocks, no epilogue): the small-problem kernels serve it from their own sections.
-  const int ksplit = cgemm_ksplit(NF, p, q, batch);
+  const int ksplit = cgemm_ksplit(k, p, q, batch);
   // The tiled GEMM reads dY^ in the [f][i][b] order of backward-data, so dy is transformed once
   // for both results; the one-wave-per-tile GEMM needs the batch-major order [f][b][i].
   const bool want_dw = dw || w_upd;
-  const bool dw_shares_dy = want_dw && cgemm_takes_tiled(NF, p, q, batch, ksplit);
+  const bool dw_shares_dy = want_dw && cgemm_takes_tiled(k, p, q, batch, ksplit);
   bool have_dyh = false;   // bufy holds dY^[f][i][b]
-  if (dx && batch <= 2 && k >= 4) {
+  if (dx && batch <= 2 && gemv_k(k)) {
     if (launch_gemv(k, blob_at<float2>(w_hat, bl.gemv_bwd), dy, nullptr, dx, q, p, batch, 0, workspace, s) != hipSuccess) return CIRC_EHIP;
   } else if (dx && use_fused_forward(q, p, k, batch)) {
     if (launch_fused(k, blob_at<float4>(w_hat, bl.fused_bwd), dy, nullptr, dx, q, p, batch, 0, s) != hipSuccess)
@@ -636,7 +658,7 @@ circ_status fc_backward_impl(const void* w_hat, const float* x, const float* dy,
     RowMap mdy{batch, p, (long long)p * k, (long long)k, 0, 1};
     if (launch_rfft(k, false, dy, bufy, mdy, yrows, yfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
     have_dyh = true;
-    if (launch_cgemm(wb, bufy, bufx, NF, q, batch, p, wfs, yfs, xfs, false, s) != hipSuccess) return CIRC_EHIP;
+    if (launch_cgemm(wb, bufy, bufx, k, q, batch, p, wfs, yfs, xfs, false, s) != hipSuccess) return CIRC_EHIP;
     RowMap mdx{batch, q, (long long)q * k, (long long)k, 0, 1};
     if (launch_irfft(k, false, bufx, dx, mdx, xrows, xfs, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
   }
@@ -656,7 +678,7 @@ circ_status fc_backward_impl(const void* w_hat, const float* x, const float* dy,
     if (launch_rfft(k, false, x, bufx, mx, xrows, xfs, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
     // the reduction over the batch is cut into slices; the IFFT adds the partial spectra in order
     const long long wpart = (long long)(align_up(spectrum_elems(k, (long long)p * q) * sizeof(float2), 256) / sizeof(float2));
-    if (launch_cgemm(bufy, bufx, bufw, NF, p, q, batch, yfs, xfs, wfs, true, s, ksplit, wpart, dw_shares_dy) != hipSuccess)
+    if (launch_cgemm(bufy, bufx, bufw, k, p, q, batch, yfs, xfs, wfs, true, s, ksplit, wpart, dw_shares_dy) != hipSuccess)
       return CIRC_EHIP;
     const long long wrows = (long long)p * q;
     RowMap mw{q, p, (long long)k, (long long)q * k, 0, 1};

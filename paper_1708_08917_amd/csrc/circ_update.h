@@ -45,17 +45,18 @@ __global__ __launch_bounds__(256) void pack_sections_kernel(PackPlan pl, int n_g
 // Block (x = 32x32 tile of (i, j), y = f, z = g) updates both spectrum sections of grid g:
 //   bwd[(g*NF + f)*p*q + i*q + j] -= a * conj(G)      (read and written along j)
 //   fwd[(g*NF + f)*p*q + j*p + i] -= a * G            (transposed through LDS, written along i)
-// The DC and Nyquist bins of a real vector are real: the imaginary part of G is dropped there.
+// The DC bin and, for even K, the Nyquist bin of a real vector are real: the imaginary part of G
+// is dropped there.
 __global__ __launch_bounds__(256) void spectra_step_kernel(const float2* __restrict__ src, int nparts,
                                                            long long part_stride, long long src_fstride,
                                                            long long src_gstride, float2* __restrict__ fwd,
-                                                           float2* __restrict__ bwd, int p, int q, int NF, float a) {
+                                                           float2* __restrict__ bwd, int p, int q, int NF, int K, float a) {
   __shared__ float2 tile[32][33];
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int tiles_j = (q + 31) / 32;
   const int i0 = (blockIdx.x / tiles_j) * 32, j0 = (blockIdx.x % tiles_j) * 32;
   const int f = blockIdx.y, g = blockIdx.z;
-  const bool real_bin = f == 0 || f == NF - 1;
+  const bool real_bin = f == 0 || 2 * f == K;
   const long long sec = ((long long)g * NF + f) * p * q;
   const float2* sp = src + (long long)f * src_fstride + (long long)g * src_gstride;
 #pragma unroll

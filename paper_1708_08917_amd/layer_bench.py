@@ -114,7 +114,7 @@ def bench_conv(cfg, reps, backward=False):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", default="all", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "head_b1", "all"])
+    ap.add_argument("--config", default="all", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "head_b1", "general", "all"])
     ap.add_argument("--reps", type=int, default=100)
     ap.add_argument("--backward", action="store_true")
     a = ap.parse_args()
@@ -134,6 +134,13 @@ def main():
         import dataclasses
         bench_fc(dataclasses.replace(synth.CFG3_L1, name="head_fc9216x4096_k128_b1", batch=1), a.reps)
         bench_fc(dataclasses.replace(synth.CFG3_L2, name="head_fc4096x4096_k128_b1", batch=1), a.reps)
+    if sel("general"):
+        # block sizes that are not powers of two (direct transforms): an FC layer with blocks of 100
+        # and the 384-channel 13 x 13 CONV layer of an AlexNet-style network as 4 x 4 blocks of 96
+        bench_fc(synth.FcConfig("fc4000_k100_b64", 4000, 4000, 100, 64, bias=True, relu=True, index=5), a.reps,
+                 backward=a.backward)
+        bench_conv(synth.ConvConfig("conv3x3_c384_13x13_k96_n32", 32, 384, 384, 13, 13, 3, 1, 1, 96, index=6), a.reps,
+                   backward=a.backward)
     if sel("cfg5"):
         bench_fc(synth.CFG5, max(10, a.reps // 4), backward=a.backward or a.config == "all")
 

@@ -45,7 +45,11 @@ def test_spectra_bytes():
     # CONV blob (9 grids of 4 x 4 blocks, k = 64): unfused sections + fused CONV operands (9*4*2*64 float2)
     # for the forward pass and the same again for backward-data (transposed grids, reflected filter)
     assert B.circ_spectra_bytes(9, 4, 4, 64) == 2 * ((9 * 16 * 33 * 8 + 255) // 256 * 256) + 2 * 9 * 4 * 2 * 64 * 8
-    for bad in [(0, 1, 1, 8), (1, 0, 1, 8), (1, 1, 0, 8), (1, 1, 1, 3), (1, 1, 1, 1), (1, 1, 1, 1024), (1, 1, 1, 0)]:
+    # block sizes that are not powers of two (and k = 1) hold only the two unfused sections
+    assert B.circ_spectra_bytes(1, 3, 5, 3) == 2 * 256          # 3*5 blocks x 2 bins x 8 B = 240 -> 256
+    assert B.circ_spectra_bytes(1, 64, 64, 96) == 2 * 64 * 64 * 49 * 8
+    assert B.circ_spectra_bytes(1, 2, 2, 1) == 2 * 256
+    for bad in [(0, 1, 1, 8), (1, 0, 1, 8), (1, 1, 0, 8), (1, 1, 1, 513), (1, 1, 1, -2), (1, 1, 1, 1024), (1, 1, 1, 0)]:
         assert B.circ_spectra_bytes(*bad) == 0
 
 
@@ -53,7 +57,8 @@ def test_workspace_bytes():
     F = 33
     assert B.circ_fc_workspace_bytes(64, 64, 64, 64) == 2 * F * 64 * 64 * 8
     assert B.circ_fc_workspace_bytes(64, 64, 64, 64, True) == 3 * F * 64 * 64 * 8
-    assert B.circ_fc_workspace_bytes(64, 64, 48, 64) == 0
+    assert B.circ_fc_workspace_bytes(64, 64, 48, 64) == 2 * 25 * 64 * 64 * 8      # any 1 <= k <= 512
+    assert B.circ_fc_workspace_bytes(64, 64, 600, 64) == 0
     assert B.circ_conv_workspace_bytes(32, 256, 256, 28, 28, 3, 1, 1, 64) == 2 * F * 4 * 32 * 784 * 8
     assert B.circ_conv_workspace_bytes(32, 256, 256, 28, 28, 3, 2, 1, 64) == 0
     assert B.circ_conv_workspace_bytes(32, 250, 256, 28, 28, 3, 1, 1, 64) == 0
@@ -71,7 +76,8 @@ def test_fc_forward_argument_errors():
         a = dict(ok_args); a.update(kw)
         return f(a["w_hat"], a["x"], a["bias"], a["y"], a["p"], a["q"], a["k"], a["batch"], a["epi"], a["wsp"], a["wsb"], None)
 
-    assert call(k=3) == B.CIRC_EINVAL
+    assert call(k=0) == B.CIRC_EINVAL
+    assert call(k=513) == B.CIRC_EINVAL
     assert call(k=1024) == B.CIRC_EINVAL
     assert call(p=0) == B.CIRC_EINVAL
     assert call(batch=-1) == B.CIRC_EINVAL
@@ -94,7 +100,7 @@ def test_fc_backward_argument_errors():
              wsp=A + 5 * big, wsb=1 << 30):
         return f(w_hat, x, dy, dx, dw, p, q, k, batch, wsp, wsb, None)
 
-    assert call(k=12) == B.CIRC_EINVAL
+    assert call(k=0) == B.CIRC_EINVAL
     assert call(dy=None) == B.CIRC_EINVAL
     assert call(dx=None, dw=None) == B.CIRC_EINVAL
     assert call(x=None) == B.CIRC_EINVAL                      # dw needs x
@@ -111,7 +117,7 @@ def test_conv_argument_errors():
         return f(w_hat, x, bias, y, N, C_in, C_out, H, W, r, stride, pad, k, epi, wsp, wsb, None)
 
     assert call(C_in=6) == B.CIRC_EINVAL                      # k does not divide C_in
-    assert call(k=3, C_in=6, C_out=6) == B.CIRC_EINVAL
+    assert call(k=1024, C_in=1024, C_out=1024) == B.CIRC_EINVAL
     assert call(stride=2) == B.CIRC_ENOTSUP
     assert call(r=2) == B.CIRC_ENOTSUP
     assert call(pad=3) == B.CIRC_EINVAL
@@ -157,7 +163,7 @@ def test_sgd_step_and_export_argument_errors():
     assert call(w_hat=None) == B.CIRC_EINVAL
     assert call(lr=float("nan")) == B.CIRC_EINVAL
     assert call(x=None) == B.CIRC_EINVAL                      # the step needs x
-    assert call(k=12) == B.CIRC_EINVAL
+    assert call(k=0) == B.CIRC_EINVAL
     assert call(batch=0) == B.CIRC_EINVAL
     assert call(x=A + 256) == B.CIRC_EINVAL                   # x lies inside the blob that is rewritten
     assert call(dx=A) == B.CIRC_EINVAL
@@ -178,7 +184,7 @@ def test_sgd_step_and_export_argument_errors():
     assert e(A, 1, 2, 2, 8, None, None) == B.CIRC_EINVAL
     assert e(None, 1, 2, 2, 8, A + big, None) == B.CIRC_EINVAL
     assert e(A, 0, 2, 2, 8, A + big, None) == B.CIRC_EINVAL
-    assert e(A, 1, 2, 2, 12, A + big, None) == B.CIRC_EINVAL
+    assert e(A, 1, 2, 2, 513, A + big, None) == B.CIRC_EINVAL
     assert e(A, 1, 2, 2, 8, A + 64, None) == B.CIRC_EINVAL    # w lies inside the blob
 
 
@@ -194,20 +200,21 @@ def test_bias_grad_argument_errors():
 
 
 def test_empty_and_degenerate_sizes_are_rejected():
-    """Empty inputs (batch 0, no blocks) and k = 1 (no compression: an ordinary dense layer, which
-    this library does not serve) come back as CIRC_EINVAL / size 0, never as a launch."""
+    """Empty inputs (batch 0, no blocks) and block sizes outside 1..512 come back as
+    CIRC_EINVAL / size 0, never as a launch."""
     assert B.circ_fc_workspace_bytes(2, 2, 8, 0) == 0
     assert B.circ_fc_workspace_bytes(0, 2, 8, 4) == 0
-    assert B.circ_spectra_bytes(1, 2, 2, 1) == 0
+    assert B.circ_fc_workspace_bytes(2, 2, 0, 4) == 0
+    assert B.circ_fc_workspace_bytes(2, 2, 3, 4) > 0
     f = B.lib().circ_fc_forward
     assert f(A, A + (1 << 28), None, A + (2 << 28), 2, 2, 8, 0, 0, A + (3 << 28), 1 << 30, None) == B.CIRC_EINVAL
-    assert f(A, A + (1 << 28), None, A + (2 << 28), 2, 2, 1, 4, 0, A + (3 << 28), 1 << 30, None) == B.CIRC_EINVAL
+    assert f(A, A + (1 << 28), None, A + (2 << 28), 2, 2, 0, 4, 0, A + (3 << 28), 1 << 30, None) == B.CIRC_EINVAL
 
 
 def test_precompute_argument_errors():
     f = B.lib().circ_precompute_spectra
     assert f(None, 1, 2, 2, 8, A, None) == B.CIRC_EINVAL
-    assert f(A, 1, 2, 2, 6, A + (1 << 20), None) == B.CIRC_EINVAL
+    assert f(A, 1, 2, 2, 600, A + (1 << 20), None) == B.CIRC_EINVAL
     assert f(A, 0, 2, 2, 8, A + (1 << 20), None) == B.CIRC_EINVAL
     assert f(A, 1, 2, 2, 8, A, None) == B.CIRC_EINVAL         # output aliases input
 

@@ -352,13 +352,76 @@ def test_conv_sgd_step_shapes(N, p, q, k, H, W, r, pad):
     check(y, O.conv_forward(w2, x1, None, False, pad), "conv forward after two steps " + what)
 
 
-@pytest.mark.parametrize("seed", [11, 12, 13])
+# ---- block sizes that are not powers of two (direct transforms around the same contraction) ----
+@pytest.mark.parametrize("k", [1, 3, 5, 6, 7, 12, 24, 40, 96, 100, 125, 250, 384, 511])
+@pytest.mark.parametrize("batch", [1, 2, 33])
+def test_fc_general_block_sizes(k, batch):
+    p, q = (3, 5) if k < 200 else (2, 3)
+    w, x, b = rand_fc(p, q, k, batch)
+    what = f"{p}x{q} k={k} B={batch}"
+    check(G.gpu_fc_forward(w, x, b, True), O.fc_forward(w, x, b, True), "fwd bias+relu " + what)
+    dy = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
+    dx, dw = G.gpu_fc_backward(w, x, dy)
+    check(dx, O.fc_backward_dx(w, dy), "dx " + what)
+    check(dw, O.fc_backward_dw(x, dy, k), "dw " + what)
+    lr = _step_size(w, O.fc_backward_dw(x, dy, k))
+    got, wh, _ = G.gpu_fc_sgd_steps(w, [(x, dy)], lr)
+    w1 = O.fc_sgd_step(w, x, dy, lr)
+    check(got, w1, "sgd w " + what)
+    y = B.circ_fc_forward(wh, G.dev(x), None, None, p, q, k).cpu().numpy()
+    check(y, O.fc_forward(w1, x), "forward after the step " + what)
+
+
+@pytest.mark.parametrize("p,q,k,batch", [(40, 37, 96, 300), (70, 33, 24, 3000), (33, 70, 3, 600), (10, 10, 100, 64),
+                                         (64, 64, 1, 50)])
+def test_fc_general_block_sizes_larger(p, q, k, batch):
+    """Several row tiles of the direct transforms, ragged GEMM tiles, split reduction for dw."""
+    w, x, b = rand_fc(p, q, k, batch)
+    what = f"{p}x{q} k={k} B={batch}"
+    check(G.gpu_fc_forward(w, x, b, False), O.fc_forward(w, x, b, False), "fwd " + what)
+    dy = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
+    dx, dw = G.gpu_fc_backward(w, x, dy)
+    check(dx, O.fc_backward_dx(w, dy), "dx " + what)
+    check(dw, O.fc_backward_dw(x, dy, k), "dw " + what)
+
+
+@pytest.mark.parametrize("N,p,q,k,H,W,r,pad", [(2, 2, 3, 3, 6, 7, 3, 1), (3, 1, 2, 6, 5, 5, 3, 0), (2, 3, 2, 24, 9, 4, 1, 0),
+                                               (2, 4, 4, 96, 13, 13, 3, 1), (2, 2, 2, 192, 13, 13, 3, 1),
+                                               (3, 2, 2, 1, 8, 8, 5, 2), (33, 2, 3, 12, 14, 14, 3, 1)])
+def test_conv_general_block_sizes(N, p, q, k, H, W, r, pad):
+    """Includes the 384-channel 13 x 13 layers of an AlexNet-style network as 4 x 4 blocks of 96
+    and 2 x 2 blocks of 192."""
+    w = (RNG.standard_normal((r, r, p, q, k)) / np.sqrt(r * r * q * k)).astype(np.float32)
+    x = RNG.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32)
+    b = (0.1 * RNG.standard_normal(p * k)).astype(np.float32)
+    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    dy = RNG.uniform(-1, 1, (N, p * k, Ho, Wo)).astype(np.float32)
+    what = f"N={N} {p}x{q} k={k} {H}x{W} r={r} pad={pad}"
+    check(G.gpu_conv_forward(w, x, b, True, pad), O.conv_forward(w, x, b, True, pad), "conv fwd " + what)
+    dx, dw = G.gpu_conv_backward(w, x, dy, pad)
+    check(dx, O.conv_backward_dx(w, dy, H, W, pad), "conv dx " + what)
+    check(dw, O.conv_backward_dw(x, dy, k, r, pad), "conv dw " + what)
+    lr = _step_size(w, O.conv_backward_dw(x, dy, k, r, pad))
+    got, _, _ = G.gpu_conv_sgd_steps(w, [(x, dy)], lr, pad)
+    check(got, O.conv_sgd_step(w, x, dy, lr, pad), "conv sgd w " + what)
+
+
+def test_fig1_example_on_gpu():
+    """The 6 x 3 matrix of Fig. 1: p = 2, q = 1, k = 3, six stored parameters."""
+    w = np.arange(1, 7, dtype=np.float32).reshape(2, 1, 3)
+    x = np.array([[1.0, -2.0, 0.5]], dtype=np.float32)
+    got = G.gpu_fc_forward(w, x)
+    check(got, O.expand_block_circulant(w) @ x[0], "Fig. 1 shape")
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
 def test_random_shapes_sweep(seed):
     rng = np.random.default_rng(seed)
     for case in range(60):
         kind = rng.choice(["fc", "fcb", "conv", "convb"], p=[0.4, 0.25, 0.2, 0.15])
         if kind in ("fc", "fcb"):
-            k = int(rng.choice([2, 4, 8, 16, 32, 64, 128, 256, 512]))
+            # seed 14 draws block sizes that are not powers of two
+            k = int(rng.choice([2, 4, 8, 16, 32, 64, 128, 256, 512] if seed != 14 else [1, 3, 6, 10, 20, 48, 96, 120, 200, 500]))
             p, q = int(rng.integers(1, 80)), int(rng.integers(1, 80))
             batch = int(rng.choice([1, 2, 3, 5, 8, 17, 33, 64, 100, 130, 257]))
             while (p * k) * (q * k) * batch > 2e8 and (p > 1 or q > 1):     # keep the dense oracle quick
@@ -379,7 +442,7 @@ def test_random_shapes_sweep(seed):
                 check(dx, O.fc_backward_dx(w, dy), what + " dx")
                 check(dw, O.fc_backward_dw(x, dy, k), what + " dw")
         else:
-            k = int(rng.choice([2, 4, 8, 16, 32, 64]))
+            k = int(rng.choice([2, 4, 8, 16, 32, 64] if seed != 14 else [1, 3, 6, 10, 24, 48]))
             p, q = int(rng.integers(1, 6)), int(rng.integers(1, 6))
             r = int(rng.choice([1, 3, 3, 3, 5]))
             pad = int(rng.integers(0, r))
