@@ -182,6 +182,28 @@ circ_status circ_export_weights(const void* w_hat, int n_grids, int p, int q, in
                                 float* w, void* stream);
 
 /*
+ * Half-width storage for FC inference.  The hardware of Sec. 4.2 keeps inputs and weights in a
+ * 16-bit representation; here activations and spectra are IEEE fp16 in memory and every
+ * butterfly and accumulation is fp32:
+ *   y = psi( IFFT( (1/k) * sum_j fp16(FFT w_ij) o fp16(FFT x_j) ) + bias ),  y rounded to fp16.
+ * Same orientation, layouts and epilogue flags as circ_fc_forward, with x and y holding fp16
+ * values ([batch][q*k] and [batch][p*k]), bias fp32.  k must be a power of two, 8 <= k <= 512.
+ * Against the exact result the error is a few fp16 roundings (2^-11 each: weights' spectra,
+ * input spectra, output spectra, output), about 1e-3 of the largest output; spectra of inputs
+ * are not normalised, so |x| * k must stay below the fp16 range (65504).
+ *   circ_spectra_bytes_f16        size of the fp16 spectra blob (0 for invalid arguments)
+ *   circ_precompute_spectra_f16   w fp32 device [p][q][k] -> blob (opaque, caller-owned, 16-byte aligned)
+ *   circ_fc_workspace_bytes_f16   workspace of circ_fc_forward_f16 for the same arguments
+ * Errors as for circ_fc_forward.
+ */
+size_t circ_spectra_bytes_f16(int p, int q, int k);
+circ_status circ_precompute_spectra_f16(const float* w, int p, int q, int k, void* w_hat, void* stream);
+size_t circ_fc_workspace_bytes_f16(int p, int q, int k, int batch);
+circ_status circ_fc_forward_f16(const void* w_hat, const void* x, const float* bias, void* y,
+                                int p, int q, int k, int batch, int epilogue,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Bias gradient (Eq. 1: a = Wx + theta, so dL/dtheta is dL/da summed over everything but the
  * channel).  dy is viewed as [outer][channels][inner]:
  *   db[c] = sum_{o, t} dy[(o*channels + c)*inner + t]

@@ -38,6 +38,11 @@ SIGNATURES = {
     "circ_fc_sgd_step": (_c_int, [_c_ptr] * 4 + [ctypes.c_float] + [_c_int] * 4 + [_c_ptr, _c_size, _c_ptr]),
     "circ_conv_sgd_step": (_c_int, [_c_ptr] * 4 + [ctypes.c_float] + [_c_int] * 9 + [_c_ptr, _c_size, _c_ptr]),
     "circ_export_weights": (_c_int, [_c_ptr] + [_c_int] * 4 + [_c_ptr, _c_ptr]),
+    "circ_spectra_bytes_f16": (_c_size, [_c_int] * 3),
+    "circ_precompute_spectra_f16": (_c_int, [_c_ptr, _c_int, _c_int, _c_int, _c_ptr, _c_ptr]),
+    "circ_fc_workspace_bytes_f16": (_c_size, [_c_int] * 4),
+    "circ_fc_forward_f16": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_int, _c_int, _c_int, _c_int, _c_int,
+                                     _c_ptr, _c_size, _c_ptr]),
 }
 
 
@@ -201,6 +206,36 @@ def circ_export_weights(w_hat, n_grids, p, q, k, w=None):
         w = torch.empty(n_grids, p, q, k, dtype=torch.float32, device=w_hat.device)
     _check(lib().circ_export_weights(_ptr(w_hat), n_grids, p, q, k, _ptr(w), _stream()), "circ_export_weights")
     return w
+
+
+def circ_precompute_spectra_f16(w: torch.Tensor, w_hat: torch.Tensor | None = None) -> torch.Tensor:
+    """w: device fp32 [p][q][k] -> opaque fp16 spectra blob (uint8 tensor)."""
+    assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and w.dim() == 3
+    p, q, k = w.shape
+    nbytes = lib().circ_spectra_bytes_f16(p, q, k)
+    if nbytes == 0:
+        raise CircError(CIRC_EINVAL, "circ_spectra_bytes_f16")
+    if w_hat is None:
+        w_hat = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    _check(lib().circ_precompute_spectra_f16(_ptr(w), p, q, k, _ptr(w_hat), _stream()), "circ_precompute_spectra_f16")
+    return w_hat
+
+
+def circ_fc_workspace_bytes_f16(p, q, k, batch) -> int:
+    return lib().circ_fc_workspace_bytes_f16(p, q, k, batch)
+
+
+def circ_fc_forward_f16(w_hat, x, bias, y, p, q, k, epilogue=EPI_NONE, workspace=None):
+    """x: fp16 [batch][q*k] -> y: fp16 [batch][p*k] (allocated if None); bias fp32.  Returns y."""
+    assert x.dtype == torch.float16 and x.is_contiguous()
+    batch = x.shape[0]
+    if y is None:
+        y = torch.empty(batch, p * k, dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(1, circ_fc_workspace_bytes_f16(p, q, k, batch)), dtype=torch.uint8, device=x.device)
+    _check(lib().circ_fc_forward_f16(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), p, q, k, batch, epilogue,
+                                     _ptr(workspace), workspace.numel(), _stream()), "circ_fc_forward_f16")
+    return y
 
 
 def circ_bias_grad(dy, db=None):

@@ -9,10 +9,29 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 
 #include "circ_fft.h"
 
 namespace circ {
+
+// Half-width storage (IEEE fp16 in memory, fp32 in registers and LDS): bit 0 of HMODE = the
+// real rows are fp16, bit 1 = the spectra are fp16 (re, im) pairs.
+constexpr int kHalfRows = 1, kHalfSpectra = 2;
+
+__device__ __forceinline__ float4 load_half4(const void* p) {          // 4 consecutive fp16 values, 8-byte aligned
+  const uint2 raw = *reinterpret_cast<const uint2*>(p);
+  const float2 a = __half22float2(*reinterpret_cast<const __half2*>(&raw.x));
+  const float2 b = __half22float2(*reinterpret_cast<const __half2*>(&raw.y));
+  return make_float4(a.x, a.y, b.x, b.y);
+}
+__device__ __forceinline__ void store_half4(void* p, float4 v) {
+  const __half2 a = __floats2half2_rn(v.x, v.y), b = __floats2half2_rn(v.z, v.w);
+  uint2 raw;
+  raw.x = *reinterpret_cast<const unsigned*>(&a);
+  raw.y = *reinterpret_cast<const unsigned*>(&b);
+  *reinterpret_cast<uint2*>(p) = raw;
+}
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -53,7 +72,9 @@ __device__ __forceinline__ float lds_get(const float2* z, int idx, int half) {
 // blockIdx.y selects one of several independent grids (weight precompute for CONV).
 // ROWS_FAST: consecutive rows are adjacent in memory (CONV, NCHW: the FFT axis is the
 // channel axis and pixels are contiguous) — lanes then run along rows when loading.
-template <int K, bool ROWS_FAST>
+// HMODE (see kHalfRows / kHalfSpectra): `in` then points to fp16 rows and / or `out` to fp16 pairs;
+// offsets and strides keep their meaning in elements.  Contiguous rows with K >= 4 only.
+template <int K, bool ROWS_FAST, int HMODE = 0>
 __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ out, RowMap map,
                             long long nrows, long long out_fstride, long long in_gstride,
                             long long out_gstride, int P, float scale, int conj) {
@@ -108,7 +129,11 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
     for (int row = tid / (K / 4); row < 2 * P; row += rstep) {
       long long b = L.rbase[row];
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n);
+      if constexpr (HMODE & kHalfRows) {
+        if (b >= 0) v = load_half4(reinterpret_cast<const __half*>(in) + b + n);
+      } else {
+        if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n);
+      }
       float* zd = zcol + 2 * (row >> 1) + (row & 1);
       zd[0] = v.x;
       zd[2 * PP] = v.y;
@@ -139,13 +164,22 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
     const int pr = tid & (P - 1), fstep = NT >> lgP;
     const long long rid = t0 + 2 * pr;
     const bool ok0 = rid < nrows, ok1 = rid + 1 < nrows;
-    float2* o = out + (long long)(tid >> lgP) * out_fstride + rid;
+    static_assert(HMODE == 0 || (!ROWS_FAST && K >= 4), "half-width storage: contiguous rows only");
+    long long o = (long long)(tid >> lgP) * out_fstride + rid;
     const long long ostep = (long long)fstep * out_fstride;
 #pragma unroll 2
     for (int f = tid >> lgP; f < NF; f += fstep, o += ostep) {
       float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>((K - f) & (K - 1)) * PP + pr];
-      if (ok0) o[0] = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
-      if (ok1) o[1] = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
+      const float2 v0 = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
+      const float2 v1 = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
+      if constexpr (HMODE & kHalfSpectra) {
+        __half2* oh = reinterpret_cast<__half2*>(out) + o;
+        if (ok0) oh[0] = __floats2half2_rn(v0.x, v0.y);
+        if (ok1) oh[1] = __floats2half2_rn(v1.x, v1.y);
+      } else {
+        if (ok0) out[o] = v0;
+        if (ok1) out[o + 1] = v1;
+      }
     }
   }
 }
@@ -155,7 +189,7 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
 // blk = rid / bias_div (the output block row / channel block of the row).
 // The spectrum may come as `nparts` partial sums (split-K GEMM), `part_stride` elements apart;
 // they are added in index order, so the result does not depend on scheduling.
-template <int K, bool ROWS_FAST>
+template <int K, bool ROWS_FAST, int HMODE = 0>
 __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ out, RowMap map,
                              long long nrows, long long in_fstride, int P, float scale,
                              const float* __restrict__ bias, long long bias_div, int relu,
@@ -175,18 +209,24 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
     const int pr = tid & (P - 1), fstep = NT >> lgP;
     const long long rid = t0 + 2 * pr;
     const bool ok0 = rid < nrows, ok1 = rid + 1 < nrows;
-    const float2* s = in + (long long)(tid >> lgP) * in_fstride + rid;
+    static_assert(HMODE == 0 || (!ROWS_FAST && K >= 4), "half-width storage: contiguous rows only");
+    long long s = (long long)(tid >> lgP) * in_fstride + rid;
     const long long sstep = (long long)fstep * in_fstride;
+    auto bin = [&](long long e, bool ok) -> float2 {
+      if (!ok) return make_float2(0.f, 0.f);
+      if constexpr (HMODE & kHalfSpectra) return __half22float2(reinterpret_cast<const __half2*>(in)[e]);
+      else return in[e];
+    };
 #pragma unroll 4
     for (int f = tid >> lgP; f < NF; f += fstep, s += sstep) {
-      float2 ya = ok0 ? s[0] : make_float2(0.f, 0.f);
-      float2 yb = ok1 ? s[1] : make_float2(0.f, 0.f);
+      float2 ya = bin(s, ok0);
+      float2 yb = bin(s + 1, ok1);
       // partial sums: loads four parts ahead, additions in index order
 #pragma unroll 4
       for (int part = 1; part < nparts; ++part) {
-        const float2* sp = s + part * part_stride;
-        const float2 pa = ok0 ? sp[0] : make_float2(0.f, 0.f);
-        const float2 pb = ok1 ? sp[1] : make_float2(0.f, 0.f);
+        const long long sp = s + part * part_stride;
+        const float2 pa = bin(sp, ok0);
+        const float2 pb = bin(sp + 1, ok1);
         ya.x += pa.x; ya.y += pa.y;
         yb.x += pb.x; yb.y += pb.y;
       }
@@ -231,7 +271,8 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
         v.x += bb.x; v.y += bb.y; v.z += bb.z; v.w += bb.w;
       }
       if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
-      *reinterpret_cast<float4*>(out + b + n) = v;
+      if constexpr (HMODE & kHalfRows) store_half4(reinterpret_cast<__half*>(out) + b + n, v);
+      else *reinterpret_cast<float4*>(out + b + n) = v;
     }
   } else if (ROWS_FAST && map.quad) {
     // 4 rows per 16-byte store (see the loader of rfft_kernel); a group of 4 rows lies inside

@@ -5,7 +5,9 @@
 Configurations: cfg1 (FC 1024x1024, k=16, batch 1), cfg2 (FC 4096x4096, k=64, batch 64),
 cfg3 (9216->4096->4096 head, k=128, batch 256, both layers), cfg4 (3x3 CONV 256->256, 28x28,
 batch 32, k=64; --backward adds dx, dw and the bias gradient), cfg5 (FC 16384x16384, k=256,
-batch 1024; --backward adds dx and dw), head_b1 (the two head layers of cfg3 at batch 1).
+batch 1024; --backward adds dx and dw), head_b1 (the two head layers of cfg3 at batch 1),
+head_chain_b1 (9216->4096->4096->1000 for one input, the three layers back to back), general
+(block sizes that are not powers of two).
 Prints one line per layer with the time per call and the algorithmic bytes/flops rates.
 This is the companion of bench.py for the workloads that bench.py does not time; it is also
 the program that the rocprofv3 summaries under profiles/ were collected with.
@@ -66,6 +68,14 @@ def bench_fc(cfg, reps, backward=False):
           f"{flops / t * 1e-6:6.2f} TFLOP/s  dense-equivalent {2.0 * cfg.n_in * cfg.n_out * cfg.batch / t * 1e-6:7.1f} TFLOP/s", flush=True)
     tp = _time(lambda: B.circ_precompute_spectra(wd, wh), 20, 3)
     print(f"{cfg.name}: precompute_spectra {tp:9.2f} us/call", flush=True)
+    if cfg.k >= 8 and cfg.k & (cfg.k - 1) == 0:
+        # the same layer with fp16 storage (activations, spectra) and fp32 arithmetic
+        wh16 = B.circ_precompute_spectra_f16(wd)
+        x16, y16 = xd.half(), torch.empty(cfg.batch, cfg.n_out, dtype=torch.float16, device=DEV)
+        ws16 = torch.empty(max(1, B.circ_fc_workspace_bytes_f16(cfg.p, cfg.q, cfg.k, cfg.batch)), dtype=torch.uint8, device=DEV)
+        th = _time(lambda: B.circ_fc_forward_f16(wh16, x16, bd, y16, cfg.p, cfg.q, cfg.k, epi, ws16), reps, max(3, reps // 10))
+        print(f"{cfg.name}: forward, fp16 storage {th:9.2f} us/call  {cfg.batch / th * 1e6:12.0f} vectors/s  "
+              f"alg {byts / 2 / th * 1e-3:7.1f} GB/s", flush=True)
     if backward:
         dy = torch.from_numpy(synth.fc_upstream_grad(cfg)).to(DEV)
         dx, dw = torch.empty_like(xd), torch.empty_like(wd)
@@ -79,6 +89,33 @@ def bench_fc(cfg, reps, backward=False):
         # against dx + dw + precompute of the new weights
         tsg = _time(lambda: B.circ_fc_sgd_step(wh, xd, dy, 0.0, cfg.p, cfg.q, cfg.k, True, dx, ws), r, 3)
         print(f"{cfg.name}: sgd step {tsg:9.2f} us/call (backward + precompute: {tb + tp:.2f})", flush=True)
+
+
+def bench_chain(cfgs, reps):
+    """A stack of FC layers applied to the same batch, back to back in one graph: time per
+    pass over the whole stack (the per-image latency of a classifier head at batch 1)."""
+    layers = []
+    act = None
+    for c in cfgs:
+        w, x, b = synth.fc_inputs(c)
+        if act is None:
+            act = torch.from_numpy(x).to(DEV)
+        wh = B.circ_precompute_spectra(torch.from_numpy(w).to(DEV))
+        bd = None if b is None else torch.from_numpy(b).to(DEV)
+        y = torch.empty(c.batch, c.n_out, device=DEV)
+        ws = torch.empty(max(1, B.circ_fc_workspace_bytes(c.p, c.q, c.k, c.batch)), dtype=torch.uint8, device=DEV)
+        epi = (B.EPI_BIAS if b is not None else 0) | (B.EPI_RELU if c.relu else 0)
+        layers.append((wh, act, bd, y, c, epi, ws))
+        act = y
+
+    def run():
+        for wh, xin, bd, y, c, epi, ws in layers:
+            B.circ_fc_forward(wh, xin, bd, y, c.p, c.q, c.k, epi, ws)
+
+    t = _time(run, reps, max(3, reps // 10))
+    names = " -> ".join([str(cfgs[0].n_in)] + [f"{c.n_out} (k={c.k})" for c in cfgs])
+    print(f"chain {names}, batch {cfgs[0].batch}: {t:9.2f} us/pass  {cfgs[0].batch / t * 1e6:10.0f} inputs/s  "
+          f"{len(cfgs) / t * 1e6:10.0f} layers/s", flush=True)
 
 
 def bench_conv(cfg, reps, backward=False):
@@ -114,7 +151,7 @@ def bench_conv(cfg, reps, backward=False):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", default="all", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "head_b1", "general", "all"])
+    ap.add_argument("--config", default="all", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "head_b1", "head_chain_b1", "general", "all"])
     ap.add_argument("--reps", type=int, default=100)
     ap.add_argument("--backward", action="store_true")
     a = ap.parse_args()
@@ -134,6 +171,11 @@ def main():
         import dataclasses
         bench_fc(dataclasses.replace(synth.CFG3_L1, name="head_fc9216x4096_k128_b1", batch=1), a.reps)
         bench_fc(dataclasses.replace(synth.CFG3_L2, name="head_fc4096x4096_k128_b1", batch=1), a.reps)
+    if sel("head_chain_b1"):
+        # a whole classifier head for one input: 9216 -> 4096 -> 4096 -> 1000 (1000 = 125 blocks of 8)
+        import dataclasses
+        bench_chain([dataclasses.replace(synth.CFG3_L1, batch=1), dataclasses.replace(synth.CFG3_L2, batch=1),
+                     synth.FcConfig("head_fc4096x1000_k8_b1", 4096, 1000, 8, 1, bias=True, relu=False, index=7)], a.reps)
     if sel("general"):
         # block sizes that are not powers of two (direct transforms): an FC layer with blocks of 100
         # and the 384-channel 13 x 13 CONV layer of an AlexNet-style network as 4 x 4 blocks of 96

@@ -18,7 +18,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="libcirc.
 def declared_functions():
     src = open(HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(circ_[a-z_]+)\s*\(", src)))
+    return sorted(set(re.findall(r"\b(circ_[a-z0-9_]+)\s*\(", src)))
 
 
 def test_exports_every_declared_symbol():
@@ -186,6 +186,33 @@ def test_sgd_step_and_export_argument_errors():
     assert e(A, 0, 2, 2, 8, A + big, None) == B.CIRC_EINVAL
     assert e(A, 1, 2, 2, 513, A + big, None) == B.CIRC_EINVAL
     assert e(A, 1, 2, 2, 8, A + 64, None) == B.CIRC_EINVAL    # w lies inside the blob
+
+
+def test_f16_argument_errors():
+    big = 1 << 28
+    assert B.lib().circ_spectra_bytes_f16(64, 64, 64) == 33 * 64 * 64 * 4
+    assert B.lib().circ_spectra_bytes_f16(64, 64, 4) == 0          # k below 8
+    assert B.lib().circ_spectra_bytes_f16(64, 64, 96) == 0         # not a power of two
+    assert B.lib().circ_spectra_bytes_f16(0, 64, 64) == 0
+    assert B.circ_fc_workspace_bytes_f16(64, 64, 64, 64) == 2 * 33 * 64 * 64 * 4
+    assert B.circ_fc_workspace_bytes_f16(64, 64, 64, 0) == 0
+    pre = B.lib().circ_precompute_spectra_f16
+    assert pre(None, 2, 2, 8, A, None) == B.CIRC_EINVAL
+    assert pre(A, 2, 2, 12, A + big, None) == B.CIRC_EINVAL
+    assert pre(A, 2, 2, 8, A, None) == B.CIRC_EINVAL              # output aliases input
+    f = B.lib().circ_fc_forward_f16
+
+    def call(w_hat=A, x=A + big, bias=None, y=A + 2 * big, p=2, q=2, k=8, batch=2, epi=0, wsp=A + 3 * big, wsb=1 << 30):
+        return f(w_hat, x, bias, y, p, q, k, batch, epi, wsp, wsb, None)
+
+    assert call(k=4) == B.CIRC_EINVAL
+    assert call(k=24) == B.CIRC_EINVAL
+    assert call(x=None) == B.CIRC_EINVAL
+    assert call(epi=B.EPI_BIAS) == B.CIRC_EINVAL                  # bias flag without a bias
+    assert call(epi=8) == B.CIRC_EINVAL
+    assert call(y=A + big) == B.CIRC_EINVAL                       # in place
+    assert call(x=A + big + 2) == B.CIRC_EINVAL                   # misaligned
+    assert call(wsb=16) == B.CIRC_EWORKSPACE
 
 
 def test_bias_grad_argument_errors():

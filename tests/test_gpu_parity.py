@@ -352,6 +352,53 @@ def test_conv_sgd_step_shapes(N, p, q, k, H, W, r, pad):
     check(y, O.conv_forward(w2, x1, None, False, pad), "conv forward after two steps " + what)
 
 
+# ---- half-width storage (fp16 in memory, fp32 arithmetic) -----------------------------------
+# Four fp16 roundings lie between the inputs and an output (spectra of the weights, spectra of the
+# inputs, output spectra, the output itself), each at most 2^-11 relative; the gate is their sum,
+# the value expected from independent roundings about a quarter of it.
+HALF_GATE = 4 * 2.0 ** -11
+
+
+def check_half(got, ref, what):
+    err = O.max_norm_rel_err(got, ref)
+    print(f"[parity f16] {what} max-norm rel err = {err:.3e}", flush=True)
+    assert np.all(np.isfinite(got)), what
+    assert err <= HALF_GATE, (what, err)
+    return err
+
+
+def gpu_fc_forward_f16(w, x16, bias, relu):
+    p, q, k = w.shape
+    wh = B.circ_precompute_spectra_f16(G.dev(w))
+    y = B.circ_fc_forward_f16(wh, torch.from_numpy(x16).to(G.DEV), G.dev(bias), None, p, q, k, G.epi_flags(bias, relu))
+    assert y.dtype == torch.float16
+    return y.float().cpu().numpy()
+
+
+@pytest.mark.parametrize("p,q,k,batch", [(1, 1, 8, 1), (3, 5, 16, 7), (5, 3, 64, 33), (2, 4, 256, 10), (33, 34, 8, 70),
+                                         (4, 6, 128, 67), (2, 3, 512, 5), (7, 9, 32, 2), (17, 64, 64, 130), (70, 12, 64, 300),
+                                         (64, 64, 64, 64), (65, 8, 32, 129)])
+def test_fc_forward_f16_shapes(p, q, k, batch):
+    w, x, b = rand_fc(p, q, k, batch)
+    x16 = x.astype(np.float16)                          # the inputs are fp16 values on both sides
+    xr = x16.astype(np.float32)
+    what = f"{p}x{q} k={k} B={batch}"
+    check_half(gpu_fc_forward_f16(w, x16, b, True), O.fc_forward(w, xr, b, True), "bias+relu " + what)
+    check_half(gpu_fc_forward_f16(w, x16, None, False), O.fc_forward(w, xr), "plain " + what)
+
+
+@pytest.mark.parametrize("cfg", ["cfg2", "cfg3_l2", "cfg5"])
+def test_fc_forward_f16_configs(cfg):
+    c = {"cfg2": synth.CFG2, "cfg3_l2": synth.CFG3_L2, "cfg5": synth.CFG5}[cfg]
+    w, x, b = synth.fc_inputs(c, 0)
+    x16 = x.astype(np.float16)
+    got = gpu_fc_forward_f16(w, x16, b, c.relu)
+    rows = sorted(set(int(i) for i in np.linspace(0, c.p - 1, 4)))   # sampled output block rows, all batch elements
+    ref = O.fc_forward(w, x16.astype(np.float32), b, c.relu, block_rows=rows)
+    sel = np.concatenate([np.arange(i * c.k, (i + 1) * c.k) for i in rows])
+    check_half(got[:, sel], ref, f"{cfg} block rows {rows}")
+
+
 # ---- block sizes that are not powers of two (direct transforms around the same contraction) ----
 @pytest.mark.parametrize("k", [1, 3, 5, 6, 7, 12, 24, 40, 96, 100, 125, 250, 384, 511])
 @pytest.mark.parametrize("batch", [1, 2, 33])
