@@ -895,6 +895,39 @@ static long long conv_dw_pix_per_block(long long npix) {
   return ppb;
 }
 
+// Weight-gradient reduction of a CONV layer: the kernel with the input spectra staged in LDS when
+// a band of rows of 4 input blocks fits 48 KB, else the one that reads every tap from global memory.
+struct ConvDwPlan {
+  bool lds;
+  int ng, BR, nbands, cpb, nparts;
+  size_t lds_bytes;
+  long long ppb;
+};
+static ConvDwPlan plan_conv_dw(int N, int H, int W, int Ho, int Wo, int r, int pad) {
+  ConvDwPlan pl{};
+  const long long npix = (long long)N * Ho * Wo;
+  pl.ppb = conv_dw_pix_per_block(npix);
+  pl.nparts = (int)cdiv(npix, pl.ppb);
+  pl.ng = 16;                                                      // offsets per block of the LDS kernel
+  // bytes per band row: 4 input blocks of padded rows + 4 output blocks; the halo adds r-1 input rows
+  const long long Wp = W + 2 * pad, row_bytes = 4 * (Wp + Wo) * (long long)sizeof(float2);
+  const long long halo_bytes = 4 * (r - 1) * Wp * (long long)sizeof(float2), budget = 40 * 1024;
+  // (W or Wo of 1: ceil(2^32 / 1) does not fit the 32-bit multipliers of the kernel)
+  if (halo_bytes + row_bytes > budget || (long long)N * Ho > (1ll << 30) || W < 2 || Wo < 2) return pl;
+  const long long fit = (budget - halo_bytes) / row_bytes;
+  const int BR = (int)(fit < Ho ? fit : Ho);
+  pl.nbands = (int)cdiv(Ho, BR);
+  pl.BR = (int)cdiv(Ho, pl.nbands);                                // bands of equal height
+  pl.nbands = (int)cdiv(Ho, pl.BR);
+  const long long total = (long long)N * pl.nbands;
+  pl.cpb = (int)cdiv(total, 32);                                   // at most 32 partial spectra
+  pl.nparts = (int)cdiv(total, pl.cpb);
+  pl.lds_bytes = size_t(4) * (dw_plane_stride(int((pl.BR + r - 1) * Wp)) + dw_plane_stride(pl.BR * Wo)) * sizeof(float2);
+  if (pl.lds_bytes < 8192) pl.lds_bytes = 8192;                    // room for the sums over the four waves
+  pl.lds = true;
+  return pl;
+}
+
 size_t circ_conv_backward_workspace_bytes(int N, int C_in, int C_out, int H, int W, int r, int stride, int pad, int k) {
   if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k) || stride != 1 || (r % 2) == 0) return 0;
   const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
@@ -903,7 +936,8 @@ size_t circ_conv_backward_workspace_bytes(int N, int C_in, int C_out, int H, int
   const size_t ya = align_up(spectrum_elems(k, (long long)p * N * Ho * Wo) * sizeof(float2), 256);
   const long long npix = (long long)N * Ho * Wo;
   const size_t wa = align_up(spectrum_elems(k, (long long)r * r * p * q) * sizeof(float2), 256);
-  return xa + ya + wa * size_t(cdiv(npix, conv_dw_pix_per_block(npix)));
+  (void)npix;
+  return xa + ya + wa * size_t(plan_conv_dw(N, H, W, Ho, Wo, r, pad).nparts);
 }
 
 }  // extern "C"
@@ -976,8 +1010,9 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
   }
   if (want_dw) {
     if (launch_rfft(k, true, x, xh, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
-    const long long npix = (long long)N * HWo, ppb = conv_dw_pix_per_block(npix);
-    const int nchunks = (int)cdiv(npix, ppb);
+    const ConvDwPlan dpl = plan_conv_dw(N, H, W, Ho, Wo, r, pad);
+    const long long npix = (long long)N * HWo, ppb = dpl.ppb;
+    const int nchunks = dpl.nparts;
     const long long wrows = (long long)r * r * p * q;
     const long long wstride = (long long)(align_up(spectrum_elems(k, wrows) * sizeof(float2), 256) / sizeof(float2));
 #ifndef CIRC_DW_NG
@@ -991,7 +1026,14 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
       return (unsigned)(((1ll << 32) + d - 1) / d);
     };
     const unsigned mul_hwo = fast_mul(npix, HWo), mul_wo = fast_mul(HWo, Wo);
-    if (r % CIRC_DW_NG == 0) {   // CIRC_DW_NG consecutive offsets per block (for r = 3: one filter row)
+    // staged element index / W: indices stay below 48 KB / 32 B, so the multiply-high is exact
+    const unsigned mul_w = (unsigned)(((1ll << 32) + W - 1) / W);
+    if (dpl.lds) {
+      dim3 grid((unsigned)dpl.nparts, (unsigned)NF, (unsigned)(cdiv(r * r, 16) * cdiv(p, 4) * cdiv(q, 4)));
+      const unsigned mul_wo_b = (unsigned)(((1ll << 32) + Wo - 1) / Wo);   // pixel index inside a band / Wo
+      hipLaunchKernelGGL(conv_dw_lds_kernel, grid, dim3(256), dpl.lds_bytes, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo, r,
+                         pad, dpl.BR, dpl.nbands, dpl.cpb, wstride, mul_wo_b, mul_w);
+    } else if (r % CIRC_DW_NG == 0) {   // CIRC_DW_NG consecutive offsets per block (for r = 3: one filter row)
       dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r / CIRC_DW_NG * cdiv(p, 4) * cdiv(q, 4)));
       hipLaunchKernelGGL((conv_dw_mfma_kernel<CIRC_DW_NG>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo,
                          r, pad, ppb, wstride, mul_hwo, mul_wo);
@@ -1001,11 +1043,21 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
                          ppb, wstride, mul_hwo, mul_wo);
     }
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+    // many partial spectra are folded into the first one by a launch of their own (one thread per
+    // value, fixed order); a few are added by the consumer while it loads them
+    int nsum = nchunks;
+    if (nchunks > 8) {
+      const long long nval = 2 * (long long)spectrum_elems(k, wrows);
+      hipLaunchKernelGGL(sum_parts_kernel, dim3((unsigned)cdiv(nval, 256)), dim3(256), 0, s, reinterpret_cast<float*>(wpart),
+                         nchunks, 2 * wstride, nval);
+      if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+      nsum = 1;
+    }
     // dw[g][i][j][:] = IFFT over f of the summed partial spectra, scale 1/k
     RowMap mw{(int)wrows, 1, (long long)k, 0, 0, 1};
-    if (dw && launch_irfft(k, false, wpart, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, nchunks, wstride) != hipSuccess)
+    if (dw && launch_irfft(k, false, wpart, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, nsum, wstride) != hipSuccess)
       return CIRC_EHIP;
-    if (w_upd) return apply_spectra_step(w_upd, wpart, nchunks, wstride, wrows, (long long)p * q, r * r, p, q, k, lr, s);
+    if (w_upd) return apply_spectra_step(w_upd, wpart, nsum, wstride, wrows, (long long)p * q, r * r, p, q, k, lr, s);
   }
   return CIRC_OK;
 }

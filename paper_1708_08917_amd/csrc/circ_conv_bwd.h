@@ -156,6 +156,167 @@ __global__ __launch_bounds__(256) void conv_dw_mfma_kernel(const float2* __restr
   }
 }
 
+// The same partial sums with both spectra staged in LDS and the 16 blocks of the matrix
+// instruction spread over the filter offsets instead of over pixels.  For one output pixel,
+// block b multiplies the 4 values dY^[i][pixel] (the same in every block) with the 4 values
+// X^[j][pixel shifted by offset g0 + b]: lane (b, sub) accumulates, in its own registers, the
+// complete sums for (offset g0 + b, i = i0 + 0..3, j = j0 + sub) over all pixels its wave sees,
+// so nothing has to be added across lanes at the end, only across the four waves.
+// A workgroup stages, for its 4 input blocks, the band of image rows that a band of BR output
+// rows touches (`pad` zero columns on either side, rows outside the image as zeros: a tap is
+// one LDS read at the pixel's address plus a per-lane constant) and the 4 x (BR*Wo) values of
+// dY^, and walks over cpb consecutive (image, band) chunks with the same accumulators.
+// Block (x = group of cpb chunks, y = frequency, z = (group of 16 offsets, tile of 4 i, tile of
+// 4 j)); output part[x][f][(g*p + i)*q + j] as above.
+// Dynamic LDS: 4 * (stride((BR + r - 1) * (W + 2*pad)) + stride(BR*Wo)) float2, stride() as below
+// (at least 2048 floats).
+// mul_wo, mul_w: ceil(2^32 / Wo), ceil(2^32 / W): exact division of indices inside a band.
+// Plane stride (in float2) for n elements per plane: the next value that is 4 modulo 16, so that the
+// four planes a wave reads at once start 8 banks apart.
+__host__ __device__ inline int dw_plane_stride(int n) { return n + (20 - n % 16) % 16; }
+
+__global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restrict__ dyh, const float2* __restrict__ xh,
+                                                          float2* __restrict__ part, int p, int q, int NF, int Nimg,
+                                                          int H, int W, int Ho, int Wo, int r, int pad, int BR,
+                                                          int nbands, int cpb, long long part_stride, unsigned mul_wo,
+                                                          unsigned mul_w) {
+  extern __shared__ float2 xs[];                  // [4 input blocks][rows_in][Wp], then [4 output blocks][BR*Wo]
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), f = blockIdx.y;
+  const int blk = lane >> 2, sub = lane & 3;
+  const int nit = (p + 3) / 4, njt = (q + 3) / 4;
+  int z = blockIdx.z;
+  const int jt = z % njt; z /= njt;
+  const int it = z % nit;
+  const int g0 = (z / nit) * 16;
+  const int i0 = it * 4, j0 = jt * 4;
+  const int Wp = W + 2 * pad;
+  const int rows_in = BR + r - 1, plane = rows_in * W;
+  const int planep = dw_plane_stride(rows_in * Wp), dplane = dw_plane_stride(BR * Wo);
+  float2* dys = xs + 4 * planep;
+  const unsigned HW = unsigned(H) * unsigned(W), HWo = unsigned(Ho) * unsigned(Wo);
+  const long long npix = (long long)Nimg * HWo;
+  const float2* dyf = dyh + (long long)f * p * npix;
+  const float2* xf = xh + (long long)f * q * Nimg * HW;
+
+  // this lane's offset (lanes past r*r repeat the last offset; their sums are never stored)
+  const int gl = min(g0 + blk, r * r - 1);
+  const float2* xsl = xs + sub * planep + (gl / r) * Wp + gl % r;   // staged column = wo + (gl % r - pad) + pad
+  const float2* dsl = dys + sub * dplane;
+  dw_floatx4 accR[2], accI[2];                    // two independent chains (even / odd pixels of a step)
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    accR[e] = dw_floatx4{0.f, 0.f, 0.f, 0.f};
+    accI[e] = dw_floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+  // the zero columns are written once; staging only ever writes the W image columns of a row
+  for (int e = tid; e < 4 * planep; e += 256) xs[e] = make_float2(0.f, 0.f);
+  const int total = Nimg * nbands;
+  const int cend = min(total, (int(blockIdx.x) + 1) * cpb);
+  for (int c = blockIdx.x * cpb; c < cend; ++c) {
+    const int n = c / nbands, band = c - n * nbands;
+    const int ho0 = band * BR, brc = min(BR, Ho - ho0), npx = brc * Wo;
+    __syncthreads();                              // the previous chunk has been read by every wave (first pass: zeros written)
+    // The staged rows are whole image rows, so the band of one input block is one contiguous run
+    // of the image: staged element t = (row, column) is image element (ho0 - pad)*W + t, or zero
+    // outside the image.  The four blocks are fetched together (four independent loads per step).
+    {
+      const int e0 = (ho0 - pad) * W;
+      const float2* src[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj)
+        src[jj] = xf + (unsigned(min(j0 + jj, q - 1)) * unsigned(Nimg) + unsigned(n)) * HW;
+#pragma unroll 2
+      for (int t = tid; t < plane; t += 256) {
+        const int e = e0 + t;
+        const bool in_img = e >= 0 && e < int(HW);
+        const int ec = min(max(e, 0), int(HW) - 1);
+        const int row = int(__umulhi(unsigned(t), mul_w));
+        const int dst = t + row * (2 * pad) + pad;   // row*Wp + pad + column
+        float2 v[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) v[jj] = src[jj][ec];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+          xs[jj * planep + dst] = (in_img && j0 + jj < q) ? v[jj] : make_float2(0.f, 0.f);
+      }
+      const float2* dsrc[4];
+#pragma unroll
+      for (int ii = 0; ii < 4; ++ii)
+        dsrc[ii] = dyf + unsigned(min(i0 + ii, p - 1)) * unsigned(npix) + unsigned(n) * HWo + unsigned(ho0) * unsigned(Wo);
+#pragma unroll 2
+      for (int t = tid; t < npx; t += 256) {
+        float2 v[4];
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) v[ii] = dsrc[ii][t];
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) dys[ii * dplane + t] = i0 + ii < p ? v[ii] : make_float2(0.f, 0.f);
+      }
+    }
+    __syncthreads();
+    // wave w takes pixels w, w + 4, ...: four at a time (operands first, then 16 matrix instructions)
+    auto mac = [&](int e, float2 dv, float2 xv) {
+      accR[e] = __builtin_amdgcn_mfma_f32_4x4x1f32(dv.x, xv.x, accR[e], 0, 0, 0);
+      accI[e] = __builtin_amdgcn_mfma_f32_4x4x1f32(dv.y, xv.x, accI[e], 0, 0, 0);
+      accR[e] = __builtin_amdgcn_mfma_f32_4x4x1f32(dv.y, xv.y, accR[e], 0, 0, 0);
+      accI[e] = __builtin_amdgcn_mfma_f32_4x4x1f32(-dv.x, xv.y, accI[e], 0, 0, 0);
+    };
+    auto tap = [&](int pix) -> int {              // staged element of output pixel pix, offset (0, 0): hl*Wp + wo
+      const int hl = int(__umulhi(unsigned(pix), mul_wo));
+      return pix + hl * (Wp - Wo);
+    };
+    int pix = wave;
+    for (; pix + 12 < npx; pix += 16) {
+      float2 dv[4], xv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        dv[u] = dsl[pix + 4 * u];
+        xv[u] = xsl[tap(pix + 4 * u)];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) mac(u & 1, dv[u], xv[u]);
+    }
+    for (; pix < npx; pix += 4) mac(0, dsl[pix], xsl[tap(pix)]);
+  }
+
+  // sums over the four waves: accumulators -> LDS (the staging area is free after the barrier)
+  __syncthreads();
+  float* wsum = reinterpret_cast<float*>(xs);    // [wave][value m*2 + c][lane]
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    wsum[(wave * 8 + 2 * m + 0) * 64 + lane] = accR[0][m] + accR[1][m];
+    wsum[(wave * 8 + 2 * m + 1) * 64 + lane] = accI[0][m] + accI[1][m];
+  }
+  __syncthreads();
+  const long long rows = (long long)r * r * p * q;
+  float* out = reinterpret_cast<float*>(part + (long long)blockIdx.x * part_stride + (long long)f * rows);
+  for (int v = tid; v < 8 * 64; v += 256) {
+    const int ln = v & 63, e = v >> 6;           // e = m*2 + c
+    const int c = e & 1, m = e >> 1;
+    const int gg = g0 + (ln >> 2), i = i0 + m, j = j0 + (ln & 3);
+    if (gg < r * r && i < p && j < q)
+      out[2 * (((long long)gg * p + i) * q + j) + c] =
+          (wsum[(0 * 8 + e) * 64 + ln] + wsum[(1 * 8 + e) * 64 + ln]) + (wsum[(2 * 8 + e) * 64 + ln] + wsum[(3 * 8 + e) * 64 + ln]);
+  }
+}
+
+// part[0][e] = sum over s < nparts of part[s][e], in index order (e < n floats): the partial
+// spectra of the weight gradient folded into the first one, one thread per value.
+__global__ __launch_bounds__(256) void sum_parts_kernel(float* __restrict__ part, int nparts, long long part_stride, long long n) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= n) return;
+  float v[8];
+  float acc = part[e];
+  int s = 1;
+  for (; s + 8 <= nparts; s += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = part[(s + u) * part_stride + e];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  for (; s < nparts; ++s) acc += part[s * part_stride + e];
+  part[e] = acc;
+}
+
 // db[c] = sum_{o < outer, t < inner} dy[(o*channels + c)*inner + t], one block per channel
 // (CONV: outer = images, inner = pixels per image).
 __global__ __launch_bounds__(256) void bias_grad_channel_kernel(const float* __restrict__ dy, float* __restrict__ db,
