@@ -16,24 +16,6 @@ namespace circ {
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef float hfloatx16 __attribute__((ext_vector_type(16)));
 
-// Eight consecutive fp16 values (four complex numbers) of a row starting at complex index j.
-// VEC: rows are 16-byte aligned and Kd is a multiple of 4, so the group is inside the row or
-// entirely past its end; otherwise element by element with a bounds test each.
-template <bool VEC>
-__device__ __forceinline__ uint4 load_complex4(const __half2* row, int j, int Kd) {
-  uint4 v = make_uint4(0u, 0u, 0u, 0u);
-  if constexpr (VEC) {
-    if (j < Kd) v = *reinterpret_cast<const uint4*>(row + j);
-  } else {
-    const unsigned* r32 = reinterpret_cast<const unsigned*>(row);
-    if (j + 0 < Kd) v.x = r32[j + 0];
-    if (j + 1 < Kd) v.y = r32[j + 1];
-    if (j + 2 < Kd) v.z = r32[j + 2];
-    if (j + 3 < Kd) v.w = r32[j + 3];
-  }
-  return v;
-}
-
 __device__ __forceinline__ halfx8 as_halfx8(uint4 v) {
   union { uint4 u; halfx8 h; } c;
   c.u = v;
@@ -46,40 +28,88 @@ __device__ __forceinline__ halfx8 as_halfx8(uint4 v) {
 //   Re C = A . (br, -bi, ...)      Im C = A . (bi, br, ...)
 // so the two real products per tile need only the B operand rewritten, lane-locally: a sign
 // flip of the odd halves and a swap inside every 32-bit word.  Lane (h, r) = (lane / 32,
-// lane % 32) loads complex elements [k0 + 4h, k0 + 4h + 4) of its row for both operands, so the
-// two operands pair up element by element whatever order the instruction sums them in.
+// lane % 32) takes complex elements [8s + 4h, 8s + 4h + 4) of its row in step s for both
+// operands, so the operands pair up element by element whatever order the instruction sums them in.
 // Accumulators: column = lane % 32, register t holds row 8*(t/4) + 4*(lane/32) + t%4.
-// No LDS and no barriers: a wave whose columns lie past N leaves at once.
+//
+// The reduction runs in chunks of 64 complex values.  A chunk of both operand tiles goes through
+// LDS: the workgroup loads it with lanes running along the rows (every 128-byte line of the
+// operands is fetched once, by one instruction), and the waves then read their fragments, 16 bytes
+// per lane, from LDS rows padded to 68 words (consecutive rows start 4 banks apart).  Fetching
+// the fragments straight from global memory makes every instruction touch 32 lines for 32 bytes
+// each, and the same lines come back for the next steps; that version ran at the L2 line rate.
+// VEC: Kd is a multiple of 4 (16-byte pieces are whole or entirely past the end of a row);
+// otherwise the chunk is staged element by element.  Values past Kd are staged as zeros.
+constexpr int kHChunk = 64;                      // complex values of the reduction per chunk
+constexpr int kHPitch = kHChunk + 4;             // LDS row pitch in complex values (272 bytes)
+
 template <bool VEC>
 __global__ __launch_bounds__(256) void cgemm_h_kernel(const __half2* __restrict__ A, const __half2* __restrict__ B,
                                                       __half2* __restrict__ C, int M, int N, int Kd, long long sA,
                                                       long long sB, long long sC, float scale) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int f = blockIdx.z, m0 = blockIdx.y * 64, n0 = blockIdx.x * 128 + 32 * wave;
-  if (n0 >= N) return;
+  __shared__ __attribute__((aligned(16))) __half2 lds[(64 + 128) * kHPitch];
+  __half2* la = lds;
+  __half2* lb = lds + 64 * kHPitch;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int f = blockIdx.z, m0 = blockIdx.y * 64, nb0 = blockIdx.x * 128;
   const int r = lane & 31, h = lane >> 5;
-  const __half2* a0 = A + f * sA + (long long)min(m0 + r, M - 1) * Kd;
-  const __half2* a1 = A + f * sA + (long long)min(m0 + 32 + r, M - 1) * Kd;
-  const __half2* b = B + f * sB + (long long)min(n0 + r, N - 1) * Kd;
+  const __half2* Af = A + f * sA;
+  const __half2* Bf = B + f * sB;
   hfloatx16 cr0, ci0, cr1, ci1;
 #pragma unroll
   for (int t = 0; t < 16; ++t) { cr0[t] = 0.f; ci0[t] = 0.f; cr1[t] = 0.f; ci1[t] = 0.f; }
-#pragma unroll 2
-  for (int k0 = 0; k0 < Kd; k0 += 8) {
-    const int j = k0 + 4 * h;
-    const uint4 va0 = load_complex4<VEC>(a0, j, Kd), va1 = load_complex4<VEC>(a1, j, Kd);
-    const uint4 vb = load_complex4<VEC>(b, j, Kd);
-    const uint4 vre = make_uint4(vb.x ^ 0x80000000u, vb.y ^ 0x80000000u, vb.z ^ 0x80000000u, vb.w ^ 0x80000000u);
-    const uint4 vim = make_uint4(__builtin_amdgcn_alignbit(vb.x, vb.x, 16), __builtin_amdgcn_alignbit(vb.y, vb.y, 16),
-                                 __builtin_amdgcn_alignbit(vb.z, vb.z, 16), __builtin_amdgcn_alignbit(vb.w, vb.w, 16));
-    const halfx8 ha0 = as_halfx8(va0), ha1 = as_halfx8(va1), hre = as_halfx8(vre), him = as_halfx8(vim);
-    cr0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha0, hre, cr0, 0, 0, 0);
-    ci0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha0, him, ci0, 0, 0, 0);
-    cr1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha1, hre, cr1, 0, 0, 0);
-    ci1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha1, him, ci1, 0, 0, 0);
+  const bool wave_active = nb0 + 32 * wave < N;  // waves past N only help with the staging
+  for (int kc = 0; kc < Kd; kc += kHChunk) {
+    __syncthreads();                             // the previous chunk has been read
+    if constexpr (VEC) {
+      // piece e of the chunk: row e / 16, 16-byte piece e % 16 of the row's 256 bytes; rows of A
+      // first, then rows of B (rows past M or N repeat the last one: their results are not stored)
+      uint4 v[12];
+#pragma unroll
+      for (int it = 0; it < 12; ++it) {
+        const int e = it * 256 + tid, row = e >> 4, j = kc + 4 * (e & 15);
+        const __half2* src = row < 64 ? Af + (long long)min(m0 + row, M - 1) * Kd : Bf + (long long)min(nb0 + row - 64, N - 1) * Kd;
+        v[it] = *reinterpret_cast<const uint4*>(src + min(j, Kd - 4));
+      }
+#pragma unroll
+      for (int it = 0; it < 12; ++it) {
+        const int e = it * 256 + tid, row = e >> 4, j = kc + 4 * (e & 15);
+        *reinterpret_cast<uint4*>(lds + row * kHPitch + 4 * (e & 15)) = j < Kd ? v[it] : make_uint4(0u, 0u, 0u, 0u);
+      }
+    } else {
+      for (int e = tid; e < (64 + 128) * kHChunk; e += 256) {
+        const int row = e >> 6, j = kc + (e & 63);
+        const __half2* src = row < 64 ? Af + (long long)min(m0 + row, M - 1) * Kd : Bf + (long long)min(nb0 + row - 64, N - 1) * Kd;
+        const unsigned v = reinterpret_cast<const unsigned*>(src)[min(j, Kd - 1)];
+        reinterpret_cast<unsigned*>(lds)[row * kHPitch + (e & 63)] = j < Kd ? v : 0u;
+      }
+    }
+    __syncthreads();
+    if (wave_active) {
+      const __half2* fa0 = la + r * kHPitch + 4 * h;
+      const __half2* fa1 = la + (32 + r) * kHPitch + 4 * h;
+      const __half2* fb = lb + (32 * wave + r) * kHPitch + 4 * h;
+      const int nsteps = min(kHChunk, Kd - kc + 7) / 8;   // whole steps of 8 that hold anything
+#pragma unroll
+      for (int s = 0; s < kHChunk / 8; ++s) {
+        if (s < nsteps) {                        // wave-uniform
+          const uint4 va0 = *reinterpret_cast<const uint4*>(fa0 + 8 * s);
+          const uint4 va1 = *reinterpret_cast<const uint4*>(fa1 + 8 * s);
+          const uint4 vb = *reinterpret_cast<const uint4*>(fb + 8 * s);
+          const uint4 vre = make_uint4(vb.x ^ 0x80000000u, vb.y ^ 0x80000000u, vb.z ^ 0x80000000u, vb.w ^ 0x80000000u);
+          const uint4 vim = make_uint4(__builtin_amdgcn_alignbit(vb.x, vb.x, 16), __builtin_amdgcn_alignbit(vb.y, vb.y, 16),
+                                       __builtin_amdgcn_alignbit(vb.z, vb.z, 16), __builtin_amdgcn_alignbit(vb.w, vb.w, 16));
+          const halfx8 ha0 = as_halfx8(va0), ha1 = as_halfx8(va1), hre = as_halfx8(vre), him = as_halfx8(vim);
+          cr0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha0, hre, cr0, 0, 0, 0);
+          ci0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha0, him, ci0, 0, 0, 0);
+          cr1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha1, hre, cr1, 0, 0, 0);
+          ci1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha1, him, ci1, 0, 0, 0);
+        }
+      }
+    }
   }
-  const int col = n0 + r;
-  if (col >= N) return;
+  const int col = nb0 + 32 * wave + r;
+  if (!wave_active || col >= N) return;
   __half2* c = C + f * sC + col;
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
