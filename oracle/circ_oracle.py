@@ -132,12 +132,18 @@ def fc_backward_dw(x, dy, k, pairs=None) -> np.ndarray:
     return dw
 
 
-def conv_forward(w, x, bias=None, relu=False, pad=0) -> np.ndarray:
-    """Block-circulant CONV layer, stride 1 (Eq. 6 with the structure of Eq. 7).
+def conv_out_size(n, r, pad, stride) -> int:
+    """Output positions along one axis: the filter is placed every `stride` pixels as long as it
+    fits the zero-padded input."""
+    return (n + 2 * pad - r) // stride + 1
+
+
+def conv_forward(w, x, bias=None, relu=False, pad=0, stride=1) -> np.ndarray:
+    """Block-circulant CONV layer (Eq. 6 with the structure of Eq. 7; Eq. 6 itself is stride 1).
 
     w[r][r][p][q][k] (offset-major), x[N][C_in][H][W] ->
-    y[N][C_out][H + 2 pad - r + 1][W + 2 pad - r + 1], with
-    y[n, co, h, w] = sum_{dh, dw, ci} Wd[dh, dw][co, ci] * xpad[n, ci, h + dh, w + dw]
+    y[N][C_out][(H + 2 pad - r) // stride + 1][(W + 2 pad - r) // stride + 1], with
+    y[n, co, h, w] = sum_{dh, dw, ci} Wd[dh, dw][co, ci] * xpad[n, ci, h*stride + dh, w*stride + dw]
     where Wd[dh, dw] is the dense expansion of the p x q grid of that offset.
     """
     w = np.asarray(w, dtype=np.float64)
@@ -147,14 +153,15 @@ def conv_forward(w, x, bias=None, relu=False, pad=0) -> np.ndarray:
     p, q, k = w.shape[2:]
     assert C_in == q * k
     C_out = p * k
-    Ho, Wo = H + 2 * pad - r + 1, Wd_ + 2 * pad - r + 1
+    Ho, Wo = conv_out_size(H, r, pad, stride), conv_out_size(Wd_, r, pad, stride)
     xp = np.zeros((N, C_in, H + 2 * pad, Wd_ + 2 * pad), dtype=np.float64)
     xp[:, :, pad:pad + H, pad:pad + Wd_] = x
     y = np.zeros((N, C_out, Ho, Wo), dtype=np.float64)
     for dh in range(r):
         for dw in range(r):
             M = expand_block_circulant(w[dh, dw])        # C_out x C_in
-            win = xp[:, :, dh:dh + Ho, dw:dw + Wo]       # N x C_in x Ho x Wo
+            # the input pixel under tap (dh, dw) of every output position
+            win = xp[:, :, dh:dh + (Ho - 1) * stride + 1:stride, dw:dw + (Wo - 1) * stride + 1:stride]
             # channel mixing at every pixel: y[n, :, h, w] += M @ win[n, :, h, w]
             y += np.matmul(M, win.reshape(N, C_in, Ho * Wo)).reshape(N, C_out, Ho, Wo)
     if bias is not None:
@@ -164,11 +171,11 @@ def conv_forward(w, x, bias=None, relu=False, pad=0) -> np.ndarray:
     return y
 
 
-def conv_backward_dx(w, dy, H, W, pad=0) -> np.ndarray:
+def conv_backward_dx(w, dy, H, W, pad=0, stride=1) -> np.ndarray:
     """dL/dx of the block-circulant CONV layer (chain rule through Eq. 6; Sec. 3.2 notes that
     training of CONV layers follows the FC derivation).
 
-    y[n, co, ho, wo] takes x[n, ci, ho + dh - pad, wo + dw - pad] with weight
+    y[n, co, ho, wo] takes x[n, ci, ho*stride + dh - pad, wo*stride + dw - pad] with weight
     Wd[dh, dw][co, ci], so every (dh, dw) scatters Wd[dh, dw]^T dy[n, :, ho, wo] back to that
     input pixel; positions in the zero padding receive nothing.
     w[r][r][p][q][k], dy[N][C_out][Ho][Wo] -> dx[N][C_in][H][W].
@@ -178,22 +185,22 @@ def conv_backward_dx(w, dy, H, W, pad=0) -> np.ndarray:
     r = w.shape[0]
     p, q, k = w.shape[2:]
     N, C_out, Ho, Wo = dy.shape
-    assert C_out == p * k and Ho == H + 2 * pad - r + 1 and Wo == W + 2 * pad - r + 1
+    assert C_out == p * k and Ho == conv_out_size(H, r, pad, stride) and Wo == conv_out_size(W, r, pad, stride)
     C_in = q * k
     dxp = np.zeros((N, C_in, H + 2 * pad, W + 2 * pad), dtype=np.float64)
     for dh in range(r):
         for dw in range(r):
             M = expand_block_circulant(w[dh, dw])        # C_out x C_in
             g = np.matmul(M.T, dy.reshape(N, C_out, Ho * Wo)).reshape(N, C_in, Ho, Wo)
-            dxp[:, :, dh:dh + Ho, dw:dw + Wo] += g
+            dxp[:, :, dh:dh + (Ho - 1) * stride + 1:stride, dw:dw + (Wo - 1) * stride + 1:stride] += g
     return dxp[:, :, pad:pad + H, pad:pad + W].copy()
 
 
-def conv_backward_dw(x, dy, k, r, pad=0) -> np.ndarray:
+def conv_backward_dw(x, dy, k, r, pad=0, stride=1) -> np.ndarray:
     """dL/dw of the block-circulant CONV layer, summed over images and pixels.
 
     For every offset the gradient of the dense channel-mixing matrix is
-    G[dh, dw] = sum_{n, ho, wo} dy[n, :, ho, wo] xpad[n, :, ho + dh, wo + dw]^T, and, as for
+    G[dh, dw] = sum_{n, ho, wo} dy[n, :, ho, wo] xpad[n, :, ho*stride + dh, wo*stride + dw]^T, and, as for
     FC layers (Eq. 4), dw[dh][dw][i][j][t] collects the entries of block (i, j) that hold
     that weight: sum_a G_ij[a][(a - t) mod k].
     x[N][C_in][H][W], dy[N][C_out][Ho][Wo] -> dw[r][r][p][q][k].
@@ -202,7 +209,7 @@ def conv_backward_dw(x, dy, k, r, pad=0) -> np.ndarray:
     dy = np.asarray(dy, dtype=np.float64)
     N, C_in, H, W = x.shape
     _, C_out, Ho, Wo = dy.shape
-    assert Ho == H + 2 * pad - r + 1 and Wo == W + 2 * pad - r + 1
+    assert Ho == conv_out_size(H, r, pad, stride) and Wo == conv_out_size(W, r, pad, stride)
     p, q = C_out // k, C_in // k
     xp = np.zeros((N, C_in, H + 2 * pad, W + 2 * pad), dtype=np.float64)
     xp[:, :, pad:pad + H, pad:pad + W] = x
@@ -213,7 +220,8 @@ def conv_backward_dw(x, dy, k, r, pad=0) -> np.ndarray:
     dw = np.empty((r, r, p, q, k), dtype=np.float64)
     for dh in range(r):
         for dw_ in range(r):
-            win = xp[:, :, dh:dh + Ho, dw_:dw_ + Wo].transpose(1, 0, 2, 3).reshape(C_in, N * Ho * Wo)
+            win = xp[:, :, dh:dh + (Ho - 1) * stride + 1:stride, dw_:dw_ + (Wo - 1) * stride + 1:stride]
+            win = win.transpose(1, 0, 2, 3).reshape(C_in, N * Ho * Wo)
             G = np.matmul(dyf, win.T)                    # C_out x C_in
             for i in range(p):
                 for j in range(q):
@@ -243,10 +251,10 @@ def fc_sgd_step(w, x, dy, lr) -> np.ndarray:
     return w - float(lr) * fc_backward_dw(x, dy, w.shape[2])
 
 
-def conv_sgd_step(w, x, dy, lr, pad=0) -> np.ndarray:
+def conv_sgd_step(w, x, dy, lr, pad=0, stride=1) -> np.ndarray:
     """The same step for a block-circulant CONV layer (Sec. 3.2): w[r][r][p][q][k]."""
     w = np.asarray(w, dtype=np.float64)
-    return w - float(lr) * conv_backward_dw(x, dy, w.shape[4], w.shape[0], pad)
+    return w - float(lr) * conv_backward_dw(x, dy, w.shape[4], w.shape[0], pad, stride)
 
 
 def max_norm_rel_err(got, ref) -> float:

@@ -279,6 +279,38 @@ def test_conv_gradients_vs_library_autograd(k, r, pad):
     np.testing.assert_allclose(O.bias_grad(dy), bt.grad.numpy(), atol=1e-12)
 
 
+@pytest.mark.parametrize("k,r,pad,stride", [(4, 3, 1, 2), (2, 3, 0, 2), (1, 5, 2, 3), (2, 2, 0, 2), (4, 4, 1, 2), (3, 2, 1, 1)])
+def test_strided_and_even_filters_vs_library_convolution(k, r, pad, stride):
+    """Stride > 1 and even filter sizes: forward and both gradients against the library's
+    conv2d (float64, autograd) on the filter bank built entry by entry; odd image sizes so that
+    the last rows and columns are not reached by any filter position."""
+    p, q, N, H, W = 2, 3, 2, 9, 8
+    w = RNG.standard_normal((r, r, p, q, k))
+    x = RNG.standard_normal((N, q * k, H, W))
+    Ho, Wo = (H + 2 * pad - r) // stride + 1, (W + 2 * pad - r) // stride + 1
+    dy = RNG.standard_normal((N, p * k, Ho, Wo))
+    xt = torch.from_numpy(x).requires_grad_(True)
+    Wt = torch.from_numpy(_dense_filter_bank(w)).requires_grad_(True)
+    y = torch.nn.functional.conv2d(xt, Wt, None, stride=stride, padding=pad)
+    assert tuple(y.shape) == (N, p * k, Ho, Wo)
+    np.testing.assert_allclose(O.conv_forward(w, x, None, False, pad, stride), y.detach().numpy(), atol=1e-11)
+    (y * torch.from_numpy(dy)).sum().backward()
+    np.testing.assert_allclose(O.conv_backward_dx(w, dy, H, W, pad, stride), xt.grad.numpy(), atol=1e-11)
+    gW = Wt.grad.numpy()
+    ref_dw = np.zeros_like(w)
+    for dh in range(r):
+        for dw in range(r):
+            for i in range(p):
+                for j in range(q):
+                    for a in range(k):
+                        for b in range(k):
+                            ref_dw[dh, dw, i, j, (a - b) % k] += gW[i * k + a, j * k + b, dh, dw]
+    np.testing.assert_allclose(O.conv_backward_dw(x, dy, k, r, pad, stride), ref_dw, atol=1e-11)
+    # stride 1 through the new argument is the old function
+    if stride == 1:
+        np.testing.assert_array_equal(O.conv_forward(w, x, None, False, pad, 1), O.conv_forward(w, x, None, False, pad))
+
+
 def test_conv_gradients_finite_differences_and_bilinear_identities():
     p, q, k, r, pad, N, H, W = 2, 2, 4, 3, 1, 2, 4, 5
     w = RNG.standard_normal((r, r, p, q, k))
