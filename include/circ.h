@@ -43,7 +43,7 @@ extern "C" {
 typedef enum {
   CIRC_OK = 0,
   CIRC_EINVAL = -1,     /* null/misaligned pointer, non-positive size, bad k, aliasing */
-  CIRC_ENOTSUP = -2,    /* valid request this build does not implement (stride != 1, even r) */
+  CIRC_ENOTSUP = -2,    /* valid request this build does not implement (none at present; kept for the ABI) */
   CIRC_EWORKSPACE = -3, /* workspace NULL or smaller than the matching *_workspace_bytes */
   CIRC_EHIP = -4        /* a HIP launch failed; hipGetLastError holds the detail */
 } circ_status;
@@ -115,8 +115,9 @@ size_t circ_conv_workspace_bytes(int N, int C_in, int C_out, int H, int W,
  *   w_hat  from circ_precompute_spectra with n_grids = r*r, p = C_out/k, q = C_in/k
  *   x      device, NCHW [N][C_in][H][W]
  *   bias   device, [C_out] (per output channel) or NULL
- *   y      device, NCHW [N][C_out][H+2*pad-r+1][W+2*pad-r+1]
- * stride must be 1 and r odd (CIRC_ENOTSUP otherwise); 0 <= pad < r.
+ *   y      device, NCHW [N][C_out][Ho][Wo], Ho = (H+2*pad-r)/stride + 1, Wo likewise
+ * With stride > 1 (Eq. 6 is the stride-1 case) the filter moves `stride` pixels per output:
+ * x is read at [h*stride+dh-pad][w*stride+dw-pad].  stride >= 1, r >= 1, 0 <= pad < r.
  */
 circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bias, float* y,
                               int N, int C_in, int C_out, int H, int W,
@@ -135,14 +136,15 @@ size_t circ_conv_backward_workspace_bytes(int N, int C_in, int C_out, int H, int
  *   dx[n][ci][h][w]     = sum_{dh,dw,co} Wd[dh][dw][co][ci] * dy[n][co][h-dh+pad][w-dw+pad]   (may be NULL)
  *   dw[dh][dw][i][j][t] = sum over images, output pixels and a of
  *                         dy[n][i*k+a][ho][wo] * x[n][j*k+((a-t) mod k)][ho+dh-pad][wo+dw-pad]  (may be NULL)
- * (terms outside the image are zero).  Both are overwritten, not accumulated, summed over the
+ * (terms outside the image are zero; written for stride 1 - with stride s the output pixel
+ * (ho, wo) pairs with input pixel (ho*s+dh-pad, wo*s+dw-pad) in both sums).  Both are overwritten, not accumulated, summed over the
  * batch without 1/N, and deterministic (no floating-point atomics).
  *   w_hat  from circ_precompute_spectra with n_grids = r*r, p = C_out/k, q = C_in/k
  *   x      device, NCHW [N][C_in][H][W]                    (needed for dw only)
- *   dy     device, NCHW [N][C_out][H+2*pad-r+1][W+2*pad-r+1]
+ *   dy     device, NCHW [N][C_out][(H+2*pad-r)/stride+1][(W+2*pad-r)/stride+1]
  *   dx     device, NCHW like x;  dw device, [r][r][p][q][k]
  *   workspace  at least circ_conv_backward_workspace_bytes(...) bytes
- * stride must be 1 and r odd (CIRC_ENOTSUP otherwise); 0 <= pad < r.
+ * stride >= 1, r >= 1, 0 <= pad < r.
  */
 circ_status circ_conv_backward(const void* w_hat, const float* x, const float* dy,
                                float* dx, float* dw,

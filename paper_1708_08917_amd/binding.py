@@ -140,7 +140,7 @@ def circ_fc_backward(w_hat, x, dy, p, q, k, need_dx=True, need_dw=True, dx=None,
 def circ_conv_forward(w_hat, x, bias, y, C_out, r, stride, pad, k, epilogue=EPI_NONE, workspace=None):
     """x: NCHW -> y: NCHW (allocated if None).  Returns y."""
     N, C_in, H, W = x.shape
-    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    Ho, Wo = (H + 2 * pad - r) // stride + 1, (W + 2 * pad - r) // stride + 1
     if y is None:
         y = torch.empty(N, C_out, Ho, Wo, dtype=torch.float32, device=x.device)
     if workspace is None:

@@ -818,6 +818,10 @@ hipError_t launch_conv_fused(const float2* wc, const float* x, const float* bias
 
 extern "C" {
 
+// Output positions along one axis (the filter is placed every `stride` pixels while it fits the
+// zero-padded input).
+static int conv_out(int n, int r, int pad, int stride) { return (n + 2 * pad - r) / stride + 1; }
+
 static bool conv_dims_ok(int N, int C_in, int C_out, int H, int W, int r, int pad, int k) {
   if (N <= 0 || C_in <= 0 || C_out <= 0 || H <= 0 || W <= 0 || r <= 0 || !valid_k(k)) return false;
   if (C_in % k || C_out % k) return false;
@@ -830,8 +834,8 @@ static bool conv_dims_ok(int N, int C_in, int C_out, int H, int W, int r, int pa
 }
 
 size_t circ_conv_workspace_bytes(int N, int C_in, int C_out, int H, int W, int r, int stride, int pad, int k) {
-  if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k) || stride != 1 || (r % 2) == 0) return 0;
-  const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
+  if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k) || stride < 1) return 0;
+  const int Ho = conv_out(H, r, pad, stride), Wo = conv_out(W, r, pad, stride);
   size_t xa = align_up(spectrum_elems(k, (long long)(C_in / k) * N * H * W) * sizeof(float2), 256);
   size_t ya = align_up(spectrum_elems(k, (long long)(C_out / k) * N * Ho * Wo) * sizeof(float2), 256);
   return xa + ya;
@@ -842,13 +846,12 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
                               void* workspace, size_t workspace_bytes, void* stream) {
   if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k)) return CIRC_EINVAL;
   if (stride <= 0) return CIRC_EINVAL;
-  if (stride != 1 || (r % 2) == 0) return CIRC_ENOTSUP;
   if (!w_hat || !x || !y) return CIRC_EINVAL;
   if (epilogue & ~(CIRC_EPI_BIAS | CIRC_EPI_RELU)) return CIRC_EINVAL;
   const bool use_bias = epilogue & CIRC_EPI_BIAS;
   if (use_bias && !bias) return CIRC_EINVAL;
   if (!aligned16(w_hat) || !aligned16(x) || !aligned16(y) || (use_bias && !aligned16(bias))) return CIRC_EINVAL;
-  const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
+  const int Ho = conv_out(H, r, pad, stride), Wo = conv_out(W, r, pad, stride);
   const size_t xbytes = size_t(N) * C_in * H * W * sizeof(float), ybytes = size_t(N) * C_out * Ho * Wo * sizeof(float);
   if (overlaps(x, xbytes, y, ybytes)) return CIRC_EINVAL;
   const size_t need = circ_conv_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k);
@@ -858,7 +861,7 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
 
   const int p = C_out / k, q = C_in / k, NF = k / 2 + 1;
   const long long HW = (long long)H * W, HWo = (long long)Ho * Wo;
-  if (conv_fused_applicable(p, q, k, r, N, H, W, Ho, Wo)) {
+  if (stride == 1 && conv_fused_applicable(p, q, k, r, N, H, W, Ho, Wo)) {
     const float2* wc = blob_at<float2>(w_hat, blob_layout(r * r, p, q, k).conv);
     return launch_conv_fused(wc, x, use_bias ? bias : nullptr, y, N, p, q, k, r, H, W, Ho, Wo, pad,
                              (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) == hipSuccess ? CIRC_OK : CIRC_EHIP;
@@ -875,7 +878,7 @@ circ_status circ_conv_forward(const void* w_hat, const float* x, const float* bi
     const long long npix = (long long)N * HWo;
     dim3 grid((unsigned)cdiv(npix, 256), (unsigned)NF, (unsigned)cdiv(p, IT));
     hipLaunchKernelGGL((conv_contract_kernel<IT>), grid, dim3(256), 0, s, static_cast<const float2*>(w_hat), xh, yh,
-                       p, q, NF, N, H, W, Ho, Wo, r, pad, 0);
+                       p, q, NF, N, H, W, Ho, Wo, r, pad, 0, stride, 1);
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
   }
   RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo, HWo % 4 == 0};
@@ -903,18 +906,19 @@ struct ConvDwPlan {
   size_t lds_bytes;
   long long ppb;
 };
-static ConvDwPlan plan_conv_dw(int N, int H, int W, int Ho, int Wo, int r, int pad) {
+static ConvDwPlan plan_conv_dw(int N, int H, int W, int Ho, int Wo, int r, int pad, int stride) {
   ConvDwPlan pl{};
   const long long npix = (long long)N * Ho * Wo;
   pl.ppb = conv_dw_pix_per_block(npix);
   pl.nparts = (int)cdiv(npix, pl.ppb);
   pl.ng = 16;                                                      // offsets per block of the LDS kernel
-  // bytes per band row: 4 input blocks of padded rows + 4 output blocks; the halo adds r-1 input rows
-  const long long Wp = W + 2 * pad, row_bytes = 4 * (Wp + Wo) * (long long)sizeof(float2);
-  const long long halo_bytes = 4 * (r - 1) * Wp * (long long)sizeof(float2), budget = 40 * 1024;
+  // a band of BR output rows needs (BR-1)*stride + r padded input rows of 4 input blocks and
+  // BR rows of 4 output blocks
+  const long long Wp = W + 2 * pad, el = 4 * (long long)sizeof(float2), budget = 40 * 1024;
+  const long long first = el * (r * Wp + Wo), more = el * (stride * Wp + Wo);   // bytes of one row, of every further row
   // (W or Wo of 1: ceil(2^32 / 1) does not fit the 32-bit multipliers of the kernel)
-  if (halo_bytes + row_bytes > budget || (long long)N * Ho > (1ll << 30) || W < 2 || Wo < 2) return pl;
-  const long long fit = (budget - halo_bytes) / row_bytes;
+  if (first > budget || (long long)N * Ho > (1ll << 30) || W < 2 || Wo < 2) return pl;
+  const long long fit = 1 + (budget - first) / more;
   const int BR = (int)(fit < Ho ? fit : Ho);
   pl.nbands = (int)cdiv(Ho, BR);
   pl.BR = (int)cdiv(Ho, pl.nbands);                                // bands of equal height
@@ -922,22 +926,22 @@ static ConvDwPlan plan_conv_dw(int N, int H, int W, int Ho, int Wo, int r, int p
   const long long total = (long long)N * pl.nbands;
   pl.cpb = (int)cdiv(total, 32);                                   // at most 32 partial spectra
   pl.nparts = (int)cdiv(total, pl.cpb);
-  pl.lds_bytes = size_t(4) * (dw_plane_stride(int((pl.BR + r - 1) * Wp)) + dw_plane_stride(pl.BR * Wo)) * sizeof(float2);
+  pl.lds_bytes = size_t(4) * (dw_plane_stride(int(((pl.BR - 1) * stride + r) * Wp)) + dw_plane_stride(pl.BR * Wo)) * sizeof(float2);
   if (pl.lds_bytes < 8192) pl.lds_bytes = 8192;                    // room for the sums over the four waves
   pl.lds = true;
   return pl;
 }
 
 size_t circ_conv_backward_workspace_bytes(int N, int C_in, int C_out, int H, int W, int r, int stride, int pad, int k) {
-  if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k) || stride != 1 || (r % 2) == 0) return 0;
-  const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
+  if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k) || stride < 1) return 0;
+  const int Ho = conv_out(H, r, pad, stride), Wo = conv_out(W, r, pad, stride);
   const int p = C_out / k, q = C_in / k;
   const size_t xa = align_up(spectrum_elems(k, (long long)q * N * H * W) * sizeof(float2), 256);
   const size_t ya = align_up(spectrum_elems(k, (long long)p * N * Ho * Wo) * sizeof(float2), 256);
   const long long npix = (long long)N * Ho * Wo;
   const size_t wa = align_up(spectrum_elems(k, (long long)r * r * p * q) * sizeof(float2), 256);
   (void)npix;
-  return xa + ya + wa * size_t(plan_conv_dw(N, H, W, Ho, Wo, r, pad).nparts);
+  return xa + ya + wa * size_t(plan_conv_dw(N, H, W, Ho, Wo, r, pad, stride).nparts);
 }
 
 }  // extern "C"
@@ -950,11 +954,10 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
                                void* workspace, size_t workspace_bytes, void* stream) {
   if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k)) return CIRC_EINVAL;
   if (stride <= 0) return CIRC_EINVAL;
-  if (stride != 1 || (r % 2) == 0) return CIRC_ENOTSUP;
   const bool want_dw = dw || w_upd;
   if (!w_hat || !dy || (!dx && !want_dw) || (want_dw && !x)) return CIRC_EINVAL;
   if (!aligned16(w_hat) || !aligned16(dy) || !aligned16(x) || !aligned16(dx) || !aligned16(dw)) return CIRC_EINVAL;
-  const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
+  const int Ho = conv_out(H, r, pad, stride), Wo = conv_out(W, r, pad, stride);
   const int p = C_out / k, q = C_in / k, NF = k / 2 + 1;
   // offsets inside one frequency of a spectrum are kept in 32 bits; grid.z holds tiles x offsets
   if ((long long)p * N * Ho * Wo > (1ll << 31) - 1 || (long long)r * r * cdiv(p, 4) * cdiv(q, 4) > 65535) return CIRC_EINVAL;
@@ -985,7 +988,7 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
 
   // backward-data: the fused forward kernel on the transposed grids when the shape allows it
   // (q output blocks, p input blocks, input image Ho x Wo, output image H x W, padding r-1-pad)
-  const bool dx_fused = dx && conv_fused_applicable(q, p, k, r, N, Ho, Wo, H, W);
+  const bool dx_fused = dx && stride == 1 && conv_fused_applicable(q, p, k, r, N, Ho, Wo, H, W);
   if (dx_fused) {
     if (launch_conv_fused(blob_at<float2>(w_hat, bl.conv_bwd), dy, nullptr, dx, N, q, p, k, r, Ho, Wo, H, W, r - 1 - pad, 0,
                           s) != hipSuccess)
@@ -1004,13 +1007,13 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
     const long long npix = (long long)N * HW;
     dim3 grid((unsigned)cdiv(npix, 256), (unsigned)NF, (unsigned)cdiv(q, IT));
     hipLaunchKernelGGL((conv_contract_kernel<IT>), grid, dim3(256), 0, s, blob_at<float2>(w_hat, bl.bwd), yh, xh, q, p,
-                       NF, N, Ho, Wo, H, W, r, r - 1 - pad, 1);
+                       NF, N, Ho, Wo, H, W, r, r - 1 - pad, 1, 1, stride);
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
     if (launch_irfft(k, true, xh, dx, mx, xrows, xrows, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
   }
   if (want_dw) {
     if (launch_rfft(k, true, x, xh, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
-    const ConvDwPlan dpl = plan_conv_dw(N, H, W, Ho, Wo, r, pad);
+    const ConvDwPlan dpl = plan_conv_dw(N, H, W, Ho, Wo, r, pad, stride);
     const long long npix = (long long)N * HWo, ppb = dpl.ppb;
     const int nchunks = dpl.nparts;
     const long long wrows = (long long)r * r * p * q;
@@ -1032,15 +1035,15 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
       dim3 grid((unsigned)dpl.nparts, (unsigned)NF, (unsigned)(cdiv(r * r, 16) * cdiv(p, 4) * cdiv(q, 4)));
       const unsigned mul_wo_b = (unsigned)(((1ll << 32) + Wo - 1) / Wo);   // pixel index inside a band / Wo
       hipLaunchKernelGGL(conv_dw_lds_kernel, grid, dim3(256), dpl.lds_bytes, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo, r,
-                         pad, dpl.BR, dpl.nbands, dpl.cpb, wstride, mul_wo_b, mul_w);
+                         pad, dpl.BR, dpl.nbands, dpl.cpb, wstride, mul_wo_b, mul_w, stride);
     } else if (r % CIRC_DW_NG == 0) {   // CIRC_DW_NG consecutive offsets per block (for r = 3: one filter row)
       dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r / CIRC_DW_NG * cdiv(p, 4) * cdiv(q, 4)));
       hipLaunchKernelGGL((conv_dw_mfma_kernel<CIRC_DW_NG>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo,
-                         r, pad, ppb, wstride, mul_hwo, mul_wo);
+                         r, pad, ppb, wstride, mul_hwo, mul_wo, stride);
     } else {            // one offset per block
       dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r * cdiv(p, 4) * cdiv(q, 4)));
       hipLaunchKernelGGL((conv_dw_mfma_kernel<1>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo, r, pad,
-                         ppb, wstride, mul_hwo, mul_wo);
+                         ppb, wstride, mul_hwo, mul_wo, stride);
     }
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
     // many partial spectra are folded into the first one by a launch of their own (one thread per

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void conv_dw_mfma_kernel(const float2* __restr
                                                            float2* __restrict__ part, int p, int q, int NF, int Nimg,
                                                            int H, int W, int Ho, int Wo, int r, int pad,
                                                            long long pix_per_block, long long part_stride,
-                                                           unsigned mul_hwo, unsigned mul_wo) {
+                                                           unsigned mul_hwo, unsigned mul_wo, int stride) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, f = blockIdx.y;
   const int blk = lane >> 2, sub = lane & 3;
   const int nit = (p + 3) / 4, njt = (q + 3) / 4;
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void conv_dw_mfma_kernel(const float2* __restr
       const unsigned xbase = jrow + n * HW;
 #pragma unroll
       for (int g = 0; g < NG; ++g) {
-        const int hi = ho + goff_h[g], wi = wo + goff_w[g];
+        const int hi = ho * stride + goff_h[g], wi = wo * stride + goff_w[g];
         // positions outside the image (and offsets past r*r) read a clamped address and count as zero
         const bool inb = gok[g] && unsigned(hi) < unsigned(H) && unsigned(wi) < unsigned(W);
         xv[u][g] = xf[xbase + unsigned(min(max(hi, 0), H - 1)) * unsigned(W) + unsigned(min(max(wi, 0), W - 1))];
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256) void conv_dw_mfma_kernel(const float2* __restr
 // dY^, and walks over cpb consecutive (image, band) chunks with the same accumulators.
 // Block (x = group of cpb chunks, y = frequency, z = (group of 16 offsets, tile of 4 i, tile of
 // 4 j)); output part[x][f][(g*p + i)*q + j] as above.
-// Dynamic LDS: 4 * (stride((BR + r - 1) * (W + 2*pad)) + stride(BR*Wo)) float2, stride() as below
+// Dynamic LDS: 4 * (S(((BR - 1)*stride + r) * (W + 2*pad)) + S(BR*Wo)) float2, S() = dw_plane_stride
 // (at least 2048 floats).
 // mul_wo, mul_w: ceil(2^32 / Wo), ceil(2^32 / W): exact division of indices inside a band.
 // Plane stride (in float2) for n elements per plane: the next value that is 4 modulo 16, so that the
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restri
                                                           float2* __restrict__ part, int p, int q, int NF, int Nimg,
                                                           int H, int W, int Ho, int Wo, int r, int pad, int BR,
                                                           int nbands, int cpb, long long part_stride, unsigned mul_wo,
-                                                          unsigned mul_w) {
+                                                          unsigned mul_w, int stride) {
   extern __shared__ float2 xs[];                  // [4 input blocks][rows_in][Wp], then [4 output blocks][BR*Wo]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), f = blockIdx.y;
   const int blk = lane >> 2, sub = lane & 3;
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restri
   const int g0 = (z / nit) * 16;
   const int i0 = it * 4, j0 = jt * 4;
   const int Wp = W + 2 * pad;
-  const int rows_in = BR + r - 1, plane = rows_in * W;
+  const int rows_in = (BR - 1) * stride + r, plane = rows_in * W;   // input rows under a band of BR output rows
   const int planep = dw_plane_stride(rows_in * Wp), dplane = dw_plane_stride(BR * Wo);
   float2* dys = xs + 4 * planep;
   const unsigned HW = unsigned(H) * unsigned(W), HWo = unsigned(Ho) * unsigned(Wo);
@@ -217,10 +217,10 @@ __global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restri
     const int ho0 = band * BR, brc = min(BR, Ho - ho0), npx = brc * Wo;
     __syncthreads();                              // the previous chunk has been read by every wave (first pass: zeros written)
     // The staged rows are whole image rows, so the band of one input block is one contiguous run
-    // of the image: staged element t = (row, column) is image element (ho0 - pad)*W + t, or zero
+    // of the image: staged element t = (row, column) is image element (ho0*stride - pad)*W + t, or zero
     // outside the image.  The four blocks are fetched together (four independent loads per step).
     {
-      const int e0 = (ho0 - pad) * W;
+      const int e0 = (ho0 * stride - pad) * W;
       const float2* src[4];
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj)
@@ -260,9 +260,9 @@ __global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restri
       accR[e] = __builtin_amdgcn_mfma_f32_4x4x1f32(dv.y, xv.y, accR[e], 0, 0, 0);
       accI[e] = __builtin_amdgcn_mfma_f32_4x4x1f32(-dv.x, xv.y, accI[e], 0, 0, 0);
     };
-    auto tap = [&](int pix) -> int {              // staged element of output pixel pix, offset (0, 0): hl*Wp + wo
+    auto tap = [&](int pix) -> int {              // staged element of output pixel pix, offset (0, 0): stride*(hl*Wp + wo)
       const int hl = int(__umulhi(unsigned(pix), mul_wo));
-      return pix + hl * (Wp - Wo);
+      return stride * (pix + hl * (Wp - Wo));
     };
     int pix = wave;
     for (; pix + 12 < npx; pix += 16) {

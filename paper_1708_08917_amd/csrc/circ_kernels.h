@@ -394,15 +394,18 @@ __global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
 // -------------------------------------------------------------------------------------
 // CONV contraction, one thread per (frequency, image, output pixel), IT output channel
 // blocks at a time:
-//   Yh[f][i][n][ho][wo] = sum_{dh,dw,j} What[dh*r+dw][f][j][i] * Xh[f][j][n][ho+dh-pad][wo+dw-pad]
+//   Yh[f][i][n][ho][wo] = sum_{dh,dw,j} What[dh*r+dw][f][j][i] * Xh[f][j][n][ho*stride+dh-pad][wo*stride+dw-pad]
 // with zero spectra outside the image (the channel FFT of a zero pixel is zero, so the
 // spatial shift is taken after the transform and every input pixel is transformed once).
 // flip: offset (dh, dw) takes the weights of offset (r-1-dh, r-1-dw) - the reflected filter of
 // backward-data, whose operand is the conjugated, transposed section and whose padding is r-1-pad.
+// stride: the filter moves `stride` input pixels per output pixel (tap = ho*stride + dh - pad).
+// dil: the input grid is the H x W one with dil-1 zeros inserted between its pixels (a tap u
+// reads input pixel u/dil when dil divides u, zero otherwise) - backward-data of a strided layer.
 template <int IT>
 __global__ void conv_contract_kernel(const float2* __restrict__ What, const float2* __restrict__ Xh,
                                      float2* __restrict__ Yh, int p, int q, int NF, int Nimg, int H,
-                                     int W, int Ho, int Wo, int r, int pad, int flip) {
+                                     int W, int Ho, int Wo, int r, int pad, int flip, int stride, int dil) {
   const long long npix = (long long)Nimg * Ho * Wo;
   const long long opix = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (opix >= npix) return;
@@ -414,8 +417,14 @@ __global__ void conv_contract_kernel(const float2* __restrict__ What, const floa
   for (int ii = 0; ii < IT; ++ii) acc[ii] = make_float2(0.f, 0.f);
   for (int dh = 0; dh < r; ++dh) {
     for (int dw = 0; dw < r; ++dw) {
-      const int hi = ho + dh - pad, wi = wo + dw - pad;
-      const bool inb = hi >= 0 && hi < H && wi >= 0 && wi < W;
+      int hi = ho * stride + dh - pad, wi = wo * stride + dw - pad;
+      bool inb = hi >= 0 && wi >= 0;
+      if (dil > 1) {
+        inb = inb && hi % dil == 0 && wi % dil == 0;
+        hi /= dil;
+        wi /= dil;
+      }
+      inb = inb && hi < H && wi < W;
       const int g = flip ? r * r - 1 - (dh * r + dw) : dh * r + dw;
       const float2* wg = What + ((long long)g * NF + f) * q * p;
       for (int j = 0; j < q; ++j) {

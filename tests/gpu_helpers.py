@@ -31,19 +31,19 @@ def gpu_fc_backward(w, x, dy, need_dx=True, need_dw=True):
     return (None if dx is None else dx.cpu().numpy()), (None if dw is None else dw.cpu().numpy())
 
 
-def gpu_conv_forward(w, x, bias=None, relu=False, pad=0):
+def gpu_conv_forward(w, x, bias=None, relu=False, pad=0, stride=1):
     r, _, p, q, k = w.shape
     wh = B.circ_precompute_spectra(dev(w))
-    y = B.circ_conv_forward(wh, dev(x), dev(bias), None, p * k, r, 1, pad, k, epi_flags(bias, relu))
+    y = B.circ_conv_forward(wh, dev(x), dev(bias), None, p * k, r, stride, pad, k, epi_flags(bias, relu))
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
 
-def gpu_conv_backward(w, x, dy, pad=0, need_dx=True, need_dw=True):
+def gpu_conv_backward(w, x, dy, pad=0, need_dx=True, need_dw=True, stride=1):
     r, _, p, q, k = w.shape
     N, C_in, H, W = x.shape
     wh = B.circ_precompute_spectra(dev(w))
-    dx, dw = B.circ_conv_backward(wh, dev(x), dev(dy), C_in, H, W, r, 1, pad, k, need_dx, need_dw)
+    dx, dw = B.circ_conv_backward(wh, dev(x), dev(dy), C_in, H, W, r, stride, pad, k, need_dx, need_dw)
     torch.cuda.synchronize()
     return (None if dx is None else dx.cpu().numpy()), (None if dw is None else dw.cpu().numpy())
 
@@ -68,13 +68,13 @@ def gpu_fc_sgd_steps(w, batches, lr, need_dx=False):
     return w_new, wh, dxs
 
 
-def gpu_conv_sgd_steps(w, batches, lr, pad, need_dx=False):
+def gpu_conv_sgd_steps(w, batches, lr, pad, need_dx=False, stride=1):
     r, _, p, q, k = w.shape
     wh = B.circ_precompute_spectra(dev(w.astype(np.float32)))
     dxs = []
     for x, dy in batches:
         _, C_in, H, W = x.shape
-        dx = B.circ_conv_sgd_step(wh, dev(x.astype(np.float32)), dev(dy.astype(np.float32)), lr, C_in, H, W, r, 1, pad, k,
+        dx = B.circ_conv_sgd_step(wh, dev(x.astype(np.float32)), dev(dy.astype(np.float32)), lr, C_in, H, W, r, stride, pad, k,
                                   need_dx=need_dx)
         dxs.append(None if dx is None else dx.cpu().numpy())
     w_new = B.circ_export_weights(wh, r * r, p, q, k).cpu().numpy().reshape(w.shape)

@@ -60,7 +60,8 @@ def test_workspace_bytes():
     assert B.circ_fc_workspace_bytes(64, 64, 48, 64) == 2 * 25 * 64 * 64 * 8      # any 1 <= k <= 512
     assert B.circ_fc_workspace_bytes(64, 64, 600, 64) == 0
     assert B.circ_conv_workspace_bytes(32, 256, 256, 28, 28, 3, 1, 1, 64) == 2 * F * 4 * 32 * 784 * 8
-    assert B.circ_conv_workspace_bytes(32, 256, 256, 28, 28, 3, 2, 1, 64) == 0
+    assert B.circ_conv_workspace_bytes(32, 256, 256, 28, 28, 3, 2, 1, 64) == F * 4 * 32 * (784 + 196) * 8    # stride 2: 14 x 14 outputs
+    assert B.circ_conv_workspace_bytes(32, 256, 256, 28, 28, 3, 0, 1, 64) == 0
     assert B.circ_conv_workspace_bytes(32, 250, 256, 28, 28, 3, 1, 1, 64) == 0
 
 
@@ -118,8 +119,10 @@ def test_conv_argument_errors():
 
     assert call(C_in=6) == B.CIRC_EINVAL                      # k does not divide C_in
     assert call(k=1024, C_in=1024, C_out=1024) == B.CIRC_EINVAL
-    assert call(stride=2) == B.CIRC_ENOTSUP
-    assert call(r=2) == B.CIRC_ENOTSUP
+    assert call(stride=0) == B.CIRC_EINVAL
+    assert call(stride=-2) == B.CIRC_EINVAL
+    assert call(r=0) == B.CIRC_EINVAL
+    assert call(r=7) == B.CIRC_EINVAL                         # filter larger than the padded image
     assert call(pad=3) == B.CIRC_EINVAL
     assert call(x=None) == B.CIRC_EINVAL
     assert call(wsb=8) == B.CIRC_EWORKSPACE
@@ -134,8 +137,8 @@ def test_conv_backward_argument_errors():
         return f(w_hat, x, dy, dx, dw, N, C_in, C_out, H, W, r, stride, pad, k, wsp, wsb, None)
 
     assert call(C_out=6) == B.CIRC_EINVAL                     # k does not divide C_out
-    assert call(stride=2) == B.CIRC_ENOTSUP
-    assert call(r=4) == B.CIRC_ENOTSUP
+    assert call(stride=0) == B.CIRC_EINVAL
+    assert call(r=0) == B.CIRC_EINVAL
     assert call(pad=3) == B.CIRC_EINVAL
     assert call(N=0) == B.CIRC_EINVAL                         # empty batch
     assert call(dy=None) == B.CIRC_EINVAL
@@ -148,7 +151,8 @@ def test_conv_backward_argument_errors():
     assert call(wsp=None) == B.CIRC_EWORKSPACE
     wb = B.circ_conv_backward_workspace_bytes
     assert wb(1, 8, 8, 4, 4, 3, 1, 1, 4) > B.circ_conv_workspace_bytes(1, 8, 8, 4, 4, 3, 1, 1, 4)
-    assert wb(1, 8, 8, 4, 4, 3, 2, 1, 4) == 0 and wb(1, 6, 8, 4, 4, 3, 1, 1, 4) == 0
+    assert wb(1, 8, 8, 4, 4, 3, 0, 1, 4) == 0 and wb(1, 6, 8, 4, 4, 3, 1, 1, 4) == 0
+    assert 0 < wb(1, 8, 8, 4, 4, 3, 2, 1, 4) < wb(1, 8, 8, 4, 4, 3, 1, 1, 4)    # stride 2: fewer output pixels
 
 
 def test_sgd_step_and_export_argument_errors():
@@ -176,7 +180,7 @@ def test_sgd_step_and_export_argument_errors():
 
     assert callc(w_hat=None) == B.CIRC_EINVAL
     assert callc(lr=float("nan")) == B.CIRC_EINVAL
-    assert callc(stride=2) == B.CIRC_ENOTSUP
+    assert callc(stride=0) == B.CIRC_EINVAL
     assert callc(x=None) == B.CIRC_EINVAL
     assert callc(dy=A + 512) == B.CIRC_EINVAL                 # dy lies inside the blob
     assert callc(wsb=64) == B.CIRC_EWORKSPACE

@@ -399,6 +399,29 @@ def test_fc_forward_f16_configs(cfg):
     check_half(got[:, sel], ref, f"{cfg} block rows {rows}")
 
 
+# ---- stride > 1 and even filter sizes (Eq. 6 is the stride-1 case) ---------------------------
+@pytest.mark.parametrize("N,p,q,k,H,W,r,pad,stride", [
+    (2, 2, 3, 8, 9, 8, 3, 1, 2), (3, 1, 2, 16, 7, 7, 3, 0, 2), (2, 4, 4, 64, 28, 28, 3, 1, 2), (2, 2, 2, 64, 13, 12, 3, 1, 3),
+    (1, 3, 2, 4, 11, 9, 5, 2, 2), (2, 2, 2, 32, 8, 8, 2, 0, 2), (2, 3, 1, 8, 9, 10, 4, 1, 2), (3, 2, 2, 16, 6, 6, 2, 1, 1),
+    (2, 2, 3, 12, 10, 7, 3, 1, 2), (33, 2, 2, 64, 14, 14, 3, 1, 2), (2, 2, 2, 8, 5, 300, 3, 1, 2), (2, 1, 1, 8, 6, 1, 1, 0, 1)])
+def test_conv_strided_and_even_filters(N, p, q, k, H, W, r, pad, stride):
+    w = (RNG.standard_normal((r, r, p, q, k)) / np.sqrt(r * r * q * k)).astype(np.float32)
+    x = RNG.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32)
+    b = (0.1 * RNG.standard_normal(p * k)).astype(np.float32)
+    Ho, Wo = (H + 2 * pad - r) // stride + 1, (W + 2 * pad - r) // stride + 1
+    dy = RNG.uniform(-1, 1, (N, p * k, Ho, Wo)).astype(np.float32)
+    what = f"N={N} {p}x{q} k={k} {H}x{W} r={r} pad={pad} stride={stride}"
+    y = G.gpu_conv_forward(w, x, b, True, pad, stride)
+    assert y.shape == (N, p * k, Ho, Wo)
+    check(y, O.conv_forward(w, x, b, True, pad, stride), "conv fwd " + what)
+    dx, dw = G.gpu_conv_backward(w, x, dy, pad, stride=stride)
+    check(dx, O.conv_backward_dx(w, dy, H, W, pad, stride), "conv dx " + what)
+    check(dw, O.conv_backward_dw(x, dy, k, r, pad, stride), "conv dw " + what)
+    lr = _step_size(w, O.conv_backward_dw(x, dy, k, r, pad, stride))
+    got, _, _ = G.gpu_conv_sgd_steps(w, [(x, dy)], lr, pad, stride=stride)
+    check(got, O.conv_sgd_step(w, x, dy, lr, pad, stride), "conv sgd w " + what)
+
+
 # ---- block sizes that are not powers of two (direct transforms around the same contraction) ----
 @pytest.mark.parametrize("k", [1, 3, 5, 6, 7, 12, 24, 40, 96, 100, 125, 250, 384, 511])
 @pytest.mark.parametrize("batch", [1, 2, 33])

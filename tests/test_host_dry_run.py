@@ -45,6 +45,9 @@ DRIVER = textwrap.dedent(r'''
         assert L.circ_conv_forward(P[0], P[1], None, P[2], N, Ci, Co, H, W, r, 1, pad, k, 0, P[3], ws, None) == 0
         assert L.circ_conv_backward(P[0], P[1], P[2], P[3], P[4], N, Ci, Co, H, W, r, 1, pad, k, P[5], ws, None) == 0
         assert L.circ_conv_sgd_step(P[0], P[1], P[2], None, c_f(0.1), N, Ci, Co, H, W, r, 1, pad, k, P[5], ws, None) == 0
+        for st in (2, 3):
+            assert L.circ_conv_forward(P[0], P[1], None, P[2], N, Ci, Co, H, W, r, st, pad, k, 0, P[3], ws, None) == 0
+            assert L.circ_conv_backward(P[0], P[1], P[2], P[3], P[4], N, Ci, Co, H, W, r, st, pad, k, P[5], ws, None) == 0
     assert L.circ_bias_grad(P[0], P[1], c_ll(32), 256, c_ll(784), None) == 0
     # random shapes, valid or not: only the absence of a trap counts
     rng = random.Random(1708)
@@ -65,13 +68,13 @@ DRIVER = textwrap.dedent(r'''
         L.circ_fc_sgd_step(P[0], P[1], P[2], None, c_f(0.1), p, q, k, b, P[5], ws, None)
         L.circ_export_weights(P[0], rng.choice([1, 9, 25]), p, q, k, P[1], None)
         N, H, W = rng.choice([1, 2, 3, 32, 33, 256, 0]), rng.choice([1, 2, 5, 13, 14, 28, 56, 224, 1024, 0]), rng.choice([1, 2, 4, 5, 13, 14, 28, 56, 224, 1024, 4000])
-        r, pad = rng.choice([1, 3, 5, 7, 9, 2, 0]), rng.choice([0, 1, 2, 3, 4])
+        r, pad, st = rng.choice([1, 3, 5, 7, 9, 2, 4, 0]), rng.choice([0, 1, 2, 3, 4]), rng.choice([1, 1, 2, 3, 0])
         Ci = min(max(q, 1) * max(k, 1), 1 << 20); Co = min(max(p, 1) * max(k, 1), 1 << 20)
-        L.circ_conv_workspace_bytes(N, Ci, Co, H, W, r, 1, pad, k); L.circ_conv_backward_workspace_bytes(N, Ci, Co, H, W, r, 1, pad, k)
-        L.circ_conv_forward(P[0], P[1], None, P[2], N, Ci, Co, H, W, r, 1, pad, k, 0, P[3], ws, None)
-        L.circ_conv_backward(P[0], P[1], P[2], P[3], P[4], N, Ci, Co, H, W, r, 1, pad, k, P[5], ws, None)
-        L.circ_conv_backward(P[0], P[1], P[2], None, P[4], N, Ci, Co, H, W, r, 1, pad, k, P[5], ws, None)
-        L.circ_conv_sgd_step(P[0], P[1], P[2], None, c_f(0.1), N, Ci, Co, H, W, r, 1, pad, k, P[5], ws, None)
+        L.circ_conv_workspace_bytes(N, Ci, Co, H, W, r, st, pad, k); L.circ_conv_backward_workspace_bytes(N, Ci, Co, H, W, r, st, pad, k)
+        L.circ_conv_forward(P[0], P[1], None, P[2], N, Ci, Co, H, W, r, st, pad, k, 0, P[3], ws, None)
+        L.circ_conv_backward(P[0], P[1], P[2], P[3], P[4], N, Ci, Co, H, W, r, st, pad, k, P[5], ws, None)
+        L.circ_conv_backward(P[0], P[1], P[2], None, P[4], N, Ci, Co, H, W, r, st, pad, k, P[5], ws, None)
+        L.circ_conv_sgd_step(P[0], P[1], P[2], None, c_f(0.1), N, Ci, Co, H, W, r, st, pad, k, P[5], ws, None)
         L.circ_bias_grad(P[0], P[1], c_ll(rng.choice([1, 32, 0, 1 << 40])), rng.choice([1, 256, 0]), c_ll(rng.choice([1, 784, 0])), None)
     print("dry run ok")
 ''')
