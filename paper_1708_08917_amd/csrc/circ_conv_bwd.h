@@ -5,9 +5,11 @@
 // gives, per frequency f,
 //   dX^[f][j][n][hi][wi] = sum_{dh,dw,i} conj(W^[dh][dw][f][i][j]) dY^[f][i][n][hi-dh+pad][wi-dw+pad]
 //   dW^[dh][dw][f][i][j] = sum_{n,ho,wo} dY^[f][i][n][ho][wo] conj(X^[f][j][n][ho+dh-pad][wo+dw-pad])
-// (zero outside the image).  The first is the forward contraction with the conjugated,
-// transposed operand, the offsets reflected and the padding r-1-pad, so it runs on
-// conv_contract_kernel; the second is a reduction over all output pixels (kernel below).
+// (zero outside the image; written for stride 1 - with stride s the output pixel (ho, wo) pairs
+// with the input pixel (ho*s+dh-pad, wo*s+dw-pad)).  The first is the forward contraction with the
+// conjugated, transposed operand, the offsets reflected and the padding r-1-pad (for s > 1 on the
+// output gradient with s-1 zeros between its pixels), so it runs on conv_contract_kernel; the
+// second is a reduction over all output pixels (kernels below).
 // The bias gradient of Eq. 1 (a = Wx + theta) is dL/da summed over everything but the channel.
 #pragma once
 

@@ -6,6 +6,8 @@
 //   conv_contract_kernel  the same contraction for CONV: sum over the r*r offsets and
 //                    the input channel blocks (Eq. 6 / Eq. 7)
 //   irfft_kernel     half spectra -> real rows, fused bias + ReLU (Eq. 1)
+// The two transform kernels can also read or write IEEE fp16 (rows and / or spectra, HMODE) for
+// the half-width storage route; their arithmetic stays fp32.
 #pragma once
 
 #include <hip/hip_runtime.h>
