@@ -206,6 +206,19 @@ circ_status circ_fc_forward_f16(const void* w_hat, const void* x, const float* b
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same with bfloat16 (the upper 16 bits of an fp32, rounded to nearest even) as the storage
+ * format: the range of fp32, so no bound on |x| * k, at 2^-8 per rounding instead of 2^-11
+ * (about 5e-3 of the largest output).  A blob made by circ_precompute_spectra_bf16 serves
+ * circ_fc_forward_bf16 only.
+ */
+size_t circ_spectra_bytes_bf16(int p, int q, int k);
+circ_status circ_precompute_spectra_bf16(const float* w, int p, int q, int k, void* w_hat, void* stream);
+size_t circ_fc_workspace_bytes_bf16(int p, int q, int k, int batch);
+circ_status circ_fc_forward_bf16(const void* w_hat, const void* x, const float* bias, void* y,
+                                 int p, int q, int k, int batch, int epilogue,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Bias gradient (Eq. 1: a = Wx + theta, so dL/dtheta is dL/da summed over everything but the
  * channel).  dy is viewed as [outer][channels][inner]:
  *   db[c] = sum_{o, t} dy[(o*channels + c)*inner + t]

@@ -43,6 +43,11 @@ SIGNATURES = {
     "circ_fc_workspace_bytes_f16": (_c_size, [_c_int] * 4),
     "circ_fc_forward_f16": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_int, _c_int, _c_int, _c_int, _c_int,
                                      _c_ptr, _c_size, _c_ptr]),
+    "circ_spectra_bytes_bf16": (_c_size, [_c_int] * 3),
+    "circ_precompute_spectra_bf16": (_c_int, [_c_ptr, _c_int, _c_int, _c_int, _c_ptr, _c_ptr]),
+    "circ_fc_workspace_bytes_bf16": (_c_size, [_c_int] * 4),
+    "circ_fc_forward_bf16": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_int, _c_int, _c_int, _c_int, _c_int,
+                                      _c_ptr, _c_size, _c_ptr]),
 }
 
 
@@ -208,33 +213,42 @@ def circ_export_weights(w_hat, n_grids, p, q, k, w=None):
     return w
 
 
-def circ_precompute_spectra_f16(w: torch.Tensor, w_hat: torch.Tensor | None = None) -> torch.Tensor:
-    """w: device fp32 [p][q][k] -> opaque fp16 spectra blob (uint8 tensor)."""
+def _half_suffix(dtype) -> str:
+    assert dtype in (torch.float16, torch.bfloat16)
+    return "f16" if dtype == torch.float16 else "bf16"
+
+
+def circ_precompute_spectra_f16(w: torch.Tensor, w_hat: torch.Tensor | None = None, dtype=torch.float16) -> torch.Tensor:
+    """w: device fp32 [p][q][k] -> opaque 16-bit spectra blob (uint8 tensor) in `dtype` (fp16 or bf16)."""
     assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and w.dim() == 3
     p, q, k = w.shape
-    nbytes = lib().circ_spectra_bytes_f16(p, q, k)
+    sfx = _half_suffix(dtype)
+    nbytes = getattr(lib(), f"circ_spectra_bytes_{sfx}")(p, q, k)
     if nbytes == 0:
-        raise CircError(CIRC_EINVAL, "circ_spectra_bytes_f16")
+        raise CircError(CIRC_EINVAL, f"circ_spectra_bytes_{sfx}")
     if w_hat is None:
         w_hat = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
-    _check(lib().circ_precompute_spectra_f16(_ptr(w), p, q, k, _ptr(w_hat), _stream()), "circ_precompute_spectra_f16")
+    _check(getattr(lib(), f"circ_precompute_spectra_{sfx}")(_ptr(w), p, q, k, _ptr(w_hat), _stream()),
+           f"circ_precompute_spectra_{sfx}")
     return w_hat
 
 
 def circ_fc_workspace_bytes_f16(p, q, k, batch) -> int:
-    return lib().circ_fc_workspace_bytes_f16(p, q, k, batch)
+    return lib().circ_fc_workspace_bytes_f16(p, q, k, batch)      # the same for both 16-bit formats
 
 
 def circ_fc_forward_f16(w_hat, x, bias, y, p, q, k, epilogue=EPI_NONE, workspace=None):
-    """x: fp16 [batch][q*k] -> y: fp16 [batch][p*k] (allocated if None); bias fp32.  Returns y."""
-    assert x.dtype == torch.float16 and x.is_contiguous()
+    """x: fp16 or bf16 [batch][q*k] -> y of the same type [batch][p*k] (allocated if None); bias fp32.
+    The blob must come from circ_precompute_spectra_f16 with the same dtype.  Returns y."""
+    sfx = _half_suffix(x.dtype)
+    assert x.is_contiguous()
     batch = x.shape[0]
     if y is None:
-        y = torch.empty(batch, p * k, dtype=torch.float16, device=x.device)
+        y = torch.empty(batch, p * k, dtype=x.dtype, device=x.device)
     if workspace is None:
         workspace = torch.empty(max(1, circ_fc_workspace_bytes_f16(p, q, k, batch)), dtype=torch.uint8, device=x.device)
-    _check(lib().circ_fc_forward_f16(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), p, q, k, batch, epilogue,
-                                     _ptr(workspace), workspace.numel(), _stream()), "circ_fc_forward_f16")
+    _check(getattr(lib(), f"circ_fc_forward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), p, q, k, batch, epilogue,
+                                                    _ptr(workspace), workspace.numel(), _stream()), f"circ_fc_forward_{sfx}")
     return y
 
 

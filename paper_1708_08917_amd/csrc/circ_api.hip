@@ -377,7 +377,10 @@ inline int gemv_splits(int p, int q, int k) {
 #ifndef CIRC_GEMV_MAXWG
 #define CIRC_GEMV_MAXWG 256
 #endif
-  if ((long long)q * k < 8192 || p * 2 > CIRC_GEMV_MAXWG) return 1;
+#ifndef CIRC_GEMV_SPLIT_MIN
+#define CIRC_GEMV_SPLIT_MIN 8192
+#endif
+  if ((long long)q * k < CIRC_GEMV_SPLIT_MIN || p * 2 > CIRC_GEMV_MAXWG) return 1;
   int ns = 1;
   while (ns < 16 && p * ns * 2 <= CIRC_GEMV_MAXWG && q / (ns * 2) >= 8) ns *= 2;
   return ns;
@@ -1101,34 +1104,46 @@ circ_status circ_bias_grad(const float* dy, float* db, long long outer, int chan
 
 }  // extern "C"
 
-// ---- half-width storage (fp16 in memory, fp32 arithmetic): FC forward -----------------------
+// ---- half-width storage (16-bit values in memory, fp32 arithmetic): FC forward ---------------
 namespace {
 
 inline bool half_k(int k) { return is_pow2(k) && k >= 8 && k <= kMaxK; }
 
+// hmode: kHalfSpectra (fp32 rows in) or kHalfSpectra | kHalfRows; bf: bfloat16 instead of fp16
 template <int K>
-hipError_t launch_rfft_half_k(int hmode, const void* in, void* out, const RowMap& map, long long nrows,
+hipError_t launch_rfft_half_k(int hmode, bool bf, const void* in, void* out, const RowMap& map, long long nrows,
                               long long out_fstride, float scale, hipStream_t s) {
   FftPlan pl = plan_fft(K, nrows);
   dim3 grid((unsigned)cdiv(nrows, 2 * pl.P), 1);
   const float* fin = static_cast<const float*>(in);
   float2* fout = static_cast<float2*>(out);
-  if (hmode == kHalfSpectra)
-    hipLaunchKernelGGL((rfft_kernel<K, false, kHalfSpectra>), grid, dim3(pl.NT), pl.lds, s, fin, fout, map, nrows,
-                       out_fstride, 0ll, 0ll, pl.P, scale, 0);
-  else
-    hipLaunchKernelGGL((rfft_kernel<K, false, kHalfSpectra | kHalfRows>), grid, dim3(pl.NT), pl.lds, s, fin, fout, map,
-                       nrows, out_fstride, 0ll, 0ll, pl.P, scale, 0);
+#define CIRC_RFFT_H(MODE)                                                                                              \
+  hipLaunchKernelGGL((rfft_kernel<K, false, MODE>), grid, dim3(pl.NT), pl.lds, s, fin, fout, map, nrows, out_fstride, 0ll, \
+                     0ll, pl.P, scale, 0)
+  if (hmode == kHalfSpectra) {
+    if (bf) CIRC_RFFT_H(kHalfSpectra | kHalfBf16);
+    else CIRC_RFFT_H(kHalfSpectra);
+  } else {
+    if (bf) CIRC_RFFT_H(kHalfSpectra | kHalfRows | kHalfBf16);
+    else CIRC_RFFT_H(kHalfSpectra | kHalfRows);
+  }
+#undef CIRC_RFFT_H
   return hipGetLastError();
 }
 
 template <int K>
-hipError_t launch_irfft_half_k(const void* in, void* out, const RowMap& map, long long nrows, long long in_fstride,
+hipError_t launch_irfft_half_k(bool bf, const void* in, void* out, const RowMap& map, long long nrows, long long in_fstride,
                                float scale, const float* bias, long long bias_div, int relu, hipStream_t s) {
   FftPlan pl = plan_fft(K, nrows);
-  hipLaunchKernelGGL((irfft_kernel<K, false, kHalfSpectra | kHalfRows>), dim3((unsigned)cdiv(nrows, 2 * pl.P)), dim3(pl.NT),
-                     pl.lds, s, static_cast<const float2*>(in), static_cast<float*>(out), map, nrows, in_fstride, pl.P,
-                     scale, bias, bias_div, relu, 1, 0ll);
+  dim3 grid((unsigned)cdiv(nrows, 2 * pl.P));
+  const float2* fin = static_cast<const float2*>(in);
+  float* fout = static_cast<float*>(out);
+  if (bf)
+    hipLaunchKernelGGL((irfft_kernel<K, false, kHalfSpectra | kHalfRows | kHalfBf16>), grid, dim3(pl.NT), pl.lds, s, fin, fout,
+                       map, nrows, in_fstride, pl.P, scale, bias, bias_div, relu, 1, 0ll);
+  else
+    hipLaunchKernelGGL((irfft_kernel<K, false, kHalfSpectra | kHalfRows>), grid, dim3(pl.NT), pl.lds, s, fin, fout, map, nrows,
+                       in_fstride, pl.P, scale, bias, bias_div, relu, 1, 0ll);
   return hipGetLastError();
 }
 
@@ -1144,52 +1159,49 @@ hipError_t launch_irfft_half_k(const void* in, void* out, const RowMap& map, lon
     default: return hipErrorInvalidValue; \
   }
 
-hipError_t launch_rfft_half(int k, int hmode, const void* in, void* out, const RowMap& map, long long nrows,
+hipError_t launch_rfft_half(int k, int hmode, bool bf, const void* in, void* out, const RowMap& map, long long nrows,
                             long long out_fstride, float scale, hipStream_t s) {
-#define CALL(KK) launch_rfft_half_k<KK>(hmode, in, out, map, nrows, out_fstride, scale, s)
+#define CALL(KK) launch_rfft_half_k<KK>(hmode, bf, in, out, map, nrows, out_fstride, scale, s)
   CIRC_DISPATCH_HALF_K(k, CALL)
 #undef CALL
 }
 
-hipError_t launch_irfft_half(int k, const void* in, void* out, const RowMap& map, long long nrows, long long in_fstride,
-                             float scale, const float* bias, long long bias_div, int relu, hipStream_t s) {
-#define CALL(KK) launch_irfft_half_k<KK>(in, out, map, nrows, in_fstride, scale, bias, bias_div, relu, s)
+hipError_t launch_irfft_half(int k, bool bf, const void* in, void* out, const RowMap& map, long long nrows,
+                             long long in_fstride, float scale, const float* bias, long long bias_div, int relu,
+                             hipStream_t s) {
+#define CALL(KK) launch_irfft_half_k<KK>(bf, in, out, map, nrows, in_fstride, scale, bias, bias_div, relu, s)
   CIRC_DISPATCH_HALF_K(k, CALL)
 #undef CALL
 }
 
 inline size_t half_spectrum_bytes(int k, long long rows) { return align_up(size_t(k / 2 + 1) * size_t(rows) * sizeof(__half2), 256); }
 
-}  // namespace
-
-extern "C" {
-
-size_t circ_spectra_bytes_f16(int p, int q, int k) {
+size_t spectra_bytes_half(int p, int q, int k) {
   if (p <= 0 || q <= 0 || !half_k(k) || (long long)p * q > (1ll << 31) - 1) return 0;
   return half_spectrum_bytes(k, (long long)p * q);
 }
 
-circ_status circ_precompute_spectra_f16(const float* w, int p, int q, int k, void* w_hat, void* stream) {
+circ_status precompute_spectra_half(bool bf, const float* w, int p, int q, int k, void* w_hat, void* stream) {
   if (!w || !w_hat || p <= 0 || q <= 0 || !half_k(k)) return CIRC_EINVAL;
   if ((long long)p * q > (1ll << 31) - 1) return CIRC_EINVAL;
   if (!aligned16(w) || !aligned16(w_hat)) return CIRC_EINVAL;
-  if (overlaps(w, size_t(p) * q * k * sizeof(float), w_hat, circ_spectra_bytes_f16(p, q, k))) return CIRC_EINVAL;
+  if (overlaps(w, size_t(p) * q * k * sizeof(float), w_hat, spectra_bytes_half(p, q, k))) return CIRC_EINVAL;
   const long long rows = (long long)p * q;
   // W^[f][i][j] = FFT(w_ij)[f], not normalised (the 1/k is applied after the contraction, in fp32):
   // row id = i*q + j -> w[i][j][:]
   RowMap mw{q, p, (long long)k, (long long)q * k, 0, 1};
-  if (launch_rfft_half(k, kHalfSpectra, w, w_hat, mw, rows, rows, 1.0f, static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (launch_rfft_half(k, kHalfSpectra, bf, w, w_hat, mw, rows, rows, 1.0f, static_cast<hipStream_t>(stream)) != hipSuccess)
     return CIRC_EHIP;
   return CIRC_OK;
 }
 
-size_t circ_fc_workspace_bytes_f16(int p, int q, int k, int batch) {
+size_t fc_workspace_bytes_half(int p, int q, int k, int batch) {
   if (!fc_dims_ok(p, q, k, batch) || !half_k(k)) return 0;
   return half_spectrum_bytes(k, (long long)q * batch) + half_spectrum_bytes(k, (long long)p * batch);
 }
 
-circ_status circ_fc_forward_f16(const void* w_hat, const void* x, const float* bias, void* y, int p, int q, int k,
-                                int batch, int epilogue, void* workspace, size_t workspace_bytes, void* stream) {
+circ_status fc_forward_half(bool bf, const void* w_hat, const void* x, const float* bias, void* y, int p, int q, int k,
+                            int batch, int epilogue, void* workspace, size_t workspace_bytes, void* stream) {
   if (!fc_dims_ok(p, q, k, batch) || !half_k(k)) return CIRC_EINVAL;
   if (!w_hat || !x || !y) return CIRC_EINVAL;
   if (epilogue & ~(CIRC_EPI_BIAS | CIRC_EPI_RELU)) return CIRC_EINVAL;
@@ -1198,7 +1210,7 @@ circ_status circ_fc_forward_f16(const void* w_hat, const void* x, const float* b
   if (!aligned16(w_hat) || !aligned16(x) || !aligned16(y) || (use_bias && !aligned16(bias))) return CIRC_EINVAL;
   const size_t xbytes = size_t(batch) * q * k * sizeof(__half), ybytes = size_t(batch) * p * k * sizeof(__half);
   if (overlaps(x, xbytes, y, ybytes)) return CIRC_EINVAL;
-  if (!workspace || workspace_bytes < circ_fc_workspace_bytes_f16(p, q, k, batch)) return CIRC_EWORKSPACE;
+  if (!workspace || workspace_bytes < fc_workspace_bytes_half(p, q, k, batch)) return CIRC_EWORKSPACE;
   if (!aligned16(workspace)) return CIRC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int NF = k / 2 + 1;
@@ -1207,22 +1219,50 @@ circ_status circ_fc_forward_f16(const void* w_hat, const void* x, const float* b
   __half2* yh = reinterpret_cast<__half2*>(static_cast<char*>(workspace) + half_spectrum_bytes(k, xrows));
   // X^[f][b][j]: row id = b*q + j -> x[b][j*k : (j+1)*k]  (j fastest: the reduction index of the contraction)
   RowMap mx{q, batch, (long long)k, (long long)q * k, 0, 1};
-  if (launch_rfft_half(k, kHalfSpectra | kHalfRows, x, xh, mx, xrows, xrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
+  if (launch_rfft_half(k, kHalfSpectra | kHalfRows, bf, x, xh, mx, xrows, xrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
   // Y^[f][i][b] = (1/k) sum_j W^[f][i][j] X^[f][b][j]
   dim3 grid((unsigned)cdiv(batch, 128), (unsigned)cdiv(p, 64), (unsigned)NF);
   const __half2* wh = static_cast<const __half2*>(w_hat);
-  if (q % 4 == 0)
-    hipLaunchKernelGGL((cgemm_h_kernel<true>), grid, dim3(256), 0, s, wh, xh, yh, p, batch, q, (long long)p * q, xrows, yrows,
-                       1.0f / float(k));
-  else
-    hipLaunchKernelGGL((cgemm_h_kernel<false>), grid, dim3(256), 0, s, wh, xh, yh, p, batch, q, (long long)p * q, xrows, yrows,
-                       1.0f / float(k));
+#define CIRC_CGEMM_H(VEC, BF)                                                                                             \
+  hipLaunchKernelGGL((cgemm_h_kernel<VEC, BF>), grid, dim3(256), 0, s, wh, xh, yh, p, batch, q, (long long)p * q, xrows, yrows, \
+                     1.0f / float(k))
+  if (q % 4 == 0) {
+    if (bf) CIRC_CGEMM_H(true, true);
+    else CIRC_CGEMM_H(true, false);
+  } else {
+    if (bf) CIRC_CGEMM_H(false, true);
+    else CIRC_CGEMM_H(false, false);
+  }
+#undef CIRC_CGEMM_H
   if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
   RowMap my{batch, p, (long long)p * k, (long long)k, 0, 1};
-  if (launch_irfft_half(k, yh, y, my, yrows, yrows, 1.0f, use_bias ? bias : nullptr, batch,
+  if (launch_irfft_half(k, bf, yh, y, my, yrows, yrows, 1.0f, use_bias ? bias : nullptr, batch,
                         (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
     return CIRC_EHIP;
   return CIRC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t circ_spectra_bytes_f16(int p, int q, int k) { return spectra_bytes_half(p, q, k); }
+size_t circ_spectra_bytes_bf16(int p, int q, int k) { return spectra_bytes_half(p, q, k); }
+circ_status circ_precompute_spectra_f16(const float* w, int p, int q, int k, void* w_hat, void* stream) {
+  return precompute_spectra_half(false, w, p, q, k, w_hat, stream);
+}
+circ_status circ_precompute_spectra_bf16(const float* w, int p, int q, int k, void* w_hat, void* stream) {
+  return precompute_spectra_half(true, w, p, q, k, w_hat, stream);
+}
+size_t circ_fc_workspace_bytes_f16(int p, int q, int k, int batch) { return fc_workspace_bytes_half(p, q, k, batch); }
+size_t circ_fc_workspace_bytes_bf16(int p, int q, int k, int batch) { return fc_workspace_bytes_half(p, q, k, batch); }
+circ_status circ_fc_forward_f16(const void* w_hat, const void* x, const float* bias, void* y, int p, int q, int k,
+                                int batch, int epilogue, void* workspace, size_t workspace_bytes, void* stream) {
+  return fc_forward_half(false, w_hat, x, bias, y, p, q, k, batch, epilogue, workspace, workspace_bytes, stream);
+}
+circ_status circ_fc_forward_bf16(const void* w_hat, const void* x, const float* bias, void* y, int p, int q, int k,
+                                 int batch, int epilogue, void* workspace, size_t workspace_bytes, void* stream) {
+  return fc_forward_half(true, w_hat, x, bias, y, p, q, k, batch, epilogue, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -1,9 +1,9 @@
-// Half-width storage: fp16 spectra and activations, fp32 accumulation.
+// Half-width storage: 16-bit spectra and activations, fp32 accumulation.
 //
 // The hardware of Sec. 4.2 keeps inputs and weights in a 16-bit representation.  Its counterpart
-// here is IEEE fp16 in memory (activations, FFT(w_ij), and the spectra that travel between the
-// three kernels of the unfused route), with every FFT butterfly and every accumulation in fp32.
-// The per-frequency contraction then runs on the fp16 matrix instructions:
+// here is IEEE fp16 or bfloat16 in memory (activations, FFT(w_ij), and the spectra that travel
+// between the three kernels of the unfused route), with every FFT butterfly and every accumulation
+// in fp32.  The per-frequency contraction then runs on the 16-bit matrix instructions:
 //   Y^[f][i][b] = (1/k) * sum_j W^[f][i][j] X^[f][b][j]
 // with both operands stored j-fastest as (re, im) pairs.
 #pragma once
@@ -11,15 +11,29 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
+#include "circ_kernels.h"
+
 namespace circ {
 
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bfloatx8 __attribute__((ext_vector_type(8)));
 typedef float hfloatx16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ halfx8 as_halfx8(uint4 v) {
   union { uint4 u; halfx8 h; } c;
   c.u = v;
   return c.h;
+}
+__device__ __forceinline__ bfloatx8 as_bfloatx8(uint4 v) {
+  union { uint4 u; bfloatx8 h; } c;
+  c.u = v;
+  return c.h;
+}
+// acc += A (32 x 16) * B (16 x 32) on 16-bit operands (fp16, or bfloat16 when BF), fp32 accumulation
+template <bool BF>
+__device__ __forceinline__ hfloatx16 mfma16(uint4 a, uint4 b, hfloatx16 acc) {
+  if constexpr (BF) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bfloatx8(a), as_bfloatx8(b), acc, 0, 0, 0);
+  else return __builtin_amdgcn_mfma_f32_32x32x16_f16(as_halfx8(a), as_halfx8(b), acc, 0, 0, 0);
 }
 
 // One workgroup = 64 rows (m) x 128 columns (n) of one frequency; wave w owns columns
@@ -43,7 +57,7 @@ __device__ __forceinline__ halfx8 as_halfx8(uint4 v) {
 constexpr int kHChunk = 64;                      // complex values of the reduction per chunk
 constexpr int kHPitch = kHChunk + 4;             // LDS row pitch in complex values (272 bytes)
 
-template <bool VEC>
+template <bool VEC, bool BF>
 __global__ __launch_bounds__(256) void cgemm_h_kernel(const __half2* __restrict__ A, const __half2* __restrict__ B,
                                                       __half2* __restrict__ C, int M, int N, int Kd, long long sA,
                                                       long long sB, long long sC, float scale) {
@@ -99,23 +113,22 @@ __global__ __launch_bounds__(256) void cgemm_h_kernel(const __half2* __restrict_
           const uint4 vre = make_uint4(vb.x ^ 0x80000000u, vb.y ^ 0x80000000u, vb.z ^ 0x80000000u, vb.w ^ 0x80000000u);
           const uint4 vim = make_uint4(__builtin_amdgcn_alignbit(vb.x, vb.x, 16), __builtin_amdgcn_alignbit(vb.y, vb.y, 16),
                                        __builtin_amdgcn_alignbit(vb.z, vb.z, 16), __builtin_amdgcn_alignbit(vb.w, vb.w, 16));
-          const halfx8 ha0 = as_halfx8(va0), ha1 = as_halfx8(va1), hre = as_halfx8(vre), him = as_halfx8(vim);
-          cr0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha0, hre, cr0, 0, 0, 0);
-          ci0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha0, him, ci0, 0, 0, 0);
-          cr1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha1, hre, cr1, 0, 0, 0);
-          ci1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ha1, him, ci1, 0, 0, 0);
+          cr0 = mfma16<BF>(va0, vre, cr0);
+          ci0 = mfma16<BF>(va0, vim, ci0);
+          cr1 = mfma16<BF>(va1, vre, cr1);
+          ci1 = mfma16<BF>(va1, vim, ci1);
         }
       }
     }
   }
   const int col = nb0 + 32 * wave + r;
   if (!wave_active || col >= N) return;
-  __half2* c = C + f * sC + col;
+  unsigned* c = reinterpret_cast<unsigned*>(C) + f * sC + col;
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
     const int row = m0 + 8 * (t / 4) + 4 * h + (t % 4);
-    if (row < M) c[(long long)row * N] = __floats2half2_rn(scale * cr0[t], scale * ci0[t]);
-    if (row + 32 < M) c[(long long)(row + 32) * N] = __floats2half2_rn(scale * cr1[t], scale * ci1[t]);
+    if (row < M) c[(long long)row * N] = pack_pair16<BF>(scale * cr0[t], scale * ci0[t]);
+    if (row + 32 < M) c[(long long)(row + 32) * N] = pack_pair16<BF>(scale * cr1[t], scale * ci1[t]);
   }
 }
 

@@ -6,8 +6,8 @@
 //   conv_contract_kernel  the same contraction for CONV: sum over the r*r offsets and
 //                    the input channel blocks (Eq. 6 / Eq. 7)
 //   irfft_kernel     half spectra -> real rows, fused bias + ReLU (Eq. 1)
-// The two transform kernels can also read or write IEEE fp16 (rows and / or spectra, HMODE) for
-// the half-width storage route; their arithmetic stays fp32.
+// The two transform kernels can also read or write 16-bit values (IEEE fp16 or bfloat16; rows and /
+// or spectra, HMODE) for the half-width storage route; their arithmetic stays fp32.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -17,22 +17,38 @@
 
 namespace circ {
 
-// Half-width storage (IEEE fp16 in memory, fp32 in registers and LDS): bit 0 of HMODE = the
-// real rows are fp16, bit 1 = the spectra are fp16 (re, im) pairs.
-constexpr int kHalfRows = 1, kHalfSpectra = 2;
+// Half-width storage (16-bit values in memory, fp32 in registers and LDS): bit 0 of HMODE = the
+// real rows are 16-bit, bit 1 = the spectra are 16-bit (re, im) pairs, bit 2 = the 16-bit format
+// is bfloat16 (the upper half of an fp32, rounded to nearest even) instead of IEEE fp16.
+constexpr int kHalfRows = 1, kHalfSpectra = 2, kHalfBf16 = 4;
 
-__device__ __forceinline__ float4 load_half4(const void* p) {          // 4 consecutive fp16 values, 8-byte aligned
+template <bool BF>
+__device__ __forceinline__ float2 unpack_pair16(unsigned w) {       // one 32-bit word = two 16-bit values
+  if constexpr (BF) return make_float2(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
+  else return __half22float2(*reinterpret_cast<const __half2*>(&w));
+}
+__device__ __forceinline__ unsigned bf16_bits(float v) {            // round to nearest even; NaN stays NaN
+  const unsigned u = __float_as_uint(v);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+template <bool BF>
+__device__ __forceinline__ unsigned pack_pair16(float a, float b) {
+  if constexpr (BF) return bf16_bits(a) | (bf16_bits(b) << 16);
+  else {
+    const __half2 h = __floats2half2_rn(a, b);
+    return *reinterpret_cast<const unsigned*>(&h);
+  }
+}
+template <bool BF>
+__device__ __forceinline__ float4 load_half4(const void* p) {       // 4 consecutive 16-bit values, 8-byte aligned
   const uint2 raw = *reinterpret_cast<const uint2*>(p);
-  const float2 a = __half22float2(*reinterpret_cast<const __half2*>(&raw.x));
-  const float2 b = __half22float2(*reinterpret_cast<const __half2*>(&raw.y));
+  const float2 a = unpack_pair16<BF>(raw.x), b = unpack_pair16<BF>(raw.y);
   return make_float4(a.x, a.y, b.x, b.y);
 }
+template <bool BF>
 __device__ __forceinline__ void store_half4(void* p, float4 v) {
-  const __half2 a = __floats2half2_rn(v.x, v.y), b = __floats2half2_rn(v.z, v.w);
-  uint2 raw;
-  raw.x = *reinterpret_cast<const unsigned*>(&a);
-  raw.y = *reinterpret_cast<const unsigned*>(&b);
-  *reinterpret_cast<uint2*>(p) = raw;
+  *reinterpret_cast<uint2*>(p) = make_uint2(pack_pair16<BF>(v.x, v.y), pack_pair16<BF>(v.z, v.w));
 }
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -74,7 +90,7 @@ __device__ __forceinline__ float lds_get(const float2* z, int idx, int half) {
 // blockIdx.y selects one of several independent grids (weight precompute for CONV).
 // ROWS_FAST: consecutive rows are adjacent in memory (CONV, NCHW: the FFT axis is the
 // channel axis and pixels are contiguous) — lanes then run along rows when loading.
-// HMODE (see kHalfRows / kHalfSpectra): `in` then points to fp16 rows and / or `out` to fp16 pairs;
+// HMODE (see kHalfRows / kHalfSpectra / kHalfBf16): `in` then points to 16-bit rows and / or `out` to 16-bit pairs;
 // offsets and strides keep their meaning in elements.  Contiguous rows with K >= 4 only.
 template <int K, bool ROWS_FAST, int HMODE = 0>
 __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ out, RowMap map,
@@ -132,7 +148,7 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
       long long b = L.rbase[row];
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if constexpr (HMODE & kHalfRows) {
-        if (b >= 0) v = load_half4(reinterpret_cast<const __half*>(in) + b + n);
+        if (b >= 0) v = load_half4<(HMODE & kHalfBf16) != 0>(reinterpret_cast<const unsigned short*>(in) + b + n);
       } else {
         if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n);
       }
@@ -175,9 +191,9 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
       const float2 v0 = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
       const float2 v1 = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
       if constexpr (HMODE & kHalfSpectra) {
-        __half2* oh = reinterpret_cast<__half2*>(out) + o;
-        if (ok0) oh[0] = __floats2half2_rn(v0.x, v0.y);
-        if (ok1) oh[1] = __floats2half2_rn(v1.x, v1.y);
+        unsigned* oh = reinterpret_cast<unsigned*>(out) + o;
+        if (ok0) oh[0] = pack_pair16<(HMODE & kHalfBf16) != 0>(v0.x, v0.y);
+        if (ok1) oh[1] = pack_pair16<(HMODE & kHalfBf16) != 0>(v1.x, v1.y);
       } else {
         if (ok0) out[o] = v0;
         if (ok1) out[o + 1] = v1;
@@ -216,7 +232,7 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
     const long long sstep = (long long)fstep * in_fstride;
     auto bin = [&](long long e, bool ok) -> float2 {
       if (!ok) return make_float2(0.f, 0.f);
-      if constexpr (HMODE & kHalfSpectra) return __half22float2(reinterpret_cast<const __half2*>(in)[e]);
+      if constexpr (HMODE & kHalfSpectra) return unpack_pair16<(HMODE & kHalfBf16) != 0>(reinterpret_cast<const unsigned*>(in)[e]);
       else return in[e];
     };
 #pragma unroll 4
@@ -273,7 +289,7 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
         v.x += bb.x; v.y += bb.y; v.z += bb.z; v.w += bb.w;
       }
       if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
-      if constexpr (HMODE & kHalfRows) store_half4(reinterpret_cast<__half*>(out) + b + n, v);
+      if constexpr (HMODE & kHalfRows) store_half4<(HMODE & kHalfBf16) != 0>(reinterpret_cast<unsigned short*>(out) + b + n, v);
       else *reinterpret_cast<float4*>(out + b + n) = v;
     }
   } else if (ROWS_FAST && map.quad) {

@@ -204,19 +204,22 @@ def test_f16_argument_errors():
     assert pre(None, 2, 2, 8, A, None) == B.CIRC_EINVAL
     assert pre(A, 2, 2, 12, A + big, None) == B.CIRC_EINVAL
     assert pre(A, 2, 2, 8, A, None) == B.CIRC_EINVAL              # output aliases input
-    f = B.lib().circ_fc_forward_f16
+    assert B.lib().circ_spectra_bytes_bf16(64, 64, 64) == 33 * 64 * 64 * 4
+    assert B.lib().circ_fc_workspace_bytes_bf16(64, 64, 64, 64) == 2 * 33 * 64 * 64 * 4
+    assert B.lib().circ_precompute_spectra_bf16(A, 2, 2, 12, A + big, None) == B.CIRC_EINVAL
+    for f in (B.lib().circ_fc_forward_f16, B.lib().circ_fc_forward_bf16):
 
-    def call(w_hat=A, x=A + big, bias=None, y=A + 2 * big, p=2, q=2, k=8, batch=2, epi=0, wsp=A + 3 * big, wsb=1 << 30):
-        return f(w_hat, x, bias, y, p, q, k, batch, epi, wsp, wsb, None)
+        def call(w_hat=A, x=A + big, bias=None, y=A + 2 * big, p=2, q=2, k=8, batch=2, epi=0, wsp=A + 3 * big, wsb=1 << 30):
+            return f(w_hat, x, bias, y, p, q, k, batch, epi, wsp, wsb, None)
 
-    assert call(k=4) == B.CIRC_EINVAL
-    assert call(k=24) == B.CIRC_EINVAL
-    assert call(x=None) == B.CIRC_EINVAL
-    assert call(epi=B.EPI_BIAS) == B.CIRC_EINVAL                  # bias flag without a bias
-    assert call(epi=8) == B.CIRC_EINVAL
-    assert call(y=A + big) == B.CIRC_EINVAL                       # in place
-    assert call(x=A + big + 2) == B.CIRC_EINVAL                   # misaligned
-    assert call(wsb=16) == B.CIRC_EWORKSPACE
+        assert call(k=4) == B.CIRC_EINVAL
+        assert call(k=24) == B.CIRC_EINVAL
+        assert call(x=None) == B.CIRC_EINVAL
+        assert call(epi=B.EPI_BIAS) == B.CIRC_EINVAL                  # bias flag without a bias
+        assert call(epi=8) == B.CIRC_EINVAL
+        assert call(y=A + big) == B.CIRC_EINVAL                       # in place
+        assert call(x=A + big + 2) == B.CIRC_EINVAL                   # misaligned
+        assert call(wsb=16) == B.CIRC_EWORKSPACE
 
 
 def test_bias_grad_argument_errors():

@@ -352,51 +352,68 @@ def test_conv_sgd_step_shapes(N, p, q, k, H, W, r, pad):
     check(y, O.conv_forward(w2, x1, None, False, pad), "conv forward after two steps " + what)
 
 
-# ---- half-width storage (fp16 in memory, fp32 arithmetic) -----------------------------------
-# Four fp16 roundings lie between the inputs and an output (spectra of the weights, spectra of the
-# inputs, output spectra, the output itself), each at most 2^-11 relative; the gate is their sum,
-# the value expected from independent roundings about a quarter of it.
-HALF_GATE = 4 * 2.0 ** -11
+# ---- half-width storage (16-bit values in memory, fp32 arithmetic) ---------------------------
+# Four 16-bit roundings lie between the inputs and an output (spectra of the weights, spectra of
+# the inputs, output spectra, the output itself), each at most 2^-11 (fp16) or 2^-8 (bfloat16)
+# relative; the gate is their sum, the value expected from independent roundings about a quarter.
+HALF_GATE = {torch.float16: 4 * 2.0 ** -11, torch.bfloat16: 4 * 2.0 ** -8}
+HALF_DTYPES = [torch.float16, torch.bfloat16]
 
 
-def check_half(got, ref, what):
+def check_half(got, ref, what, dtype):
     err = O.max_norm_rel_err(got, ref)
-    print(f"[parity f16] {what} max-norm rel err = {err:.3e}", flush=True)
+    print(f"[parity {dtype}] {what} max-norm rel err = {err:.3e}", flush=True)
     assert np.all(np.isfinite(got)), what
-    assert err <= HALF_GATE, (what, err)
+    assert err <= HALF_GATE[dtype], (what, err)
     return err
 
 
-def gpu_fc_forward_f16(w, x16, bias, relu):
+def to_half(x, dtype):
+    """fp32 array -> (device tensor of `dtype`, the same values back in fp32): the inputs are
+    16-bit values on both sides of the comparison."""
+    t = torch.from_numpy(x).to(dtype)
+    return t.to(G.DEV), t.float().numpy()
+
+
+def gpu_fc_forward_half(w, xt, bias, relu):
     p, q, k = w.shape
-    wh = B.circ_precompute_spectra_f16(G.dev(w))
-    y = B.circ_fc_forward_f16(wh, torch.from_numpy(x16).to(G.DEV), G.dev(bias), None, p, q, k, G.epi_flags(bias, relu))
-    assert y.dtype == torch.float16
+    wh = B.circ_precompute_spectra_f16(G.dev(w), dtype=xt.dtype)
+    y = B.circ_fc_forward_f16(wh, xt, G.dev(bias), None, p, q, k, G.epi_flags(bias, relu))
+    assert y.dtype == xt.dtype
     return y.float().cpu().numpy()
 
 
+@pytest.mark.parametrize("dtype", HALF_DTYPES)
 @pytest.mark.parametrize("p,q,k,batch", [(1, 1, 8, 1), (3, 5, 16, 7), (5, 3, 64, 33), (2, 4, 256, 10), (33, 34, 8, 70),
                                          (4, 6, 128, 67), (2, 3, 512, 5), (7, 9, 32, 2), (17, 64, 64, 130), (70, 12, 64, 300),
-                                         (64, 64, 64, 64), (65, 8, 32, 129)])
-def test_fc_forward_f16_shapes(p, q, k, batch):
+                                         (64, 64, 64, 64), (65, 8, 32, 129), (3, 72, 128, 40), (2, 130, 16, 9)])
+def test_fc_forward_half_shapes(p, q, k, batch, dtype):
     w, x, b = rand_fc(p, q, k, batch)
-    x16 = x.astype(np.float16)                          # the inputs are fp16 values on both sides
-    xr = x16.astype(np.float32)
+    xt, xr = to_half(x, dtype)
     what = f"{p}x{q} k={k} B={batch}"
-    check_half(gpu_fc_forward_f16(w, x16, b, True), O.fc_forward(w, xr, b, True), "bias+relu " + what)
-    check_half(gpu_fc_forward_f16(w, x16, None, False), O.fc_forward(w, xr), "plain " + what)
+    check_half(gpu_fc_forward_half(w, xt, b, True), O.fc_forward(w, xr, b, True), "bias+relu " + what, dtype)
+    check_half(gpu_fc_forward_half(w, xt, None, False), O.fc_forward(w, xr), "plain " + what, dtype)
 
 
-@pytest.mark.parametrize("cfg", ["cfg2", "cfg3_l2", "cfg5"])
-def test_fc_forward_f16_configs(cfg):
-    c = {"cfg2": synth.CFG2, "cfg3_l2": synth.CFG3_L2, "cfg5": synth.CFG5}[cfg]
+def test_fc_forward_bf16_large_inputs():
+    """Inputs far outside the fp16 range (|x| k up to 4e7) are fine in bfloat16."""
+    p, q, k, batch = 3, 4, 64, 9
+    w, x, _ = rand_fc(p, q, k, batch, bias=False)
+    xt, xr = to_half(x * 6.0e5, torch.bfloat16)
+    check_half(gpu_fc_forward_half(w, xt, None, False), O.fc_forward(w, xr), "large inputs", torch.bfloat16)
+
+
+@pytest.mark.parametrize("dtype", HALF_DTYPES)
+@pytest.mark.parametrize("cfg", ["cfg2", "cfg3_l1", "cfg5"])
+def test_fc_forward_half_configs(cfg, dtype):
+    c = {"cfg2": synth.CFG2, "cfg3_l1": synth.CFG3_L1, "cfg5": synth.CFG5}[cfg]
     w, x, b = synth.fc_inputs(c, 0)
-    x16 = x.astype(np.float16)
-    got = gpu_fc_forward_f16(w, x16, b, c.relu)
+    xt, xr = to_half(x, dtype)
+    got = gpu_fc_forward_half(w, xt, b, c.relu)
     rows = sorted(set(int(i) for i in np.linspace(0, c.p - 1, 4)))   # sampled output block rows, all batch elements
-    ref = O.fc_forward(w, x16.astype(np.float32), b, c.relu, block_rows=rows)
+    ref = O.fc_forward(w, xr, b, c.relu, block_rows=rows)
     sel = np.concatenate([np.arange(i * c.k, (i + 1) * c.k) for i in rows])
-    check_half(got[:, sel], ref, f"{cfg} block rows {rows}")
+    check_half(got[:, sel], ref, f"{cfg} block rows {rows}", dtype)
 
 
 # ---- stride > 1 and even filter sizes (Eq. 6 is the stride-1 case) ---------------------------
