@@ -352,6 +352,58 @@ def test_conv_sgd_step_shapes(N, p, q, k, H, W, r, pad):
     check(y, O.conv_forward(w2, x1, None, False, pad), "conv forward after two steps " + what)
 
 
+def test_conv_large_image():
+    """A 224 x 224 image: many tiles of the fused kernel per image, and for the weight gradient
+    many bands of rows per image (a band of 4 input blocks must fit the LDS budget) walked over by
+    one workgroup.  Also with stride 2 (unfused route)."""
+    N, p, q, k, H, W, r, pad = 2, 1, 1, 64, 224, 224, 3, 1
+    w = (RNG.standard_normal((r, r, p, q, k)) / np.sqrt(r * r * q * k)).astype(np.float32)
+    x = RNG.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32)
+    for stride in (1, 2):
+        Ho = (H + 2 * pad - r) // stride + 1
+        dy = RNG.uniform(-1, 1, (N, p * k, Ho, Ho)).astype(np.float32)
+        check(G.gpu_conv_forward(w, x, None, False, pad, stride), O.conv_forward(w, x, None, False, pad, stride),
+              f"224x224 fwd stride {stride}")
+        dx, dw = G.gpu_conv_backward(w, x, dy, pad, stride=stride)
+        check(dx, O.conv_backward_dx(w, dy, H, W, pad, stride), f"224x224 dx stride {stride}")
+        check(dw, O.conv_backward_dw(x, dy, k, r, pad, stride), f"224x224 dw stride {stride}")
+
+
+def test_fc_forward_largest_batch():
+    """The largest batch the ABI accepts (65535 * 16 vectors): activations of 4.29 GB each (byte
+    offsets up to 2^32), spectra of 5.4e8 elements and 4.31 GB each (byte offsets beyond 2^32).
+    Inputs are made on the GPU; rows at the start, around the 2^31-byte mark, in the middle and at
+    the end are checked against the oracle."""
+    p, q, k, batch = 2, 2, 512, 65535 * 16
+    w = (RNG.standard_normal((p, q, k)) / np.sqrt(q * k)).astype(np.float32)
+    b = (0.1 * RNG.standard_normal(p * k)).astype(np.float32)
+    gen = torch.Generator(device=G.DEV)
+    gen.manual_seed(1708)
+    x = torch.rand(batch, q * k, device=G.DEV, generator=gen) * 2 - 1
+    wh = B.circ_precompute_spectra(G.dev(w))
+    y = B.circ_fc_forward(wh, x, G.dev(b), None, p, q, k, epilogue=B.EPI_BIAS | B.EPI_RELU)
+    torch.cuda.synchronize()
+    row_bytes = q * k * 4
+    marks = [0, (1 << 31) // row_bytes - 4, batch // 2 + 5, 3 * (batch // 4), batch - 8]
+    for r0 in marks:
+        xs = x[r0:r0 + 8].cpu().numpy()
+        check(y[r0:r0 + 8].cpu().numpy(), O.fc_forward(w, xs, b, True), f"largest batch, rows {r0}..{r0 + 7}")
+    # backward at the same size: dx on the same rows against the oracle; dw (a sum over all
+    # 1,048,560 rows) through the bilinear identity <dw, w> = <dy, W x> with the forward result
+    dy = torch.rand(batch, p * k, device=G.DEV, generator=gen) * 2 - 1
+    dx, dw = B.circ_fc_backward(wh, x, dy, p, q, k)
+    y_lin = B.circ_fc_forward(wh, x, None, y, p, q, k)
+    torch.cuda.synchronize()
+    for r0 in marks:
+        check(dx[r0:r0 + 8].cpu().numpy(), O.fc_backward_dx(w, dy[r0:r0 + 8].cpu().numpy()), f"largest batch dx, rows {r0}..{r0 + 7}")
+    lhs = float((dw.double() * torch.from_numpy(w).to(G.DEV).double()).sum())
+    rhs = float((dy.double() * y_lin.double()).sum())
+    print(f"[identity] <dw, w> = {lhs:.6e}, <dy, y> = {rhs:.6e}", flush=True)
+    assert abs(lhs - rhs) <= 1e-4 * abs(rhs) + 1e-2
+    del x, y, dy, dx
+    torch.cuda.empty_cache()
+
+
 # ---- half-width storage (16-bit values in memory, fp32 arithmetic) ---------------------------
 # Four 16-bit roundings lie between the inputs and an output (spectra of the weights, spectra of
 # the inputs, output spectra, the output itself), each at most 2^-11 (fp16) or 2^-8 (bfloat16)
