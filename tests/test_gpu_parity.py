@@ -472,7 +472,8 @@ def test_fc_forward_half_configs(cfg, dtype):
 @pytest.mark.parametrize("N,p,q,k,H,W,r,pad,stride", [
     (2, 2, 3, 8, 9, 8, 3, 1, 2), (3, 1, 2, 16, 7, 7, 3, 0, 2), (2, 4, 4, 64, 28, 28, 3, 1, 2), (2, 2, 2, 64, 13, 12, 3, 1, 3),
     (1, 3, 2, 4, 11, 9, 5, 2, 2), (2, 2, 2, 32, 8, 8, 2, 0, 2), (2, 3, 1, 8, 9, 10, 4, 1, 2), (3, 2, 2, 16, 6, 6, 2, 1, 1),
-    (2, 2, 3, 12, 10, 7, 3, 1, 2), (33, 2, 2, 64, 14, 14, 3, 1, 2), (2, 2, 2, 8, 5, 300, 3, 1, 2), (2, 1, 1, 8, 6, 1, 1, 0, 1)])
+    (2, 2, 3, 12, 10, 7, 3, 1, 2), (33, 2, 2, 64, 14, 14, 3, 1, 2), (2, 2, 2, 8, 5, 300, 3, 1, 2), (2, 1, 1, 8, 6, 1, 1, 0, 1),
+    (1, 1, 2, 8, 9, 9, 7, 3, 1), (2, 2, 1, 4, 10, 10, 7, 6, 3), (1, 1, 1, 2, 1, 1, 1, 0, 1), (2, 5, 6, 4, 3, 2000, 3, 1, 1)])
 def test_conv_strided_and_even_filters(N, p, q, k, H, W, r, pad, stride):
     w = (RNG.standard_normal((r, r, p, q, k)) / np.sqrt(r * r * q * k)).astype(np.float32)
     x = RNG.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32)
