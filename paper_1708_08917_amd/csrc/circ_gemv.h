@@ -27,7 +27,10 @@ template <int K>
 struct GemvShape {
   static constexpr int NT = 256;
   static constexpr int S = K / 2;                       // complex slots per block
-  static constexpr int PT = 4096 / K < 128 ? 4096 / K : 128;   // input blocks (FFT columns) per chunk
+  // input blocks (FFT columns) per chunk: up to 128, for the shortest blocks up to 512 (a chunk costs
+  // one round trip to memory for its x rows, and layers with k <= 8 have many blocks per row)
+  static constexpr int PTMAX = K <= 8 ? 512 : 128;
+  static constexpr int PT = 4096 / K < PTMAX ? 4096 / K : PTMAX;
   static constexpr int PP = PT + 1;
   static constexpr int OPROW = 2 * K + 2;
   static constexpr int JG = NT / S >= 1 ? NT / S : 1;   // threads sharing a slot split the j range
