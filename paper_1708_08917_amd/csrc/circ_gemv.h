@@ -35,8 +35,13 @@ struct GemvShape {
   static constexpr int OPROW = 2 * K + 2;
   static constexpr int JG = NT / S >= 1 ? NT / S : 1;   // threads sharing a slot split the j range
   static constexpr int ZELEMS = K * PP;
+  // the sum over the JG j-groups runs in two stages when there are threads to spare: NV values
+  // (8 per slot), each first summed over NR contiguous ranges of GL groups, then over the ranges
+  static constexpr int NV = 8 * S;
+  static constexpr int NR = NT / NV >= 1 ? (NT / NV < JG ? NT / NV : JG) : 1;
+  static constexpr int GL = JG / NR;
   static constexpr size_t LDS_BYTES = size_t(ZELEMS) * sizeof(float2) + size_t(PT) * OPROW * sizeof(float) +
-                                      size_t(K) * sizeof(float2) + size_t(NT) * 8 * sizeof(float);
+                                      size_t(K) * sizeof(float2) + size_t(NT) * 9 * sizeof(float);
   static_assert(K >= 4 && K <= 512 && S <= NT, "block size out of range for this kernel");
 };
 
@@ -178,14 +183,33 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
       }
     }
     __syncthreads();
+    constexpr int NV = Sh::NV, NR = Sh::NR, GL = Sh::GL;
+    float* red2 = red + NT * 8;                    // [range][value]
+    if constexpr (NR > 1) {
+      // stage 1: thread (range r, value v = m8*S + slot) adds its GL groups in index order
+      if (tid < NV * NR) {
+        const int v = tid % NV, r = tid / NV, m8 = v / S, sl = v % S;
+        float a = 0.f;
+        for (int g = r * GL; g < (r + 1) * GL; ++g) a += red[(m8 * JG + g) * S + sl];
+        red2[r * NV + v] = a;
+      }
+      __syncthreads();
+    }
     if (tid < S) {
       float Ps[4], Qs[4];
   #pragma unroll
       for (int m = 0; m < 4; ++m) {
         float a = 0.f, b = 0.f;
-        for (int g = 0; g < JG; ++g) {
-          a += red[(m * JG + g) * S + tid];
-          b += red[((4 + m) * JG + g) * S + tid];
+        if constexpr (NR > 1) {
+          for (int r = 0; r < NR; ++r) {             // stage 2: the ranges, in index order
+            a += red2[r * NV + m * S + tid];
+            b += red2[r * NV + (4 + m) * S + tid];
+          }
+        } else {
+          for (int g = 0; g < JG; ++g) {
+            a += red[(m * JG + g) * S + tid];
+            b += red[((4 + m) * JG + g) * S + tid];
+          }
         }
         Ps[m] = a;
         Qs[m] = b;
