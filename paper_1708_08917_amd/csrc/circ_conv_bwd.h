@@ -17,20 +17,6 @@
 
 namespace circ {
 
-// Sum `v` over the threads of a 256-thread block, in a fixed order: butterfly inside each wave,
-// then the four wave sums in index order.  `red` holds 4 floats per call site in flight; the
-// result is valid in thread 0.
-__device__ __forceinline__ float block_sum_256(float v, float* red, int tid) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
-  if ((tid & 63) == 0) red[tid >> 6] = v;
-  __syncthreads();
-  float s = 0.f;
-  if (tid == 0) s = (red[0] + red[1]) + (red[2] + red[3]);
-  __syncthreads();
-  return s;
-}
-
 // Partial weight-gradient spectra on the matrix cores.  Block (x = pixel chunk, y = frequency f,
 // z = (offset group, tile of 4 output blocks, tile of 4 input blocks)) accumulates, over its
 // chunk of output pixels, the 4 x 4 x NG products dY^ conj(X^) of NG consecutive offsets and
@@ -319,22 +305,32 @@ __global__ __launch_bounds__(256) void sum_parts_kernel(float* __restrict__ part
   part[e] = acc;
 }
 
-// db[c] = sum_{o < outer, t < inner} dy[(o*channels + c)*inner + t], one block per channel
-// (CONV: outer = images, inner = pixels per image).
-__global__ __launch_bounds__(256) void bias_grad_channel_kernel(const float* __restrict__ dy, float* __restrict__ db,
-                                                                long long outer, int channels, long long inner) {
-  __shared__ float red[4];
+// db[c] = sum_{o < outer, t < inner} dy[(o*channels + c)*inner + t], one block of 1024 threads per
+// channel (CONV: outer = images, inner = pixels per image; with as many channels as CUs, the
+// threads of a block are what keeps enough loads in flight).  Fixed order: each thread adds its
+// strided elements in index order, a butterfly adds the lanes of a wave, one thread the 16 waves.
+__global__ __launch_bounds__(1024) void bias_grad_channel_kernel(const float* __restrict__ dy, float* __restrict__ db,
+                                                                 long long outer, int channels, long long inner) {
+  __shared__ float red[16];
   const int c = blockIdx.x, tid = threadIdx.x;
   float s = 0.f;
   const long long total = outer * inner;
   // flat element index e = o*inner + t of this channel; the loads of a thread are independent
 #pragma unroll 8
-  for (long long e = tid; e < total; e += 256) {
+  for (long long e = tid; e < total; e += 1024) {
     const long long o = e / inner, t = e - o * inner;
     s += dy[(o * channels + c) * inner + t];
   }
-  const float tot = block_sum_256(s, red, tid);
-  if (tid == 0) db[c] = tot;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) s += __shfl_down(s, off, 64);
+  if ((tid & 63) == 0) red[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) {
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += red[w];
+    db[c] = tot;
+  }
 }
 
 // inner == 1 (FC: dy[batch][m]): a block owns 64 consecutive columns; its four waves take the
