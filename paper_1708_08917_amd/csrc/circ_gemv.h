@@ -21,6 +21,11 @@
 #include "circ_fft.h"
 #include "circ_kernels.h"
 
+// Optional phase-timing hook for profiling builds; expands to nothing in the library.
+#ifndef CIRC_PROBE
+#define CIRC_PROBE(id)
+#endif
+
 namespace circ {
 
 template <int K>
@@ -105,6 +110,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
     }
   };
   if (MODE != 2) fetch_w(0);
+  CIRC_PROBE(0);
 
   for (int c = 0; c < nchunks; ++c) {
     const int j0 = jbeg + c * PT;
@@ -120,6 +126,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
       lds_put(z, (n + 3) * PP + col, half, v.w);
     }
     __syncthreads();
+    CIRC_PROBE(1 + 3 * c);
     auto sink = [&](int col) {
       return [=](int f, float2 v) {
         int sl, h;
@@ -140,6 +147,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
       fft_lds_pass2<K, false>(z, PP, col, t, NT / PT, sink(col));
     }
     __syncthreads();
+    CIRC_PROBE(2 + 3 * c);
     float2 wcur[NPF];
 #pragma unroll
     for (int u = 0; u < NPF; ++u) wcur[u] = wnext[u];
@@ -158,6 +166,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
       }
     }
     __syncthreads();   // z and op are rewritten by the next chunk
+    CIRC_PROBE(3 + 3 * c);
   }
 
   if constexpr (MODE == 2) {
@@ -224,6 +233,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
     }
   }
   __syncthreads();
+  CIRC_PROBE(40);
   if constexpr (MODE == 1) {
     // partial spectrum of the output pair (column 0 of z, row stride 2) -> workspace
     float2* dst = part + ((long long)blockIdx.y * p + i) * K;
@@ -242,6 +252,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
     fft_lds_pass2_inplace<K, true>(z, 2, 0, tid, NT);
     __syncthreads();
   }
+  CIRC_PROBE(41);
   auto opos = [](int n) { return K <= 16 ? K + n : fft_pos<K>(n); };
   for (int idx = tid; idx < 2 * K; idx += NT) {
     const int half = idx / K, n = idx % K;
@@ -252,6 +263,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
       y[(long long)half * ldy + (long long)i * K + n] = v;
     }
   }
+  CIRC_PROBE(42);
 }
 
 }  // namespace circ
