@@ -139,24 +139,30 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
     }
   } else if constexpr (K >= 4) {
     // rows are contiguous (element stride 1) and 16-byte aligned: vector loads along the row.
-    // NT is a multiple of K/4 (both powers of two, NT >= K/4): a thread keeps its position n in
-    // the row and only its row index advances, by NT/(K/4) per step.
-    const int n = 4 * (tid % (K / 4)), rstep = NT / (K / 4);
-    float* zcol = reinterpret_cast<float*>(L.z) + 2 * n * PP;
-#pragma unroll 4
-    for (int row = tid / (K / 4); row < 2 * P; row += rstep) {
-      long long b = L.rbase[row];
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if constexpr (HMODE & kHalfRows) {
-        if (b >= 0) v = load_half4<(HMODE & kHalfBf16) != 0>(reinterpret_cast<const unsigned short*>(in) + b + n);
-      } else {
-        if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n);
+    // One wave-load covers 64/GW rows x GW*16 contiguous bytes.  A step of one float4 along the
+    // row is 8*PP words in the tile, a multiple of 8 (PP is odd), so with all 64 lanes along one
+    // row they would share 4 LDS banks; 8 lanes along the row (4 banks, twice) times 8 rows
+    // (row r sits r words from row 0) give every bank exactly two lanes.
+    constexpr int GW = K / 4 < 8 ? K / 4 : 8, NSEG = K / (4 * GW);
+    const int gl = tid % GW, rstep = NT / GW;
+    for (int row = tid / GW; row < 2 * P; row += rstep) {
+      const long long b = L.rbase[row];
+      float* zrow = reinterpret_cast<float*>(L.z) + row;      // 2*(row >> 1) + (row & 1) == row
+#pragma unroll
+      for (int seg = 0; seg < NSEG; ++seg) {
+        const int n = 4 * (seg * GW + gl);
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if constexpr (HMODE & kHalfRows) {
+          if (b >= 0) v = load_half4<(HMODE & kHalfBf16) != 0>(reinterpret_cast<const unsigned short*>(in) + b + n);
+        } else {
+          if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n);
+        }
+        float* zd = zrow + 2 * n * PP;
+        zd[0] = v.x;
+        zd[2 * PP] = v.y;
+        zd[4 * PP] = v.z;
+        zd[6 * PP] = v.w;
       }
-      float* zd = zcol + 2 * (row >> 1) + (row & 1);
-      zd[0] = v.x;
-      zd[2 * PP] = v.y;
-      zd[4 * PP] = v.z;
-      zd[6 * PP] = v.w;
     }
   } else {
     for (int idx = tid; idx < 2 * P * K; idx += NT) {
@@ -185,6 +191,27 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
     static_assert(HMODE == 0 || (!ROWS_FAST && K >= 4), "half-width storage: contiguous rows only");
     long long o = (long long)(tid >> lgP) * out_fstride + rid;
     const long long ostep = (long long)fstep * out_fstride;
+    // whole tile inside the buffer and the pair (rid, rid + 1) aligned to its combined width:
+    // one store per bin, no predicates (the loop body is then branch-free and several bins'
+    // LDS reads are in flight at once)
+    constexpr int PAIRB = (HMODE & kHalfSpectra) ? 8 : 16;
+    const bool whole = t0 + 2 * P <= nrows && (out_fstride & 1) == 0 &&
+                       (reinterpret_cast<unsigned long long>(out) & (PAIRB - 1)) == 0;
+    if (whole) {
+#pragma unroll 4
+      for (int f = tid >> lgP; f < NF; f += fstep, o += ostep) {
+        float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>((K - f) & (K - 1)) * PP + pr];
+        const float2 v0 = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
+        const float2 v1 = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
+        if constexpr (HMODE & kHalfSpectra) {
+          *reinterpret_cast<uint2*>(reinterpret_cast<unsigned*>(out) + o) =
+              make_uint2(pack_pair16<(HMODE & kHalfBf16) != 0>(v0.x, v0.y), pack_pair16<(HMODE & kHalfBf16) != 0>(v1.x, v1.y));
+        } else {
+          *reinterpret_cast<float4*>(out + o) = make_float4(v0.x, v0.y, v1.x, v1.y);
+        }
+      }
+      return;
+    }
 #pragma unroll 2
     for (int f = tid >> lgP; f < NF; f += fstep, o += ostep) {
       float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>((K - f) & (K - 1)) * PP + pr];
@@ -235,24 +262,55 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
       if constexpr (HMODE & kHalfSpectra) return unpack_pair16<(HMODE & kHalfBf16) != 0>(reinterpret_cast<const unsigned*>(in)[e]);
       else return in[e];
     };
-#pragma unroll 4
-    for (int f = tid >> lgP; f < NF; f += fstep, s += sstep) {
-      float2 ya = bin(s, ok0);
-      float2 yb = bin(s + 1, ok1);
-      // partial sums: loads four parts ahead, additions in index order
-#pragma unroll 4
-      for (int part = 1; part < nparts; ++part) {
-        const long long sp = s + part * part_stride;
-        const float2 pa = bin(sp, ok0);
-        const float2 pb = bin(sp + 1, ok1);
-        ya.x += pa.x; ya.y += pa.y;
-        yb.x += pb.x; yb.y += pb.y;
-      }
-      if (f == 0 || 2 * f == K) {            // DC and Nyquist bins of a real signal are real
-        L.z[f * PP + pr] = make_float2(ya.x, yb.x);
+    // both bins of a column pair in one access (see the store of rfft_kernel)
+    constexpr int PAIRB = (HMODE & kHalfSpectra) ? 8 : 16;
+    const bool whole = t0 + 2 * P <= nrows && ((in_fstride | part_stride) & 1) == 0 &&
+                       (reinterpret_cast<unsigned long long>(in) & (PAIRB - 1)) == 0;
+    auto bin2 = [&](long long e) -> float4 {
+      if constexpr (HMODE & kHalfSpectra) {
+        const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned*>(in) + e);
+        const float2 a = unpack_pair16<(HMODE & kHalfBf16) != 0>(raw.x), b = unpack_pair16<(HMODE & kHalfBf16) != 0>(raw.y);
+        return make_float4(a.x, a.y, b.x, b.y);
       } else {
-        L.z[f * PP + pr] = make_float2(ya.x - yb.y, ya.y + yb.x);
-        L.z[(K - f) * PP + pr] = make_float2(ya.x + yb.y, yb.x - ya.y);
+        return *reinterpret_cast<const float4*>(in + e);
+      }
+    };
+    if (whole) {
+#pragma unroll 4
+      for (int f = tid >> lgP; f < NF; f += fstep, s += sstep) {
+        float4 y = bin2(s);
+#pragma unroll 4
+        for (int part = 1; part < nparts; ++part) {
+          const float4 v = bin2(s + part * part_stride);
+          y.x += v.x; y.y += v.y; y.z += v.z; y.w += v.w;
+        }
+        if (f == 0 || 2 * f == K) {
+          L.z[f * PP + pr] = make_float2(y.x, y.z);
+        } else {
+          L.z[f * PP + pr] = make_float2(y.x - y.w, y.y + y.z);
+          L.z[(K - f) * PP + pr] = make_float2(y.x + y.w, y.z - y.y);
+        }
+      }
+    } else {
+#pragma unroll 4
+      for (int f = tid >> lgP; f < NF; f += fstep, s += sstep) {
+        float2 ya = bin(s, ok0);
+        float2 yb = bin(s + 1, ok1);
+        // partial sums: loads four parts ahead, additions in index order
+#pragma unroll 4
+        for (int part = 1; part < nparts; ++part) {
+          const long long sp = s + part * part_stride;
+          const float2 pa = bin(sp, ok0);
+          const float2 pb = bin(sp + 1, ok1);
+          ya.x += pa.x; ya.y += pa.y;
+          yb.x += pb.x; yb.y += pb.y;
+        }
+        if (f == 0 || 2 * f == K) {            // DC and Nyquist bins of a real signal are real
+          L.z[f * PP + pr] = make_float2(ya.x, yb.x);
+        } else {
+          L.z[f * PP + pr] = make_float2(ya.x - yb.y, ya.y + yb.x);
+          L.z[(K - f) * PP + pr] = make_float2(ya.x + yb.y, yb.x - ya.y);
+        }
       }
     }
   }
