@@ -114,10 +114,16 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
 
   for (int c = 0; c < nchunks; ++c) {
     const int j0 = jbeg + c * PT;
-    // rows b0 (real part) and b1 (imaginary part) of the chunk -> z[n][column j]
+    // rows b0 (real part) and b1 (imaginary part) of the chunk -> z[n][column j].  A step of one
+    // float4 along n is 8*PP words in the tile (8 banks modulo 32, PP odd) and a step of one
+    // column 2 words: GW lanes along n times 64/GW consecutive columns per wave spread the LDS
+    // stores over 16 banks (all lanes along n would share 4).  A wave stays inside one row, so
+    // that for batch 1 the waves of the absent row issue no loads.
+    constexpr int GW = K / 4 < 8 ? K / 4 : 8;
+    static_assert(PT % (64 / GW) == 0, "a wave-load must not straddle the two rows");
     for (int idx = tid; idx < 2 * PT * (K / 4); idx += NT) {
-      const int half = idx / (PT * (K / 4)), rem = idx % (PT * (K / 4));
-      const int col = rem / (K / 4), n = 4 * (rem % (K / 4));
+      const int gl = idx % GW, rest = idx / GW;
+      const int col = rest % PT, half = (rest / PT) & 1, n = 4 * ((rest / (2 * PT)) * GW + gl);
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (half < B && j0 + col < jend) v = *reinterpret_cast<const float4*>(x + (long long)half * ldx + (long long)(j0 + col) * K + n);
       lds_put(z, (n + 0) * PP + col, half, v.x);
