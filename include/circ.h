@@ -209,7 +209,7 @@ circ_status circ_fc_forward_f16(const void* w_hat, const void* x, const float* b
  * The same with bfloat16 (the upper 16 bits of an fp32, rounded to nearest even) as the storage
  * format: the range of fp32, so no bound on |x| * k, at 2^-8 per rounding instead of 2^-11
  * (about 5e-3 of the largest output).  A blob made by circ_precompute_spectra_bf16 serves
- * circ_fc_forward_bf16 only.
+ * circ_fc_forward_bf16 and circ_fc_backward_bf16 only.
  */
 size_t circ_spectra_bytes_bf16(int p, int q, int k);
 circ_status circ_precompute_spectra_bf16(const float* w, int p, int q, int k, void* w_hat, void* stream);
@@ -217,6 +217,29 @@ size_t circ_fc_workspace_bytes_bf16(int p, int q, int k, int batch);
 circ_status circ_fc_forward_bf16(const void* w_hat, const void* x, const float* bias, void* y,
                                  int p, int q, int k, int batch, int epilogue,
                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * FC backward with 16-bit storage (Algorithm 2 on the same 16-bit spectra): dy and x hold fp16
+ * (bf16) values, dx receives fp16 (bf16) values, dw receives the gradient of the block vectors
+ * in fp32 (the copy of the weights an optimiser updates is fp32; its new spectra come from
+ * circ_precompute_spectra_f16).  Layouts and orientation as for circ_fc_backward:
+ *   dx_j  = IFFT( (1/k) * sum_i conj(h(FFT w_ij)) o h(FFT dy_i) ),   rounded to 16 bits
+ *   dw_ij = IFFT( sum_b h(FFT dy_i) o conj(h(FFT x_j)) ),            h = rounding to 16 bits,
+ * all sums in fp32; the spectrum of dw stays fp32 (a sum over a long batch leaves the fp16
+ * range).  dx or dw may be NULL (not both); x may be NULL when dw is.  dx, dw are overwritten.
+ *   circ_fc_backward_workspace_bytes_f16   workspace size for the same arguments (0 if invalid)
+ * Errors as for circ_fc_backward: CIRC_EINVAL for bad dimensions, k not a power of two in
+ * 8..512, a NULL required pointer, pointers not 16-byte aligned or overlapping outputs;
+ * CIRC_EWORKSPACE for a short workspace; CIRC_EHIP for a failed launch.
+ */
+size_t circ_fc_backward_workspace_bytes_f16(int p, int q, int k, int batch);
+circ_status circ_fc_backward_f16(const void* w_hat, const void* x, const void* dy, void* dx, float* dw,
+                                 int p, int q, int k, int batch,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+size_t circ_fc_backward_workspace_bytes_bf16(int p, int q, int k, int batch);
+circ_status circ_fc_backward_bf16(const void* w_hat, const void* x, const void* dy, void* dx, float* dw,
+                                  int p, int q, int k, int batch,
+                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Bias gradient (Eq. 1: a = Wx + theta, so dL/dtheta is dL/da summed over everything but the

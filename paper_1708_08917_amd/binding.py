@@ -43,6 +43,10 @@ SIGNATURES = {
     "circ_fc_workspace_bytes_f16": (_c_size, [_c_int] * 4),
     "circ_fc_forward_f16": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_int, _c_int, _c_int, _c_int, _c_int,
                                      _c_ptr, _c_size, _c_ptr]),
+    "circ_fc_backward_workspace_bytes_f16": (_c_size, [_c_int] * 4),
+    "circ_fc_backward_f16": (_c_int, [_c_ptr] * 5 + [_c_int] * 4 + [_c_ptr, _c_size, _c_ptr]),
+    "circ_fc_backward_workspace_bytes_bf16": (_c_size, [_c_int] * 4),
+    "circ_fc_backward_bf16": (_c_int, [_c_ptr] * 5 + [_c_int] * 4 + [_c_ptr, _c_size, _c_ptr]),
     "circ_spectra_bytes_bf16": (_c_size, [_c_int] * 3),
     "circ_precompute_spectra_bf16": (_c_int, [_c_ptr, _c_int, _c_int, _c_int, _c_ptr, _c_ptr]),
     "circ_fc_workspace_bytes_bf16": (_c_size, [_c_int] * 4),
@@ -250,6 +254,27 @@ def circ_fc_forward_f16(w_hat, x, bias, y, p, q, k, epilogue=EPI_NONE, workspace
     _check(getattr(lib(), f"circ_fc_forward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), p, q, k, batch, epilogue,
                                                     _ptr(workspace), workspace.numel(), _stream()), f"circ_fc_forward_{sfx}")
     return y
+
+
+def circ_fc_backward_workspace_bytes_f16(p, q, k, batch) -> int:
+    return lib().circ_fc_backward_workspace_bytes_f16(p, q, k, batch)      # the same for both 16-bit formats
+
+
+def circ_fc_backward_f16(w_hat, x, dy, p, q, k, need_dx=True, need_dw=True, dx=None, dw=None, workspace=None):
+    """dy (and x when need_dw): fp16 or bf16.  Returns (dx of the same type or None, dw fp32 [p][q][k] or None)."""
+    sfx = _half_suffix(dy.dtype)
+    assert dy.is_contiguous() and (x is None or (x.is_contiguous() and x.dtype == dy.dtype))
+    batch = dy.shape[0]
+    if need_dx and dx is None:
+        dx = torch.empty(batch, q * k, dtype=dy.dtype, device=dy.device)
+    if need_dw and dw is None:
+        dw = torch.empty(p, q, k, dtype=torch.float32, device=dy.device)
+    if workspace is None:
+        workspace = torch.empty(max(1, circ_fc_backward_workspace_bytes_f16(p, q, k, batch)), dtype=torch.uint8, device=dy.device)
+    _check(getattr(lib(), f"circ_fc_backward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx) if need_dx else None,
+                                                     _ptr(dw) if need_dw else None, p, q, k, batch, _ptr(workspace),
+                                                     workspace.numel(), _stream()), f"circ_fc_backward_{sfx}")
+    return (dx if need_dx else None), (dw if need_dw else None)
 
 
 def circ_bias_grad(dy, db=None):

@@ -123,6 +123,9 @@ FftPlan plan_fft(int K, long long nrows) {
   if (TT < 1) TT = 1;
   int NT = P * TT;
   if (NT < 64) NT = 64;
+  // a launch that leaves CUs idle is bound by the latency of its loads and stores, which all
+  // threads share (the butterflies occupy R2 threads per column, the others skip them)
+  if (cdiv(pairs, P) <= 256 && NT < 256) NT = 256;
   if (NT < K / 4) NT = K / 4;   // the row loaders keep one float4 column per thread
   return FftPlan{P, NT, fft_tile_lds_bytes(K, P)};
 }
@@ -1104,7 +1107,7 @@ circ_status circ_bias_grad(const float* dy, float* db, long long outer, int chan
 
 }  // extern "C"
 
-// ---- half-width storage (16-bit values in memory, fp32 arithmetic): FC forward ---------------
+// ---- half-width storage (16-bit values in memory, fp32 arithmetic): FC forward and backward ----
 namespace {
 
 inline bool half_k(int k) { return is_pow2(k) && k >= 8 && k <= kMaxK; }
@@ -1112,14 +1115,14 @@ inline bool half_k(int k) { return is_pow2(k) && k >= 8 && k <= kMaxK; }
 // hmode: kHalfSpectra (fp32 rows in) or kHalfSpectra | kHalfRows; bf: bfloat16 instead of fp16
 template <int K>
 hipError_t launch_rfft_half_k(int hmode, bool bf, const void* in, void* out, const RowMap& map, long long nrows,
-                              long long out_fstride, float scale, hipStream_t s) {
+                              long long out_fstride, float scale, int conj, hipStream_t s) {
   FftPlan pl = plan_fft(K, nrows);
   dim3 grid((unsigned)cdiv(nrows, 2 * pl.P), 1);
   const float* fin = static_cast<const float*>(in);
   float2* fout = static_cast<float2*>(out);
 #define CIRC_RFFT_H(MODE)                                                                                              \
   hipLaunchKernelGGL((rfft_kernel<K, false, MODE>), grid, dim3(pl.NT), pl.lds, s, fin, fout, map, nrows, out_fstride, 0ll, \
-                     0ll, pl.P, scale, 0)
+                     0ll, pl.P, scale, conj)
   if (hmode == kHalfSpectra) {
     if (bf) CIRC_RFFT_H(kHalfSpectra | kHalfBf16);
     else CIRC_RFFT_H(kHalfSpectra);
@@ -1160,8 +1163,8 @@ hipError_t launch_irfft_half_k(bool bf, const void* in, void* out, const RowMap&
   }
 
 hipError_t launch_rfft_half(int k, int hmode, bool bf, const void* in, void* out, const RowMap& map, long long nrows,
-                            long long out_fstride, float scale, hipStream_t s) {
-#define CALL(KK) launch_rfft_half_k<KK>(hmode, bf, in, out, map, nrows, out_fstride, scale, s)
+                            long long out_fstride, float scale, hipStream_t s, int conj = 0) {
+#define CALL(KK) launch_rfft_half_k<KK>(hmode, bf, in, out, map, nrows, out_fstride, scale, conj, s)
   CIRC_DISPATCH_HALF_K(k, CALL)
 #undef CALL
 }
@@ -1178,7 +1181,7 @@ inline size_t half_spectrum_bytes(int k, long long rows) { return align_up(size_
 
 size_t spectra_bytes_half(int p, int q, int k) {
   if (p <= 0 || q <= 0 || !half_k(k) || (long long)p * q > (1ll << 31) - 1) return 0;
-  return half_spectrum_bytes(k, (long long)p * q);
+  return 2 * half_spectrum_bytes(k, (long long)p * q);   // W^[f][i][j] and conj(W^)[f][j][i]
 }
 
 circ_status precompute_spectra_half(bool bf, const float* w, int p, int q, int k, void* w_hat, void* stream) {
@@ -1191,6 +1194,11 @@ circ_status precompute_spectra_half(bool bf, const float* w, int p, int q, int k
   // row id = i*q + j -> w[i][j][:]
   RowMap mw{q, p, (long long)k, (long long)q * k, 0, 1};
   if (launch_rfft_half(k, kHalfSpectra, bf, w, w_hat, mw, rows, rows, 1.0f, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return CIRC_EHIP;
+  // conj(W^)[f][j][i] for backward-data (the transposed grid): row id = j*p + i -> w[i][j][:]
+  RowMap mt{p, q, (long long)q * k, (long long)k, 0, 1};
+  void* sec2 = static_cast<char*>(w_hat) + half_spectrum_bytes(k, rows);
+  if (launch_rfft_half(k, kHalfSpectra, bf, w, sec2, mt, rows, rows, 1.0f, static_cast<hipStream_t>(stream), 1) != hipSuccess)
     return CIRC_EHIP;
   return CIRC_OK;
 }
@@ -1242,6 +1250,92 @@ circ_status fc_forward_half(bool bf, const void* w_hat, const void* x, const flo
   return CIRC_OK;
 }
 
+
+// Slices of the batch for the weight-gradient contraction: enough workgroups to cover the chip,
+// each slice a multiple of 64 and at least 128 long, at most 16 slices.
+inline int half_dw_slices(int p, int q, int k, int batch) {
+  const long long tiles = (long long)(k / 2 + 1) * cdiv(p, 64) * cdiv(q, 64);
+  int ks = 1;
+  while (ks < 16 && tiles * ks < 512 && cdiv(batch, ks * 2) >= 128) ks *= 2;
+  return ks;
+}
+inline int half_dw_slice_len(int batch, int ks) { return int(align_up(size_t(cdiv(batch, ks)), 64)); }
+inline size_t half_dw_part_elems(int p, int q, int k) {
+  return align_up(size_t(k / 2 + 1) * size_t(p) * q * sizeof(float2), 256) / sizeof(float2);
+}
+
+// workspace: dY^[f][b][i] and dX^[f][j][b] (backward-data), X^[f][j][b] and dY^[f][i][b] (batch
+// fastest, for the weight gradient), the fp32 partial spectra of the weight gradient
+size_t fc_backward_workspace_bytes_half(int p, int q, int k, int batch) {
+  if (!fc_dims_ok(p, q, k, batch) || !half_k(k)) return 0;
+  return 2 * half_spectrum_bytes(k, (long long)q * batch) + 2 * half_spectrum_bytes(k, (long long)p * batch) +
+         size_t(half_dw_slices(p, q, k, batch)) * half_dw_part_elems(p, q, k) * sizeof(float2);
+}
+
+circ_status fc_backward_half(bool bf, const void* w_hat, const void* x, const void* dy, void* dx, float* dw, int p, int q,
+                             int k, int batch, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!fc_dims_ok(p, q, k, batch) || !half_k(k)) return CIRC_EINVAL;
+  if (!w_hat || !dy || (!dx && !dw) || (dw && !x)) return CIRC_EINVAL;
+  if (!aligned16(w_hat) || !aligned16(dy) || !aligned16(x) || !aligned16(dx) || !aligned16(dw)) return CIRC_EINVAL;
+  const size_t xbytes = size_t(batch) * q * k * sizeof(__half), ybytes = size_t(batch) * p * k * sizeof(__half);
+  const size_t wbytes = size_t(p) * q * k * sizeof(float);
+  if (dx && (overlaps(dx, xbytes, dy, ybytes) || (x && overlaps(dx, xbytes, x, xbytes)))) return CIRC_EINVAL;
+  if (dw && (overlaps(dw, wbytes, dy, ybytes) || overlaps(dw, wbytes, x, xbytes) || (dx && overlaps(dw, wbytes, dx, xbytes))))
+    return CIRC_EINVAL;
+  if (!workspace || workspace_bytes < fc_backward_workspace_bytes_half(p, q, k, batch)) return CIRC_EWORKSPACE;
+  if (!aligned16(workspace)) return CIRC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int NF = k / 2 + 1;
+  const long long xrows = (long long)q * batch, yrows = (long long)p * batch, wrows = (long long)p * q;
+  const size_t xs = half_spectrum_bytes(k, xrows), ys = half_spectrum_bytes(k, yrows);
+  char* ws = static_cast<char*>(workspace);
+  __half2* dyh = reinterpret_cast<__half2*>(ws);                  // dY^[f][b][i]
+  __half2* dxh = reinterpret_cast<__half2*>(ws + ys);             // dX^[f][j][b]
+  __half2* xt = reinterpret_cast<__half2*>(ws + ys + xs);         // X^[f][j][b]
+  __half2* dyt = reinterpret_cast<__half2*>(ws + ys + 2 * xs);    // dY^[f][i][b]
+  float2* wpart = reinterpret_cast<float2*>(ws + 2 * ys + 2 * xs);
+  const int hm = kHalfSpectra | kHalfRows;
+#define CIRC_CGEMM_H(KERNEL, GRID, KD, ...)                                                             \
+  do {                                                                                                \
+    if ((KD) % 4 == 0) {                                                                              \
+      if (bf) hipLaunchKernelGGL((KERNEL<true, true>), GRID, dim3(256), 0, s, __VA_ARGS__);           \
+      else hipLaunchKernelGGL((KERNEL<true, false>), GRID, dim3(256), 0, s, __VA_ARGS__);             \
+    } else {                                                                                          \
+      if (bf) hipLaunchKernelGGL((KERNEL<false, true>), GRID, dim3(256), 0, s, __VA_ARGS__);          \
+      else hipLaunchKernelGGL((KERNEL<false, false>), GRID, dim3(256), 0, s, __VA_ARGS__);            \
+    }                                                                                                 \
+  } while (0)
+  if (dx) {
+    // backward-data = the forward route on the transposed, conjugated grid (Algorithm 2):
+    // dX^[f][j][b] = (1/k) sum_i conj(W^)[f][j][i] dY^[f][b][i]
+    RowMap mdy{p, batch, (long long)k, (long long)p * k, 0, 1};
+    if (launch_rfft_half(k, hm, bf, dy, dyh, mdy, yrows, yrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
+    const __half2* wt = reinterpret_cast<const __half2*>(static_cast<const char*>(w_hat) + half_spectrum_bytes(k, wrows));
+    dim3 grid((unsigned)cdiv(batch, 128), (unsigned)cdiv(q, 64), (unsigned)NF);
+    CIRC_CGEMM_H(cgemm_h_kernel, grid, p, wt, dyh, dxh, q, batch, p, wrows, yrows, xrows, 1.0f / float(k));
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+    RowMap mdx{batch, q, (long long)q * k, (long long)k, 0, 1};
+    if (launch_irfft_half(k, bf, dxh, dx, mdx, xrows, xrows, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
+  }
+  if (dw) {
+    // dW^[f][i][j] = sum_b dY^[f][i][b] conj(X^[f][j][b]): both operands with the batch fastest
+    RowMap mxt{batch, q, (long long)q * k, (long long)k, 0, 1};
+    if (launch_rfft_half(k, hm, bf, x, xt, mxt, xrows, xrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
+    RowMap myt{batch, p, (long long)p * k, (long long)k, 0, 1};
+    if (launch_rfft_half(k, hm, bf, dy, dyt, myt, yrows, yrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
+    const int ks = half_dw_slices(p, q, k, batch), klen = half_dw_slice_len(batch, ks);
+    const long long ps = (long long)half_dw_part_elems(p, q, k);
+    dim3 grid((unsigned)(cdiv(q, 64) * ks), (unsigned)cdiv(p, 64), (unsigned)NF);
+    CIRC_CGEMM_H(cgemm_h_dw_kernel, grid, batch, dyt, xt, wpart, p, q, batch, yrows, xrows, wrows, 1.0f, klen, ps);
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+    RowMap mw{q, p, (long long)k, (long long)q * k, 0, 1};
+    if (launch_irfft(k, false, wpart, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, ks, ps) != hipSuccess)
+      return CIRC_EHIP;
+  }
+#undef CIRC_CGEMM_H
+  return CIRC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1263,6 +1357,16 @@ circ_status circ_fc_forward_f16(const void* w_hat, const void* x, const float* b
 circ_status circ_fc_forward_bf16(const void* w_hat, const void* x, const float* bias, void* y, int p, int q, int k,
                                  int batch, int epilogue, void* workspace, size_t workspace_bytes, void* stream) {
   return fc_forward_half(true, w_hat, x, bias, y, p, q, k, batch, epilogue, workspace, workspace_bytes, stream);
+}
+size_t circ_fc_backward_workspace_bytes_f16(int p, int q, int k, int batch) { return fc_backward_workspace_bytes_half(p, q, k, batch); }
+size_t circ_fc_backward_workspace_bytes_bf16(int p, int q, int k, int batch) { return fc_backward_workspace_bytes_half(p, q, k, batch); }
+circ_status circ_fc_backward_f16(const void* w_hat, const void* x, const void* dy, void* dx, float* dw, int p, int q, int k,
+                                 int batch, void* workspace, size_t workspace_bytes, void* stream) {
+  return fc_backward_half(false, w_hat, x, dy, dx, dw, p, q, k, batch, workspace, workspace_bytes, stream);
+}
+circ_status circ_fc_backward_bf16(const void* w_hat, const void* x, const void* dy, void* dx, float* dw, int p, int q, int k,
+                                  int batch, void* workspace, size_t workspace_bytes, void* stream) {
+  return fc_backward_half(true, w_hat, x, dy, dx, dw, p, q, k, batch, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -132,4 +132,82 @@ __global__ __launch_bounds__(256) void cgemm_h_kernel(const __half2* __restrict_
   }
 }
 
+// Backward-weights (Algorithm 2: the spectrum of dL/dw_ij is the sum over the batch of
+// FFT(dL/da_i) o conj(FFT(x_j))):
+//   C[f][m][n] = scale * sum_k A[f][m][k] conj(B[f][n][k]),   k = the batch index,
+// with Re C = A . (br, bi, ...) and Im C = A . (-bi, br, ...).  The output is narrow (p x q block
+// pairs) and the reduction long, so a workgroup owns a 64 x 64 tile (wave w the 32 x 32 quadrant
+// (w % 2, w / 2): every staged row feeds two waves) and the reduction is cut into slices of `klen`
+// values (a multiple of 64): blockIdx.x = slice * ceil(N/64) + column tile, slice ks writes its
+// partial sums to C + ks*part_stride, to be added later in index order.  C is fp32: a sum over a
+// long batch leaves the fp16 range, and the output is small.
+template <bool VEC, bool BF>
+__global__ __launch_bounds__(256) void cgemm_h_dw_kernel(const __half2* __restrict__ A, const __half2* __restrict__ B,
+                                                         float2* __restrict__ C, int M, int N, int Kd, long long sA,
+                                                         long long sB, long long sC, float scale, int klen,
+                                                         long long part_stride) {
+  __shared__ __attribute__((aligned(16))) __half2 lds[(64 + 64) * kHPitch];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int ntn = (N + 63) / 64, ks = blockIdx.x / ntn;
+  const int f = blockIdx.z, m0 = blockIdx.y * 64, nb0 = (blockIdx.x - ks * ntn) * 64;
+  const int kbeg = ks * klen, kend = min(Kd, kbeg + klen);
+  const int r = lane & 31, h = lane >> 5, wm = wave & 1, wn = wave >> 1;
+  const __half2* Af = A + f * sA;
+  const __half2* Bf = B + f * sB;
+  hfloatx16 cr, ci;
+#pragma unroll
+  for (int t = 0; t < 16; ++t) { cr[t] = 0.f; ci[t] = 0.f; }
+  const bool wave_active = m0 + 32 * wm < M && nb0 + 32 * wn < N;   // the others only help with the staging
+  for (int kc = kbeg; kc < kend; kc += kHChunk) {
+    __syncthreads();                             // the previous chunk has been read
+    if constexpr (VEC) {
+      uint4 v[8];
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int e = it * 256 + tid, row = e >> 4, j = kc + 4 * (e & 15);
+        const __half2* src = row < 64 ? Af + (long long)min(m0 + row, M - 1) * Kd : Bf + (long long)min(nb0 + row - 64, N - 1) * Kd;
+        v[it] = *reinterpret_cast<const uint4*>(src + min(j, Kd - 4));
+      }
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int e = it * 256 + tid, row = e >> 4, j = kc + 4 * (e & 15);
+        *reinterpret_cast<uint4*>(lds + row * kHPitch + 4 * (e & 15)) = j < kend ? v[it] : make_uint4(0u, 0u, 0u, 0u);
+      }
+    } else {
+      for (int e = tid; e < (64 + 64) * kHChunk; e += 256) {
+        const int row = e >> 6, j = kc + (e & 63);
+        const __half2* src = row < 64 ? Af + (long long)min(m0 + row, M - 1) * Kd : Bf + (long long)min(nb0 + row - 64, N - 1) * Kd;
+        const unsigned v = reinterpret_cast<const unsigned*>(src)[min(j, Kd - 1)];
+        reinterpret_cast<unsigned*>(lds)[row * kHPitch + (e & 63)] = j < kend ? v : 0u;
+      }
+    }
+    __syncthreads();
+    if (wave_active) {
+      const __half2* fa = lds + (32 * wm + r) * kHPitch + 4 * h;
+      const __half2* fb = lds + (64 + 32 * wn + r) * kHPitch + 4 * h;
+      const int nsteps = min(kHChunk, kend - kc + 7) / 8;   // whole steps of 8 that hold anything
+#pragma unroll
+      for (int s = 0; s < kHChunk / 8; ++s) {
+        if (s < nsteps) {                        // wave-uniform
+          const uint4 va = *reinterpret_cast<const uint4*>(fa + 8 * s);
+          const uint4 vb = *reinterpret_cast<const uint4*>(fb + 8 * s);
+          // (bi, br) after the swap inside each word; the sign goes to the half that now holds bi
+          const uint4 vim = make_uint4(__builtin_amdgcn_alignbit(vb.x, vb.x, 16) ^ 0x8000u, __builtin_amdgcn_alignbit(vb.y, vb.y, 16) ^ 0x8000u,
+                                       __builtin_amdgcn_alignbit(vb.z, vb.z, 16) ^ 0x8000u, __builtin_amdgcn_alignbit(vb.w, vb.w, 16) ^ 0x8000u);
+          cr = mfma16<BF>(va, vb, cr);
+          ci = mfma16<BF>(va, vim, ci);
+        }
+      }
+    }
+  }
+  const int col = nb0 + 32 * wn + r;
+  if (!wave_active || col >= N) return;
+  float2* c = C + ks * part_stride + f * sC + col;
+#pragma unroll
+  for (int t = 0; t < 16; ++t) {
+    const int row = m0 + 32 * wm + 8 * (t / 4) + 4 * h + (t % 4);
+    if (row < M) c[(long long)row * N] = make_float2(scale * cr[t], scale * ci[t]);
+  }
+}
+
 }  // namespace circ

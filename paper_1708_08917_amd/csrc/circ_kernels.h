@@ -276,19 +276,34 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
       }
     };
     if (whole) {
-#pragma unroll 4
-      for (int f = tid >> lgP; f < NF; f += fstep, s += sstep) {
-        float4 y = bin2(s);
-#pragma unroll 4
+      // GB bins at a time: their loads (and those of every further partial spectrum) are issued
+      // together, so that a thread waits for memory once per group and part, not once per load.
+      // Bins past the end reload the last one and are dropped.
+      constexpr int GB = 8;
+      for (int f0 = tid >> lgP; f0 < NF; f0 += GB * fstep) {
+        long long e[GB];
+        float4 y[GB];
+#pragma unroll
+        for (int g = 0; g < GB; ++g) e[g] = (long long)min(f0 + g * fstep, NF - 1) * in_fstride + rid;
+#pragma unroll
+        for (int g = 0; g < GB; ++g) y[g] = bin2(e[g]);
         for (int part = 1; part < nparts; ++part) {
-          const float4 v = bin2(s + part * part_stride);
-          y.x += v.x; y.y += v.y; y.z += v.z; y.w += v.w;
+          float4 v[GB];
+#pragma unroll
+          for (int g = 0; g < GB; ++g) v[g] = bin2(e[g] + part * part_stride);
+#pragma unroll
+          for (int g = 0; g < GB; ++g) { y[g].x += v[g].x; y[g].y += v[g].y; y[g].z += v[g].z; y[g].w += v[g].w; }
         }
-        if (f == 0 || 2 * f == K) {
-          L.z[f * PP + pr] = make_float2(y.x, y.z);
-        } else {
-          L.z[f * PP + pr] = make_float2(y.x - y.w, y.y + y.z);
-          L.z[(K - f) * PP + pr] = make_float2(y.x + y.w, y.z - y.y);
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+          const int f = f0 + g * fstep;
+          if (f >= NF) break;
+          if (f == 0 || 2 * f == K) {
+            L.z[f * PP + pr] = make_float2(y[g].x, y[g].z);
+          } else {
+            L.z[f * PP + pr] = make_float2(y[g].x - y[g].w, y[g].y + y[g].z);
+            L.z[(K - f) * PP + pr] = make_float2(y[g].x + y[g].w, y[g].z - y[g].y);
+          }
         }
       }
     } else {

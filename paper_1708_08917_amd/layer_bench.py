@@ -89,6 +89,13 @@ def bench_fc(cfg, reps, backward=False):
         # against dx + dw + precompute of the new weights
         tsg = _time(lambda: B.circ_fc_sgd_step(wh, xd, dy, 0.0, cfg.p, cfg.q, cfg.k, True, dx, ws), r, 3)
         print(f"{cfg.name}: sgd step {tsg:9.2f} us/call (backward + precompute: {tb + tp:.2f})", flush=True)
+        if cfg.k >= 8 and cfg.k & (cfg.k - 1) == 0:
+            dy16, dx16 = dy.half(), torch.empty_like(x16)
+            wsb = torch.empty(max(1, B.circ_fc_backward_workspace_bytes_f16(cfg.p, cfg.q, cfg.k, cfg.batch)), dtype=torch.uint8, device=DEV)
+            tbh = _time(lambda: B.circ_fc_backward_f16(wh16, x16, dy16, cfg.p, cfg.q, cfg.k, True, True, dx16, dw, wsb), r, 3)
+            tdxh = _time(lambda: B.circ_fc_backward_f16(wh16, x16, dy16, cfg.p, cfg.q, cfg.k, True, False, dx16, None, wsb), r, 3)
+            tdwh = _time(lambda: B.circ_fc_backward_f16(wh16, x16, dy16, cfg.p, cfg.q, cfg.k, False, True, None, dw, wsb), r, 3)
+            print(f"{cfg.name}: backward, fp16 storage {tbh:9.2f} us/call (dx only {tdxh:.2f}, dw only {tdwh:.2f})", flush=True)
 
 
 def bench_chain(cfgs, reps):

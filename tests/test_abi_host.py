@@ -194,7 +194,7 @@ def test_sgd_step_and_export_argument_errors():
 
 def test_f16_argument_errors():
     big = 1 << 28
-    assert B.lib().circ_spectra_bytes_f16(64, 64, 64) == 33 * 64 * 64 * 4
+    assert B.lib().circ_spectra_bytes_f16(64, 64, 64) == 2 * 33 * 64 * 64 * 4   # both orientations of the grid
     assert B.lib().circ_spectra_bytes_f16(64, 64, 4) == 0          # k below 8
     assert B.lib().circ_spectra_bytes_f16(64, 64, 96) == 0         # not a power of two
     assert B.lib().circ_spectra_bytes_f16(0, 64, 64) == 0
@@ -204,7 +204,7 @@ def test_f16_argument_errors():
     assert pre(None, 2, 2, 8, A, None) == B.CIRC_EINVAL
     assert pre(A, 2, 2, 12, A + big, None) == B.CIRC_EINVAL
     assert pre(A, 2, 2, 8, A, None) == B.CIRC_EINVAL              # output aliases input
-    assert B.lib().circ_spectra_bytes_bf16(64, 64, 64) == 33 * 64 * 64 * 4
+    assert B.lib().circ_spectra_bytes_bf16(64, 64, 64) == 2 * 33 * 64 * 64 * 4
     assert B.lib().circ_fc_workspace_bytes_bf16(64, 64, 64, 64) == 2 * 33 * 64 * 64 * 4
     assert B.lib().circ_precompute_spectra_bf16(A, 2, 2, 12, A + big, None) == B.CIRC_EINVAL
     for f in (B.lib().circ_fc_forward_f16, B.lib().circ_fc_forward_bf16):
@@ -219,6 +219,33 @@ def test_f16_argument_errors():
         assert call(epi=8) == B.CIRC_EINVAL
         assert call(y=A + big) == B.CIRC_EINVAL                       # in place
         assert call(x=A + big + 2) == B.CIRC_EINVAL                   # misaligned
+        assert call(wsb=16) == B.CIRC_EWORKSPACE
+
+
+def test_f16_backward_argument_errors():
+    big = 1 << 28
+    spec = 33 * 64 * 64 * 4
+    # two spectra each of x and dy, one fp32 partial spectrum of dw per slice of the batch
+    assert B.circ_fc_backward_workspace_bytes_f16(64, 64, 64, 64) == 4 * spec + 2 * spec
+    assert B.lib().circ_fc_backward_workspace_bytes_bf16(64, 64, 64, 64) == 6 * spec
+    assert B.circ_fc_backward_workspace_bytes_f16(64, 64, 64, 1024) == 4 * 16 * spec + 8 * 2 * spec   # 8 slices of 128
+    assert B.circ_fc_backward_workspace_bytes_f16(64, 64, 24, 64) == 0
+    assert B.circ_fc_backward_workspace_bytes_f16(64, 0, 64, 64) == 0
+    for f in (B.lib().circ_fc_backward_f16, B.lib().circ_fc_backward_bf16):
+
+        def call(w_hat=A, x=A + big, dy=A + 2 * big, dx=A + 3 * big, dw=A + 4 * big, p=2, q=2, k=8, batch=2, wsp=A + 5 * big,
+                 wsb=1 << 30):
+            return f(w_hat, x, dy, dx, dw, p, q, k, batch, wsp, wsb, None)
+
+        assert call(k=4) == B.CIRC_EINVAL
+        assert call(k=48) == B.CIRC_EINVAL
+        assert call(dy=None) == B.CIRC_EINVAL
+        assert call(dx=None, dw=None) == B.CIRC_EINVAL               # nothing to compute
+        assert call(x=None) == B.CIRC_EINVAL                         # dw needs x
+        assert call(dx=A + 2 * big) == B.CIRC_EINVAL                 # dx aliases dy
+        assert call(dw=A + 3 * big) == B.CIRC_EINVAL                 # dw aliases dx
+        assert call(dy=A + 2 * big + 2) == B.CIRC_EINVAL             # misaligned
+        assert call(batch=0) == B.CIRC_EINVAL
         assert call(wsb=16) == B.CIRC_EWORKSPACE
 
 

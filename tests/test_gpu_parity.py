@@ -468,6 +468,50 @@ def test_fc_forward_half_configs(cfg, dtype):
     check_half(got[:, sel], ref, f"{cfg} block rows {rows}", dtype)
 
 
+# Backward with 16-bit storage.  dx passes the same four roundings as y; dw (fp32 out, fp32
+# spectrum) only the two of the operand spectra.  Batches that are not multiples of 4 take the
+# element-wise staging of the contraction, long batches cut the reduction into slices.
+@pytest.mark.parametrize("dtype", HALF_DTYPES)
+@pytest.mark.parametrize("p,q,k,batch", [(1, 1, 8, 1), (3, 5, 16, 7), (5, 3, 64, 33), (2, 4, 256, 10), (33, 34, 8, 70),
+                                         (4, 6, 128, 68), (2, 3, 512, 5), (7, 9, 32, 2), (2, 3, 16, 700), (3, 2, 8, 1025),
+                                         (70, 130, 8, 260), (64, 64, 64, 64), (65, 8, 32, 129), (3, 72, 128, 40)])
+def test_fc_backward_half_shapes(p, q, k, batch, dtype):
+    w, x, _ = rand_fc(p, q, k, batch, bias=False)
+    dy = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
+    xt, xr = to_half(x, dtype)
+    dyt, dyr = to_half(dy, dtype)
+    wh = B.circ_precompute_spectra_f16(G.dev(w), dtype=dtype)
+    what = f"{p}x{q} k={k} B={batch}"
+    dx, dw = B.circ_fc_backward_f16(wh, xt, dyt, p, q, k)
+    assert dx.dtype == dtype and dw.dtype == torch.float32
+    check_half(dx.float().cpu().numpy(), O.fc_backward_dx(w, dyr), "dx " + what, dtype)
+    check_half(dw.cpu().numpy(), O.fc_backward_dw(xr, dyr, k), "dw " + what, dtype)
+    # one result at a time gives the same values
+    dx1, _ = B.circ_fc_backward_f16(wh, None, dyt, p, q, k, need_dw=False)
+    _, dw1 = B.circ_fc_backward_f16(wh, xt, dyt, p, q, k, need_dx=False)
+    assert torch.equal(dx1, dx) and torch.equal(dw1, dw)
+
+
+@pytest.mark.parametrize("dtype", HALF_DTYPES)
+def test_cfg5_backward_half(dtype):
+    c = synth.CFG5
+    w, x, _ = synth.fc_inputs(c, 0)
+    dy = synth.fc_upstream_grad(c, 0)
+    xt, xr = to_half(x, dtype)
+    dyt, dyr = to_half(dy, dtype)
+    wh = B.circ_precompute_spectra_f16(G.dev(w), dtype=dtype)
+    dx, dw = B.circ_fc_backward_f16(wh, xt, dyt, c.p, c.q, c.k)
+    dx, dw = dx.float().cpu().numpy(), dw.cpu().numpy()
+    pick = np.random.default_rng(5)
+    cols = sorted(pick.choice(c.q, 4, replace=False).tolist())
+    pairs = [(int(i), int(j)) for i, j in zip(pick.integers(0, c.p, 64), pick.integers(0, c.q, 64))]
+    k = c.k
+    dx_s = np.concatenate([dx[:, j * k:(j + 1) * k] for j in cols], axis=1)
+    dw_s = np.stack([dw[i, j] for (i, j) in pairs])
+    check_half(dx_s, O.fc_backward_dx(w, dyr, block_cols=cols), "cfg5 dx", dtype)
+    check_half(dw_s, O.fc_backward_dw(xr, dyr, k, pairs=pairs), "cfg5 dw", dtype)
+
+
 # ---- stride > 1 and even filter sizes (Eq. 6 is the stride-1 case) ---------------------------
 @pytest.mark.parametrize("N,p,q,k,H,W,r,pad,stride", [
     (2, 2, 3, 8, 9, 8, 3, 1, 2), (3, 1, 2, 16, 7, 7, 3, 0, 2), (2, 4, 4, 64, 28, 28, 3, 1, 2), (2, 2, 2, 64, 13, 12, 3, 1, 3),

@@ -21,7 +21,8 @@ DRIVER = textwrap.dedent(r'''
     L = ctypes.CDLL(sys.argv[1])
     c_int, c_size, c_ptr, c_ll, c_f = ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_float
     for n in ["circ_spectra_bytes", "circ_fc_workspace_bytes", "circ_conv_workspace_bytes",
-              "circ_conv_backward_workspace_bytes", "circ_spectra_bytes_f16", "circ_fc_workspace_bytes_f16"]:
+              "circ_conv_backward_workspace_bytes", "circ_spectra_bytes_f16", "circ_fc_workspace_bytes_f16",
+              "circ_fc_backward_workspace_bytes_f16"]:
         getattr(L, n).restype = c_size
     A, big = 0x10000, 1 << 36
     P = [c_ptr(A + i * big) for i in range(6)]
@@ -41,6 +42,8 @@ DRIVER = textwrap.dedent(r'''
             assert L.circ_fc_forward_f16(P[0], P[1], None, P[2], p, q, k, b, 0, P[3], ws, None) == 0
             assert L.circ_precompute_spectra_bf16(P[0], p, q, k, P[1], None) == 0
             assert L.circ_fc_forward_bf16(P[0], P[1], None, P[2], p, q, k, b, 0, P[3], ws, None) == 0
+            assert L.circ_fc_backward_f16(P[0], P[1], P[2], P[3], P[4], p, q, k, b, P[5], ws, None) == 0
+            assert L.circ_fc_backward_bf16(P[0], P[1], P[2], P[3], P[4], p, q, k, b, P[5], ws, None) == 0
     for (N, Ci, Co, H, W, r, pad, k) in [(32, 256, 256, 28, 28, 3, 1, 64), (2, 384, 384, 13, 13, 3, 1, 96), (1, 8, 8, 5, 5, 3, 0, 4),
                                          (3, 16, 32, 9, 4, 1, 0, 16), (2, 128, 64, 7, 32, 5, 2, 64), (2, 64, 64, 224, 224, 3, 1, 64),
                                          (1, 64, 64, 6, 2000, 3, 1, 64), (2, 6, 9, 8, 1, 3, 1, 3)]:
@@ -66,6 +69,9 @@ DRIVER = textwrap.dedent(r'''
         L.circ_fc_forward(P[0], P[1], None, P[2], p, q, k, b, 0, P[3], ws, None)
         L.circ_fc_forward_f16(P[0], P[1], None, P[2], p, q, k, b, 0, P[3], ws, None)
         L.circ_fc_forward_bf16(P[0], P[1], None, P[2], p, q, k, b, 0, P[3], ws, None)
+        L.circ_fc_backward_workspace_bytes_f16(p, q, k, b)
+        L.circ_fc_backward_f16(P[0], P[1], P[2], P[3], P[4], p, q, k, b, P[5], ws, None)
+        L.circ_fc_backward_bf16(P[0], P[1], P[2], None, P[4], p, q, k, b, P[5], ws, None)
         L.circ_fc_backward(P[0], P[1], P[2], P[3], P[4], p, q, k, b, P[5], ws, None)
         L.circ_fc_backward(P[0], P[1], P[2], None, P[4], p, q, k, b, P[5], ws, None)
         L.circ_fc_sgd_step(P[0], P[1], P[2], None, c_f(0.1), p, q, k, b, P[5], ws, None)
