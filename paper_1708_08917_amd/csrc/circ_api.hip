@@ -1177,6 +1177,22 @@ hipError_t launch_irfft_half(int k, bool bf, const void* in, void* out, const Ro
 #undef CALL
 }
 
+// C[f][m][n] = scale * sum_k A[f][m][k] B[f][n][k] on 16-bit operands; TB: B is stored [f][k][n]
+template <bool TB>
+hipError_t launch_cgemm_h(bool bf, hipStream_t s, int NF, const __half2* A, const __half2* B, __half2* C, int M, int N, int Kd,
+                          long long sA, long long sB, long long sC, float scale) {
+  dim3 grid((unsigned)cdiv(N, 128), (unsigned)cdiv(M, 64), (unsigned)NF);
+  const bool vec = Kd % 4 == 0 && (!TB || N % 4 == 0);
+  if (vec) {
+    if (bf) hipLaunchKernelGGL((cgemm_h_kernel<true, true, TB>), grid, dim3(256), 0, s, A, B, C, M, N, Kd, sA, sB, sC, scale);
+    else hipLaunchKernelGGL((cgemm_h_kernel<true, false, TB>), grid, dim3(256), 0, s, A, B, C, M, N, Kd, sA, sB, sC, scale);
+  } else {
+    if (bf) hipLaunchKernelGGL((cgemm_h_kernel<false, true, TB>), grid, dim3(256), 0, s, A, B, C, M, N, Kd, sA, sB, sC, scale);
+    else hipLaunchKernelGGL((cgemm_h_kernel<false, false, TB>), grid, dim3(256), 0, s, A, B, C, M, N, Kd, sA, sB, sC, scale);
+  }
+  return hipGetLastError();
+}
+
 inline size_t half_spectrum_bytes(int k, long long rows) { return align_up(size_t(k / 2 + 1) * size_t(rows) * sizeof(__half2), 256); }
 
 size_t spectra_bytes_half(int p, int q, int k) {
@@ -1229,20 +1245,9 @@ circ_status fc_forward_half(bool bf, const void* w_hat, const void* x, const flo
   RowMap mx{q, batch, (long long)k, (long long)q * k, 0, 1};
   if (launch_rfft_half(k, kHalfSpectra | kHalfRows, bf, x, xh, mx, xrows, xrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
   // Y^[f][i][b] = (1/k) sum_j W^[f][i][j] X^[f][b][j]
-  dim3 grid((unsigned)cdiv(batch, 128), (unsigned)cdiv(p, 64), (unsigned)NF);
   const __half2* wh = static_cast<const __half2*>(w_hat);
-#define CIRC_CGEMM_H(VEC, BF)                                                                                             \
-  hipLaunchKernelGGL((cgemm_h_kernel<VEC, BF>), grid, dim3(256), 0, s, wh, xh, yh, p, batch, q, (long long)p * q, xrows, yrows, \
-                     1.0f / float(k))
-  if (q % 4 == 0) {
-    if (bf) CIRC_CGEMM_H(true, true);
-    else CIRC_CGEMM_H(true, false);
-  } else {
-    if (bf) CIRC_CGEMM_H(false, true);
-    else CIRC_CGEMM_H(false, false);
-  }
-#undef CIRC_CGEMM_H
-  if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  if (launch_cgemm_h<false>(bf, s, NF, wh, xh, yh, p, batch, q, (long long)p * q, xrows, yrows, 1.0f / float(k)) != hipSuccess)
+    return CIRC_EHIP;
   RowMap my{batch, p, (long long)p * k, (long long)k, 0, 1};
   if (launch_irfft_half(k, bf, yh, y, my, yrows, yrows, 1.0f, use_bias ? bias : nullptr, batch,
                         (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) != hipSuccess)
@@ -1295,25 +1300,26 @@ circ_status fc_backward_half(bool bf, const void* w_hat, const void* x, const vo
   __half2* dyt = reinterpret_cast<__half2*>(ws + ys + 2 * xs);    // dY^[f][i][b]
   float2* wpart = reinterpret_cast<float2*>(ws + 2 * ys + 2 * xs);
   const int hm = kHalfSpectra | kHalfRows;
-#define CIRC_CGEMM_H(KERNEL, GRID, KD, ...)                                                             \
-  do {                                                                                                \
-    if ((KD) % 4 == 0) {                                                                              \
-      if (bf) hipLaunchKernelGGL((KERNEL<true, true>), GRID, dim3(256), 0, s, __VA_ARGS__);           \
-      else hipLaunchKernelGGL((KERNEL<true, false>), GRID, dim3(256), 0, s, __VA_ARGS__);             \
-    } else {                                                                                          \
-      if (bf) hipLaunchKernelGGL((KERNEL<false, true>), GRID, dim3(256), 0, s, __VA_ARGS__);          \
-      else hipLaunchKernelGGL((KERNEL<false, false>), GRID, dim3(256), 0, s, __VA_ARGS__);            \
-    }                                                                                                 \
-  } while (0)
+  // dY^[f][i][b] (batch fastest) serves the weight gradient directly and, transposed on its way
+  // into the contraction, backward-data as well: dy is transformed once when both are wanted.
+  // Backward-data alone takes dY^[f][b][i], which its contraction reads without the transposition.
+  if (dw) {
+    RowMap myt{batch, p, (long long)p * k, (long long)k, 0, 1};
+    if (launch_rfft_half(k, hm, bf, dy, dyt, myt, yrows, yrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
+  }
   if (dx) {
     // backward-data = the forward route on the transposed, conjugated grid (Algorithm 2):
-    // dX^[f][j][b] = (1/k) sum_i conj(W^)[f][j][i] dY^[f][b][i]
-    RowMap mdy{p, batch, (long long)k, (long long)p * k, 0, 1};
-    if (launch_rfft_half(k, hm, bf, dy, dyh, mdy, yrows, yrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
+    // dX^[f][j][b] = (1/k) sum_i conj(W^)[f][j][i] dY^[f][.][.]
     const __half2* wt = reinterpret_cast<const __half2*>(static_cast<const char*>(w_hat) + half_spectrum_bytes(k, wrows));
-    dim3 grid((unsigned)cdiv(batch, 128), (unsigned)cdiv(q, 64), (unsigned)NF);
-    CIRC_CGEMM_H(cgemm_h_kernel, grid, p, wt, dyh, dxh, q, batch, p, wrows, yrows, xrows, 1.0f / float(k));
-    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+    if (dw) {
+      if (launch_cgemm_h<true>(bf, s, NF, wt, dyt, dxh, q, batch, p, wrows, yrows, xrows, 1.0f / float(k)) != hipSuccess)
+        return CIRC_EHIP;
+    } else {
+      RowMap mdy{p, batch, (long long)k, (long long)p * k, 0, 1};
+      if (launch_rfft_half(k, hm, bf, dy, dyh, mdy, yrows, yrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
+      if (launch_cgemm_h<false>(bf, s, NF, wt, dyh, dxh, q, batch, p, wrows, yrows, xrows, 1.0f / float(k)) != hipSuccess)
+        return CIRC_EHIP;
+    }
     RowMap mdx{batch, q, (long long)q * k, (long long)k, 0, 1};
     if (launch_irfft_half(k, bf, dxh, dx, mdx, xrows, xrows, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
   }
@@ -1321,18 +1327,21 @@ circ_status fc_backward_half(bool bf, const void* w_hat, const void* x, const vo
     // dW^[f][i][j] = sum_b dY^[f][i][b] conj(X^[f][j][b]): both operands with the batch fastest
     RowMap mxt{batch, q, (long long)q * k, (long long)k, 0, 1};
     if (launch_rfft_half(k, hm, bf, x, xt, mxt, xrows, xrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
-    RowMap myt{batch, p, (long long)p * k, (long long)k, 0, 1};
-    if (launch_rfft_half(k, hm, bf, dy, dyt, myt, yrows, yrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
     const int ks = half_dw_slices(p, q, k, batch), klen = half_dw_slice_len(batch, ks);
     const long long ps = (long long)half_dw_part_elems(p, q, k);
     dim3 grid((unsigned)(cdiv(q, 64) * ks), (unsigned)cdiv(p, 64), (unsigned)NF);
-    CIRC_CGEMM_H(cgemm_h_dw_kernel, grid, batch, dyt, xt, wpart, p, q, batch, yrows, xrows, wrows, 1.0f, klen, ps);
+    if (batch % 4 == 0) {
+      if (bf) hipLaunchKernelGGL((cgemm_h_dw_kernel<true, true>), grid, dim3(256), 0, s, dyt, xt, wpart, p, q, batch, yrows, xrows, wrows, 1.0f, klen, ps);
+      else hipLaunchKernelGGL((cgemm_h_dw_kernel<true, false>), grid, dim3(256), 0, s, dyt, xt, wpart, p, q, batch, yrows, xrows, wrows, 1.0f, klen, ps);
+    } else {
+      if (bf) hipLaunchKernelGGL((cgemm_h_dw_kernel<false, true>), grid, dim3(256), 0, s, dyt, xt, wpart, p, q, batch, yrows, xrows, wrows, 1.0f, klen, ps);
+      else hipLaunchKernelGGL((cgemm_h_dw_kernel<false, false>), grid, dim3(256), 0, s, dyt, xt, wpart, p, q, batch, yrows, xrows, wrows, 1.0f, klen, ps);
+    }
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
     RowMap mw{q, p, (long long)k, (long long)q * k, 0, 1};
     if (launch_irfft(k, false, wpart, dw, mw, wrows, wrows, 1.0f / float(k), nullptr, 1, 0, s, ks, ps) != hipSuccess)
       return CIRC_EHIP;
   }
-#undef CIRC_CGEMM_H
   return CIRC_OK;
 }
 

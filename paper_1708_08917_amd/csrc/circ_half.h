@@ -54,10 +54,14 @@ __device__ __forceinline__ hfloatx16 mfma16(uint4 a, uint4 b, hfloatx16 acc) {
 // each, and the same lines come back for the next steps; that version ran at the L2 line rate.
 // VEC: Kd is a multiple of 4 (16-byte pieces are whole or entirely past the end of a row);
 // otherwise the chunk is staged element by element.  Values past Kd are staged as zeros.
+// TB: B is stored with n fastest, B[f][k][n] (row pitch N), and is transposed on its way into
+// LDS: a wave-load takes 16 values of k times four 16-byte groups along n, so that the four
+// 4-byte LDS stores of a lane fall on 16 consecutive banks per group and two groups 16 banks
+// apart.  VEC then also requires N to be a multiple of 4.
 constexpr int kHChunk = 64;                      // complex values of the reduction per chunk
 constexpr int kHPitch = kHChunk + 4;             // LDS row pitch in complex values (272 bytes)
 
-template <bool VEC, bool BF>
+template <bool VEC, bool BF, bool TB = false>
 __global__ __launch_bounds__(256) void cgemm_h_kernel(const __half2* __restrict__ A, const __half2* __restrict__ B,
                                                       __half2* __restrict__ C, int M, int N, int Kd, long long sA,
                                                       long long sB, long long sC, float scale) {
@@ -78,24 +82,52 @@ __global__ __launch_bounds__(256) void cgemm_h_kernel(const __half2* __restrict_
     if constexpr (VEC) {
       // piece e of the chunk: row e / 16, 16-byte piece e % 16 of the row's 256 bytes; rows of A
       // first, then rows of B (rows past M or N repeat the last one: their results are not stored)
-      uint4 v[12];
+      constexpr int NIT = TB ? 4 : 12;             // direct rows: A only, or A and B
+      uint4 v[NIT];
 #pragma unroll
-      for (int it = 0; it < 12; ++it) {
+      for (int it = 0; it < NIT; ++it) {
         const int e = it * 256 + tid, row = e >> 4, j = kc + 4 * (e & 15);
         const __half2* src = row < 64 ? Af + (long long)min(m0 + row, M - 1) * Kd : Bf + (long long)min(nb0 + row - 64, N - 1) * Kd;
         v[it] = *reinterpret_cast<const uint4*>(src + min(j, Kd - 4));
       }
+      uint4 vt[TB ? 8 : 1];
+      if constexpr (TB) {
 #pragma unroll
-      for (int it = 0; it < 12; ++it) {
+        for (int it = 0; it < 8; ++it) {
+          const int combo = it * 4 + wave, kk = kc + 16 * (combo & 3) + (lane & 15), n = nb0 + 4 * (4 * (combo >> 2) + (lane >> 4));
+          vt[it] = *reinterpret_cast<const uint4*>(Bf + (long long)min(kk, Kd - 1) * N + min(n, N - 4));
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
         const int e = it * 256 + tid, row = e >> 4, j = kc + 4 * (e & 15);
         *reinterpret_cast<uint4*>(lds + row * kHPitch + 4 * (e & 15)) = j < Kd ? v[it] : make_uint4(0u, 0u, 0u, 0u);
       }
+      if constexpr (TB) {
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+          const int combo = it * 4 + wave, kl = 16 * (combo & 3) + (lane & 15), nl = 4 * (4 * (combo >> 2) + (lane >> 4));
+          const uint4 w = kc + kl < Kd ? vt[it] : make_uint4(0u, 0u, 0u, 0u);
+          unsigned* d = reinterpret_cast<unsigned*>(lb) + nl * kHPitch + kl;
+          d[0] = w.x;
+          d[kHPitch] = w.y;
+          d[2 * kHPitch] = w.z;
+          d[3 * kHPitch] = w.w;
+        }
+      }
     } else {
-      for (int e = tid; e < (64 + 128) * kHChunk; e += 256) {
+      for (int e = tid; e < (TB ? 64 : 64 + 128) * kHChunk; e += 256) {
         const int row = e >> 6, j = kc + (e & 63);
         const __half2* src = row < 64 ? Af + (long long)min(m0 + row, M - 1) * Kd : Bf + (long long)min(nb0 + row - 64, N - 1) * Kd;
         const unsigned v = reinterpret_cast<const unsigned*>(src)[min(j, Kd - 1)];
         reinterpret_cast<unsigned*>(lds)[row * kHPitch + (e & 63)] = j < Kd ? v : 0u;
+      }
+      if constexpr (TB) {
+        for (int e = tid; e < 128 * kHChunk; e += 256) {
+          const int nl = e & 127, kl = e >> 7;
+          const unsigned v = reinterpret_cast<const unsigned*>(Bf)[(long long)min(kc + kl, Kd - 1) * N + min(nb0 + nl, N - 1)];
+          reinterpret_cast<unsigned*>(lb)[nl * kHPitch + kl] = kc + kl < Kd ? v : 0u;
+        }
       }
     }
     __syncthreads();

@@ -486,10 +486,13 @@ def test_fc_backward_half_shapes(p, q, k, batch, dtype):
     assert dx.dtype == dtype and dw.dtype == torch.float32
     check_half(dx.float().cpu().numpy(), O.fc_backward_dx(w, dyr), "dx " + what, dtype)
     check_half(dw.cpu().numpy(), O.fc_backward_dw(xr, dyr, k), "dw " + what, dtype)
-    # one result at a time gives the same values
+    # one result at a time: dw is the same computation; dx then reads the spectra of dy in the
+    # other order, in which a row shares its packed transform with a different partner row, so
+    # the 16-bit spectra can differ in their last bit
     dx1, _ = B.circ_fc_backward_f16(wh, None, dyt, p, q, k, need_dw=False)
     _, dw1 = B.circ_fc_backward_f16(wh, xt, dyt, p, q, k, need_dx=False)
-    assert torch.equal(dx1, dx) and torch.equal(dw1, dw)
+    assert torch.equal(dw1, dw)
+    check_half(dx1.float().cpu().numpy(), O.fc_backward_dx(w, dyr), "dx alone " + what, dtype)
 
 
 @pytest.mark.parametrize("dtype", HALF_DTYPES)
