@@ -8,7 +8,7 @@
 // of contiguous rows and goes to LDS as it is; v_mfma_f32_32x32x2_f32 then takes, per lane,
 // element (k = lane/32, m or n = lane%32) of a slab, which is one 8-byte LDS read (re, im).
 // A workgroup of four waves owns a (32*FM*WM) x (32*WN) tile of one frequency; every wave owns
-// FM 32x32 sub-tiles.  A complex product is four real accumulations.
+// FM 32x32 sub-tiles.  A complex product is three real accumulations (Gauss, see multiply).
 //
 // The DC and the Nyquist bin of a real signal are real (Sec. 4.1: the spectrum of a real
 // sequence is Hermitian), so these two frequencies share one tile: its operands carry
@@ -174,7 +174,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
   const float2* pb = sb + (lane >> 5) * TN + wn * 32 + (lane & 31);
 
   // accumulator layout of a 32x32 tile: column = lane % 32; row = 8*(r/4) + 4*(lane/32) + r%4
-  auto store_tile = [&](const Tile& T, const floatx16 (&oR)[FM], const floatx16 (&oI)[FM]) {
+  // o1, o2, o3: the three sums of products (see multiply)
+  auto store_tile = [&](const Tile& T, const floatx16 (&o1)[FM], const floatx16 (&o2)[FM], const floatx16 (&o3)[FM]) {
     const int n = T.n0 + wn * 32 + (lane & 31);
     const int mb = T.m0 + wm * 32 * FM + 4 * (lane >> 5);
     const unsigned base = unsigned(mb) * unsigned(N) + unsigned(n);
@@ -186,10 +187,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
         if (mb + dm < M && n < N) {
           const unsigned off = base + unsigned(dm) * unsigned(N);
           if (T.shared) {
-            T.c0[off] = make_float2(oR[fm][rr], 0.f);
-            T.c1[off] = make_float2(oI[fm][rr], 0.f);
+            T.c0[off] = make_float2(o1[fm][rr], 0.f);
+            T.c1[off] = make_float2(o3[fm][rr], 0.f);
           } else {
-            T.c0[off] = make_float2(oR[fm][rr], oI[fm][rr]);
+            T.c0[off] = make_float2(o1[fm][rr] - o3[fm][rr], o1[fm][rr] + o2[fm][rr]);
           }
         }
       }
@@ -197,30 +198,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
 
   // One k-slab of the current tile: registers -> LDS, prefetch of the next slab (of this tile or
   // of the next one), 8 k-steps on the matrix cores.
-  floatx16 accR[FM], accI[FM];
+  floatx16 acc1[FM], acc2[FM], acc3[FM];
   auto zero_acc = [&]() {
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) { accR[fm][i] = 0.f; accI[fm][i] = 0.f; }
+      for (int i = 0; i < 16; ++i) { acc1[fm][i] = 0.f; acc2[fm][i] = 0.f; acc3[fm][i] = 0.f; }
   };
   auto multiply = [&](bool sh) {
+    // Three real products per complex one (Gauss): with b.y already conjugated when CONJ_B,
+    //   K1 += (ar + ai) br,  K2 += ar (bi - br),  K3 += ai (br + bi);  Re = K1 - K3,  Im = K1 + K2.
     // One instruction sequence for both kinds of tile (two would make the compiler move the
-    // accumulators between register files around the branch): the shared tile multiplies
-    // (a.x, b.x) into accR and (a.y, b.y) into accI and feeds zeros to the other two.
+    // accumulators between register files around the branch): the shared tile holds two real
+    // bins in (x, y) and multiplies (a.x, b.x) into K1 and (a.y, b.y) into K3, zeros into K2.
 #pragma unroll
     for (int kk = 0; kk < KT / 2; ++kk) {
       float2 b = pb[2 * kk * TN];
       if (CONJ_B) b.y = -b.y;
+      const float b2 = b.y - b.x, b3 = sh ? (CONJ_B ? -b.y : b.y) : b.x + b.y;
 #pragma unroll
       for (int fm = 0; fm < FM; ++fm) {
         const float2 a = pa[kk * KSA + fm * FSA];
-        // (ar + i ai)(br + i bi) = (ar br - ai bi) + i (ar bi + ai br)
-        const float a2 = sh ? (CONJ_B ? -a.y : a.y) : a.x, a3 = sh ? 0.f : -a.y, a4 = sh ? 0.f : a.y;
-        accR[fm] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, accR[fm], 0, 0, 0);
-        accI[fm] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2, b.y, accI[fm], 0, 0, 0);
-        accR[fm] = __builtin_amdgcn_mfma_f32_32x32x2f32(a3, b.y, accR[fm], 0, 0, 0);
-        accI[fm] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4, b.x, accI[fm], 0, 0, 0);
+        const float a1 = sh ? a.x : a.x + a.y, a2 = sh ? 0.f : a.x;
+        acc1[fm] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b.x, acc1[fm], 0, 0, 0);
+        acc2[fm] = __builtin_amdgcn_mfma_f32_32x32x2f32(a2, b2, acc2[fm], 0, 0, 0);
+        acc3[fm] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b3, acc3[fm], 0, 0, 0);
       }
     }
   };
@@ -249,9 +251,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
     // tile would also wait for these stores (loads and stores complete in one order), and all
     // workgroups reach that point together.
     for (unsigned t = first + 1; t < last; ++t) {
-      floatx16 outR[FM], outI[FM];
+      floatx16 out1[FM], out2[FM], out3[FM];
 #pragma unroll
-      for (int fm = 0; fm < FM; ++fm) { outR[fm] = accR[fm]; outI[fm] = accI[fm]; }
+      for (int fm = 0; fm < FM; ++fm) { out1[fm] = acc1[fm]; out2[fm] = acc2[fm]; out3[fm] = acc3[fm]; }
       const Tile done = cur;
       cur = nxt;
       const bool more2 = t + 1 < last;
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
       zero_acc();
       stage();
       __syncthreads();
-      store_tile(done, outR, outI);
+      store_tile(done, out1, out2, out3);
       if (1 < nslab) fetch(cur, 1);
       else if (more2) fetch(nxt, 0);
       multiply(cur.shared);
@@ -267,7 +269,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
       run_slabs(cur, nxt, more2, 1);
     }
   }
-  store_tile(cur, accR, accI);
+  store_tile(cur, acc1, acc2, acc3);
 }
 
 }  // namespace circ

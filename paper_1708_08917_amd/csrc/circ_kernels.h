@@ -404,7 +404,7 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
 // Per-frequency complex GEMM on the fp32 MFMA units, one wave per output tile:
 //   C[f][m][n] = sum_k A[f][k][m] * B[f][k][n]        (B conjugated if CONJ_B)
 // A is stored with m fastest, B and C with n fastest, so every operand load is one
-// contiguous run per k.  A complex product is four real MFMA accumulations.
+// contiguous run per k.  A complex product is three real MFMA accumulations (see below).
 // TILE = 32 uses v_mfma_f32_32x32x2_f32, TILE = 16 uses v_mfma_f32_16x16x4_f32.
 // Operand loads run one group of U k-steps ahead of the matrix instructions.
 // Split-K: blockIdx.x = ks*ntn + (tile along n); slice ks reduces k in [ks*kchunk, (ks+1)*kchunk)
@@ -429,9 +429,13 @@ __global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
   const int kk = lane / TILE, mm = lane % TILE;
   const int am = min(m0 + mm, M - 1);
   const int bn = min(n0 + mm, N - 1);
-  accv accR, accI;
+  // Three real products per complex one instead of four (Gauss):
+  //   K1 = (ar + ai) br,  K2 = ar (bi - br),  K3 = ai (br + bi):  Re = K1 - K3,  Im = K1 + K2
+  // (conj(b): bi -> -bi).  The three operand sums are vector additions per loaded value; the
+  // matrix cores, which bound this kernel, do a quarter less work.
+  accv acc1, acc2, acc3;
 #pragma unroll
-  for (int r = 0; r < NACC; ++r) { accR[r] = 0.f; accI[r] = 0.f; }
+  for (int r = 0; r < NACC; ++r) { acc1[r] = 0.f; acc2[r] = 0.f; acc3[r] = 0.f; }
 
   float2 a[U], b[U], an[U], bn2[U];
   auto load_group = [&](int k0, float2 (&ga)[U], float2 (&gb)[U]) {
@@ -451,19 +455,16 @@ __global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
     if (k0 + U * KS < kend) load_group(k0 + U * KS, an, bn2);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      // (ar + i ai)(br + i bi) = (ar br - ai bi) + i (ar bi + ai br); conj(b): bi -> -bi
-      float a_rr = a[u].x, a_ii = CONJ_B ? a[u].y : -a[u].y;
-      float a_ri = CONJ_B ? -a[u].x : a[u].x, a_ir = a[u].y;
+      const float bi = CONJ_B ? -b[u].y : b[u].y;
+      const float a_s = a[u].x + a[u].y, b_d = bi - b[u].x, b_s = b[u].x + bi;
       if constexpr (TILE == 32) {
-        accR = __builtin_amdgcn_mfma_f32_32x32x2f32(a_rr, b[u].x, accR, 0, 0, 0);
-        accI = __builtin_amdgcn_mfma_f32_32x32x2f32(a_ri, b[u].y, accI, 0, 0, 0);
-        accR = __builtin_amdgcn_mfma_f32_32x32x2f32(a_ii, b[u].y, accR, 0, 0, 0);
-        accI = __builtin_amdgcn_mfma_f32_32x32x2f32(a_ir, b[u].x, accI, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_s, b[u].x, acc1, 0, 0, 0);
+        acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u].x, b_d, acc2, 0, 0, 0);
+        acc3 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u].y, b_s, acc3, 0, 0, 0);
       } else {
-        accR = __builtin_amdgcn_mfma_f32_16x16x4f32(a_rr, b[u].x, accR, 0, 0, 0);
-        accI = __builtin_amdgcn_mfma_f32_16x16x4f32(a_ri, b[u].y, accI, 0, 0, 0);
-        accR = __builtin_amdgcn_mfma_f32_16x16x4f32(a_ii, b[u].y, accR, 0, 0, 0);
-        accI = __builtin_amdgcn_mfma_f32_16x16x4f32(a_ir, b[u].x, accI, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a_s, b[u].x, acc1, 0, 0, 0);
+        acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].x, b_d, acc2, 0, 0, 0);
+        acc3 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u].y, b_s, acc3, 0, 0, 0);
       }
     }
 #pragma unroll
@@ -478,7 +479,7 @@ __global__ __launch_bounds__(64) void cgemm_kernel(const float2* __restrict__ A,
     if constexpr (TILE == 32) i = 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
     else i = 4 * (lane / 16) + r;
     i += m0;
-    if (i < M && j < N) C[(long long)i * N + j] = make_float2(accR[r], accI[r]);
+    if (i < M && j < N) C[(long long)i * N + j] = make_float2(acc1[r] - acc3[r], acc1[r] + acc2[r]);
   }
 }
 
