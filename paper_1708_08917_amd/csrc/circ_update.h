@@ -59,23 +59,36 @@ __global__ __launch_bounds__(256) void spectra_step_kernel(const float2* __restr
   const bool real_bin = f == 0 || 2 * f == K;
   const long long sec = ((long long)g * NF + f) * p * q;
   const float2* sp = src + (long long)f * src_fstride + (long long)g * src_gstride;
+  // the four elements of a thread: their loads of one partial spectrum are issued together (one
+  // wait per part, not per load); elements outside the grid reload element 0 and are dropped
+  long long e[4];
+  bool ok[4];
+  float2 G[4];
 #pragma unroll
   for (int m = 0; m < 4; ++m) {
     const int i = i0 + ty + 8 * m, j = j0 + tx;
-    if (i < p && j < q) {
-      const long long e = (long long)i * q + j;
-      float2 G = sp[e];
-      for (int s = 1; s < nparts; ++s) {
-        const float2 v = sp[s * part_stride + e];
-        G.x += v.x;
-        G.y += v.y;
-      }
-      if (real_bin) G.y = 0.f;
-      float2 b = bwd[sec + e];
-      b.x -= a * G.x;
-      b.y += a * G.y;
-      bwd[sec + e] = b;
-      tile[ty + 8 * m][tx] = G;
+    ok[m] = i < p && j < q;
+    e[m] = ok[m] ? (long long)i * q + j : 0;
+  }
+#pragma unroll
+  for (int m = 0; m < 4; ++m) G[m] = sp[e[m]];
+#pragma unroll 2
+  for (int s = 1; s < nparts; ++s) {
+    float2 v[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) v[m] = sp[s * part_stride + e[m]];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) { G[m].x += v[m].x; G[m].y += v[m].y; }
+  }
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    if (ok[m]) {
+      if (real_bin) G[m].y = 0.f;
+      float2 b = bwd[sec + e[m]];
+      b.x -= a * G[m].x;
+      b.y += a * G[m].y;
+      bwd[sec + e[m]] = b;
+      tile[ty + 8 * m][tx] = G[m];
     }
   }
   __syncthreads();
