@@ -295,13 +295,14 @@ hipError_t ensure_lds(Kern kern, size_t bytes, bool& done) {
 }
 
 // ONE: all q input blocks fit one chunk of the kernel (no double buffering of the operands).
-template <int K, int IT, int NP, int NT, bool ONE>
+// HM: 0 fp32, 1 fp16, 2 bfloat16 storage (wf, x, y then point to the 16-bit data).
+template <int K, int IT, int NP, int NT, bool ONE, int HM>
 hipError_t launch_fused_v(const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
                           int relu, hipStream_t s) {
   using Sh = FusedShape<K, IT, NP, NT>;
   static_assert((4096 / K) % Sh::JC == 0, "packed weights are padded to chunks of 4096/K input blocks");
   static bool opted_in = false;
-  if (ensure_lds(&fc_fused_kernel<K, IT, NP, NT, ONE>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
+  if (ensure_lds(&fc_fused_kernel<K, IT, NP, NT, ONE, HM>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
   const int n_it = (int)cdiv(p, IT), n_bt = (int)cdiv(batch, 2 * NP);
   // Split the tile grid over the 8 XCDs as xa x (8/xa) rectangles; pick the split that
   // minimises the bytes every XCD pulls into its own L2 (weight tiles + x rows).
@@ -313,16 +314,16 @@ hipError_t launch_fused_v(const float4* wf, const float* x, const float* bias, f
     if (wbytes + xbytes < best) { best = wbytes + xbytes; xa = cand; }
   }
   const long long grid = 8 * cdiv(n_it, xa) * cdiv(n_bt, 8 / xa);
-  hipLaunchKernelGGL((fc_fused_kernel<K, IT, NP, NT, ONE>), dim3((unsigned)grid), dim3(NT), Sh::LDS_BYTES, s, wf, x, bias,
+  hipLaunchKernelGGL((fc_fused_kernel<K, IT, NP, NT, ONE, HM>), dim3((unsigned)grid), dim3(NT), Sh::LDS_BYTES, s, wf, x, bias,
                      y, p, q, batch, n_it, fused_q2p(q, K), xa, relu);
   return hipGetLastError();
 }
 
-template <int K, int IT, int NP, int NT>
+template <int K, int IT, int NP, int NT, int HM>
 hipError_t launch_fused_t(const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
                           int relu, hipStream_t s) {
-  if (q <= FusedShape<K, IT, NP, NT>::JC) return launch_fused_v<K, IT, NP, NT, true>(wf, x, bias, y, p, q, batch, relu, s);
-  return launch_fused_v<K, IT, NP, NT, false>(wf, x, bias, y, p, q, batch, relu, s);
+  if (q <= FusedShape<K, IT, NP, NT>::JC) return launch_fused_v<K, IT, NP, NT, true, HM>(wf, x, bias, y, p, q, batch, relu, s);
+  return launch_fused_v<K, IT, NP, NT, false, HM>(wf, x, bias, y, p, q, batch, relu, s);
 }
 
 // Packed batch pairs per workgroup: two when that still leaves at least 256 tiles (one per
@@ -336,19 +337,32 @@ inline int fused_np(int p, int k, int batch) {
 #define CIRC_NT128 512
 #endif
 
-hipError_t launch_fused(int k, const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
-                        int relu, hipStream_t s) {
+template <int HM>
+hipError_t launch_fused_h(int k, const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
+                          int relu, hipStream_t s) {
   const int np = fused_np(p, k, batch);
   switch (k) {
-    case 32: return launch_fused_t<32, 16, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
-    case 64: return np == 2 ? launch_fused_t<64, 8, 2, 512>(wf, x, bias, y, p, q, batch, relu, s)
-                            : launch_fused_t<64, 8, 1, 512>(wf, x, bias, y, p, q, batch, relu, s);
-    case 128: return np == 2 ? launch_fused_t<128, 8, 2, CIRC_NT128>(wf, x, bias, y, p, q, batch, relu, s)
-                             : launch_fused_t<128, 8, 1, CIRC_NT128>(wf, x, bias, y, p, q, batch, relu, s);
-    case 256: return np == 2 ? launch_fused_t<256, 8, 2, 256>(wf, x, bias, y, p, q, batch, relu, s)
-                             : launch_fused_t<256, 8, 1, 256>(wf, x, bias, y, p, q, batch, relu, s);
+    case 32: return launch_fused_t<32, 16, 1, 256, HM>(wf, x, bias, y, p, q, batch, relu, s);
+    case 64: return np == 2 ? launch_fused_t<64, 8, 2, 512, HM>(wf, x, bias, y, p, q, batch, relu, s)
+                            : launch_fused_t<64, 8, 1, 512, HM>(wf, x, bias, y, p, q, batch, relu, s);
+    case 128: return np == 2 ? launch_fused_t<128, 8, 2, CIRC_NT128, HM>(wf, x, bias, y, p, q, batch, relu, s)
+                             : launch_fused_t<128, 8, 1, CIRC_NT128, HM>(wf, x, bias, y, p, q, batch, relu, s);
+    case 256: return np == 2 ? launch_fused_t<256, 8, 2, 256, HM>(wf, x, bias, y, p, q, batch, relu, s)
+                             : launch_fused_t<256, 8, 1, 256, HM>(wf, x, bias, y, p, q, batch, relu, s);
     default: return hipErrorInvalidValue;
   }
+}
+hipError_t launch_fused(int k, const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
+                        int relu, hipStream_t s) {
+  return launch_fused_h<0>(k, wf, x, bias, y, p, q, batch, relu, s);
+}
+// 16-bit storage: wf = operands packed by pack_fused_half_kernel, x and y 16-bit values
+hipError_t launch_fused_half(bool bf, int k, const void* wf, const void* x, const float* bias, void* y, int p, int q,
+                             int batch, int relu, hipStream_t s) {
+  const float4* w4 = static_cast<const float4*>(wf);
+  const float* xf = static_cast<const float*>(x);
+  float* yf = static_cast<float*>(y);
+  return bf ? launch_fused_h<2>(k, w4, xf, bias, yf, p, q, batch, relu, s) : launch_fused_h<1>(k, w4, xf, bias, yf, p, q, batch, relu, s);
 }
 
 // Upper bound, in MiB, of the operand bytes all workgroups of the fused kernel pull through
@@ -1195,9 +1209,27 @@ hipError_t launch_cgemm_h(bool bf, hipStream_t s, int NF, const __half2* A, cons
 
 inline size_t half_spectrum_bytes(int k, long long rows) { return align_up(size_t(k / 2 + 1) * size_t(rows) * sizeof(__half2), 256); }
 
+// bytes of the fused kernel's 16-bit operand section for a p x q grid (0 where that kernel does not apply)
+inline size_t half_fused_bytes(int p, int q, int k) {
+  if (fused_it(k) == 0) return 0;
+  return align_up(size_t(fused_igp(p, k)) * fused_q2p(q, k) * (k / 32) * 64 * sizeof(uint2), 256);
+}
+// 16-bit blob: W^[f][i][j], conj(W^)[f][j][i], then the fused kernel's operand order of either
+struct HalfBlob { size_t fwd, bwd, fused_fwd, fused_bwd, total; };
+inline HalfBlob half_blob(int p, int q, int k) {
+  HalfBlob b;
+  const size_t sec = half_spectrum_bytes(k, (long long)p * q);
+  b.fwd = 0;
+  b.bwd = sec;
+  b.fused_fwd = 2 * sec;
+  b.fused_bwd = b.fused_fwd + half_fused_bytes(p, q, k);
+  b.total = b.fused_bwd + half_fused_bytes(q, p, k);
+  return b;
+}
+
 size_t spectra_bytes_half(int p, int q, int k) {
   if (p <= 0 || q <= 0 || !half_k(k) || (long long)p * q > (1ll << 31) - 1) return 0;
-  return 2 * half_spectrum_bytes(k, (long long)p * q);   // W^[f][i][j] and conj(W^)[f][j][i]
+  return half_blob(p, q, k).total;
 }
 
 circ_status precompute_spectra_half(bool bf, const float* w, int p, int q, int k, void* w_hat, void* stream) {
@@ -1216,6 +1248,21 @@ circ_status precompute_spectra_half(bool bf, const float* w, int p, int q, int k
   void* sec2 = static_cast<char*>(w_hat) + half_spectrum_bytes(k, rows);
   if (launch_rfft_half(k, kHalfSpectra, bf, w, sec2, mt, rows, rows, 1.0f, static_cast<hipStream_t>(stream), 1) != hipSuccess)
     return CIRC_EHIP;
+  if (fused_it(k) != 0) {
+    // rearrangements of the two sections for the fused kernel (forward and backward-data)
+    const HalfBlob hb = half_blob(p, q, k);
+    char* base = static_cast<char*>(w_hat);
+    const int FG = k / 32;
+    for (int dir = 0; dir < 2; ++dir) {
+      const int pp = dir ? q : p, qq = dir ? p : q;
+      const int igp = fused_igp(pp, k), q2p = fused_q2p(qq, k);
+      const long long total = (long long)igp * q2p * FG * 64;
+      hipLaunchKernelGGL(pack_fused_half_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                         reinterpret_cast<const unsigned*>(base + (dir ? hb.bwd : hb.fwd)),
+                         reinterpret_cast<uint2*>(base + (dir ? hb.fused_bwd : hb.fused_fwd)), pp, qq, k, igp, q2p);
+      if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+    }
+  }
   return CIRC_OK;
 }
 
@@ -1237,6 +1284,13 @@ circ_status fc_forward_half(bool bf, const void* w_hat, const void* x, const flo
   if (!workspace || workspace_bytes < fc_workspace_bytes_half(p, q, k, batch)) return CIRC_EWORKSPACE;
   if (!aligned16(workspace)) return CIRC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (use_fused_forward(p, q, k, batch)) {
+    // one launch: 16-bit loads of x and of the packed operands, fp32 inside, 16-bit store of y
+    const void* wfu = static_cast<const char*>(w_hat) + half_blob(p, q, k).fused_fwd;
+    return launch_fused_half(bf, k, wfu, x, use_bias ? bias : nullptr, y, p, q, batch, (epilogue & CIRC_EPI_RELU) ? 1 : 0, s) == hipSuccess
+               ? CIRC_OK
+               : CIRC_EHIP;
+  }
   const int NF = k / 2 + 1;
   const long long xrows = (long long)q * batch, yrows = (long long)p * batch;
   __half2* xh = static_cast<__half2*>(workspace);
@@ -1310,18 +1364,25 @@ circ_status fc_backward_half(bool bf, const void* w_hat, const void* x, const vo
   if (dx) {
     // backward-data = the forward route on the transposed, conjugated grid (Algorithm 2):
     // dX^[f][j][b] = (1/k) sum_i conj(W^)[f][j][i] dY^[f][.][.]
-    const __half2* wt = reinterpret_cast<const __half2*>(static_cast<const char*>(w_hat) + half_spectrum_bytes(k, wrows));
-    if (dw) {
-      if (launch_cgemm_h<true>(bf, s, NF, wt, dyt, dxh, q, batch, p, wrows, yrows, xrows, 1.0f / float(k)) != hipSuccess)
+    const HalfBlob hb = half_blob(p, q, k);
+    const __half2* wt = reinterpret_cast<const __half2*>(static_cast<const char*>(w_hat) + hb.bwd);
+    if (use_fused_forward(q, p, k, batch)) {
+      // small problems: the fused kernel on the transposed grid's operands, one launch
+      if (launch_fused_half(bf, k, static_cast<const char*>(w_hat) + hb.fused_bwd, dy, nullptr, dx, q, p, batch, 0, s) != hipSuccess)
         return CIRC_EHIP;
     } else {
-      RowMap mdy{p, batch, (long long)k, (long long)p * k, 0, 1};
-      if (launch_rfft_half(k, hm, bf, dy, dyh, mdy, yrows, yrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
-      if (launch_cgemm_h<false>(bf, s, NF, wt, dyh, dxh, q, batch, p, wrows, yrows, xrows, 1.0f / float(k)) != hipSuccess)
-        return CIRC_EHIP;
+      if (dw) {
+        if (launch_cgemm_h<true>(bf, s, NF, wt, dyt, dxh, q, batch, p, wrows, yrows, xrows, 1.0f / float(k)) != hipSuccess)
+          return CIRC_EHIP;
+      } else {
+        RowMap mdy{p, batch, (long long)k, (long long)p * k, 0, 1};
+        if (launch_rfft_half(k, hm, bf, dy, dyh, mdy, yrows, yrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
+        if (launch_cgemm_h<false>(bf, s, NF, wt, dyh, dxh, q, batch, p, wrows, yrows, xrows, 1.0f / float(k)) != hipSuccess)
+          return CIRC_EHIP;
+      }
+      RowMap mdx{batch, q, (long long)q * k, (long long)k, 0, 1};
+      if (launch_irfft_half(k, bf, dxh, dx, mdx, xrows, xrows, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
     }
-    RowMap mdx{batch, q, (long long)q * k, (long long)k, 0, 1};
-    if (launch_irfft_half(k, bf, dxh, dx, mdx, xrows, xrows, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
   }
   if (dw) {
     // dW^[f][i][j] = sum_b dY^[f][i][b] conj(X^[f][j][b]): both operands with the batch fastest

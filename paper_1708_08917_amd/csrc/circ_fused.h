@@ -97,6 +97,39 @@ __device__ __forceinline__ void pack_fused_elem(long long idx, const float2* __r
   Wf[idx] = make_float4(v[0].x, v[0].y, v[1].x, v[1].y);
 }
 
+// The same operand order for 16-bit storage: element idx = two 32-bit words, each the (re, im)
+// 16-bit pair of one input block; `spec` is the 16-bit section [f][i][j] (one word per value, not
+// normalised), so packing only moves bits and works for fp16 and bfloat16 alike.
+__device__ __forceinline__ void pack_fused_half_elem(long long idx, const unsigned* __restrict__ spec, uint2* __restrict__ Wf,
+                                                     int p, int q, int K, int igp, int q2p) {
+  const int FG = K / 32;
+  const long long total = (long long)igp * q2p * FG * 64;
+  if (idx >= total) return;
+  const int l = int(idx & 63);
+  long long r = idx >> 6;
+  const int fg = int(r % FG); r /= FG;
+  const int j2 = int(r % q2p);
+  const int ig = int(r / q2p);
+  const int i = 4 * ig + (l & 3), slot = 16 * fg + (l >> 2);
+  const long long fs = (long long)p * q;
+  unsigned v[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int j = 2 * j2 + h;
+    v[h] = 0u;
+    if (i < p && j < q) {
+      const long long e = (long long)i * q + j;
+      if (slot == 0) v[h] = (spec[e] & 0xffffu) | (spec[(K / 2) * fs + e] << 16);   // the two real bins
+      else v[h] = spec[slot * fs + e];
+    }
+  }
+  Wf[idx] = make_uint2(v[0], v[1]);
+}
+__global__ __launch_bounds__(256) void pack_fused_half_kernel(const unsigned* __restrict__ spec, uint2* __restrict__ Wf, int p,
+                                                              int q, int K, int igp, int q2p) {
+  pack_fused_half_elem((long long)blockIdx.x * 256 + threadIdx.x, spec, Wf, p, q, K, igp, q2p);
+}
+
 // Exchange each lane's value with its neighbour inside a quad: lanes (0,1) and (2,3) swap.
 __device__ __forceinline__ float quad_swap_pairs(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false));
@@ -107,11 +140,17 @@ __device__ __forceinline__ float quad_swap_pairs(float v) {
 // workgroups then fit one CU (registers and LDS), and a launch on another stream can start on
 // a CU while the previous one is still waiting for its operands or draining.  Kernels of
 // independent batches overlap that way; a single launch is not slowed down.
-template <int K, int IT, int NP, int NT, bool ONE = false>
+// HM: 0 = fp32 operands; 1 (fp16) / 2 (bfloat16) = 16-bit storage: Wf then points to the packed
+// 16-bit operands (pack_fused_half_elem: 8 bytes per element, not normalised), x and y to 16-bit
+// values; everything between the loads and the final store is the same fp32 arithmetic, and the
+// 1/k of the inverse transform is applied to the fp32 result.
+template <int K, int IT, int NP, int NT, bool ONE = false, int HM = 0>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(ONE && NT == 512 ? 4 : 1, ONE && NT == 512 ? 4 : 8)))
 void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
                                                       const float* __restrict__ bias, float* __restrict__ y,
                                                       int p, int q, int B, int n_it, int q2p, int xa, int relu) {
+  constexpr bool BF = HM == 2;
+  using AOp = typename std::conditional<HM != 0, uint2, float4>::type;   // weight operand of two input blocks
   using Sh = FusedShape<K, IT, NP, NT>;
   constexpr int PT = Sh::PT, JC = Sh::JC, S = Sh::S, FG = Sh::FG, IG = Sh::IG, CPW = Sh::CPW, JS = Sh::JS;
   constexpr int JW = Sh::JW, NW = Sh::NW, NCOMBO = Sh::NCOMBO;
@@ -188,11 +227,13 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
     xoff[e] = unsigned(brow) * unsigned(ldx) + unsigned(4 * n4);
   }
   const float* xtile = x + (long long)b0 * ldx;
+  const unsigned short* xtile16 = reinterpret_cast<const unsigned short*>(x) + (long long)b0 * ldx;
   auto load_x = [&](int c) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const unsigned j = unsigned(min(c * JC + xjj[e], q - 1));
-      xr[e] = *reinterpret_cast<const float4*>(xtile + (xoff[e] + j * unsigned(K)));
+      if constexpr (HM == 0) xr[e] = *reinterpret_cast<const float4*>(xtile + (xoff[e] + j * unsigned(K)));
+      else xr[e] = load_half4<BF>(xtile16 + (xoff[e] + j * unsigned(K)));
     }
   };
   auto store_x = [&]() {
@@ -209,19 +250,19 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
   };
   // weight operands: the packed section is zero-padded to whole tiles (q2p pairs of block
   // columns per row group), so no clamping is needed
-  const float4* wtile = Wf + ((long long)it * IG * q2p + js * (JW / 2)) * FG * 64;
+  const AOp* wtile = reinterpret_cast<const AOp*>(Wf) + ((long long)it * IG * q2p + js * (JW / 2)) * FG * 64;
   unsigned aoff[CPW];
 #pragma unroll
   for (int cc = 0; cc < CPW; ++cc) {
     const int combo = combo0 + cc;
     aoff[cc] = unsigned(((combo % IG) * q2p) * FG + combo / IG) * 64u + unsigned(lane);
   }
-  float4 a_even[CPW][JW / 2], a_odd[ONE ? 1 : CPW][ONE ? 1 : JW / 2];
+  AOp a_even[CPW][JW / 2], a_odd[ONE ? 1 : CPW][ONE ? 1 : JW / 2];
   // [lo, hi) selects a part of the chunk's operands: a workgroup can only push requests into
   // the memory pipeline at a bounded rate, so the loads of the next chunk are issued in
   // pieces between the phases of the current one instead of stalling one phase
-  auto load_a = [&](int c, float4 (&a)[CPW][JW / 2], int lo, int hi) {
-    const float4* wc = wtile + (long long)c * (JC / 2) * FG * 64;
+  auto load_a = [&](int c, AOp (&a)[CPW][JW / 2], int lo, int hi) {
+    const AOp* wc = wtile + (long long)c * (JC / 2) * FG * 64;
 #pragma unroll
     for (int jh = 0; jh < JW / 2; ++jh)
 #pragma unroll
@@ -262,7 +303,7 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
   // one chunk of JC input blocks: FFT of its 2*PT rows, then the contraction with `a_use`;
   // meanwhile the loads of the next chunk (x into xr, weights into `a_pref`) are in flight.
   // `more` (a compile-time tag): another chunk follows, so its loads are issued here.
-  auto chunk = [&](int c, float4 (&a_use)[CPW][JW / 2], float4 (&a_pref)[CPW][JW / 2], auto more_tag) {
+  auto chunk = [&](int c, AOp (&a_use)[CPW][JW / 2], AOp (&a_pref)[CPW][JW / 2], auto more_tag) {
     constexpr bool more = decltype(more_tag)::value;
     store_x();
     __syncthreads();
@@ -313,8 +354,16 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
 #pragma unroll
           for (int cc = 0; cc < CPW; ++cc) {
             const float bval = bvv[cur][jj][u][NFW > 1 ? cc / IG : 0];
-            const float4 av = a_use[cc][(jb + jj) / 2];
-            const float ar = ((jb + jj) & 1) ? av.z : av.x, ai = ((jb + jj) & 1) ? av.w : av.y;
+            const AOp av = a_use[cc][(jb + jj) / 2];
+            float ar, ai;
+            if constexpr (HM == 0) {
+              ar = ((jb + jj) & 1) ? av.z : av.x;
+              ai = ((jb + jj) & 1) ? av.w : av.y;
+            } else {
+              const float2 cv = unpack_pair16<BF>(((jb + jj) & 1) ? av.y : av.x);
+              ar = cv.x;
+              ai = cv.y;
+            }
             P[jj % NCH][cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(ar, bval, P[jj % NCH][cc][u], 0, 0, 0);
             Q[jj % NCH][cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(ai, bval, Q[jj % NCH][cc][u], 0, 0, 0);
           }
@@ -433,13 +482,16 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
     const int coli = row >> 1, half = row & 1;
     const int i = i0 + coli / NP, b = b0 + 2 * (coli % NP) + half;
     if (idx < NOUT4 && i < p && b < B) {
+      constexpr float osc = HM == 0 ? 1.0f : 1.0f / float(K);   // fp32 operands carry the 1/k already
       float4 v;
-      v.x = lds_get(z, fft_pos<K>(n + 0) * PPI + coli, half) + bv4[s].x;
-      v.y = lds_get(z, fft_pos<K>(n + 1) * PPI + coli, half) + bv4[s].y;
-      v.z = lds_get(z, fft_pos<K>(n + 2) * PPI + coli, half) + bv4[s].z;
-      v.w = lds_get(z, fft_pos<K>(n + 3) * PPI + coli, half) + bv4[s].w;
+      v.x = lds_get(z, fft_pos<K>(n + 0) * PPI + coli, half) * osc + bv4[s].x;
+      v.y = lds_get(z, fft_pos<K>(n + 1) * PPI + coli, half) * osc + bv4[s].y;
+      v.z = lds_get(z, fft_pos<K>(n + 2) * PPI + coli, half) * osc + bv4[s].z;
+      v.w = lds_get(z, fft_pos<K>(n + 3) * PPI + coli, half) * osc + bv4[s].w;
       if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
-      *reinterpret_cast<float4*>(y + (long long)b * ldy + (long long)i * K + n) = v;
+      const long long yo = (long long)b * ldy + (long long)i * K + n;
+      if constexpr (HM == 0) *reinterpret_cast<float4*>(y + yo) = v;
+      else store_half4<BF>(reinterpret_cast<unsigned short*>(y) + yo, v);
     }
   }
   CIRC_PROBE(62);

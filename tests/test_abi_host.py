@@ -194,7 +194,9 @@ def test_sgd_step_and_export_argument_errors():
 
 def test_f16_argument_errors():
     big = 1 << 28
-    assert B.lib().circ_spectra_bytes_f16(64, 64, 64) == 2 * 33 * 64 * 64 * 4   # both orientations of the grid
+    # both orientations of the grid, each also in the fused kernel's operand order (32 slots per block)
+    assert B.lib().circ_spectra_bytes_f16(64, 64, 64) == 2 * 33 * 64 * 64 * 4 + 2 * 32 * 64 * 64 * 4
+    assert B.lib().circ_spectra_bytes_f16(64, 64, 512) == 2 * 257 * 64 * 64 * 4   # no fused kernel for k = 512
     assert B.lib().circ_spectra_bytes_f16(64, 64, 4) == 0          # k below 8
     assert B.lib().circ_spectra_bytes_f16(64, 64, 96) == 0         # not a power of two
     assert B.lib().circ_spectra_bytes_f16(0, 64, 64) == 0
@@ -204,7 +206,7 @@ def test_f16_argument_errors():
     assert pre(None, 2, 2, 8, A, None) == B.CIRC_EINVAL
     assert pre(A, 2, 2, 12, A + big, None) == B.CIRC_EINVAL
     assert pre(A, 2, 2, 8, A, None) == B.CIRC_EINVAL              # output aliases input
-    assert B.lib().circ_spectra_bytes_bf16(64, 64, 64) == 2 * 33 * 64 * 64 * 4
+    assert B.lib().circ_spectra_bytes_bf16(64, 64, 64) == B.lib().circ_spectra_bytes_f16(64, 64, 64)
     assert B.lib().circ_fc_workspace_bytes_bf16(64, 64, 64, 64) == 2 * 33 * 64 * 64 * 4
     assert B.lib().circ_precompute_spectra_bf16(A, 2, 2, 12, A + big, None) == B.CIRC_EINVAL
     for f in (B.lib().circ_fc_forward_f16, B.lib().circ_fc_forward_bf16):
