@@ -178,6 +178,13 @@ hipError_t launch_rfft(int k, bool rows_fast, const float* in, float2* out, cons
                        long long out_fstride, int n_grids, long long in_gstride, long long out_gstride,
                        float scale, int conj, hipStream_t s) {
   if (!radix2_k(k)) {
+    if (const int k1 = dft_factor(k); k1 > 1) {   // composite: two factors
+      const int R = dft2_rows_per_block(k, nrows);
+      hipLaunchKernelGGL(dft2_rows_kernel, dim3((unsigned)cdiv(nrows, R), (unsigned)n_grids), dim3(256),
+                         dft2_tile_lds_bytes(k, R), s, in, out, map, nrows, out_fstride, in_gstride, out_gstride, k, k1, R,
+                         scale, conj, int(rows_fast));
+      return hipGetLastError();
+    }
     const int R = dft_rows_per_block(k, nrows);
     hipLaunchKernelGGL(dft_rows_kernel, dim3((unsigned)cdiv(nrows, R), (unsigned)n_grids), dim3(256),
                        dft_tile_lds_bytes(k, R), s, in, out, map, nrows, out_fstride, in_gstride, out_gstride, k, R, scale,
@@ -193,6 +200,12 @@ hipError_t launch_irfft(int k, bool rows_fast, const float2* in, float* out, con
                         long long in_fstride, float scale, const float* bias, long long bias_div, int relu,
                         hipStream_t s, int nparts = 1, long long part_stride = 0) {
   if (!radix2_k(k)) {
+    if (const int k1 = dft_factor(k); k1 > 1) {
+      const int R = dft2_rows_per_block(k, nrows);
+      hipLaunchKernelGGL(idft2_rows_kernel, dim3((unsigned)cdiv(nrows, R)), dim3(256), dft2_tile_lds_bytes(k, R), s, in, out,
+                         map, nrows, in_fstride, k, k1, R, scale, bias, bias_div, relu, nparts, part_stride, int(rows_fast));
+      return hipGetLastError();
+    }
     const int R = dft_rows_per_block(k, nrows);
     hipLaunchKernelGGL(idft_rows_kernel, dim3((unsigned)cdiv(nrows, R)), dim3(256), dft_tile_lds_bytes(k, R), s, in, out,
                        map, nrows, in_fstride, k, R, scale, bias, bias_div, relu, nparts, part_stride, int(rows_fast));
