@@ -540,7 +540,7 @@ def test_conv_strided_and_even_filters(N, p, q, k, H, W, r, pad, stride):
 
 
 # ---- block sizes that are not powers of two (direct transforms around the same contraction) ----
-@pytest.mark.parametrize("k", [1, 3, 5, 6, 7, 12, 24, 40, 96, 100, 125, 250, 384, 511])
+@pytest.mark.parametrize("k", [1, 3, 5, 6, 7, 9, 12, 15, 24, 40, 96, 100, 125, 225, 250, 384, 509, 511])
 @pytest.mark.parametrize("batch", [1, 2, 33])
 def test_fc_general_block_sizes(k, batch):
     p, q = (3, 5) if k < 200 else (2, 3)
