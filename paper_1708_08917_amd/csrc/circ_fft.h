@@ -23,8 +23,12 @@ namespace circ {
 __device__ const TwiddleTable kTw = TwiddleTable();
 
 constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
-// K = R1 * R2 with R2 <= R1 <= 2 * R2
-constexpr int radix2_of(int K) { return 1 << (ilog2(K) / 2); }
+// K = R1 * R2 with R1 <= R2 <= 2 * R1.  For odd log2 K the longer sub-transform is the second
+// one: the first pass then has R2 = 2*R1 short sub-transforms (plus the twiddles) per column, which
+// keep every thread of a 16-threads-per-column kernel busy, and the second pass R1 long ones
+// without twiddles (fused kernel, K = 128: 1.25 + 0.47 us per chunk with the longer one first,
+// about 0.4 us less this way).
+constexpr int radix2_of(int K) { return 1 << ((ilog2(K) + 1) / 2); }
 constexpr int radix1_of(int K) { return K / radix2_of(K); }
 
 // ---- in-register radix-2 FFT of R points, natural order in and out ------------------
