@@ -192,7 +192,9 @@ circ_status circ_export_weights(const void* w_hat, int n_grids, int p, int q, in
  * values ([batch][q*k] and [batch][p*k]), bias fp32.  k must be a power of two, 8 <= k <= 512.
  * Against the exact result the error is a few fp16 roundings (2^-11 each: weights' spectra,
  * input spectra, output spectra, output), about 1e-3 of the largest output; spectra of inputs
- * are not normalised, so |x| * k must stay below the fp16 range (65504).
+ * are not normalised, so |x| * k must stay below the fp16 range (65504).  Small layers (the
+ * ones circ_fc_forward runs as one fused launch) are computed in one launch here too: the
+ * spectra of x and y then never leave the chip and only the weights' spectra and y are rounded.
  *   circ_spectra_bytes_f16        size of the fp16 spectra blob (0 for invalid arguments)
  *   circ_precompute_spectra_f16   w fp32 device [p][q][k] -> blob (opaque, caller-owned, 16-byte aligned)
  *   circ_fc_workspace_bytes_f16   workspace of circ_fc_forward_f16 for the same arguments
