@@ -420,7 +420,8 @@ inline size_t gemv_partial_bytes(int p, int q, int k) {
   return ns > 1 ? size_t(ns) * p * k * sizeof(float2) : 0;
 }
 
-template <int K>
+// HM: 0 fp32, 1 fp16, 2 bfloat16 storage (wg, x, y then point to the 16-bit data)
+template <int K, int HM>
 hipError_t launch_gemv_k(const float2* wg, const float* x, const float* bias, float* y, int p, int q, int batch, int relu,
                          void* workspace, hipStream_t s) {
   using Sh = GemvShape<K>;
@@ -428,36 +429,49 @@ hipError_t launch_gemv_k(const float2* wg, const float* x, const float* bias, fl
   const int ns = gemv_splits(p, q, K);
   if (ns > 1) {
     static bool opted1 = false, opted2 = false;
-    if (ensure_lds(&fc_gemv_kernel<K, 1>, Sh::LDS_BYTES, opted1) != hipSuccess) return hipErrorInvalidValue;
-    if (ensure_lds(&fc_gemv_kernel<K, 2>, Sh::LDS_BYTES, opted2) != hipSuccess) return hipErrorInvalidValue;
+    if (ensure_lds(&fc_gemv_kernel<K, 1, HM>, Sh::LDS_BYTES, opted1) != hipSuccess) return hipErrorInvalidValue;
+    if (ensure_lds(&fc_gemv_kernel<K, 2, HM>, Sh::LDS_BYTES, opted2) != hipSuccess) return hipErrorInvalidValue;
     float2* part = static_cast<float2*>(workspace);
     const int jper = (int)cdiv(q, ns);
-    hipLaunchKernelGGL((fc_gemv_kernel<K, 1>), dim3((unsigned)p, (unsigned)ns), dim3(256), Sh::LDS_BYTES, s, wg, x,
+    hipLaunchKernelGGL((fc_gemv_kernel<K, 1, HM>), dim3((unsigned)p, (unsigned)ns), dim3(256), Sh::LDS_BYTES, s, wg, x,
                        (const float*)nullptr, (float*)nullptr, p, q, batch, 0, part, ns, jper);
     if (hipGetLastError() != hipSuccess) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fc_gemv_kernel<K, 2>), dim3((unsigned)p), dim3(256), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch,
+    hipLaunchKernelGGL((fc_gemv_kernel<K, 2, HM>), dim3((unsigned)p), dim3(256), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch,
                        relu, part, ns, jper);
     return hipGetLastError();
   }
-  if (ensure_lds(&fc_gemv_kernel<K, 0>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((fc_gemv_kernel<K, 0>), dim3((unsigned)p), dim3(256), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch,
+  if (ensure_lds(&fc_gemv_kernel<K, 0, HM>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((fc_gemv_kernel<K, 0, HM>), dim3((unsigned)p), dim3(256), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch,
                      relu, (float2*)nullptr, 1, q);
   return hipGetLastError();
 }
 
-hipError_t launch_gemv(int k, const float2* wg, const float* x, const float* bias, float* y, int p, int q, int batch,
-                       int relu, void* workspace, hipStream_t s) {
+template <int HM>
+hipError_t launch_gemv_h(int k, const float2* wg, const float* x, const float* bias, float* y, int p, int q, int batch,
+                         int relu, void* workspace, hipStream_t s) {
   switch (k) {
-    case 4: return launch_gemv_k<4>(wg, x, bias, y, p, q, batch, relu, workspace, s);
-    case 8: return launch_gemv_k<8>(wg, x, bias, y, p, q, batch, relu, workspace, s);
-    case 16: return launch_gemv_k<16>(wg, x, bias, y, p, q, batch, relu, workspace, s);
-    case 32: return launch_gemv_k<32>(wg, x, bias, y, p, q, batch, relu, workspace, s);
-    case 64: return launch_gemv_k<64>(wg, x, bias, y, p, q, batch, relu, workspace, s);
-    case 128: return launch_gemv_k<128>(wg, x, bias, y, p, q, batch, relu, workspace, s);
-    case 256: return launch_gemv_k<256>(wg, x, bias, y, p, q, batch, relu, workspace, s);
-    case 512: return launch_gemv_k<512>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 4: return launch_gemv_k<4, HM>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 8: return launch_gemv_k<8, HM>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 16: return launch_gemv_k<16, HM>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 32: return launch_gemv_k<32, HM>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 64: return launch_gemv_k<64, HM>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 128: return launch_gemv_k<128, HM>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 256: return launch_gemv_k<256, HM>(wg, x, bias, y, p, q, batch, relu, workspace, s);
+    case 512: return launch_gemv_k<512, HM>(wg, x, bias, y, p, q, batch, relu, workspace, s);
     default: return hipErrorInvalidValue;
   }
+}
+hipError_t launch_gemv(int k, const float2* wg, const float* x, const float* bias, float* y, int p, int q, int batch,
+                       int relu, void* workspace, hipStream_t s) {
+  return launch_gemv_h<0>(k, wg, x, bias, y, p, q, batch, relu, workspace, s);
+}
+hipError_t launch_gemv_half(bool bf, int k, const void* wg, const void* x, const float* bias, void* y, int p, int q,
+                            int batch, int relu, void* workspace, hipStream_t s) {
+  const float2* w2 = static_cast<const float2*>(wg);
+  const float* xf = static_cast<const float*>(x);
+  float* yf = static_cast<float*>(y);
+  return bf ? launch_gemv_h<2>(k, w2, xf, bias, yf, p, q, batch, relu, workspace, s)
+            : launch_gemv_h<1>(k, w2, xf, bias, yf, p, q, batch, relu, workspace, s);
 }
 
 inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
@@ -1227,8 +1241,9 @@ inline size_t half_fused_bytes(int p, int q, int k) {
   if (fused_it(k) == 0) return 0;
   return align_up(size_t(fused_igp(p, k)) * fused_q2p(q, k) * (k / 32) * 64 * sizeof(uint2), 256);
 }
-// 16-bit blob: W^[f][i][j], conj(W^)[f][j][i], then the fused kernel's operand order of either
-struct HalfBlob { size_t fwd, bwd, fused_fwd, fused_bwd, total; };
+// 16-bit blob: W^[f][i][j], conj(W^)[f][j][i], then the fused kernel's operand order of either,
+// then the batch <= 2 kernel's
+struct HalfBlob { size_t fwd, bwd, fused_fwd, fused_bwd, gemv_fwd, gemv_bwd, total; };
 inline HalfBlob half_blob(int p, int q, int k) {
   HalfBlob b;
   const size_t sec = half_spectrum_bytes(k, (long long)p * q);
@@ -1236,7 +1251,11 @@ inline HalfBlob half_blob(int p, int q, int k) {
   b.bwd = sec;
   b.fused_fwd = 2 * sec;
   b.fused_bwd = b.fused_fwd + half_fused_bytes(p, q, k);
-  b.total = b.fused_bwd + half_fused_bytes(q, p, k);
+  // one word per value in the order of the batch <= 2 kernel, either orientation
+  const size_t gsec = align_up(size_t(p) * q * (k / 2) * sizeof(unsigned), 256);
+  b.gemv_fwd = b.fused_bwd + half_fused_bytes(q, p, k);
+  b.gemv_bwd = b.gemv_fwd + gsec;
+  b.total = b.gemv_bwd + gsec;
   return b;
 }
 
@@ -1261,10 +1280,18 @@ circ_status precompute_spectra_half(bool bf, const float* w, int p, int q, int k
   void* sec2 = static_cast<char*>(w_hat) + half_spectrum_bytes(k, rows);
   if (launch_rfft_half(k, kHalfSpectra, bf, w, sec2, mt, rows, rows, 1.0f, static_cast<hipStream_t>(stream), 1) != hipSuccess)
     return CIRC_EHIP;
+  const HalfBlob hb = half_blob(p, q, k);
+  char* base = static_cast<char*>(w_hat);
+  for (int dir = 0; dir < 2; ++dir) {   // operand order of the batch <= 2 kernel
+    const int pp = dir ? q : p, qq = dir ? p : q;
+    const long long total = (long long)pp * qq * (k / 2);
+    hipLaunchKernelGGL(pack_gemv_half_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<const unsigned*>(base + (dir ? hb.bwd : hb.fwd)),
+                       reinterpret_cast<unsigned*>(base + (dir ? hb.gemv_bwd : hb.gemv_fwd)), pp, qq, k);
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  }
   if (fused_it(k) != 0) {
     // rearrangements of the two sections for the fused kernel (forward and backward-data)
-    const HalfBlob hb = half_blob(p, q, k);
-    char* base = static_cast<char*>(w_hat);
     const int FG = k / 32;
     for (int dir = 0; dir < 2; ++dir) {
       const int pp = dir ? q : p, qq = dir ? p : q;
@@ -1281,7 +1308,9 @@ circ_status precompute_spectra_half(bool bf, const float* w, int p, int q, int k
 
 size_t fc_workspace_bytes_half(int p, int q, int k, int batch) {
   if (!fc_dims_ok(p, q, k, batch) || !half_k(k)) return 0;
-  return half_spectrum_bytes(k, (long long)q * batch) + half_spectrum_bytes(k, (long long)p * batch);
+  const size_t sp = half_spectrum_bytes(k, (long long)q * batch) + half_spectrum_bytes(k, (long long)p * batch);
+  const size_t gp = batch <= 2 ? align_up(gemv_partial_bytes(p, q, k), 256) : 0;   // partial spectra of the split batch <= 2 kernel
+  return sp > gp ? sp : gp;
 }
 
 circ_status fc_forward_half(bool bf, const void* w_hat, const void* x, const float* bias, void* y, int p, int q, int k,
@@ -1297,6 +1326,12 @@ circ_status fc_forward_half(bool bf, const void* w_hat, const void* x, const flo
   if (!workspace || workspace_bytes < fc_workspace_bytes_half(p, q, k, batch)) return CIRC_EWORKSPACE;
   if (!aligned16(workspace)) return CIRC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (batch <= 2) {   // one or two vectors: the streaming matrix-vector kernel on 16-bit operands
+    const void* wg = static_cast<const char*>(w_hat) + half_blob(p, q, k).gemv_fwd;
+    return launch_gemv_half(bf, k, wg, x, use_bias ? bias : nullptr, y, p, q, batch, (epilogue & CIRC_EPI_RELU) ? 1 : 0, workspace, s) == hipSuccess
+               ? CIRC_OK
+               : CIRC_EHIP;
+  }
   if (use_fused_forward(p, q, k, batch)) {
     // one launch: 16-bit loads of x and of the packed operands, fp32 inside, 16-bit store of y
     const void* wfu = static_cast<const char*>(w_hat) + half_blob(p, q, k).fused_fwd;
@@ -1340,8 +1375,12 @@ inline size_t half_dw_part_elems(int p, int q, int k) {
 // fastest, for the weight gradient), the fp32 partial spectra of the weight gradient
 size_t fc_backward_workspace_bytes_half(int p, int q, int k, int batch) {
   if (!fc_dims_ok(p, q, k, batch) || !half_k(k)) return 0;
-  return 2 * half_spectrum_bytes(k, (long long)q * batch) + 2 * half_spectrum_bytes(k, (long long)p * batch) +
-         size_t(half_dw_slices(p, q, k, batch)) * half_dw_part_elems(p, q, k) * sizeof(float2);
+  const size_t sp = 2 * half_spectrum_bytes(k, (long long)q * batch) + 2 * half_spectrum_bytes(k, (long long)p * batch) +
+                    size_t(half_dw_slices(p, q, k, batch)) * half_dw_part_elems(p, q, k) * sizeof(float2);
+  // batch <= 2: partial spectra of the split streaming kernel on the transposed grid (they sit at
+  // the start of the workspace, which the weight gradient only uses afterwards)
+  const size_t gp = batch <= 2 ? align_up(gemv_partial_bytes(q, p, k), 256) : 0;
+  return sp > gp ? sp : gp;
 }
 
 circ_status fc_backward_half(bool bf, const void* w_hat, const void* x, const void* dy, void* dx, float* dw, int p, int q,
@@ -1370,8 +1409,11 @@ circ_status fc_backward_half(bool bf, const void* w_hat, const void* x, const vo
   // dY^[f][i][b] (batch fastest) serves the weight gradient directly and, transposed on its way
   // into the contraction, backward-data as well: dy is transformed once when both are wanted.
   // Backward-data alone takes dY^[f][b][i], which its contraction reads without the transposition.
-  if (dw) {
-    RowMap myt{batch, p, (long long)p * k, (long long)k, 0, 1};
+  // (The one-launch kernels of small problems read dy itself; the batch <= 2 one may use the start
+  // of the workspace for its partial spectra, so the transform for the weight gradient follows it.)
+  const bool dx_one_launch = batch <= 2 || use_fused_forward(q, p, k, batch);
+  RowMap myt{batch, p, (long long)p * k, (long long)k, 0, 1};
+  if (dw && dx && !dx_one_launch) {
     if (launch_rfft_half(k, hm, bf, dy, dyt, myt, yrows, yrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
   }
   if (dx) {
@@ -1379,7 +1421,10 @@ circ_status fc_backward_half(bool bf, const void* w_hat, const void* x, const vo
     // dX^[f][j][b] = (1/k) sum_i conj(W^)[f][j][i] dY^[f][.][.]
     const HalfBlob hb = half_blob(p, q, k);
     const __half2* wt = reinterpret_cast<const __half2*>(static_cast<const char*>(w_hat) + hb.bwd);
-    if (use_fused_forward(q, p, k, batch)) {
+    if (batch <= 2) {
+      if (launch_gemv_half(bf, k, static_cast<const char*>(w_hat) + hb.gemv_bwd, dy, nullptr, dx, q, p, batch, 0, workspace, s) != hipSuccess)
+        return CIRC_EHIP;
+    } else if (use_fused_forward(q, p, k, batch)) {
       // small problems: the fused kernel on the transposed grid's operands, one launch
       if (launch_fused_half(bf, k, static_cast<const char*>(w_hat) + hb.fused_bwd, dy, nullptr, dx, q, p, batch, 0, s) != hipSuccess)
         return CIRC_EHIP;
@@ -1399,6 +1444,9 @@ circ_status fc_backward_half(bool bf, const void* w_hat, const void* x, const vo
   }
   if (dw) {
     // dW^[f][i][j] = sum_b dY^[f][i][b] conj(X^[f][j][b]): both operands with the batch fastest
+    if (!dx || dx_one_launch) {
+      if (launch_rfft_half(k, hm, bf, dy, dyt, myt, yrows, yrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
+    }
     RowMap mxt{batch, q, (long long)q * k, (long long)k, 0, 1};
     if (launch_rfft_half(k, hm, bf, x, xt, mxt, xrows, xrows, 1.0f, s) != hipSuccess) return CIRC_EHIP;
     const int ks = half_dw_slices(p, q, k, batch), klen = half_dw_slice_len(batch, ks);

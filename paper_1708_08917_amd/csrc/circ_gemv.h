@@ -18,6 +18,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "circ_fft.h"
 #include "circ_kernels.h"
 
@@ -64,6 +66,21 @@ __device__ __forceinline__ void pack_gemv_elem(long long idx, const float2* __re
   Wg[idx] = slot == 0 ? make_float2(spec[e].x, spec[(long long)S * fs + e].x) : spec[(long long)slot * fs + e];
 }
 
+// The same order for 16-bit storage, one word per value; `spec` is the 16-bit section [f][i][j].
+__device__ __forceinline__ void pack_gemv_half_elem(long long idx, const unsigned* __restrict__ spec, unsigned* __restrict__ Wg,
+                                                    int p, int q, int K) {
+  const int S = K / 2;
+  const long long total = (long long)p * q * S;
+  if (idx >= total) return;
+  const int slot = int(idx % S);
+  const long long e = idx / S, fs = (long long)p * q;   // e = i*q + j
+  Wg[idx] = slot == 0 ? ((spec[e] & 0xffffu) | (spec[(long long)S * fs + e] << 16)) : spec[(long long)slot * fs + e];
+}
+__global__ __launch_bounds__(256) void pack_gemv_half_kernel(const unsigned* __restrict__ spec, unsigned* __restrict__ Wg, int p,
+                                                             int q, int K) {
+  pack_gemv_half_elem((long long)blockIdx.x * 256 + threadIdx.x, spec, Wg, p, q, K);
+}
+
 // MODE 0: the whole layer in one launch, one workgroup per output block row (grid p).
 // Layers with few block rows and long rows leave most of the chip idle that way and make every
 // workgroup transform all of x; they run as two launches instead:
@@ -71,7 +88,10 @@ __device__ __forceinline__ void pack_gemv_elem(long long idx, const float2* __re
 //   [js*jper, (js+1)*jper) and writes the spectrum of its partial output pair to
 //   part[(js*p + i)*K + f];
 // MODE 2 (grid p): adds the nsplit partial spectra in index order, inverse transform, epilogue.
-template <int K, int MODE>
+// HM: 0 = fp32; 1 (fp16) / 2 (bfloat16) = 16-bit storage: Wg then points to one 32-bit word per
+// value (the 16-bit (re, im) pair, not normalised; pack_gemv_half_elem), x and y to 16-bit values;
+// the arithmetic and the partial spectra of MODE 1 / 2 stay fp32, the 1/k goes onto the result.
+template <int K, int MODE, int HM = 0>
 __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__ Wg, const float* __restrict__ x,
                                                       const float* __restrict__ bias, float* __restrict__ y,
                                                       int p, int q, int B, int relu, float2* __restrict__ part,
@@ -96,16 +116,18 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
   const int slot = tid % S, jg = tid / S;          // contraction role (threads beyond S*JG idle)
   const bool active = jg < JG;
   float P[4] = {0.f, 0.f, 0.f, 0.f}, Q[4] = {0.f, 0.f, 0.f, 0.f};
-  const float2* wrow = Wg + (long long)i * q * S + slot;
+  constexpr bool BF = HM == 2;
+  using WOp = typename std::conditional<HM != 0, unsigned, float2>::type;
+  const WOp* wrow = reinterpret_cast<const WOp*>(Wg) + (long long)i * q * S + slot;
   // The weights of a chunk are fetched one chunk ahead (those of the first chunk before x is
   // even staged), so that their latency overlaps the FFT instead of following it.
   constexpr int NPF = (PT + JG - 1) / JG;          // weights per thread and chunk
-  float2 wnext[NPF];
+  WOp wnext[NPF];
   auto fetch_w = [&](int c) {
 #pragma unroll
     for (int u = 0; u < NPF; ++u) {
       const int jj = jg + u * JG, j = jbeg + c * PT + jj;
-      wnext[u] = make_float2(0.f, 0.f);
+      wnext[u] = WOp{};                              // zero in either format
       if (active && jj < PT && j < jend) wnext[u] = wrow[(long long)j * S];
     }
   };
@@ -125,7 +147,11 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
       const int gl = idx % GW, rest = idx / GW;
       const int col = rest % PT, half = (rest / PT) & 1, n = 4 * ((rest / (2 * PT)) * GW + gl);
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (half < B && j0 + col < jend) v = *reinterpret_cast<const float4*>(x + (long long)half * ldx + (long long)(j0 + col) * K + n);
+      if (half < B && j0 + col < jend) {
+        const long long xo = (long long)half * ldx + (long long)(j0 + col) * K + n;
+        if constexpr (HM == 0) v = *reinterpret_cast<const float4*>(x + xo);
+        else v = load_half4<BF>(reinterpret_cast<const unsigned short*>(x) + xo);
+      }
       lds_put(z, (n + 0) * PP + col, half, v.x);
       lds_put(z, (n + 1) * PP + col, half, v.y);
       lds_put(z, (n + 2) * PP + col, half, v.z);
@@ -154,7 +180,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
     }
     __syncthreads();
     CIRC_PROBE(2 + 3 * c);
-    float2 wcur[NPF];
+    WOp wcur[NPF];
 #pragma unroll
     for (int u = 0; u < NPF; ++u) wcur[u] = wnext[u];
     if (c + 1 < nchunks) fetch_w(c + 1);
@@ -164,7 +190,9 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
       for (int u = 0; u < NPF; ++u) {
         const int jj = jg + u * JG;
         if (jj < jlim) {     // (weights past the end were fetched as zeros; the operand row must exist)
-          const float2 w = wcur[u];
+          float2 w;
+          if constexpr (HM == 0) w = wcur[u];
+          else w = unpack_pair16<BF>(wcur[u]);
           const float4 cv = *reinterpret_cast<const float4*>(op + jj * OPROW + 4 * slot);
           P[0] += w.x * cv.x; P[1] += w.x * cv.y; P[2] += w.x * cv.z; P[3] += w.x * cv.w;
           Q[0] += w.y * cv.x; Q[1] += w.y * cv.y; Q[2] += w.y * cv.z; Q[3] += w.y * cv.w;
@@ -263,10 +291,13 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
   for (int idx = tid; idx < 2 * K; idx += NT) {
     const int half = idx / K, n = idx % K;
     if (half < B) {
-      float v = lds_get(z, opos(n) * 2, half);
+      constexpr float osc = HM == 0 ? 1.0f : 1.0f / float(K);   // fp32 operands carry the 1/k already
+      float v = lds_get(z, opos(n) * 2, half) * osc;
       if (bias) v += bias[(long long)i * K + n];
       if (relu) v = fmaxf(v, 0.f);
-      y[(long long)half * ldy + (long long)i * K + n] = v;
+      const long long yo = (long long)half * ldy + (long long)i * K + n;
+      if constexpr (HM == 0) y[yo] = v;
+      else reinterpret_cast<unsigned short*>(y)[yo] = (unsigned short)(pack_pair16<BF>(v, 0.f) & 0xffffu);
     }
   }
   CIRC_PROBE(42);

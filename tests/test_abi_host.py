@@ -195,8 +195,9 @@ def test_sgd_step_and_export_argument_errors():
 def test_f16_argument_errors():
     big = 1 << 28
     # both orientations of the grid, each also in the fused kernel's operand order (32 slots per block)
-    assert B.lib().circ_spectra_bytes_f16(64, 64, 64) == 2 * 33 * 64 * 64 * 4 + 2 * 32 * 64 * 64 * 4
-    assert B.lib().circ_spectra_bytes_f16(64, 64, 512) == 2 * 257 * 64 * 64 * 4   # no fused kernel for k = 512
+    # ... and in the batch <= 2 kernel's (k/2 words per block)
+    assert B.lib().circ_spectra_bytes_f16(64, 64, 64) == 2 * 33 * 64 * 64 * 4 + 2 * 32 * 64 * 64 * 4 + 2 * 32 * 64 * 64 * 4
+    assert B.lib().circ_spectra_bytes_f16(64, 64, 512) == 2 * 257 * 64 * 64 * 4 + 2 * 256 * 64 * 64 * 4   # no fused kernel for k = 512
     assert B.lib().circ_spectra_bytes_f16(64, 64, 4) == 0          # k below 8
     assert B.lib().circ_spectra_bytes_f16(64, 64, 96) == 0         # not a power of two
     assert B.lib().circ_spectra_bytes_f16(0, 64, 64) == 0

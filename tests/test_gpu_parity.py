@@ -438,7 +438,9 @@ def gpu_fc_forward_half(w, xt, bias, relu):
 @pytest.mark.parametrize("dtype", HALF_DTYPES)
 @pytest.mark.parametrize("p,q,k,batch", [(1, 1, 8, 1), (3, 5, 16, 7), (5, 3, 64, 33), (2, 4, 256, 10), (33, 34, 8, 70),
                                          (4, 6, 128, 67), (2, 3, 512, 5), (7, 9, 32, 2), (17, 64, 64, 130), (70, 12, 64, 300),
-                                         (64, 64, 64, 64), (65, 8, 32, 129), (3, 72, 128, 40), (2, 130, 16, 9)])
+                                         (64, 64, 64, 64), (65, 8, 32, 129), (3, 72, 128, 40), (2, 130, 16, 9),
+                                         (4, 72, 128, 1), (32, 32, 128, 2), (125, 512, 8, 1), (3, 5, 16, 2), (2, 3, 512, 1),
+                                         (64, 64, 16, 1), (5, 40, 256, 2)])
 def test_fc_forward_half_shapes(p, q, k, batch, dtype):
     w, x, b = rand_fc(p, q, k, batch)
     xt, xr = to_half(x, dtype)
@@ -474,7 +476,8 @@ def test_fc_forward_half_configs(cfg, dtype):
 @pytest.mark.parametrize("dtype", HALF_DTYPES)
 @pytest.mark.parametrize("p,q,k,batch", [(1, 1, 8, 1), (3, 5, 16, 7), (5, 3, 64, 33), (2, 4, 256, 10), (33, 34, 8, 70),
                                          (4, 6, 128, 68), (2, 3, 512, 5), (7, 9, 32, 2), (2, 3, 16, 700), (3, 2, 8, 1025),
-                                         (70, 130, 8, 260), (64, 64, 64, 64), (65, 8, 32, 129), (3, 72, 128, 40)])
+                                         (70, 130, 8, 260), (64, 64, 64, 64), (65, 8, 32, 129), (3, 72, 128, 40),
+                                         (72, 4, 128, 1), (32, 32, 128, 2), (512, 125, 8, 1), (3, 5, 16, 2), (40, 5, 256, 2)])
 def test_fc_backward_half_shapes(p, q, k, batch, dtype):
     w, x, _ = rand_fc(p, q, k, batch, bias=False)
     dy = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
