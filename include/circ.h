@@ -244,6 +244,22 @@ circ_status circ_fc_backward_bf16(const void* w_hat, const void* x, const void* 
                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * CONV forward with 16-bit activations (inference in the 16-bit representation of Sec. 4.2):
+ * x and y hold fp16 (bf16) values in NCHW, bias is fp32, and w_hat is the blob of
+ * circ_precompute_spectra for the same (r*r, p, q, k): the cached weight spectra, about 0.1 %
+ * of the bytes a layer moves, stay fp32, so that the only roundings are those of x (the caller's)
+ * and of y.  Everything else as circ_conv_forward (layouts, stride, padding, epilogue flags,
+ * workspace size from circ_conv_workspace_bytes); k must be a power of two, 8 <= k <= 512.
+ * Errors as for circ_conv_forward.
+ */
+circ_status circ_conv_forward_f16(const void* w_hat, const void* x, const float* bias, void* y,
+                                  int N, int C_in, int C_out, int H, int W, int r, int stride, int pad,
+                                  int k, int epilogue, void* workspace, size_t workspace_bytes, void* stream);
+circ_status circ_conv_forward_bf16(const void* w_hat, const void* x, const float* bias, void* y,
+                                   int N, int C_in, int C_out, int H, int W, int r, int stride, int pad,
+                                   int k, int epilogue, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Bias gradient (Eq. 1: a = Wx + theta, so dL/dtheta is dL/da summed over everything but the
  * channel).  dy is viewed as [outer][channels][inner]:
  *   db[c] = sum_{o, t} dy[(o*channels + c)*inner + t]

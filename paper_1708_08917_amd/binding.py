@@ -32,6 +32,8 @@ SIGNATURES = {
                                   _c_ptr, _c_size, _c_ptr]),
     "circ_conv_workspace_bytes": (_c_size, [_c_int] * 9),
     "circ_conv_forward": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr] + [_c_int] * 10 + [_c_ptr, _c_size, _c_ptr]),
+    "circ_conv_forward_f16": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr] + [_c_int] * 10 + [_c_ptr, _c_size, _c_ptr]),
+    "circ_conv_forward_bf16": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr] + [_c_int] * 10 + [_c_ptr, _c_size, _c_ptr]),
     "circ_conv_backward_workspace_bytes": (_c_size, [_c_int] * 9),
     "circ_conv_backward": (_c_int, [_c_ptr] * 5 + [_c_int] * 9 + [_c_ptr, _c_size, _c_ptr]),
     "circ_bias_grad": (_c_int, [_c_ptr, _c_ptr, ctypes.c_longlong, _c_int, ctypes.c_longlong, _c_ptr]),
@@ -275,6 +277,23 @@ def circ_fc_backward_f16(w_hat, x, dy, p, q, k, need_dx=True, need_dw=True, dx=N
                                                      _ptr(dw) if need_dw else None, p, q, k, batch, _ptr(workspace),
                                                      workspace.numel(), _stream()), f"circ_fc_backward_{sfx}")
     return (dx if need_dx else None), (dw if need_dw else None)
+
+
+def circ_conv_forward_f16(w_hat, x, bias, y, C_out, r, stride, pad, k, epilogue=EPI_NONE, workspace=None):
+    """x: fp16 or bf16 NCHW -> y of the same type (allocated if None); w_hat from circ_precompute_spectra, bias fp32."""
+    sfx = _half_suffix(x.dtype)
+    assert x.is_contiguous()
+    N, C_in, H, W = x.shape
+    Ho, Wo = (H + 2 * pad - r) // stride + 1, (W + 2 * pad - r) // stride + 1
+    if y is None:
+        y = torch.empty(N, C_out, Ho, Wo, dtype=x.dtype, device=x.device)
+    if workspace is None:
+        nb = circ_conv_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
+        workspace = torch.empty(max(1, nb), dtype=torch.uint8, device=x.device)
+    _check(getattr(lib(), f"circ_conv_forward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), N, C_in, C_out, H, W, r, stride,
+                                                      pad, k, epilogue, _ptr(workspace), workspace.numel(), _stream()),
+           f"circ_conv_forward_{sfx}")
+    return y
 
 
 def circ_bias_grad(dy, db=None):

@@ -803,7 +803,7 @@ bool plan_conv_tile(int p, int qh, int r, int Ho, int Wo, int ncombo, ConvTilePl
 }
 
 // NT threads per workgroup, QH input channel blocks whose spectra are held in LDS at a time.
-template <int Q, int NT, int QH>
+template <int Q, int NT, int QH, int HM>
 hipError_t launch_conv_fused_t(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
                                int W, int Ho, int Wo, int pad, int ncombo, int relu, hipStream_t s) {
   constexpr int K = 64, R = 3;
@@ -812,14 +812,14 @@ hipError_t launch_conv_fused_t(const float2* wc, const float* x, const float* bi
   if (pl.lds > 64 * 1024) {   // opt in to more than the default LDS limit, once per size increase
     static size_t opted = 0;
     if (pl.lds > opted) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_fused_kernel<K, NT, R, Q, QH>),
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_fused_kernel<K, NT, R, Q, QH, HM>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
         return hipErrorInvalidValue;
       opted = pl.lds;
     }
   }
   const long long grid = (long long)cdiv(N, 2) * pl.tiles_h * pl.tiles_w;
-  hipLaunchKernelGGL((conv_fused_kernel<K, NT, R, Q, QH>), dim3((unsigned)grid), dim3(NT), pl.lds, s, wc, x, bias, y, N, C_out,
+  hipLaunchKernelGGL((conv_fused_kernel<K, NT, R, Q, QH, HM>), dim3((unsigned)grid), dim3(NT), pl.lds, s, wc, x, bias, y, N, C_out,
                      H, W, Ho, Wo, pad, pl.TH, pl.TW, pl.tiles_h, pl.tiles_w, ncombo, relu);
   return hipGetLastError();
 }
@@ -831,12 +831,12 @@ hipError_t launch_conv_fused_t(const float2* wc, const float* x, const float* bi
 #ifndef CIRC_CONV_SMALL_WG
 #define CIRC_CONV_SMALL_WG 1
 #endif
-template <int Q>
+template <int Q, int HM>
 hipError_t launch_conv_fused_q(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
                                int W, int Ho, int Wo, int pad, int ncombo, int relu, hipStream_t s) {
   if (CIRC_CONV_SMALL_WG && ncombo <= 4)
-    return launch_conv_fused_t<Q, 256, 1>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
-  return launch_conv_fused_t<Q, 512, (Q < 2 ? Q : 2)>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+    return launch_conv_fused_t<Q, 256, 1, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+  return launch_conv_fused_t<Q, 512, (Q < 2 ? Q : 2), HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
 }
 
 }  // namespace
@@ -853,12 +853,18 @@ inline bool conv_fused_applicable(int p, int q, int k, int r, int N, int H, int 
          2 * (long long)p * k * HWo < (1ll << 31) && (long long)cdiv(N, 2) * HWo < (1ll << 31);
 }
 
+// HM: 0 fp32, 1 fp16, 2 bfloat16 activations (x, y then point to the 16-bit data)
+template <int HM>
+hipError_t launch_conv_fused_h(const float2* wc, const float* x, const float* bias, float* y, int N, int p, int q, int k,
+                               int r, int H, int W, int Ho, int Wo, int pad, int relu, hipStream_t s) {
+  const int ncombo = conv_fused_ncombo(p, q, k, r), C_out = p * k;
+  return q == 1 ? launch_conv_fused_q<1, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
+       : q == 2 ? launch_conv_fused_q<2, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
+                : launch_conv_fused_q<4, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+}
 hipError_t launch_conv_fused(const float2* wc, const float* x, const float* bias, float* y, int N, int p, int q, int k,
                              int r, int H, int W, int Ho, int Wo, int pad, int relu, hipStream_t s) {
-  const int ncombo = conv_fused_ncombo(p, q, k, r), C_out = p * k;
-  return q == 1 ? launch_conv_fused_q<1>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
-       : q == 2 ? launch_conv_fused_q<2>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
-                : launch_conv_fused_q<4>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+  return launch_conv_fused_h<0>(wc, x, bias, y, N, p, q, k, r, H, W, Ho, Wo, pad, relu, s);
 }
 
 }  // namespace
@@ -1467,6 +1473,97 @@ circ_status fc_backward_half(bool bf, const void* w_hat, const void* x, const vo
   return CIRC_OK;
 }
 
+
+// ---- CONV forward with 16-bit activations (the cached weight spectra stay fp32) ----------------
+template <int K>
+hipError_t launch_rfft_chan16_k(bool bf, const void* in, float2* out, const RowMap& map, long long nrows, long long out_fstride,
+                                hipStream_t s) {
+  FftPlan pl = plan_fft(K, nrows);
+  dim3 grid((unsigned)cdiv(nrows, 2 * pl.P), 1);
+  const float* fin = static_cast<const float*>(in);
+  if (bf)
+    hipLaunchKernelGGL((rfft_kernel<K, true, kHalfRows | kHalfBf16>), grid, dim3(pl.NT), pl.lds, s, fin, out, map, nrows,
+                       out_fstride, 0ll, 0ll, pl.P, 1.0f, 0);
+  else
+    hipLaunchKernelGGL((rfft_kernel<K, true, kHalfRows>), grid, dim3(pl.NT), pl.lds, s, fin, out, map, nrows, out_fstride, 0ll,
+                       0ll, pl.P, 1.0f, 0);
+  return hipGetLastError();
+}
+template <int K>
+hipError_t launch_irfft_chan16_k(bool bf, const float2* in, void* out, const RowMap& map, long long nrows, long long in_fstride,
+                                 const float* bias, long long bias_div, int relu, hipStream_t s) {
+  FftPlan pl = plan_fft(K, nrows);
+  dim3 grid((unsigned)cdiv(nrows, 2 * pl.P));
+  float* fout = static_cast<float*>(out);
+  if (bf)
+    hipLaunchKernelGGL((irfft_kernel<K, true, kHalfRows | kHalfBf16>), grid, dim3(pl.NT), pl.lds, s, in, fout, map, nrows,
+                       in_fstride, pl.P, 1.0f, bias, bias_div, relu, 1, 0ll);
+  else
+    hipLaunchKernelGGL((irfft_kernel<K, true, kHalfRows>), grid, dim3(pl.NT), pl.lds, s, in, fout, map, nrows, in_fstride, pl.P,
+                       1.0f, bias, bias_div, relu, 1, 0ll);
+  return hipGetLastError();
+}
+hipError_t launch_rfft_chan16(int k, bool bf, const void* in, float2* out, const RowMap& map, long long nrows,
+                              long long out_fstride, hipStream_t s) {
+#define CALL(KK) launch_rfft_chan16_k<KK>(bf, in, out, map, nrows, out_fstride, s)
+  CIRC_DISPATCH_HALF_K(k, CALL)
+#undef CALL
+}
+hipError_t launch_irfft_chan16(int k, bool bf, const float2* in, void* out, const RowMap& map, long long nrows,
+                               long long in_fstride, const float* bias, long long bias_div, int relu, hipStream_t s) {
+#define CALL(KK) launch_irfft_chan16_k<KK>(bf, in, out, map, nrows, in_fstride, bias, bias_div, relu, s)
+  CIRC_DISPATCH_HALF_K(k, CALL)
+#undef CALL
+}
+
+circ_status conv_forward_half(bool bf, const void* w_hat, const void* x, const float* bias, void* y, int N, int C_in, int C_out,
+                              int H, int W, int r, int stride, int pad, int k, int epilogue, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k) || !half_k(k)) return CIRC_EINVAL;
+  if (stride <= 0) return CIRC_EINVAL;
+  if (!w_hat || !x || !y) return CIRC_EINVAL;
+  if (epilogue & ~(CIRC_EPI_BIAS | CIRC_EPI_RELU)) return CIRC_EINVAL;
+  const bool use_bias = epilogue & CIRC_EPI_BIAS;
+  if (use_bias && !bias) return CIRC_EINVAL;
+  if (!aligned16(w_hat) || !aligned16(x) || !aligned16(y) || (use_bias && !aligned16(bias))) return CIRC_EINVAL;
+  const int Ho = conv_out(H, r, pad, stride), Wo = conv_out(W, r, pad, stride);
+  const size_t xbytes = size_t(N) * C_in * H * W * sizeof(__half), ybytes = size_t(N) * C_out * Ho * Wo * sizeof(__half);
+  if (overlaps(x, xbytes, y, ybytes)) return CIRC_EINVAL;
+  const size_t need = circ_conv_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k);
+  if (!workspace || workspace_bytes < need) return CIRC_EWORKSPACE;
+  if (!aligned16(workspace)) return CIRC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int p = C_out / k, q = C_in / k, NF = k / 2 + 1;
+  const long long HW = (long long)H * W, HWo = (long long)Ho * Wo;
+  const int relu = (epilogue & CIRC_EPI_RELU) ? 1 : 0;
+  if (stride == 1 && conv_fused_applicable(p, q, k, r, N, H, W, Ho, Wo)) {
+    const float2* wc = blob_at<float2>(w_hat, blob_layout(r * r, p, q, k).conv);
+    const float* xf = static_cast<const float*>(x);
+    float* yf = static_cast<float*>(y);
+    const hipError_t e = bf ? launch_conv_fused_h<2>(wc, xf, use_bias ? bias : nullptr, yf, N, p, q, k, r, H, W, Ho, Wo, pad, relu, s)
+                            : launch_conv_fused_h<1>(wc, xf, use_bias ? bias : nullptr, yf, N, p, q, k, r, H, W, Ho, Wo, pad, relu, s);
+    return e == hipSuccess ? CIRC_OK : CIRC_EHIP;
+  }
+  const long long xrows = (long long)q * N * HW, yrows = (long long)p * N * HWo;
+  float2* xh = static_cast<float2*>(workspace);
+  float2* yh = reinterpret_cast<float2*>(static_cast<char*>(workspace) + align_up(spectrum_elems(k, xrows) * sizeof(float2), 256));
+  // the three kernels of the unfused route; only the loads of x and the stores of y are 16-bit
+  RowMap mx{(int)HW, N, 1, (long long)C_in * HW, (long long)k * HW, HW, HW % 4 == 0};
+  if (launch_rfft_chan16(k, bf, x, xh, mx, xrows, xrows, s) != hipSuccess) return CIRC_EHIP;
+  {
+    constexpr int IT = 4;
+    const long long npix = (long long)N * HWo;
+    dim3 grid((unsigned)cdiv(npix, 256), (unsigned)NF, (unsigned)cdiv(p, IT));
+    hipLaunchKernelGGL((conv_contract_kernel<IT>), grid, dim3(256), 0, s, static_cast<const float2*>(w_hat), xh, yh, p, q, NF,
+                       N, H, W, Ho, Wo, r, pad, 0, stride, 1);
+    if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
+  }
+  RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo, HWo % 4 == 0};
+  if (launch_irfft_chan16(k, bf, yh, y, my, yrows, yrows, use_bias ? bias : nullptr, (long long)N * HWo, relu, s) != hipSuccess)
+    return CIRC_EHIP;
+  return CIRC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1488,6 +1585,18 @@ circ_status circ_fc_forward_f16(const void* w_hat, const void* x, const float* b
 circ_status circ_fc_forward_bf16(const void* w_hat, const void* x, const float* bias, void* y, int p, int q, int k,
                                  int batch, int epilogue, void* workspace, size_t workspace_bytes, void* stream) {
   return fc_forward_half(true, w_hat, x, bias, y, p, q, k, batch, epilogue, workspace, workspace_bytes, stream);
+}
+circ_status circ_conv_forward_f16(const void* w_hat, const void* x, const float* bias, void* y, int N, int C_in, int C_out, int H,
+                                  int W, int r, int stride, int pad, int k, int epilogue, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  return conv_forward_half(false, w_hat, x, bias, y, N, C_in, C_out, H, W, r, stride, pad, k, epilogue, workspace, workspace_bytes,
+                           stream);
+}
+circ_status circ_conv_forward_bf16(const void* w_hat, const void* x, const float* bias, void* y, int N, int C_in, int C_out, int H,
+                                   int W, int r, int stride, int pad, int k, int epilogue, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  return conv_forward_half(true, w_hat, x, bias, y, N, C_in, C_out, H, W, r, stride, pad, k, epilogue, workspace, workspace_bytes,
+                           stream);
 }
 size_t circ_fc_backward_workspace_bytes_f16(int p, int q, int k, int batch) { return fc_backward_workspace_bytes_half(p, q, k, batch); }
 size_t circ_fc_backward_workspace_bytes_bf16(int p, int q, int k, int batch) { return fc_backward_workspace_bytes_half(p, q, k, batch); }

@@ -80,7 +80,10 @@ __device__ __forceinline__ void pack_conv_elem(long long idx, const float2* __re
 // in LDS at a time (the contraction runs in Q/QH rounds over the same accumulators).  All are
 // compile-time so that the weight operands live in registers.
 // One workgroup = one tile of TH x TW output positions of one image pair.
-template <int K, int NT, int R, int Q, int QH>
+// HM: 0 = fp32 activations; 1 (fp16) / 2 (bfloat16): x and y point to 16-bit values (the loads
+// convert on the way into the tile, the stores round the finished outputs; the cached weight
+// spectra, 0.1 % of the bytes of a layer, stay fp32).
+template <int K, int NT, int R, int Q, int QH, int HM = 0>
 __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restrict__ Wc, const float* __restrict__ x,
                                                         const float* __restrict__ bias, float* __restrict__ y,
                                                         int N, int C_out, int H, int W, int Ho, int Wo, int pad,
@@ -125,12 +128,15 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
   constexpr int NLD = 2 * K * RPC * NG / NT;        // tasks per thread and chunk
   static_assert(PT % IWP == 0 && (2 * K * RPC * NG) % NT == 0, "x tasks must split evenly over the threads");
   const int colc = tid % PT;
+  constexpr bool BF = HM == 2;
   const float* ximg = x + (long long)n0 * C_in * HW;
+  const unsigned short* ximg16 = reinterpret_cast<const unsigned short*>(x) + (long long)n0 * C_in * HW;
   const bool second = n0 + 1 < N;
   const int gx0 = w0 - pad, g0 = gx0 >> 2, gsh = gx0 - 4 * g0;   // arithmetic shift = floor division
   auto load_chunk = [&](int ch, float4 (&xr)[NLD]) {  // ch = global chunk index over (j, row chunk)
     const int j = ch / cpj, pc = ch % cpj;
     const float* pj = ximg + (long long)j * K * HW;        // wave-uniform part of the address
+    const unsigned short* pj16 = ximg16 + (long long)j * K * HW;
 #pragma unroll
     for (int it = 0; it < NLD; ++it) {
       const int task = it * NT + tid;
@@ -142,8 +148,13 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
       const bool ok = bool(int(rowg < IH) & int(gh >= 0) & int(gh < H) & int(px0 >= 0) & int(px0 < W) &
                            (int(img == 0) | int(second)));
       // padding is read from a block of zeros: the load itself is unconditional
-      const float* src = ok ? pj + ((img * C_in + chn) * HW + gh * W + px0) : kZeroPixels;
-      xr[it] = *reinterpret_cast<const float4*>(src);
+      if constexpr (HM == 0) {
+        const float* src = ok ? pj + ((img * C_in + chn) * HW + gh * W + px0) : kZeroPixels;
+        xr[it] = *reinterpret_cast<const float4*>(src);
+      } else {
+        const unsigned short* src = ok ? pj16 + ((img * C_in + chn) * HW + gh * W + px0) : reinterpret_cast<const unsigned short*>(kZeroPixels);
+        xr[it] = load_half4<BF>(src);
+      }
     }
   };
   auto store_chunk = [&](const float4 (&xr)[NLD]) {
@@ -330,6 +341,7 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
     const bool lane_ok = c_sub < cpl && oh < Ho && ow < Wo;
     const int zoff = orow * TW + 2 * pr;
     float* yimg = y + (long long)n0 * C_out * HWo + oh * Wo + ow;
+    unsigned short* yimg16 = reinterpret_cast<unsigned short*>(y) + (long long)n0 * C_out * HWo + oh * Wo + ow;
 #pragma unroll 4
     for (int cb = wave * cpl; cb < C_out; cb += NW * cpl) {
       const int c = cb + c_sub;
@@ -343,9 +355,15 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
           o0.x = fmaxf(o0.x, 0.f); o0.y = fmaxf(o0.y, 0.f);
           o1.x = fmaxf(o1.x, 0.f); o1.y = fmaxf(o1.y, 0.f);
         }
-        float* yo = yimg + (long long)c * HWo;
-        *reinterpret_cast<float2*>(yo) = o0;
-        if (second) *reinterpret_cast<float2*>(yo + (long long)C_out * HWo) = o1;
+        if constexpr (HM == 0) {
+          float* yo = yimg + (long long)c * HWo;
+          *reinterpret_cast<float2*>(yo) = o0;
+          if (second) *reinterpret_cast<float2*>(yo + (long long)C_out * HWo) = o1;
+        } else {
+          unsigned short* yo = yimg16 + (long long)c * HWo;
+          *reinterpret_cast<unsigned*>(yo) = pack_pair16<BF>(o0.x, o0.y);
+          if (second) *reinterpret_cast<unsigned*>(yo + (long long)C_out * HWo) = pack_pair16<BF>(o1.x, o1.y);
+        }
       }
     }
   }

@@ -91,7 +91,7 @@ __device__ __forceinline__ float lds_get(const float2* z, int idx, int half) {
 // ROWS_FAST: consecutive rows are adjacent in memory (CONV, NCHW: the FFT axis is the
 // channel axis and pixels are contiguous) — lanes then run along rows when loading.
 // HMODE (see kHalfRows / kHalfSpectra / kHalfBf16): `in` then points to 16-bit rows and / or `out` to 16-bit pairs;
-// offsets and strides keep their meaning in elements.  Contiguous rows with K >= 4 only.
+// offsets and strides keep their meaning in elements.  K >= 4 only.
 template <int K, bool ROWS_FAST, int HMODE = 0>
 __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ out, RowMap map,
                             long long nrows, long long out_fstride, long long in_gstride,
@@ -123,7 +123,11 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
         const int qd = idx & (nq - 1), n = idx >> (lgP - 1);
         long long b = L.rbase[4 * qd];
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n * map.es);
+        if constexpr (HMODE & kHalfRows) {
+          if (b >= 0) v = load_half4<(HMODE & kHalfBf16) != 0>(reinterpret_cast<const unsigned short*>(in) + b + n * map.es);
+        } else {
+          if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n * map.es);
+        }
         float2* zd = L.z + n * PP + 2 * qd;
         zd[0] = make_float2(v.x, v.y);
         zd[1] = make_float2(v.z, v.w);
@@ -133,7 +137,12 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
       for (int idx = tid; idx < 2 * P * K; idx += NT) {
         int row = idx & (2 * P - 1), n = idx >> (lgP + 1);
         long long b = L.rbase[row];
-        float v = b >= 0 ? in[b + n * map.es] : 0.f;
+        float v = 0.f;
+        if constexpr (HMODE & kHalfRows) {
+          if (b >= 0) v = unpack_pair16<(HMODE & kHalfBf16) != 0>(reinterpret_cast<const unsigned short*>(in)[b + n * map.es]).x;
+        } else {
+          if (b >= 0) v = in[b + n * map.es];
+        }
         lds_put(L.z, n * PP + (row >> 1), row & 1, v);
       }
     }
@@ -188,7 +197,7 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
     const int pr = tid & (P - 1), fstep = NT >> lgP;
     const long long rid = t0 + 2 * pr;
     const bool ok0 = rid < nrows, ok1 = rid + 1 < nrows;
-    static_assert(HMODE == 0 || (!ROWS_FAST && K >= 4), "half-width storage: contiguous rows only");
+    static_assert(HMODE == 0 || K >= 4, "half-width storage: K >= 4 only");
     long long o = (long long)(tid >> lgP) * out_fstride + rid;
     const long long ostep = (long long)fstep * out_fstride;
     // whole tile inside the buffer and the pair (rid, rid + 1) aligned to its combined width:
@@ -254,7 +263,7 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
     const int pr = tid & (P - 1), fstep = NT >> lgP;
     const long long rid = t0 + 2 * pr;
     const bool ok0 = rid < nrows, ok1 = rid + 1 < nrows;
-    static_assert(HMODE == 0 || (!ROWS_FAST && K >= 4), "half-width storage: contiguous rows only");
+    static_assert(HMODE == 0 || K >= 4, "half-width storage: K >= 4 only");
     long long s = (long long)(tid >> lgP) * in_fstride + rid;
     const long long sstep = (long long)fstep * in_fstride;
     auto bin = [&](long long e, bool ok) -> float2 {
@@ -382,7 +391,8 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
         v.x += bb; v.y += bb; v.z += bb; v.w += bb;
       }
       if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
-      *reinterpret_cast<float4*>(out + b + n * map.es) = v;
+      if constexpr (HMODE & kHalfRows) store_half4<(HMODE & kHalfBf16) != 0>(reinterpret_cast<unsigned short*>(out) + b + n * map.es, v);
+      else *reinterpret_cast<float4*>(out + b + n * map.es) = v;
     }
   } else {
 #pragma unroll 4
@@ -395,7 +405,9 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
       float v = lds_get(L.z, fft_pos<K>(n) * PP + (row >> 1), row & 1) * scale;
       if (bias) v += bias[(long long)L.rblk[row] * K + n];
       if (relu) v = fmaxf(v, 0.f);
-      out[b + n * map.es] = v;
+      if constexpr (HMODE & kHalfRows)
+        reinterpret_cast<unsigned short*>(out)[b + n * map.es] = (unsigned short)(pack_pair16<(HMODE & kHalfBf16) != 0>(v, 0.f) & 0xffffu);
+      else out[b + n * map.es] = v;
     }
   }
 }

@@ -137,6 +137,10 @@ def bench_conv(cfg, reps, backward=False):
     dense = 2.0 * cfg.N * cfg.H * cfg.W * cfg.r * cfg.r * cfg.C_in * cfg.C_out
     print(f"{cfg.name}: forward {t:9.2f} us/call  {cfg.N / t * 1e6:10.0f} images/s  alg {byts / t * 1e-3:7.1f} GB/s  "
           f"dense-equivalent {dense / t * 1e-6:7.1f} TFLOP/s", flush=True)
+    if cfg.k >= 8 and cfg.k & (cfg.k - 1) == 0:
+        x16, y16 = xd.half(), torch.empty(cfg.N, cfg.C_out, cfg.H, cfg.W, dtype=torch.float16, device=DEV)
+        th = _time(lambda: B.circ_conv_forward_f16(wh, x16, None, y16, cfg.C_out, cfg.r, 1, cfg.pad, cfg.k, 0, ws), reps, max(3, reps // 10))
+        print(f"{cfg.name}: forward, fp16 activations {th:9.2f} us/call  {cfg.N / th * 1e6:10.0f} images/s", flush=True)
     if backward:
         dy = torch.from_numpy(synth.conv_upstream_grad(cfg)).to(DEV)
         dx, dw, db = torch.empty_like(xd), torch.empty_like(wd), torch.empty(cfg.C_out, device=DEV)

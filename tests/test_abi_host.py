@@ -252,6 +252,25 @@ def test_f16_backward_argument_errors():
         assert call(wsb=16) == B.CIRC_EWORKSPACE
 
 
+def test_conv_f16_argument_errors():
+    big = 1 << 28
+    for f in (B.lib().circ_conv_forward_f16, B.lib().circ_conv_forward_bf16):
+
+        def call(w_hat=A, x=A + big, bias=None, y=A + 2 * big, N=2, Ci=16, Co=16, H=5, W=5, r=3, stride=1, pad=1, k=8, epi=0,
+                 wsp=A + 3 * big, wsb=1 << 30):
+            return f(w_hat, x, bias, y, N, Ci, Co, H, W, r, stride, pad, k, epi, wsp, wsb, None)
+
+        assert call(k=4) == B.CIRC_EINVAL                             # below the 16-bit range of k
+        assert call(Ci=12, Co=12, k=12) == B.CIRC_EINVAL              # not a power of two
+        assert call(x=None) == B.CIRC_EINVAL
+        assert call(Ci=20) == B.CIRC_EINVAL                           # channels not a multiple of k
+        assert call(stride=0) == B.CIRC_EINVAL
+        assert call(pad=3) == B.CIRC_EINVAL
+        assert call(epi=B.EPI_BIAS) == B.CIRC_EINVAL
+        assert call(y=A + big) == B.CIRC_EINVAL                       # in place
+        assert call(wsb=16) == B.CIRC_EWORKSPACE
+
+
 def test_bias_grad_argument_errors():
     f = B.lib().circ_bias_grad
     assert f(None, A, 2, 8, 1, None) == B.CIRC_EINVAL

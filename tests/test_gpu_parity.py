@@ -518,6 +518,38 @@ def test_cfg5_backward_half(dtype):
     check_half(dw_s, O.fc_backward_dw(xr, dyr, k, pairs=pairs), "cfg5 dw", dtype)
 
 
+# CONV forward with 16-bit activations: the weight spectra stay fp32, so only x (rounded before the
+# comparison, on both sides) and y are 16-bit: one rounding of the output, gated like the others.
+@pytest.mark.parametrize("dtype", HALF_DTYPES)
+@pytest.mark.parametrize("N,p,q,k,H,W,r,pad,stride", [
+    (2, 4, 4, 64, 28, 28, 3, 1, 1), (3, 2, 1, 64, 14, 12, 3, 1, 1), (1, 1, 2, 64, 8, 8, 3, 0, 1), (5, 16, 4, 64, 6, 8, 3, 1, 1),
+    (2, 2, 3, 8, 9, 8, 3, 1, 2), (3, 1, 2, 16, 7, 7, 3, 0, 1), (2, 2, 2, 32, 8, 8, 2, 0, 2), (2, 3, 1, 8, 9, 10, 5, 2, 1),
+    (2, 1, 1, 128, 5, 7, 1, 0, 1), (2, 2, 2, 64, 13, 12, 3, 1, 3), (1, 1, 1, 512, 3, 4, 3, 1, 1), (2, 2, 2, 256, 6, 5, 3, 1, 1)])
+def test_conv_forward_half(N, p, q, k, H, W, r, pad, stride, dtype):
+    w = (RNG.standard_normal((r, r, p, q, k)) / np.sqrt(r * r * q * k)).astype(np.float32)
+    x = RNG.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32)
+    b = (0.1 * RNG.standard_normal(p * k)).astype(np.float32)
+    xt, xr = to_half(x, dtype)
+    wh = B.circ_precompute_spectra(G.dev(w))
+    what = f"N={N} {p}x{q} k={k} {H}x{W} r={r} pad={pad} stride={stride}"
+    y = B.circ_conv_forward_f16(wh, xt, G.dev(b), None, p * k, r, stride, pad, k, B.EPI_BIAS | B.EPI_RELU)
+    assert y.dtype == dtype
+    check_half(y.float().cpu().numpy(), O.conv_forward(w, xr, b, True, pad, stride), "conv fwd bias+relu " + what, dtype)
+    y = B.circ_conv_forward_f16(wh, xt, None, None, p * k, r, stride, pad, k)
+    check_half(y.float().cpu().numpy(), O.conv_forward(w, xr, None, False, pad, stride), "conv fwd " + what, dtype)
+
+
+@pytest.mark.parametrize("dtype", HALF_DTYPES)
+def test_cfg4_forward_half(dtype):
+    c = synth.CFG4
+    w, x = synth.conv_inputs(c)
+    xt, xr = to_half(x, dtype)
+    wh = B.circ_precompute_spectra(G.dev(w))
+    y = B.circ_conv_forward_f16(wh, xt, None, None, c.C_out, c.r, 1, c.pad, c.k).float().cpu().numpy()
+    for n in (0, c.N - 1):
+        check_half(y[n:n + 1], O.conv_forward(w, xr[n:n + 1], pad=c.pad), f"cfg4 image {n}", dtype)
+
+
 # ---- stride > 1 and even filter sizes (Eq. 6 is the stride-1 case) ---------------------------
 @pytest.mark.parametrize("N,p,q,k,H,W,r,pad,stride", [
     (2, 2, 3, 8, 9, 8, 3, 1, 2), (3, 1, 2, 16, 7, 7, 3, 0, 2), (2, 4, 4, 64, 28, 28, 3, 1, 2), (2, 2, 2, 64, 13, 12, 3, 1, 3),
