@@ -232,7 +232,7 @@ def main():
                    "p": p, "q": q, "k": k, "batch": batch, "launch": f"one hip graph of K independent steps, round-robin over {S} streams"},
         "dense_equivalent_gflops": 2.0 * cfg.n_in * cfg.n_out * batch / t_step * 1e-9,
         "roofline": {
-            "bound": "mfma", "kernel": "circ::fc_fused_kernel<64,8,1,512> (the one kernel of a step)",
+            "bound": "mfma", "kernel": "circ::fc_fused_kernel<64, 8, 1, 512, true, 0> (the one kernel of a step)",
             "achieved": alg_flops / t_step * 1e-12, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": alg_flops / t_step * 1e-12 / MFMA_FP32_PEAK_TFLOPS,
             "traffic": MEASURED_TRAFFIC_BYTES,
