@@ -260,6 +260,20 @@ circ_status circ_conv_forward_bf16(const void* w_hat, const void* x, const float
                                    int k, int epilogue, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * CONV backward with 16-bit activations: x, dy and dx hold fp16 (bf16) values, dw receives the
+ * gradient of the block vectors in fp32; all spectra and the blob (circ_precompute_spectra) stay
+ * fp32, so the roundings are those of the inputs (the caller's) and of dx.  Everything else as
+ * circ_conv_backward, workspace size from circ_conv_backward_workspace_bytes; k a power of two,
+ * 8 <= k <= 512.  dx or dw may be NULL (not both); x may be NULL when dw is.
+ */
+circ_status circ_conv_backward_f16(const void* w_hat, const void* x, const void* dy, void* dx, float* dw,
+                                   int N, int C_in, int C_out, int H, int W, int r, int stride, int pad,
+                                   int k, void* workspace, size_t workspace_bytes, void* stream);
+circ_status circ_conv_backward_bf16(const void* w_hat, const void* x, const void* dy, void* dx, float* dw,
+                                    int N, int C_in, int C_out, int H, int W, int r, int stride, int pad,
+                                    int k, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Bias gradient (Eq. 1: a = Wx + theta, so dL/dtheta is dL/da summed over everything but the
  * channel).  dy is viewed as [outer][channels][inner]:
  *   db[c] = sum_{o, t} dy[(o*channels + c)*inner + t]

@@ -34,6 +34,8 @@ SIGNATURES = {
     "circ_conv_forward": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr] + [_c_int] * 10 + [_c_ptr, _c_size, _c_ptr]),
     "circ_conv_forward_f16": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr] + [_c_int] * 10 + [_c_ptr, _c_size, _c_ptr]),
     "circ_conv_forward_bf16": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr] + [_c_int] * 10 + [_c_ptr, _c_size, _c_ptr]),
+    "circ_conv_backward_f16": (_c_int, [_c_ptr] * 5 + [_c_int] * 9 + [_c_ptr, _c_size, _c_ptr]),
+    "circ_conv_backward_bf16": (_c_int, [_c_ptr] * 5 + [_c_int] * 9 + [_c_ptr, _c_size, _c_ptr]),
     "circ_conv_backward_workspace_bytes": (_c_size, [_c_int] * 9),
     "circ_conv_backward": (_c_int, [_c_ptr] * 5 + [_c_int] * 9 + [_c_ptr, _c_size, _c_ptr]),
     "circ_bias_grad": (_c_int, [_c_ptr, _c_ptr, ctypes.c_longlong, _c_int, ctypes.c_longlong, _c_ptr]),
@@ -294,6 +296,25 @@ def circ_conv_forward_f16(w_hat, x, bias, y, C_out, r, stride, pad, k, epilogue=
                                                       pad, k, epilogue, _ptr(workspace), workspace.numel(), _stream()),
            f"circ_conv_forward_{sfx}")
     return y
+
+
+def circ_conv_backward_f16(w_hat, x, dy, C_in, H, W, r, stride, pad, k, need_dx=True, need_dw=True, dx=None, dw=None,
+                           workspace=None):
+    """dy (and x when need_dw): fp16 or bf16 NCHW.  Returns (dx of the same type or None, dw fp32 [r][r][p][q][k] or None)."""
+    sfx = _half_suffix(dy.dtype)
+    assert dy.is_contiguous() and (x is None or (x.is_contiguous() and x.dtype == dy.dtype))
+    N, C_out = dy.shape[0], dy.shape[1]
+    if need_dx and dx is None:
+        dx = torch.empty(N, C_in, H, W, dtype=dy.dtype, device=dy.device)
+    if need_dw and dw is None:
+        dw = torch.empty(r, r, C_out // k, C_in // k, k, dtype=torch.float32, device=dy.device)
+    if workspace is None:
+        nb = circ_conv_backward_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
+        workspace = torch.empty(max(1, nb), dtype=torch.uint8, device=dy.device)
+    _check(getattr(lib(), f"circ_conv_backward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx) if need_dx else None,
+                                                       _ptr(dw) if need_dw else None, N, C_in, C_out, H, W, r, stride, pad, k,
+                                                       _ptr(workspace), workspace.numel(), _stream()), f"circ_conv_backward_{sfx}")
+    return (dx if need_dx else None), (dw if need_dw else None)
 
 
 def circ_bias_grad(dy, db=None):

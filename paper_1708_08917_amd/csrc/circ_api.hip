@@ -1002,10 +1002,22 @@ size_t circ_conv_backward_workspace_bytes(int N, int C_in, int C_out, int H, int
 namespace {
 
 // CONV backward; dw / w_upd as in fc_backward_impl.
+// the channel-axis transforms with 16-bit rows (defined with the other 16-bit code below)
+hipError_t launch_rfft_chan16(int k, bool bf, const void* in, float2* out, const RowMap& map, long long nrows,
+                              long long out_fstride, hipStream_t s);
+hipError_t launch_irfft_chan16(int k, bool bf, const float2* in, void* out, const RowMap& map, long long nrows,
+                               long long in_fstride, const float* bias, long long bias_div, int relu, hipStream_t s);
+inline bool half_k(int k);
+
+// hm: 0 = fp32 activations; 1 (fp16) / 2 (bfloat16): x, dy and dx point to 16-bit values (all
+// spectra, the weight gradient and the blob stay fp32)
 circ_status conv_backward_impl(const void* w_hat, const float* x, const float* dy, float* dx, float* dw, void* w_upd,
                                float lr, int N, int C_in, int C_out, int H, int W, int r, int stride, int pad, int k,
-                               void* workspace, size_t workspace_bytes, void* stream) {
+                               void* workspace, size_t workspace_bytes, void* stream, int hm = 0) {
   if (!conv_dims_ok(N, C_in, C_out, H, W, r, pad, k)) return CIRC_EINVAL;
+  if (hm != 0 && !half_k(k)) return CIRC_EINVAL;
+  const bool bf = hm == 2;
+  const size_t esz = hm ? sizeof(__half) : sizeof(float);
   if (stride <= 0) return CIRC_EINVAL;
   const bool want_dw = dw || w_upd;
   if (!w_hat || !dy || (!dx && !want_dw) || (want_dw && !x)) return CIRC_EINVAL;
@@ -1014,7 +1026,7 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
   const int p = C_out / k, q = C_in / k, NF = k / 2 + 1;
   // offsets inside one frequency of a spectrum are kept in 32 bits; grid.z holds tiles x offsets
   if ((long long)p * N * Ho * Wo > (1ll << 31) - 1 || (long long)r * r * cdiv(p, 4) * cdiv(q, 4) > 65535) return CIRC_EINVAL;
-  const size_t xbytes = size_t(N) * C_in * H * W * sizeof(float), ybytes = size_t(N) * C_out * Ho * Wo * sizeof(float);
+  const size_t xbytes = size_t(N) * C_in * H * W * esz, ybytes = size_t(N) * C_out * Ho * Wo * esz;
   const size_t wbytes = size_t(r) * r * p * q * k * sizeof(float);
   if (dx && (overlaps(dx, xbytes, dy, ybytes) || (x && overlaps(dx, xbytes, x, xbytes)))) return CIRC_EINVAL;
   if (dw && (overlaps(dw, wbytes, dy, ybytes) || overlaps(dw, wbytes, x, xbytes))) return CIRC_EINVAL;
@@ -1043,14 +1055,18 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
   // (q output blocks, p input blocks, input image Ho x Wo, output image H x W, padding r-1-pad)
   const bool dx_fused = dx && stride == 1 && conv_fused_applicable(q, p, k, r, N, Ho, Wo, H, W);
   if (dx_fused) {
-    if (launch_conv_fused(blob_at<float2>(w_hat, bl.conv_bwd), dy, nullptr, dx, N, q, p, k, r, Ho, Wo, H, W, r - 1 - pad, 0,
-                          s) != hipSuccess)
-      return CIRC_EHIP;
+    const float2* wcb = blob_at<float2>(w_hat, bl.conv_bwd);
+    const hipError_t e = hm == 0 ? launch_conv_fused_h<0>(wcb, dy, nullptr, dx, N, q, p, k, r, Ho, Wo, H, W, r - 1 - pad, 0, s)
+                       : hm == 1 ? launch_conv_fused_h<1>(wcb, dy, nullptr, dx, N, q, p, k, r, Ho, Wo, H, W, r - 1 - pad, 0, s)
+                                 : launch_conv_fused_h<2>(wcb, dy, nullptr, dx, N, q, p, k, r, Ho, Wo, H, W, r - 1 - pad, 0, s);
+    if (e != hipSuccess) return CIRC_EHIP;
   }
   // dY^[f][i][n][pixel]: the FFT runs down the channel axis of dy
   RowMap my{(int)HWo, N, 1, (long long)C_out * HWo, (long long)k * HWo, HWo, HWo % 4 == 0};
   if (want_dw || (dx && !dx_fused)) {
-    if (launch_rfft(k, true, dy, yh, my, yrows, yrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    if ((hm ? launch_rfft_chan16(k, bf, dy, yh, my, yrows, yrows, s) : launch_rfft(k, true, dy, yh, my, yrows, yrows, 1, 0, 0, 1.0f, 0, s)) !=
+        hipSuccess)
+      return CIRC_EHIP;
   }
   RowMap mx{(int)HW, N, 1, (long long)C_in * HW, (long long)k * HW, HW, HW % 4 == 0};
   if (dx && !dx_fused) {
@@ -1062,10 +1078,14 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
     hipLaunchKernelGGL((conv_contract_kernel<IT>), grid, dim3(256), 0, s, blob_at<float2>(w_hat, bl.bwd), yh, xh, q, p,
                        NF, N, Ho, Wo, H, W, r, r - 1 - pad, 1, 1, stride);
     if (hipGetLastError() != hipSuccess) return CIRC_EHIP;
-    if (launch_irfft(k, true, xh, dx, mx, xrows, xrows, 1.0f, nullptr, 1, 0, s) != hipSuccess) return CIRC_EHIP;
+    if ((hm ? launch_irfft_chan16(k, bf, xh, dx, mx, xrows, xrows, nullptr, 1, 0, s)
+            : launch_irfft(k, true, xh, dx, mx, xrows, xrows, 1.0f, nullptr, 1, 0, s)) != hipSuccess)
+      return CIRC_EHIP;
   }
   if (want_dw) {
-    if (launch_rfft(k, true, x, xh, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s) != hipSuccess) return CIRC_EHIP;
+    if ((hm ? launch_rfft_chan16(k, bf, x, xh, mx, xrows, xrows, s) : launch_rfft(k, true, x, xh, mx, xrows, xrows, 1, 0, 0, 1.0f, 0, s)) !=
+        hipSuccess)
+      return CIRC_EHIP;
     const ConvDwPlan dpl = plan_conv_dw(N, H, W, Ho, Wo, r, pad, stride);
     const long long npix = (long long)N * HWo, ppb = dpl.ppb;
     const int nchunks = dpl.nparts;
@@ -1597,6 +1617,20 @@ circ_status circ_conv_forward_bf16(const void* w_hat, const void* x, const float
                                    size_t workspace_bytes, void* stream) {
   return conv_forward_half(true, w_hat, x, bias, y, N, C_in, C_out, H, W, r, stride, pad, k, epilogue, workspace, workspace_bytes,
                            stream);
+}
+circ_status circ_conv_backward_f16(const void* w_hat, const void* x, const void* dy, void* dx, float* dw, int N, int C_in,
+                                   int C_out, int H, int W, int r, int stride, int pad, int k, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  if (!dx && !dw) return CIRC_EINVAL;
+  return conv_backward_impl(w_hat, static_cast<const float*>(x), static_cast<const float*>(dy), static_cast<float*>(dx), dw,
+                            nullptr, 0.f, N, C_in, C_out, H, W, r, stride, pad, k, workspace, workspace_bytes, stream, 1);
+}
+circ_status circ_conv_backward_bf16(const void* w_hat, const void* x, const void* dy, void* dx, float* dw, int N, int C_in,
+                                    int C_out, int H, int W, int r, int stride, int pad, int k, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  if (!dx && !dw) return CIRC_EINVAL;
+  return conv_backward_impl(w_hat, static_cast<const float*>(x), static_cast<const float*>(dy), static_cast<float*>(dx), dw,
+                            nullptr, 0.f, N, C_in, C_out, H, W, r, stride, pad, k, workspace, workspace_bytes, stream, 2);
 }
 size_t circ_fc_backward_workspace_bytes_f16(int p, int q, int k, int batch) { return fc_backward_workspace_bytes_half(p, q, k, batch); }
 size_t circ_fc_backward_workspace_bytes_bf16(int p, int q, int k, int batch) { return fc_backward_workspace_bytes_half(p, q, k, batch); }

@@ -271,6 +271,23 @@ def test_conv_f16_argument_errors():
         assert call(wsb=16) == B.CIRC_EWORKSPACE
 
 
+def test_conv_backward_f16_argument_errors():
+    big = 1 << 28
+    for f in (B.lib().circ_conv_backward_f16, B.lib().circ_conv_backward_bf16):
+
+        def call(w_hat=A, x=A + big, dy=A + 2 * big, dx=A + 3 * big, dw=A + 4 * big, N=2, Ci=16, Co=16, H=5, W=5, r=3, stride=1,
+                 pad=1, k=8, wsp=A + 5 * big, wsb=1 << 30):
+            return f(w_hat, x, dy, dx, dw, N, Ci, Co, H, W, r, stride, pad, k, wsp, wsb, None)
+
+        assert call(k=4) == B.CIRC_EINVAL
+        assert call(Ci=12, Co=12, k=12) == B.CIRC_EINVAL              # not a power of two
+        assert call(dy=None) == B.CIRC_EINVAL
+        assert call(dx=None, dw=None) == B.CIRC_EINVAL
+        assert call(x=None) == B.CIRC_EINVAL                          # dw needs x
+        assert call(dx=A + 2 * big) == B.CIRC_EINVAL                  # dx aliases dy
+        assert call(wsb=16) == B.CIRC_EWORKSPACE
+
+
 def test_bias_grad_argument_errors():
     f = B.lib().circ_bias_grad
     assert f(None, A, 2, 8, 1, None) == B.CIRC_EINVAL

@@ -537,6 +537,14 @@ def test_conv_forward_half(N, p, q, k, H, W, r, pad, stride, dtype):
     check_half(y.float().cpu().numpy(), O.conv_forward(w, xr, b, True, pad, stride), "conv fwd bias+relu " + what, dtype)
     y = B.circ_conv_forward_f16(wh, xt, None, None, p * k, r, stride, pad, k)
     check_half(y.float().cpu().numpy(), O.conv_forward(w, xr, None, False, pad, stride), "conv fwd " + what, dtype)
+    # backward on the same 16-bit activations: dx rounded to 16 bits, dw in fp32
+    Ho, Wo = (H + 2 * pad - r) // stride + 1, (W + 2 * pad - r) // stride + 1
+    dy = RNG.uniform(-1, 1, (N, p * k, Ho, Wo)).astype(np.float32)
+    dyt, dyr = to_half(dy, dtype)
+    dx, dw = B.circ_conv_backward_f16(wh, xt, dyt, q * k, H, W, r, stride, pad, k)
+    assert dx.dtype == dtype and dw.dtype == torch.float32
+    check_half(dx.float().cpu().numpy(), O.conv_backward_dx(w, dyr, H, W, pad, stride), "conv dx " + what, dtype)
+    check(dw.cpu().numpy(), O.conv_backward_dw(xr, dyr, k, r, pad, stride), "conv dw (fp32 from 16-bit inputs) " + what)
 
 
 @pytest.mark.parametrize("dtype", HALF_DTYPES)

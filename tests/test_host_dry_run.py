@@ -52,6 +52,8 @@ DRIVER = textwrap.dedent(r'''
         if k >= 8 and k & (k - 1) == 0:
             assert L.circ_conv_forward_f16(P[0], P[1], None, P[2], N, Ci, Co, H, W, r, 1, pad, k, 0, P[3], ws, None) == 0
             assert L.circ_conv_forward_bf16(P[0], P[1], None, P[2], N, Ci, Co, H, W, r, 2, pad, k, 0, P[3], ws, None) == 0
+            assert L.circ_conv_backward_f16(P[0], P[1], P[2], P[3], P[4], N, Ci, Co, H, W, r, 1, pad, k, P[5], ws, None) == 0
+            assert L.circ_conv_backward_bf16(P[0], P[1], P[2], P[3], P[4], N, Ci, Co, H, W, r, 2, pad, k, P[5], ws, None) == 0
         assert L.circ_conv_sgd_step(P[0], P[1], P[2], None, c_f(0.1), N, Ci, Co, H, W, r, 1, pad, k, P[5], ws, None) == 0
         for st in (2, 3):
             assert L.circ_conv_forward(P[0], P[1], None, P[2], N, Ci, Co, H, W, r, st, pad, k, 0, P[3], ws, None) == 0
@@ -85,6 +87,7 @@ DRIVER = textwrap.dedent(r'''
         L.circ_conv_workspace_bytes(N, Ci, Co, H, W, r, st, pad, k); L.circ_conv_backward_workspace_bytes(N, Ci, Co, H, W, r, st, pad, k)
         L.circ_conv_forward(P[0], P[1], None, P[2], N, Ci, Co, H, W, r, st, pad, k, 0, P[3], ws, None)
         L.circ_conv_forward_f16(P[0], P[1], None, P[2], N, Ci, Co, H, W, r, st, pad, k, 0, P[3], ws, None)
+        L.circ_conv_backward_bf16(P[0], P[1], P[2], P[3], P[4], N, Ci, Co, H, W, r, st, pad, k, P[5], ws, None)
         L.circ_conv_backward(P[0], P[1], P[2], P[3], P[4], N, Ci, Co, H, W, r, st, pad, k, P[5], ws, None)
         L.circ_conv_backward(P[0], P[1], P[2], None, P[4], N, Ci, Co, H, W, r, st, pad, k, P[5], ws, None)
         L.circ_conv_sgd_step(P[0], P[1], P[2], None, c_f(0.1), N, Ci, Co, H, W, r, st, pad, k, P[5], ws, None)
