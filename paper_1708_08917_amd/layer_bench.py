@@ -123,6 +123,24 @@ def bench_chain(cfgs, reps):
     names = " -> ".join([str(cfgs[0].n_in)] + [f"{c.n_out} (k={c.k})" for c in cfgs])
     print(f"chain {names}, batch {cfgs[0].batch}: {t:9.2f} us/pass  {cfgs[0].batch / t * 1e6:10.0f} inputs/s  "
           f"{len(cfgs) / t * 1e6:10.0f} layers/s", flush=True)
+    if all(c.k >= 8 and c.k & (c.k - 1) == 0 for c in cfgs):
+        # the same stack with fp16 storage of activations and weight spectra
+        layers16 = []
+        for (wh, xin, bd, y, c, epi, ws), cfg in zip(layers, cfgs):
+            w, _, _ = synth.fc_inputs(cfg)
+            wh16 = B.circ_precompute_spectra_f16(torch.from_numpy(w).to(DEV))
+            ws16 = torch.empty(max(1, B.circ_fc_workspace_bytes_f16(c.p, c.q, c.k, c.batch)), dtype=torch.uint8, device=DEV)
+            layers16.append((wh16, xin.half(), bd, y.half(), c, epi, ws16))
+        for i in range(1, len(layers16)):   # each layer reads the previous one's output buffer
+            l = layers16[i]
+            layers16[i] = (l[0], layers16[i - 1][3], l[2], l[3], l[4], l[5], l[6])
+
+        def run16():
+            for wh16, xin, bd, y, c, epi, ws16 in layers16:
+                B.circ_fc_forward_f16(wh16, xin, bd, y, c.p, c.q, c.k, epi, ws16)
+
+        t16 = _time(run16, reps, max(3, reps // 10))
+        print(f"chain {names}, batch {cfgs[0].batch}, fp16 storage: {t16:9.2f} us/pass  {len(cfgs) / t16 * 1e6:10.0f} layers/s", flush=True)
 
 
 def bench_conv(cfg, reps, backward=False):
