@@ -171,6 +171,65 @@ __device__ __forceinline__ void fft_lds_single(const float2* z, int PP, int col,
   for (int f = 0; f < K; ++f) sink(f, make_float2(re[f], im[f]));
 }
 
+// ---- an 8-point transform spread over 8 consecutive lanes ----------------------------
+// For tiles with few columns (the inverse transform of the fused kernel: 8 columns) the
+// lane-local sub-transforms above leave most of a workgroup idle, and the few lanes that work run
+// a chain of ~100 dependent instructions per pass.  Here lane m (m = lane % 8) holds point m, the
+// three radix-2 stages (decimation in frequency) exchange values with lanes m^4, m^2, m^1 through
+// DPP moves, and the chain is ~30 instructions.  On return lane m holds output index bitrev3(m).
+__device__ __forceinline__ int bitrev3(int m) { return ((m & 1) << 2) | (m & 2) | ((m >> 2) & 1); }
+
+__device__ __forceinline__ float lane_xor4(float v) {
+  // lanes with bit 2 clear (banks 0 and 2 of a row of 16) take lane + 4, the others lane - 4
+  int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x104 /* row_shl:4 */, 0xF, 0x5, false);
+  t = __builtin_amdgcn_update_dpp(t, __float_as_int(v), 0x114 /* row_shr:4 */, 0xF, 0xA, false);
+  return __int_as_float(t);
+}
+__device__ __forceinline__ float lane_xor2(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float lane_xor1(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false));
+}
+
+// Per-lane constants of the three stages: the sign that turns (mine, other) into a + b or a - b,
+// and the twiddles of the upper halves, W8^(m & 3) after the first stage and W4^(m & 1) after
+// the second (forward: e^{-2 pi i ./8}; INV: e^{+2 pi i ./8}).
+template <bool INV>
+struct Fft8Lanes {
+  float s4, s2, s1;      // -1 in the upper half of the stage's pairs, +1 in the lower
+  float c1, d1, c2, d2;  // twiddles (cos, signed sin) after stages 1 and 2; (1, 0) in the lower halves
+  __device__ __forceinline__ explicit Fft8Lanes(int m) {
+    constexpr float r = 0.70710678118654752440f;
+    s4 = (m & 4) ? -1.f : 1.f;
+    s2 = (m & 2) ? -1.f : 1.f;
+    s1 = (m & 1) ? -1.f : 1.f;
+    const int a = m & 3;
+    float c = a == 0 ? 1.f : (a == 1 ? r : (a == 2 ? 0.f : -r));
+    float d = a == 0 ? 0.f : (a == 2 ? 1.f : r);
+    c1 = (m & 4) ? c : 1.f;
+    d1 = (m & 4) ? (INV ? d : -d) : 0.f;
+    c2 = ((m & 2) && (m & 1)) ? 0.f : 1.f;
+    d2 = ((m & 2) && (m & 1)) ? (INV ? 1.f : -1.f) : 0.f;
+  }
+  __device__ __forceinline__ void run(float& re, float& im) const {
+    // stage 1: pairs (m, m^4)
+    float tr = fmaf(s4, re, lane_xor4(re)), ti = fmaf(s4, im, lane_xor4(im));
+    re = tr * c1 - ti * d1;
+    im = tr * d1 + ti * c1;
+    // stage 2: pairs (m, m^2)
+    tr = fmaf(s2, re, lane_xor2(re));
+    ti = fmaf(s2, im, lane_xor2(im));
+    re = tr * c2 - ti * d2;
+    im = tr * d2 + ti * c2;
+    // stage 3: pairs (m, m^1), no twiddle
+    tr = fmaf(s1, re, lane_xor1(re));
+    ti = fmaf(s1, im, lane_xor1(im));
+    re = tr;
+    im = ti;
+  }
+};
+
 // ---- addressing of "rows" (the length-K vectors that are transformed) ----------------
 // Row ids enumerate the rows in the order of the spectrum buffer:
 // spectrum[f][rid].  A row id decomposes as rid = (a*n1 + b)*n0 + c and the first

@@ -466,7 +466,27 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
   }
   __syncthreads();
   CIRC_PROBE(60);
-  {
+  if constexpr (K == 64) {
+    // few columns (IT*NP), 8 x 8 points each: every 8-point sub-transform runs on 8 lanes
+    // (Fft8Lanes), so that all waves take part and the dependent chain per pass is short
+    const int m = tid & 7, fo = bitrev3(m);
+    const Fft8Lanes<true> F(m);
+    for (int task = tid >> 3; task < PTI * 8; task += NT / 8) {      // pass 1: (column, n2), lane = n1
+      const int n2 = task & 7, coli = task >> 3;
+      float2 v = z[(8 * m + n2) * PPI + coli];
+      const float2 w = twl[fo * n2];                                 // twiddle of output f1 = fo
+      F.run(v.x, v.y);
+      z[(8 * fo + n2) * PPI + coli] = make_float2(w.x * v.x - w.y * v.y, w.x * v.y + w.y * v.x);
+    }
+    __syncthreads();
+    for (int task = tid >> 3; task < PTI * 8; task += NT / 8) {      // pass 2: (column, f1), lane = n2
+      const int f1 = task & 7, coli = task >> 3;
+      float2 v = z[(8 * f1 + m) * PPI + coli];
+      F.run(v.x, v.y);
+      z[(8 * f1 + fo) * PPI + coli] = v;                             // index f1 + 8*f2 at fft_pos = 8*f1 + f2
+    }
+    __syncthreads();
+  } else {
     const int coli = tid % PTI, ti = tid / PTI;
     constexpr int TTI = NT / PTI;
     fft_lds_pass1<K, true>(z, PPI, coli, ti, TTI, twl);
