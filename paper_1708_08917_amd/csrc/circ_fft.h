@@ -230,6 +230,70 @@ struct Fft8Lanes {
   }
 };
 
+// The same for 16 points on 16 consecutive lanes (one DPP row): a first stage over the pairs
+// (m, m^8) with twiddles W16^(m & 7), then the 8-point network on each half.  `w16` is that
+// twiddle of the lane, (cos, sin)(2 pi (m & 7) / 16), e.g. from the LDS table of K roots at index
+// (m & 7) * K / 16.  On return lane m holds output index bitrev4(m).
+__device__ __forceinline__ int bitrev4(int m) { return ((m & 1) << 3) | ((m & 2) << 1) | ((m & 4) >> 1) | ((m >> 3) & 1); }
+__device__ __forceinline__ float lane_xor8(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128 /* row_ror:8 */, 0xF, 0xF, false));
+}
+template <bool INV>
+struct Fft16Lanes {
+  Fft8Lanes<INV> f8;
+  float s8, c0, d0;
+  __device__ __forceinline__ Fft16Lanes(int m, float2 w16) : f8(m & 7) {
+    s8 = (m & 8) ? -1.f : 1.f;
+    c0 = (m & 8) ? w16.x : 1.f;
+    d0 = (m & 8) ? (INV ? w16.y : -w16.y) : 0.f;
+  }
+  __device__ __forceinline__ void run(float& re, float& im) const {
+    const float tr = fmaf(s8, re, lane_xor8(re)), ti = fmaf(s8, im, lane_xor8(im));
+    re = tr * c0 - ti * d0;
+    im = tr * d0 + ti * c0;
+    f8.run(re, im);
+  }
+};
+
+// A transform of R points (8 or 16) on R consecutive lanes; lane m in, index lane_rev<R>(m) out.
+template <int R>
+__device__ __forceinline__ int lane_rev(int m) { return R == 8 ? bitrev3(m) : bitrev4(m); }
+template <int R, int K, bool INV>
+__device__ __forceinline__ void fft_lanes(float2& v, int m, const float2* twl) {
+  static_assert(R == 8 || R == 16, "8 or 16 lanes");
+  if constexpr (R == 8) {
+    const Fft8Lanes<INV> F(m);
+    F.run(v.x, v.y);
+  } else {
+    const Fft16Lanes<INV> F(m, twl[(m & 7) * (K / 16)]);
+    F.run(v.x, v.y);
+  }
+}
+
+// One column of K = R1*R2 points (both 8 or 16; element n at z[n*stride]) transformed by the
+// first K threads of the workgroup, every sub-transform on R1 (then R2) lanes.  In place; index f
+// ends at position fft_pos<K>(f), as with the lane-local passes.  Call with all threads (it
+// holds the barrier between the passes); twl must be staged.
+template <int K, bool INV>
+__device__ __forceinline__ void fft_column_lanes(float2* z, int stride, int tid, const float2* twl) {
+  constexpr int R2 = radix2_of(K), R1 = radix1_of(K);
+  if (tid < K) {                                   // pass 1: lane = n1, task = n2
+    const int m = tid % R1, n2 = tid / R1, fo = lane_rev<R1>(m);
+    float2 v = z[(R2 * m + n2) * stride];
+    const float2 w = twl[fo * n2];
+    fft_lanes<R1, K, INV>(v, m, twl);
+    const float s = INV ? w.y : -w.y;
+    z[(R2 * fo + n2) * stride] = make_float2(w.x * v.x - s * v.y, w.x * v.y + s * v.x);
+  }
+  __syncthreads();
+  if (tid < K) {                                   // pass 2: lane = n2, task = f1
+    const int m = tid % R2, f1 = tid / R2;
+    float2 v = z[(R2 * f1 + m) * stride];
+    fft_lanes<R2, K, INV>(v, m, twl);
+    z[(R2 * f1 + lane_rev<R2>(m)) * stride] = v;
+  }
+}
+
 // ---- addressing of "rows" (the length-K vectors that are transformed) ----------------
 // Row ids enumerate the rows in the order of the spectrum buffer:
 // spectrum[f][rid].  A row id decomposes as rid = (a*n1 + b)*n0 + c and the first

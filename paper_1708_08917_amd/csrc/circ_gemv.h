@@ -276,9 +276,22 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
   }
   // inverse transform of the single column (row stride 2); afterwards sample n of the pair sits
   // at position opos(n)
-  if constexpr (K <= 16) {
+  if constexpr (K == 8 || K == 16) {
+    // one short column: its K points on K lanes (DPP exchanges) instead of one thread's ~170
+    // dependent instructions
+    float2* zo = z + 2 * K;                      // natural order, behind the input column
+    if (tid < K) {
+      float2 v = z[2 * tid];
+      fft_lanes<K, K, true>(v, tid, twl);
+      zo[2 * lane_rev<K>(tid)] = v;
+    }
+    __syncthreads();
+  } else if constexpr (K <= 16) {
     float2* zo = z + 2 * K;                      // natural order, behind the input column
     if (tid == 0) fft_lds_single<K, true>(z, 2, 0, [&](int n, float2 v) { zo[2 * n] = v; });
+    __syncthreads();
+  } else if constexpr (K == 64 || K == 128 || K == 256) {
+    fft_column_lanes<K, true>(z, 2, tid, twl);   // sub-transforms of 8 or 16 points, on as many lanes each
     __syncthreads();
   } else {
     fft_lds_pass1<K, true>(z, 2, 0, tid, NT, twl);
