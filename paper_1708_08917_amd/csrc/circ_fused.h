@@ -392,8 +392,7 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
     }
   }
 
-  // --- sum the partial accumulators; waves that split the j range meet in LDS, and the
-  // additions happen in a fixed order, so the result is deterministic
+  // --- sum the accumulation chains of this wave, in a fixed order
 #pragma unroll
   for (int cc = 0; cc < CPW; ++cc)
 #pragma unroll
@@ -406,40 +405,14 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
         Q[0][cc][u] += Q[1][cc][u];
       }
     }
-  if constexpr (JS > 1) {
-    if (js > 0) {
-#pragma unroll
-      for (int cc = 0; cc < CPW; ++cc)
-#pragma unroll
-        for (int u = 0; u < NP; ++u) {
-          float* r = red + ((((js - 1) * NCOMBO + combo0 + cc) * NP + u) * 8) * 64 + lane;
-#pragma unroll
-          for (int m = 0; m < 4; ++m) {
-            r[m * 64] = P[0][cc][u][m];
-            r[(4 + m) * 64] = Q[0][cc][u][m];
-          }
-        }
-    }
-    __syncthreads();
-    if (js == 0) {
-#pragma unroll
-      for (int s2 = 1; s2 < JS; ++s2)
-#pragma unroll
-        for (int cc = 0; cc < CPW; ++cc)
-#pragma unroll
-          for (int u = 0; u < NP; ++u) {
-            const float* r = red + ((((s2 - 1) * NCOMBO + combo0 + cc) * NP + u) * 8) * 64 + lane;
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-              P[0][cc][u][m] += r[m * 64];
-              Q[0][cc][u][m] += r[(4 + m) * 64];
-            }
-          }
-    }
-  }
-
+  // Waves that split the j range (JS = 2) each assemble the output spectra of their share: the
+  // first into the inverse tile, the second into a twin of it in `red`; the first pass of the
+  // inverse transform adds the twin as it reads (first + second: a fixed order), which saves a
+  // round trip through LDS and a barrier over summing the accumulators first.
+  static_assert(JS <= 2 && (JS == 1 || K == 64), "the twin tile is added by the k = 64 inverse transform only");
+  static_assert(JS == 1 || Sh::RED_FLOATS >= 2 * K * PPI, "the twin tile must fit the reduction buffer");
   // --- assemble Zy of every (output block row, batch pair) into the inverse tile
-  if (js == 0) {
+  {
     const int n = lane & 3, blk = lane >> 2;
 #pragma unroll
     for (int cc = 0; cc < CPW; ++cc) {
@@ -452,7 +425,7 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
       const float ca = (slot == 0 && n >= 2) ? 0.f : 1.f;
       const float cb = (slot == 0 && n >= 2) ? 1.f : 0.f;
       const float cs = slot == 0 ? 0.f : ((n == 0 || n == 3) ? -1.f : 1.f);
-      float* zl = reinterpret_cast<float*>(z) + 2 * (fidx * PPI + 4 * ig * NP) + (n & 1);
+      float* zl = (js == 0 ? reinterpret_cast<float*>(z) : red) + 2 * (fidx * PPI + 4 * ig * NP) + (n & 1);
 #pragma unroll
       for (int u = 0; u < NP; ++u) {
 #pragma unroll
@@ -474,6 +447,11 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
     for (int task = tid >> 3; task < PTI * 8; task += NT / 8) {      // pass 1: (column, n2), lane = n1
       const int n2 = task & 7, coli = task >> 3;
       float2 v = z[(8 * m + n2) * PPI + coli];
+      if constexpr (JS > 1) {                                        // the second wave's share of the j range
+        const float2 v2 = reinterpret_cast<const float2*>(red)[(8 * m + n2) * PPI + coli];
+        v.x += v2.x;
+        v.y += v2.y;
+      }
       const float2 w = twl[fo * n2];                                 // twiddle of output f1 = fo
       F.run(v.x, v.y);
       z[(8 * fo + n2) * PPI + coli] = make_float2(w.x * v.x - w.y * v.y, w.x * v.y + w.y * v.x);
