@@ -310,16 +310,30 @@ __global__ __launch_bounds__(256) void sum_parts_kernel(float* __restrict__ part
 // threads of a block are what keeps enough loads in flight).  Fixed order: each thread adds its
 // strided elements in index order, a butterfly adds the lanes of a wave, one thread the 16 waves.
 __global__ __launch_bounds__(1024) void bias_grad_channel_kernel(const float* __restrict__ dy, float* __restrict__ db,
-                                                                 long long outer, int channels, long long inner) {
+                                                                 long long outer, int channels, long long inner, int vec4) {
   __shared__ float red[16];
   const int c = blockIdx.x, tid = threadIdx.x;
   float s = 0.f;
   const long long total = outer * inner;
   // flat element index e = o*inner + t of this channel; the loads of a thread are independent
+  if (vec4) {
+    // inner is a multiple of 4 (a 16-byte group never straddles two images), dy is 16-byte
+    // aligned and total < 2^32 (host checks): 16-byte loads, 32-bit index arithmetic
+    const unsigned ngroups = unsigned(total >> 2), inner4 = unsigned(inner >> 2);
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll 4
+    for (unsigned g = tid; g < ngroups; g += 1024) {
+      const unsigned o = g / inner4, t4 = g - o * inner4;
+      const float4 v = *reinterpret_cast<const float4*>(dy + ((long long)o * channels + c) * inner + 4 * t4);
+      s += v.x; s1 += v.y; s2 += v.z; s3 += v.w;
+    }
+    s = (s + s1) + (s2 + s3);
+  } else {
 #pragma unroll 8
-  for (long long e = tid; e < total; e += 1024) {
-    const long long o = e / inner, t = e - o * inner;
-    s += dy[(o * channels + c) * inner + t];
+    for (long long e = tid; e < total; e += 1024) {
+      const long long o = e / inner, t = e - o * inner;
+      s += dy[(o * channels + c) * inner + t];
+    }
   }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) s += __shfl_down(s, off, 64);
