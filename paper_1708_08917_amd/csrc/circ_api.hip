@@ -1166,7 +1166,7 @@ circ_status circ_bias_grad(const float* dy, float* db, long long outer, int chan
   if (overlaps(db, size_t(channels) * sizeof(float), dy, ybytes)) return CIRC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (inner == 1)
-    hipLaunchKernelGGL(bias_grad_column_kernel, dim3((unsigned)cdiv(channels, 64)), dim3(256), 0, s, dy, db, outer, channels);
+    hipLaunchKernelGGL(bias_grad_column_kernel, dim3((unsigned)cdiv(channels, 64)), dim3(1024), 0, s, dy, db, outer, channels);
   else
     hipLaunchKernelGGL(bias_grad_channel_kernel, dim3((unsigned)channels), dim3(1024), 0, s, dy, db, outer, channels, inner,
                        int(inner % 4 == 0 && outer * inner < (1ll << 32)));

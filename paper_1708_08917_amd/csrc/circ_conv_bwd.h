@@ -347,19 +347,36 @@ __global__ __launch_bounds__(1024) void bias_grad_channel_kernel(const float* __
   }
 }
 
-// inner == 1 (FC: dy[batch][m]): a block owns 64 consecutive columns; its four waves take the
-// rows r = wave, wave + 4, ... and their sums are added in wave order.
-__global__ __launch_bounds__(256) void bias_grad_column_kernel(const float* __restrict__ dy, float* __restrict__ db,
-                                                               long long rows, int cols) {
-  __shared__ float red[4][64];
+// inner == 1 (FC: dy[batch][m]): a block owns 64 consecutive columns; its 16 waves take the
+// rows r = wave, wave + 16, ... and their sums are added in wave order.
+__global__ __launch_bounds__(1024) void bias_grad_column_kernel(const float* __restrict__ dy, float* __restrict__ db,
+                                                                long long rows, int cols) {
+  // 64 columns per block, 16 waves: wave w adds rows w, w + 16, ... with four independent partial
+  // sums (several loads in flight per lane); fixed order throughout
+  __shared__ float red[16][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + lane;
-  float s = 0.f;
-  if (c < cols)
-    for (long long rr = wave; rr < rows; rr += 4) s += dy[rr * cols + c];
-  red[wave][lane] = s;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (c < cols) {
+    const float* col = dy + c;
+    long long rr = wave;
+#pragma unroll 2
+    for (; rr + 48 < rows; rr += 64) {
+      s0 += col[rr * cols];
+      s1 += col[(rr + 16) * cols];
+      s2 += col[(rr + 32) * cols];
+      s3 += col[(rr + 48) * cols];
+    }
+    for (; rr < rows; rr += 16) s0 += col[rr * cols];
+  }
+  red[wave][lane] = (s0 + s1) + (s2 + s3);
   __syncthreads();
-  if (wave == 0 && c < cols) db[c] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+  if (wave == 0 && c < cols) {
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += red[w][lane];
+    db[c] = tot;
+  }
 }
 
 }  // namespace circ

@@ -83,7 +83,9 @@ def bench_fc(cfg, reps, backward=False):
         tb = _time(lambda: B.circ_fc_backward(wh, xd, dy, cfg.p, cfg.q, cfg.k, True, True, dx, dw, ws), r, 3)
         tdx = _time(lambda: B.circ_fc_backward(wh, xd, dy, cfg.p, cfg.q, cfg.k, True, False, dx, None, ws), r, 3)
         tdw = _time(lambda: B.circ_fc_backward(wh, xd, dy, cfg.p, cfg.q, cfg.k, False, True, None, dw, ws), r, 3)
-        print(f"{cfg.name}: backward {tb:9.2f} us/call (dx only {tdx:.2f}, dw only {tdw:.2f})  dense-equivalent "
+        db = torch.empty(cfg.n_out, device=DEV)
+        tdb = _time(lambda: B.circ_bias_grad(dy, db), r, 3)
+        print(f"{cfg.name}: backward {tb:9.2f} us/call (dx only {tdx:.2f}, dw only {tdw:.2f}; bias gradient {tdb:.2f})  dense-equivalent "
               f"{4.0 * cfg.n_in * cfg.n_out * cfg.batch / tb * 1e-6:7.1f} TFLOP/s", flush=True)
         # dx + step on the cached spectra (lr = 0 keeps the weights as they are over the repetitions),
         # against dx + dw + precompute of the new weights
