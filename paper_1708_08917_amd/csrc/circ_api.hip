@@ -1105,10 +1105,19 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
     // staged element index / W: indices stay below 48 KB / 32 B, so the multiply-high is exact
     const unsigned mul_w = (unsigned)(((1ll << 32) + W - 1) / W);
     if (dpl.lds) {
-      dim3 grid((unsigned)dpl.nparts, (unsigned)NF, (unsigned)(cdiv(r * r, 16) * cdiv(p, 4) * cdiv(q, 4)));
       const unsigned mul_wo_b = (unsigned)(((1ll << 32) + Wo - 1) / Wo);   // pixel index inside a band / Wo
-      hipLaunchKernelGGL(conv_dw_lds_kernel, grid, dim3(256), dpl.lds_bytes, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo, r,
-                         pad, dpl.BR, dpl.nbands, dpl.cpb, wstride, mul_wo_b, mul_w, stride);
+      // tiles of 2 x 2 channel blocks (one matrix instruction per pixel) when that takes fewer
+      // instructions than tiles of 4 x 4 (four per pixel): layers with at most 2 blocks on a side
+      const long long t2 = cdiv(p, 2) * cdiv(q, 2), t4 = cdiv(p, 4) * cdiv(q, 4);
+      if (t2 < 4 * t4 && cdiv(r * r, 16) * t2 <= 65535) {
+        dim3 grid((unsigned)dpl.nparts, (unsigned)NF, (unsigned)(cdiv(r * r, 16) * t2));
+        hipLaunchKernelGGL((conv_dw_lds_kernel<true>), grid, dim3(256), dpl.lds_bytes, s, yh, xh, wpart, p, q, NF, N, H, W, Ho,
+                           Wo, r, pad, dpl.BR, dpl.nbands, dpl.cpb, wstride, mul_wo_b, mul_w, stride);
+      } else {
+        dim3 grid((unsigned)dpl.nparts, (unsigned)NF, (unsigned)(cdiv(r * r, 16) * t4));
+        hipLaunchKernelGGL((conv_dw_lds_kernel<false>), grid, dim3(256), dpl.lds_bytes, s, yh, xh, wpart, p, q, NF, N, H, W, Ho,
+                           Wo, r, pad, dpl.BR, dpl.nbands, dpl.cpb, wstride, mul_wo_b, mul_w, stride);
+      }
     } else if (r % CIRC_DW_NG == 0) {   // CIRC_DW_NG consecutive offsets per block (for r = 3: one filter row)
       dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r / CIRC_DW_NG * cdiv(p, 4) * cdiv(q, 4)));
       hipLaunchKernelGGL((conv_dw_mfma_kernel<CIRC_DW_NG>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo,

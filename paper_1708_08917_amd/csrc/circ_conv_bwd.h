@@ -163,6 +163,13 @@ __global__ __launch_bounds__(256) void conv_dw_mfma_kernel(const float2* __restr
 // four planes a wave reads at once start 8 banks apart.
 __host__ __device__ inline int dw_plane_stride(int n) { return n + (20 - n % 16) % 16; }
 
+// PAIR: tiles of 2 x 2 channel blocks for layers with few of them.  The rows of the matrix
+// instruction then are (output block, re / im of dY^) and its columns (input block, re / im of X^):
+// one instruction per pixel yields all four real products of every one of the 4 block pairs (the
+// 4 x 4 form spends four instructions per pixel on 16 pairs, most of them absent when p, q <= 2),
+// and a lane reads 4 bytes per operand instead of 8.  Re = rr + ii and Im = ir - ri are put
+// together from a lane and its neighbour (same input block, other component) at the end.
+template <bool PAIR>
 __global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restrict__ dyh, const float2* __restrict__ xh,
                                                           float2* __restrict__ part, int p, int q, int NF, int Nimg,
                                                           int H, int W, int Ho, int Wo, int r, int pad, int BR,
@@ -171,12 +178,13 @@ __global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restri
   extern __shared__ float2 xs[];                  // [4 input blocks][rows_in][Wp], then [4 output blocks][BR*Wo]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), f = blockIdx.y;
   const int blk = lane >> 2, sub = lane & 3;
-  const int nit = (p + 3) / 4, njt = (q + 3) / 4;
+  constexpr int T = PAIR ? 2 : 4;                 // channel blocks per tile side
+  const int nit = (p + T - 1) / T, njt = (q + T - 1) / T;
   int z = blockIdx.z;
   const int jt = z % njt; z /= njt;
   const int it = z % nit;
   const int g0 = (z / nit) * 16;
-  const int i0 = it * 4, j0 = jt * 4;
+  const int i0 = it * T, j0 = jt * T;
   const int Wp = W + 2 * pad;
   const int rows_in = (BR - 1) * stride + r, plane = rows_in * W;   // input rows under a band of BR output rows
   const int planep = dw_plane_stride(rows_in * Wp), dplane = dw_plane_stride(BR * Wo);
@@ -188,9 +196,11 @@ __global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restri
 
   // this lane's offset (lanes past r*r repeat the last offset; their sums are never stored)
   const int gl = min(g0 + blk, r * r - 1);
-  const float2* xsl = xs + sub * planep + (gl / r) * Wp + gl % r;   // staged column = wo + (gl % r - pad) + pad
-  const float2* dsl = dys + sub * dplane;
-  dw_floatx4 accR[2], accI[2];                    // two independent chains (even / odd pixels of a step)
+  const float2* xsl = xs + (PAIR ? sub >> 1 : sub) * planep + (gl / r) * Wp + gl % r;   // staged column = wo + (gl % r - pad) + pad
+  const float2* dsl = dys + (PAIR ? sub >> 1 : sub) * dplane;
+  const float* xslf = reinterpret_cast<const float*>(xsl) + (sub & 1);   // PAIR: this lane's component of X^ ...
+  const float* dslf = reinterpret_cast<const float*>(dsl) + (sub & 1);   // ... and of dY^
+  dw_floatx4 accR[2], accI[2];                    // two independent chains (even / odd pixels of a step); PAIR uses accR only
 #pragma unroll
   for (int e = 0; e < 2; ++e) {
     accR[e] = dw_floatx4{0.f, 0.f, 0.f, 0.f};
@@ -209,9 +219,9 @@ __global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restri
     // outside the image.  The four blocks are fetched together (four independent loads per step).
     {
       const int e0 = (ho0 * stride - pad) * W;
-      const float2* src[4];
+      const float2* src[T];
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj)
+      for (int jj = 0; jj < T; ++jj)
         src[jj] = xf + (unsigned(min(j0 + jj, q - 1)) * unsigned(Nimg) + unsigned(n)) * HW;
 #pragma unroll 2
       for (int t = tid; t < plane; t += 256) {
@@ -220,24 +230,24 @@ __global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restri
         const int ec = min(max(e, 0), int(HW) - 1);
         const int row = int(__umulhi(unsigned(t), mul_w));
         const int dst = t + row * (2 * pad) + pad;   // row*Wp + pad + column
-        float2 v[4];
+        float2 v[T];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) v[jj] = src[jj][ec];
+        for (int jj = 0; jj < T; ++jj) v[jj] = src[jj][ec];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
+        for (int jj = 0; jj < T; ++jj)
           xs[jj * planep + dst] = (in_img && j0 + jj < q) ? v[jj] : make_float2(0.f, 0.f);
       }
-      const float2* dsrc[4];
+      const float2* dsrc[T];
 #pragma unroll
-      for (int ii = 0; ii < 4; ++ii)
+      for (int ii = 0; ii < T; ++ii)
         dsrc[ii] = dyf + unsigned(min(i0 + ii, p - 1)) * unsigned(npix) + unsigned(n) * HWo + unsigned(ho0) * unsigned(Wo);
 #pragma unroll 2
       for (int t = tid; t < npx; t += 256) {
-        float2 v[4];
+        float2 v[T];
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) v[ii] = dsrc[ii][t];
+        for (int ii = 0; ii < T; ++ii) v[ii] = dsrc[ii][t];
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) dys[ii * dplane + t] = i0 + ii < p ? v[ii] : make_float2(0.f, 0.f);
+        for (int ii = 0; ii < T; ++ii) dys[ii * dplane + t] = i0 + ii < p ? v[ii] : make_float2(0.f, 0.f);
       }
     }
     __syncthreads();
@@ -253,35 +263,66 @@ __global__ __launch_bounds__(256) void conv_dw_lds_kernel(const float2* __restri
       return stride * (pix + hl * (Wp - Wo));
     };
     int pix = wave;
-    for (; pix + 12 < npx; pix += 16) {
-      float2 dv[4], xv[4];
+    if constexpr (PAIR) {
+      for (; pix + 12 < npx; pix += 16) {
+        float dv[4], xv[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        dv[u] = dsl[pix + 4 * u];
-        xv[u] = xsl[tap(pix + 4 * u)];
+        for (int u = 0; u < 4; ++u) {
+          dv[u] = dslf[2 * (pix + 4 * u)];
+          xv[u] = xslf[2 * tap(pix + 4 * u)];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) accR[u & 1] = __builtin_amdgcn_mfma_f32_4x4x1f32(dv[u], xv[u], accR[u & 1], 0, 0, 0);
       }
+      for (; pix < npx; pix += 4) accR[0] = __builtin_amdgcn_mfma_f32_4x4x1f32(dslf[2 * pix], xslf[2 * tap(pix)], accR[0], 0, 0, 0);
+    } else {
+      for (; pix + 12 < npx; pix += 16) {
+        float2 dv[4], xv[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) mac(u & 1, dv[u], xv[u]);
+        for (int u = 0; u < 4; ++u) {
+          dv[u] = dsl[pix + 4 * u];
+          xv[u] = xsl[tap(pix + 4 * u)];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) mac(u & 1, dv[u], xv[u]);
+      }
+      for (; pix < npx; pix += 4) mac(0, dsl[pix], xsl[tap(pix)]);
     }
-    for (; pix < npx; pix += 4) mac(0, dsl[pix], xsl[tap(pix)]);
   }
 
   // sums over the four waves: accumulators -> LDS (the staging area is free after the barrier)
   __syncthreads();
   float* wsum = reinterpret_cast<float*>(xs);    // [wave][value m*2 + c][lane]
+  if constexpr (PAIR) {
+    // register m = row (output block m / 2, component m % 2); this lane's column = (input block
+    // sub / 2, component sub % 2).  Lanes of component 0 take the neighbour's sums:
+    //   Re(i, j) = rr + ii = mine[2i] + other[2i + 1],  Im(i, j) = ir - ri = mine[2i + 1] - other[2i]
+    float mine[4], other[4];
 #pragma unroll
-  for (int m = 0; m < 4; ++m) {
-    wsum[(wave * 8 + 2 * m + 0) * 64 + lane] = accR[0][m] + accR[1][m];
-    wsum[(wave * 8 + 2 * m + 1) * 64 + lane] = accI[0][m] + accI[1][m];
+    for (int m = 0; m < 4; ++m) {
+      mine[m] = accR[0][m] + accR[1][m];
+      other[m] = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mine[m]), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false));
+    }
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii) {
+      wsum[(wave * 8 + 2 * ii + 0) * 64 + lane] = mine[2 * ii] + other[2 * ii + 1];
+      wsum[(wave * 8 + 2 * ii + 1) * 64 + lane] = mine[2 * ii + 1] - other[2 * ii];
+    }
+  } else {
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      wsum[(wave * 8 + 2 * m + 0) * 64 + lane] = accR[0][m] + accR[1][m];
+      wsum[(wave * 8 + 2 * m + 1) * 64 + lane] = accI[0][m] + accI[1][m];
+    }
   }
   __syncthreads();
   const long long rows = (long long)r * r * p * q;
   float* out = reinterpret_cast<float*>(part + (long long)blockIdx.x * part_stride + (long long)f * rows);
-  for (int v = tid; v < 8 * 64; v += 256) {
-    const int ln = v & 63, e = v >> 6;           // e = m*2 + c
+  for (int v = tid; v < (PAIR ? 4 : 8) * 64; v += 256) {
+    const int ln = v & 63, e = v >> 6;           // e = m*2 + c (PAIR: m = output block of the pair, lanes of component 0 only)
     const int c = e & 1, m = e >> 1;
-    const int gg = g0 + (ln >> 2), i = i0 + m, j = j0 + (ln & 3);
-    if (gg < r * r && i < p && j < q)
+    const int gg = g0 + (ln >> 2), i = i0 + m, j = j0 + (PAIR ? (ln & 3) >> 1 : ln & 3);
+    if (gg < r * r && i < p && j < q && !(PAIR && (ln & 1)))
       out[2 * (((long long)gg * p + i) * q + j) + c] =
           (wsum[(0 * 8 + e) * 64 + ln] + wsum[(1 * 8 + e) * 64 + ln]) + (wsum[(2 * 8 + e) * 64 + ln] + wsum[(3 * 8 + e) * 64 + ln]);
   }
