@@ -60,11 +60,11 @@ inline size_t gemv_section_elems(int n_grids, int p, int q, int k) {      // in 
   return size_t(p) * q * (k / 2);
 }
 
-// Fused CONV kernel: built for k = 64, 3x3 filters, q in {1, 2, 4} input channel blocks and
+// Fused CONV kernel: built for k = 64, 3x3 filters, q in {1, 2, 3, 4, 6, 8} input channel blocks and
 // up to 16 output channel blocks.  ncombo = (slot groups) x (groups of 4 output blocks, rounded
 // up to a power of two) must divide the 8 waves of a workgroup.
 inline int conv_fused_ncombo(int p, int q, int k, int r) {
-  if (k != 64 || r != 3 || !(q == 1 || q == 2 || q == 4)) return 0;
+  if (k != 64 || r != 3 || !(q == 1 || q == 2 || q == 3 || q == 4 || q == 6 || q == 8)) return 0;
   int ig = 1;
   while (ig * 4 < p) ig *= 2;
   const int ncombo = (k / 32) * ig;
@@ -786,7 +786,7 @@ bool plan_conv_tile(int p, int qh, int r, int Ho, int Wo, int ncombo, ConvTilePl
   const int max_pos = Sh::MAXT * (Sh::NW / ncombo);
   long long best_cost = -1;
   for (int th = 1; th <= Ho && th + r - 1 <= 16; ++th)
-    for (int tw = 2; tw <= Wo && tw + r - 1 <= 16; tw += 2) {   // row pitch of 16 input positions; outputs stored in pairs
+    for (int tw = 2; tw <= Wo + (Wo & 1) && tw + r - 1 <= 16; tw += 2) {   // row pitch of 16 input positions; outputs stored in pairs
       if (th * tw > max_pos) continue;
       const int ipos = (th + r - 1) * 16;
       const size_t lds = conv_fused_lds_bytes<K, NT>(qh * ipos, p * th * tw);
@@ -803,8 +803,10 @@ bool plan_conv_tile(int p, int qh, int r, int Ho, int Wo, int ncombo, ConvTilePl
 }
 
 // NT threads per workgroup, QH input channel blocks whose spectra are held in LDS at a time.
-template <int Q, int NT, int QH, int HM>
-hipError_t launch_conv_fused_t(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
+// RAGGED: rows that are not 4n input pixels and 2n output pixels long (element-wise loads and
+// stores instead of aligned 16-byte loads and paired stores).
+template <int Q, int NT, int QH, int HM, bool RAGGED>
+hipError_t launch_conv_fused_r(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
                                int W, int Ho, int Wo, int pad, int ncombo, int relu, hipStream_t s) {
   constexpr int K = 64, R = 3;
   ConvTilePlan pl;
@@ -812,16 +814,23 @@ hipError_t launch_conv_fused_t(const float2* wc, const float* x, const float* bi
   if (pl.lds > 64 * 1024) {   // opt in to more than the default LDS limit, once per size increase
     static size_t opted = 0;
     if (pl.lds > opted) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_fused_kernel<K, NT, R, Q, QH, HM>),
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_fused_kernel<K, NT, R, Q, QH, HM, RAGGED>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
         return hipErrorInvalidValue;
       opted = pl.lds;
     }
   }
   const long long grid = (long long)cdiv(N, 2) * pl.tiles_h * pl.tiles_w;
-  hipLaunchKernelGGL((conv_fused_kernel<K, NT, R, Q, QH, HM>), dim3((unsigned)grid), dim3(NT), pl.lds, s, wc, x, bias, y, N, C_out,
-                     H, W, Ho, Wo, pad, pl.TH, pl.TW, pl.tiles_h, pl.tiles_w, ncombo, relu);
+  hipLaunchKernelGGL((conv_fused_kernel<K, NT, R, Q, QH, HM, RAGGED>), dim3((unsigned)grid), dim3(NT), pl.lds, s, wc, x, bias, y,
+                     N, C_out, H, W, Ho, Wo, pad, pl.TH, pl.TW, pl.tiles_h, pl.tiles_w, ncombo, relu);
   return hipGetLastError();
+}
+template <int Q, int NT, int QH, int HM>
+hipError_t launch_conv_fused_t(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
+                               int W, int Ho, int Wo, int pad, int ncombo, int relu, hipStream_t s) {
+  if (W % 4 != 0 || Wo % 2 != 0)
+    return launch_conv_fused_r<Q, NT, QH, HM, true>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+  return launch_conv_fused_r<Q, NT, QH, HM, false>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
 }
 
 // Up to 4 (slot group, row group) combinations (p <= 8) run as workgroups of 256 threads with one
@@ -834,22 +843,26 @@ hipError_t launch_conv_fused_t(const float2* wc, const float* x, const float* bi
 template <int Q, int HM>
 hipError_t launch_conv_fused_q(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
                                int W, int Ho, int Wo, int pad, int ncombo, int relu, hipStream_t s) {
-  if (CIRC_CONV_SMALL_WG && ncombo <= 4)
+  // ... provided there are enough of them for two per CU; a grid that leaves most CUs with one
+  // workgroup is served faster by the larger workgroups (twice the waves on every serial phase)
+  ConvTilePlan pl;
+  const bool small_wg = CIRC_CONV_SMALL_WG && ncombo <= 4 && plan_conv_tile<64, 256>(C_out / 64, 1, 3, Ho, Wo, ncombo, pl) &&
+                        (long long)cdiv(N, 2) * pl.tiles_h * pl.tiles_w >= 384;
+  if (small_wg)
     return launch_conv_fused_t<Q, 256, 1, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
-  return launch_conv_fused_t<Q, 512, (Q < 2 ? Q : 2), HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+  return launch_conv_fused_t<Q, 512, (Q % 2 == 0 ? 2 : 1), HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
 }
 
 }  // namespace
 
 namespace {
 
-// The fused CONV kernel serves k = 64, 3x3 filters, 1, 2 or 4 input channel blocks and up to 16
-// output channel blocks; it loads aligned groups of 4 pixels and stores pairs of outputs, and
-// keeps offsets inside an image pair in 32 bits.  p, q: output / input channel blocks; H x W the
+// The fused CONV kernel serves k = 64, 3x3 filters, 1, 2, 3, 4, 6 or 8 input channel blocks and up
+// to 16 output channel blocks; it keeps offsets inside an image pair in 32 bits.  p, q: output / input channel blocks; H x W the
 // input image, Ho x Wo the output image.
 inline bool conv_fused_applicable(int p, int q, int k, int r, int N, int H, int W, int Ho, int Wo) {
   const long long HW = (long long)H * W, HWo = (long long)Ho * Wo;
-  return conv_fused_ncombo(p, q, k, r) > 0 && W % 4 == 0 && Wo % 2 == 0 && 2 * (long long)q * k * HW < (1ll << 31) &&
+  return conv_fused_ncombo(p, q, k, r) > 0 && Wo >= 2 && 2 * (long long)q * k * HW < (1ll << 31) &&
          2 * (long long)p * k * HWo < (1ll << 31) && (long long)cdiv(N, 2) * HWo < (1ll << 31);
 }
 
@@ -858,9 +871,15 @@ template <int HM>
 hipError_t launch_conv_fused_h(const float2* wc, const float* x, const float* bias, float* y, int N, int p, int q, int k,
                                int r, int H, int W, int Ho, int Wo, int pad, int relu, hipStream_t s) {
   const int ncombo = conv_fused_ncombo(p, q, k, r), C_out = p * k;
-  return q == 1 ? launch_conv_fused_q<1, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
-       : q == 2 ? launch_conv_fused_q<2, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s)
-                : launch_conv_fused_q<4, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+  switch (q) {
+    case 1: return launch_conv_fused_q<1, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+    case 2: return launch_conv_fused_q<2, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+    case 3: return launch_conv_fused_q<3, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+    case 4: return launch_conv_fused_q<4, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+    case 6: return launch_conv_fused_q<6, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+    case 8: return launch_conv_fused_q<8, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 hipError_t launch_conv_fused(const float2* wc, const float* x, const float* bias, float* y, int N, int p, int q, int k,
                              int r, int H, int W, int Ho, int Wo, int pad, int relu, hipStream_t s) {

@@ -83,7 +83,7 @@ __device__ __forceinline__ void pack_conv_elem(long long idx, const float2* __re
 // HM: 0 = fp32 activations; 1 (fp16) / 2 (bfloat16): x and y point to 16-bit values (the loads
 // convert on the way into the tile, the stores round the finished outputs; the cached weight
 // spectra, 0.1 % of the bytes of a layer, stay fp32).
-template <int K, int NT, int R, int Q, int QH, int HM = 0>
+template <int K, int NT, int R, int Q, int QH, int HM = 0, bool RAGGED = false>
 __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restrict__ Wc, const float* __restrict__ x,
                                                         const float* __restrict__ bias, float* __restrict__ y,
                                                         int N, int C_out, int H, int W, int Ho, int Wo, int pad,
@@ -148,12 +148,30 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
       const bool ok = bool(int(rowg < IH) & int(gh >= 0) & int(gh < H) & int(px0 >= 0) & int(px0 < W) &
                            (int(img == 0) | int(second)));
       // padding is read from a block of zeros: the load itself is unconditional
-      if constexpr (HM == 0) {
-        const float* src = ok ? pj + ((img * C_in + chn) * HW + gh * W + px0) : kZeroPixels;
-        xr[it] = *reinterpret_cast<const float4*>(src);
+      if constexpr (!RAGGED) {
+        if constexpr (HM == 0) {
+          const float* src = ok ? pj + ((img * C_in + chn) * HW + gh * W + px0) : kZeroPixels;
+          xr[it] = *reinterpret_cast<const float4*>(src);
+        } else {
+          const unsigned short* src = ok ? pj16 + ((img * C_in + chn) * HW + gh * W + px0) : reinterpret_cast<const unsigned short*>(kZeroPixels);
+          xr[it] = load_half4<BF>(src);
+        }
       } else {
-        const unsigned short* src = ok ? pj16 + ((img * C_in + chn) * HW + gh * W + px0) : reinterpret_cast<const unsigned short*>(kZeroPixels);
-        xr[it] = load_half4<BF>(src);
+        // rows that are no multiple of 4 pixels: a group is neither aligned nor entirely inside
+        // the row, so its pixels are fetched one by one, each with its own test
+        float vals[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bool oke = ok && px0 + e < W;
+          const int off = oke ? (img * C_in + chn) * HW + gh * W + px0 + e : 0;
+          if constexpr (HM == 0) {
+            vals[e] = oke ? pj[off] : 0.f;
+          } else {
+            const unsigned short hv = oke ? pj16[off] : (unsigned short)0;
+            vals[e] = unpack_pair16<BF>(unsigned(hv)).x;
+          }
+        }
+        xr[it] = make_float4(vals[0], vals[1], vals[2], vals[3]);
       }
     }
   };
@@ -339,6 +357,7 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
     const int orow = rem / NPAIR, pr = rem - orow * NPAIR;
     const int oh = h0 + orow, ow = w0 + 2 * pr;
     const bool lane_ok = c_sub < cpl && oh < Ho && ow < Wo;
+    const bool two = ow + 1 < Wo;                           // false only for the last column of an odd row length
     const int zoff = orow * TW + 2 * pr;
     float* yimg = y + (long long)n0 * C_out * HWo + oh * Wo + ow;
     unsigned short* yimg16 = reinterpret_cast<unsigned short*>(y) + (long long)n0 * C_out * HWo + oh * Wo + ow;
@@ -357,12 +376,33 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
         }
         if constexpr (HM == 0) {
           float* yo = yimg + (long long)c * HWo;
-          *reinterpret_cast<float2*>(yo) = o0;
-          if (second) *reinterpret_cast<float2*>(yo + (long long)C_out * HWo) = o1;
+          float* yo1 = yo + (long long)C_out * HWo;
+          if constexpr (!RAGGED) {
+            *reinterpret_cast<float2*>(yo) = o0;
+            if (second) *reinterpret_cast<float2*>(yo1) = o1;
+          } else {                                          // odd row length: pairs are not aligned
+            yo[0] = o0.x;
+            if (two) yo[1] = o0.y;
+            if (second) {
+              yo1[0] = o1.x;
+              if (two) yo1[1] = o1.y;
+            }
+          }
         } else {
           unsigned short* yo = yimg16 + (long long)c * HWo;
-          *reinterpret_cast<unsigned*>(yo) = pack_pair16<BF>(o0.x, o0.y);
-          if (second) *reinterpret_cast<unsigned*>(yo + (long long)C_out * HWo) = pack_pair16<BF>(o1.x, o1.y);
+          unsigned short* yo1 = yo + (long long)C_out * HWo;
+          const unsigned w0p = pack_pair16<BF>(o0.x, o0.y), w1p = pack_pair16<BF>(o1.x, o1.y);
+          if constexpr (!RAGGED) {
+            *reinterpret_cast<unsigned*>(yo) = w0p;
+            if (second) *reinterpret_cast<unsigned*>(yo1) = w1p;
+          } else {
+            yo[0] = (unsigned short)(w0p & 0xffffu);
+            if (two) yo[1] = (unsigned short)(w0p >> 16);
+            if (second) {
+              yo1[0] = (unsigned short)(w1p & 0xffffu);
+              if (two) yo1[1] = (unsigned short)(w1p >> 16);
+            }
+          }
         }
       }
     }

@@ -179,13 +179,16 @@ def test_conv_forward_shapes(N, p, q, k, H, W, r, pad):
     _conv_case(N, p, q, k, H, W, r, pad)
 
 
-# ---- fused CONV kernel (k = 64, 3x3, q in {1,2,4}, p <= 16, image rows a multiple of 4 pixels):
-# odd image counts, ragged tiles in both directions, every padding, every row-group count; the
-# shapes with other row lengths take the unfused route
+# ---- fused CONV kernel (k = 64, 3x3, q in {1,2,3,4,6,8}, p <= 16): odd image counts, ragged tiles
+# in both directions, every padding, every row-group count; rows that are a multiple of 4 input
+# and 2 output pixels (aligned vector loads and paired stores) and rows that are not (13 x 13,
+# 7 x 7, 14 x 14: element-wise loads and stores)
 @pytest.mark.parametrize("N,p,q,H,W,pad", [(1, 1, 1, 5, 8, 1), (3, 4, 4, 9, 12, 1), (2, 5, 2, 13, 8, 0), (5, 9, 1, 7, 32, 2),
                                            (2, 16, 4, 8, 8, 1), (4, 3, 2, 28, 28, 1), (1, 2, 4, 3, 4, 0), (2, 4, 4, 33, 4, 2),
                                            (3, 2, 2, 10, 20, 1), (2, 4, 4, 16, 16, 0), (1, 1, 1, 5, 5, 1), (3, 4, 4, 9, 11, 1),
-                                           (2, 5, 2, 13, 6, 0)])
+                                           (2, 5, 2, 13, 6, 0), (3, 6, 6, 13, 13, 1), (2, 3, 3, 8, 8, 1), (2, 2, 8, 7, 7, 1),
+                                           (1, 8, 6, 14, 14, 1), (2, 4, 3, 13, 13, 2), (1, 1, 1, 4, 3, 1), (2, 2, 1, 5, 17, 0),
+                                           (1, 3, 8, 6, 31, 1)])
 def test_conv_forward_fused_shapes(N, p, q, H, W, pad):
     _conv_case(N, p, q, 64, H, W, 3, pad)
 
@@ -220,11 +223,13 @@ def test_conv_backward_shapes(N, p, q, k, H, W, r, pad):
 
 
 # backward-data on the fused forward kernel (k = 64, 3x3; the p x q grid is transposed, so it needs
-# p in {1, 2, 4} and q <= 16, and rows of dy that are a multiple of 4 pixels): odd image
-# counts, ragged tiles, every padding; the shapes that do not qualify take the unfused route
+# p in {1, 2, 3, 4, 6, 8} and q <= 16): odd image counts, ragged tiles, every padding, aligned and
+# unaligned row lengths; the shapes that do not qualify take the unfused route
 @pytest.mark.parametrize("N,p,q,H,W,pad", [(1, 1, 1, 5, 8, 1), (3, 4, 4, 9, 12, 1), (2, 2, 5, 13, 8, 0), (5, 1, 9, 7, 32, 2),
                                            (2, 4, 16, 8, 8, 1), (4, 2, 3, 28, 28, 1), (1, 4, 2, 3, 6, 0), (2, 4, 4, 33, 4, 2),
-                                           (3, 2, 2, 10, 20, 1), (2, 3, 4, 16, 16, 1), (1, 1, 1, 5, 5, 1), (2, 5, 2, 13, 6, 0)])
+                                           (3, 2, 2, 10, 20, 1), (2, 3, 4, 16, 16, 1), (1, 1, 1, 5, 5, 1), (2, 5, 2, 13, 6, 0),
+                                           (3, 6, 6, 13, 13, 1), (2, 8, 2, 7, 7, 1), (1, 6, 8, 14, 14, 1), (2, 3, 4, 13, 13, 0),
+                                           (1, 1, 1, 4, 3, 1), (2, 8, 3, 6, 31, 2)])
 def test_conv_backward_fused_shapes(N, p, q, H, W, pad):
     k, r = 64, 3
     w = (RNG.standard_normal((r, r, p, q, k)) * np.sqrt(2.0 / (r * r * q * k))).astype(np.float32)
@@ -524,7 +529,8 @@ def test_cfg5_backward_half(dtype):
 @pytest.mark.parametrize("N,p,q,k,H,W,r,pad,stride", [
     (2, 4, 4, 64, 28, 28, 3, 1, 1), (3, 2, 1, 64, 14, 12, 3, 1, 1), (1, 1, 2, 64, 8, 8, 3, 0, 1), (5, 16, 4, 64, 6, 8, 3, 1, 1),
     (2, 2, 3, 8, 9, 8, 3, 1, 2), (3, 1, 2, 16, 7, 7, 3, 0, 1), (2, 2, 2, 32, 8, 8, 2, 0, 2), (2, 3, 1, 8, 9, 10, 5, 2, 1),
-    (2, 1, 1, 128, 5, 7, 1, 0, 1), (2, 2, 2, 64, 13, 12, 3, 1, 3), (1, 1, 1, 512, 3, 4, 3, 1, 1), (2, 2, 2, 256, 6, 5, 3, 1, 1)])
+    (2, 1, 1, 128, 5, 7, 1, 0, 1), (2, 2, 2, 64, 13, 12, 3, 1, 3), (1, 1, 1, 512, 3, 4, 3, 1, 1), (2, 2, 2, 256, 6, 5, 3, 1, 1),
+    (3, 6, 6, 64, 13, 13, 3, 1, 1), (2, 3, 8, 64, 7, 7, 3, 1, 1), (1, 2, 3, 64, 14, 14, 3, 0, 1)])
 def test_conv_forward_half(N, p, q, k, H, W, r, pad, stride, dtype):
     w = (RNG.standard_normal((r, r, p, q, k)) / np.sqrt(r * r * q * k)).astype(np.float32)
     x = RNG.uniform(-1, 1, (N, q * k, H, W)).astype(np.float32)
@@ -678,7 +684,7 @@ def test_random_shapes_sweep(seed):
             pad = int(rng.integers(0, r))
             H, W = int(rng.integers(1, 18)), int(rng.integers(1, 18))
             if rng.integers(0, 2):
-                W = max(4, (W // 4) * 4)                 # rows that are a multiple of 4 pixels can take the fused kernel
+                W = max(4, (W // 4) * 4)                 # rows that are a multiple of 4 pixels take the aligned loads of the fused kernel
             while W + 2 * pad < r:
                 W += 4
             while H + 2 * pad < r:
