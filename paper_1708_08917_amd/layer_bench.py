@@ -214,6 +214,11 @@ def main():
                  backward=a.backward)
         bench_conv(synth.ConvConfig("conv3x3_c384_13x13_k96_n32", 32, 384, 384, 13, 13, 3, 1, 1, 96, index=6), a.reps,
                    backward=a.backward)
+        # the same layer as 6 x 6 blocks of 64 (fused kernel; rows of 13 pixels: element-wise loads), at two batch sizes
+        bench_conv(synth.ConvConfig("conv3x3_c384_13x13_k64_n32", 32, 384, 384, 13, 13, 3, 1, 1, 64, index=8), a.reps,
+                   backward=a.backward)
+        bench_conv(synth.ConvConfig("conv3x3_c384_13x13_k64_n128", 128, 384, 384, 13, 13, 3, 1, 1, 64, index=9), a.reps,
+                   backward=a.backward)
     if sel("cfg5"):
         bench_fc(synth.CFG5, max(10, a.reps // 4), backward=a.backward or a.config == "all")
 
