@@ -188,7 +188,7 @@ def test_conv_forward_shapes(N, p, q, k, H, W, r, pad):
                                            (3, 2, 2, 10, 20, 1), (2, 4, 4, 16, 16, 0), (1, 1, 1, 5, 5, 1), (3, 4, 4, 9, 11, 1),
                                            (2, 5, 2, 13, 6, 0), (3, 6, 6, 13, 13, 1), (2, 3, 3, 8, 8, 1), (2, 2, 8, 7, 7, 1),
                                            (1, 8, 6, 14, 14, 1), (2, 4, 3, 13, 13, 2), (1, 1, 1, 4, 3, 1), (2, 2, 1, 5, 17, 0),
-                                           (1, 3, 8, 6, 31, 1)])
+                                           (1, 3, 8, 6, 31, 1), (1, 1, 1, 3, 3, 0), (2, 2, 2, 20, 2, 1), (3, 1, 2, 1, 9, 1)])
 def test_conv_forward_fused_shapes(N, p, q, H, W, pad):
     _conv_case(N, p, q, 64, H, W, 3, pad)
 
@@ -229,7 +229,7 @@ def test_conv_backward_shapes(N, p, q, k, H, W, r, pad):
                                            (2, 4, 16, 8, 8, 1), (4, 2, 3, 28, 28, 1), (1, 4, 2, 3, 6, 0), (2, 4, 4, 33, 4, 2),
                                            (3, 2, 2, 10, 20, 1), (2, 3, 4, 16, 16, 1), (1, 1, 1, 5, 5, 1), (2, 5, 2, 13, 6, 0),
                                            (3, 6, 6, 13, 13, 1), (2, 8, 2, 7, 7, 1), (1, 6, 8, 14, 14, 1), (2, 3, 4, 13, 13, 0),
-                                           (1, 1, 1, 4, 3, 1), (2, 8, 3, 6, 31, 2)])
+                                           (1, 1, 1, 4, 3, 1), (2, 8, 3, 6, 31, 2), (1, 1, 1, 3, 3, 0), (2, 2, 2, 20, 2, 1), (3, 2, 1, 1, 9, 1)])
 def test_conv_backward_fused_shapes(N, p, q, H, W, pad):
     k, r = 64, 3
     w = (RNG.standard_normal((r, r, p, q, k)) * np.sqrt(2.0 / (r * r * q * k))).astype(np.float32)
