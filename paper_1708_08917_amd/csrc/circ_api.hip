@@ -1125,10 +1125,12 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
     const unsigned mul_w = (unsigned)(((1ll << 32) + W - 1) / W);
     if (dpl.lds) {
       const unsigned mul_wo_b = (unsigned)(((1ll << 32) + Wo - 1) / Wo);   // pixel index inside a band / Wo
-      // tiles of 2 x 2 channel blocks (one matrix instruction per pixel) when that takes fewer
-      // instructions than tiles of 4 x 4 (four per pixel): layers with at most 2 blocks on a side
+      // tiles of 2 x 2 channel blocks (one matrix instruction per pixel) or of 4 x 4 (four per
+      // pixel): a 2 x 2 tile measures about 0.65 of the time of a 4 x 4 tile (staging and LDS
+      // reads, not the matrix instructions, set the pace), so the small tiles win only where they
+      // are fewer than 1.5 times as many: layers with at most 2 blocks on either side
       const long long t2 = cdiv(p, 2) * cdiv(q, 2), t4 = cdiv(p, 4) * cdiv(q, 4);
-      if (t2 < 4 * t4 && cdiv(r * r, 16) * t2 <= 65535) {
+      if (2 * t2 < 3 * t4 && cdiv(r * r, 16) * t2 <= 65535) {
         dim3 grid((unsigned)dpl.nparts, (unsigned)NF, (unsigned)(cdiv(r * r, 16) * t2));
         hipLaunchKernelGGL((conv_dw_lds_kernel<true>), grid, dim3(256), dpl.lds_bytes, s, yh, xh, wpart, p, q, NF, N, H, W, Ho,
                            Wo, r, pad, dpl.BR, dpl.nbands, dpl.cpb, wstride, mul_wo_b, mul_w, stride);
