@@ -113,6 +113,30 @@ def test_k1_is_dense_layer():
     np.testing.assert_allclose(O.fc_backward_dw(x, dy, 1)[:, :, 0], dy.T @ x, atol=1e-13)
 
 
+# ---- bias and ReLU at k > 1 (Eq. 1 on the matrix of Eq. 3): W written entry by entry -------
+@pytest.mark.parametrize("p,q,k,B", [(2, 3, 3, 4), (3, 2, 8, 5), (4, 2, 3, 2)])
+def test_bias_relu_epilogue_vs_entrywise_dense_matrix(p, q, k, B):
+    w = RNG.standard_normal((p, q, k))
+    x = RNG.standard_normal((B, q * k))
+    # distinct, large entries: a bias slice taken at the wrong offset changes every output
+    bias = 3.0 * RNG.standard_normal(p * k) + np.arange(p * k)
+    W = torch.zeros(p * k, q * k, dtype=torch.float64)
+    for i in range(p):
+        for j in range(q):
+            for a in range(k):
+                for b in range(k):
+                    W[i * k + a, j * k + b] = w[i, j, (a - b) % k]
+    xt, bt = torch.from_numpy(x), torch.from_numpy(bias)
+    lin = xt @ W.T + bt
+    assert (lin < 0).any() and (lin > 0).any()          # the ReLU really clips some outputs
+    np.testing.assert_allclose(O.fc_forward(w, x, bias=bias, relu=True), torch.relu(lin).numpy(), atol=1e-12)
+    np.testing.assert_allclose(O.fc_forward(w, x, bias=bias, relu=False), lin.numpy(), atol=1e-12)
+    np.testing.assert_allclose(O.fc_forward(w, x, relu=True), torch.relu(xt @ W.T).numpy(), atol=1e-12)
+    # a listed subset of block rows takes the bias of those rows
+    np.testing.assert_allclose(O.fc_forward(w, x, bias=bias, relu=True, block_rows=[p - 1, 0]),
+                               torch.relu(torch.cat([lin[:, (p - 1) * k:], lin[:, :k]], dim=1)).numpy(), atol=1e-12)
+
+
 # ---- p = q = 1: one circulant matrix = library circular convolution ------------------------
 @pytest.mark.parametrize("k", [3, 8, 16, 64])
 def test_single_circulant_vs_library_fft(k):
