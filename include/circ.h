@@ -18,7 +18,10 @@
  *    is the reading under which the FFT formula of Sec. 3.1 holds as printed.
  *  - All tensors are fp32, dense, row-major, in DEVICE memory of the current HIP
  *    device.  Every pointer must be 16-byte aligned.  The caller owns every
- *    buffer; the library allocates no device memory and keeps no global state.
+ *    buffer; the library allocates no device memory.  The only state it keeps is,
+ *    per kernel and device, the note that it has opted that kernel in to more than
+ *    64 KB of LDS (an atomic flag, set under a lock: entry points may be called
+ *    from several host threads and on several devices).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue work on it and return; nothing synchronises.
  *  - Block size k: 1 <= k <= 512, and k must divide the layer widths exactly

@@ -83,8 +83,20 @@ def status_string(status: int) -> str:
     return lib().circ_status_string(status).decode()
 
 
-def _ptr(t):
-    return None if t is None else ctypes.c_void_p(t.data_ptr())
+def _ptr(t, dtype=None):
+    """Device pointer of a dense device tensor (None passes through as NULL).  The library reads raw
+    memory, so a host tensor, a strided view or a tensor of another element type is refused here."""
+    if t is None:
+        return None
+    if not (t.is_cuda and t.is_contiguous()):
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected a {dtype} tensor, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _f32(t):
+    return _ptr(t, torch.float32)
 
 
 def _stream():
@@ -118,7 +130,7 @@ def circ_precompute_spectra(w: torch.Tensor, w_hat: torch.Tensor | None = None) 
         raise CircError(CIRC_EINVAL, "circ_spectra_bytes")
     if w_hat is None:
         w_hat = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
-    _check(lib().circ_precompute_spectra(_ptr(w), n_grids, p, q, k, _ptr(w_hat), _stream()), "circ_precompute_spectra")
+    _check(lib().circ_precompute_spectra(_f32(w), n_grids, p, q, k, _ptr(w_hat), _stream()), "circ_precompute_spectra")
     return w_hat
 
 
@@ -129,7 +141,7 @@ def circ_fc_forward(w_hat, x, bias, y, p, q, k, epilogue=EPI_NONE, workspace=Non
         y = torch.empty(batch, p * k, dtype=torch.float32, device=x.device)
     if workspace is None:
         workspace = torch.empty(max(1, circ_fc_workspace_bytes(p, q, k, batch)), dtype=torch.uint8, device=x.device)
-    _check(lib().circ_fc_forward(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), p, q, k, batch, epilogue,
+    _check(lib().circ_fc_forward(_ptr(w_hat), _f32(x), _f32(bias), _f32(y), p, q, k, batch, epilogue,
                                  _ptr(workspace), workspace.numel(), _stream()), "circ_fc_forward")
     return y
 
@@ -144,8 +156,8 @@ def circ_fc_backward(w_hat, x, dy, p, q, k, need_dx=True, need_dw=True, dx=None,
     if workspace is None:
         workspace = torch.empty(max(1, circ_fc_workspace_bytes(p, q, k, batch, True)), dtype=torch.uint8,
                                 device=dy.device)
-    _check(lib().circ_fc_backward(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx if need_dx else None),
-                                  _ptr(dw if need_dw else None), p, q, k, batch, _ptr(workspace),
+    _check(lib().circ_fc_backward(_ptr(w_hat), _f32(x), _f32(dy), _f32(dx if need_dx else None),
+                                  _f32(dw if need_dw else None), p, q, k, batch, _ptr(workspace),
                                   workspace.numel(), _stream()), "circ_fc_backward")
     return (dx if need_dx else None), (dw if need_dw else None)
 
@@ -159,7 +171,7 @@ def circ_conv_forward(w_hat, x, bias, y, C_out, r, stride, pad, k, epilogue=EPI_
     if workspace is None:
         nb = circ_conv_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
         workspace = torch.empty(max(1, nb), dtype=torch.uint8, device=x.device)
-    _check(lib().circ_conv_forward(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), N, C_in, C_out, H, W, r, stride, pad,
+    _check(lib().circ_conv_forward(_ptr(w_hat), _f32(x), _f32(bias), _f32(y), N, C_in, C_out, H, W, r, stride, pad,
                                    k, epilogue, _ptr(workspace), workspace.numel(), _stream()), "circ_conv_forward")
     return y
 
@@ -180,8 +192,8 @@ def circ_conv_backward(w_hat, x, dy, C_in, H, W, r, stride, pad, k, need_dx=True
     if workspace is None:
         nb = circ_conv_backward_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
         workspace = torch.empty(max(1, nb), dtype=torch.uint8, device=dy.device)
-    _check(lib().circ_conv_backward(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx if need_dx else None),
-                                    _ptr(dw if need_dw else None), N, C_in, C_out, H, W, r, stride, pad, k,
+    _check(lib().circ_conv_backward(_ptr(w_hat), _f32(x), _f32(dy), _f32(dx if need_dx else None),
+                                    _f32(dw if need_dw else None), N, C_in, C_out, H, W, r, stride, pad, k,
                                     _ptr(workspace), workspace.numel(), _stream()), "circ_conv_backward")
     return (dx if need_dx else None), (dw if need_dw else None)
 
@@ -194,7 +206,7 @@ def circ_fc_sgd_step(w_hat, x, dy, lr, p, q, k, need_dx=False, dx=None, workspac
     if workspace is None:
         workspace = torch.empty(max(1, circ_fc_workspace_bytes(p, q, k, batch, True)), dtype=torch.uint8,
                                 device=dy.device)
-    _check(lib().circ_fc_sgd_step(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx if need_dx else None), float(lr), p, q, k,
+    _check(lib().circ_fc_sgd_step(_ptr(w_hat), _f32(x), _f32(dy), _f32(dx if need_dx else None), float(lr), p, q, k,
                                   batch, _ptr(workspace), workspace.numel(), _stream()), "circ_fc_sgd_step")
     return dx if need_dx else None
 
@@ -207,7 +219,7 @@ def circ_conv_sgd_step(w_hat, x, dy, lr, C_in, H, W, r, stride, pad, k, need_dx=
     if workspace is None:
         nb = circ_conv_backward_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
         workspace = torch.empty(max(1, nb), dtype=torch.uint8, device=dy.device)
-    _check(lib().circ_conv_sgd_step(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx if need_dx else None), float(lr), N, C_in,
+    _check(lib().circ_conv_sgd_step(_ptr(w_hat), _f32(x), _f32(dy), _f32(dx if need_dx else None), float(lr), N, C_in,
                                     C_out, H, W, r, stride, pad, k, _ptr(workspace), workspace.numel(), _stream()),
            "circ_conv_sgd_step")
     return dx if need_dx else None
@@ -217,7 +229,7 @@ def circ_export_weights(w_hat, n_grids, p, q, k, w=None):
     """Block vectors [n_grids][p][q][k] recovered from a spectra blob."""
     if w is None:
         w = torch.empty(n_grids, p, q, k, dtype=torch.float32, device=w_hat.device)
-    _check(lib().circ_export_weights(_ptr(w_hat), n_grids, p, q, k, _ptr(w), _stream()), "circ_export_weights")
+    _check(lib().circ_export_weights(_ptr(w_hat), n_grids, p, q, k, _f32(w), _stream()), "circ_export_weights")
     return w
 
 
@@ -236,7 +248,7 @@ def circ_precompute_spectra_f16(w: torch.Tensor, w_hat: torch.Tensor | None = No
         raise CircError(CIRC_EINVAL, f"circ_spectra_bytes_{sfx}")
     if w_hat is None:
         w_hat = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
-    _check(getattr(lib(), f"circ_precompute_spectra_{sfx}")(_ptr(w), p, q, k, _ptr(w_hat), _stream()),
+    _check(getattr(lib(), f"circ_precompute_spectra_{sfx}")(_f32(w), p, q, k, _ptr(w_hat), _stream()),
            f"circ_precompute_spectra_{sfx}")
     return w_hat
 
@@ -255,7 +267,7 @@ def circ_fc_forward_f16(w_hat, x, bias, y, p, q, k, epilogue=EPI_NONE, workspace
         y = torch.empty(batch, p * k, dtype=x.dtype, device=x.device)
     if workspace is None:
         workspace = torch.empty(max(1, circ_fc_workspace_bytes_f16(p, q, k, batch)), dtype=torch.uint8, device=x.device)
-    _check(getattr(lib(), f"circ_fc_forward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), p, q, k, batch, epilogue,
+    _check(getattr(lib(), f"circ_fc_forward_{sfx}")(_ptr(w_hat), _ptr(x), _f32(bias), _ptr(y, x.dtype), p, q, k, batch, epilogue,
                                                     _ptr(workspace), workspace.numel(), _stream()), f"circ_fc_forward_{sfx}")
     return y
 
@@ -275,8 +287,8 @@ def circ_fc_backward_f16(w_hat, x, dy, p, q, k, need_dx=True, need_dw=True, dx=N
         dw = torch.empty(p, q, k, dtype=torch.float32, device=dy.device)
     if workspace is None:
         workspace = torch.empty(max(1, circ_fc_backward_workspace_bytes_f16(p, q, k, batch)), dtype=torch.uint8, device=dy.device)
-    _check(getattr(lib(), f"circ_fc_backward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx) if need_dx else None,
-                                                     _ptr(dw) if need_dw else None, p, q, k, batch, _ptr(workspace),
+    _check(getattr(lib(), f"circ_fc_backward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx, dy.dtype) if need_dx else None,
+                                                     _f32(dw) if need_dw else None, p, q, k, batch, _ptr(workspace),
                                                      workspace.numel(), _stream()), f"circ_fc_backward_{sfx}")
     return (dx if need_dx else None), (dw if need_dw else None)
 
@@ -292,7 +304,7 @@ def circ_conv_forward_f16(w_hat, x, bias, y, C_out, r, stride, pad, k, epilogue=
     if workspace is None:
         nb = circ_conv_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
         workspace = torch.empty(max(1, nb), dtype=torch.uint8, device=x.device)
-    _check(getattr(lib(), f"circ_conv_forward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(bias), _ptr(y), N, C_in, C_out, H, W, r, stride,
+    _check(getattr(lib(), f"circ_conv_forward_{sfx}")(_ptr(w_hat), _ptr(x), _f32(bias), _ptr(y, x.dtype), N, C_in, C_out, H, W, r, stride,
                                                       pad, k, epilogue, _ptr(workspace), workspace.numel(), _stream()),
            f"circ_conv_forward_{sfx}")
     return y
@@ -311,8 +323,8 @@ def circ_conv_backward_f16(w_hat, x, dy, C_in, H, W, r, stride, pad, k, need_dx=
     if workspace is None:
         nb = circ_conv_backward_workspace_bytes(N, C_in, C_out, H, W, r, stride, pad, k)
         workspace = torch.empty(max(1, nb), dtype=torch.uint8, device=dy.device)
-    _check(getattr(lib(), f"circ_conv_backward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx) if need_dx else None,
-                                                       _ptr(dw) if need_dw else None, N, C_in, C_out, H, W, r, stride, pad, k,
+    _check(getattr(lib(), f"circ_conv_backward_{sfx}")(_ptr(w_hat), _ptr(x), _ptr(dy), _ptr(dx, dy.dtype) if need_dx else None,
+                                                       _f32(dw) if need_dw else None, N, C_in, C_out, H, W, r, stride, pad, k,
                                                        _ptr(workspace), workspace.numel(), _stream()), f"circ_conv_backward_{sfx}")
     return (dx if need_dx else None), (dw if need_dw else None)
 
@@ -324,6 +336,6 @@ def circ_bias_grad(dy, db=None):
     inner = int(dy.numel() // (outer * channels))
     if db is None:
         db = torch.empty(channels, dtype=torch.float32, device=dy.device)
-    _check(lib().circ_bias_grad(_ptr(dy), _ptr(db), outer, channels, inner, _stream()), "circ_bias_grad")
+    _check(lib().circ_bias_grad(_f32(dy), _f32(db), outer, channels, inner, _stream()), "circ_bias_grad")
     return db
 

@@ -2,7 +2,9 @@
 // launch planning.  Every operation of the layers runs in the kernels of circ_kernels.h.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
+#include <mutex>
 
 #include "../../include/circ.h"
 #include "circ_kernels.h"
@@ -109,13 +111,11 @@ struct FftPlan { int P, NT; size_t lds; };
 
 // P column pairs per block, NT threads.  Small problems get small tiles so that the
 // launch still covers the chip; the tile must fit comfortably in LDS.
-#ifndef CIRC_FFT_MAXLDS_KB
-#define CIRC_FFT_MAXLDS_KB 40
-#endif
+constexpr size_t kFftMaxLdsBytes = 40 * 1024;   // LDS tile limit of the unfused transform kernels
 FftPlan plan_fft(int K, long long nrows) {
   int R2 = radix2_of(K);
   int P = 64;
-  while (P > 8 && fft_tile_lds_bytes(K, P) > CIRC_FFT_MAXLDS_KB * 1024) P >>= 1;
+  while (P > 8 && fft_tile_lds_bytes(K, P) > kFftMaxLdsBytes) P >>= 1;
   long long pairs = cdiv(nrows, 2);
   while (P > 8 && cdiv(pairs, P) < 512) P >>= 1;
   int TT = R2;
@@ -227,9 +227,7 @@ inline int cgemm_ksplit(int k, int M, int N, int Kd) {
 }
 
 // Workgroups of the persistent tiled GEMM: two per CU.
-#ifndef CIRC_GEMM_WGS
-#define CIRC_GEMM_WGS 512
-#endif
+constexpr int kGemmWorkgroups = 512;
 template <int FM, int WM, int WN>
 hipError_t launch_cgemm_tiled(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, long long sA,
                               long long sB, long long sC, bool conj_b, bool a_t, hipStream_t s, int ksplit, int kchunk,
@@ -238,7 +236,7 @@ hipError_t launch_cgemm_tiled(const float2* A, const float2* B, float2* C, int N
   const int ntm = (int)cdiv(M, Sh::TM), ntn = (int)cdiv(N, Sh::TN);
   const long long ntiles = (long long)(NF - 1) * ksplit * ntm * ntn;   // bins 0 and NF-1 share a tile
   if (ntiles > (1ll << 31) - 8) return hipErrorInvalidValue;
-  const long long chunk = cdiv(ntiles, CIRC_GEMM_WGS);
+  const long long chunk = cdiv(ntiles, kGemmWorkgroups);
   dim3 grid((unsigned)(cdiv(cdiv(ntiles, chunk), 8) * 8));
 #define CIRC_TILED(CJ, AT)                                                                                              \
   hipLaunchKernelGGL((cgemm_tiled_kernel<FM, WM, WN, CJ, AT>), grid, dim3(256), 0, s, A, B, C, M, N, Kd, NF, sA, sB, sC, ntm, \
@@ -260,9 +258,7 @@ hipError_t launch_cgemm_tiled(const float2* A, const float2* B, float2* C, int N
 // straight from global memory, which was measured faster there (56 us against 62 us for
 // 64x128 tiles): its many independent waves drift apart, whereas the workgroups of the tiled
 // kernel stay in step and load, multiply and store at the same moments.
-#ifndef CIRC_GEMM_TILED_MIN
-#define CIRC_GEMM_TILED_MIN 256
-#endif
+constexpr long long kGemmTiledMinTiles = 256;
 inline bool cgemm_takes_tiled(int k, int M, int N, int Kd, int ksplit) {
   if (k & 1) return false;   // the tiled kernel pairs bin 0 with a real Nyquist bin, which odd sizes lack
   const int NF = k / 2 + 1;
@@ -270,7 +266,7 @@ inline bool cgemm_takes_tiled(int k, int M, int N, int Kd, int ksplit) {
   // the tiled kernel keeps offsets inside one frequency of an operand in 32 bits
   const long long lim = (1ll << 31) - 1;
   const bool fits32 = (long long)Kd * M <= lim && (long long)Kd * N <= lim && (long long)M * N <= lim;
-  return fits32 && M > 32 && N <= 64 && tiles_s >= CIRC_GEMM_TILED_MIN;
+  return fits32 && M > 32 && N <= 64 && tiles_s >= kGemmTiledMinTiles;
 }
 // a_t: A is stored [f][m][kd] instead of [f][kd][m]; only the tiled kernel reads that layout, so
 // callers pass it only when cgemm_takes_tiled() holds.
@@ -296,14 +292,30 @@ hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int k, int 
   return hipGetLastError();
 }
 
-// Kernels whose LDS tile exceeds the 64 KB default opt in once (gfx950: 160 KB per workgroup).
+// Kernels whose LDS tile exceeds the 64 KB default opt in (gfx950: 160 KB per workgroup).  The
+// attribute belongs to the kernel on one device, so what has been granted is remembered per kernel
+// instantiation and device: an atomic read on the fast path, a lock around the runtime call, so
+// that first calls from several host threads, or on several devices, neither race nor miss it.
+constexpr int kMaxDevices = 64;
+struct LdsOptIn {
+  std::atomic<size_t> granted[kMaxDevices];   // static storage: starts at zero
+};
+inline std::mutex& lds_opt_in_mutex() {
+  static std::mutex m;
+  return m;
+}
 template <class Kern>
-hipError_t ensure_lds(Kern kern, size_t bytes, bool& done) {
-  if (bytes > 64 * 1024 && !done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e != hipSuccess) return e;
-    done = true;
-  }
+hipError_t ensure_lds(Kern kern, size_t bytes, LdsOptIn& st) {
+  if (bytes <= 64 * 1024) return hipSuccess;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+  const bool tracked = dev >= 0 && dev < kMaxDevices;
+  if (tracked && st.granted[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+  std::lock_guard<std::mutex> lock(lds_opt_in_mutex());
+  if (tracked && st.granted[dev].load(std::memory_order_relaxed) >= bytes) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return e;
+  if (tracked) st.granted[dev].store(bytes, std::memory_order_release);
   return hipSuccess;
 }
 
@@ -314,7 +326,7 @@ hipError_t launch_fused_v(const float4* wf, const float* x, const float* bias, f
                           int relu, hipStream_t s) {
   using Sh = FusedShape<K, IT, NP, NT>;
   static_assert((4096 / K) % Sh::JC == 0, "packed weights are padded to chunks of 4096/K input blocks");
-  static bool opted_in = false;
+  static LdsOptIn opted_in;
   if (ensure_lds(&fc_fused_kernel<K, IT, NP, NT, ONE, HM>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
   const int n_it = (int)cdiv(p, IT), n_bt = (int)cdiv(batch, 2 * NP);
   // Split the tile grid over the 8 XCDs as xa x (8/xa) rectangles; pick the split that
@@ -346,10 +358,6 @@ inline int fused_np(int p, int k, int batch) {
   return (k >= 64 && tiles2 >= 256) ? 2 : 1;
 }
 
-#ifndef CIRC_NT128
-#define CIRC_NT128 512
-#endif
-
 template <int HM>
 hipError_t launch_fused_h(int k, const float4* wf, const float* x, const float* bias, float* y, int p, int q, int batch,
                           int relu, hipStream_t s) {
@@ -358,8 +366,8 @@ hipError_t launch_fused_h(int k, const float4* wf, const float* x, const float* 
     case 32: return launch_fused_t<32, 16, 1, 256, HM>(wf, x, bias, y, p, q, batch, relu, s);
     case 64: return np == 2 ? launch_fused_t<64, 8, 2, 512, HM>(wf, x, bias, y, p, q, batch, relu, s)
                             : launch_fused_t<64, 8, 1, 512, HM>(wf, x, bias, y, p, q, batch, relu, s);
-    case 128: return np == 2 ? launch_fused_t<128, 8, 2, CIRC_NT128, HM>(wf, x, bias, y, p, q, batch, relu, s)
-                             : launch_fused_t<128, 8, 1, CIRC_NT128, HM>(wf, x, bias, y, p, q, batch, relu, s);
+    case 128: return np == 2 ? launch_fused_t<128, 8, 2, 512, HM>(wf, x, bias, y, p, q, batch, relu, s)
+                             : launch_fused_t<128, 8, 1, 512, HM>(wf, x, bias, y, p, q, batch, relu, s);
     case 256: return np == 2 ? launch_fused_t<256, 8, 2, 256, HM>(wf, x, bias, y, p, q, batch, relu, s)
                              : launch_fused_t<256, 8, 1, 256, HM>(wf, x, bias, y, p, q, batch, relu, s);
     default: return hipErrorInvalidValue;
@@ -380,9 +388,7 @@ hipError_t launch_fused_half(bool bf, int k, const void* wf, const void* x, cons
 
 // Upper bound, in MiB, of the operand bytes all workgroups of the fused kernel pull through
 // L2 (see use_fused_forward).
-#ifndef CIRC_FUSED_MAX_L2_MIB
-#define CIRC_FUSED_MAX_L2_MIB 256
-#endif
+constexpr double kFusedMaxL2MiB = 256.0;
 
 // Fused or unfused forward?  The fused kernel re-reads the weight tile once per tile of batch
 // rows and the x tile once per tile of output block rows, all through L2 (about 45 GB/s per
@@ -396,7 +402,7 @@ inline bool use_fused_forward(int p, int q, int k, int batch) {
   const double n_it = double(cdiv(p, it)), n_bt = double(cdiv(batch, 2 * fused_np(p, k, batch)));
   const double w_bytes = double(p) * q * k * 4.0, x_bytes = double(batch) * q * k * 4.0;
   const double l2_bytes = n_bt * w_bytes + n_it * x_bytes;
-  return n_it <= 8 && l2_bytes <= double(CIRC_FUSED_MAX_L2_MIB) * 1048576.0;
+  return n_it <= 8 && l2_bytes <= kFusedMaxL2MiB * 1048576.0;
 }
 
 // Batch <= 2 on few block rows with long rows: split the input blocks over several workgroups per
@@ -404,15 +410,11 @@ inline bool use_fused_forward(int p, int q, int k, int batch) {
 // (1 = single launch).  Each split keeps at least 8 input blocks; the split pays for its second
 // launch only when a workgroup would otherwise transform >= 8192 input values.
 inline int gemv_splits(int p, int q, int k) {
-#ifndef CIRC_GEMV_MAXWG
-#define CIRC_GEMV_MAXWG 256
-#endif
-#ifndef CIRC_GEMV_SPLIT_MIN
-#define CIRC_GEMV_SPLIT_MIN 8192
-#endif
-  if ((long long)q * k < CIRC_GEMV_SPLIT_MIN || p * 2 > CIRC_GEMV_MAXWG) return 1;
+  constexpr int kMaxWg = 256;              // workgroups of the split launch: one per CU
+  constexpr long long kSplitMin = 8192;    // input values per workgroup from which the split pays
+  if ((long long)q * k < kSplitMin || p * 2 > kMaxWg) return 1;
   int ns = 1;
-  while (ns < 16 && p * ns * 2 <= CIRC_GEMV_MAXWG && q / (ns * 2) >= 8) ns *= 2;
+  while (ns < 16 && p * ns * 2 <= kMaxWg && q / (ns * 2) >= 8) ns *= 2;
   return ns;
 }
 inline size_t gemv_partial_bytes(int p, int q, int k) {
@@ -425,10 +427,10 @@ template <int K, int HM>
 hipError_t launch_gemv_k(const float2* wg, const float* x, const float* bias, float* y, int p, int q, int batch, int relu,
                          void* workspace, hipStream_t s) {
   using Sh = GemvShape<K>;
-  static bool opted_in = false;
+  static LdsOptIn opted_in;
   const int ns = gemv_splits(p, q, K);
   if (ns > 1) {
-    static bool opted1 = false, opted2 = false;
+    static LdsOptIn opted1, opted2;
     if (ensure_lds(&fc_gemv_kernel<K, 1, HM>, Sh::LDS_BYTES, opted1) != hipSuccess) return hipErrorInvalidValue;
     if (ensure_lds(&fc_gemv_kernel<K, 2, HM>, Sh::LDS_BYTES, opted2) != hipSuccess) return hipErrorInvalidValue;
     float2* part = static_cast<float2*>(workspace);
@@ -811,15 +813,8 @@ hipError_t launch_conv_fused_r(const float2* wc, const float* x, const float* bi
   constexpr int K = 64, R = 3;
   ConvTilePlan pl;
   if (!plan_conv_tile<K, NT>(C_out / K, QH, R, Ho, Wo, ncombo, pl)) return hipErrorInvalidValue;
-  if (pl.lds > 64 * 1024) {   // opt in to more than the default LDS limit, once per size increase
-    static size_t opted = 0;
-    if (pl.lds > opted) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_fused_kernel<K, NT, R, Q, QH, HM, RAGGED>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds) != hipSuccess)
-        return hipErrorInvalidValue;
-      opted = pl.lds;
-    }
-  }
+  static LdsOptIn opted;   // the tile, and with it the LDS size, depends on the image: granted sizes only grow
+  if (ensure_lds(&conv_fused_kernel<K, NT, R, Q, QH, HM, RAGGED>, pl.lds, opted) != hipSuccess) return hipErrorInvalidValue;
   const long long grid = (long long)cdiv(N, 2) * pl.tiles_h * pl.tiles_w;
   hipLaunchKernelGGL((conv_fused_kernel<K, NT, R, Q, QH, HM, RAGGED>), dim3((unsigned)grid), dim3(NT), pl.lds, s, wc, x, bias, y,
                      N, C_out, H, W, Ho, Wo, pad, pl.TH, pl.TW, pl.tiles_h, pl.tiles_w, ncombo, relu);
@@ -837,16 +832,13 @@ hipError_t launch_conv_fused_t(const float2* wc, const float* x, const float* bi
 // channel block of spectra in LDS at a time: two such workgroups share a CU, so the loads and
 // stores of one overlap the transforms and the contraction of the other.  More combinations need
 // the 8 waves of a 512-thread workgroup.
-#ifndef CIRC_CONV_SMALL_WG
-#define CIRC_CONV_SMALL_WG 1
-#endif
 template <int Q, int HM>
 hipError_t launch_conv_fused_q(const float2* wc, const float* x, const float* bias, float* y, int N, int C_out, int H,
                                int W, int Ho, int Wo, int pad, int ncombo, int relu, hipStream_t s) {
   // ... provided there are enough of them for two per CU; a grid that leaves most CUs with one
   // workgroup is served faster by the larger workgroups (twice the waves on every serial phase)
   ConvTilePlan pl;
-  const bool small_wg = CIRC_CONV_SMALL_WG && ncombo <= 4 && plan_conv_tile<64, 256>(C_out / 64, 1, 3, Ho, Wo, ncombo, pl) &&
+  const bool small_wg = ncombo <= 4 && plan_conv_tile<64, 256>(C_out / 64, 1, 3, Ho, Wo, ncombo, pl) &&
                         (long long)cdiv(N, 2) * pl.tiles_h * pl.tiles_w >= 384;
   if (small_wg)
     return launch_conv_fused_t<Q, 256, 1, HM>(wc, x, bias, y, N, C_out, H, W, Ho, Wo, pad, ncombo, relu, s);
@@ -1126,9 +1118,7 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
     const int nchunks = dpl.nparts;
     const long long wrows = (long long)r * r * p * q;
     const long long wstride = (long long)(align_up(spectrum_elems(k, wrows) * sizeof(float2), 256) / sizeof(float2));
-#ifndef CIRC_DW_NG
-#define CIRC_DW_NG 3
-#endif
+    constexpr int kDwOffsets = 3;   // consecutive filter offsets per block of conv_dw_mfma_kernel
     // exact division of the pixel index by a multiply-high: q = (pix * ceil(2^32/d)) >> 32 equals
     // pix / d whenever pix * d < 2^32 (the rounding excess of the multiplier, below d, times pix
     // stays below 2^32)
@@ -1155,9 +1145,9 @@ circ_status conv_backward_impl(const void* w_hat, const float* x, const float* d
         hipLaunchKernelGGL((conv_dw_lds_kernel<false>), grid, dim3(256), dpl.lds_bytes, s, yh, xh, wpart, p, q, NF, N, H, W, Ho,
                            Wo, r, pad, dpl.BR, dpl.nbands, dpl.cpb, wstride, mul_wo_b, mul_w, stride);
       }
-    } else if (r % CIRC_DW_NG == 0) {   // CIRC_DW_NG consecutive offsets per block (for r = 3: one filter row)
-      dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r / CIRC_DW_NG * cdiv(p, 4) * cdiv(q, 4)));
-      hipLaunchKernelGGL((conv_dw_mfma_kernel<CIRC_DW_NG>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo,
+    } else if (r % kDwOffsets == 0) {   // kDwOffsets consecutive offsets per block (for r = 3: one filter row)
+      dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r / kDwOffsets * cdiv(p, 4) * cdiv(q, 4)));
+      hipLaunchKernelGGL((conv_dw_mfma_kernel<kDwOffsets>), grid, dim3(256), 0, s, yh, xh, wpart, p, q, NF, N, H, W, Ho, Wo,
                          r, pad, ppb, wstride, mul_hwo, mul_wo, stride);
     } else {            // one offset per block
       dim3 grid((unsigned)nchunks, (unsigned)NF, (unsigned)(r * r * cdiv(p, 4) * cdiv(q, 4)));

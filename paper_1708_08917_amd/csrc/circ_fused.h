@@ -28,11 +28,8 @@
 
 #include "circ_fft.h"
 #include "circ_kernels.h"
+#include "circ_probe.h"
 
-// Optional phase-timing hook for profiling builds; expands to nothing in the library.
-#ifndef CIRC_PROBE
-#define CIRC_PROBE(id)
-#endif
 
 namespace circ {
 

@@ -728,7 +728,7 @@ def test_cfg2_graph_over_streams_matches_eager():
     w, x0, b = synth.fc_inputs(c)
     wh = B.circ_precompute_spectra(G.dev(w))
     bd = G.dev(b)
-    nsteps, nstreams = 24, 4
+    nsteps, nstreams = 40, 16                    # the stream count the benchmark uses
     gen = torch.Generator(device=G.DEV); gen.manual_seed(7)
     xs = torch.empty(nsteps, c.batch, c.n_in, device=G.DEV).uniform_(-1, 1, generator=gen)
     xs[0].copy_(torch.from_numpy(x0))
@@ -783,9 +783,8 @@ def test_cfg4_conv(seed):
     c = synth.CFG4
     w, x = synth.conv_inputs(c, seed)
     y = G.gpu_conv_forward(w, x, None, False, c.pad)
-    # oracle on a subset of images (each image is independent): first, last and one in the middle
-    for n in (0, c.N // 2, c.N - 1):
-        check(y[n:n + 1], O.conv_forward(w, x[n:n + 1], pad=c.pad), f"cfg4 seed {seed} image {n}")
+    # every image of the batch (the kernel packs images in pairs; each image is independent)
+    check(y, O.conv_forward(w, x, pad=c.pad), f"cfg4 seed {seed}, all {c.N} images")
 
 
 @pytest.mark.parametrize("seed", [0, 1, 2])
