@@ -20,8 +20,9 @@
  *    device.  Every pointer must be 16-byte aligned.  The caller owns every
  *    buffer; the library allocates no device memory.  The only state it keeps is,
  *    per kernel and device, the note that it has opted that kernel in to more than
- *    64 KB of LDS (an atomic flag, set under a lock: entry points may be called
- *    from several host threads and on several devices).
+ *    64 KB of LDS, and per device the address of the fixed scratch array of
+ *    circ_fc_forward_static (atomic values, set under a lock: entry points may be
+ *    called from several host threads and on several devices).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue work on it and return; nothing synchronises.
  *  - Block size k: 1 <= k <= 512, and k must divide the layer widths exactly
@@ -90,6 +91,26 @@ size_t circ_fc_workspace_bytes(int p, int q, int k, int batch, int backward);
 circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias, float* y,
                             int p, int q, int k, int batch, int epilogue,
                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * circ_fc_forward for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same
+ * arguments, result and errors as circ_fc_forward, without the workspace: the scratch the kernels
+ * need (activation spectra of the three-kernel route, partial spectra of the split batch <= 2
+ * kernel) is a fixed array of CIRC_STATIC_SCRATCH_BYTES inside the library's code object, which
+ * every device the library runs on holds until the process ends.  The call allocates and frees
+ * nothing.  Shapes whose circ_fc_workspace_bytes(p,q,k,batch,0) exceeds CIRC_STATIC_SCRATCH_BYTES
+ * return CIRC_EWORKSPACE (nothing is enqueued); use circ_fc_forward with a workspace for those.
+ * All calls on one device share that device's array: calls that overlap in time on one device
+ * (different streams, or different host threads without ordering) race on it and must be
+ * ordered by the caller; consecutive calls on one stream are safe, and nothing has to be
+ * cleared in between (each call overwrites what it reads).  The first call on a device looks
+ * the array's address up (a host-side runtime query, no device work); make it outside a
+ * graph capture.
+ */
+#define CIRC_STATIC_SCRATCH_BYTES (32u << 20)
+circ_status circ_fc_forward_static(const void* w_hat, const float* x, const float* bias, float* y,
+                                   int p, int q, int k, int batch, int epilogue, void* stream);
 
 /*
  * FC backward (Algorithm 2; Eq. 4 and Eq. 5).  `dy` is the gradient with respect

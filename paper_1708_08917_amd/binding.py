@@ -28,6 +28,7 @@ SIGNATURES = {
     "circ_fc_workspace_bytes": (_c_size, [_c_int] * 5),
     "circ_fc_forward": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_int, _c_int, _c_int, _c_int, _c_int,
                                  _c_ptr, _c_size, _c_ptr]),
+    "circ_fc_forward_static": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_int, _c_int, _c_int, _c_int, _c_int, _c_ptr]),
     "circ_fc_backward": (_c_int, [_c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_ptr, _c_int, _c_int, _c_int, _c_int,
                                   _c_ptr, _c_size, _c_ptr]),
     "circ_conv_workspace_bytes": (_c_size, [_c_int] * 9),
@@ -143,6 +144,16 @@ def circ_fc_forward(w_hat, x, bias, y, p, q, k, epilogue=EPI_NONE, workspace=Non
         workspace = torch.empty(max(1, circ_fc_workspace_bytes(p, q, k, batch)), dtype=torch.uint8, device=x.device)
     _check(lib().circ_fc_forward(_ptr(w_hat), _f32(x), _f32(bias), _f32(y), p, q, k, batch, epilogue,
                                  _ptr(workspace), workspace.numel(), _stream()), "circ_fc_forward")
+    return y
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def circ_fc_forward_static(w_hat, x, bias, y, p, q, k, epilogue=EPI_NONE):
+    """circ_fc_forward on the library's own fixed scratch array: y must be given (nothing is allocated)."""
+    _check(lib().circ_fc_forward_static(_ptr(w_hat), _f32(x), _f32(bias), _f32(y), p, q, k, x.shape[0], epilogue,
+                                        _stream()), "circ_fc_forward_static")
     return y
 
 

@@ -636,6 +636,58 @@ circ_status circ_fc_forward(const void* w_hat, const float* x, const float* bias
 
 }  // extern "C"
 
+// ---- FC forward for callers that cannot allocate ------------------------------------------------
+// The workspace of circ_fc_forward (activation spectra of the three-kernel route, partial
+// spectra of the split batch <= 2 kernel) lives in this array instead of a caller's buffer.  In
+// host code the name `scratch` is only a handle for the symbol, not a device address: the
+// address of the current device's copy is looked up once per device and that pointer is what
+// the kernels receive.
+static __device__ __align__(256) unsigned char scratch[CIRC_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+struct StaticScratch {
+  std::atomic<void*> ptr[kMaxDevices];   // static storage: starts at null
+};
+StaticScratch g_static_scratch;
+
+// Device address of `scratch` on the current device (each device holds its own copy).
+hipError_t static_scratch_ptr(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = g_static_scratch.ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    std::lock_guard<std::mutex> lock(lds_opt_in_mutex());
+    p = g_static_scratch.ptr[dev].load(std::memory_order_relaxed);
+    if (!p) {
+      const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return e;
+      if (!p) return hipErrorInvalidSymbol;
+      g_static_scratch.ptr[dev].store(p, std::memory_order_release);
+    }
+  }
+  *out = p;
+  return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+circ_status circ_fc_forward_static(const void* w_hat, const float* x, const float* bias, float* y, int p, int q, int k,
+                                   int batch, int epilogue, void* stream) {
+  if (!fc_dims_ok(p, q, k, batch)) return CIRC_EINVAL;
+  if (circ_fc_workspace_bytes(p, q, k, batch, 0) > size_t(CIRC_STATIC_SCRATCH_BYTES)) return CIRC_EWORKSPACE;
+  void* ws = nullptr;
+  if (static_scratch_ptr(&ws) != hipSuccess) return CIRC_EHIP;
+  // every kernel of the forward pass writes the part of the workspace it later reads, so nothing
+  // has to be cleared between calls
+  return circ_fc_forward(w_hat, x, bias, y, p, q, k, batch, epilogue, ws, size_t(CIRC_STATIC_SCRATCH_BYTES), stream);
+}
+
+}  // extern "C"
+
 namespace {
 
 // Launch one step (kernel above) on the spectrum sections of `w_hat`, then rebuild the operand

@@ -16,3 +16,4 @@ static inline void circ_dry_check(dim3 g, dim3 b, size_t lds) {
 #define hipGetLastError() hipSuccess
 #define hipFuncSetAttribute(...) hipSuccess
 #define hipGetDevice(p) ((*(p) = 0), hipSuccess)
+#define hipGetSymbolAddress(pp, sym) ((*(pp) = reinterpret_cast<void*>(0x7000000000ull)), hipSuccess)

@@ -34,6 +34,8 @@ DRIVER = textwrap.dedent(r'''
     for (p, q, k, b) in [(64, 64, 16, 1), (64, 64, 64, 64), (32, 72, 128, 256), (32, 72, 128, 1), (64, 64, 256, 1024),
                          (3, 5, 12, 7), (40, 40, 100, 64), (2, 3, 1, 4), (125, 512, 8, 1), (2, 3, 512, 2)]:
         assert L.circ_fc_forward(P[0], P[1], None, P[2], p, q, k, b, 0, P[3], ws, None) == 0, (p, q, k, b)
+        fits = L.circ_fc_workspace_bytes(p, q, k, b, 0) <= (32 << 20)
+        assert L.circ_fc_forward_static(P[0], P[1], None, P[2], p, q, k, b, 0, None) == (0 if fits else -3), (p, q, k, b)
         assert L.circ_fc_backward(P[0], P[1], P[2], P[3], P[4], p, q, k, b, P[5], ws, None) == 0, (p, q, k, b)
         assert L.circ_fc_sgd_step(P[0], P[1], P[2], P[3], c_f(0.1), p, q, k, b, P[5], ws, None) == 0, (p, q, k, b)
         assert L.circ_export_weights(P[0], 1, p, q, k, P[1], None) == 0
@@ -72,6 +74,7 @@ DRIVER = textwrap.dedent(r'''
         L.circ_precompute_spectra(P[0], rng.choice([1, 9, 25]), p, q, k, P[1], None)
         L.circ_precompute_spectra_f16(P[0], p, q, k, P[1], None)
         L.circ_fc_forward(P[0], P[1], None, P[2], p, q, k, b, 0, P[3], ws, None)
+        L.circ_fc_forward_static(P[0], P[1], None, P[2], p, q, k, b, 0, None)
         L.circ_fc_forward_f16(P[0], P[1], None, P[2], p, q, k, b, 0, P[3], ws, None)
         L.circ_fc_forward_bf16(P[0], P[1], None, P[2], p, q, k, b, 0, P[3], ws, None)
         L.circ_fc_backward_workspace_bytes_f16(p, q, k, b)
