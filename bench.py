@@ -7,16 +7,18 @@ circ_fc_forward (FFT of the activations, per-frequency contraction with the cach
 spectra, inverse FFT with the epilogue) over one batch of 64 synthetic input vectors.  The
 weight spectra are computed once before the timed region, as the method caches FFT(w_ij).
 
-Timed region: K steps recorded into one HIP graph and replayed once, bracketed by events on
-the launch stream and by torch.cuda.synchronize().  Each step reads a different activation
-buffer and writes a different output buffer out of a pool larger than twice the 256 MB
-Infinity Cache, so activations really come from HBM while the 1 MB of weight spectra
-legitimately stays cached.  The steps are independent batches, so the graph issues them
-round-robin on several streams (--streams, all default priority): two workgroups of the
-kernel fit one CU, so a step starts while the previous ones are still waiting for their
-operands or draining, and the ~2 us between two kernels of one stream is filled as well.
-Extra fields report the single-stream graph, eager launches, and one warm buffer pair; the
-roofline entry always uses the single-stream kernel time.
+Timed region: K steps recorded into one HIP graph; the graph is replayed `--replays` times and the
+median replay time divided by K is a step's time.  Every step has its own activation and output
+buffer, and before each timed replay the caches are emptied (a 1 GB buffer is read and rewritten)
+and the 1 MB of weight spectra is touched again by one untimed step on a spare buffer pair, so for
+any K the activations come from HBM while the weight spectra stay cached, as the method keeps them
+between batches.  The same replays without the eviction give the "warm" figures.  Two launch
+shapes are timed: all steps on one stream (its event time is the kernel time of the roofline
+entry), and the steps round-robin over several streams (--streams, all default priority; the
+steps are independent batches and two workgroups of the kernel fit one CU, so a step starts while
+earlier ones wait for operands or drain).  `value` is the better of the two by the host clock;
+`config.launch` says which.  Extra fields report both shapes cold and warm, eager launches and
+one warm buffer pair.
 
 Prints ONE JSON line.
 """
@@ -34,11 +36,29 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "fc_fused_kernel_cfg2_pmc_traffic.md")
 
-# Bytes per launch between L2 and the memory side, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# each scaled by what the counter reads for a plain 256 MiB copy
-# (profiles/fc_fused_kernel_cfg2_pmc_traffic.md): 6.49 MB fetched + 1.05 MB written.
-MEASURED_TRAFFIC_BYTES = 7537095
+
+def recorded_traffic():
+    """HBM-side bytes per launch of the step's kernel as recorded by the committed rocprofv3 --pmc
+    summary (line `traffic_bytes_per_launch: N`; the file states the commands, the raw FETCH_SIZE /
+    WRITE_SIZE readings and the copy-kernel scale factors).  None when the summary is absent."""
+    try:
+        import re
+        m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", open(TRAFFIC_PROFILE).read(), re.M)
+        return (int(m.group(1)), os.path.relpath(TRAFFIC_PROFILE, ROOT)) if m else (None, None)
+    except OSError:
+        return None, None
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def algorithmic_work(p, q, k, B, bias):
@@ -57,6 +77,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=16, help="streams the graph of independent steps is spread over")
     ap.add_argument("--pool-mb", type=int, default=640, help="size of the rotating activation/output pool")
+    ap.add_argument("--replays", type=int, default=50, help="timed replays of the K-step graph per figure (the median is reported)")
+    ap.add_argument("--evict-mb", type=int, default=1024, help="buffer rewritten before every cold replay to empty the caches")
     ap.add_argument("--pmc", action="store_true",
                     help="counter-collection mode for rocprofv3 --pmc: eager launches only (no graph), plus "
                          "8 plain device copies of 256 MiB as the known-size reference for FETCH_SIZE/WRITE_SIZE")
@@ -137,22 +159,50 @@ def main():
         print(json.dumps({"pmc_mode": True, "steps": K, "warmup": Wm, "copy_bytes": 256 << 20, "copies": 8}))
         return
 
-    # --- eager launches, rotating buffers
-    ev_eager, wall_eager = timed(lambda: [step(i % npairs) for i in range(K)])
-    # --- eager launches, one warm pair
+    # Cold activations for ANY number of steps: before every timed replay a buffer of four times the
+    # 256 MB Infinity Cache is read and rewritten, which evicts the activations the previous replay
+    # (or the graph upload) left in the caches; one untimed step on a pair outside the graph's
+    # window then brings the 1 MB of weight spectra back, since the method keeps those cached
+    # between batches.  "Warm" replays skip the eviction.
+    evict = torch.zeros(args.evict_mb << 18, dtype=torch.float32, device=dev)
+    window = [(Wm + i) % npairs for i in range(K)]
+    spare = next((i for i in range(npairs) if i not in set(window)), window[-1])
+
+    def replay_stats(graph, cold, reps):
+        ev, wall = [], []
+        for _ in range(reps):
+            if cold:
+                evict.add_(1.0)
+                torch.cuda.synchronize()
+                with torch.cuda.stream(stream):
+                    step(spare)
+            e, w_ = timed(graph.replay)
+            ev.append(e)
+            wall.append(w_)
+        ev.sort(); wall.sort()
+        return {"events_median": ev[len(ev) // 2] / K * 1e6, "events_min": ev[0] / K * 1e6,
+                "wall_median": wall[len(wall) // 2] / K * 1e6}
+
+    def capture(launch_all):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            launch_all()
+        g.replay()                                   # untimed: uploads the executable graph
+        torch.cuda.synchronize()
+        return g
+
+    R = max(1, args.replays)
+    # --- eager launches, rotating buffers / one warm pair (single measurements of K launches)
+    evict.add_(1.0)
+    ev_eager, wall_eager = timed(lambda: [step(i) for i in window])
     ev_warm, _ = timed(lambda: [step(0) for _ in range(K)])
 
-    # --- K steps in one HIP graph (rotating buffers), replayed: the figure reported
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=stream):
-        for i in range(K):
-            step((Wm + i) % npairs)
-    graph.replay()                                   # untimed: uploads the executable graph
-    torch.cuda.synchronize()
-    ev_graph, wall_graph = timed(graph.replay)
+    # --- K steps in one HIP graph on one stream: the kernel time of the roofline entry
+    graph1 = capture(lambda: [step(i) for i in window])
+    one_cold, one_warm = replay_stats(graph1, True, R), replay_stats(graph1, False, R)
 
-    # --- the same K steps, round-robin over several streams inside one graph
-    S = max(1, args.streams)
+    # --- the same K steps round-robin over several streams inside one graph: the reported throughput
+    S = max(1, min(args.streams, K))
     side = [torch.cuda.Stream(device=dev) for _ in range(S - 1)]     # default priority
     lanes = [(sptr, wsp)]
     side_ws = []
@@ -166,20 +216,19 @@ def main():
         if st != 0:
             raise RuntimeError(B.status_string(st))
 
-    graph2 = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph2, stream=stream):
+    def multi():
         for st_ in side:
             st_.wait_stream(stream)                  # fork
-        for i in range(K):
-            step_on((Wm + i) % npairs, i % S)
+        for n_, i in enumerate(window):
+            step_on(i, n_ % S)
         for st_ in side:
             stream.wait_stream(st_)                  # join
-    graph2.replay()
-    torch.cuda.synchronize()
-    ev_graph2, wall_graph2 = timed(graph2.replay)
+
+    graphS = capture(multi)
+    multi_cold, multi_warm = replay_stats(graphS, True, R), replay_stats(graphS, False, R)
 
     # --- floors: kernels without arithmetic, same launch shape (256 workgroups x 512 threads), timed
-    # like the one-stream graph above.  `copy`: every byte of x, of a weight-sized buffer and of y
+    # like the one-stream graph above (cold).  `copy`: every byte of x, of a weight-sized buffer and of y
     # is touched once (the algorithmic bytes); `same_footprint`: every workgroup loads what a
     # workgroup of the fused kernel loads (one 128 KB weight tile and two rows of x, shared
     # between workgroups and XCDs through the same tile map) and stores its 4 KB of y.
@@ -198,14 +247,11 @@ def main():
         xb, wb, yb = 4 * batch * cfg.n_in, 4 * p * q * k, 4 * batch * cfg.n_out
 
         def graph_time(launch):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=stream):
-                for i in range(K):
-                    if launch((Wm + i) % npairs) != 0:
+            def all_():
+                for i in window:
+                    if launch(i) != 0:
                         raise RuntimeError("floor kernel launch failed")
-            g.replay()
-            torch.cuda.synchronize()
-            return timed(g.replay)[0] / K * 1e6
+            return replay_stats(capture(all_), True, max(1, R // 2))["events_median"]
 
         floors = {
             "empty_launch_us": graph_time(lambda i: FL.circ_floor_empty(nwg, nthr, sptr)),
@@ -213,39 +259,52 @@ def main():
                 wdp, wb, xp[i], xb, yp[i], yb, nwg, nthr, wb // nwg, xb // nwg, yb // nwg, 0, 0, 0, sptr)),
             "same_footprint_loads_us": graph_time(lambda i: FL.circ_floor_stream(
                 wdp, wb, xp[i], xb, yp[i], yb, nwg, nthr, wb // 8, xb // 32, yb // nwg, 4, 2, 16, sptr)),
-            "note": "HIP events over a one-stream graph of K launches of 256 workgroups x 512 threads, no arithmetic",
+            "note": "HIP events over a one-stream graph of K launches of 256 workgroups x 512 threads, no arithmetic, "
+                    "cold activations, median over replays",
         }
 
-    t_step = ev_graph / K
+    # the reported throughput: the better of the two launch shapes on cold activations, by the host clock
+    use_multi = multi_cold["wall_median"] <= one_cold["wall_median"]
+    best = multi_cold if use_multi else one_cold
+    t_step = one_cold["events_median"] * 1e-6
     alg_bytes, alg_flops = algorithmic_work(p, q, k, batch, True)
+    traffic, traffic_src = recorded_traffic()
     out = {
         "metric": "vectors/s for block-circulant FC (4096^2, k=64, B=64); % of HBM/MFMA roofline",
-        "value": batch * K / wall_graph2,
+        "value": batch / (best["wall_median"] * 1e-6),
         "unit": "vectors/s",
         "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": wall_graph2 / K * 1e3,
+        "ms_per_step": best["wall_median"] * 1e-3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "cfg2: block-circulant FC forward, n_in=n_out=4096, k=64 (p=q=64), batch 64, "
-                               "fp32, bias+ReLU; cached weight spectra; activations rotate through a "
-                               f"{npairs * pair_bytes >> 20} MB pool (HBM-resident, not cache-resident)",
-                   "p": p, "q": q, "k": k, "batch": batch, "launch": f"one hip graph of K independent steps, round-robin over {S} streams"},
+                               "fp32, bias+ReLU; cached weight spectra; every step has its own activation and output "
+                               f"buffers out of a {npairs * pair_bytes >> 20} MB pool and the caches are evicted before "
+                               "each timed replay (activations come from HBM, the 1 MB of weight spectra stays cached)",
+                   "p": p, "q": q, "k": k, "batch": batch,
+                   "launch": (f"one hip graph of K independent steps, round-robin over {S} streams" if use_multi
+                              else "one hip graph of K steps on one stream"),
+                   "replays_timed": R, "statistic": "median over replays of (host-clock time of one replay) / K"},
         "dense_equivalent_gflops": 2.0 * cfg.n_in * cfg.n_out * batch / t_step * 1e-9,
         "roofline": {
-            "bound": "mfma", "kernel": "circ::fc_fused_kernel<64, 8, 1, 512, true, 0> (the one kernel of a step)",
+            "bound": "mfma", "kernel": "circ::fc_fused_kernel (k = 64 instantiation; the one kernel of a step)",
             "achieved": alg_flops / t_step * 1e-12, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": alg_flops / t_step * 1e-12 / MFMA_FP32_PEAK_TFLOPS,
-            "traffic": MEASURED_TRAFFIC_BYTES,
+            "traffic": traffic, "traffic_source": traffic_src,
             "algorithmic_flops_per_step": alg_flops, "algorithmic_bytes_per_step": alg_bytes,
             "avg_kernel_us_by_events": t_step * 1e6,
+            "avg_kernel_us_by_events_warm": one_warm["events_median"],
             "hbm_view": {"achieved": alg_bytes / t_step * 1e-9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": alg_bytes / t_step * 1e-9 / HBM_PEAK_GBS},
         },
         "timing_detail_us_per_step": {
-            "graph_multi_stream_events": ev_graph2 / K * 1e6, "graph_multi_stream_wall": wall_graph2 / K * 1e6, "streams": S,
-            "graph_one_stream_events": ev_graph / K * 1e6, "graph_one_stream_wall": wall_graph / K * 1e6,
+            "replays": R, "streams": S,
+            "graph_one_stream_cold": one_cold, "graph_one_stream_warm": one_warm,
+            "graph_multi_stream_cold": multi_cold, "graph_multi_stream_warm": multi_warm,
+            "warm_means": f"no eviction between replays: the graph's own working set ({min(K, npairs) * pair_bytes >> 20} MB) "
+                          "is what the caches hold",
             "eager_rotating_events": ev_eager / K * 1e6, "eager_rotating_wall": wall_eager / K * 1e6,
-            "eager_warm_pair_events": ev_warm / K * 1e6,
+            "eager_one_warm_pair_events": ev_warm / K * 1e6,
         },
     }
 
@@ -264,17 +323,27 @@ def main():
             step(0)
         torch.cuda.synchronize()
         out["max_norm_rel_err_vs_oracle"] = O.max_norm_rel_err(ys[0].cpu().numpy(), ref)
-        reps, t0 = 0, time.perf_counter()
-        while True:
-            O.fc_forward(w, x0, bias, True)
-            reps += 1
-            el = time.perf_counter() - t0
-            if el > 12.0 or reps >= 1000:
-                break
+
+        def repeat(fn_, budget_s):
+            reps, t0 = 0, time.perf_counter()
+            while True:
+                fn_()
+                reps += 1
+                el = time.perf_counter() - t0
+                if el > budget_s:
+                    return reps, el
+
+        reps, el = repeat(lambda: O.fc_forward(w, x0, bias, True), 10.0)
+        Wdense = O.expand_block_circulant(w)         # expanded once, outside the timed loop
+        reps2, el2 = repeat(lambda: O.fc_forward_expanded(Wdense, x0, bias, True), 6.0)
         out["cpu_baseline"] = {
-            "value": batch * reps / el, "unit": "vectors/s", "cores": cores, "kind": "oracle",
+            "value": batch * reps / el, "unit": "vectors/s", "cores": cores, "kind": "oracle", "cpu": cpu_model(),
             "sample": f"{reps} repetitions of the full cfg2 batch (64 vectors each, float64, dense expansion of "
-                      f"the blocks included), {el:.1f} s",
+                      f"the blocks included in every repetition), {el:.1f} s",
+            "weights_pre_expanded": {
+                "value": batch * reps2 / el2, "unit": "vectors/s",
+                "sample": f"{reps2} repetitions of the same batch on the dense matrix expanded once beforehand "
+                          f"(the counterpart of cached weight spectra), {el2:.1f} s"},
         }
     print(json.dumps(out))
 

@@ -27,7 +27,8 @@ Readings of the paper taken here (each also pinned by a CPU test):
 
 Parity pins: all functions below are pinned (see tests/test_oracle_pins.py):
 circulant definition, shift direction, DFT diagonalisation, brute-force
-circular convolution, exact integers, k = 1 dense layer, p = q = 1 library
+circular convolution, exact integers, k = 1 dense layer, bias and ReLU at k > 1 on a
+matrix written entry by entry (also for the pre-expanded form), p = q = 1 library
 circular convolution, finite differences and bilinear identities for the
 gradients, library convolution and single-pixel response for CONV; the CONV
 gradients and the bias gradient by finite differences, the library's own
@@ -87,6 +88,17 @@ def fc_forward(w, x, bias=None, relu=False, block_rows=None) -> np.ndarray:
     if relu:
         out = np.maximum(out, 0.0)
     return out
+
+
+def fc_forward_expanded(W, x, bias=None, relu=False) -> np.ndarray:
+    """y = psi(W x + theta) (Eq. 1) on a matrix that has already been written out with
+    expand_block_circulant: the same layer as fc_forward when the dense expansion of the blocks
+    is done once and kept, the counterpart of keeping FFT(w_ij) instead of recomputing it.
+    W[p*k][q*k], x[B][q*k] -> y[B][p*k]."""
+    a = np.matmul(np.asarray(x, dtype=np.float64), np.asarray(W, dtype=np.float64).T)
+    if bias is not None:
+        a = a + np.asarray(bias, dtype=np.float64)
+    return np.maximum(a, 0.0) if relu else a
 
 
 def fc_backward_dx(w, dy, block_cols=None) -> np.ndarray:

@@ -132,6 +132,9 @@ def test_bias_relu_epilogue_vs_entrywise_dense_matrix(p, q, k, B):
     np.testing.assert_allclose(O.fc_forward(w, x, bias=bias, relu=True), torch.relu(lin).numpy(), atol=1e-12)
     np.testing.assert_allclose(O.fc_forward(w, x, bias=bias, relu=False), lin.numpy(), atol=1e-12)
     np.testing.assert_allclose(O.fc_forward(w, x, relu=True), torch.relu(xt @ W.T).numpy(), atol=1e-12)
+    # the pre-expanded form: the same numbers from a matrix expanded once
+    np.testing.assert_allclose(O.fc_forward_expanded(O.expand_block_circulant(w), x, bias, True), torch.relu(lin).numpy(), atol=1e-12)
+    np.testing.assert_allclose(O.fc_forward_expanded(W.numpy(), x), (xt @ W.T).numpy(), atol=1e-12)
     # a listed subset of block rows takes the bias of those rows
     np.testing.assert_allclose(O.fc_forward(w, x, bias=bias, relu=True, block_rows=[p - 1, 0]),
                                torch.relu(torch.cat([lin[:, (p - 1) * k:], lin[:, :k]], dim=1)).numpy(), atol=1e-12)
