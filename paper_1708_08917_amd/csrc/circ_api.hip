@@ -327,20 +327,10 @@ hipError_t launch_fused_v(const float4* wf, const float* x, const float* bias, f
   using Sh = FusedShape<K, IT, NP, NT>;
   static_assert((4096 / K) % Sh::JC == 0, "packed weights are padded to chunks of 4096/K input blocks");
   static LdsOptIn opted_in;
-  if (ensure_lds(&fc_fused_kernel<K, IT, NP, NT, ONE, HM>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
-  const int n_it = (int)cdiv(p, IT), n_bt = (int)cdiv(batch, 2 * NP);
-  // Split the tile grid over the 8 XCDs as xa x (8/xa) rectangles; pick the split that
-  // minimises the bytes every XCD pulls into its own L2 (weight tiles + x rows).
-  int xa = 1;
-  double best = 1e300;
-  for (int cand = 1; cand <= 8; cand *= 2) {
-    const double wbytes = double(cdiv(n_it, cand)) * IT * q * K * 4.0;
-    const double xbytes = double(cdiv(n_bt, 8 / cand)) * 2 * NP * q * K * 4.0;
-    if (wbytes + xbytes < best) { best = wbytes + xbytes; xa = cand; }
-  }
-  const long long grid = 8 * cdiv(n_it, xa) * cdiv(n_bt, 8 / xa);
-  hipLaunchKernelGGL((fc_fused_kernel<K, IT, NP, NT, ONE, HM>), dim3((unsigned)grid), dim3(NT), Sh::LDS_BYTES, s, wf, x, bias,
-                     y, p, q, batch, n_it, fused_q2p(q, K), xa, relu);
+  if (ensure_lds(&fc_fused_kernel<K, IT, NP, NT, ONE, HM>, Sh::lds_bytes(ONE), opted_in) != hipSuccess) return hipErrorInvalidValue;
+  const FusedTileMap tm = make_fused_tile_map(p, q, K, IT, NP, batch);
+  hipLaunchKernelGGL((fc_fused_kernel<K, IT, NP, NT, ONE, HM>), dim3(tm.grid), dim3(NT), Sh::lds_bytes(ONE), s, wf, x, bias,
+                     y, p, q, batch, tm, fused_q2p(q, K), relu);
   return hipGetLastError();
 }
 

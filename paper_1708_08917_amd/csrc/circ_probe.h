@@ -4,9 +4,9 @@
 // translation unit, outside the product, that defines CIRC_PROBE(id) before it includes the
 // library source, e.g. as "thread 0 of the workgroup stores the clock (s_memtime) into slot
 // (workgroup, id) of a device array", and reads that array back after one launch.  The ids mark
-// phase boundaries: 0 kernel start, 1 + 4c .. 4 + 4c the four phases of chunk c (x staged, first
-// transform pass, second pass, contraction), 60 .. 62 output spectra assembled, inverse
-// transform done, outputs stored.  This is the only profiling switch in the sources.
+// phase boundaries: 0 kernel start; for chunk c: 2 + 4c first transform pass done, 3 + 4c
+// second pass written, 1 + 4c barrier passed (operands ready), 4 + 4c contraction issued; 60 .. 62
+// output spectra assembled, inverse transform done, outputs stored.  This is the only profiling switch in the sources.
 #pragma once
 
 #ifndef CIRC_PROBE

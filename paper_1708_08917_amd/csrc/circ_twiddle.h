@@ -49,14 +49,17 @@ constexpr float tw_sin(int m, int n) { return float(cos_sin_frac(m, n).s); }
 
 constexpr int kTwN = 512;   // largest supported block size
 
-struct TwiddleTable {
+struct alignas(16) TwiddleTable {
   float c[kTwN];   // cos(2 pi m / 512)
   float s[kTwN];   // sin(2 pi m / 512)
-  constexpr TwiddleTable() : c(), s() {
+  float cs[2 * kTwN];   // the same values as (cos, sin) pairs, for one 8-byte load per twiddle
+  constexpr TwiddleTable() : c(), s(), cs() {
     for (int m = 0; m < kTwN; ++m) {
       cpair v = cos_sin_frac(m, kTwN);
       c[m] = float(v.c);
       s[m] = float(v.s);
+      cs[2 * m] = float(v.c);
+      cs[2 * m + 1] = float(v.s);
     }
   }
 };
