@@ -307,6 +307,53 @@ circ_status circ_conv_backward_bf16(const void* w_hat, const void* x, const void
 circ_status circ_bias_grad(const float* dy, float* db, long long outer, int channels,
                            long long inner, void* stream);
 
+/*
+ * Max-pooling, the subsampling (POOL) layer of Sec. 2.1, run by the peripheral block on
+ * comparators in the paper's architecture (Sec. 4.2):
+ *   y[n][c][ho][wo] = max_{a,b < window} x[n][c][ho*stride + a][wo*stride + b]
+ *   x  device, NCHW [N][C][H][W];  y  device, NCHW [N][C][(H-window)/stride+1][(W-window)/stride+1]
+ * Windows lie entirely inside the image (no padding); 1 <= window <= min(H, W), stride >= 1.
+ * The result is exact (no arithmetic).  CIRC_EINVAL for bad sizes, NULL / misaligned / overlapping
+ * pointers; CIRC_EHIP for a failed launch.
+ */
+circ_status circ_maxpool_forward(const float* x, float* y, int N, int C, int H, int W,
+                                 int window, int stride, void* stream);
+
+/*
+ * A chain of layers evaluated back to back on one stream: the inference regime of Sec. 5.3 (one
+ * image through a whole network; Sec. 2.1: DNNs cascade FC, CONV and POOL layers).  Each layer is
+ * what the single-layer entry point computes (circ_fc_forward, circ_conv_forward,
+ * circ_maxpool_forward); activations between layers stay in the workspace, and a batch of one
+ * or two vectors takes the streaming kernels of the FC layers.  Activations are NCHW; an FC
+ * layer reads the preceding image as the vector [C*H*W] it is in memory.
+ *   layers   HOST array of n_layers descriptors (read during the call only):
+ *     kind      CIRC_LAYER_FC: p, q, k, w_hat, bias, epilogue as for circ_fc_forward
+ *               CIRC_LAYER_CONV: C_in, C_out, H, W (input image), r, stride, pad, k, w_hat, bias,
+ *                                epilogue as for circ_conv_forward
+ *               CIRC_LAYER_MAXPOOL: C_in (channels), H, W (input image), r (window), stride
+ *     the output of every layer must have as many elements as the next layer's input
+ *   x  device, input of the first layer, [batch][...];  y  device, output of the last layer
+ *   workspace  device, at least circ_chain_workspace_bytes(layers, n_layers, batch) bytes
+ *              (0 for an invalid chain); must not overlap x or y
+ * CIRC_EINVAL: invalid or ill-fitting descriptors, NULL / misaligned pointers, overlaps;
+ * CIRC_EWORKSPACE: short workspace; CIRC_EHIP: a failed launch (earlier layers are enqueued).
+ */
+typedef enum { CIRC_LAYER_FC = 0, CIRC_LAYER_CONV = 1, CIRC_LAYER_MAXPOOL = 2 } circ_layer_kind;
+typedef struct {
+  int kind;             /* circ_layer_kind */
+  int epilogue;         /* CIRC_EPI_* flags (FC, CONV) */
+  const void* w_hat;    /* device: spectra blob of the layer (FC, CONV) */
+  const float* bias;    /* device: [p*k] (FC) / [C_out] (CONV), or NULL */
+  int k;                /* block size (FC, CONV) */
+  int p, q;             /* FC: grid of blocks (p*k outputs, q*k inputs) */
+  int C_in, C_out;      /* CONV: channels; MAXPOOL: C_in = channels */
+  int H, W;             /* CONV, MAXPOOL: input image */
+  int r, stride, pad;   /* CONV: filter size, stride, padding; MAXPOOL: r = window, stride (pad unused) */
+} circ_layer;
+size_t circ_chain_workspace_bytes(const circ_layer* layers, int n_layers, int batch);
+circ_status circ_chain_forward(const circ_layer* layers, int n_layers, const float* x, float* y,
+                               int batch, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

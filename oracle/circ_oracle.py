@@ -35,7 +35,8 @@ gradients and the bias gradient by finite differences, the library's own
 convolution gradients, the bilinear identities and the r = 1 reduction to the
 FC gradients; the gradient-descent steps by the library's own optimiser acting
 on gathered dense weights, a closed form for k = 1 and the decrease of a
-quadratic loss.
+quadratic loss; max-pooling and chains of layers by the library's float64 pooling, dense
+convolution and linear layers on weights written entry by entry, and a hand-worked window.
 """
 from __future__ import annotations
 
@@ -240,6 +241,41 @@ def conv_backward_dw(x, dy, k, r, pad=0, stride=1) -> np.ndarray:
                     Gb = G[i * k:(i + 1) * k, j * k:(j + 1) * k]
                     dw[dh, dw_, i, j] = Gb[a, col].sum(axis=0)
     return dw
+
+
+def maxpool_forward(x, window, stride) -> np.ndarray:
+    """Max-pooling (the POOL layer of Sec. 2.1): x[N][C][H][W] ->
+    y[n, c, ho, wo] = max over a, b < window of x[n, c, ho*stride + a, wo*stride + b];
+    windows lie inside the image, (H - window) // stride + 1 output rows."""
+    x = np.asarray(x, dtype=np.float64)
+    N, C, H, W = x.shape
+    Ho, Wo = (H - window) // stride + 1, (W - window) // stride + 1
+    y = np.full((N, C, Ho, Wo), -np.inf)
+    for a in range(window):
+        for b in range(window):
+            y = np.maximum(y, x[:, :, a:a + (Ho - 1) * stride + 1:stride, b:b + (Wo - 1) * stride + 1:stride])
+    return y
+
+
+def chain_forward(layers, x) -> np.ndarray:
+    """A cascade of layers (Sec. 2.1), each the definition above applied to the previous output.
+    `layers`: list of dicts, kind = "fc" (w[p][q][k], bias, relu), "conv" (w[r][r][p][q][k], bias,
+    relu, pad, stride) or "pool" (window, stride).  An FC layer reads the preceding image as the
+    vector [C*H*W] it is in NCHW order; a CONV / POOL layer after an FC layer needs "shape":
+    (C, H, W) to view the vector as an image."""
+    a = np.asarray(x, dtype=np.float64)
+    for l in layers:
+        if "shape" in l:
+            a = a.reshape((a.shape[0],) + tuple(l["shape"]))
+        if l["kind"] == "fc":
+            a = fc_forward(l["w"], a.reshape(a.shape[0], -1), l.get("bias"), l.get("relu", False))
+        elif l["kind"] == "conv":
+            a = conv_forward(l["w"], a, l.get("bias"), l.get("relu", False), l.get("pad", 0), l.get("stride", 1))
+        elif l["kind"] == "pool":
+            a = maxpool_forward(a, l["window"], l["stride"])
+        else:
+            raise ValueError(l["kind"])
+    return a
 
 
 def bias_grad(dy, channel_axis=1) -> np.ndarray:

@@ -60,6 +60,23 @@ SIGNATURES = {
 }
 
 
+LAYER_FC, LAYER_CONV, LAYER_MAXPOOL = 0, 1, 2
+
+
+class CircLayer(ctypes.Structure):
+    """circ_layer of include/circ.h (one layer of a chain; a host-side descriptor)."""
+    _fields_ = [("kind", _c_int), ("epilogue", _c_int), ("w_hat", _c_ptr), ("bias", _c_ptr), ("k", _c_int),
+                ("p", _c_int), ("q", _c_int), ("C_in", _c_int), ("C_out", _c_int), ("H", _c_int), ("W", _c_int),
+                ("r", _c_int), ("stride", _c_int), ("pad", _c_int)]
+
+
+SIGNATURES.update({
+    "circ_maxpool_forward": (_c_int, [_c_ptr, _c_ptr] + [_c_int] * 6 + [_c_ptr]),
+    "circ_chain_workspace_bytes": (_c_size, [ctypes.POINTER(CircLayer), _c_int, _c_int]),
+    "circ_chain_forward": (_c_int, [ctypes.POINTER(CircLayer), _c_int, _c_ptr, _c_ptr, _c_int, _c_ptr, _c_size, _c_ptr]),
+})
+
+
 class CircError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -350,3 +367,45 @@ def circ_bias_grad(dy, db=None):
     _check(lib().circ_bias_grad(_f32(dy), _f32(db), outer, channels, inner, _stream()), "circ_bias_grad")
     return db
 
+
+
+def circ_maxpool_forward(x, window, stride, y=None):
+    """x: NCHW fp32 -> y: NCHW [(H - window) // stride + 1][(W - window) // stride + 1] (allocated if None)."""
+    N, C, H, W = x.shape
+    if y is None:
+        y = torch.empty(N, C, (H - window) // stride + 1, (W - window) // stride + 1, dtype=torch.float32, device=x.device)
+    _check(lib().circ_maxpool_forward(_f32(x), _f32(y), N, C, H, W, window, stride, _stream()), "circ_maxpool_forward")
+    return y
+
+
+def fc_layer(w_hat, bias, p, q, k, epilogue=EPI_NONE) -> CircLayer:
+    return CircLayer(kind=LAYER_FC, epilogue=epilogue, w_hat=_ptr(w_hat), bias=_f32(bias), k=k, p=p, q=q)
+
+
+def conv_layer(w_hat, bias, C_in, C_out, H, W, r, stride, pad, k, epilogue=EPI_NONE) -> CircLayer:
+    return CircLayer(kind=LAYER_CONV, epilogue=epilogue, w_hat=_ptr(w_hat), bias=_f32(bias), k=k, C_in=C_in, C_out=C_out,
+                     H=H, W=W, r=r, stride=stride, pad=pad)
+
+
+def maxpool_layer(C, H, W, window, stride) -> CircLayer:
+    return CircLayer(kind=LAYER_MAXPOOL, C_in=C, H=H, W=W, r=window, stride=stride)
+
+
+def circ_chain_workspace_bytes(layers, batch) -> int:
+    arr = (CircLayer * len(layers))(*layers)
+    return lib().circ_chain_workspace_bytes(arr, len(layers), batch)
+
+
+def circ_chain_forward(layers, x, y, workspace=None):
+    """layers: list of CircLayer (the tensors they point to must stay alive); x: [batch][...] device fp32;
+    y: output of the last layer, preallocated.  Returns y."""
+    batch = x.shape[0]
+    arr = (CircLayer * len(layers))(*layers)
+    if workspace is None:
+        nb = lib().circ_chain_workspace_bytes(arr, len(layers), batch)
+        if nb == 0:
+            raise CircError(CIRC_EINVAL, "circ_chain_workspace_bytes")
+        workspace = torch.empty(nb, dtype=torch.uint8, device=x.device)
+    _check(lib().circ_chain_forward(arr, len(layers), _f32(x), _f32(y), batch, _ptr(workspace), workspace.numel(), _stream()),
+           "circ_chain_forward")
+    return y

@@ -16,6 +16,7 @@
 #include "circ_conv_bwd.h"
 #include "circ_update.h"
 #include "circ_half.h"
+#include "circ_pool.h"
 
 namespace {
 
@@ -1715,6 +1716,145 @@ circ_status circ_fc_backward_f16(const void* w_hat, const void* x, const void* d
 circ_status circ_fc_backward_bf16(const void* w_hat, const void* x, const void* dy, void* dx, float* dw, int p, int q, int k,
                                   int batch, void* workspace, size_t workspace_bytes, void* stream) {
   return fc_backward_half(true, w_hat, x, dy, dx, dw, p, q, k, batch, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"
+
+// ---- max-pooling and chains of layers (the single-image regime of Sec. 5.3) ----------------------
+namespace {
+
+inline int pool_out(int n, int window, int stride) { return (n - window) / stride + 1; }
+
+inline bool pool_dims_ok(int N, int C, int H, int W, int window, int stride) {
+  if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || window <= 0 || stride <= 0 || window > H || window > W) return false;
+  const long long Ho = pool_out(H, window, stride), Wo = pool_out(W, window, stride);
+  // image planes fit the grid, the in-plane index its 32-bit reciprocal division
+  return (long long)N * C <= 65535ll * 65535ll && (long long)N * C * H * W <= (1ll << 40) && Ho * Wo * Wo < (1ll << 32);
+}
+
+// elements per batch item that a layer consumes / produces (0: invalid descriptor)
+long long layer_in_elems(const circ_layer& l) {
+  switch (l.kind) {
+    case CIRC_LAYER_FC: return (long long)l.q * l.k;
+    case CIRC_LAYER_CONV:
+    case CIRC_LAYER_MAXPOOL: return (long long)l.C_in * l.H * l.W;
+  }
+  return 0;
+}
+long long layer_out_elems(const circ_layer& l) {
+  switch (l.kind) {
+    case CIRC_LAYER_FC: return (long long)l.p * l.k;
+    case CIRC_LAYER_CONV: return (long long)l.C_out * conv_out(l.H, l.r, l.pad, l.stride) * conv_out(l.W, l.r, l.pad, l.stride);
+    case CIRC_LAYER_MAXPOOL: return (long long)l.C_in * pool_out(l.H, l.r, l.stride) * pool_out(l.W, l.r, l.stride);
+  }
+  return 0;
+}
+bool layer_ok(const circ_layer& l, int batch) {
+  switch (l.kind) {
+    case CIRC_LAYER_FC: return fc_dims_ok(l.p, l.q, l.k, batch);
+    case CIRC_LAYER_CONV: return conv_dims_ok(batch, l.C_in, l.C_out, l.H, l.W, l.r, l.pad, l.k) && l.stride >= 1;
+    case CIRC_LAYER_MAXPOOL: return pool_dims_ok(batch, l.C_in, l.H, l.W, l.r, l.stride);
+  }
+  return false;
+}
+size_t layer_workspace(const circ_layer& l, int batch) {
+  switch (l.kind) {
+    case CIRC_LAYER_FC: return circ_fc_workspace_bytes(l.p, l.q, l.k, batch, 0);
+    case CIRC_LAYER_CONV: return circ_conv_workspace_bytes(batch, l.C_in, l.C_out, l.H, l.W, l.r, l.stride, l.pad, l.k);
+    default: return 0;
+  }
+}
+// Layers that fit together: every layer valid, each output as long as the next input.
+// Returns the largest intermediate activation (elements per batch item) through *mid.
+bool chain_ok(const circ_layer* layers, int n_layers, int batch, long long* mid) {
+  if (!layers || n_layers <= 0 || n_layers > 4096 || batch <= 0) return false;
+  long long m = 0;
+  for (int i = 0; i < n_layers; ++i) {
+    if (!layer_ok(layers[i], batch)) return false;
+    if (i + 1 < n_layers) {
+      const long long o = layer_out_elems(layers[i]);
+      if (o != layer_in_elems(layers[i + 1])) return false;
+      if (o > m) m = o;
+    }
+  }
+  *mid = m;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+circ_status circ_maxpool_forward(const float* x, float* y, int N, int C, int H, int W, int window, int stride, void* stream) {
+  if (!x || !y || !pool_dims_ok(N, C, H, W, window, stride)) return CIRC_EINVAL;
+  if (!aligned16(x) || !aligned16(y)) return CIRC_EINVAL;
+  const int Ho = pool_out(H, window, stride), Wo = pool_out(W, window, stride);
+  const long long planes = (long long)N * C, total = planes * Ho * Wo;
+  if (overlaps(x, size_t(planes) * H * W * sizeof(float), y, size_t(total) * sizeof(float))) return CIRC_EINVAL;
+  const unsigned mul_wo = Wo > 1 ? unsigned(((1ull << 32) + unsigned(Wo) - 1) / unsigned(Wo)) : 0u;
+  const dim3 grid((unsigned)cdiv((long long)Ho * Wo, 256), (unsigned)(planes < 65535 ? planes : 65535), (unsigned)cdiv(planes, 65535));
+  hipLaunchKernelGGL(maxpool_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), x, y, (unsigned)planes, H, W, Ho, Wo,
+                     window, stride, mul_wo);
+  return hipGetLastError() == hipSuccess ? CIRC_OK : CIRC_EHIP;
+}
+
+size_t circ_chain_workspace_bytes(const circ_layer* layers, int n_layers, int batch) {
+  long long mid = 0;
+  if (!chain_ok(layers, n_layers, batch, &mid)) return 0;
+  size_t ws = 0;
+  for (int i = 0; i < n_layers; ++i) {
+    const size_t w = layer_workspace(layers[i], batch);
+    if (w > ws) ws = w;
+  }
+  // two buffers for the activations between the layers, then the largest layer workspace
+  const size_t act = align_up(size_t(mid) * batch * sizeof(float), 256);
+  return 2 * act + align_up(ws, 256) + 256;
+}
+
+circ_status circ_chain_forward(const circ_layer* layers, int n_layers, const float* x, float* y, int batch, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  long long mid = 0;
+  if (!chain_ok(layers, n_layers, batch, &mid)) return CIRC_EINVAL;
+  if (!x || !y || !aligned16(x) || !aligned16(y)) return CIRC_EINVAL;
+  for (int i = 0; i < n_layers; ++i) {
+    const circ_layer& l = layers[i];
+    if (l.kind == CIRC_LAYER_MAXPOOL) continue;
+    if (!l.w_hat || !aligned16(l.w_hat)) return CIRC_EINVAL;
+    if (l.epilogue & ~(CIRC_EPI_BIAS | CIRC_EPI_RELU)) return CIRC_EINVAL;
+    if ((l.epilogue & CIRC_EPI_BIAS) && (!l.bias || !aligned16(l.bias))) return CIRC_EINVAL;
+  }
+  const size_t xin = size_t(layer_in_elems(layers[0])) * batch * sizeof(float);
+  const size_t yout = size_t(layer_out_elems(layers[n_layers - 1])) * batch * sizeof(float);
+  if (overlaps(x, xin, y, yout)) return CIRC_EINVAL;
+  const size_t need = circ_chain_workspace_bytes(layers, n_layers, batch);
+  if (!workspace || workspace_bytes < need) return CIRC_EWORKSPACE;
+  if (!aligned16(workspace)) return CIRC_EINVAL;
+  if (overlaps(workspace, need, x, xin) || overlaps(workspace, need, y, yout)) return CIRC_EINVAL;
+  const size_t act = align_up(size_t(mid) * batch * sizeof(float), 256);
+  float* buf[2] = {static_cast<float*>(workspace), reinterpret_cast<float*>(static_cast<char*>(workspace) + act)};
+  void* lws = static_cast<char*>(workspace) + 2 * act;
+  const size_t lws_bytes = workspace_bytes - 2 * act;
+  const float* src = x;
+  for (int i = 0; i < n_layers; ++i) {
+    const circ_layer& l = layers[i];
+    float* dst = i + 1 == n_layers ? y : buf[i & 1];
+    circ_status st = CIRC_EINVAL;
+    switch (l.kind) {
+      case CIRC_LAYER_FC:
+        st = circ_fc_forward(l.w_hat, src, l.bias, dst, l.p, l.q, l.k, batch, l.epilogue, lws, lws_bytes, stream);
+        break;
+      case CIRC_LAYER_CONV:
+        st = circ_conv_forward(l.w_hat, src, l.bias, dst, batch, l.C_in, l.C_out, l.H, l.W, l.r, l.stride, l.pad, l.k, l.epilogue,
+                               lws, lws_bytes, stream);
+        break;
+      case CIRC_LAYER_MAXPOOL:
+        st = circ_maxpool_forward(src, dst, batch, l.C_in, l.H, l.W, l.r, l.stride, stream);
+        break;
+    }
+    if (st != CIRC_OK) return st;
+    src = dst;
+  }
+  return CIRC_OK;
 }
 
 }  // extern "C"

@@ -101,7 +101,7 @@ def bench_fc(cfg, reps, backward=False):
 
 
 def bench_chain(cfgs, reps):
-    """A stack of FC layers applied to the same batch, back to back in one graph: time per
+    """A stack of FC layers applied to the same batch through circ_chain_forward: time per
     pass over the whole stack (the per-image latency of a classifier head at batch 1)."""
     layers = []
     act = None
@@ -117,9 +117,13 @@ def bench_chain(cfgs, reps):
         layers.append((wh, act, bd, y, c, epi, ws))
         act = y
 
+    # one call of the chain entry point (the layers back to back on one stream, activations in its workspace)
+    descs = [B.fc_layer(wh, bd, c.p, c.q, c.k, epi) for wh, xin, bd, y, c, epi, ws in layers]
+    cws = torch.empty(B.circ_chain_workspace_bytes(descs, cfgs[0].batch), dtype=torch.uint8, device=DEV)
+    x0, ylast = layers[0][1], layers[-1][3]
+
     def run():
-        for wh, xin, bd, y, c, epi, ws in layers:
-            B.circ_fc_forward(wh, xin, bd, y, c.p, c.q, c.k, epi, ws)
+        B.circ_chain_forward(descs, x0, ylast, cws)
 
     t = _time(run, reps, max(3, reps // 10))
     names = " -> ".join([str(cfgs[0].n_in)] + [f"{c.n_out} (k={c.k})" for c in cfgs])

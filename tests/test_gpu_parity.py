@@ -816,6 +816,108 @@ def test_cfg5_forward_backward(seed):
     assert abs(np.sum(dw.astype(np.float64) * w) - s) <= 1e-4 * abs(s) + 1e-2
 
 
+# ---- max-pooling and chains of layers (single-image regime) ---------------------------------
+@pytest.mark.parametrize("N,C,H,W,window,stride", [(1, 1, 4, 4, 2, 2), (2, 3, 7, 9, 2, 2), (1, 4, 8, 8, 3, 2), (3, 1, 5, 6, 3, 3),
+                                                   (2, 2, 6, 6, 1, 1), (32, 256, 28, 28, 2, 2), (2, 96, 55, 55, 3, 2),
+                                                   (1, 2, 300, 1, 1, 1), (1, 1, 1, 1, 1, 1), (2, 70000, 3, 3, 2, 1)])
+def test_maxpool(N, C, H, W, window, stride):
+    x = RNG.standard_normal((N, C, H, W)).astype(np.float32)
+    y = B.circ_maxpool_forward(G.dev(x), window, stride)
+    torch.cuda.synchronize()
+    ref = O.maxpool_forward(x, window, stride)
+    assert y.shape == ref.shape
+    assert np.array_equal(y.cpu().numpy().astype(np.float64), ref)       # a maximum is exact
+
+
+def _chain_inputs(rng, spec, batch):
+    """spec: list of ("fc", p, q, k, bias, relu) / ("conv", C_in, C_out, H, W, r, stride, pad, k, bias, relu) /
+    ("pool", C, H, W, window, stride).  Returns (oracle layers, device layers, keep-alive tensors, x)."""
+    olayers, dlayers, keep = [], [], []
+    for l in spec:
+        if l[0] == "fc":
+            _, p, q, k, bias, relu = l
+            w = (rng.standard_normal((p, q, k)) / np.sqrt(q * k)).astype(np.float32)
+            b = (0.1 * rng.standard_normal(p * k)).astype(np.float32) if bias else None
+            wh = B.circ_precompute_spectra(G.dev(w)); bd = G.dev(b)
+            keep += [wh, bd]
+            olayers.append(dict(kind="fc", w=w, bias=b, relu=relu))
+            dlayers.append(B.fc_layer(wh, bd, p, q, k, G.epi_flags(b, relu)))
+        elif l[0] == "conv":
+            _, Ci, Co, H, W, r, stride, pad, k, bias, relu = l
+            w = (rng.standard_normal((r, r, Co // k, Ci // k, k)) * np.sqrt(2.0 / (r * r * Ci))).astype(np.float32)
+            b = (0.1 * rng.standard_normal(Co)).astype(np.float32) if bias else None
+            wh = B.circ_precompute_spectra(G.dev(w)); bd = G.dev(b)
+            keep += [wh, bd]
+            olayers.append(dict(kind="conv", w=w, bias=b, relu=relu, pad=pad, stride=stride))
+            dlayers.append(B.conv_layer(wh, bd, Ci, Co, H, W, r, stride, pad, k, G.epi_flags(b, relu)))
+        else:
+            _, C, H, W, window, stride = l
+            olayers.append(dict(kind="pool", window=window, stride=stride))
+            dlayers.append(B.maxpool_layer(C, H, W, window, stride))
+    first = spec[0]
+    shape = (batch, first[2] * first[3]) if first[0] == "fc" else (batch, first[1], first[2], first[3]) if first[0] == "pool" \
+        else (batch, first[1], first[3], first[4])
+    x = rng.uniform(-1, 1, shape).astype(np.float32)
+    return olayers, dlayers, keep, x
+
+
+HEAD = [("fc", 32, 72, 128, True, True), ("fc", 32, 32, 128, True, True), ("fc", 125, 512, 8, True, False)]
+CONVNET = [("conv", 64, 128, 14, 14, 3, 1, 1, 64, True, True), ("pool", 128, 14, 14, 2, 2),
+           ("fc", 4, 98, 64, True, True), ("fc", 5, 128, 2, True, False)]
+SMALLNET = [("conv", 8, 16, 12, 12, 3, 1, 1, 4, True, True), ("pool", 16, 12, 12, 2, 2), ("conv", 16, 16, 6, 6, 3, 1, 1, 8, False, False),
+            ("pool", 16, 6, 6, 2, 2), ("fc", 4, 9, 16, True, True), ("fc", 5, 32, 2, True, False)]
+
+
+@pytest.mark.parametrize("name,spec,batch", [("head 9216-4096-4096-1000", HEAD, 1), ("head 9216-4096-4096-1000", HEAD, 2),
+                                             ("head 9216-4096-4096-1000", HEAD, 5), ("conv-pool-fc-fc", CONVNET, 1),
+                                             ("conv-pool-fc-fc", CONVNET, 4), ("conv-pool-conv-pool-fc-fc", SMALLNET, 1),
+                                             ("conv-pool-conv-pool-fc-fc", SMALLNET, 3)])
+def test_chain_forward(name, spec, batch):
+    rng = np.random.default_rng(41 + batch)
+    olayers, dlayers, keep, x = _chain_inputs(rng, spec, batch)
+    ref = O.chain_forward(olayers, x)
+    y = torch.full(ref.shape, float("nan"), dtype=torch.float32, device=G.DEV)
+    B.circ_chain_forward(dlayers, G.dev(x), y)
+    torch.cuda.synchronize()
+    check(y.cpu().numpy(), ref, f"chain {name} batch {batch}")
+    # the chain is the single-layer entry points back to back: bit-identical to calling them one by one
+    a = G.dev(x)
+    for l, d in zip(spec, dlayers):
+        if l[0] == "fc":
+            a = B.circ_fc_forward(ctypes_tensor(keep, d.w_hat), a.reshape(batch, -1), ctypes_tensor(keep, d.bias), None, d.p, d.q, d.k, d.epilogue)
+        elif l[0] == "conv":
+            a = B.circ_conv_forward(ctypes_tensor(keep, d.w_hat), a, ctypes_tensor(keep, d.bias), None, d.C_out, d.r, d.stride, d.pad, d.k, d.epilogue)
+        else:
+            a = B.circ_maxpool_forward(a.reshape(batch, d.C_in, d.H, d.W), d.r, d.stride)
+    torch.cuda.synchronize()
+    assert torch.equal(a.reshape(y.shape), y)
+
+
+def ctypes_tensor(keep, ptr):
+    """The tensor in `keep` that starts at device address `ptr` (None for a NULL pointer)."""
+    if not ptr:
+        return None
+    return next(t for t in keep if t is not None and t.data_ptr() == ptr)
+
+
+def test_chain_rejects_ill_fitting_layers_and_short_workspace():
+    rng = np.random.default_rng(5)
+    _, dlayers, keep, x = _chain_inputs(rng, [("fc", 3, 4, 8, True, True), ("fc", 2, 3, 8, False, False)], 2)
+    y = torch.empty(2, 16, device=G.DEV)
+    B.circ_chain_forward(dlayers, G.dev(x), y)                        # fits
+    bad = [dlayers[0], B.fc_layer(ctypes_tensor(keep, dlayers[1].w_hat), None, 2, 4, 8)]   # 24 outputs into 32 inputs
+    assert B.circ_chain_workspace_bytes(bad, 2) == 0
+    with pytest.raises(B.CircError) as e:
+        B.circ_chain_forward(bad, G.dev(x), y, workspace=torch.empty(1 << 20, dtype=torch.uint8, device=G.DEV))
+    assert e.value.status == B.CIRC_EINVAL
+    with pytest.raises(B.CircError) as e:
+        B.circ_chain_forward(dlayers, G.dev(x), y, workspace=torch.empty(256, dtype=torch.uint8, device=G.DEV))
+    assert e.value.status == B.CIRC_EWORKSPACE
+    with pytest.raises(B.CircError) as e:
+        B.circ_maxpool_forward(G.dev(np.zeros((1, 1, 2, 2), np.float32)), 3, 1, y=torch.empty(1, 1, 1, 1, device=G.DEV))
+    assert e.value.status == B.CIRC_EINVAL
+
+
 # ---- error paths through the binding on the GPU box ---------------------------------------
 def test_errors_raise_through_binding():
     w, x, b = rand_fc(2, 2, 8, 2)

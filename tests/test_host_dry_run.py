@@ -61,6 +61,33 @@ DRIVER = textwrap.dedent(r'''
             assert L.circ_conv_forward(P[0], P[1], None, P[2], N, Ci, Co, H, W, r, st, pad, k, 0, P[3], ws, None) == 0
             assert L.circ_conv_backward(P[0], P[1], P[2], P[3], P[4], N, Ci, Co, H, W, r, st, pad, k, P[5], ws, None) == 0
     assert L.circ_bias_grad(P[0], P[1], c_ll(32), 256, c_ll(784), None) == 0
+    # max-pooling and chains of layers
+    class Layer(ctypes.Structure):
+        _fields_ = [("kind", c_int), ("epilogue", c_int), ("w_hat", c_ptr), ("bias", c_ptr), ("k", c_int), ("p", c_int), ("q", c_int),
+                    ("C_in", c_int), ("C_out", c_int), ("H", c_int), ("W", c_int), ("r", c_int), ("stride", c_int), ("pad", c_int)]
+    L.circ_chain_workspace_bytes.restype = c_size
+    for (N, C, H, W, win, st) in [(32, 256, 28, 28, 2, 2), (1, 1, 1, 1, 1, 1), (2, 70000, 3, 3, 2, 1), (1, 3, 1000, 1000, 3, 2)]:
+        assert L.circ_maxpool_forward(P[0], P[1], N, C, H, W, win, st, None) == 0, (N, C, H, W, win, st)
+    assert L.circ_maxpool_forward(P[0], P[1], 1, 1, 2, 2, 3, 1, None) == -1
+    assert L.circ_maxpool_forward(P[0], P[1], 1, 3, 60000, 60000, 3, 2, None) == -1      # in-plane index beyond 32 bits
+    head = (Layer * 3)(Layer(kind=0, epilogue=3, w_hat=P[2], bias=P[3], k=128, p=32, q=72),
+                       Layer(kind=0, epilogue=3, w_hat=P[2], bias=P[3], k=128, p=32, q=32),
+                       Layer(kind=0, epilogue=1, w_hat=P[2], bias=P[3], k=8, p=125, q=512))
+    net = (Layer * 4)(Layer(kind=1, epilogue=3, w_hat=P[2], bias=P[3], k=64, C_in=64, C_out=128, H=14, W=14, r=3, stride=1, pad=1),
+                      Layer(kind=2, C_in=128, H=14, W=14, r=2, stride=2),
+                      Layer(kind=0, epilogue=3, w_hat=P[2], bias=P[3], k=64, p=4, q=98),
+                      Layer(kind=0, epilogue=0, w_hat=P[2], bias=None, k=2, p=5, q=128))
+    for chain, n in ((head, 3), (net, 4)):
+        for b in (1, 2, 64):
+            need = L.circ_chain_workspace_bytes(chain, n, b)
+            assert need > 0
+            assert L.circ_chain_forward(chain, n, P[0], P[1], b, P[5], ws, None) == 0
+            assert L.circ_chain_forward(chain, n, P[0], P[1], b, P[5], c_size(need - 1), None) == -3
+    net[2].q = 97
+    assert L.circ_chain_workspace_bytes(net, 4, 1) == 0 and L.circ_chain_forward(net, 4, P[0], P[1], 1, P[5], ws, None) == -1
+    assert L.circ_chain_forward(head, 0, P[0], P[1], 1, P[5], ws, None) == -1
+    head[1].kind = 7
+    assert L.circ_chain_forward(head, 3, P[0], P[1], 1, P[5], ws, None) == -1
     # random shapes, valid or not: only the absence of a trap counts
     rng = random.Random(1708)
     ks = [1, 2, 3, 4, 5, 6, 7, 8, 12, 16, 24, 32, 48, 64, 96, 100, 128, 192, 256, 384, 500, 511, 512, 0, -1, 513, 1024]

@@ -449,6 +449,57 @@ def test_sgd_step_closed_form_and_descent():
     assert abs((loss(O.fc_sgd_step(w, x, dy, lr)) - loss(w)) / (-lr * float((g * g).sum())) - 1.0) < 1e-3
 
 
+# ---- max-pooling (Sec. 2.1) and a cascade of layers ------------------------------------------
+def test_maxpool_hand_example_and_library():
+    x = np.array([[1., 5., 2., 0.], [3., 4., 9., 1.], [7., 0., 6., 8.], [2., 2., 3., 3.]]).reshape(1, 1, 4, 4)
+    np.testing.assert_array_equal(O.maxpool_forward(x, 2, 2)[0, 0], [[5., 9.], [7., 8.]])           # by hand
+    np.testing.assert_array_equal(O.maxpool_forward(x, 3, 1)[0, 0], [[9., 9.], [9., 9.]])
+    np.testing.assert_array_equal(O.maxpool_forward(x, 2, 1)[0, 0], [[5., 9., 9.], [7., 9., 9.], [7., 6., 8.]])
+    for (N, C, H, W, win, st) in [(2, 3, 7, 9, 2, 2), (1, 4, 8, 8, 3, 2), (3, 1, 5, 6, 3, 3), (2, 2, 6, 6, 1, 1), (1, 2, 13, 13, 3, 2)]:
+        a = RNG.standard_normal((N, C, H, W))
+        ref = torch.nn.functional.max_pool2d(torch.from_numpy(a), win, st).numpy()
+        np.testing.assert_array_equal(O.maxpool_forward(a, win, st), ref)
+
+
+def test_chain_vs_library_layers():
+    """conv -> ReLU -> pool -> conv -> pool -> fc -> ReLU -> fc against torch's float64 conv2d / max_pool2d /
+    linear on dense weights gathered entry by entry from the block vectors."""
+    B = 3
+    w1 = RNG.standard_normal((3, 3, 4, 2, 4)) * 0.3; b1 = RNG.standard_normal(16)      # 8 -> 16 channels, k = 4
+    w2 = RNG.standard_normal((3, 3, 2, 2, 8)) * 0.2                                    # 16 -> 16 channels, k = 8
+    w3 = RNG.standard_normal((4, 9, 16)) * 0.1; b3 = RNG.standard_normal(64)           # 16*3*3 = 144 -> 64, k = 16
+    w4 = RNG.standard_normal((5, 32, 2)) * 0.2; b4 = RNG.standard_normal(10)           # 64 -> 10, k = 2
+    x = RNG.standard_normal((B, 8, 12, 12))
+    layers = [dict(kind="conv", w=w1, bias=b1, relu=True, pad=1), dict(kind="pool", window=2, stride=2),
+              dict(kind="conv", w=w2, pad=1), dict(kind="pool", window=2, stride=2),
+              dict(kind="fc", w=w3, bias=b3, relu=True), dict(kind="fc", w=w4, bias=b4)]
+    got = O.chain_forward(layers, x)
+
+    def dense_fc(w):
+        p, q, k = w.shape
+        W = torch.zeros(p * k, q * k, dtype=torch.float64)
+        for i in range(p):
+            for j in range(q):
+                for a in range(k):
+                    for b in range(k):
+                        W[i * k + a, j * k + b] = w[i, j, (a - b) % k]
+        return W
+    F = torch.nn.functional
+    t = torch.from_numpy(x)
+    t = F.max_pool2d(torch.relu(F.conv2d(t, torch.from_numpy(_dense_filter_bank(w1)), torch.from_numpy(b1), padding=1)), 2, 2)
+    t = F.max_pool2d(F.conv2d(t, torch.from_numpy(_dense_filter_bank(w2)), None, padding=1), 2, 2)
+    t = torch.relu(F.linear(t.reshape(B, -1), dense_fc(w3), torch.from_numpy(b3)))
+    t = F.linear(t, dense_fc(w4), torch.from_numpy(b4))
+    assert got.shape == (B, 10)
+    np.testing.assert_allclose(got, t.numpy(), atol=1e-11)
+    # an FC layer followed by an image layer: the vector is viewed as (C, H, W)
+    w5 = RNG.standard_normal((9, 2, 8)) * 0.2                                          # 16 -> 72 = 2 x 6 x 6
+    xs = RNG.standard_normal((2, 16))
+    got2 = O.chain_forward([dict(kind="fc", w=w5), dict(kind="pool", window=3, stride=3, shape=(2, 6, 6))], xs)
+    ref2 = F.max_pool2d(F.linear(torch.from_numpy(xs), dense_fc(w5)).reshape(2, 2, 6, 6), 3, 3)
+    np.testing.assert_allclose(got2, ref2.numpy(), atol=1e-12)
+
+
 def test_error_measure():
     ref = np.array([1.0, -4.0, 0.0]); got = np.array([1.0, -4.0, 0.002])
     assert abs(O.max_norm_rel_err(got, ref) - 0.0005) < 1e-15
