@@ -294,87 +294,6 @@ __device__ __forceinline__ void fft_column_lanes(float2* z, int stride, int tid,
   }
 }
 
-// ---- a whole transform on L lanes x R registers: no LDS, no barrier -------------------------
-// K = L * R points of one column: lane m (of L = 8 or 16 consecutive lanes) holds the R values
-// x[R*m + r].  With f = f' + L*s,
-//   X[f' + L*s] = sum_r W_R^(r*s) * ( W_K^(r*f') * A_r[f'] ),   A_r[f'] = sum_m x[R*m + r] W_L^(m*f'),
-// so the L-point transforms over m run on the lanes (DPP network above, once per register r),
-// the twiddles W_K^(r*f') are per-lane constants, and the R-point transforms over r run in
-// registers.  The radix-2 recursion of Sec. 4.1 is cut between the lane network and the
-// registers instead of between two LDS passes.  The inverse takes X[m + L*s] on lane m
-// (register s) and mirrors the steps: R-point inverse transforms in registers, twiddles
-// W_K^(-r*m), L-point inverse transforms over the lanes.
-// Lane index conventions (rev = lane_rev<L>): forward  in: lane m, reg r = x[R*m + r];
-//                                                       out: lane m, reg s = X[rev(m) + L*s]
-//                                             inverse  in: lane m, reg s = X[m + L*s];
-//                                                       out: lane m, reg r = K * x[R*rev(m) + r]
-constexpr int lane_fft_lanes(int K) { return K >= 128 ? 16 : 8; }
-
-template <int K>
-struct LaneFft {
-  static constexpr int L = lane_fft_lanes(K), R = K / L;
-  static_assert(K % L == 0 && R >= 2 && R <= 16, "block sizes 16..256");
-
-  // Twiddles of the forward transform for lane m straight from the table in the code object
-  // (issued at kernel start, their latency overlaps the first data loads): tw[r] = (cos, sin)
-  // of 2 pi r rev(m) / K, and for L = 16 the first-stage twiddle of the lane network.
-  struct Fwd {
-    float2 tw[R];
-    float2 w16;
-  };
-  static __device__ __forceinline__ Fwd load_forward_twiddles(int m) {
-    Fwd t;
-    const int fp = lane_rev<L>(m);
-    const float2* tab = reinterpret_cast<const float2*>(kTw.cs);
-#pragma unroll
-    for (int r = 1; r < R; ++r) t.tw[r] = tab[((r * fp) % K) * (kTwN / K)];
-    t.tw[0] = make_float2(1.f, 0.f);
-    t.w16 = tab[(m & 7) * (kTwN / 16)];
-    return t;
-  }
-
-  static __device__ __forceinline__ void forward(float (&re)[R], float (&im)[R], int m, const Fwd& t) {
-    if constexpr (L == 8) {
-      const Fft8Lanes<false> F(m);
-#pragma unroll
-      for (int r = 0; r < R; ++r) F.run(re[r], im[r]);
-    } else {
-      const Fft16Lanes<false> F(m, t.w16);
-#pragma unroll
-      for (int r = 0; r < R; ++r) F.run(re[r], im[r]);
-    }
-#pragma unroll
-    for (int r = 1; r < R; ++r) {                  // times W_K^(r f') = cos - i sin
-      const float c = t.tw[r].x, s = t.tw[r].y;
-      const float xr = c * re[r] + s * im[r];
-      im[r] = c * im[r] - s * re[r];
-      re[r] = xr;
-    }
-    FftReg<R, false>::run(re, im);
-  }
-
-  // twl: LDS copy of the K roots (stage_twiddles<K>)
-  static __device__ __forceinline__ void inverse(float (&re)[R], float (&im)[R], int m, const float2* twl) {
-    FftReg<R, true>::run(re, im);
-#pragma unroll
-    for (int r = 1; r < R; ++r) {                  // times W_K^(-r m) = cos + i sin
-      const float2 w = twl[r * m];
-      const float xr = w.x * re[r] - w.y * im[r];
-      im[r] = w.x * im[r] + w.y * re[r];
-      re[r] = xr;
-    }
-    if constexpr (L == 8) {
-      const Fft8Lanes<true> F(m);
-#pragma unroll
-      for (int r = 0; r < R; ++r) F.run(re[r], im[r]);
-    } else {
-      const Fft16Lanes<true> F(m, twl[(m & 7) * (K / 16)]);
-#pragma unroll
-      for (int r = 0; r < R; ++r) F.run(re[r], im[r]);
-    }
-  }
-};
-
 // ---- addressing of "rows" (the length-K vectors that are transformed) ----------------
 // Row ids enumerate the rows in the order of the spectrum buffer:
 // spectrum[f][rid].  A row id decomposes as rid = (a*n1 + b)*n0 + c and the first
