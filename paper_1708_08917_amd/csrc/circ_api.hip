@@ -26,8 +26,19 @@ constexpr int kMinK = 1, kMaxK = 512;
 
 inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 inline bool valid_k(int k) { return k >= kMinK && k <= kMaxK; }
-// Block sizes served by the radix-2 kernels; every other size takes the direct transforms.
+// Block sizes served by the radix-2 kernels.
 inline bool radix2_k(int k) { return is_pow2(k) && k >= 2; }
+// Block sizes 3 * 2^a, 5 * 2^a and 25 * 2^a (multiples of 4): the same kernels with mixed-radix
+// sub-transforms in registers (96 and 384 are the channel counts of AlexNet-style CONV layers).
+// Every other size takes the transforms by their definition.
+inline bool mixed_k(int k) {
+  switch (k) {
+    case 12: case 24: case 48: case 96: case 192: case 384:
+    case 20: case 40: case 80: case 160: case 320:
+    case 100: case 200: case 400: return true;
+    default: return false;
+  }
+}
 // Block sizes served by the batch <= 2 streaming kernel.
 inline bool gemv_k(int k) { return is_pow2(k) && k >= 4; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -120,14 +131,19 @@ FftPlan plan_fft(int K, long long nrows) {
   long long pairs = cdiv(nrows, 2);
   while (P > 8 && cdiv(pairs, P) < 512) P >>= 1;
   int TT = R2;
-  if (P * TT > 256) TT = 256 / P;
+  if (is_pow2(K)) {
+    if (P * TT > 256) TT = 256 / P;
+  } else {
+    // a divisor of the R2 sub-transforms of the first pass, so that no round of it is half empty
+    while (P * TT > 512 || R2 % TT != 0) --TT;
+  }
   if (TT < 1) TT = 1;
   int NT = P * TT;
   if (NT < 64) NT = 64;
   // a launch that leaves CUs idle is bound by the latency of its loads and stores, which all
   // threads share (the butterflies occupy R2 threads per column, the others skip them)
   if (cdiv(pairs, P) <= 256 && NT < 256) NT = 256;
-  if (NT < K / 4) NT = K / 4;   // the row loaders keep one float4 column per thread
+  if (is_pow2(K) && NT < K / 4) NT = K / 4;   // the row loaders keep one float4 column per thread
   return FftPlan{P, NT, fft_tile_lds_bytes(K, P)};
 }
 
@@ -174,10 +190,31 @@ hipError_t launch_irfft_k(bool rows_fast, const float2* in, float* out, const Ro
     case 512: return CALL(512);                     \
     default: return hipErrorInvalidValue;           \
   }
+#define CIRC_DISPATCH_MIXED_K(k, CALL)              \
+  switch (k) {                                      \
+    case 12: return CALL(12);                       \
+    case 24: return CALL(24);                       \
+    case 48: return CALL(48);                       \
+    case 96: return CALL(96);                       \
+    case 192: return CALL(192);                     \
+    case 384: return CALL(384);                     \
+    case 20: return CALL(20);                       \
+    case 40: return CALL(40);                       \
+    case 80: return CALL(80);                       \
+    case 160: return CALL(160);                     \
+    case 320: return CALL(320);                     \
+    case 100: return CALL(100);                     \
+    case 200: return CALL(200);                     \
+    case 400: return CALL(400);                     \
+    default: break;                                 \
+  }
 
 hipError_t launch_rfft(int k, bool rows_fast, const float* in, float2* out, const RowMap& map, long long nrows,
                        long long out_fstride, int n_grids, long long in_gstride, long long out_gstride,
                        float scale, int conj, hipStream_t s) {
+#define CALL(KK) launch_rfft_k<KK>(rows_fast, in, out, map, nrows, out_fstride, n_grids, in_gstride, out_gstride, scale, conj, s)
+  CIRC_DISPATCH_MIXED_K(k, CALL)
+#undef CALL
   if (!radix2_k(k)) {
     if (const int k1 = dft_factor(k); k1 > 1) {   // composite: two factors
       const int R = dft2_rows_per_block(k, nrows);
@@ -200,6 +237,9 @@ hipError_t launch_rfft(int k, bool rows_fast, const float* in, float2* out, cons
 hipError_t launch_irfft(int k, bool rows_fast, const float2* in, float* out, const RowMap& map, long long nrows,
                         long long in_fstride, float scale, const float* bias, long long bias_div, int relu,
                         hipStream_t s, int nparts = 1, long long part_stride = 0) {
+#define CALL(KK) launch_irfft_k<KK>(rows_fast, in, out, map, nrows, in_fstride, scale, bias, bias_div, relu, nparts, part_stride, s)
+  CIRC_DISPATCH_MIXED_K(k, CALL)
+#undef CALL
   if (!radix2_k(k)) {
     if (const int k1 = dft_factor(k); k1 > 1) {
       const int R = dft2_rows_per_block(k, nrows);

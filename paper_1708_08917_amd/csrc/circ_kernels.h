@@ -146,7 +146,7 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
         lds_put(L.z, n * PP + (row >> 1), row & 1, v);
       }
     }
-  } else if constexpr (K >= 4) {
+  } else if constexpr (K >= 4 && is_pow2_c(K)) {
     // rows are contiguous (element stride 1) and 16-byte aligned: vector loads along the row.
     // One wave-load covers 64/GW rows x GW*16 contiguous bytes.  A step of one float4 along the
     // row is 8*PP words in the tile, a multiple of 8 (PP is odd), so with all 64 lanes along one
@@ -172,6 +172,25 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
         zd[4 * PP] = v.z;
         zd[6 * PP] = v.w;
       }
+    }
+  } else if constexpr (K % 4 == 0) {
+    // the same for block sizes that are not powers of two: one float4 per thread and step,
+    // consecutive threads along the row
+    constexpr int Q4 = K / 4;
+    for (int idx = tid; idx < 2 * P * Q4; idx += NT) {
+      const int row = idx / Q4, n = 4 * (idx - row * Q4);
+      const long long b = L.rbase[row];
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if constexpr (HMODE & kHalfRows) {
+        if (b >= 0) v = load_half4<(HMODE & kHalfBf16) != 0>(reinterpret_cast<const unsigned short*>(in) + b + n);
+      } else {
+        if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n);
+      }
+      float* zd = reinterpret_cast<float*>(L.z) + row + 2 * n * PP;
+      zd[0] = v.x;
+      zd[2 * PP] = v.y;
+      zd[4 * PP] = v.z;
+      zd[6 * PP] = v.w;
     }
   } else {
     for (int idx = tid; idx < 2 * P * K; idx += NT) {
@@ -209,7 +228,7 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
     if (whole) {
 #pragma unroll 4
       for (int f = tid >> lgP; f < NF; f += fstep, o += ostep) {
-        float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>((K - f) & (K - 1)) * PP + pr];
+        float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>(f == 0 ? 0 : K - f) * PP + pr];
         const float2 v0 = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
         const float2 v1 = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
         if constexpr (HMODE & kHalfSpectra) {
@@ -223,7 +242,7 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
     }
 #pragma unroll 2
     for (int f = tid >> lgP; f < NF; f += fstep, o += ostep) {
-      float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>((K - f) & (K - 1)) * PP + pr];
+      float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>(f == 0 ? 0 : K - f) * PP + pr];
       const float2 v0 = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
       const float2 v1 = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
       if constexpr (HMODE & kHalfSpectra) {
@@ -352,7 +371,7 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
   fft_lds_pass2_inplace<K, true>(L.z, PP, col, t, TT);
   __syncthreads();
 
-  if constexpr (!ROWS_FAST && K >= 4) {
+  if constexpr (!ROWS_FAST && K >= 4 && is_pow2_c(K)) {
     // contiguous rows: float4 stores; a thread keeps its position n in the row, its row index
     // advances by NT/(K/4) per step (NT is a multiple of K/4)
     const int n = 4 * (tid % (K / 4)), rstep = NT / (K / 4);
@@ -366,6 +385,25 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
       if (b < 0) continue;
       const int c = 2 * (row >> 1) + (row & 1);
       float4 v = make_float4(z0[c] * scale, z1[c] * scale, z2[c] * scale, z3[c] * scale);
+      if (bias) {
+        const float4 bb = *reinterpret_cast<const float4*>(bias + (long long)L.rblk[row] * K + n);
+        v.x += bb.x; v.y += bb.y; v.z += bb.z; v.w += bb.w;
+      }
+      if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+      if constexpr (HMODE & kHalfRows) store_half4<(HMODE & kHalfBf16) != 0>(reinterpret_cast<unsigned short*>(out) + b + n, v);
+      else *reinterpret_cast<float4*>(out + b + n) = v;
+    }
+  } else if constexpr (!ROWS_FAST && K % 4 == 0) {
+    // the same for block sizes that are not powers of two
+    constexpr int Q4 = K / 4;
+#pragma unroll 2
+    for (int idx = tid; idx < 2 * P * Q4; idx += NT) {
+      const int row = idx / Q4, n = 4 * (idx - row * Q4);
+      const long long b = L.rbase[row];
+      if (b < 0) continue;
+      const float* zc = reinterpret_cast<const float*>(L.z) + row;
+      float4 v = make_float4(zc[2 * fft_pos<K>(n + 0) * PP] * scale, zc[2 * fft_pos<K>(n + 1) * PP] * scale,
+                             zc[2 * fft_pos<K>(n + 2) * PP] * scale, zc[2 * fft_pos<K>(n + 3) * PP] * scale);
       if (bias) {
         const float4 bb = *reinterpret_cast<const float4*>(bias + (long long)L.rblk[row] * K + n);
         v.x += bb.x; v.y += bb.y; v.z += bb.z; v.w += bb.w;

@@ -64,4 +64,17 @@ struct alignas(16) TwiddleTable {
   }
 };
 
+// The K roots of unity (cos, sin)(2 pi m / K) of a block size that does not divide 512.
+template <int K>
+struct alignas(8) RootsTable {
+  float cs[2 * K];
+  constexpr RootsTable() : cs() {
+    for (int m = 0; m < K; ++m) {
+      cpair v = cos_sin_frac(m, K);
+      cs[2 * m] = float(v.c);
+      cs[2 * m + 1] = float(v.s);
+    }
+  }
+};
+
 }  // namespace circ

@@ -589,9 +589,12 @@ def test_conv_strided_and_even_filters(N, p, q, k, H, W, r, pad, stride):
 
 
 # ---- block sizes that are not powers of two (direct transforms around the same contraction) ----
-@pytest.mark.parametrize("k", [1, 3, 5, 6, 7, 9, 12, 15, 24, 40, 96, 100, 125, 225, 250, 384, 509, 511])
+@pytest.mark.parametrize("k", [1, 3, 5, 6, 7, 9, 12, 15, 20, 24, 40, 48, 80, 96, 100, 125, 160, 192, 200, 225, 250, 320,
+                               384, 400, 509, 511])
 @pytest.mark.parametrize("batch", [1, 2, 33])
 def test_fc_general_block_sizes(k, batch):
+    """Sizes 3 * 2^a, 5 * 2^a and 25 * 2^a (multiples of 4) run the mixed-radix transforms, the rest
+    the transforms by their definition."""
     p, q = (3, 5) if k < 200 else (2, 3)
     w, x, b = rand_fc(p, q, k, batch)
     what = f"{p}x{q} k={k} B={batch}"
@@ -623,7 +626,8 @@ def test_fc_general_block_sizes_larger(p, q, k, batch):
 
 @pytest.mark.parametrize("N,p,q,k,H,W,r,pad", [(2, 2, 3, 3, 6, 7, 3, 1), (3, 1, 2, 6, 5, 5, 3, 0), (2, 3, 2, 24, 9, 4, 1, 0),
                                                (2, 4, 4, 96, 13, 13, 3, 1), (2, 2, 2, 192, 13, 13, 3, 1),
-                                               (3, 2, 2, 1, 8, 8, 5, 2), (33, 2, 3, 12, 14, 14, 3, 1)])
+                                               (3, 2, 2, 1, 8, 8, 5, 2), (33, 2, 3, 12, 14, 14, 3, 1),
+                                               (5, 2, 1, 80, 7, 9, 3, 1), (3, 1, 2, 100, 6, 6, 3, 1)])
 def test_conv_general_block_sizes(N, p, q, k, H, W, r, pad):
     """Includes the 384-channel 13 x 13 layers of an AlexNet-style network as 4 x 4 blocks of 96
     and 2 x 2 blocks of 192."""
