@@ -1,7 +1,8 @@
-// Transforms for block sizes that are not powers of two.
+// Transforms for block sizes without a fast transform.
 //
 // Sec. 3.1 only asks that the block size k divide the layer dimensions (the example of Fig. 1
-// has k = 3); the radix-2 recursion of Sec. 4.1 covers powers of two.  Every other k takes the
+// has k = 3); the radix-2 recursion of Sec. 4.1 covers powers of two, and its mixed-radix form
+// (FftReg) the sizes 3 * 2^a, 5 * 2^a and 25 * 2^a.  Every other k takes the
 // transform by its definition, X[f] = sum_t x[t] e^{-2 pi i f t / k}: O(k^2) per row instead of
 // O(k log k), on the plain vector units, with the k roots of unity tabulated in LDS.  The
 // contraction between the two transforms does not depend on how they are computed.

@@ -212,7 +212,7 @@ def main():
         bench_chain([dataclasses.replace(synth.CFG3_L1, batch=1), dataclasses.replace(synth.CFG3_L2, batch=1),
                      synth.FcConfig("head_fc4096x1000_k8_b1", 4096, 1000, 8, 1, bias=True, relu=False, index=7)], a.reps)
     if sel("general"):
-        # block sizes that are not powers of two (direct transforms): an FC layer with blocks of 100
+        # block sizes that are not powers of two (mixed-radix transforms): an FC layer with blocks of 100
         # and the 384-channel 13 x 13 CONV layer of an AlexNet-style network as 4 x 4 blocks of 96
         bench_fc(synth.FcConfig("fc4000_k100_b64", 4000, 4000, 100, 64, bias=True, relu=True, index=5), a.reps,
                  backward=a.backward)
