@@ -176,6 +176,17 @@ __device__ __forceinline__ float quad_swap_pairs(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, false));
 }
 
+// W_R2^f = e^{-2 pi i f / R2}, f < R2/2, as (cos, -sin) on the odd lane of a pair and (1, 0) on the even one.
+template <int R2, int F = 1>
+__device__ __forceinline__ void pair_twiddles(float (&c)[R2 / 2], float (&s)[R2 / 2], int odd) {
+  if constexpr (F == 1) { c[0] = 1.f; s[0] = 0.f; }
+  if constexpr (F < R2 / 2) {
+    c[F] = odd ? tw_cos(F, R2) : 1.f;
+    s[F] = odd ? -tw_sin(F, R2) : 0.f;
+    pair_twiddles<R2, F + 1>(c, s, odd);
+  }
+}
+
 // ONE: all q input blocks fit one chunk, so the second (prefetch) set of weight operands is
 // never needed.  With 512 threads that variant is held to 128 registers per lane: two
 // workgroups then fit one CU (registers and LDS), and a launch on another stream can start on
@@ -304,7 +315,14 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
       for (int cc = 0; cc < CPW; ++cc)
         if (jh >= lo && jh < hi) a[cc][jh] = wc[(long long)jh * FG * 64 + aoff[cc]];
   };
-  constexpr int AH = JW / 2, AH1 = (AH + 1) / 2;
+  constexpr int AH = JW / 2;
+  // Where the weight operands of the next chunk are requested: in portions ahead of each batch of
+  // matrix instructions (the requests queue while the matrix cores work), or, k = 128, all of
+  // them behind the last matrix instruction.  Measured, warm, multi-chunk layers: k = 32 16.3 ->
+  // 12.8 us (q = 300), k = 64 65.8 -> 58.7 us (q = 200, batch 512), k = 256 26.7 -> 25.6 us with
+  // the first placement against half of the requests on either side of the barrier; k = 128
+  // (9216 -> 4096, batch 256) 14.6 -> 15.1 us with the first, 13.8 us with the second.
+  constexpr bool kWeightsLast = K == 128;
   // weight loads of the first chunk issued before x has arrived (see below); kernels that loop
   // over chunks keep a second set of operands in registers and issue all of the first set at once
   constexpr int AF0 = ONE ? (AH + 7) / 8 : AH;
@@ -316,6 +334,14 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
   float2 ftw[R1];
 #pragma unroll
   for (int f1 = 1; f1 < R1; ++f1) ftw[f1] = reinterpret_cast<const float2*>(kTw.cs)[((f1 * fn2) % K) * (kTwN / K)];
+  // second pass shared by lane pairs (R2 = 2*R1, see below): which half this lane takes, the sign of
+  // its own value in the final butterfly, and its twiddles W_R2^f (1 on the even lane)
+  // (k = 128: 14.6 -> 14.0 us for 9216 -> 4096 at batch 256; k = 32, 4-point halves: slower, not used)
+  constexpr bool kPairPass2 = R2 == 2 * R1 && R2 >= 16;
+  const int p2h = fn2 & 1;
+  const float p2sgn = p2h ? -1.f : 1.f;
+  float p2c[kPairPass2 ? R2 / 2 : 1], p2s[kPairPass2 ? R2 / 2 : 1];
+  if constexpr (kPairPass2) pair_twiddles<R2>(p2c, p2s, p2h);
   float2 tw_stage[(K + NT - 1) / NT];
 #pragma unroll
   for (int s = 0; s < (K + NT - 1) / NT; ++s) {
@@ -412,7 +438,50 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
       __builtin_amdgcn_wave_barrier();
       CIRC_PROBE(2 + 4 * c);
       if (rd == 0) more_weights(2);
-      if (fwd_active && fn2 < R1) {                   // lane f1 = fn2: Z[f1 + R1*f2] = sum_n2 A[f1][n2] W_R2^(f2*n2)
+      if constexpr (kPairPass2) {
+        // R2 = 2*R1: with one lane per second-pass transform half of the column's lanes would idle.
+        // A pair of lanes shares one instead: lane hh of the pair runs the R2/2-point transform
+        // of the inputs n2 = 2m + hh, E_hh, the odd lane multiplies by W_R2^f', the two exchange
+        // their values, and lane hh ends with Z[f1 + R1*(f' + hh*R2/2)] = E_0[f'] +/- W_R2^f' E_1[f'].
+        if (fwd_active) {
+          constexpr int H = R2 / 2;
+          const int f1 = fn2 >> 1;
+          float re[H], im[H];
+#pragma unroll
+          for (int m = 0; m < H; ++m) {
+            const float2 v = xch[f1 * (R2 + 1) + 2 * m + p2h];
+            re[m] = v.x;
+            im[m] = v.y;
+          }
+          if (rd == 0) more_weights(3);
+          FftReg<H, false>::run(re, im);
+#pragma unroll
+          for (int f = 1; f < H; ++f) {
+            const float tr = p2c[f] * re[f] - p2s[f] * im[f];
+            im[f] = p2c[f] * im[f] + p2s[f] * re[f];
+            re[f] = tr;
+          }
+#pragma unroll
+          for (int f = 0; f < H; ++f) {
+            re[f] = fmaf(p2sgn, re[f], quad_swap_pairs(re[f]));
+            im[f] = fmaf(p2sgn, im[f], quad_swap_pairs(im[f]));
+          }
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+          __builtin_amdgcn_wave_barrier();            // every lane of the column has read its inputs
+#pragma unroll
+          for (int fp = 0; fp < H; ++fp) {
+            const int f = f1 + R1 * (fp + H * p2h);
+            int slot, h;
+            if (f == 0) { slot = 0; h = 0; }
+            else if (f == S) { slot = 0; h = 1; }
+            else if (f < S) { slot = f; h = 0; }
+            else { slot = K - f; h = 1; }
+            *reinterpret_cast<float2*>(creg + 4 * slot + 2 * h) = make_float2(re[fp], im[fp]);
+          }
+        } else if (rd == 0) {
+          more_weights(3);
+        }
+      } else if (fwd_active && fn2 < R1) {            // lane f1 = fn2: Z[f1 + R1*f2] = sum_n2 A[f1][n2] W_R2^(f2*n2)
         float re[R2], im[R2];
 #pragma unroll
         for (int n2 = 0; n2 < R2; ++n2) {
@@ -440,13 +509,12 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
     }
     more_weights(4);
     CIRC_PROBE(3 + 4 * c);
-    if constexpr (more) {
-      load_x(c + 1);
-      load_a(c + 1, a_pref, 0, AH1);
-    }
+    // The x of the next chunk goes out before the barrier: a CU takes load instructions at a bounded
+    // rate, and a wave that has to wait for the others anyway is the one place where queueing behind
+    // them costs nothing.  The next chunk's weights follow inside the contraction (below).
+    if constexpr (more) load_x(c + 1);
     __syncthreads();
     CIRC_PROBE(1 + 4 * c);
-    if constexpr (more) load_a(c + 1, a_pref, AH1, AH);
     // operand rows come from LDS one batch ahead of the matrix instructions that use them
     const float* opw = op + (js * JW * NP) * OPROW + lane;
     float bvv[2][JB][NP][NFW];
@@ -466,6 +534,12 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
     for (int jb = 0; jb < JW; jb += JB) {
       const int cur = (jb / JB) & 1;
       if (jb + JB < JW) fetch_b(jb + JB, bvv[cur ^ 1]);
+      if constexpr (more && !kWeightsLast) {   // one portion ahead of each batch of matrix instructions
+        constexpr int NB = JW / JB;
+        __builtin_amdgcn_sched_barrier(0);
+        load_a(c + 1, a_pref, (jb / JB) * AH / NB, (jb / JB + 1) * AH / NB);
+        __builtin_amdgcn_sched_barrier(0);
+      }
 #pragma unroll
       for (int jj = 0; jj < JB; ++jj)
 #pragma unroll
@@ -486,6 +560,11 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
             P[jj % NCH][cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(ar, bval, P[jj % NCH][cc][u], 0, 0, 0);
             Q[jj % NCH][cc][u] = __builtin_amdgcn_mfma_f32_4x4x1f32(ai, bval, Q[jj % NCH][cc][u], 0, 0, 0);
           }
+    }
+    if constexpr (more && kWeightsLast) {
+      __builtin_amdgcn_sched_barrier(0);
+      load_a(c + 1, a_pref, 0, AH);
+      __builtin_amdgcn_sched_barrier(0);
     }
     CIRC_PROBE(4 + 4 * c);
   };
