@@ -897,6 +897,33 @@ def test_chain_forward(name, spec, batch):
     assert torch.equal(a.reshape(y.shape), y)
 
 
+@pytest.mark.parametrize("name,spec,batch", [("head 9216-4096-4096-1000", HEAD, 1), ("conv-pool-fc-fc", CONVNET, 1)])
+def test_chain_recorded_in_a_graph_matches_eager(name, spec, batch):
+    """A whole network for one input recorded into a HIP graph (the single-image serving loop):
+    every replay, with eager work on the same buffers in between, reproduces the eager call bit for bit."""
+    rng = np.random.default_rng(77)
+    olayers, dlayers, keep, x = _chain_inputs(rng, spec, batch)
+    ref = O.chain_forward(olayers, x)
+    xd = G.dev(x)
+    eager = torch.empty(ref.shape, dtype=torch.float32, device=G.DEV)
+    B.circ_chain_forward(dlayers, xd, eager)
+    torch.cuda.synchronize()
+    check(eager.cpu().numpy(), ref, f"chain {name} eager")
+    ws = torch.empty(B.circ_chain_workspace_bytes(dlayers, batch), dtype=torch.uint8, device=G.DEV)
+    y = torch.zeros_like(eager)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        B.circ_chain_forward(dlayers, xd, y, workspace=ws)
+    for rep in range(3):
+        y.fill_(-1.0)
+        ws.fill_(0xFF)                         # the workspace carries nothing from one call to the next
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager), f"replay {rep} of {name} differs from the eager result"
+
+
 def ctypes_tensor(keep, ptr):
     """The tensor in `keep` that starts at device address `ptr` (None for a NULL pointer)."""
     if not ptr:
