@@ -26,7 +26,8 @@ DEV = "cuda:0"
 
 def _time(fn, reps, warm):
     """Microseconds per call: `reps` calls captured in one HIP graph (so that the host-side
-    cost of the Python binding is not in the figure), replayed once between two events."""
+    cost of the Python binding is not in the figure), replayed between two events; the median of
+    five such replays."""
     for _ in range(warm):
         fn()
     torch.cuda.synchronize()
@@ -38,12 +39,15 @@ def _time(fn, reps, warm):
                 fn()
         graph.replay()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        graph.replay()
-        e1.record(stream)
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / reps
+        ts = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            graph.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3 / reps)
+    return sorted(ts)[len(ts) // 2]
 
 
 def fc_work(cfg):
