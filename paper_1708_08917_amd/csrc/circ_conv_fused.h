@@ -45,7 +45,7 @@ inline size_t conv_fused_lds_bytes(int nrows, int ncoli) {
   using Sh = ConvFusedShape<K, NT>;
   size_t fwd = size_t(K) * Sh::PP * sizeof(float2) + size_t(nrows) * Sh::OPROW * sizeof(float);
   size_t inv = size_t(K) * (ncoli + 1) * sizeof(float2);   // overlays the forward tile and the operand rows
-  return size_t(K) * sizeof(float2) + 64 * sizeof(int) + (fwd > inv ? fwd : inv);
+  return size_t(K) * sizeof(float2) + (fwd > inv ? fwd : inv);
 }
 
 // Weight spectra in the operand order of the fused CONV kernel:
@@ -95,8 +95,7 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
   static_assert(Q % QH == 0, "rounds must cover the input channel blocks evenly");
   extern __shared__ float smem[];
   float2* twl = reinterpret_cast<float2*>(smem);
-  int* outtab = reinterpret_cast<int*>(twl + K);    // output position -> its first input position, or -1
-  float2* z = reinterpret_cast<float2*>(outtab + 64);
+  float2* z = twl + K;
   float* op = reinterpret_cast<float*>(z + K * PP);
   float2* zi = z;                                   // inverse tile, reuses the forward tile and the operand rows
 
@@ -196,10 +195,17 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
       }
     }
   };
-  // the first chunk's loads go out before anything else needs memory
+  // Memory returns loads in issue order: the K roots (from the table in the code object, cached) are
+  // requested first, so that writing them to LDS does not wait for the first chunk of x behind them.
+  float2 tw_stage[(K + NT - 1) / NT];
+#pragma unroll
+  for (int s = 0; s < (K + NT - 1) / NT; ++s)
+    tw_stage[s] = reinterpret_cast<const float2*>(kTw.cs)[min(s * NT + tid, K - 1) * (kTwN / K)];
   float4 xa[NLD];
   load_chunk(0, xa);
-  stage_twiddles<K>(twl, tid, NT);
+#pragma unroll
+  for (int s = 0; s < (K + NT - 1) / NT; ++s)
+    if (s * NT + tid < K) twl[s * NT + tid] = tw_stage[s];
 
   // weight operands of this wave's (slot group, row group), one round (R*R*QH values) at a time
   const int combo = wave % ncombo, fg = combo % FG, ig = combo / FG;
@@ -220,25 +226,32 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
     P[tk] = floatx4{0.f, 0.f, 0.f, 0.f};
     Qa[tk] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
-  // output position -> its first input position (top-left tap), or -1 past the tile
-  for (int pos = tid; pos < 64; pos += NT) outtab[pos] = pos < NPOS ? (pos / TW) * IWP + pos % TW : -1;
-  __syncthreads();   // the tables are ready
-  // first input position of each of this wave's output positions (wave-uniform); positions past
-  // the end of the tile use row 0 (their results are never stored); ntk = positions that count
+  // first input position (top-left tap) of each of this wave's output positions, wave-uniform:
+  // row*IWP + column of the output position, stepped from one position to the next without a
+  // division; positions past the end of the tile use row 0 (their results are never stored);
+  // ntk = positions that count
   static_assert(MAXT % 2 == 0, "positions are taken in pairs");
   int ipos[MAXT];
   int ntk = 0;
+  {
+    int prow = 0, pcol = pos_first;                   // pos_first < pos_step <= 8
+    while (pcol >= TW) { pcol -= TW; ++prow; }
 #pragma unroll
-  for (int tk = 0; tk < MAXT; ++tk) {
-    const int v = __builtin_amdgcn_readfirstlane(outtab[pos_first + tk * pos_step]);
-    ipos[tk] = v >= 0 ? v : 0;
-    ntk += v >= 0 ? 1 : 0;
+    for (int tk = 0; tk < MAXT; ++tk) {
+      const bool in = pos_first + tk * pos_step < NPOS;
+      ipos[tk] = __builtin_amdgcn_readfirstlane(in ? prow * IWP + pcol : 0);
+      ntk += in ? 1 : 0;
+      pcol += pos_step;
+      while (pcol >= TW) { pcol -= TW; ++prow; }
+    }
   }
+  CIRC_PROBE(2);
 
   const int nch_total = Q * cpj, nch_round = QH * cpj;
 
   // one chunk: registers -> z tile -> two FFT passes -> operand rows
   auto fft_chunk = [&](int ch, float4 (&xr)[NLD], float4 (&xnext)[NLD]) {
+    CIRC_PROBE(9 + 4 * ch);
     store_chunk(xr);
     __syncthreads();
     CIRC_PROBE(10 + 4 * ch);
@@ -266,7 +279,7 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
   for (int round = 0; round < Q / QH; ++round) {
     load_a(round);
     for (int cl = 0; cl < nch_round; ++cl) fft_chunk(round * nch_round + cl, xa, xa);
-    CIRC_PROBE(1 + 3 * round);
+    CIRC_PROBE(44 + 3 * round);
     // ---- contraction of this round: every wave takes up to MAXT output positions for its combo,
     // two at a time (independent accumulators back to back).  Rows of positions outside the
     // image hold the spectrum of zeros, so the taps need no border test.  Row indices are
@@ -298,9 +311,9 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
         }
       }
     }
-    CIRC_PROBE(2 + 3 * round);
+    CIRC_PROBE(45 + 3 * round);
     __syncthreads();   // every wave is done with the operand rows of this round
-    CIRC_PROBE(3 + 3 * round);
+    CIRC_PROBE(46 + 3 * round);
   }
   // ---- spectra of the output pairs -> inverse tile (reuses the operand buffer),
   // column = i*NPOS + position, padded to CP (a power of two) columns for the thread mapping
@@ -314,6 +327,15 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
     const float ca = (slot == 0 && n >= 2) ? 0.f : 1.f;
     const float cb = (slot == 0 && n >= 2) ? 1.f : 0.f;
     const float cs = slot == 0 ? 0.f : ((n == 0 || n == 3) ? -1.f : 1.f);
+    // rows of output blocks that do not exist (the last group of a p that is no multiple of 4) go to
+    // the spare column of the tile, so that no store needs a test of its own
+    int rowoff[4], posmul[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const bool have = 4 * ig + m < p;
+      rowoff[m] = __builtin_amdgcn_readfirstlane(have ? 2 * (4 * ig + m) * NPOS : 2 * NCOLI);
+      posmul[m] = __builtin_amdgcn_readfirstlane(have ? 2 : 0);
+    }
 #pragma unroll
     for (int tk = 0; tk < MAXT; ++tk) {
       const int pos = pos_first + tk * pos_step;
@@ -322,35 +344,40 @@ __global__ __launch_bounds__(NT, 2) void conv_fused_kernel(const float2* __restr
         for (int m = 0; m < 4; ++m) {
           const float pv = P[tk][m], qv = Qa[tk][m];
           const float qs = quad_swap_pairs(qv);
-          const int i = 4 * ig + m;
-          if (i < p) zl[2 * (i * NPOS + pos)] = fmaf(cs, qs, fmaf(cb, qv, ca * pv));
+          zl[rowoff[m] + posmul[m] * pos] = fmaf(cs, qs, fmaf(cb, qv, ca * pv));
         }
       }
     }
   }
+  CIRC_PROBE(57);
   __syncthreads();
   CIRC_PROBE(58);
+  // Inverse transform of the NCOLI columns.  Several independent sub-transforms per thread and pass
+  // (the loops are unrolled) hide each other's LDS latency: cfg4 47.6 -> 45 us.  (Running the
+  // transform and the stores in two stages over halves of the output blocks, so that the stores of
+  // one half overlap the transform of the other, measured 0.8 us slower: two more barriers.)
   int lgcp = 6;
   while ((1 << lgcp) < NCOLI) ++lgcp;
   const int CP = 1 << lgcp;
+#pragma unroll 4
   for (int wk = tid; wk < CP * R2; wk += NT) {
     const int col = wk & (CP - 1);
     if (col < NCOLI) fft_lds_pass1<K, true>(zi, PPI, col, wk >> lgcp, R2, twl);
   }
   __syncthreads();
   CIRC_PROBE(59);
+#pragma unroll 4
   for (int wk = tid; wk < CP * R1; wk += NT) {
     const int col = wk & (CP - 1);
     if (col < NCOLI) fft_lds_pass2_inplace<K, true>(zi, PPI, col, wk >> lgcp, R1);
   }
   __syncthreads();
   CIRC_PROBE(60);
-
-  // ---- store: a task is one pair of neighbouring output positions of one output channel,
-  // for both images (two 8-byte stores); tile origins and row lengths are even (checked on the
-  // host), so a pair is aligned and entirely inside or outside the image.  A wave covers
-  // 64 / (pairs per channel) channels at a time; a lane keeps its pair for the whole loop.
   {
+    // ---- store: a task is one pair of neighbouring output positions of one output channel,
+    // for both images (two 8-byte stores); tile origins and row lengths are even (checked on the
+    // host), so a pair is aligned and entirely inside or outside the image.  A wave covers
+    // 64 / (pairs per channel) channels at a time; a lane keeps its pair for the whole loop.
     const int NPAIR = TW / 2, per_ch = TH * NPAIR;          // per_ch <= 32
     const int cpl = 64 / per_ch;                            // channels per wave iteration
     const int c_sub = lane / per_ch, rem = lane - c_sub * per_ch;
