@@ -355,8 +355,8 @@ void fc_fused_kernel(const float4* __restrict__ Wf, const float* __restrict__ x,
   // wave before it: the transforms start when the 32 KB of x have arrived, and the weights, which
   // are not needed before the contraction, stream in meanwhile.
   __builtin_amdgcn_s_barrier();
-  // The first half of the first chunk's weights goes out now, while x is on its way; the rest is
-  // issued between the passes of the first transform.  A CU takes load instructions at a
+  // When one chunk holds all input blocks, an eighth of its weights goes out now, while x is on its
+  // way, and the rest is issued between the passes of the first transform.  A CU takes load instructions at a
   // bounded rate (one 16-byte load of a wave per 16 cycles): with all of them ahead of the
   // transform, its first instruction would wait for the last load to be accepted.
   load_a(0, a_even, 0, AF0);
