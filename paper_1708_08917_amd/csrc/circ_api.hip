@@ -147,10 +147,34 @@ FftPlan plan_fft(int K, long long nrows) {
   return FftPlan{P, NT, fft_tile_lds_bytes(K, P)};
 }
 
+// Long runs of contiguous rows take the streaming form of the transform (rfft_stream_kernel: tiles of
+// 4096 / K column pairs, at most four workgroups per CU walking over them) once there is at least
+// one tile per CU; 65,536 rows of 256: 28.8 -> 23.7 us, 18,432 rows of 128: 7.4 -> 6.5 us.
+constexpr long long kStreamMinTiles = 256, kStreamMaxWorkgroups = 1024;
+template <int K>
+constexpr bool stream_k() { return is_pow2_c(K) && K >= 32 && K <= 256; }
+template <int K, int HMODE>
+bool launch_rfft_stream(const float* in, float2* out, const RowMap& map, long long nrows, long long out_fstride, float scale,
+                        int conj, hipStream_t s) {
+  if constexpr (stream_k<K>()) {
+    constexpr int P = 4096 / K;
+    const long long ntiles = cdiv(nrows, 2 * P);
+    if (ntiles < kStreamMinTiles || ntiles > (1ll << 31) - 1) return false;
+    const unsigned grid = unsigned(ntiles < kStreamMaxWorkgroups ? ntiles : kStreamMaxWorkgroups);
+    hipLaunchKernelGGL((rfft_stream_kernel<K, HMODE>), dim3(grid), dim3(256), fft_tile_lds_bytes(K, P), s, in, out, map, nrows,
+                       out_fstride, int(ntiles), scale, conj);
+    return true;
+  } else {
+    return false;
+  }
+}
+
 template <int K>
 hipError_t launch_rfft_k(bool rows_fast, const float* in, float2* out, const RowMap& map, long long nrows,
                          long long out_fstride, int n_grids, long long in_gstride, long long out_gstride,
                          float scale, int conj, hipStream_t s) {
+  if (!rows_fast && n_grids == 1 && launch_rfft_stream<K, 0>(in, out, map, nrows, out_fstride, scale, conj, s))
+    return hipGetLastError();
   FftPlan pl = plan_fft(K, nrows);
   dim3 grid((unsigned)cdiv(nrows, 2 * pl.P), (unsigned)n_grids);
   if (rows_fast)
@@ -1308,14 +1332,15 @@ hipError_t launch_rfft_half_k(int hmode, bool bf, const void* in, void* out, con
   const float* fin = static_cast<const float*>(in);
   float2* fout = static_cast<float2*>(out);
 #define CIRC_RFFT_H(MODE)                                                                                              \
+  if (!launch_rfft_stream<K, MODE>(fin, fout, map, nrows, out_fstride, scale, conj, s))                                \
   hipLaunchKernelGGL((rfft_kernel<K, false, MODE>), grid, dim3(pl.NT), pl.lds, s, fin, fout, map, nrows, out_fstride, 0ll, \
                      0ll, pl.P, scale, conj)
   if (hmode == kHalfSpectra) {
-    if (bf) CIRC_RFFT_H(kHalfSpectra | kHalfBf16);
-    else CIRC_RFFT_H(kHalfSpectra);
+    if (bf) { CIRC_RFFT_H(kHalfSpectra | kHalfBf16); }
+    else { CIRC_RFFT_H(kHalfSpectra); }
   } else {
-    if (bf) CIRC_RFFT_H(kHalfSpectra | kHalfRows | kHalfBf16);
-    else CIRC_RFFT_H(kHalfSpectra | kHalfRows);
+    if (bf) { CIRC_RFFT_H(kHalfSpectra | kHalfRows | kHalfBf16); }
+    else { CIRC_RFFT_H(kHalfSpectra | kHalfRows); }
   }
 #undef CIRC_RFFT_H
   return hipGetLastError();

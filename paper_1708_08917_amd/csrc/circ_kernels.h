@@ -84,6 +84,61 @@ __device__ __forceinline__ float lds_get(const float2* z, int idx, int half) {
   return reinterpret_cast<const float*>(z)[2 * idx + half];
 }
 
+// Separates the two real rows of each column of a transformed tile (z, P column pairs starting at
+// row id t0) and stores bins 0..K/2: out[f*out_fstride + rid], scaled, conjugated if `conj`.
+template <int K, int HMODE>
+__device__ __forceinline__ void rfft_store_tile(const float2* z, int P, int lgP, int tid, int NT, long long t0, long long nrows,
+                                                float2* __restrict__ out, long long out_fstride, float scale, int conj) {
+  const int PP = P + 1;
+  // separate the two real rows of each column and store bins 0..K/2
+  constexpr int NF = K / 2 + 1;
+  const float h = 0.5f * scale, hc = conj ? -h : h;
+  {
+    // a thread keeps its column pair; its bin advances by NT/P per step
+    const int pr = tid & (P - 1), fstep = NT >> lgP;
+    const long long rid = t0 + 2 * pr;
+    const bool ok0 = rid < nrows, ok1 = rid + 1 < nrows;
+    static_assert(HMODE == 0 || K >= 4, "half-width storage: K >= 4 only");
+    long long o = (long long)(tid >> lgP) * out_fstride + rid;
+    const long long ostep = (long long)fstep * out_fstride;
+    // whole tile inside the buffer and the pair (rid, rid + 1) aligned to its combined width:
+    // one store per bin, no predicates (the loop body is then branch-free and several bins'
+    // LDS reads are in flight at once)
+    constexpr int PAIRB = (HMODE & kHalfSpectra) ? 8 : 16;
+    const bool whole = t0 + 2 * P <= nrows && (out_fstride & 1) == 0 &&
+                       (reinterpret_cast<unsigned long long>(out) & (PAIRB - 1)) == 0;
+    if (whole) {
+#pragma unroll 4
+      for (int f = tid >> lgP; f < NF; f += fstep, o += ostep) {
+        float2 u = z[fft_pos<K>(f) * PP + pr], w = z[fft_pos<K>(f == 0 ? 0 : K - f) * PP + pr];
+        const float2 v0 = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
+        const float2 v1 = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
+        if constexpr (HMODE & kHalfSpectra) {
+          *reinterpret_cast<uint2*>(reinterpret_cast<unsigned*>(out) + o) =
+              make_uint2(pack_pair16<(HMODE & kHalfBf16) != 0>(v0.x, v0.y), pack_pair16<(HMODE & kHalfBf16) != 0>(v1.x, v1.y));
+        } else {
+          *reinterpret_cast<float4*>(out + o) = make_float4(v0.x, v0.y, v1.x, v1.y);
+        }
+      }
+      return;
+    }
+#pragma unroll 2
+    for (int f = tid >> lgP; f < NF; f += fstep, o += ostep) {
+      float2 u = z[fft_pos<K>(f) * PP + pr], w = z[fft_pos<K>(f == 0 ? 0 : K - f) * PP + pr];
+      const float2 v0 = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
+      const float2 v1 = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
+      if constexpr (HMODE & kHalfSpectra) {
+        unsigned* oh = reinterpret_cast<unsigned*>(out) + o;
+        if (ok0) oh[0] = pack_pair16<(HMODE & kHalfBf16) != 0>(v0.x, v0.y);
+        if (ok1) oh[1] = pack_pair16<(HMODE & kHalfBf16) != 0>(v1.x, v1.y);
+      } else {
+        if (ok0) out[o] = v0;
+        if (ok1) out[o + 1] = v1;
+      }
+    }
+  }
+}
+
 // -------------------------------------------------------------------------------------
 // Forward real FFT of rows.  Block b handles rows [2*P*b, 2*P*(b+1)); out[f*fstride + rid]
 // holds bin f (0..K/2) of row rid, scaled by `scale`, conjugated if `conj`.
@@ -208,52 +263,84 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
   fft_lds_pass2_inplace<K, false>(L.z, PP, col, t, TT);
   __syncthreads();
 
-  // separate the two real rows of each column and store bins 0..K/2
-  constexpr int NF = K / 2 + 1;
-  const float h = 0.5f * scale, hc = conj ? -h : h;
-  {
-    // a thread keeps its column pair; its bin advances by NT/P per step
-    const int pr = tid & (P - 1), fstep = NT >> lgP;
-    const long long rid = t0 + 2 * pr;
-    const bool ok0 = rid < nrows, ok1 = rid + 1 < nrows;
-    static_assert(HMODE == 0 || K >= 4, "half-width storage: K >= 4 only");
-    long long o = (long long)(tid >> lgP) * out_fstride + rid;
-    const long long ostep = (long long)fstep * out_fstride;
-    // whole tile inside the buffer and the pair (rid, rid + 1) aligned to its combined width:
-    // one store per bin, no predicates (the loop body is then branch-free and several bins'
-    // LDS reads are in flight at once)
-    constexpr int PAIRB = (HMODE & kHalfSpectra) ? 8 : 16;
-    const bool whole = t0 + 2 * P <= nrows && (out_fstride & 1) == 0 &&
-                       (reinterpret_cast<unsigned long long>(out) & (PAIRB - 1)) == 0;
-    if (whole) {
-#pragma unroll 4
-      for (int f = tid >> lgP; f < NF; f += fstep, o += ostep) {
-        float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>(f == 0 ? 0 : K - f) * PP + pr];
-        const float2 v0 = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
-        const float2 v1 = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
-        if constexpr (HMODE & kHalfSpectra) {
-          *reinterpret_cast<uint2*>(reinterpret_cast<unsigned*>(out) + o) =
-              make_uint2(pack_pair16<(HMODE & kHalfBf16) != 0>(v0.x, v0.y), pack_pair16<(HMODE & kHalfBf16) != 0>(v1.x, v1.y));
-        } else {
-          *reinterpret_cast<float4*>(out + o) = make_float4(v0.x, v0.y, v1.x, v1.y);
-        }
+  rfft_store_tile<K, HMODE>(L.z, P, lgP, tid, NT, t0, nrows, out, out_fstride, scale, conj);
+}
+
+// -------------------------------------------------------------------------------------
+// The same transform for long runs of contiguous rows (the activations of a large FC layer):
+// a workgroup walks over tiles of 4096 / K column pairs, blockIdx.x, blockIdx.x + gridDim.x, ..., and
+// requests the rows of its next tile before it transforms the current one, so that a CU keeps
+// loads in flight while its vector units work (in rfft_kernel a workgroup spends half of its time
+// waiting for its 32 KB of rows: 10,500 of 21,900 cycles at 65,536 rows of 256).  Memory returns
+// loads in issue order, so the K roots are requested ahead of the first rows, and a thread works
+// out the addresses of its own rows instead of waiting for a table of them in LDS.
+// 256 threads; rows contiguous (element stride 1) and 16-byte aligned; 32 <= K <= 256.
+template <int K, int HMODE = 0>
+__global__ __launch_bounds__(256) void rfft_stream_kernel(const float* __restrict__ in, float2* __restrict__ out, RowMap map,
+                                                          long long nrows, long long out_fstride, int ntiles, float scale,
+                                                          int conj) {
+  static_assert(is_pow2_c(K) && K >= 32 && K <= 256, "block sizes of the streaming transform");
+  constexpr int P = 4096 / K, PP = P + 1, NT = 256, lgP = ilog2(P);
+  constexpr int GW = 8, NSEG = K / (4 * GW), RSTEP = NT / GW, NRI = 2 * P / RSTEP;   // NRI * NSEG = 8 loads per thread
+  static_assert(NRI >= 1 && NRI * RSTEP == 2 * P, "rows of a tile split evenly over the threads");
+  extern __shared__ float smem[];
+  TileLds L = carve_tile<K>(smem, P);
+  const int tid = threadIdx.x, gl = tid % GW, r0 = tid / GW;
+  constexpr bool BF = (HMODE & kHalfBf16) != 0;
+
+  float2 tw_stage[(K + NT - 1) / NT];
+#pragma unroll
+  for (int s = 0; s < (K + NT - 1) / NT; ++s)
+    tw_stage[s] = reinterpret_cast<const float2*>(kTw.cs)[min(s * NT + tid, K - 1) * (kTwN / K)];
+
+  float4 xr[NRI][NSEG];
+  // rows past the end are read from the last row (a valid address) and zeroed
+  auto request = [&](int tile) {
+#pragma unroll
+    for (int i = 0; i < NRI; ++i) {
+      const long long rid = (long long)tile * 2 * P + r0 + i * RSTEP;
+      const bool ok = rid < nrows;
+      const long long b = row_base(map, ok ? rid : nrows - 1);
+#pragma unroll
+      for (int seg = 0; seg < NSEG; ++seg) {
+        const int n = 4 * (seg * GW + gl);
+        float4 v;
+        if constexpr (HMODE & kHalfRows) v = load_half4<BF>(reinterpret_cast<const unsigned short*>(in) + b + n);
+        else v = *reinterpret_cast<const float4*>(in + b + n);
+        xr[i][seg] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
       }
-      return;
     }
-#pragma unroll 2
-    for (int f = tid >> lgP; f < NF; f += fstep, o += ostep) {
-      float2 u = L.z[fft_pos<K>(f) * PP + pr], w = L.z[fft_pos<K>(f == 0 ? 0 : K - f) * PP + pr];
-      const float2 v0 = make_float2(h * (u.x + w.x), hc * (u.y - w.y));
-      const float2 v1 = make_float2(h * (u.y + w.y), hc * (w.x - u.x));
-      if constexpr (HMODE & kHalfSpectra) {
-        unsigned* oh = reinterpret_cast<unsigned*>(out) + o;
-        if (ok0) oh[0] = pack_pair16<(HMODE & kHalfBf16) != 0>(v0.x, v0.y);
-        if (ok1) oh[1] = pack_pair16<(HMODE & kHalfBf16) != 0>(v1.x, v1.y);
-      } else {
-        if (ok0) out[o] = v0;
-        if (ok1) out[o + 1] = v1;
+  };
+  int tile = blockIdx.x;
+  if (tile < ntiles) request(tile);
+#pragma unroll
+  for (int s = 0; s < (K + NT - 1) / NT; ++s)
+    if (s * NT + tid < K) L.tw[s * NT + tid] = tw_stage[s];
+
+  for (; tile < ntiles; tile += gridDim.x) {
+    // 8 lanes along the row times 8 rows per wave-store: every LDS bank gets exactly two lanes
+    // (see the row loader of rfft_kernel)
+#pragma unroll
+    for (int i = 0; i < NRI; ++i) {
+      float* zrow = reinterpret_cast<float*>(L.z) + r0 + i * RSTEP;
+#pragma unroll
+      for (int seg = 0; seg < NSEG; ++seg) {
+        float* zd = zrow + 2 * (4 * (seg * GW + gl)) * PP;
+        zd[0] = xr[i][seg].x;
+        zd[2 * PP] = xr[i][seg].y;
+        zd[4 * PP] = xr[i][seg].z;
+        zd[6 * PP] = xr[i][seg].w;
       }
     }
+    __syncthreads();
+    if (tile + (int)gridDim.x < ntiles) request(tile + gridDim.x);
+    const int col = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
+    fft_lds_pass1<K, false>(L.z, PP, col, t, TT, L.tw);
+    __syncthreads();
+    fft_lds_pass2_inplace<K, false>(L.z, PP, col, t, TT);
+    __syncthreads();
+    rfft_store_tile<K, HMODE>(L.z, P, lgP, tid, NT, (long long)tile * 2 * P, nrows, out, out_fstride, scale, conj);
+    __syncthreads();   // the tile is free for the next rows
   }
 }
 
