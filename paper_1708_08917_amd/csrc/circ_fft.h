@@ -48,6 +48,33 @@ __device__ __forceinline__ void stage_twiddles(float2* twl, int tid, int nthread
   }
 }
 
+// The same in two steps, for kernels that have other loads to issue: memory returns loads in issue
+// order, so the roots are requested first (into registers), the kernel's own loads go out behind
+// them, and the roots are written to LDS later, when they have long arrived.  nthreads >= 64.
+template <int K>
+struct TwiddleStage {
+  static constexpr int N = (K + 63) / 64;
+  float2 v[N];
+  __device__ __forceinline__ void request(int tid, int nthreads) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int m = tid + i * nthreads;
+      v[i] = make_float2(0.f, 0.f);
+      if (m < K) {
+        if constexpr (kTwN % K == 0) v[i] = reinterpret_cast<const float2*>(kTw.cs)[m * (kTwN / K)];
+        else v[i] = reinterpret_cast<const float2*>(kRoots<K>.cs)[m];
+      }
+    }
+  }
+  __device__ __forceinline__ void store(float2* twl, int tid, int nthreads) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int m = tid + i * nthreads;
+      if (m < K) twl[m] = v[i];
+    }
+  }
+};
+
 // z: tile of complex values, element (n, col) at z[n*PP + col].
 // col: column of this thread; t, TT: index and count of threads sharing a column.
 // twl: LDS copy of the twiddles made by stage_twiddles<K>.

@@ -160,7 +160,8 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
   const long long t0 = (long long)blockIdx.x * 2 * P;
   const int tid = threadIdx.x, NT = blockDim.x;
 
-  stage_twiddles<K>(L.tw, tid, NT);
+  TwiddleStage<K> tws;
+  tws.request(tid, NT);
   for (int r = tid; r < 2 * P; r += NT) {
     long long rid = t0 + r;
     L.rbase[r] = rid < nrows ? row_base(map, rid) : -1;
@@ -255,6 +256,7 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
       lds_put(L.z, n * PP + (row >> 1), row & 1, v);
     }
   }
+  tws.store(L.tw, tid, NT);
   __syncthreads();
 
   const int col = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
@@ -288,10 +290,8 @@ __global__ __launch_bounds__(256) void rfft_stream_kernel(const float* __restric
   const int tid = threadIdx.x, gl = tid % GW, r0 = tid / GW;
   constexpr bool BF = (HMODE & kHalfBf16) != 0;
 
-  float2 tw_stage[(K + NT - 1) / NT];
-#pragma unroll
-  for (int s = 0; s < (K + NT - 1) / NT; ++s)
-    tw_stage[s] = reinterpret_cast<const float2*>(kTw.cs)[min(s * NT + tid, K - 1) * (kTwN / K)];
+  TwiddleStage<K> tws;
+  tws.request(tid, NT);
 
   float4 xr[NRI][NSEG];
   // rows past the end are read from the last row (a valid address) and zeroed
@@ -313,9 +313,7 @@ __global__ __launch_bounds__(256) void rfft_stream_kernel(const float* __restric
   };
   int tile = blockIdx.x;
   if (tile < ntiles) request(tile);
-#pragma unroll
-  for (int s = 0; s < (K + NT - 1) / NT; ++s)
-    if (s * NT + tid < K) L.tw[s * NT + tid] = tw_stage[s];
+  tws.store(L.tw, tid, NT);
 
   for (; tile < ntiles; tile += gridDim.x) {
     // 8 lanes along the row times 8 rows per wave-store: every LDS bank gets exactly two lanes
@@ -361,7 +359,8 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
   const long long t0 = (long long)blockIdx.x * 2 * P;
   const int tid = threadIdx.x, NT = blockDim.x;
 
-  stage_twiddles<K>(L.tw, tid, NT);
+  TwiddleStage<K> tws;
+  tws.request(tid, NT);
   // build Z = Ya + i*Yb on all K bins from the two half spectra (Hermitian symmetry)
   constexpr int NF = K / 2 + 1;
   {
@@ -450,6 +449,7 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
     L.rbase[r] = ok ? row_base(map, rid) : -1;
     L.rblk[r] = ok ? int((unsigned)rid / (unsigned)bias_div) : 0;   // both fit 32 bits (host check)
   }
+  tws.store(L.tw, tid, NT);
   __syncthreads();
 
   const int col = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
