@@ -767,6 +767,29 @@ def test_cfg2_graph_over_streams_matches_eager():
         assert torch.equal(ys, eager), f"replay {rep} differs from the eager result"
 
 
+@pytest.mark.parametrize("p,q,k,batch", [(70, 40, 256, 901), (72, 33, 128, 1001), (130, 3, 64, 17000), (130, 70, 32, 1950)])
+def test_fc_unfused_route_with_long_ragged_runs_of_rows(p, q, k, batch):
+    """More than 8 tiles of output block rows keep these layers off the fused kernel: q * batch rows go
+    through the streaming row transform (at least 256 tiles of 4096 / k column pairs, the last tile
+    ragged), p * batch rows through the inverse transform.  Forward on sampled block rows, backward
+    on sampled block columns and (i, j) pairs."""
+    w, x, b = rand_fc(p, q, k, batch)
+    assert (q * batch) % (2 * 4096 // k) != 0 and q * batch >= 256 * 2 * 4096 // k
+    what = f"{p}x{q} k={k} B={batch}"
+    rows = [0, p // 2, p - 1]
+    got = G.gpu_fc_forward(w, x, b, True)
+    sel = np.concatenate([np.arange(i * k, (i + 1) * k) for i in rows])
+    check(got[:, sel], O.fc_forward(w, x, b, True, block_rows=rows), "fwd " + what)
+    dy = RNG.uniform(-1, 1, (batch, p * k)).astype(np.float32)
+    dx, dw = G.gpu_fc_backward(w, x, dy)
+    cols = [0, q - 1]
+    csel = np.concatenate([np.arange(j * k, (j + 1) * k) for j in cols])
+    check(dx[:, csel], O.fc_backward_dx(w, dy, block_cols=cols), "dx " + what)
+    pairs = [(0, 0), (p - 1, q - 1), (p // 2, q // 3)]
+    ref = O.fc_backward_dw(x, dy, k, pairs=pairs)
+    check(np.stack([dw[i, j] for i, j in pairs]), ref, "dw " + what)
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_cfg3_two_stacked_layers(seed):
     w1, x, b1 = synth.fc_inputs(synth.CFG3_L1, seed)
