@@ -162,31 +162,44 @@ __global__ void rfft_kernel(const float* __restrict__ in, float2* __restrict__ o
 
   TwiddleStage<K> tws;
   tws.request(tid, NT);
-  for (int r = tid; r < 2 * P; r += NT) {
-    long long rid = t0 + r;
-    L.rbase[r] = rid < nrows ? row_base(map, rid) : -1;
+  // (groups of 4 adjacent rows, below, need no table of row addresses and no barrier before their loads)
+  const bool quad_rows = ROWS_FAST && map.quad;
+  if (!quad_rows) {
+    for (int r = tid; r < 2 * P; r += NT) {
+      long long rid = t0 + r;
+      L.rbase[r] = rid < nrows ? row_base(map, rid) : -1;
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
   // load: row 2u -> real part of column u, row 2u+1 -> imaginary part
   if constexpr (ROWS_FAST) {
     if (map.quad) {
       // 4 rows per 16-byte load; they are the (re, im) slots of two neighbouring columns, i.e.
-      // 4 consecutive floats of the tile (8-byte aligned: two 8-byte LDS stores)
+      // 4 consecutive floats of the tile (8-byte aligned: two 8-byte LDS stores).  A thread keeps
+      // its group of 4 rows (NT is a multiple of the P/2 groups of a tile) and works out their
+      // address itself; its loads, one per element index, go out together.
       const int nq = P >> 1;                       // groups of 4 rows in the tile
-#pragma unroll 4
-      for (int idx = tid; idx < nq * K; idx += NT) {
-        const int qd = idx & (nq - 1), n = idx >> (lgP - 1);
-        long long b = L.rbase[4 * qd];
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if constexpr (HMODE & kHalfRows) {
-          if (b >= 0) v = load_half4<(HMODE & kHalfBf16) != 0>(reinterpret_cast<const unsigned short*>(in) + b + n * map.es);
-        } else {
-          if (b >= 0) v = *reinterpret_cast<const float4*>(in + b + n * map.es);
+      const int qd = tid & (nq - 1), nstep = NT >> (lgP - 1);
+      const long long rid = t0 + 4 * qd;
+      float2* zq = L.z + 2 * qd;
+      if (rid < nrows) {
+        const long long b = row_base(map, rid);
+#pragma unroll 8
+        for (int n = tid >> (lgP - 1); n < K; n += nstep) {
+          float4 v;
+          if constexpr (HMODE & kHalfRows) v = load_half4<(HMODE & kHalfBf16) != 0>(reinterpret_cast<const unsigned short*>(in) + b + n * map.es);
+          else v = *reinterpret_cast<const float4*>(in + b + n * map.es);
+          float2* zd = zq + n * PP;
+          zd[0] = make_float2(v.x, v.y);
+          zd[1] = make_float2(v.z, v.w);
         }
-        float2* zd = L.z + n * PP + 2 * qd;
-        zd[0] = make_float2(v.x, v.y);
-        zd[1] = make_float2(v.z, v.w);
+      } else {
+        for (int n = tid >> (lgP - 1); n < K; n += nstep) {
+          float2* zd = zq + n * PP;
+          zd[0] = make_float2(0.f, 0.f);
+          zd[1] = make_float2(0.f, 0.f);
+        }
       }
     } else {
 #pragma unroll 4
