@@ -108,7 +108,10 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
   const int jbeg = MODE == 1 ? blockIdx.y * jper : 0;
   const int jend = MODE == 1 ? min(q, jbeg + jper) : q;
   const int nchunks = MODE == 2 ? 0 : (jend - jbeg + PT - 1) / PT;
-  stage_twiddles<K>(twl, tid, NT);
+  // the K roots are requested first and written to LDS once the first x loads are out (memory
+  // returns loads in issue order: nothing waits for the roots before x and the weights are requested)
+  TwiddleStage<K> tws;
+  tws.request(tid, NT);
 
   const int slot = tid % S, jg = tid / S;          // contraction role (threads beyond S*JG idle)
   const bool active = jg < JG;
@@ -154,6 +157,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
       lds_put(z, (n + 2) * PP + col, half, v.z);
       lds_put(z, (n + 3) * PP + col, half, v.w);
     }
+    if (c == 0) tws.store(twl, tid, NT);
     __syncthreads();
     CIRC_PROBE(1 + 3 * c);
     auto sink = [&](int col) {
@@ -201,6 +205,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
   }
 
   if constexpr (MODE == 2) {
+    tws.store(twl, tid, NT);
     // spectrum of the output pair = sum of the partial spectra, in index order
     for (int f = tid; f < K; f += NT) {
       float2 acc = make_float2(0.f, 0.f);
