@@ -106,6 +106,45 @@ __device__ __forceinline__ void fft_lds_pass1(float2* z, int PP, int col, int t,
   }
 }
 
+// The same with a compile-time count TT of threads per column: a thread's R2 / TT sub-transforms are
+// unrolled, so that their loads, butterflies and stores interleave (a thread with two of them
+// otherwise runs two dependent chains one after the other).
+template <int K, bool INV, int TT>
+__device__ __forceinline__ void fft_lds_pass1_unrolled(float2* z, int PP, int col, int t, const float2* twl) {
+  constexpr int R2 = radix2_of(K), R1 = radix1_of(K), NI = (R2 + TT - 1) / TT;
+  float re[NI][R1], im[NI][R1];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int n2 = min(t + i * TT, R2 - 1);
+#pragma unroll
+    for (int n1 = 0; n1 < R1; ++n1) {
+      const float2 v = z[(R2 * n1 + n2) * PP + col];
+      re[i][n1] = v.x;
+      im[i][n1] = v.y;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NI; ++i) FftReg<R1, INV>::run(re[i], im[i]);
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int n2 = t + i * TT;
+    if (n2 < R2) {
+#pragma unroll
+      for (int f1 = 0; f1 < R1; ++f1) {
+        float vr = re[i][f1], vi = im[i][f1];
+        if (f1 > 0 && R2 > 1) {
+          const float2 w = twl[f1 * n2];
+          const float c = w.x, s = INV ? w.y : -w.y;
+          const float xr = c * vr - s * vi;
+          vi = c * vi + s * vr;
+          vr = xr;
+        }
+        z[(R2 * f1 + n2) * PP + col] = make_float2(vr, vi);
+      }
+    }
+  }
+}
+
 // Pass 2 hands every finished value to `sink(f, value)` with f = f1 + R1*f2 instead of
 // storing it, so that callers choose where spectra (or time samples) go.
 template <int K, bool INV, class Sink>

@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__
       for (int col = tid; col < PT; col += NT) fft_lds_single<K, false>(z, PP, col, sink(col));
     } else {
       const int col = tid % PT, t = tid / PT;
-      fft_lds_pass1<K, false>(z, PP, col, t, NT / PT, twl);
+      fft_lds_pass1_unrolled<K, false, NT / PT>(z, PP, col, t, twl);
       __syncthreads();
       fft_lds_pass2<K, false>(z, PP, col, t, NT / PT, sink(col));
     }
