@@ -490,15 +490,15 @@ hipError_t launch_gemv_k(const float2* wg, const float* x, const float* bias, fl
     if (ensure_lds(&fc_gemv_kernel<K, 2, HM>, Sh::LDS_BYTES, opted2) != hipSuccess) return hipErrorInvalidValue;
     float2* part = static_cast<float2*>(workspace);
     const int jper = (int)cdiv(q, ns);
-    hipLaunchKernelGGL((fc_gemv_kernel<K, 1, HM>), dim3((unsigned)p, (unsigned)ns), dim3(256), Sh::LDS_BYTES, s, wg, x,
+    hipLaunchKernelGGL((fc_gemv_kernel<K, 1, HM>), dim3((unsigned)p, (unsigned)ns), dim3(Sh::NT), Sh::LDS_BYTES, s, wg, x,
                        (const float*)nullptr, (float*)nullptr, p, q, batch, 0, part, ns, jper);
     if (hipGetLastError() != hipSuccess) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fc_gemv_kernel<K, 2, HM>), dim3((unsigned)p), dim3(256), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch,
+    hipLaunchKernelGGL((fc_gemv_kernel<K, 2, HM>), dim3((unsigned)p), dim3(Sh::NT), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch,
                        relu, part, ns, jper);
     return hipGetLastError();
   }
   if (ensure_lds(&fc_gemv_kernel<K, 0, HM>, Sh::LDS_BYTES, opted_in) != hipSuccess) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((fc_gemv_kernel<K, 0, HM>), dim3((unsigned)p), dim3(256), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch,
+  hipLaunchKernelGGL((fc_gemv_kernel<K, 0, HM>), dim3((unsigned)p), dim3(Sh::NT), Sh::LDS_BYTES, s, wg, x, bias, y, p, q, batch,
                      relu, (float2*)nullptr, 1, q);
   return hipGetLastError();
 }

@@ -29,7 +29,9 @@ namespace circ {
 
 template <int K>
 struct GemvShape {
-  static constexpr int NT = 256;
+  // threads per workgroup: these launches have few workgroups (one per output block row, times the
+  // splits of the j range), so from k = 64 on a workgroup takes 512 threads for its transforms
+  static constexpr int NT = K >= 64 ? 512 : 256;
   static constexpr int S = K / 2;                       // complex slots per block
   // input blocks (FFT columns) per chunk: up to 128, for the shortest blocks up to 512 (a chunk costs
   // one round trip to memory for its x rows, and layers with k <= 8 have many blocks per row)
@@ -89,7 +91,7 @@ __global__ __launch_bounds__(256) void pack_gemv_half_kernel(const unsigned* __r
 // value (the 16-bit (re, im) pair, not normalised; pack_gemv_half_elem), x and y to 16-bit values;
 // the arithmetic and the partial spectra of MODE 1 / 2 stay fp32, the 1/k goes onto the result.
 template <int K, int MODE, int HM = 0>
-__global__ __launch_bounds__(256) void fc_gemv_kernel(const float2* __restrict__ Wg, const float* __restrict__ x,
+__global__ __launch_bounds__(GemvShape<K>::NT) void fc_gemv_kernel(const float2* __restrict__ Wg, const float* __restrict__ x,
                                                       const float* __restrict__ bias, float* __restrict__ y,
                                                       int p, int q, int B, int relu, float2* __restrict__ part,
                                                       int nsplit, int jper) {
