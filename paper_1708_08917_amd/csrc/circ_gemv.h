@@ -30,8 +30,9 @@ namespace circ {
 template <int K>
 struct GemvShape {
   // threads per workgroup: these launches have few workgroups (one per output block row, times the
-  // splits of the j range), so from k = 64 on a workgroup takes 512 threads for its transforms
-  static constexpr int NT = K >= 64 ? 512 : 256;
+  // splits of the j range), so a workgroup takes 512 threads for its transforms and its share of
+  // the weights (k = 4, whose chunks hold 512 one-thread columns, measured faster with 256)
+  static constexpr int NT = K >= 8 ? 512 : 256;
   static constexpr int S = K / 2;                       // complex slots per block
   // input blocks (FFT columns) per chunk: up to 128, for the shortest blocks up to 512 (a chunk costs
   // one round trip to memory for its x rows, and layers with k <= 8 have many blocks per row)
