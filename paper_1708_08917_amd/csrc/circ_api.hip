@@ -10,6 +10,7 @@
 #include "circ_kernels.h"
 #include "circ_dft.h"
 #include "circ_gemm.h"
+#include "circ_gemm_split.h"
 #include "circ_fused.h"
 #include "circ_gemv.h"
 #include "circ_conv_fused.h"
@@ -333,6 +334,35 @@ inline bool cgemm_takes_tiled(int k, int M, int N, int Kd, int ksplit) {
   const bool fits32 = (long long)Kd * M <= lim && (long long)Kd * N <= lim && (long long)M * N <= lim;
   return fits32 && M > 32 && N <= 64 && tiles_s >= kGemmTiledMinTiles;
 }
+// Wide outputs without split-K (forward and backward-data of large layers) run on the bfloat16
+// matrix instruction with every fp32 operand split into three bfloat16 terms (circ_gemm_split.h):
+// the fp32 matrix instruction bounds the one-wave kernel there (16384x16384, k=256, batch 1024:
+// 35 us against 47 us; the error against a float64 sum is no larger, 3.8e-7 against 5.3e-7 of
+// the largest output).  Workgroups: two per CU, each with its share of consecutive tiles.
+constexpr long long kGemmSplitMinTiles = 256;
+constexpr int kGemmSplitWorkgroups = 512;
+inline bool cgemm_takes_split(int k, int M, int N, int Kd, int ksplit) {
+  const int NF = k / 2 + 1;
+  const long long tiles = (long long)NF * cdiv(M, SplitGemmShape::TM) * cdiv(N, SplitGemmShape::TN);
+  const long long lim = (1ll << 31) - 1;       // offsets inside one frequency of an operand are kept in 32 bits
+  const bool fits32 = (long long)Kd * M <= lim && (long long)Kd * N <= lim && (long long)M * N <= lim;
+  return ksplit == 1 && fits32 && M > 32 && Kd >= 16 && tiles >= kGemmSplitMinTiles && tiles <= lim;
+}
+hipError_t launch_cgemm_split(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, long long sA,
+                              long long sB, long long sC, bool conj_b, hipStream_t s) {
+  const int ntm = (int)cdiv(M, SplitGemmShape::TM), ntn = (int)cdiv(N, SplitGemmShape::TN);
+  const long long ntiles = (long long)NF * ntm * ntn;
+  const long long nwg = ntiles < kGemmSplitWorkgroups ? ntiles : kGemmSplitWorkgroups;
+  dim3 grid((unsigned)(cdiv(nwg, 8) * 8));
+  const unsigned base = (unsigned)(ntiles / nwg), rem = (unsigned)(ntiles % nwg);
+  if (conj_b)
+    hipLaunchKernelGGL((cgemm_split_kernel<true>), grid, dim3(SplitGemmShape::NT), 0, s, A, B, C, M, N, Kd, sA, sB, sC, ntm, ntn,
+                       (unsigned)ntiles, base, rem);
+  else
+    hipLaunchKernelGGL((cgemm_split_kernel<false>), grid, dim3(SplitGemmShape::NT), 0, s, A, B, C, M, N, Kd, sA, sB, sC, ntm, ntn,
+                       (unsigned)ntiles, base, rem);
+  return hipGetLastError();
+}
 // a_t: A is stored [f][m][kd] instead of [f][kd][m]; only the tiled kernel reads that layout, so
 // callers pass it only when cgemm_takes_tiled() holds.
 hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int k, int M, int N, int Kd, long long sA,
@@ -343,6 +373,7 @@ hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int k, int 
   if (cgemm_takes_tiled(k, M, N, Kd, ksplit))
     return launch_cgemm_tiled<1, 2, 2>(A, B, C, NF, M, N, Kd, sA, sB, sC, conj_b, a_t, s, ksplit, kchunk, part_stride);
   if (a_t) return hipErrorInvalidValue;
+  if (cgemm_takes_split(k, M, N, Kd, ksplit)) return launch_cgemm_split(A, B, C, NF, M, N, Kd, sA, sB, sC, conj_b, s);
   bool big = (long long)NF * cdiv(M, 32) * cdiv(N, 32) * ksplit >= 1024;
   int tile = big ? 32 : 16;
   const int ntn = (int)cdiv(N, tile);
