@@ -790,6 +790,37 @@ def test_fc_unfused_route_with_long_ragged_runs_of_rows(p, q, k, batch):
     check(np.stack([dw[i, j] for i, j in pairs]), ref, "dw " + what)
 
 
+def test_fc_split_gemm_route_keeps_fp32_accuracy_per_batch_row():
+    """Layers with at least 256 tiles of 64 x 128 outputs per frequency take the contraction that
+    splits every fp32 operand into three bfloat16 terms.  Each value is split on its own, so batch
+    rows of small magnitude next to rows eight decades larger must come out with the same relative
+    accuracy as any others: the error of every output row is measured against that row's own
+    largest value (forward; backward-data takes the same kernel with the transposed weights).  Rows
+    2i and 2i + 1 share a scale: the row transforms carry two rows as one complex sequence, and
+    their separation is exact only relative to the larger of the two."""
+    p, q, k, batch = 34, 20, 256, 260
+    w, x, b = rand_fc(p, q, k, batch, bias=False)
+    scale = np.repeat(10.0 ** RNG.uniform(-4, 4, batch // 2), 2).astype(np.float32)
+    x = x * scale[:, None]
+    w = w * (10.0 ** RNG.uniform(-2, 2, (p, q, 1))).astype(np.float32)
+    rows = [0, p // 2, p - 1]
+    sel = np.concatenate([np.arange(i * k, (i + 1) * k) for i in rows])
+    got = G.gpu_fc_forward(w, x)[:, sel]
+    ref = O.fc_forward(w, x, block_rows=rows)
+    assert np.all(np.isfinite(got))
+    err = np.max(np.abs(got - ref), axis=1) / np.max(np.abs(ref), axis=1)
+    print(f"[parity] split contraction, per-row rel err: max {err.max():.3e} median {np.median(err):.3e}", flush=True)
+    assert err.max() <= TIGHT, err.max()
+    dy = (RNG.uniform(-1, 1, (batch, p * k)) * scale[:, None]).astype(np.float32)
+    cols = [0, q - 1]
+    csel = np.concatenate([np.arange(j * k, (j + 1) * k) for j in cols])
+    dx = G.gpu_fc_backward(w, x, dy)[0][:, csel]
+    dref = O.fc_backward_dx(w, dy, block_cols=cols)
+    derr = np.max(np.abs(dx - dref), axis=1) / np.max(np.abs(dref), axis=1)
+    print(f"[parity] split contraction, backward-data per-row rel err: max {derr.max():.3e}", flush=True)
+    assert derr.max() <= TIGHT, derr.max()
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_cfg3_two_stacked_layers(seed):
     w1, x, b1 = synth.fc_inputs(synth.CFG3_L1, seed)
