@@ -363,15 +363,31 @@ hipError_t launch_cgemm_split(const float2* A, const float2* B, float2* C, int N
                        (unsigned)ntiles, base, rem);
   return hipGetLastError();
 }
-// a_t: A is stored [f][m][kd] instead of [f][kd][m]; only the tiled kernel reads that layout, so
+hipError_t launch_cgemm_split_dw(const float2* A, const float2* B, float2* C, int NF, int M, int N, int Kd, long long sA,
+                                 long long sB, long long sC, hipStream_t s, int ksplit, int kchunk, long long part_stride) {
+  const int ntm = (int)cdiv(M, 64), ntn = (int)cdiv(N, 64);
+  const long long ntiles = (long long)NF * ntm * ntn * ksplit;
+  if (ntiles > (1ll << 31) - 8) return hipErrorInvalidValue;
+  const long long nwg = ntiles < kGemmSplitWorkgroups ? ntiles : kGemmSplitWorkgroups;
+  dim3 grid((unsigned)(cdiv(nwg, 8) * 8));
+  hipLaunchKernelGGL(cgemm_split_dw_kernel, grid, dim3(SplitGemmShape::NT), 0, s, A, B, C, M, N, Kd, sA, sB, sC, ntm, ntn, ksplit,
+                     kchunk, part_stride, (unsigned)ntiles, (unsigned)(ntiles / nwg), (unsigned)(ntiles % nwg));
+  return hipGetLastError();
+}
+// a_t: A is stored [f][m][kd] instead of [f][kd][m]; only the tiled kernels read that layout, so
 // callers pass it only when cgemm_takes_tiled() holds.
 hipError_t launch_cgemm(const float2* A, const float2* B, float2* C, int k, int M, int N, int Kd, long long sA,
                         long long sB, long long sC, bool conj_b, hipStream_t s, int ksplit = 1,
                         long long part_stride = 0, bool a_t = false) {
   const int NF = k / 2 + 1;                                    // one complex product per bin 0..k/2
   const int kchunk = (int)(cdiv(cdiv(Kd, ksplit), 32) * 32);   // whole operand groups per slice
-  if (cgemm_takes_tiled(k, M, N, Kd, ksplit))
+  if (cgemm_takes_tiled(k, M, N, Kd, ksplit)) {
+    // backward-weights of large layers: the split arithmetic (whole quads and slabs of the reduction only)
+    const long long tiles = (long long)NF * cdiv(M, 64) * cdiv(N, 64) * ksplit;
+    if (conj_b && a_t && Kd % 4 == 0 && kchunk % SplitGemmShape::KA == 0 && (sA & 1) == 0 && tiles >= kGemmSplitMinTiles)
+      return launch_cgemm_split_dw(A, B, C, NF, M, N, Kd, sA, sB, sC, s, ksplit, kchunk, part_stride);
     return launch_cgemm_tiled<1, 2, 2>(A, B, C, NF, M, N, Kd, sA, sB, sC, conj_b, a_t, s, ksplit, kchunk, part_stride);
+  }
   if (a_t) return hipErrorInvalidValue;
   if (cgemm_takes_split(k, M, N, Kd, ksplit)) return launch_cgemm_split(A, B, C, NF, M, N, Kd, sA, sB, sC, conj_b, s);
   bool big = (long long)NF * cdiv(M, 32) * cdiv(N, 32) * ksplit >= 1024;

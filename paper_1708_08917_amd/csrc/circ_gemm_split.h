@@ -260,4 +260,203 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void c
   }
 }
 
+
+// Backward-weights (Algorithm 2: the spectrum of dL/dw_ij is the sum over the batch of
+// FFT(dL/da_i) o conj(FFT(x_j))) on the same split arithmetic:
+//   C[ks][f][m][n] = sum_{k in slice ks} A[f][m][k] * conj(B[f][k][n])
+// A = the spectrum of dy stored [f][i][b] (k = the batch index fastest: the order backward-data
+// needs it in, so dy is transformed once), B = the spectrum of x stored [f][b][j] (n fastest).
+// The output is narrow (p x q block pairs) and the reduction long, so the reduction is cut into
+// `ksplit` slices of `kchunk` values (a multiple of 64) whose partial sums go to
+// C + ks*part_stride, to be added later in index order.
+// A workgroup owns a 64 (m) x 64 (n) tile of one (frequency, slice): wave w takes the columns
+// 32*(w % 2) .. + 31 and, of every slab of 64 k, the steps 4*(w / 2) .. + 3 - all four waves
+// share the staged A slab, and the two halves of the reduction meet in LDS at the end of the tile.
+// B goes from memory to the lanes as in cgemm_split_kernel; the A slab of the next 64 k is
+// requested (lanes along k: runs of 512 bytes) while the current one is multiplied.
+// Requires Kd to be a multiple of 4 (16-byte loads of whole quads along k); offsets inside one
+// frequency fit 32 bits (host check).
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void cgemm_split_dw_kernel(
+    const float2* __restrict__ A, const float2* __restrict__ B, float2* __restrict__ C, int M, int N, int Kd, long long sA,
+    long long sB, long long sC, int ntm, int ntn, int ksplit, int kchunk, long long part_stride, unsigned ntiles, unsigned base,
+    unsigned rem) {
+  using Sh = SplitGemmShape;
+  constexpr int TM = Sh::TM, TN = 64, KA = Sh::KA, PITCH = Sh::PITCH, WSTEP = Sh::NSTEP / 2;   // steps per wave and slab
+  __shared__ __attribute__((aligned(16))) unsigned la[3 * Sh::PLANE];      // [term][m][k]; at a tile's end: partial sums
+
+  const unsigned v = (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+  const unsigned first = v * base + min(v, rem);
+  if (first >= ntiles) return;
+  const unsigned count = min(base + (v < rem ? 1u : 0u), ntiles - first);
+  const int nkc = kchunk / KA;                         // slabs per tile
+  const unsigned nslabs = count * unsigned(nkc);
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wn = wave & 1, kh = wave >> 1;
+  const int r = lane & 31, h = lane >> 5;
+
+  struct Slab {
+    int f, m0, n0, ks, kc, kend;
+    int last;                // 1: the last slab of its tile
+  };
+  auto slab_at = [&](unsigned i) {
+    Slab S;
+    unsigned t = first + i / unsigned(nkc);
+    const int sl = int(i % unsigned(nkc));
+    S.ks = int(t % unsigned(ksplit));
+    t /= unsigned(ksplit);
+    S.n0 = int(t % unsigned(ntn)) * TN;
+    S.m0 = int((t / unsigned(ntn)) % unsigned(ntm)) * TM;
+    S.f = int(t / unsigned(ntn * ntm));
+    S.kc = S.ks * kchunk + sl * KA;
+    S.kend = min(Kd, (S.ks + 1) * kchunk);
+    S.last = sl == nkc - 1 ? 1 : 0;
+    return S;
+  };
+
+  // B: lane (h, r) takes column n0 + 32*wn + r (clamped), rows kc + 8*(4*kh + j) + 4h + u of step j
+  float2 braw[WSTEP][4];
+  auto b_column = [&](const Slab& S) { return B + S.f * sB + min(S.n0 + 32 * wn + r, N - 1); };
+  auto fetch_b = [&](const float2* bcol, unsigned pitch, int kc, int j) {
+    const int k0 = kc + 8 * (WSTEP * kh + j) + 4 * h;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) braw[j][u] = bcol[unsigned(min(k0 + u, Kd - 1)) * pitch];
+  };
+
+  // A slab -> LDS planes: thread (row tid / 16 + 16e, k-quad tid % 16): 16 lanes along k
+  const int qa = tid & 15, ra = tid >> 4;
+  float4 va[4][2];
+  auto load_a = [&](const float2* abase, int m0, int kc) {
+    const int k = min(kc + 4 * qa, Kd - 4);             // a quad inside the row (quads past Kd are zeroed at the split)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float2* src = abase + unsigned(min(m0 + ra + 16 * e, M - 1)) * unsigned(Kd) + k;
+      va[e][0] = *reinterpret_cast<const float4*>(src);
+      va[e][1] = *reinterpret_cast<const float4*>(src + 2);
+    }
+  };
+  auto put_a = [&](int m0, int kc, int kend) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool okrow = m0 + ra + 16 * e < M;
+      uint4 th, tm, tl;
+      unsigned* ph = reinterpret_cast<unsigned*>(&th);
+      unsigned* pm = reinterpret_cast<unsigned*>(&tm);
+      unsigned* pl = reinterpret_cast<unsigned*>(&tl);
+      const float2 x[4] = {make_float2(va[e][0].x, va[e][0].y), make_float2(va[e][0].z, va[e][0].w),
+                           make_float2(va[e][1].x, va[e][1].y), make_float2(va[e][1].z, va[e][1].w)};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool keep = okrow && kc + 4 * qa + u < kend;
+        split_bf16x3(keep ? x[u] : make_float2(0.f, 0.f), ph[u], pm[u], pl[u]);
+      }
+      unsigned* d = la + (ra + 16 * e) * PITCH + 4 * qa;
+      *reinterpret_cast<uint4*>(d) = th;
+      *reinterpret_cast<uint4*>(d + Sh::PLANE) = tm;
+      *reinterpret_cast<uint4*>(d + 2 * Sh::PLANE) = tl;
+    }
+  };
+
+  hfloatx16 cre[2], cim[2];
+  auto zero_acc = [&]() {
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { cre[s][i] = 0.f; cim[s][i] = 0.f; }
+  };
+  const unsigned* fa = la + r * PITCH + 4 * h;
+  float* red = reinterpret_cast<float*>(la) + (wn * 64) * 64 + lane;   // [wn][value 0..63][lane]
+
+  Slab cur = slab_at(0);
+  load_a(A + cur.f * sA, cur.m0, cur.kc);
+  {
+    const float2* bcol = b_column(cur);
+#pragma unroll
+    for (int j = 0; j < WSTEP; ++j) fetch_b(bcol, unsigned(N), cur.kc, j);
+  }
+  zero_acc();
+  CIRC_PROBE(0);
+  for (unsigned i = 0; i < nslabs; ++i) {
+    const bool more = i + 1 < nslabs;
+    Slab nxt = cur;
+    if (more) nxt = slab_at(i + 1);
+    const float2* bnext = more ? b_column(nxt) : B;
+    const unsigned pnext = more ? unsigned(N) : 0u;
+    __syncthreads();                                    // every wave has finished with the planes
+    put_a(cur.m0, cur.kc, cur.kend);
+    __syncthreads();
+    // the next slab of A; behind the last slab the same one again (unconditional: see fetch_b of cgemm_split_kernel)
+    load_a(A + nxt.f * sA, nxt.m0, nxt.kc);
+    CIRC_PROBE(1 + 3 * i);
+#pragma unroll
+    for (int j = 0; j < WSTEP; ++j) {
+      const int step = WSTEP * kh + j;                   // wave-uniform
+      uint4 bt[3];
+      {
+        unsigned* ph = reinterpret_cast<unsigned*>(&bt[0]);
+        unsigned* pm = reinterpret_cast<unsigned*>(&bt[1]);
+        unsigned* pl = reinterpret_cast<unsigned*>(&bt[2]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bool keep = cur.kc + 8 * step + 4 * h + u < cur.kend;
+          split_bf16x3(keep ? braw[j][u] : make_float2(0.f, 0.f), ph[u], pm[u], pl[u]);
+        }
+      }
+      fetch_b(bnext, pnext, nxt.kc, j);                 // the registers are free again: next slab
+      __builtin_amdgcn_sched_barrier(0);
+      uint4 a[2][3], bre[3], bim[3];
+#pragma unroll
+      for (int term = 0; term < 3; ++term) {
+        a[0][term] = *reinterpret_cast<const uint4*>(fa + term * Sh::PLANE + 8 * step);
+        a[1][term] = *reinterpret_cast<const uint4*>(fa + term * Sh::PLANE + 32 * PITCH + 8 * step);
+        const uint4 b = bt[term];
+        // conj(B): re form (br, bi), im form (-bi, br)
+        bre[term] = b;
+        bim[term] = make_uint4(__builtin_amdgcn_alignbit(b.x, b.x, 16) ^ 0x8000u, __builtin_amdgcn_alignbit(b.y, b.y, 16) ^ 0x8000u,
+                               __builtin_amdgcn_alignbit(b.z, b.z, 16) ^ 0x8000u, __builtin_amdgcn_alignbit(b.w, b.w, 16) ^ 0x8000u);
+      }
+      constexpr int TA[6] = {1, 2, 0, 1, 0, 0}, TB[6] = {1, 0, 2, 0, 1, 0};
+#pragma unroll
+      for (int pp = 0; pp < 6; ++pp) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          cre[s] = mfma16<true>(a[s][TA[pp]], bre[TB[pp]], cre[s]);
+          cim[s] = mfma16<true>(a[s][TA[pp]], bim[TB[pp]], cim[s]);
+        }
+      }
+    }
+    CIRC_PROBE(2 + 3 * i);
+    if (cur.last) {
+      // the two halves of the reduction: waves 2, 3 hand their sums to waves 0, 1 through LDS
+      __syncthreads();                                  // the planes are free
+      if (kh == 1) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int q = 0; q < 16; ++q) {
+            red[(32 * s + q) * 64] = cre[s][q];
+            red[(32 * s + 16 + q) * 64] = cim[s][q];
+          }
+      }
+      __syncthreads();
+      const int col = cur.n0 + 32 * wn + r;
+      if (kh == 0 && col < N) {
+        float2* c = C + cur.ks * part_stride + cur.f * sC + col;
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int q = 0; q < 16; ++q) {
+            const int row = cur.m0 + 32 * s + 8 * (q / 4) + 4 * h + (q % 4);
+            if (row < M)
+              c[unsigned(row) * unsigned(N)] = make_float2(cre[s][q] + red[(32 * s + q) * 64], cim[s][q] + red[(32 * s + 16 + q) * 64]);
+          }
+      }
+      zero_acc();
+    }
+    CIRC_PROBE(3 + 3 * i);
+    cur = nxt;
+  }
+}
+
 }  // namespace circ
