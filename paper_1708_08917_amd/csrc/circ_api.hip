@@ -191,6 +191,18 @@ template <int K>
 hipError_t launch_irfft_k(bool rows_fast, const float2* in, float* out, const RowMap& map, long long nrows,
                           long long in_fstride, float scale, const float* bias, long long bias_div, int relu,
                           int nparts, long long part_stride, hipStream_t s) {
+  if constexpr (stream_k<K>()) {
+    // long runs of contiguous rows: the streaming form (65,536 rows of 256)
+    constexpr int P = 4096 / K;
+    const long long ntiles = cdiv(nrows, 2 * P);
+    if (!rows_fast && nparts == 1 && ntiles >= kStreamMinTiles && ntiles <= (1ll << 31) - 1 && (nrows & 1) == 0 &&
+        (in_fstride & 1) == 0 && aligned16(in)) {
+      const unsigned grid = unsigned(ntiles < kStreamMaxWorkgroups ? ntiles : kStreamMaxWorkgroups);
+      hipLaunchKernelGGL((irfft_stream_kernel<K>), dim3(grid), dim3(256), fft_tile_lds_bytes(K, P), s, in, out, map, nrows,
+                         in_fstride, int(ntiles), scale, bias, bias_div, relu);
+      return hipGetLastError();
+    }
+  }
   FftPlan pl = plan_fft(K, nrows);
   dim3 grid((unsigned)cdiv(nrows, 2 * pl.P));
   if (rows_fast)

@@ -551,6 +551,98 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
 }
 
 // -------------------------------------------------------------------------------------
+// The inverse transform for long runs of contiguous rows (the outputs of a large FC layer), in
+// the streaming form of rfft_stream_kernel: a workgroup walks over tiles of 4096 / K column pairs
+// and requests the spectra of its next tile before it transforms the current one (in irfft_kernel
+// a workgroup waits 9,500 of its 24,900 cycles for its spectra at 65,536 rows of 256, and for the
+// roots before that).  A thread keeps its column pair and takes bins f0, f0 + K/16, ..., nine of
+// them (the ninth, bin K/2, only for f0 = 0), both rows of the pair in one 16-byte load.
+// 256 threads; one spectrum (no partial sums); an even number of rows, an even plane pitch and a
+// 16-byte aligned input (whole pairs); contiguous 16-byte aligned output rows; 32 <= K <= 256.
+template <int K>
+__global__ __launch_bounds__(256) void irfft_stream_kernel(const float2* __restrict__ in, float* __restrict__ out, RowMap map,
+                                                           long long nrows, long long in_fstride, int ntiles, float scale,
+                                                           const float* __restrict__ bias, long long bias_div, int relu) {
+  static_assert(is_pow2_c(K) && K >= 32 && K <= 256, "block sizes of the streaming transform");
+  constexpr int P = 4096 / K, PP = P + 1, NT = 256, lgP = ilog2(P), NF = K / 2 + 1, FSTEP = NT / P, NG = 8;
+  static_assert(NG * FSTEP == K / 2, "eight bins per thread, and bin K/2 for the threads of bin 0");
+  extern __shared__ float smem[];
+  TileLds L = carve_tile<K>(smem, P);
+  const int tid = threadIdx.x, pr = tid & (P - 1), f0 = tid >> lgP;
+
+  TwiddleStage<K> tws;
+  tws.request(tid, NT);
+
+  float4 y[NG + 1];
+  // pairs past the end reload the last pair (a valid address) and are zeroed when they are written to LDS
+  auto request = [&](int tile) {
+    const long long rid = (long long)tile * 2 * P + 2 * pr;
+    const float2* src = in + (rid < nrows ? rid : nrows - 2) + (long long)f0 * in_fstride;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) y[g] = *reinterpret_cast<const float4*>(src + (long long)(g * FSTEP) * in_fstride);
+    y[NG] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (f0 == 0) y[NG] = *reinterpret_cast<const float4*>(src + (long long)(K / 2) * in_fstride);
+  };
+  int tile = blockIdx.x;
+  if (tile < ntiles) request(tile);
+  tws.store(L.tw, tid, NT);
+
+  for (; tile < ntiles; tile += gridDim.x) {
+    const long long t0 = (long long)tile * 2 * P;
+    if (tid < 2 * P) {
+      const long long rid = t0 + tid;
+      const bool ok = rid < nrows;
+      L.rbase[tid] = ok ? row_base(map, rid) : -1;
+      L.rblk[tid] = ok ? int((unsigned)rid / (unsigned)bias_div) : 0;   // both fit 32 bits (host check)
+    }
+    // Z = Ya + i*Yb on all K bins from the two half spectra (Hermitian symmetry; bins 0 and K/2 are real)
+    const bool ok = t0 + 2 * pr < nrows;
+#pragma unroll
+    for (int g = 0; g <= NG; ++g) {
+      const int f = f0 + g * FSTEP;
+      const float4 v = ok ? y[g] : make_float4(0.f, 0.f, 0.f, 0.f);
+      if (g == NG) {
+        if (f0 == 0) L.z[(K / 2) * PP + pr] = make_float2(v.x, v.z);
+      } else if (g == 0 && f0 == 0) {
+        L.z[pr] = make_float2(v.x, v.z);
+      } else {
+        L.z[f * PP + pr] = make_float2(v.x - v.w, v.y + v.z);
+        L.z[(K - f) * PP + pr] = make_float2(v.x + v.w, v.z - v.y);
+      }
+    }
+    __syncthreads();
+    if (tile + (int)gridDim.x < ntiles) request(tile + gridDim.x);
+    const int col = tid & (P - 1), t = tid >> lgP, TT = NT >> lgP;
+    fft_lds_pass1<K, true>(L.z, PP, col, t, TT, L.tw);
+    __syncthreads();
+    fft_lds_pass2_inplace<K, true>(L.z, PP, col, t, TT);
+    __syncthreads();
+    // float4 stores: a thread keeps its position n in the row, its row advances by NT/(K/4) per step
+    {
+      const int n = 4 * (tid % (K / 4)), rstep = NT / (K / 4);
+      const float* z0 = reinterpret_cast<const float*>(L.z) + 2 * fft_pos<K>(n + 0) * PP;
+      const float* z1 = reinterpret_cast<const float*>(L.z) + 2 * fft_pos<K>(n + 1) * PP;
+      const float* z2 = reinterpret_cast<const float*>(L.z) + 2 * fft_pos<K>(n + 2) * PP;
+      const float* z3 = reinterpret_cast<const float*>(L.z) + 2 * fft_pos<K>(n + 3) * PP;
+#pragma unroll 4
+      for (int row = tid / (K / 4); row < 2 * P; row += rstep) {
+        const long long b = L.rbase[row];
+        if (b < 0) continue;
+        const int c = 2 * (row >> 1) + (row & 1);
+        float4 v = make_float4(z0[c] * scale, z1[c] * scale, z2[c] * scale, z3[c] * scale);
+        if (bias) {
+          const float4 bb = *reinterpret_cast<const float4*>(bias + (long long)L.rblk[row] * K + n);
+          v.x += bb.x; v.y += bb.y; v.z += bb.z; v.w += bb.w;
+        }
+        if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+        *reinterpret_cast<float4*>(out + b + n) = v;
+      }
+    }
+    __syncthreads();   // the tile and the row tables are free for the next spectra
+  }
+}
+
+// -------------------------------------------------------------------------------------
 // Per-frequency complex GEMM on the fp32 MFMA units, one wave per output tile:
 //   C[f][m][n] = sum_k A[f][k][m] * B[f][k][n]        (B conjugated if CONJ_B)
 // A is stored with m fastest, B and C with n fastest, so every operand load is one
