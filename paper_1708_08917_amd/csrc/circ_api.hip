@@ -1408,10 +1408,25 @@ hipError_t launch_rfft_half_k(int hmode, bool bf, const void* in, void* out, con
 template <int K>
 hipError_t launch_irfft_half_k(bool bf, const void* in, void* out, const RowMap& map, long long nrows, long long in_fstride,
                                float scale, const float* bias, long long bias_div, int relu, hipStream_t s) {
-  FftPlan pl = plan_fft(K, nrows);
-  dim3 grid((unsigned)cdiv(nrows, 2 * pl.P));
   const float2* fin = static_cast<const float2*>(in);
   float* fout = static_cast<float*>(out);
+  if constexpr (stream_k<K>()) {
+    // long runs of contiguous rows: the streaming form
+    constexpr int P = 4096 / K;
+    const long long ntiles = cdiv(nrows, 2 * P);
+    if (ntiles >= kStreamMinTiles && ntiles <= (1ll << 31) - 1 && (nrows & 1) == 0 && (in_fstride & 1) == 0 && aligned16(in)) {
+      const unsigned sgrid = unsigned(ntiles < kStreamMaxWorkgroups ? ntiles : kStreamMaxWorkgroups);
+      if (bf)
+        hipLaunchKernelGGL((irfft_stream_kernel<K, kHalfSpectra | kHalfRows | kHalfBf16>), dim3(sgrid), dim3(256), fft_tile_lds_bytes(K, P),
+                           s, fin, fout, map, nrows, in_fstride, int(ntiles), scale, bias, bias_div, relu);
+      else
+        hipLaunchKernelGGL((irfft_stream_kernel<K, kHalfSpectra | kHalfRows>), dim3(sgrid), dim3(256), fft_tile_lds_bytes(K, P), s, fin,
+                           fout, map, nrows, in_fstride, int(ntiles), scale, bias, bias_div, relu);
+      return hipGetLastError();
+    }
+  }
+  FftPlan pl = plan_fft(K, nrows);
+  dim3 grid((unsigned)cdiv(nrows, 2 * pl.P));
   if (bf)
     hipLaunchKernelGGL((irfft_kernel<K, false, kHalfSpectra | kHalfRows | kHalfBf16>), grid, dim3(pl.NT), pl.lds, s, fin, fout,
                        map, nrows, in_fstride, pl.P, scale, bias, bias_div, relu, 1, 0ll);

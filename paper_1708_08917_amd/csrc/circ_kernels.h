@@ -559,13 +559,16 @@ __global__ void irfft_kernel(const float2* __restrict__ in, float* __restrict__ 
 // them (the ninth, bin K/2, only for f0 = 0), both rows of the pair in one 16-byte load.
 // 256 threads; one spectrum (no partial sums); an even number of rows, an even plane pitch and a
 // 16-byte aligned input (whole pairs); contiguous 16-byte aligned output rows; 32 <= K <= 256.
-template <int K>
+// HMODE: 0, or 16-bit spectra and rows (kHalfSpectra | kHalfRows, with kHalfBf16 for bfloat16).
+template <int K, int HMODE = 0>
 __global__ __launch_bounds__(256) void irfft_stream_kernel(const float2* __restrict__ in, float* __restrict__ out, RowMap map,
                                                            long long nrows, long long in_fstride, int ntiles, float scale,
                                                            const float* __restrict__ bias, long long bias_div, int relu) {
   static_assert(is_pow2_c(K) && K >= 32 && K <= 256, "block sizes of the streaming transform");
+  static_assert(HMODE == 0 || (HMODE & (kHalfSpectra | kHalfRows)) == (kHalfSpectra | kHalfRows), "16-bit spectra come with 16-bit rows");
   constexpr int P = 4096 / K, PP = P + 1, NT = 256, lgP = ilog2(P), NF = K / 2 + 1, FSTEP = NT / P, NG = 8;
-  static_assert(NG * FSTEP == K / 2, "eight bins per thread, and bin K/2 for the threads of bin 0");
+  static_assert(NG * FSTEP == K / 2 && NF == K / 2 + 1, "eight bins per thread, and bin K/2 for the threads of bin 0");
+  constexpr bool HALF = HMODE != 0, BF = (HMODE & kHalfBf16) != 0;
   extern __shared__ float smem[];
   TileLds L = carve_tile<K>(smem, P);
   const int tid = threadIdx.x, pr = tid & (P - 1), f0 = tid >> lgP;
@@ -573,15 +576,29 @@ __global__ __launch_bounds__(256) void irfft_stream_kernel(const float2* __restr
   TwiddleStage<K> tws;
   tws.request(tid, NT);
 
-  float4 y[NG + 1];
+  // the two rows of a pair at one bin: 16 bytes of fp32 spectra, 8 bytes of 16-bit ones
+  using PairT = typename std::conditional<HALF, uint2, float4>::type;
+  PairT y[NG + 1];
+  auto pair_at = [&](long long e) -> PairT {
+    if constexpr (HALF) return *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned*>(in) + e);
+    else return *reinterpret_cast<const float4*>(in + e);
+  };
+  auto pair_values = [&](const PairT& v) -> float4 {
+    if constexpr (HALF) {
+      const float2 a = unpack_pair16<BF>(v.x), b = unpack_pair16<BF>(v.y);
+      return make_float4(a.x, a.y, b.x, b.y);
+    } else {
+      return v;
+    }
+  };
   // pairs past the end reload the last pair (a valid address) and are zeroed when they are written to LDS
   auto request = [&](int tile) {
     const long long rid = (long long)tile * 2 * P + 2 * pr;
-    const float2* src = in + (rid < nrows ? rid : nrows - 2) + (long long)f0 * in_fstride;
+    const long long e0 = (rid < nrows ? rid : nrows - 2) + (long long)f0 * in_fstride;
 #pragma unroll
-    for (int g = 0; g < NG; ++g) y[g] = *reinterpret_cast<const float4*>(src + (long long)(g * FSTEP) * in_fstride);
-    y[NG] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (f0 == 0) y[NG] = *reinterpret_cast<const float4*>(src + (long long)(K / 2) * in_fstride);
+    for (int g = 0; g < NG; ++g) y[g] = pair_at(e0 + (long long)(g * FSTEP) * in_fstride);
+    y[NG] = PairT{};
+    if (f0 == 0) y[NG] = pair_at(e0 + (long long)(K / 2) * in_fstride);
   };
   int tile = blockIdx.x;
   if (tile < ntiles) request(tile);
@@ -600,7 +617,7 @@ __global__ __launch_bounds__(256) void irfft_stream_kernel(const float2* __restr
 #pragma unroll
     for (int g = 0; g <= NG; ++g) {
       const int f = f0 + g * FSTEP;
-      const float4 v = ok ? y[g] : make_float4(0.f, 0.f, 0.f, 0.f);
+      const float4 v = ok ? pair_values(y[g]) : make_float4(0.f, 0.f, 0.f, 0.f);
       if (g == NG) {
         if (f0 == 0) L.z[(K / 2) * PP + pr] = make_float2(v.x, v.z);
       } else if (g == 0 && f0 == 0) {
@@ -635,7 +652,8 @@ __global__ __launch_bounds__(256) void irfft_stream_kernel(const float2* __restr
           v.x += bb.x; v.y += bb.y; v.z += bb.z; v.w += bb.w;
         }
         if (relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
-        *reinterpret_cast<float4*>(out + b + n) = v;
+        if constexpr (HALF) store_half4<BF>(reinterpret_cast<unsigned short*>(out) + b + n, v);
+        else *reinterpret_cast<float4*>(out + b + n) = v;
       }
     }
     __syncthreads();   // the tile and the row tables are free for the next spectra
