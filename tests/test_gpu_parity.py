@@ -791,6 +791,18 @@ def test_fc_unfused_route_with_long_ragged_runs_of_rows(p, q, k, batch):
     check(np.stack([dw[i, j] for i, j in pairs]), ref, "dw " + what)
 
 
+def test_fc_split_gemm_route_with_fewer_columns_than_a_wave():
+    """257 frequency slices of a 40 x 16 grid of 512-point blocks are enough tiles for the split
+    contraction even at batch 5: every wave of a tile then has columns past the batch (computed on
+    copies of the last one, not stored), three of the four waves nothing but such columns."""
+    p, q, k, batch = 40, 16, 512, 5
+    w, x, b = rand_fc(p, q, k, batch)
+    rows = [0, 17, p - 1]
+    sel = np.concatenate([np.arange(i * k, (i + 1) * k) for i in rows])
+    got = G.gpu_fc_forward(w, x, b, True)
+    check(got[:, sel], O.fc_forward(w, x, b, True, block_rows=rows), "split contraction, batch 5, k=512")
+
+
 def test_fc_split_gemm_route_keeps_fp32_accuracy_per_batch_row():
     """Layers with at least 256 tiles of 64 x 128 outputs per frequency take the contraction that
     splits every fp32 operand into three bfloat16 terms.  Each value is split on its own, so batch
