@@ -12,6 +12,9 @@
 // values are exact in fp32 and the matrix cores accumulate in fp32, so the result carries the
 // rounding errors of an fp32 sum of products, at 6/16 of the matrix-core time of the fp32
 // instruction (v_mfma_f32_32x32x16_bf16 multiplies 8 times as many values in half the cycles).
+// bfloat16 has the exponent range of fp32, so no scaling is involved; the two ends of that range
+// are the exceptions: |x| within 2^-8 of the largest finite fp32 value rounds to infinity in its
+// first term, and the lower terms of |x| < 2^-110 fall below the smallest normal value.
 //
 // A complex product runs on the real instruction with the (re, im) pairs interleaved along the
 // reduction index:   Re C = A' . (br, -bi, ...)      Im C = A' . (bi, br, ...),   A' = (ar, ai, ...)
@@ -23,7 +26,8 @@
 // k = 8*step + 4h .. + 3 of row (A) or column (B) r:
 // - B: these are four loads straight from memory (two runs of 32 consecutive n per instruction);
 //   every value of B is read by exactly one lane, split in registers and used for both sub-tiles.
-//   The loads of a slab of 64 k run one whole slab ahead of their use.
+//   The requests run RING = 4 steps (32 k) ahead of their use in a register ring (a scheduling
+//   barrier keeps the compiler from sinking them to their first use).
 // - A (the small operand: the weights of one frequency) is split once per workgroup and slab
 //   and kept in LDS as planes [term][m][k] (row pitch 68 words: eight consecutive rows start at
 //   eight different groups of four banks, for the 16-byte stores and for the 16-byte fragment
