@@ -6,11 +6,12 @@
 // The fp32 matrix instruction bounds the plain fp32 kernel (cgemm_kernel).  Here every fp32
 // operand value x is written as the sum of three bfloat16 terms,
 //   h = bf16(x),  m = bf16(x - h),  l = bf16(x - h - m)      (both differences are exact in fp32),
-// which carry 24 or more leading bits of x, and a product a*b is taken as the six partial
-// products of combined order <= 2 (hh, hm, mh, hl, lh, mm); the three left out (ml, lm, ll) are
-// below 2^-25 |a b|, the size of the rounding of an fp32 product.  Partial products of bfloat16
-// values are exact in fp32 and the matrix cores accumulate in fp32, so the result carries the
-// rounding errors of an fp32 sum of products, at 6/16 of the matrix-core time of the fp32
+// which reproduce x to within 2^-24 |x|, and a product a*b is taken as the six partial products
+// of combined order <= 2 (hh, hm, mh, hl, lh, mm); the three left out (ml, lm, ll) and the two
+// residuals add up to at most 2^-22 |a b| (2^-24.5 over random operands: one rounding of an fp32
+// product is 2^-24).  Partial products of bfloat16 values are exact in fp32 and the matrix cores
+// accumulate in fp32, so the result carries the rounding errors of an fp32 sum of products (measured:
+// no larger than those of the fp32 matrix instruction), at 6/16 of the matrix-core time of the fp32
 // instruction (v_mfma_f32_32x32x16_bf16 multiplies 8 times as many values in half the cycles).
 // bfloat16 has the exponent range of fp32, so no scaling is involved; the two ends of that range
 // are the exceptions: |x| within 2^-8 of the largest finite fp32 value rounds to infinity in its
@@ -58,7 +59,7 @@ __device__ __forceinline__ unsigned pack_bf16x2(float re, float im) {
   c.b = __builtin_convertvector(v, bfloatx2);
   return c.u;
 }
-// v = h + m + l up to 2^-25 |v| per component
+// v = h + m + l up to 2^-24 |v| per component
 __device__ __forceinline__ void split_bf16x3(float2 v, unsigned& h, unsigned& m, unsigned& l) {
   h = pack_bf16x2(v.x, v.y);
   float2 r = make_float2(v.x - __uint_as_float(h << 16), v.y - __uint_as_float(h & 0xffff0000u));
