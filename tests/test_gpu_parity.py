@@ -767,15 +767,17 @@ def test_cfg2_graph_over_streams_matches_eager():
         assert torch.equal(ys, eager), f"replay {rep} differs from the eager result"
 
 
-@pytest.mark.parametrize("p,q,k,batch", [(70, 40, 256, 901), (70, 41, 256, 900), (9, 9, 256, 1001), (72, 33, 128, 1001), (130, 3, 64, 17000), (130, 70, 32, 1950)])
+@pytest.mark.parametrize("p,q,k,batch", [(70, 40, 256, 901), (70, 41, 256, 900), (9, 9, 256, 1001), (72, 33, 128, 1001), (130, 3, 64, 17000), (130, 70, 32, 1950),
+                                           (70, 40, 100, 651), (70, 40, 81, 651)])
 def test_fc_unfused_route_with_long_ragged_runs_of_rows(p, q, k, batch):
     """More than 8 tiles of output block rows keep these layers off the fused kernel: q * batch rows go
     through the streaming row transform (at least 256 tiles of 4096 / k column pairs, the last tile
     ragged), p * batch rows through the inverse transform (its streaming form when their number is
-    even, the tile-per-workgroup form when it is odd: 9 * 1001).  Forward on sampled block rows, backward
-    on sampled block columns and (i, j) pairs."""
+    even, the tile-per-workgroup form when it is odd: 9 * 1001).  The last two cases take the split
+    contraction with a mixed-radix block size and with an odd one (no real last bin).  Forward on sampled
+    block rows, backward on sampled block columns and (i, j) pairs."""
     w, x, b = rand_fc(p, q, k, batch)
-    assert (q * batch) % (2 * 4096 // k) != 0 and q * batch >= 256 * 2 * 4096 // k
+    assert (q * batch) % (2 * (4096 // k)) != 0 and q * batch >= 256 * 2 * (4096 // k)
     what = f"{p}x{q} k={k} B={batch}"
     rows = [0, p // 2, p - 1]
     got = G.gpu_fc_forward(w, x, b, True)
